@@ -1,0 +1,262 @@
+"""CPU oracle for the factorized operators over ``T = sum_k I_k D_k M_k^T``.
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition the device library is
+checked against.  It is imported by the tests, by the smoke check and by the benchmark's
+CPU-baseline leg, and by nothing on the product path.  It shares no code with the device
+library and never calls it.
+
+What it computes (paper, Sec. 2.1 and 2.2):
+
+* the target table by join-gather, i.e. the rewrite rule of Sec. 2.2 with ``X = I``:
+  ``T = I_1 D_1 M_1^T + ... + I_n D_n M_n^T`` where ``M_k`` is the mapping matrix of Def. 1 and
+  ``I_k`` the indicator matrix of Def. 2;
+* on that *materialized* table, in float64: ``T X`` (left multiply, Sec. 2.2), ``T^T Y``
+  (the transpose operator Sec. 2.2 names for linear regression), ``T^T T`` and the
+  gradient-descent loop of Alg. 1.
+
+Because the rewrite is an identity of linear algebra, the result of every factorized operator
+has a plain definition, and the oracle is that definition written out: materialize, then dense
+float64 products.  The factorized form appears nowhere in this file.
+
+Readings of the paper taken here (each is also listed in the design document):
+
+* Def. 2 prints the indicator matrix once with the shape of a mapping matrix and once as a "row
+  vector of size r_T".  Read: ``I_k`` is logically ``r_T x r_k`` binary with at most one 1 per
+  row; the length-``r_T`` vector is its compressed storage (source row, or -1 for none).
+* Def. 1: ``M_k`` is ``c_T x c_k`` binary with at most one 1 per row and per column; a source
+  column may be unmapped (-1).
+* Cells supplied by several sources are summed, literally as the rule of Sec. 2.2 says.
+* Alg. 1 prints ``w = w - gamma * X^T((X w) - y)`` with ``X`` the target table.  Read with the
+  mean gradient: ``w <- w - gamma * T^T (T w - y) / r_T``; loss ``||T w - y||^2 / (2 r_T)``.
+* Logistic regression is only named by the paper (Sec. 3.1, Tab. 7-9).  Read: labels in {0,1},
+  ``z = T w``, loss ``mean(softplus(z) - y z)``, gradient ``T^T (sigmoid(z) - y) / r_T``.
+
+Pins (tests/test_oracle_pins.py): brute force from Def. 1 / Def. 2 with dense 0/1 matrices on tiny
+schemas; the star-join special case ``T = [S | R[fk]]``; ``T I = T``; ``rowSum``/``colSum`` (Tab. 2);
+the adjoint identity; the weighted-Gram closed form of ``T^T T`` for a star join; the closed-form
+gradient-descent iterate through an eigendecomposition and its least-squares limit; ``ln 2`` and a
+finite-difference gradient for the logistic loss; ``bincount``/stable ``argsort`` for the inverse
+index.
+"""
+from __future__ import annotations
+
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+ROW_CHUNK = 262_144   # rows converted to float64 at a time; memory bound only, no effect on values
+
+
+# ----------------------------------------------------------------------------- definitions
+def dense_mapping(col_map: np.ndarray, c_T: int) -> np.ndarray:
+    """Def. 1: ``M_k[i, j] = 1`` iff source column ``j`` is mapped to target column ``i``."""
+    c_k = len(col_map)
+    M = np.zeros((c_T, c_k), dtype=np.float64)
+    for j in range(c_k):
+        i = int(col_map[j])
+        if i >= 0:
+            M[i, j] = 1.0
+    return M
+
+
+def dense_indicator(row_idx: Optional[np.ndarray], r_T: int, r_k: int) -> np.ndarray:
+    """Def. 2: ``I_k[i, j] = 1`` iff source row ``j`` is mapped to target row ``i``."""
+    I = np.zeros((r_T, r_k), dtype=np.float64)
+    for i in range(r_T):
+        j = i if row_idx is None else int(row_idx[i])
+        if j >= 0:
+            I[i, j] = 1.0
+    return I
+
+
+def brute_force_target(schema) -> np.ndarray:
+    """Sec. 2.2 rewrite with ``X = I``, evaluated with dense 0/1 matrices (tiny inputs only)."""
+    T = np.zeros((schema.r_T, schema.c_T), dtype=np.float64)
+    for s in schema.sources:
+        I = dense_indicator(s.row_idx, schema.r_T, s.rows)
+        M = dense_mapping(s.col_map, schema.c_T)
+        T += I @ s.D.astype(np.float64) @ M.T
+    return T
+
+
+# ----------------------------------------------------------------------------- materialize
+def materialize(schema, row_lo: int = 0, row_hi: Optional[int] = None) -> np.ndarray:
+    """Join-gather of target rows ``[row_lo, row_hi)`` in float32.
+
+    For every source in order, every target row ``i`` with a source row and every mapped source
+    column ``j``: ``T[i, col_map[j]] += D_k[row_idx[i], j]`` starting from ``+0.0``.  This float32
+    table is the bit-exact expectation for the device join-gather.
+    """
+    row_hi = schema.r_T if row_hi is None else row_hi
+    n = row_hi - row_lo
+    T = np.zeros((n, schema.c_T), dtype=np.float32)
+    for s in schema.sources:
+        if s.row_idx is None:
+            src_rows = np.arange(row_lo, row_hi, dtype=np.int64)
+        else:
+            src_rows = s.row_idx[row_lo:row_hi].astype(np.int64)
+        present = np.flatnonzero(src_rows >= 0)
+        if present.size == 0:
+            continue
+        picked = src_rows[present]
+        for j in range(s.cols):
+            t = int(s.col_map[j])
+            if t < 0:
+                continue
+            T[present, t] += s.D[picked, j]
+    return T
+
+
+def _chunks(r_T: int):
+    for lo in range(0, r_T, ROW_CHUNK):
+        yield lo, min(r_T, lo + ROW_CHUNK)
+
+
+class Target:
+    """The materialized float32 target table, held once, widened to float64 chunk by chunk."""
+
+    def __init__(self, schema=None, table: Optional[np.ndarray] = None):
+        if table is None:
+            table = np.empty((schema.r_T, schema.c_T), dtype=np.float32)
+            for lo, hi in _chunks(schema.r_T):
+                table[lo:hi] = materialize(schema, lo, hi)
+        self.T32 = table
+        self.r_T, self.c_T = table.shape
+
+    def rows64(self, lo: int, hi: int) -> np.ndarray:
+        return self.T32[lo:hi].astype(np.float64)
+
+
+def _as_target(obj) -> Target:
+    return obj if isinstance(obj, Target) else Target(obj)
+
+
+# ----------------------------------------------------------------------------- operators
+def lmm(target, X: np.ndarray) -> np.ndarray:
+    """Left multiply ``T X`` (Sec. 2.2), float64, ``X`` is ``c_T x c_X``."""
+    tg = _as_target(target)
+    X64 = np.asarray(X, dtype=np.float64).reshape(tg.c_T, -1)
+    out = np.empty((tg.r_T, X64.shape[1]), dtype=np.float64)
+    for lo, hi in _chunks(tg.r_T):
+        out[lo:hi] = tg.rows64(lo, hi) @ X64
+    return out
+
+
+def tmm(target, Y: np.ndarray) -> np.ndarray:
+    """Transposed multiply ``T^T Y``, float64, ``Y`` is ``r_T x c_X``."""
+    tg = _as_target(target)
+    Y64 = np.asarray(Y, dtype=np.float64).reshape(tg.r_T, -1)
+    out = np.zeros((tg.c_T, Y64.shape[1]), dtype=np.float64)
+    for lo, hi in _chunks(tg.r_T):
+        out += tg.rows64(lo, hi).T @ Y64[lo:hi]
+    return out
+
+
+def crossprod(target) -> np.ndarray:
+    """Gram matrix ``T^T T``, float64, full symmetric ``c_T x c_T``."""
+    tg = _as_target(target)
+    out = np.zeros((tg.c_T, tg.c_T), dtype=np.float64)
+    for lo, hi in _chunks(tg.r_T):
+        blk = tg.rows64(lo, hi)
+        out += blk.T @ blk
+    return out
+
+
+# ----------------------------------------------------------------------------- inverse index
+def inverse_index(row_idx: np.ndarray, r_k: int) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """Compressed-row form of ``I_k^T``: for each source row the target rows it feeds, ascending.
+
+    Returns ``(rowptr int32[r_k+1], perm int32[nnz], cnt int32[r_k])``.  Written as the definition:
+    walk the target rows in order and append each to the list of its source row.
+    """
+    lists: List[List[int]] = [[] for _ in range(r_k)]
+    for i, j in enumerate(np.asarray(row_idx).tolist()):
+        if j >= 0:
+            lists[j].append(i)
+    cnt = np.array([len(l) for l in lists], dtype=np.int32)
+    rowptr = np.zeros(r_k + 1, dtype=np.int32)
+    rowptr[1:] = np.cumsum(cnt)
+    perm = np.array([i for l in lists for i in l], dtype=np.int32)
+    return rowptr, perm, cnt
+
+
+def segment_sum(row_idx: np.ndarray, r_k: int, Y: np.ndarray) -> np.ndarray:
+    """``I_k^T Y`` from the dense definition of ``I_k`` chunked over target rows, float64."""
+    Y64 = np.asarray(Y, dtype=np.float64).reshape(len(row_idx), -1)
+    Z = np.zeros((r_k, Y64.shape[1]), dtype=np.float64)
+    for i, j in enumerate(np.asarray(row_idx).tolist()):
+        if j >= 0:
+            Z[j] += Y64[i]
+    return Z
+
+
+# ----------------------------------------------------------------------------- gradient descent
+def linear_loss_grad(target, y: np.ndarray, W: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """Loss ``||T w - y||^2 / (2 r_T)`` and gradient ``T^T (T w - y) / r_T`` per column of ``W``."""
+    tg = _as_target(target)
+    W = np.asarray(W, dtype=np.float64).reshape(tg.c_T, -1)
+    y64 = np.asarray(y, dtype=np.float64).reshape(-1, 1)
+    loss = np.zeros(W.shape[1])
+    grad = np.zeros_like(W)
+    for lo, hi in _chunks(tg.r_T):
+        blk = tg.rows64(lo, hi)
+        e = blk @ W - y64[lo:hi]
+        loss += 0.5 * np.sum(e * e, axis=0)
+        grad += blk.T @ e
+    return loss / tg.r_T, grad / tg.r_T
+
+
+def _softplus(z: np.ndarray) -> np.ndarray:
+    return np.maximum(z, 0.0) + np.log1p(np.exp(-np.abs(z)))
+
+
+def _sigmoid(z: np.ndarray) -> np.ndarray:
+    out = np.empty_like(z)
+    pos = z >= 0
+    out[pos] = 1.0 / (1.0 + np.exp(-z[pos]))
+    ez = np.exp(z[~pos])
+    out[~pos] = ez / (1.0 + ez)
+    return out
+
+
+def logistic_loss_grad(target, y01: np.ndarray, W: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """Mean cross-entropy ``mean(softplus(z) - y z)`` with ``z = T w`` and its gradient
+    ``T^T (sigmoid(z) - y) / r_T``; labels in {0, 1}."""
+    tg = _as_target(target)
+    W = np.asarray(W, dtype=np.float64).reshape(tg.c_T, -1)
+    y64 = np.asarray(y01, dtype=np.float64).reshape(-1, 1)
+    loss = np.zeros(W.shape[1])
+    grad = np.zeros_like(W)
+    for lo, hi in _chunks(tg.r_T):
+        blk = tg.rows64(lo, hi)
+        z = blk @ W
+        loss += np.sum(_softplus(z) - y64[lo:hi] * z, axis=0)
+        grad += blk.T @ (_sigmoid(z) - y64[lo:hi])
+    return loss / tg.r_T, grad / tg.r_T
+
+
+def gd(target, model: str, y: np.ndarray, W0: np.ndarray, lr: Sequence[float], iters: int):
+    """Alg. 1 for ``iters`` iterations: ``W <- W - grad * diag(lr)``, one learning rate per column.
+
+    Returns the final weights and the per-iteration loss measured *before* each update.
+    """
+    tg = _as_target(target)
+    W = np.array(W0, dtype=np.float64).reshape(tg.c_T, -1).copy()
+    lr64 = np.asarray(lr, dtype=np.float64).reshape(1, -1)
+    fn = {"linear": linear_loss_grad, "logistic": logistic_loss_grad}[model]
+    losses = []
+    for _ in range(iters):
+        loss, grad = fn(tg, y, W)
+        losses.append(loss)
+        W -= grad * lr64
+    return W, np.array(losses)
+
+
+# ----------------------------------------------------------------------------- complexity (Tab. 2)
+def complexity_lmm(schema, c_X: int) -> Tuple[int, int]:
+    """Tab. 2 row ``T X``: (materialized, factorized) operation counts for dense operands."""
+    m_T = schema.r_T * schema.c_T
+    m_X = schema.c_T * c_X
+    mat = c_X * m_T + schema.r_T * m_X
+    fact = sum(c_X * s.rows * s.cols + s.rows * m_X for s in schema.sources)
+    return mat, fact

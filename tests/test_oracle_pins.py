@@ -1,0 +1,335 @@
+"""Pins for the CPU oracle: every check compares it with something other than itself.
+
+Sources of truth used here: the dense 0/1 matrices of Def. 1 and Def. 2 multiplied out as the
+rewrite rule of Sec. 2.2 says (brute force on tiny schemas), numpy library routines on special
+cases (fancy indexing for a star join, bincount, stable argsort, lstsq, eigh), algebraic
+identities (adjoint, trace, x^T G x = |T x|^2) and closed forms for gradient descent.
+"""
+import numpy as np
+import pytest
+
+import datagen
+import oracle
+
+TINY_SEEDS = list(range(12))
+
+
+def _factorized_lmm_fp64(schema, X):
+    """The rewritten form  sum_k I_k (D_k (M_k^T X))  spelled out with index arrays, for the identity test."""
+    X = np.asarray(X, dtype=np.float64)
+    out = np.zeros((schema.r_T, X.shape[1]))
+    for s in schema.sources:
+        keep = np.flatnonzero(s.col_map >= 0)
+        P = s.D[:, keep].astype(np.float64) @ X[s.col_map[keep]]
+        if s.row_idx is None:
+            out += P
+        else:
+            ok = np.flatnonzero(s.row_idx >= 0)
+            out[ok] += P[s.row_idx[ok]]
+    return out
+
+
+# ------------------------------------------------------------------ materialize
+@pytest.mark.parametrize("seed", TINY_SEEDS)
+def test_materialize_equals_dense_definition_bit_exact(seed):
+    # integer-valued tables: every partial sum is exact, so float32 join-gather must equal the
+    # float64 triple products of the 0/1 matrices bit for bit, shared columns included
+    sch = datagen.tiny_random_schema(seed, r_T=11, c_T=8, n=3, integer_values=True)
+    want = oracle.brute_force_target(sch)
+    got = oracle.materialize(sch)
+    assert got.dtype == np.float32
+    assert np.array_equal(got.astype(np.float64), want)
+
+
+@pytest.mark.parametrize("seed", TINY_SEEDS)
+def test_materialize_equals_dense_definition_real_values(seed):
+    sch = datagen.tiny_random_schema(100 + seed, r_T=12, c_T=6, n=3)
+    want = oracle.brute_force_target(sch)
+    got = oracle.materialize(sch).astype(np.float64)
+    np.testing.assert_allclose(got, want, rtol=0, atol=4e-7 * max(1.0, np.abs(want).max()))
+    # cells fed by at most one source are copies: exact
+    feeders = np.zeros((sch.r_T, sch.c_T), dtype=int)
+    for s in sch.sources:
+        rows = np.flatnonzero(s.row_idx >= 0)
+        cols = s.col_map[s.col_map >= 0]
+        feeders[np.ix_(rows, cols)] += 1
+    single = feeders <= 1
+    assert np.array_equal(got[single], want[single])
+    assert np.all(got[feeders == 0] == 0.0)
+
+
+def test_materialize_star_join_is_hstack():
+    sch = datagen.config0()
+    S, R = sch.sources[0].D, sch.sources[1].D
+    fk = sch.sources[1].row_idx
+    want = np.hstack([S, R[fk]])
+    got = oracle.materialize(sch)
+    assert got.shape == (10_000, 12)
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+
+
+def test_materialize_row_ranges_tile_the_table():
+    sch = datagen.config3(rows=500, cols=8, shared=4)
+    full = oracle.materialize(sch)
+    parts = [oracle.materialize(sch, lo, min(lo + 137, sch.r_T)) for lo in range(0, sch.r_T, 137)]
+    assert np.array_equal(np.vstack(parts), full)
+
+
+def test_union_config_structure():
+    sch = datagen.config3(rows=1000, cols=8, shared=4)
+    assert sch.r_T == 1700 and sch.c_T == 12
+    T = oracle.materialize(sch)
+    S1, S2 = sch.sources[0].D, sch.sources[1].D
+    idx2 = sch.sources[1].row_idx
+    # S1 rows occupy the first block, their shared cells come from S1 alone
+    assert np.array_equal(T[:1000, :8], S1)
+    matched = np.flatnonzero(idx2[:1000] >= 0)
+    assert matched.size == 300
+    assert np.array_equal(T[matched, 8:], S2[idx2[matched], 4:])
+    # the new S2 rows carry zeros in the S1-only block
+    assert np.all(T[1000:, :4] == 0)
+    assert np.array_equal(T[1000:, 4:], S2[idx2[1000:]])
+
+
+# ------------------------------------------------------------------ LMM
+@pytest.mark.parametrize("seed", TINY_SEEDS[:6])
+def test_lmm_tiny_equals_dense_definition(seed):
+    sch = datagen.tiny_random_schema(200 + seed, n=3)
+    X = datagen.rng_for(seed).standard_normal((sch.c_T, 3))
+    # the brute-force target shares columns between sources in float64; the oracle adds them in
+    # float32 first, hence the tolerance
+    np.testing.assert_allclose(oracle.lmm(sch, X), oracle.brute_force_target(sch) @ X, rtol=0, atol=1e-5)
+
+
+def test_lmm_identity_and_rowsum():
+    sch = datagen.config0(r_S=777, r_R=50)
+    T = oracle.materialize(sch).astype(np.float64)
+    assert np.array_equal(oracle.lmm(sch, np.eye(sch.c_T)), T)
+    np.testing.assert_allclose(oracle.lmm(sch, np.ones((sch.c_T, 1)))[:, 0], T.sum(axis=1), rtol=1e-13)
+
+
+@pytest.mark.parametrize("maker", [
+    lambda: datagen.config0(),
+    lambda: datagen.config2(r_S=4000, dim_rows=(100, 50, 10)),
+    lambda: datagen.config3(rows=900, cols=16, shared=8),
+    lambda: datagen.tiny_random_schema(5, r_T=40, c_T=9, n=4),
+])
+def test_factorized_form_equals_materialized_form(maker):
+    sch = maker()
+    X = datagen.rng_for(9).standard_normal((sch.c_T, 5))
+    want = _factorized_lmm_fp64(sch, X)
+    got = oracle.lmm(sch, X)
+    # shared target cells are added in float32 by the join-gather, in float64 by the rewritten form
+    np.testing.assert_allclose(got, want, rtol=0, atol=2e-6 * np.abs(want).max())
+
+
+# ------------------------------------------------------------------ TMM
+def test_tmm_adjoint_identity():
+    sch = datagen.config2(r_S=3000, dim_rows=(120, 60, 10))
+    rng = datagen.rng_for(3)
+    X = rng.standard_normal((sch.c_T, 4))
+    Y = rng.standard_normal((sch.r_T, 4))
+    lhs = np.sum(oracle.lmm(sch, X) * Y)
+    rhs = np.sum(X * oracle.tmm(sch, Y))
+    assert abs(lhs - rhs) <= 1e-10 * max(abs(lhs), 1.0)
+
+
+def test_tmm_colsum_and_unit_vectors():
+    sch = datagen.config3(rows=300, cols=8, shared=4)
+    T = oracle.materialize(sch).astype(np.float64)
+    np.testing.assert_allclose(oracle.tmm(sch, np.ones((sch.r_T, 1)))[:, 0], T.sum(axis=0), rtol=1e-12, atol=1e-12)
+    for i in (0, 299, 300, sch.r_T - 1):
+        e = np.zeros((sch.r_T, 1)); e[i] = 1.0
+        assert np.array_equal(oracle.tmm(sch, e)[:, 0], T[i])
+
+
+def test_tmm_not_transposed_operand():
+    # a non-square case where T X and T^T Y cannot be confused
+    sch = datagen.tiny_random_schema(7, r_T=13, c_T=5, n=2)
+    T = oracle.brute_force_target(sch)
+    Y = datagen.rng_for(1).standard_normal((13, 2))
+    np.testing.assert_allclose(oracle.tmm(sch, Y), T.T @ Y, atol=1e-5)
+
+
+# ------------------------------------------------------------------ segment sum / inverse index
+def test_segment_sum_equals_bincount():
+    rng = datagen.rng_for(11)
+    r_k, r_T = 37, 1000
+    idx = rng.integers(-1, r_k, size=r_T).astype(np.int32)
+    Y = rng.standard_normal((r_T, 3))
+    got = oracle.segment_sum(idx, r_k, Y)
+    ok = idx >= 0
+    for c in range(3):
+        want = np.bincount(idx[ok], weights=Y[ok, c], minlength=r_k)
+        np.testing.assert_allclose(got[:, c], want, rtol=1e-12, atol=1e-12)
+    cnt = oracle.segment_sum(idx, r_k, np.ones((r_T, 1)))[:, 0]
+    assert np.array_equal(cnt, np.bincount(idx[ok], minlength=r_k))
+
+
+def test_inverse_index_is_stable_grouping():
+    rng = datagen.rng_for(12)
+    r_k, r_T = 23, 500
+    idx = rng.integers(-1, r_k + 0, size=r_T).astype(np.int32)
+    idx[idx == 5] = 6            # an empty segment
+    rowptr, perm, cnt = oracle.inverse_index(idx, r_k)
+    valid = np.flatnonzero(idx >= 0)
+    order = valid[np.argsort(idx[valid], kind="stable")]
+    assert np.array_equal(perm, order.astype(np.int32))
+    assert np.array_equal(cnt, np.bincount(idx[valid], minlength=r_k))
+    assert rowptr[0] == 0 and rowptr[-1] == valid.size and np.all(np.diff(rowptr) == cnt)
+    assert cnt[5] == 0
+    for j in range(r_k):
+        seg = perm[rowptr[j]:rowptr[j + 1]]
+        assert np.all(idx[seg] == j) and np.all(np.diff(seg) > 0)
+
+
+# ------------------------------------------------------------------ crossprod
+def test_crossprod_identities():
+    sch = datagen.config3(rows=400, cols=8, shared=4)
+    G = oracle.crossprod(sch)
+    T = oracle.materialize(sch)
+    np.testing.assert_allclose(G, oracle.tmm(sch, T), rtol=1e-12, atol=1e-10)
+    assert np.array_equal(G, G.T)
+    assert abs(np.trace(G) - np.sum(T.astype(np.float64) ** 2)) < 1e-9 * np.trace(G)
+    assert np.linalg.eigvalsh(G).min() >= -1e-9 * np.trace(G)
+    x = datagen.rng_for(2).standard_normal((sch.c_T, 1))
+    q = (x.T @ G @ x).item()
+    assert abs(q - float(np.sum(oracle.lmm(sch, x) ** 2))) < 1e-9 * q
+
+
+def test_crossprod_star_closed_form():
+    sch = datagen.config0(r_S=2000, r_R=64)
+    S = sch.sources[0].D.astype(np.float64)
+    R = sch.sources[1].D.astype(np.float64)
+    fk = sch.sources[1].row_idx
+    cnt = np.bincount(fk, minlength=64).astype(np.float64)
+    seg = np.zeros((64, 4))
+    np.add.at(seg, fk, S)
+    want = np.block([[S.T @ S, seg.T @ R], [R.T @ seg, R.T @ (cnt[:, None] * R)]])
+    np.testing.assert_allclose(oracle.crossprod(sch), want, rtol=1e-11, atol=1e-9)
+
+
+# ------------------------------------------------------------------ linear regression (Alg. 1)
+def _config0_problem():
+    sch = datagen.config0()
+    tg = oracle.Target(sch)
+    y = datagen.finish_labels("linear", oracle.lmm(tg, sch.extras["w_star"].reshape(-1, 1)), sch.extras["noise"])
+    return sch, tg, y
+
+
+def test_linear_gd_matches_closed_form_iterate():
+    sch, tg, y = _config0_problem()
+    T = tg.T32.astype(np.float64)
+    y64 = y.astype(np.float64)
+    gamma, iters = 0.1, 20
+    W, losses = oracle.gd(tg, "linear", y, np.zeros((12, 1)), [gamma], iters)
+    w_ls = np.linalg.lstsq(T, y64, rcond=None)[0]
+    H = T.T @ T / sch.r_T
+    lam, Q = np.linalg.eigh(H)
+    assert gamma * lam.max() < 2.0
+    # w_t - w_ls = (I - gamma H)^t (w_0 - w_ls)
+    w_t = w_ls + Q @ (((1.0 - gamma * lam) ** iters) * (Q.T @ (0.0 - w_ls)))
+    np.testing.assert_allclose(W[:, 0], w_t, rtol=0, atol=1e-11)
+    assert np.all(np.diff(losses[:, 0]) < 0)
+    # loss before the first update is |y|^2 / (2 r_T)
+    assert abs(losses[0, 0] - 0.5 * np.mean(y64 ** 2)) < 1e-12 * losses[0, 0]
+    # after 20 iterations the iterate is still visibly away from the optimum: trajectory, not limit
+    assert 0.02 < np.linalg.norm(W[:, 0] - w_ls) / np.linalg.norm(w_ls) < 0.3
+
+
+def test_linear_gd_converges_to_least_squares():
+    sch, tg, y = _config0_problem()
+    T = tg.T32.astype(np.float64)
+    w_ls = np.linalg.lstsq(T, y.astype(np.float64), rcond=None)[0]
+    W, _ = oracle.gd(tg, "linear", y, np.zeros((12, 1)), [1.0], 400)
+    assert np.linalg.norm(W[:, 0] - w_ls) / np.linalg.norm(w_ls) < 1e-10
+    # the optimum sits within the noise floor of the generating weights
+    assert np.linalg.norm(w_ls - sch.extras["w_star"]) < 10 * 0.01 * np.sqrt(12 / 10_000)
+
+
+def test_linear_gd_one_learning_rate_per_column():
+    sch = datagen.config0(r_S=500, r_R=20)
+    tg = oracle.Target(sch)
+    y = datagen.finish_labels("linear", oracle.lmm(tg, sch.extras["w_star"].reshape(-1, 1)), sch.extras["noise"])
+    lrs = [0.05, 0.3, 1.0]
+    W, L = oracle.gd(tg, "linear", y, np.zeros((12, 3)), lrs, 7)
+    for c, g in enumerate(lrs):
+        Wc, Lc = oracle.gd(tg, "linear", y, np.zeros((12, 1)), [g], 7)
+        np.testing.assert_allclose(W[:, c], Wc[:, 0], rtol=1e-13, atol=1e-15)
+        np.testing.assert_allclose(L[:, c], Lc[:, 0], rtol=1e-13)
+
+
+# ------------------------------------------------------------------ logistic regression
+def _small_logistic():
+    sch = datagen.config2(r_S=3000, dim_rows=(100, 50, 10))
+    tg = oracle.Target(sch)
+    y01 = datagen.finish_labels("logistic", oracle.lmm(tg, sch.extras["w_star"].reshape(-1, 1)), sch.extras["noise"])
+    return sch, tg, y01
+
+
+def test_logistic_at_zero_weights():
+    sch, tg, y01 = _small_logistic()
+    loss, grad = oracle.logistic_loss_grad(tg, y01, np.zeros((sch.c_T, 1)))
+    assert abs(loss[0] - np.log(2.0)) < 1e-15
+    T = tg.T32.astype(np.float64)
+    np.testing.assert_allclose(grad[:, 0], T.T @ (0.5 - y01.astype(np.float64)) / sch.r_T, rtol=1e-12, atol=1e-15)
+    assert set(np.unique(y01)) == {0.0, 1.0}
+
+
+def test_logistic_gradient_finite_difference():
+    sch, tg, y01 = _small_logistic()
+    rng = datagen.rng_for(5)
+    w = 0.3 * rng.standard_normal((sch.c_T, 1))
+    _, grad = oracle.logistic_loss_grad(tg, y01, w)
+    h = 1e-6
+    for j in rng.choice(sch.c_T, size=12, replace=False):
+        d = np.zeros_like(w); d[j] = h
+        lp, _ = oracle.logistic_loss_grad(tg, y01, w + d)
+        lm, _ = oracle.logistic_loss_grad(tg, y01, w - d)
+        assert abs((lp[0] - lm[0]) / (2 * h) - grad[j, 0]) < 1e-8
+
+
+def test_logistic_loss_matches_plus_minus_one_form_and_decreases():
+    sch, tg, y01 = _small_logistic()
+    rng = datagen.rng_for(6)
+    w = 0.2 * rng.standard_normal((sch.c_T, 1))
+    loss, _ = oracle.logistic_loss_grad(tg, y01, w)
+    z = (tg.T32.astype(np.float64) @ w)[:, 0]
+    ypm = 2.0 * y01.astype(np.float64) - 1.0
+    assert abs(loss[0] - np.mean(np.log1p(np.exp(-ypm * z)))) < 1e-12
+    # 50 Zipf keys put a quarter of the rows on one key: the curvature bound needs a small step here
+    _, losses = oracle.gd(tg, "logistic", y01, np.zeros((sch.c_T, 1)), [0.05], 15)
+    assert np.all(np.diff(losses[:, 0]) < 0)
+
+
+def test_logistic_stable_for_large_logits():
+    T = np.array([[800.0], [-800.0]], dtype=np.float32)
+    tg = oracle.Target(table=T)
+    loss, grad = oracle.logistic_loss_grad(tg, np.array([1.0, 0.0]), np.ones((1, 1)))
+    assert np.isfinite(loss[0]) and loss[0] < 1e-300 + 1e-12
+    assert np.all(np.isfinite(grad))
+
+
+# ------------------------------------------------------------------ generators
+def test_zipf_keys_head_mass():
+    rng = datagen.rng_for(2)
+    keys = datagen.bounded_zipf_keys(rng, 400_000, 50_000, 1.1)
+    cnt = np.sort(np.bincount(keys, minlength=50_000))[::-1]
+    H = np.sum(np.arange(1, 50_001, dtype=np.float64) ** -1.1)
+    assert abs(cnt[0] / 400_000 - 1.0 / H) < 0.01
+    assert abs(cnt[1] / cnt[0] - 2 ** -1.1) < 0.03
+
+
+def test_generators_are_seeded():
+    a, b = datagen.config0(), datagen.config0()
+    assert all(np.array_equal(x.D, y.D) for x, y in zip(a.sources, b.sources))
+    assert np.array_equal(a.sources[1].row_idx, b.sources[1].row_idx)
+    c = datagen.config0(seed=5)
+    assert not np.array_equal(a.sources[0].D, c.sources[0].D)
+
+
+def test_complexity_formula_tab2():
+    sch = datagen.config1(r_S=1000, r_R=100, c_R=200)
+    mat, fact = oracle.complexity_lmm(sch, 1)
+    assert mat == 1 * 1000 * 220 + 1000 * 220
+    assert fact == (1000 * 20 + 1000 * 220) + (100 * 200 + 100 * 220)
