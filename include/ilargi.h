@@ -1,0 +1,139 @@
+/*
+ * ilargi.h -- C ABI of the MI355X (gfx950) library for factorized linear algebra over a target
+ * table that is never built:
+ *
+ *     T = I_1 D_1 M_1^T + ... + I_n D_n M_n^T                 (paper, Sec. 2.2, rewrite rule)
+ *
+ * D_k  source table k (the paper's S_k), r_k x c_k, float32, row-major, leading dimension c_k.
+ * I_k  indicator matrix (paper, Def. 2), logically r_T x r_k binary with at most one 1 per row.
+ *      Stored compressed as row_idx: int32[r_T], row_idx[i] = the row of D_k that feeds target row
+ *      i, or -1 when target row i takes nothing from source k.  Never stored as a matrix.
+ * M_k  mapping matrix (paper, Def. 1), c_T x c_k binary, at most one 1 per row and per column.
+ *      Stored compressed as col_map: int32[c_k], col_map[j] = target column of source column j, or
+ *      -1 when the column is dropped.  Different sources may map to the same target column; their
+ *      contributions are summed, as the rewrite rule says.
+ *
+ * Conventions for every call
+ *   - Matrices are dense float32, row-major, with no padding between rows.
+ *   - "device" pointers are HIP device addresses valid on the current device; "host" pointers are
+ *     ordinary process memory.  The library never takes ownership of caller memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Operator calls only
+ *     enqueue work on that stream and return; outputs are valid once the stream has reached that
+ *     point.  ilargi_plan_create synchronizes the stream before it returns.
+ *   - The library allocates no device memory.  All device state of a plan (inverse indices, column
+ *     tables, intermediates, reduction partials) lives in the caller's workspace, whose size
+ *     ilargi_plan_workspace_bytes reports.  Calls that share a plan must not overlap in time.
+ *   - Every call returns an ilargi_status_t and never throws or aborts.  On an error detected
+ *     before launch, outputs are untouched.  ilargi_last_error() gives a message for the last
+ *     failure on the calling thread.
+ *   - Floating-point results are deterministic: the same plan and inputs give the same bits on
+ *     every run; no floating-point atomics are used.
+ */
+#ifndef ILARGI_H_
+#define ILARGI_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ilargi_plan ilargi_plan_t; /* opaque; host object owned by the library */
+
+typedef enum {
+  ILARGI_OK = 0,
+  ILARGI_ERR_NULL = 1,        /* a required pointer is NULL */
+  ILARGI_ERR_SHAPE = 2,       /* negative or inconsistent sizes */
+  ILARGI_ERR_COLMAP = 3,      /* col_map entry outside [-1, c_T) or two columns of one source share a target */
+  ILARGI_ERR_INDEX_RANGE = 4, /* row_idx entry outside [-1, r_k) */
+  ILARGI_ERR_WORKSPACE = 5,   /* workspace too small or misaligned, or cx / m above max_cx */
+  ILARGI_ERR_UNSUPPORTED = 6, /* combination of arguments that has no kernel */
+  ILARGI_ERR_DEVICE = 7       /* a HIP call failed */
+} ilargi_status_t;
+
+typedef enum {
+  ILARGI_F32 = 0,            /* float32 operands, float32 accumulation */
+  ILARGI_BF16_IN_F32_ACC = 1 /* table and X/W entries rounded to bfloat16 (nearest even) as they are
+                                read, products accumulated in float32; wide operands only */
+} ilargi_precision_t;
+
+typedef enum { ILARGI_LINEAR = 0, ILARGI_LOGISTIC = 1 } ilargi_model_t;
+
+typedef struct {
+  const float* D;         /* device, rows x cols; borrowed: must stay alive and unchanged while the plan lives */
+  int64_t rows, cols;     /* r_k, c_k (both may be 0) */
+  const int32_t* row_idx; /* device int32[r_T], borrowed; NULL = identity (requires rows == r_T) */
+  const int32_t* col_map; /* HOST int32[cols]; copied when the plan is created */
+} ilargi_source_t;
+
+/* Bytes of device workspace a plan over these shapes needs when operands have at most max_cx
+ * columns (X / Y / W columns).  Reads only sizes and whether row_idx is NULL; touches no device.
+ * Errors: NULL, SHAPE. */
+ilargi_status_t ilargi_plan_workspace_bytes(int n, const ilargi_source_t* sources, int64_t r_T,
+                                            int64_t c_T, int64_t max_cx, size_t* bytes);
+
+/* Build a plan: validate shapes and column maps (Def. 1), range-check row_idx on the device
+ * (Def. 2) and build, for every source whose row_idx is not the identity, the inverse index of
+ * I_k in compressed-row form: rowptr int32[r_k+1] and perm int32[nnz_k], the target rows fed by
+ * each source row, ascending within a source row.  `workspace` is device memory, 256-byte aligned,
+ * of at least the reported size, owned by the caller and used by the plan until it is destroyed.
+ * Errors: NULL, SHAPE, COLMAP, INDEX_RANGE, WORKSPACE, DEVICE.  *plan is written only on success. */
+ilargi_status_t ilargi_plan_create(int n, const ilargi_source_t* sources, int64_t r_T, int64_t c_T,
+                                   int64_t max_cx, void* workspace, size_t workspace_bytes,
+                                   void* stream, ilargi_plan_t** plan);
+
+/* Release the host object.  The workspace and all borrowed arrays stay with the caller. */
+ilargi_status_t ilargi_plan_destroy(ilargi_plan_t* plan);
+
+/* Left multiply (paper, Sec. 2.2):  out = T X = sum_k I_k (D_k (M_k^T X)).
+ * X device c_T x cx, out device r_T x cx, 1 <= cx <= max_cx.  Errors: NULL, WORKSPACE, UNSUPPORTED. */
+ilargi_status_t ilargi_lmm(ilargi_plan_t* plan, const float* X, int64_t cx, float* out,
+                           ilargi_precision_t precision, void* stream);
+
+/* Transposed multiply (the transpose operator of Sec. 2.2 / Alg. 1):
+ * out = T^T Y = sum_k M_k (D_k^T (I_k^T Y)).  Y device r_T x cx, out device c_T x cx. */
+ilargi_status_t ilargi_tmm(ilargi_plan_t* plan, const float* Y, int64_t cx, float* out,
+                           ilargi_precision_t precision, void* stream);
+
+/* Gram matrix  out = T^T T = sum_k sum_l M_k D_k^T (I_k^T I_l) D_l M_l^T, cross terms included.
+ * out device c_T x c_T, both triangles written. */
+ilargi_status_t ilargi_crossprod(ilargi_plan_t* plan, float* out, void* stream);
+
+/* Join-gather baseline: write the materialized target table.  T device r_T x c_T.  Each cell is the
+ * float32 sum, in source order starting from +0.0, of the source cells mapped to it; cells nobody
+ * maps to are +0.0.  The result is reproducible bit for bit. */
+ilargi_status_t ilargi_materialize(ilargi_plan_t* plan, float* T, void* stream);
+
+/* One gradient-descent iteration of Alg. 1 for m models at once, without materializing T:
+ *   Z = T W;   E = Z - y (LINEAR)  or  sigmoid(Z) - y (LOGISTIC, y in {0,1});
+ *   G = T^T E / r_T;   W[:, j] -= lr[j] * G[:, j].
+ * Alg. 1 prints the update without the 1/r_T factor; pass lr = gamma * r_T to obtain it.
+ * loss[j] (optional, device float[m]) receives the loss at the weights the call started from:
+ * ||Z - y||^2 / (2 r_T) for LINEAR, mean(softplus(Z) - y Z) for LOGISTIC.
+ * W device c_T x m in/out, y device float[r_T], lr device float[m], 1 <= m <= max_cx. */
+ilargi_status_t ilargi_gd_step(ilargi_plan_t* plan, ilargi_model_t model, float* W, int64_t m,
+                               const float* y, const float* lr, float* loss,
+                               ilargi_precision_t precision, void* stream);
+
+/* I_k^T Y for one source (the segmented sum inside ilargi_tmm), exposed for inspection:
+ * Z[j, :] = sum of Y[i, :] over the target rows i with row_idx_k[i] == j.
+ * Y device r_T x cx, Z device r_k x cx. */
+ilargi_status_t ilargi_segment_sum(ilargi_plan_t* plan, int k, const float* Y, int64_t cx, float* Z,
+                                   void* stream);
+
+/* Device pointers to the inverse index of source k inside the workspace (valid while the plan
+ * lives).  For an identity source *rowptr and *perm are NULL and *nnz = r_k. */
+ilargi_status_t ilargi_plan_inverse_index(const ilargi_plan_t* plan, int k, const int32_t** rowptr,
+                                          const int32_t** perm, int64_t* nnz);
+
+/* Message for the most recent failure on this thread ("" if none).  Static storage. */
+const char* ilargi_last_error(void);
+
+/* Library version, "major.minor". */
+const char* ilargi_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ILARGI_H_ */

@@ -1,0 +1,283 @@
+"""Python binding of libilargi (MI355X / gfx950): factorized linear algebra over
+``T = sum_k I_k D_k M_k^T`` (paper, Sec. 2.1-2.2).
+
+The binding only marshals arguments: torch tensors become raw device pointers plus the current
+HIP stream, and every step of every operator runs in the library's kernels.  There is no CPU or
+PyTorch fallback: importing this package fails if the compiled library is missing.
+
+Functions carry the names of the C entry points declared in ``include/ilargi.h``.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libilargi.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()' "
+        "or python paper_2502_01985_amd/build.py). There is no fallback path.")
+
+lib = ctypes.CDLL(LIB_PATH)
+
+OK, ERR_NULL, ERR_SHAPE, ERR_COLMAP, ERR_INDEX_RANGE, ERR_WORKSPACE, ERR_UNSUPPORTED, ERR_DEVICE = range(8)
+F32, BF16_IN_F32_ACC = 0, 1
+LINEAR, LOGISTIC = 0, 1
+STATUS_NAMES = ["OK", "ERR_NULL", "ERR_SHAPE", "ERR_COLMAP", "ERR_INDEX_RANGE", "ERR_WORKSPACE",
+                "ERR_UNSUPPORTED", "ERR_DEVICE"]
+
+EXPORTED = [
+    "ilargi_plan_workspace_bytes", "ilargi_plan_create", "ilargi_plan_destroy", "ilargi_lmm", "ilargi_tmm",
+    "ilargi_crossprod", "ilargi_materialize", "ilargi_gd_step", "ilargi_segment_sum",
+    "ilargi_plan_inverse_index", "ilargi_last_error", "ilargi_version",
+]
+
+
+class SourceStruct(ctypes.Structure):
+    _fields_ = [("D", ctypes.c_void_p), ("rows", ctypes.c_int64), ("cols", ctypes.c_int64),
+                ("row_idx", ctypes.c_void_p), ("col_map", ctypes.c_void_p)]
+
+
+_vp, _i64, _int = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
+lib.ilargi_plan_workspace_bytes.argtypes = [_int, ctypes.POINTER(SourceStruct), _i64, _i64, _i64,
+                                            ctypes.POINTER(ctypes.c_size_t)]
+lib.ilargi_plan_create.argtypes = [_int, ctypes.POINTER(SourceStruct), _i64, _i64, _i64, _vp, ctypes.c_size_t, _vp,
+                                   ctypes.POINTER(_vp)]
+lib.ilargi_plan_destroy.argtypes = [_vp]
+lib.ilargi_lmm.argtypes = [_vp, _vp, _i64, _vp, _int, _vp]
+lib.ilargi_tmm.argtypes = [_vp, _vp, _i64, _vp, _int, _vp]
+lib.ilargi_crossprod.argtypes = [_vp, _vp, _vp]
+lib.ilargi_materialize.argtypes = [_vp, _vp, _vp]
+lib.ilargi_gd_step.argtypes = [_vp, _int, _vp, _i64, _vp, _vp, _vp, _int, _vp]
+lib.ilargi_segment_sum.argtypes = [_vp, _int, _vp, _i64, _vp, _vp]
+lib.ilargi_plan_inverse_index.argtypes = [_vp, _int, ctypes.POINTER(_vp), ctypes.POINTER(_vp), ctypes.POINTER(_i64)]
+for _name in EXPORTED[:-2]:
+    getattr(lib, _name).restype = _int
+lib.ilargi_last_error.restype = ctypes.c_char_p
+lib.ilargi_version.restype = ctypes.c_char_p
+
+
+class IlargiError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = lib.ilargi_last_error().decode()
+        super().__init__(f"{where}: {STATUS_NAMES[status] if 0 <= status < 8 else status}: {msg}")
+
+
+def _check(status: int, where: str) -> None:
+    if status != OK:
+        raise IlargiError(status, where)
+
+
+def ilargi_last_error() -> str:
+    return lib.ilargi_last_error().decode()
+
+
+def ilargi_version() -> str:
+    return lib.ilargi_version().decode()
+
+
+def _torch():
+    import torch
+    return torch
+
+
+def _stream_ptr(stream=None) -> int:
+    torch = _torch()
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return int(s.cuda_stream)
+
+
+def _dev_f32(t, name: str):
+    torch = _torch()
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()):
+        raise TypeError(f"{name} must be a contiguous float32 CUDA tensor")
+    return t
+
+
+def make_source_array(sources: Sequence[Tuple[int, int, int, int, np.ndarray]]):
+    """ctypes array from ``(D_ptr, rows, cols, row_idx_ptr_or_0, col_map int32 ndarray)`` tuples.
+    Returns the array and the objects that must stay alive while it is used."""
+    arr = (SourceStruct * len(sources))()
+    keep = []
+    for k, (dptr, rows, cols, iptr, cmap) in enumerate(sources):
+        cm = np.ascontiguousarray(cmap, dtype=np.int32)
+        keep.append(cm)
+        arr[k].D = dptr or None
+        arr[k].rows = rows
+        arr[k].cols = cols
+        arr[k].row_idx = iptr or None
+        arr[k].col_map = cm.ctypes.data if cm.size else None
+    return arr, keep
+
+
+def ilargi_plan_workspace_bytes(sources, r_T: int, c_T: int, max_cx: int) -> int:
+    arr, _keep = make_source_array(sources)
+    out = ctypes.c_size_t(0)
+    _check(lib.ilargi_plan_workspace_bytes(len(sources), arr, r_T, c_T, max_cx, ctypes.byref(out)),
+           "ilargi_plan_workspace_bytes")
+    return int(out.value)
+
+
+class Plan:
+    """Owns the plan handle, its device workspace and references to the borrowed tensors."""
+
+    def __init__(self, handle: int, workspace, borrowed, r_T: int, c_T: int, max_cx: int, src_shapes):
+        self.handle = handle
+        self.workspace = workspace
+        self._borrowed = borrowed
+        self.r_T, self.c_T, self.max_cx = r_T, c_T, max_cx
+        self.src_shapes = src_shapes
+
+    def destroy(self) -> None:
+        if self.handle:
+            lib.ilargi_plan_destroy(self.handle)
+            self.handle = 0
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def ilargi_plan_create(sources, r_T: int, c_T: int, max_cx: int = 1, stream=None) -> Plan:
+    """``sources``: list of ``(D, row_idx, col_map)`` with ``D`` a float32 CUDA tensor ``r_k x c_k``,
+    ``row_idx`` an int32 CUDA tensor of length ``r_T`` or ``None`` (identity) and ``col_map`` an int32
+    host array of length ``c_k``."""
+    torch = _torch()
+    tuples, borrowed, shapes = [], [], []
+    for D, row_idx, col_map in sources:
+        _dev_f32(D, "D")
+        if D.dim() != 2:
+            raise TypeError("D must be 2-D")
+        if row_idx is not None:
+            if not (row_idx.is_cuda and row_idx.dtype == torch.int32 and row_idx.is_contiguous()
+                    and row_idx.numel() == r_T):
+                raise TypeError("row_idx must be a contiguous int32 CUDA tensor of length r_T")
+        borrowed.append((D, row_idx))
+        shapes.append((int(D.shape[0]), int(D.shape[1])))
+        tuples.append((D.data_ptr(), int(D.shape[0]), int(D.shape[1]),
+                       row_idx.data_ptr() if row_idx is not None else 0, np.asarray(col_map, dtype=np.int32)))
+    arr, keep = make_source_array(tuples)
+    nbytes = ctypes.c_size_t(0)
+    _check(lib.ilargi_plan_workspace_bytes(len(tuples), arr, r_T, c_T, max_cx, ctypes.byref(nbytes)),
+           "ilargi_plan_workspace_bytes")
+    workspace = torch.empty(int(nbytes.value) + 256, dtype=torch.uint8, device=sources[0][0].device)
+    base = workspace.data_ptr()
+    aligned = (base + 255) // 256 * 256
+    handle = _vp(0)
+    _check(lib.ilargi_plan_create(len(tuples), arr, r_T, c_T, max_cx, aligned, int(nbytes.value),
+                                  _stream_ptr(stream), ctypes.byref(handle)), "ilargi_plan_create")
+    del keep
+    return Plan(handle.value, workspace, borrowed, r_T, c_T, max_cx, shapes)
+
+
+def ilargi_lmm(plan: Plan, X, out=None, precision: int = F32, stream=None):
+    torch = _torch()
+    _dev_f32(X, "X")
+    cx = X.shape[1] if X.dim() == 2 else 1
+    if X.numel() != plan.c_T * cx:
+        raise ValueError("X must be c_T x cx")
+    if out is None:
+        out = torch.empty((plan.r_T, cx), dtype=torch.float32, device=X.device)
+    _dev_f32(out, "out")
+    _check(lib.ilargi_lmm(plan.handle, X.data_ptr(), cx, out.data_ptr(), precision, _stream_ptr(stream)), "ilargi_lmm")
+    return out
+
+
+def ilargi_tmm(plan: Plan, Y, out=None, precision: int = F32, stream=None):
+    torch = _torch()
+    _dev_f32(Y, "Y")
+    cx = Y.shape[1] if Y.dim() == 2 else 1
+    if Y.numel() != plan.r_T * cx:
+        raise ValueError("Y must be r_T x cx")
+    if out is None:
+        out = torch.empty((plan.c_T, cx), dtype=torch.float32, device=Y.device)
+    _dev_f32(out, "out")
+    _check(lib.ilargi_tmm(plan.handle, Y.data_ptr(), cx, out.data_ptr(), precision, _stream_ptr(stream)), "ilargi_tmm")
+    return out
+
+
+def ilargi_crossprod(plan: Plan, out=None, stream=None):
+    torch = _torch()
+    if out is None:
+        out = torch.empty((plan.c_T, plan.c_T), dtype=torch.float32, device=plan.workspace.device)
+    _dev_f32(out, "out")
+    _check(lib.ilargi_crossprod(plan.handle, out.data_ptr(), _stream_ptr(stream)), "ilargi_crossprod")
+    return out
+
+
+def ilargi_materialize(plan: Plan, out=None, stream=None):
+    torch = _torch()
+    if out is None:
+        out = torch.empty((plan.r_T, plan.c_T), dtype=torch.float32, device=plan.workspace.device)
+    _dev_f32(out, "T")
+    _check(lib.ilargi_materialize(plan.handle, out.data_ptr(), _stream_ptr(stream)), "ilargi_materialize")
+    return out
+
+
+def ilargi_gd_step(plan: Plan, model: int, W, y, lr, loss=None, precision: int = F32, stream=None):
+    """In-place update of ``W`` (``c_T x m``); ``loss`` (optional, float32[m]) receives the pre-update loss."""
+    _dev_f32(W, "W"); _dev_f32(y, "y"); _dev_f32(lr, "lr")
+    m = W.shape[1] if W.dim() == 2 else 1
+    if W.numel() != plan.c_T * m or y.numel() != plan.r_T or lr.numel() != m:
+        raise ValueError("W must be c_T x m, y of length r_T, lr of length m")
+    lptr = 0
+    if loss is not None:
+        _dev_f32(loss, "loss")
+        if loss.numel() != m:
+            raise ValueError("loss must have m entries")
+        lptr = loss.data_ptr()
+    _check(lib.ilargi_gd_step(plan.handle, model, W.data_ptr(), m, y.data_ptr(), lr.data_ptr(), lptr or None,
+                              precision, _stream_ptr(stream)), "ilargi_gd_step")
+    return W
+
+
+def ilargi_segment_sum(plan: Plan, k: int, Y, out=None, stream=None):
+    torch = _torch()
+    _dev_f32(Y, "Y")
+    cx = Y.shape[1] if Y.dim() == 2 else 1
+    if Y.numel() != plan.r_T * cx:
+        raise ValueError("Y must be r_T x cx")
+    if out is None:
+        out = torch.empty((plan.src_shapes[k][0], cx), dtype=torch.float32, device=Y.device)
+    _check(lib.ilargi_segment_sum(plan.handle, k, Y.data_ptr(), cx, out.data_ptr(), _stream_ptr(stream)),
+           "ilargi_segment_sum")
+    return out
+
+
+def ilargi_plan_inverse_index(plan: Plan, k: int):
+    """``(rowptr, perm)`` of source ``k`` copied to host int32 arrays, or ``(None, None)`` for an identity source."""
+    torch = _torch()
+    rp, pm, nnz = _vp(0), _vp(0), _i64(0)
+    _check(lib.ilargi_plan_inverse_index(plan.handle, k, ctypes.byref(rp), ctypes.byref(pm), ctypes.byref(nnz)),
+           "ilargi_plan_inverse_index")
+    if not rp.value:
+        return None, None
+    torch.cuda.synchronize()
+    ws = plan.workspace
+    base = ws.data_ptr()
+    r_k = plan.src_shapes[k][0]
+
+    def view(ptr, count):
+        off = ptr - base
+        return ws[off:off + 4 * count].view(torch.int32).cpu().numpy().copy()
+
+    return view(rp.value, r_k + 1), view(pm.value, int(nnz.value))
+
+
+def schema_to_device(schema, device="cuda:0"):
+    """Uploads a ``datagen.Schema`` and returns the ``(D, row_idx, col_map)`` list for ilargi_plan_create."""
+    torch = _torch()
+    out = []
+    for s in schema.sources:
+        D = torch.from_numpy(np.ascontiguousarray(s.D)).to(device)
+        idx = None if s.row_idx is None else torch.from_numpy(np.ascontiguousarray(s.row_idx)).to(device)
+        out.append((D, idx, s.col_map))
+    return out

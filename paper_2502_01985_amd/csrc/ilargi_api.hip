@@ -1,0 +1,631 @@
+// C ABI of libilargi: argument validation, the plan (workspace layout, inverse indices, column tables)
+// and the sequencing of kernels for each operator.  See include/ilargi.h for the contract of every call.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <new>
+#include <vector>
+
+#include "ilargi_internal.h"
+
+using namespace ilargi;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+ilargi_status_t fail(ilargi_status_t code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+#define HIP_TRY(expr)                                                                        \
+  do {                                                                                       \
+    hipError_t e_ = (expr);                                                                  \
+    if (e_ != hipSuccess) return fail(ILARGI_ERR_DEVICE, "%s: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+constexpr size_t kAlign = 256;
+size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+struct SourcePlan {
+  const float* D = nullptr;
+  int64_t rows = 0, cols = 0;
+  const int32_t* idx = nullptr;   // caller's row_idx (device) or NULL
+  bool has_idx = false;           // row_idx was given
+  bool ident = false;             // identity on the first `rows` target rows, nothing beyond
+  bool empty = false;             // contributes nothing (no rows or no columns)
+  int vec = 1;
+  std::vector<int32_t> colmap_h;
+  // offsets into the workspace
+  size_t o_colmap = 0, o_tcol = 0, o_rowptr = 0, o_perm = 0, o_chunk_seg = 0, o_chunk_beg = 0, o_chunk_end = 0,
+         o_long_seg = 0, o_long_first = 0, o_chunk_partial = 0, o_pz = 0, o_partial = 0;
+  int64_t nch_max = 0, nl_max = 0;
+  int n_chunks = 0, n_long = 0;
+  int64_t nnz = 0;
+  int logG = 0;
+};
+
+struct Layout {
+  size_t o_flags = 0, o_tcol_table = 0, o_pairs = 0, o_E = 0, o_loss = 0, o_sort = 0, o_hist = 0, o_zc = 0,
+         o_gpartial = 0, o_blocks = 0;
+  int64_t zc_floats = 0, gpartial_floats = 0, blocks_floats = 0;
+  size_t total = 0;
+};
+
+}  // namespace
+
+struct ilargi_plan {
+  int n = 0;
+  int64_t r_T = 0, c_T = 0, max_cx = 0;
+  char* ws = nullptr;
+  size_t ws_bytes = 0;
+  std::vector<SourcePlan> src;
+  Layout lay;
+  int fused = -1;   // identity source whose product is fused into the assembly pass
+  int npairs = 0;
+  std::vector<size_t> block_off;  // offset (floats) of Gram block (k,l), k <= l, index k * n + l
+  template <class T> T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
+};
+
+namespace {
+
+int64_t colred_rows_per_block(int64_t rows) {
+  int64_t rpb = (rows + kColredBlocks - 1) / kColredBlocks;
+  rpb = (rpb + 63) / 64 * 64;
+  return rpb < 64 ? 64 : rpb;
+}
+int colred_nblocks(int64_t rows) {
+  int64_t rpb = colred_rows_per_block(rows);
+  return (int)((rows + rpb - 1) / rpb);
+}
+
+// Shape-only part of a plan: fills the offsets of every workspace region.
+ilargi_status_t make_layout(int n, const ilargi_source_t* s, int64_t r_T, int64_t c_T, int64_t max_cx,
+                            std::vector<SourcePlan>& src, Layout& lay) {
+  if (s == nullptr) return fail(ILARGI_ERR_NULL, "sources is NULL");
+  if (n < 1 || n > kMaxSources) return fail(ILARGI_ERR_SHAPE, "n = %d outside [1, %d]", n, kMaxSources);
+  if (r_T < 0 || r_T > 2147483646ll) return fail(ILARGI_ERR_SHAPE, "r_T = %lld out of range", (long long)r_T);
+  if (c_T < 1 || c_T > (1 << 20)) return fail(ILARGI_ERR_SHAPE, "c_T = %lld outside [1, 2^20]", (long long)c_T);
+  if (max_cx < 1 || max_cx > 65536) return fail(ILARGI_ERR_SHAPE, "max_cx = %lld outside [1, 65536]", (long long)max_cx);
+  src.assign(n, SourcePlan());
+  int64_t cmax = 1;
+  for (int k = 0; k < n; ++k) {
+    if (s[k].rows < 0 || s[k].cols < 0 || s[k].rows > 2147483646ll)
+      return fail(ILARGI_ERR_SHAPE, "source %d: rows = %lld, cols = %lld", k, (long long)s[k].rows, (long long)s[k].cols);
+    if (s[k].cols > kMaxLdsFloats)
+      return fail(ILARGI_ERR_UNSUPPORTED, "source %d: more than %d columns", k, kMaxLdsFloats);
+    if (s[k].row_idx == nullptr && s[k].rows != r_T)
+      return fail(ILARGI_ERR_SHAPE, "source %d: NULL row_idx (identity) needs rows == r_T", k);
+    src[k].rows = s[k].rows;
+    src[k].cols = s[k].cols;
+    src[k].has_idx = s[k].row_idx != nullptr;
+    src[k].empty = s[k].rows == 0 || s[k].cols == 0;
+    cmax = std::max<int64_t>(cmax, s[k].cols);
+  }
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+  lay.o_flags = take(sizeof(int32_t) * 2 * n);
+  lay.o_tcol_table = take(sizeof(void*) * n);
+  lay.o_pairs = take(sizeof(GramAsmPair) * n * (n + 1) / 2);
+  const int64_t wmax = std::max<int64_t>(max_cx, cmax);
+  for (int k = 0; k < n; ++k) {
+    SourcePlan& p = src[k];
+    p.o_colmap = take(sizeof(int32_t) * std::max<int64_t>(p.cols, 1));
+    p.o_tcol = take(sizeof(int32_t) * c_T);
+    if (p.has_idx) {
+      p.o_rowptr = take(sizeof(int32_t) * (p.rows + 1));
+      p.o_perm = take(sizeof(int32_t) * std::max<int64_t>(r_T, 1));
+      p.nl_max = r_T / kLongSeg + 1;
+      p.nch_max = r_T / kSegChunk + p.nl_max + 1;
+      p.o_chunk_seg = take(sizeof(int32_t) * p.nch_max);
+      p.o_chunk_beg = take(sizeof(int32_t) * p.nch_max);
+      p.o_chunk_end = take(sizeof(int32_t) * p.nch_max);
+      p.o_long_seg = take(sizeof(int32_t) * p.nl_max);
+      p.o_long_first = take(sizeof(int32_t) * (p.nl_max + 1));
+      p.o_chunk_partial = take(sizeof(float) * p.nch_max * wmax);
+    }
+    p.o_pz = take(sizeof(float) * std::max<int64_t>(p.rows, 1) * max_cx);
+    p.o_partial = take(sizeof(float) * kColredBlocks * std::max<int64_t>(p.cols, 1) * kNarrowCT);
+  }
+  lay.o_E = take(sizeof(float) * std::max<int64_t>(r_T, 1) * max_cx);
+  lay.o_loss = take(sizeof(float) * 2048 * kNarrowCT);
+  lay.o_sort = take(sizeof(int32_t) * 4 * std::max<int64_t>(r_T, 1));
+  lay.o_hist = take(sizeof(int32_t) * sort_hist_ints(r_T));
+  // Gram scratch: summed rows for the "via sums" route, chunk partials, the (k,l) blocks
+  lay.zc_floats = 1;
+  lay.gpartial_floats = kGramPartialFloats;
+  lay.blocks_floats = 0;
+  for (int k = 0; k < n; ++k)
+    for (int l = k; l < n; ++l) {
+      int64_t cc = src[k].cols * src[l].cols;
+      lay.blocks_floats += cc;
+      lay.gpartial_floats = std::max(lay.gpartial_floats, cc);
+      if (l > k) {
+        if (src[l].has_idx && src[l].rows * 2 <= r_T) lay.zc_floats = std::max(lay.zc_floats, src[l].rows * src[k].cols);
+        if (src[k].has_idx && src[k].rows * 2 <= r_T) lay.zc_floats = std::max(lay.zc_floats, src[k].rows * src[l].cols);
+      }
+    }
+  lay.o_zc = take(sizeof(float) * lay.zc_floats);
+  lay.o_gpartial = take(sizeof(float) * lay.gpartial_floats);
+  lay.o_blocks = take(sizeof(float) * std::max<int64_t>(lay.blocks_floats, 1));
+  lay.total = off;
+  return ILARGI_OK;
+}
+
+int pick_vec(const float* D, int64_t cols) {
+  uintptr_t a = reinterpret_cast<uintptr_t>(D);
+  if (cols % 4 == 0 && a % 16 == 0) return 4;
+  if (cols % 2 == 0 && a % 8 == 0) return 2;
+  return 1;
+}
+
+int pick_logL(int64_t cols, int vec) {
+  int64_t nvec = cols > 0 ? cols / vec : 1;
+  int l = ilog2_ceil(nvec);
+  return l > 6 ? 6 : l;
+}
+
+// Splits the segments longer than kLongSeg into chunks (host side, once per plan).
+void build_long_tables(const std::vector<int32_t>& rowptr, std::vector<int32_t>& chunk_seg,
+                       std::vector<int32_t>& chunk_beg, std::vector<int32_t>& chunk_end,
+                       std::vector<int32_t>& long_seg, std::vector<int32_t>& long_first) {
+  long_first.push_back(0);
+  for (size_t j = 0; j + 1 < rowptr.size(); ++j) {
+    int32_t b = rowptr[j], e = rowptr[j + 1];
+    if (e - b <= kLongSeg) continue;
+    long_seg.push_back((int32_t)j);
+    for (int32_t c = b; c < e; c += kSegChunk) {
+      chunk_seg.push_back((int32_t)j);
+      chunk_beg.push_back(c);
+      chunk_end.push_back(std::min(e, c + kSegChunk));
+    }
+    long_first.push_back((int32_t)chunk_seg.size());
+  }
+}
+
+SegArgs seg_args(const ilargi_plan* pl, int k) {
+  const SourcePlan& p = pl->src[k];
+  SegArgs a;
+  memset(&a, 0, sizeof(a));
+  a.rowptr = pl->at<int32_t>(p.o_rowptr);
+  a.perm = pl->at<int32_t>(p.o_perm);
+  a.chunk_seg = pl->at<int32_t>(p.o_chunk_seg);
+  a.chunk_beg = pl->at<int32_t>(p.o_chunk_beg);
+  a.chunk_end = pl->at<int32_t>(p.o_chunk_end);
+  a.long_seg = pl->at<int32_t>(p.o_long_seg);
+  a.long_first = pl->at<int32_t>(p.o_long_first);
+  a.n_chunks = p.n_chunks;
+  a.n_long = p.n_long;
+  a.r_k = p.rows;
+  a.gidx = nullptr;
+  a.g_rows = -1;
+  a.chunk_partial = pl->at<float>(p.o_chunk_partial);
+  a.logG = p.logG;
+  return a;
+}
+
+// Widest operand slice one narrow pass can stage in LDS for every source of the plan.
+int pass_width(const ilargi_plan* pl) {
+  int64_t cmax = 1;
+  for (const SourcePlan& p : pl->src) cmax = std::max(cmax, p.cols);
+  int w = (int)std::min<int64_t>(kNarrowCT, kMaxLdsFloats / cmax);
+  return w >= 4 ? 4 : (w >= 2 ? 2 : 1);
+}
+
+// out (or the residual E) for operand columns [col0, col0 + ncols):  per-source products, then the assembly.
+ilargi_status_t lmm_pass(ilargi_plan* pl, const float* X, int ldx, int col0, int ncols, float* out, int ldo,
+                         int mode, const float* y, int* loss_grid, hipStream_t st) {
+  GatherArgs g;
+  memset(&g, 0, sizeof(g));
+  g.ldp = ldx;
+  for (int k = 0; k < pl->n; ++k) {
+    SourcePlan& p = pl->src[k];
+    if (p.empty || k == pl->fused) continue;
+    LmmArgs a;
+    memset(&a, 0, sizeof(a));
+    a.D = p.D; a.d_rows = p.rows; a.ck = (int)p.cols; a.colmap = pl->at<int32_t>(p.o_colmap);
+    a.X = X; a.ldx = ldx; a.col0 = col0; a.ncols = ncols;
+    a.out = pl->at<float>(p.o_pz); a.ldo = ldx; a.r_out = p.rows;
+    a.logL = pick_logL(p.cols, p.vec);
+    HIP_TRY(launch_lmm_rows(a, p.vec, 0, st, nullptr));
+    g.idx[g.n] = p.ident ? nullptr : p.idx;
+    g.P[g.n] = pl->at<float>(p.o_pz);
+    g.rows[g.n] = p.rows;
+    ++g.n;
+  }
+  LmmArgs a;
+  memset(&a, 0, sizeof(a));
+  int vec = 1;
+  if (pl->fused >= 0) {
+    SourcePlan& f = pl->src[pl->fused];
+    a.D = f.D; a.d_rows = f.rows; a.ck = (int)f.cols; a.colmap = pl->at<int32_t>(f.o_colmap);
+    vec = f.vec;
+    a.logL = pick_logL(f.cols, f.vec);
+  }
+  a.X = X; a.ldx = ldx; a.col0 = col0; a.ncols = ncols;
+  a.out = out; a.ldo = ldo; a.r_out = pl->r_T;
+  a.g = g;
+  a.y = y;
+  a.loss_partial = pl->at<float>(pl->lay.o_loss);
+  HIP_TRY(launch_lmm_rows(a, vec, mode, st, loss_grid));
+  return ILARGI_OK;
+}
+
+// T^T Y for operand columns [col0, col0 + ncols); mode 1 turns the finalize step into the update of Alg. 1.
+ilargi_status_t tmm_pass(ilargi_plan* pl, const float* Y, int ldy, int col0, int ncols, float* out, int ldo,
+                         int mode, const float* lr, float* loss, int n_loss_partial, float loss_scale,
+                         hipStream_t st) {
+  FinArgs f;
+  memset(&f, 0, sizeof(f));
+  for (int k = 0; k < pl->n; ++k) {
+    SourcePlan& p = pl->src[k];
+    if (p.empty) continue;
+    ColredArgs c;
+    memset(&c, 0, sizeof(c));
+    c.D = p.D; c.rows = p.rows; c.ck = (int)p.cols; c.vec = p.vec;
+    if (p.ident) {
+      c.Z = Y; c.ldz = ldy; c.col0 = col0;
+    } else {
+      SegArgs s = seg_args(pl, k);
+      s.Y = Y; s.ldy = ldy; s.col0 = col0; s.ncols = ncols;
+      s.Z = pl->at<float>(p.o_pz); s.ldz = ldy; s.zcol0 = col0;
+      HIP_TRY(launch_segsum(s, st));
+      c.Z = pl->at<float>(p.o_pz); c.ldz = ldy; c.col0 = col0;
+    }
+    c.ncols = ncols;
+    c.partial = pl->at<float>(p.o_partial);
+    c.rows_per_block = colred_rows_per_block(p.rows);
+    int nb = colred_nblocks(p.rows);
+    HIP_TRY(launch_colred(c, nb, st));
+    f.s[f.n].tcol2src = pl->at<int32_t>(p.o_tcol);
+    f.s[f.n].partial = c.partial;
+    f.s[f.n].nblocks = nb;
+    f.s[f.n].ck = (int)p.cols;
+    ++f.n;
+  }
+  f.out = out; f.ldo = ldo; f.col0 = col0; f.ncols = ncols;
+  f.lr = lr;
+  f.inv_rT = pl->r_T > 0 ? 1.0f / (float)pl->r_T : 0.0f;
+  f.loss_partial = pl->at<float>(pl->lay.o_loss);
+  f.n_loss_partial = n_loss_partial;
+  f.loss = loss;
+  f.loss_scale = loss_scale;
+  HIP_TRY(launch_finalize(f, (int)pl->c_T, mode, st));
+  return ILARGI_OK;
+}
+
+ilargi_status_t check_call(const ilargi_plan* pl, const void* a, const void* b, int64_t cx, const char* what) {
+  if (pl == nullptr) return fail(ILARGI_ERR_NULL, "%s: plan is NULL", what);
+  if (a == nullptr || b == nullptr) return fail(ILARGI_ERR_NULL, "%s: operand pointer is NULL", what);
+  if (cx < 1) return fail(ILARGI_ERR_SHAPE, "%s: %lld operand columns", what, (long long)cx);
+  if (cx > pl->max_cx)
+    return fail(ILARGI_ERR_WORKSPACE, "%s: %lld operand columns but the plan was sized for %lld", what,
+                (long long)cx, (long long)pl->max_cx);
+  return ILARGI_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* ilargi_last_error(void) { return g_err; }
+const char* ilargi_version(void) { return "0.1"; }
+
+ilargi_status_t ilargi_plan_workspace_bytes(int n, const ilargi_source_t* sources, int64_t r_T, int64_t c_T,
+                                            int64_t max_cx, size_t* bytes) {
+  if (bytes == nullptr) return fail(ILARGI_ERR_NULL, "bytes is NULL");
+  std::vector<SourcePlan> src;
+  Layout lay;
+  ilargi_status_t st = make_layout(n, sources, r_T, c_T, max_cx, src, lay);
+  if (st != ILARGI_OK) return st;
+  *bytes = lay.total;
+  return ILARGI_OK;
+}
+
+ilargi_status_t ilargi_plan_create(int n, const ilargi_source_t* sources, int64_t r_T, int64_t c_T,
+                                   int64_t max_cx, void* workspace, size_t workspace_bytes, void* stream,
+                                   ilargi_plan_t** plan) {
+  if (plan == nullptr) return fail(ILARGI_ERR_NULL, "plan is NULL");
+  std::vector<SourcePlan> src;
+  Layout lay;
+  ilargi_status_t rc = make_layout(n, sources, r_T, c_T, max_cx, src, lay);
+  if (rc != ILARGI_OK) return rc;
+  // column maps (Def. 1): entries in [-1, c_T), no target column hit twice by one source
+  std::vector<std::vector<int32_t>> tcol(n, std::vector<int32_t>((size_t)c_T, -1));
+  for (int k = 0; k < n; ++k) {
+    if (sources[k].cols > 0 && sources[k].col_map == nullptr) return fail(ILARGI_ERR_NULL, "source %d: col_map is NULL", k);
+    if (sources[k].rows > 0 && sources[k].cols > 0 && sources[k].D == nullptr)
+      return fail(ILARGI_ERR_NULL, "source %d: D is NULL", k);
+    src[k].colmap_h.assign(sources[k].col_map, sources[k].col_map + sources[k].cols);
+    for (int64_t j = 0; j < sources[k].cols; ++j) {
+      int32_t t = sources[k].col_map[j];
+      if (t < -1 || t >= c_T) return fail(ILARGI_ERR_COLMAP, "source %d: col_map[%lld] = %d outside [-1, %lld)", k, (long long)j, t, (long long)c_T);
+      if (t < 0) continue;
+      if (tcol[k][t] >= 0) return fail(ILARGI_ERR_COLMAP, "source %d: columns %d and %lld both map to target column %d", k, tcol[k][t], (long long)j, t);
+      tcol[k][t] = (int32_t)j;
+    }
+    src[k].D = sources[k].D;
+    src[k].idx = sources[k].row_idx;
+    src[k].vec = pick_vec(sources[k].D, sources[k].cols);
+  }
+  if (workspace == nullptr) return fail(ILARGI_ERR_NULL, "workspace is NULL");
+  if (reinterpret_cast<uintptr_t>(workspace) % kAlign != 0) return fail(ILARGI_ERR_WORKSPACE, "workspace is not %zu-byte aligned", kAlign);
+  if (workspace_bytes < lay.total) return fail(ILARGI_ERR_WORKSPACE, "workspace has %zu bytes, plan needs %zu", workspace_bytes, lay.total);
+
+  ilargi_plan* pl = new (std::nothrow) ilargi_plan();
+  if (pl == nullptr) return fail(ILARGI_ERR_DEVICE, "out of host memory");
+  struct Guard { ilargi_plan* p; ~Guard() { delete p; } } guard{pl};
+  pl->n = n; pl->r_T = r_T; pl->c_T = c_T; pl->max_cx = max_cx;
+  pl->ws = static_cast<char*>(workspace); pl->ws_bytes = workspace_bytes;
+  pl->src = std::move(src); pl->lay = lay;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+
+  HIP_TRY(hipMemsetAsync(pl->at<int32_t>(lay.o_flags), 0, sizeof(int32_t) * 2 * n, st));
+  std::vector<const int32_t*> tcol_ptrs(n);
+  for (int k = 0; k < n; ++k) {
+    SourcePlan& p = pl->src[k];
+    if (p.cols > 0) HIP_TRY(hipMemcpyAsync(pl->at<int32_t>(p.o_colmap), p.colmap_h.data(), sizeof(int32_t) * p.cols, hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync(pl->at<int32_t>(p.o_tcol), tcol[k].data(), sizeof(int32_t) * c_T, hipMemcpyHostToDevice, st));
+    tcol_ptrs[k] = pl->at<int32_t>(p.o_tcol);
+    if (p.has_idx) HIP_TRY(launch_check_idx(p.idx, r_T, p.rows, pl->at<int32_t>(lay.o_flags) + 2 * k, st));
+  }
+  HIP_TRY(hipMemcpyAsync(pl->at<void*>(lay.o_tcol_table), tcol_ptrs.data(), sizeof(void*) * n, hipMemcpyHostToDevice, st));
+  std::vector<int32_t> flags(2 * n, 0);
+  HIP_TRY(hipMemcpyAsync(flags.data(), pl->at<int32_t>(lay.o_flags), sizeof(int32_t) * 2 * n, hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  for (int k = 0; k < n; ++k) {
+    SourcePlan& p = pl->src[k];
+    if (!p.has_idx) { p.ident = true; p.nnz = p.rows; continue; }
+    if (flags[2 * k] != 0) return fail(ILARGI_ERR_INDEX_RANGE, "source %d: row_idx has an entry outside [-1, %lld)", k, (long long)p.rows);
+    p.ident = flags[2 * k + 1] == 0 && p.rows <= r_T;
+    if (p.ident) p.nnz = p.rows;
+  }
+  // inverse index of every non-identity source (Def. 2, transposed): stable sort by source row
+  for (int k = 0; k < n; ++k) {
+    SourcePlan& p = pl->src[k];
+    if (p.ident) continue;
+    int32_t* sortbuf = pl->at<int32_t>(lay.o_sort);
+    int64_t rr = std::max<int64_t>(r_T, 1);
+    HIP_TRY(launch_sort_by_source_row(p.idx, r_T, p.rows, sortbuf, sortbuf + rr, sortbuf + 2 * rr, sortbuf + 3 * rr,
+                                      pl->at<int32_t>(lay.o_hist), pl->at<int32_t>(p.o_rowptr),
+                                      pl->at<int32_t>(p.o_perm), st));
+    std::vector<int32_t> rowptr((size_t)p.rows + 1);
+    HIP_TRY(hipMemcpyAsync(rowptr.data(), pl->at<int32_t>(p.o_rowptr), sizeof(int32_t) * (p.rows + 1), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    p.nnz = rowptr[(size_t)p.rows];
+    std::vector<int32_t> cs, cb, ce, ls, lf;
+    build_long_tables(rowptr, cs, cb, ce, ls, lf);
+    p.n_chunks = (int)cs.size();
+    p.n_long = (int)ls.size();
+    if (p.n_chunks > p.nch_max || p.n_long > p.nl_max) return fail(ILARGI_ERR_WORKSPACE, "internal: long-segment tables overflow");
+    if (p.n_chunks > 0) {
+      HIP_TRY(hipMemcpyAsync(pl->at<int32_t>(p.o_chunk_seg), cs.data(), sizeof(int32_t) * cs.size(), hipMemcpyHostToDevice, st));
+      HIP_TRY(hipMemcpyAsync(pl->at<int32_t>(p.o_chunk_beg), cb.data(), sizeof(int32_t) * cb.size(), hipMemcpyHostToDevice, st));
+      HIP_TRY(hipMemcpyAsync(pl->at<int32_t>(p.o_chunk_end), ce.data(), sizeof(int32_t) * ce.size(), hipMemcpyHostToDevice, st));
+      HIP_TRY(hipMemcpyAsync(pl->at<int32_t>(p.o_long_seg), ls.data(), sizeof(int32_t) * ls.size(), hipMemcpyHostToDevice, st));
+      HIP_TRY(hipMemcpyAsync(pl->at<int32_t>(p.o_long_first), lf.data(), sizeof(int32_t) * lf.size(), hipMemcpyHostToDevice, st));
+      HIP_TRY(hipStreamSynchronize(st));
+    }
+    int64_t avg = p.rows > 0 ? (p.nnz + p.rows - 1) / p.rows : 1;
+    p.logG = std::min(6, ilog2_ceil(std::max<int64_t>(avg, 1)));
+  }
+  // the identity source with the most cells has its product fused into the assembly pass
+  int64_t best = -1;
+  for (int k = 0; k < n; ++k) {
+    const SourcePlan& p = pl->src[k];
+    if (p.ident && !p.empty && p.rows * p.cols > best) { best = p.rows * p.cols; pl->fused = k; }
+  }
+  // Gram blocks (k <= l) and the table the assembly kernel walks
+  pl->block_off.assign((size_t)n * n, 0);
+  std::vector<GramAsmPair> pairs;
+  size_t boff = 0;
+  for (int k = 0; k < n; ++k)
+    for (int l = k; l < n; ++l) {
+      pl->block_off[(size_t)k * n + l] = boff;
+      if (!pl->src[k].empty && !pl->src[l].empty) {
+        GramAsmPair pr;
+        pr.block = pl->at<float>(lay.o_blocks) + boff;
+        pr.k = k; pr.l = l; pr.cb = (int)pl->src[l].cols;
+        pairs.push_back(pr);
+      }
+      boff += (size_t)(pl->src[k].cols * pl->src[l].cols);
+    }
+  pl->npairs = (int)pairs.size();
+  if (!pairs.empty())
+    HIP_TRY(hipMemcpyAsync(pl->at<GramAsmPair>(lay.o_pairs), pairs.data(), sizeof(GramAsmPair) * pairs.size(), hipMemcpyHostToDevice, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  guard.p = nullptr;
+  *plan = pl;
+  return ILARGI_OK;
+}
+
+ilargi_status_t ilargi_plan_destroy(ilargi_plan_t* plan) {
+  if (plan == nullptr) return fail(ILARGI_ERR_NULL, "plan is NULL");
+  delete plan;
+  return ILARGI_OK;
+}
+
+ilargi_status_t ilargi_plan_inverse_index(const ilargi_plan_t* plan, int k, const int32_t** rowptr,
+                                          const int32_t** perm, int64_t* nnz) {
+  if (plan == nullptr || rowptr == nullptr || perm == nullptr || nnz == nullptr) return fail(ILARGI_ERR_NULL, "inverse_index: NULL argument");
+  if (k < 0 || k >= plan->n) return fail(ILARGI_ERR_SHAPE, "inverse_index: source %d of %d", k, plan->n);
+  const SourcePlan& p = plan->src[k];
+  if (p.ident) { *rowptr = nullptr; *perm = nullptr; *nnz = p.rows; return ILARGI_OK; }
+  *rowptr = plan->at<int32_t>(p.o_rowptr);
+  *perm = plan->at<int32_t>(p.o_perm);
+  *nnz = p.nnz;
+  return ILARGI_OK;
+}
+
+ilargi_status_t ilargi_lmm(ilargi_plan_t* plan, const float* X, int64_t cx, float* out,
+                           ilargi_precision_t precision, void* stream) {
+  ilargi_status_t rc = check_call(plan, X, out, cx, "lmm");
+  if (rc != ILARGI_OK) return rc;
+  if (precision != ILARGI_F32) return fail(ILARGI_ERR_UNSUPPORTED, "lmm: bf16 inputs need a wide operand");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int w = pass_width(plan);
+  for (int64_t col0 = 0; col0 < cx; col0 += w) {
+    int ncols = (int)std::min<int64_t>(w, cx - col0);
+    rc = lmm_pass(plan, X, (int)cx, (int)col0, ncols, out, (int)cx, 0, nullptr, nullptr, st);
+    if (rc != ILARGI_OK) return rc;
+  }
+  return ILARGI_OK;
+}
+
+ilargi_status_t ilargi_tmm(ilargi_plan_t* plan, const float* Y, int64_t cx, float* out,
+                           ilargi_precision_t precision, void* stream) {
+  ilargi_status_t rc = check_call(plan, Y, out, cx, "tmm");
+  if (rc != ILARGI_OK) return rc;
+  if (precision != ILARGI_F32) return fail(ILARGI_ERR_UNSUPPORTED, "tmm: bf16 inputs need a wide operand");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  for (int64_t col0 = 0; col0 < cx; col0 += kNarrowCT) {
+    int ncols = (int)std::min<int64_t>(kNarrowCT, cx - col0);
+    rc = tmm_pass(plan, Y, (int)cx, (int)col0, ncols, out, (int)cx, 0, nullptr, nullptr, 0, 0.0f, st);
+    if (rc != ILARGI_OK) return rc;
+  }
+  return ILARGI_OK;
+}
+
+ilargi_status_t ilargi_gd_step(ilargi_plan_t* plan, ilargi_model_t model, float* W, int64_t m, const float* y,
+                               const float* lr, float* loss, ilargi_precision_t precision, void* stream) {
+  ilargi_status_t rc = check_call(plan, W, y, m, "gd_step");
+  if (rc != ILARGI_OK) return rc;
+  if (lr == nullptr) return fail(ILARGI_ERR_NULL, "gd_step: lr is NULL");
+  if (model != ILARGI_LINEAR && model != ILARGI_LOGISTIC) return fail(ILARGI_ERR_UNSUPPORTED, "gd_step: unknown model %d", (int)model);
+  if (plan->r_T < 1) return fail(ILARGI_ERR_SHAPE, "gd_step: the target table has no rows");
+  if (precision != ILARGI_F32) return fail(ILARGI_ERR_UNSUPPORTED, "gd_step: bf16 inputs need a wide operand");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  float* E = plan->at<float>(plan->lay.o_E);
+  const int w = pass_width(plan);
+  const float loss_scale = (model == ILARGI_LINEAR ? 0.5f : 1.0f) / (float)plan->r_T;
+  for (int64_t col0 = 0; col0 < m; col0 += w) {
+    int ncols = (int)std::min<int64_t>(w, m - col0);
+    int loss_grid = 0;
+    rc = lmm_pass(plan, W, (int)m, (int)col0, ncols, E, (int)m, model == ILARGI_LINEAR ? 1 : 2, y, &loss_grid, st);
+    if (rc != ILARGI_OK) return rc;
+    rc = tmm_pass(plan, E, (int)m, (int)col0, ncols, W, (int)m, 1, lr, loss, loss_grid, loss_scale, st);
+    if (rc != ILARGI_OK) return rc;
+  }
+  return ILARGI_OK;
+}
+
+ilargi_status_t ilargi_segment_sum(ilargi_plan_t* plan, int k, const float* Y, int64_t cx, float* Z, void* stream) {
+  ilargi_status_t rc = check_call(plan, Y, Z, cx, "segment_sum");
+  if (rc != ILARGI_OK) return rc;
+  if (k < 0 || k >= plan->n) return fail(ILARGI_ERR_SHAPE, "segment_sum: source %d of %d", k, plan->n);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const SourcePlan& p = plan->src[k];
+  if (p.rows == 0) return ILARGI_OK;
+  if (p.ident) {
+    HIP_TRY(hipMemcpyAsync(Z, Y, sizeof(float) * p.rows * cx, hipMemcpyDeviceToDevice, st));
+    return ILARGI_OK;
+  }
+  SegArgs s = seg_args(plan, k);
+  s.Y = Y; s.ldy = (int)cx; s.col0 = 0; s.ncols = (int)cx;
+  s.Z = Z; s.ldz = (int)cx; s.zcol0 = 0;
+  HIP_TRY(launch_segsum(s, st));
+  return ILARGI_OK;
+}
+
+ilargi_status_t ilargi_materialize(ilargi_plan_t* plan, float* T, void* stream) {
+  if (plan == nullptr) return fail(ILARGI_ERR_NULL, "materialize: plan is NULL");
+  if (T == nullptr) return fail(ILARGI_ERR_NULL, "materialize: T is NULL");
+  MatArgs a;
+  memset(&a, 0, sizeof(a));
+  for (int k = 0; k < plan->n; ++k) {
+    const SourcePlan& p = plan->src[k];
+    if (p.empty) continue;
+    a.D[a.n] = p.D;
+    a.idx[a.n] = p.ident ? nullptr : p.idx;
+    a.tcol2src[a.n] = plan->at<int32_t>(p.o_tcol);
+    a.rows[a.n] = p.rows;
+    a.ck[a.n] = (int)p.cols;
+    ++a.n;
+  }
+  a.T = T; a.r_T = plan->r_T; a.c_T = (int)plan->c_T;
+  HIP_TRY(launch_materialize(a, static_cast<hipStream_t>(stream)));
+  return ILARGI_OK;
+}
+
+ilargi_status_t ilargi_crossprod(ilargi_plan_t* plan, float* out, void* stream) {
+  if (plan == nullptr) return fail(ILARGI_ERR_NULL, "crossprod: plan is NULL");
+  if (out == nullptr) return fail(ILARGI_ERR_NULL, "crossprod: out is NULL");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int n = plan->n;
+  float* blocks = plan->at<float>(plan->lay.o_blocks);
+  float* gpart = plan->at<float>(plan->lay.o_gpartial);
+  float* zc = plan->at<float>(plan->lay.o_zc);
+  auto run_gram = [&](GramArgs& g, float* block) -> ilargi_status_t {
+    int64_t elems = (int64_t)g.ca * g.cb;
+    int64_t nch = (g.n_rows + 4095) / 4096;
+    nch = std::min<int64_t>(nch, std::max<int64_t>(1, plan->lay.gpartial_floats / elems));
+    nch = std::min<int64_t>(std::max<int64_t>(nch, 1), 1024);
+    g.rows_per_chunk = (g.n_rows + nch - 1) / nch;
+    g.rows_per_chunk = std::max<int64_t>(16, (g.rows_per_chunk + 15) / 16 * 16);
+    nch = std::max<int64_t>(1, (g.n_rows + g.rows_per_chunk - 1) / g.rows_per_chunk);
+    g.partial = gpart;
+    HIP_TRY(launch_gram(g, (int)nch, st));
+    HIP_TRY(launch_gram_reduce(gpart, (int)nch, elems, block, st));
+    return ILARGI_OK;
+  };
+  for (int k = 0; k < n; ++k) {
+    const SourcePlan& a = plan->src[k];
+    if (a.empty) continue;
+    for (int l = k; l < n; ++l) {
+      const SourcePlan& b = plan->src[l];
+      if (b.empty) continue;
+      float* block = blocks + plan->block_off[(size_t)k * n + l];
+      GramArgs g;
+      memset(&g, 0, sizeof(g));
+      ilargi_status_t rc;
+      if (l == k) {
+        g.A = a.D; g.lda = (int)a.cols; g.ca = (int)a.cols; g.a_rows = a.rows;
+        g.B = a.D; g.ldb = (int)a.cols; g.cb = (int)a.cols; g.b_rows = a.rows;
+        g.wptr = a.ident ? nullptr : plan->at<int32_t>(a.o_rowptr);
+        g.n_rows = a.rows;
+        rc = run_gram(g, block);
+      } else {
+        bool via_l = !b.ident && b.rows * 2 <= plan->r_T;
+        bool via_k = !a.ident && a.rows * 2 <= plan->r_T;
+        if (via_l && via_k) { if (a.rows < b.rows) via_l = false; else via_k = false; }
+        if (via_l) {
+          // Zc = I_l^T (I_k D_k):  rows of D_k summed per source row of l, then  Zc^T D_l
+          SegArgs s = seg_args(plan, l);
+          s.Y = a.D; s.ldy = (int)a.cols; s.col0 = 0; s.ncols = (int)a.cols;
+          s.gidx = a.ident ? nullptr : a.idx; s.g_rows = a.ident ? a.rows : -1;
+          s.Z = zc; s.ldz = (int)a.cols; s.zcol0 = 0;
+          HIP_TRY(launch_segsum(s, st));
+          g.A = zc; g.lda = (int)a.cols; g.ca = (int)a.cols; g.a_rows = b.rows;
+          g.B = b.D; g.ldb = (int)b.cols; g.cb = (int)b.cols; g.b_rows = b.rows;
+          g.n_rows = b.rows;
+        } else if (via_k) {
+          SegArgs s = seg_args(plan, k);
+          s.Y = b.D; s.ldy = (int)b.cols; s.col0 = 0; s.ncols = (int)b.cols;
+          s.gidx = b.ident ? nullptr : b.idx; s.g_rows = b.ident ? b.rows : -1;
+          s.Z = zc; s.ldz = (int)b.cols; s.zcol0 = 0;
+          HIP_TRY(launch_segsum(s, st));
+          g.A = a.D; g.lda = (int)a.cols; g.ca = (int)a.cols; g.a_rows = a.rows;
+          g.B = zc; g.ldb = (int)b.cols; g.cb = (int)b.cols; g.b_rows = a.rows;
+          g.n_rows = a.rows;
+        } else {
+          g.A = a.D; g.lda = (int)a.cols; g.ca = (int)a.cols; g.ia = a.ident ? nullptr : a.idx; g.a_rows = a.rows;
+          g.B = b.D; g.ldb = (int)b.cols; g.cb = (int)b.cols; g.ib = b.ident ? nullptr : b.idx; g.b_rows = b.rows;
+          g.n_rows = plan->r_T;
+        }
+        rc = run_gram(g, block);
+      }
+      if (rc != ILARGI_OK) return rc;
+    }
+  }
+  HIP_TRY(launch_gram_assemble(plan->at<GramAsmPair>(plan->lay.o_pairs), plan->npairs,
+                               plan->at<const int32_t*>(plan->lay.o_tcol_table), (int)plan->c_T, out, st));
+  return ILARGI_OK;
+}
+
+}  // extern "C"

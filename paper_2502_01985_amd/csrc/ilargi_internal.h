@@ -1,0 +1,142 @@
+// Internal declarations shared by the translation units of libilargi (not installed).
+#ifndef ILARGI_INTERNAL_H_
+#define ILARGI_INTERNAL_H_
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ilargi.h"
+
+namespace ilargi {
+
+constexpr int kMaxSources = 16;      // sources per plan (kernel argument arrays are this long)
+constexpr int kWave = 64;            // gfx950 wavefront
+constexpr int kBlock = 256;          // threads per workgroup in the streaming kernels
+constexpr int kNarrowCT = 4;         // operand columns one narrow (VALU) pass handles
+constexpr int kColredBlocks = 1024;  // row chunks (= partial results) of the D^T Z reduction
+constexpr int kLongSeg = 2048;       // inverse-index segments longer than this are split ...
+constexpr int kSegChunk = 2048;      // ... into chunks of this many entries
+constexpr int kSortChunk = 2048;     // keys per workgroup in one radix pass
+constexpr int kMaxLdsFloats = 16384; // 64 KiB of LDS for the staged operand
+constexpr int64_t kGramPartialFloats = 4ll << 20;
+
+// Row gathers of per-source products:  out[i,:] += P_s[row_s(i), :]  (assembly step of Sec. 2.2).
+struct GatherArgs {
+  int n;
+  const int32_t* idx[kMaxSources];  // NULL: identity on the first rows[s] target rows
+  const float* P[kMaxSources];
+  int64_t rows[kMaxSources];
+  int ldp;
+};
+
+struct LmmArgs {
+  const float* D;         // fused identity-prefix source (may be NULL)
+  int64_t d_rows;         // target rows [0, d_rows) take row i of D
+  int ck;                 // columns of D
+  const int32_t* colmap;  // device int32[ck]
+  const float* X;         // c_T x ldx
+  int ldx, col0, ncols;   // operand columns [col0, col0 + ncols)
+  float* out;             // r_out x ldo
+  int ldo;
+  int64_t r_out;
+  int logL;               // lanes per row = 1 << logL
+  GatherArgs g;
+  // gradient-descent modes
+  const float* y;         // labels, r_out
+  float* loss_partial;    // [gridDim.x][kNarrowCT]
+};
+
+struct SegArgs {
+  const int32_t* rowptr;   // r_k + 1
+  const int32_t* perm;     // nnz
+  const int32_t* chunk_seg, *chunk_beg, *chunk_end;  // long-segment chunks
+  const int32_t* long_seg, *long_first;              // long segments and their chunk ranges
+  int n_chunks, n_long;
+  int64_t r_k;
+  const float* Y;          // rows addressed through perm (and gidx if given)
+  int ldy, col0, ncols;
+  const int32_t* gidx;     // optional second-level gather: Y row = gidx[perm[p]] (skip if < 0)
+  int64_t g_rows;          // with gidx == NULL and g_rows >= 0: rows >= g_rows are skipped
+  float* Z;                // r_k x ldz
+  int ldz, zcol0;
+  float* chunk_partial;    // n_chunks x ncols
+  int logG;                // lanes per segment in the narrow kernel
+};
+
+struct ColredArgs {
+  const float* D;
+  int64_t rows;
+  int ck;
+  const float* Z;          // rows x ldz
+  int ldz, col0, ncols;
+  float* partial;          // [nblocks][ck][kNarrowCT]
+  int64_t rows_per_block;
+  int vec;
+};
+
+struct FinSource {
+  const int32_t* tcol2src;  // c_T
+  const float* partial;     // [nblocks][ck][kNarrowCT]
+  int nblocks, ck;
+};
+
+struct FinArgs {
+  int n;
+  FinSource s[kMaxSources];
+  float* out;  // c_T x ldo (or W for the update mode)
+  int ldo, col0, ncols;
+  // update mode
+  const float* lr;
+  float inv_rT;
+  const float* loss_partial;
+  int n_loss_partial;
+  float* loss;
+  float loss_scale;
+};
+
+struct MatArgs {
+  int n;
+  const float* D[kMaxSources];
+  const int32_t* idx[kMaxSources];
+  const int32_t* tcol2src[kMaxSources];
+  int64_t rows[kMaxSources];
+  int ck[kMaxSources];
+  float* T;
+  int64_t r_T;
+  int c_T;
+};
+
+struct GramArgs {
+  const float* A; int lda, ca; const int32_t* ia; int64_t a_rows;  // row t of A = A[ia ? ia[t] : t]
+  const float* B; int ldb, cb; const int32_t* ib; int64_t b_rows;
+  const int32_t* wptr;   // optional: weight of row t = wptr[t+1] - wptr[t]
+  int64_t n_rows;        // t in [0, n_rows)
+  int64_t rows_per_chunk;
+  float* partial;        // [nchunks][ca][cb]
+};
+
+struct GramAsmPair { const float* block; int k, l, cb; };
+
+// ---- launchers (each enqueues on `st`; returns the HIP error of the launch) ----
+hipError_t launch_check_idx(const int32_t* idx, int64_t r_T, int64_t r_k, int32_t* flags, hipStream_t st);
+hipError_t launch_sort_by_source_row(const int32_t* idx, int64_t r_T, int64_t r_k, int32_t* keys_a,
+                                     int32_t* vals_a, int32_t* keys_b, int32_t* vals_b, int32_t* hist,
+                                     int32_t* rowptr, int32_t* perm, hipStream_t st);
+size_t sort_hist_ints(int64_t r_T);
+
+hipError_t launch_lmm_rows(const LmmArgs& a, int vec, int mode, hipStream_t st, int* grid_out);
+int lmm_grid(int64_t r_out, int logL);
+hipError_t launch_segsum(const SegArgs& a, hipStream_t st);
+hipError_t launch_colred(const ColredArgs& a, int nblocks, hipStream_t st);
+hipError_t launch_finalize(const FinArgs& a, int c_T, int mode, hipStream_t st);
+hipError_t launch_materialize(const MatArgs& a, hipStream_t st);
+hipError_t launch_gram(const GramArgs& a, int nchunks, hipStream_t st);
+hipError_t launch_gram_reduce(const float* partial, int nchunks, int64_t elems, float* block, hipStream_t st);
+hipError_t launch_gram_assemble(const GramAsmPair* pairs_dev, int npairs, const int32_t* const* tcol2src_dev,
+                                int c_T, float* out, hipStream_t st);
+hipError_t launch_fill_zero(float* p, int64_t n, hipStream_t st);
+
+inline int ilog2_ceil(int64_t v) { int l = 0; while ((1ll << l) < v) ++l; return l; }
+
+}  // namespace ilargi
+#endif

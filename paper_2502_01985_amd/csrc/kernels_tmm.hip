@@ -1,0 +1,293 @@
+// Transposed multiply  T^T Y = sum_k M_k (D_k^T (I_k^T Y))  for narrow operands, in three steps:
+//   segment sum   Z_k = I_k^T Y        over the inverse index (rowptr, perm) -- no floating-point atomics;
+//   column reduce G_k = D_k^T Z_k      per-workgroup partial sums over contiguous row chunks;
+//   finalize      out[col_map_k[j], :] += G_k[j, :]   partials added in a fixed order, sources in order.
+// The finalize step also performs the weight update of Alg. 1 when called from the gradient-descent step.
+#include "ilargi_internal.h"
+
+namespace ilargi {
+
+namespace {
+
+// Row of Y addressed by entry p of the inverse index (or -1 to skip).
+__device__ __forceinline__ int64_t seg_row(const SegArgs& a, int64_t p) {
+  int64_t i = a.perm[p];
+  if (a.gidx != nullptr) return a.gidx[i];
+  if (a.g_rows >= 0 && i >= a.g_rows) return -1;
+  return i;
+}
+
+// Narrow form: G = 2^logG lanes share one segment and stride over its entries; CT columns per lane.
+// Work items [0, r_k) are whole segments (skipped when longer than kLongSeg), items [r_k, r_k + n_chunks)
+// are chunks of long segments whose sums go to chunk_partial.
+template <int CT>
+__global__ __launch_bounds__(kBlock) void segsum_narrow_kernel(SegArgs a) {
+  const int G = 1 << a.logG;
+  const int lig = threadIdx.x & (G - 1);
+  const int64_t n_items = a.r_k + a.n_chunks;
+  const int64_t gpb = kBlock >> a.logG;
+  for (int64_t item = (int64_t)blockIdx.x * gpb + (threadIdx.x >> a.logG); item < n_items + gpb;
+       item += (int64_t)gridDim.x * gpb) {
+    // keep whole wavefronts in the loop so that the butterfly below is convergent
+    bool live = item < n_items;
+    int64_t beg = 0, end = 0;
+    float* dst = nullptr;
+    if (live) {
+      if (item < a.r_k) {
+        beg = a.rowptr[item];
+        end = a.rowptr[item + 1];
+        dst = a.Z + item * a.ldz + a.zcol0;
+        if (end - beg > kLongSeg) { live = false; }
+      } else {
+        int c = (int)(item - a.r_k);
+        beg = a.chunk_beg[c];
+        end = a.chunk_end[c];
+        dst = a.chunk_partial + (int64_t)c * a.ncols;
+      }
+    }
+    float acc[CT];
+#pragma unroll
+    for (int n = 0; n < CT; ++n) acc[n] = 0.0f;
+    if (live) {
+      for (int64_t p = beg + lig; p < end; p += G) {
+        int64_t r = seg_row(a, p);
+        if (r >= 0) {
+          const float* y = a.Y + r * a.ldy + a.col0;
+#pragma unroll
+          for (int n = 0; n < CT; ++n)
+            if (n < a.ncols) acc[n] += y[n];
+        }
+      }
+    }
+    for (int m = G >> 1; m >= 1; m >>= 1) {
+#pragma unroll
+      for (int n = 0; n < CT; ++n) acc[n] += __shfl_xor(acc[n], m);
+    }
+    if (live && lig == 0) {
+#pragma unroll
+      for (int n = 0; n < CT; ++n)
+        if (n < a.ncols) dst[n] = acc[n];
+    }
+    if (item >= n_items) break;
+  }
+}
+
+// Wide form: W lanes of a segment each own columns lane, lane + W, ... and walk the entries in order.
+template <int W>
+__global__ __launch_bounds__(kBlock) void segsum_wide_kernel(SegArgs a) {
+  const int lig = threadIdx.x & (W - 1);
+  const int64_t n_items = a.r_k + a.n_chunks;
+  constexpr int64_t gpb = kBlock / W;
+  for (int64_t item = (int64_t)blockIdx.x * gpb + threadIdx.x / W; item < n_items;
+       item += (int64_t)gridDim.x * gpb) {
+    int64_t beg, end;
+    float* dst;
+    if (item < a.r_k) {
+      beg = a.rowptr[item];
+      end = a.rowptr[item + 1];
+      dst = a.Z + item * a.ldz + a.zcol0;
+      if (end - beg > kLongSeg) continue;
+    } else {
+      int c = (int)(item - a.r_k);
+      beg = a.chunk_beg[c];
+      end = a.chunk_end[c];
+      dst = a.chunk_partial + (int64_t)c * a.ncols;
+    }
+    for (int n0 = lig; n0 < a.ncols; n0 += W) {
+      float acc = 0.0f;
+      int64_t p = beg;
+      for (; p + 4 <= end; p += 4) {
+        int64_t r0 = seg_row(a, p), r1 = seg_row(a, p + 1), r2 = seg_row(a, p + 2), r3 = seg_row(a, p + 3);
+        float v0 = r0 >= 0 ? a.Y[r0 * a.ldy + a.col0 + n0] : 0.0f;
+        float v1 = r1 >= 0 ? a.Y[r1 * a.ldy + a.col0 + n0] : 0.0f;
+        float v2 = r2 >= 0 ? a.Y[r2 * a.ldy + a.col0 + n0] : 0.0f;
+        float v3 = r3 >= 0 ? a.Y[r3 * a.ldy + a.col0 + n0] : 0.0f;
+        acc += v0; acc += v1; acc += v2; acc += v3;
+      }
+      for (; p < end; ++p) {
+        int64_t r = seg_row(a, p);
+        if (r >= 0) acc += a.Y[r * a.ldy + a.col0 + n0];
+      }
+      dst[n0] = acc;
+    }
+  }
+}
+
+// Long segments: add the chunk sums in chunk order.
+__global__ __launch_bounds__(kBlock) void segsum_combine_kernel(SegArgs a) {
+  int64_t total = (int64_t)a.n_long * a.ncols;
+  for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total;
+       e += (int64_t)gridDim.x * blockDim.x) {
+    int s = (int)(e / a.ncols), n = (int)(e % a.ncols);
+    float acc = 0.0f;
+    for (int c = a.long_first[s]; c < a.long_first[s + 1]; ++c) acc += a.chunk_partial[(int64_t)c * a.ncols + n];
+    a.Z[(int64_t)a.long_seg[s] * a.ldz + a.zcol0 + n] = acc;
+  }
+}
+
+template <int VEC> __device__ __forceinline__ void load_vec(const float* p, float (&v)[VEC]) {
+  if constexpr (VEC == 4) {
+    float4 t = *reinterpret_cast<const float4*>(p);
+    v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+  } else if constexpr (VEC == 2) {
+    float2 t = *reinterpret_cast<const float2*>(p);
+    v[0] = t.x; v[1] = t.y;
+  } else {
+    v[0] = *p;
+  }
+}
+
+constexpr int kUnroll = 4;
+
+// Partial of D^T Z over the rows of one workgroup.  blockIdx.y selects a slab of 64*VEC columns of D;
+// inside a slab lane -> (row offset, column group), so a wavefront reads whole contiguous rows.
+template <int VEC, int CT>
+__global__ __launch_bounds__(kBlock) void colred_kernel(ColredArgs a) {
+  __shared__ float red[VEC * CT][kBlock];
+  const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+  const int slab0 = blockIdx.y * kWave * VEC;                       // first column of the slab
+  const int wck = min(a.ck - slab0, kWave * VEC);                   // its width
+  const int nvec = wck / VEC;                                       // column groups (<= 64)
+  const int rp = kWave / nvec;                                      // rows per wavefront step
+  const int rsub = lane / nvec, cg = lane - rsub * nvec;
+  const bool active = rsub < rp;
+  const int64_t b0 = (int64_t)blockIdx.x * a.rows_per_block;
+  const int64_t b1 = min(b0 + a.rows_per_block, a.rows);
+  const int64_t step = (int64_t)rp * kUnroll;                       // rows per wavefront iteration
+
+  float g[VEC][CT];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e)
+#pragma unroll
+    for (int n = 0; n < CT; ++n) g[e][n] = 0.0f;
+
+  if (active) {
+    for (int64_t r0 = b0 + (int64_t)wave * step; r0 < b1; r0 += (int64_t)(kBlock / kWave) * step) {
+      float v[kUnroll][VEC], z[kUnroll][CT];
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) {
+        int64_t r = r0 + (int64_t)u * rp + rsub;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) v[u][e] = 0.0f;
+#pragma unroll
+        for (int n = 0; n < CT; ++n) z[u][n] = 0.0f;
+        if (r < b1) {
+          load_vec<VEC>(a.D + r * a.ck + slab0 + cg * VEC, v[u]);
+          const float* zp = a.Z + r * a.ldz + a.col0;
+#pragma unroll
+          for (int n = 0; n < CT; ++n)
+            if (n < a.ncols) z[u][n] = zp[n];
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u)
+#pragma unroll
+        for (int e = 0; e < VEC; ++e)
+#pragma unroll
+          for (int n = 0; n < CT; ++n) g[e][n] = fmaf(v[u][e], z[u][n], g[e][n]);
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < VEC; ++e)
+#pragma unroll
+    for (int n = 0; n < CT; ++n) red[e * CT + n][tid] = g[e][n];
+  __syncthreads();
+  // column j of the slab, operand column n: add the wavefronts and row offsets in a fixed order
+  for (int o = tid; o < wck * CT; o += kBlock) {
+    int j = o / CT, n = o - j * CT;
+    int jcg = j / VEC, e = j - jcg * VEC;
+    float s = 0.0f;
+    for (int w = 0; w < kBlock / kWave; ++w)
+      for (int q = 0; q < rp; ++q) s += red[e * CT + n][w * kWave + q * nvec + jcg];
+    a.partial[((int64_t)blockIdx.x * a.ck + slab0 + j) * kNarrowCT + n] = s;
+  }
+}
+
+// One workgroup per target column: sum each contributing source's partials (lanes stride over the row
+// chunks, xor butterfly), add the sources in order.  MODE 0 stores, MODE 1 applies  W -= lr * G / r_T  and
+// reduces the loss partials (Alg. 1).
+template <int MODE>
+__global__ __launch_bounds__(kBlock) void finalize_kernel(FinArgs a) {
+  const int t = blockIdx.x;
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  for (int n = wave; n < a.ncols; n += kBlock / kWave) {
+    float acc = 0.0f;
+    for (int k = 0; k < a.n; ++k) {
+      int j = a.s[k].tcol2src[t];
+      if (j < 0) continue;
+      float s = 0.0f;
+      for (int b = lane; b < a.s[k].nblocks; b += kWave)
+        s += a.s[k].partial[((int64_t)b * a.s[k].ck + j) * kNarrowCT + n];
+      for (int m = kWave / 2; m >= 1; m >>= 1) s += __shfl_xor(s, m);
+      acc += s;
+    }
+    if (lane == 0) {
+      float* o = a.out + (int64_t)t * a.ldo + a.col0 + n;
+      if constexpr (MODE == 0) *o = acc;
+      else *o = *o - a.lr[a.col0 + n] * (acc * a.inv_rT);
+    }
+    if constexpr (MODE == 1) {
+      if (t == 0 && a.loss != nullptr) {
+        float s = 0.0f;
+        for (int b = lane; b < a.n_loss_partial; b += kWave) s += a.loss_partial[(int64_t)b * kNarrowCT + n];
+        for (int m = kWave / 2; m >= 1; m >>= 1) s += __shfl_xor(s, m);
+        if (lane == 0) a.loss[a.col0 + n] = s * a.loss_scale;
+      }
+    }
+  }
+}
+
+}  // namespace
+
+hipError_t launch_segsum(const SegArgs& a, hipStream_t st) {
+  int64_t n_items = a.r_k + a.n_chunks;
+  if (n_items <= 0 || a.ncols <= 0) return hipSuccess;
+  if (a.ncols <= kNarrowCT) {
+    int64_t gpb = kBlock >> a.logG;
+    int64_t grid = (n_items + gpb - 1) / gpb;
+    if (grid > 65536) grid = 65536;
+    if (a.ncols == 1) segsum_narrow_kernel<1><<<(int)grid, kBlock, 0, st>>>(a);
+    else if (a.ncols == 2) segsum_narrow_kernel<2><<<(int)grid, kBlock, 0, st>>>(a);
+    else segsum_narrow_kernel<4><<<(int)grid, kBlock, 0, st>>>(a);
+  } else {
+    int W = a.ncols <= 16 ? 16 : (a.ncols <= 32 ? 32 : 64);
+    int64_t gpb = kBlock / W;
+    int64_t grid = (n_items + gpb - 1) / gpb;
+    if (grid > 65536) grid = 65536;
+    if (W == 16) segsum_wide_kernel<16><<<(int)grid, kBlock, 0, st>>>(a);
+    else if (W == 32) segsum_wide_kernel<32><<<(int)grid, kBlock, 0, st>>>(a);
+    else segsum_wide_kernel<64><<<(int)grid, kBlock, 0, st>>>(a);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  if (a.n_long > 0) {
+    int64_t total = (int64_t)a.n_long * a.ncols;
+    int grid = (int)((total + kBlock - 1) / kBlock);
+    if (grid > 1024) grid = 1024;
+    segsum_combine_kernel<<<grid, kBlock, 0, st>>>(a);
+    e = hipGetLastError();
+  }
+  return e;
+}
+
+hipError_t launch_colred(const ColredArgs& a, int nblocks, hipStream_t st) {
+  if (a.ck <= 0 || nblocks <= 0) return hipSuccess;
+  int slabw = kWave * a.vec;
+  dim3 grid(nblocks, (a.ck + slabw - 1) / slabw);
+  int ct = a.ncols <= 1 ? 1 : (a.ncols <= 2 ? 2 : 4);
+#define ILARGI_COLRED(V, C) colred_kernel<V, C><<<grid, kBlock, 0, st>>>(a)
+  if (a.vec == 4) { if (ct == 1) ILARGI_COLRED(4, 1); else if (ct == 2) ILARGI_COLRED(4, 2); else ILARGI_COLRED(4, 4); }
+  else if (a.vec == 2) { if (ct == 1) ILARGI_COLRED(2, 1); else if (ct == 2) ILARGI_COLRED(2, 2); else ILARGI_COLRED(2, 4); }
+  else { if (ct == 1) ILARGI_COLRED(1, 1); else if (ct == 2) ILARGI_COLRED(1, 2); else ILARGI_COLRED(1, 4); }
+#undef ILARGI_COLRED
+  return hipGetLastError();
+}
+
+hipError_t launch_finalize(const FinArgs& a, int c_T, int mode, hipStream_t st) {
+  if (c_T <= 0 || a.ncols <= 0) return hipSuccess;
+  if (mode == 0) finalize_kernel<0><<<c_T, kBlock, 0, st>>>(a);
+  else finalize_kernel<1><<<c_T, kBlock, 0, st>>>(a);
+  return hipGetLastError();
+}
+
+}  // namespace ilargi

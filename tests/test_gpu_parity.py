@@ -1,0 +1,359 @@
+"""Device library against the CPU oracle, element by element, on the same seeded inputs.
+
+Sizes here are the ones the oracle finishes in seconds; they span many workgroup tiles, ragged
+tails, long and empty inverse-index segments.  Tolerances are the ones the task fixes: bit-exact
+for integer work and the join-gather, 1e-5 relative Frobenius error for float32 operators, 1e-4
+relative 2-norm for gradient-descent weights.
+"""
+import ctypes
+
+import numpy as np
+import pytest
+
+import datagen
+import oracle
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+OP_TOL = 1e-5
+GD_TOL = 1e-4
+
+
+@pytest.fixture(scope="module")
+def il():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2502_01985_amd as mod
+    return mod
+
+
+def rel(a, b):
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    nb = np.linalg.norm(b)
+    return float(np.linalg.norm(a - b) / (nb if nb > 0 else 1.0))
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+SCHEMAS = {
+    "config0": lambda: datagen.config0(),
+    "config1_small": lambda: datagen.config1(r_S=30_011, r_R=3_001, c_R=200),
+    "config1_fr1": lambda: datagen.config1(r_S=20_000, r_R=10_000, c_R=20),
+    "config1_wide_dim": lambda: datagen.config1(r_S=20_003, r_R=257, c_R=800),
+    "config2_small": lambda: datagen.config2(r_S=200_003, dim_rows=(4_000, 2_000, 400)),
+    "config3_small": lambda: datagen.config3(rows=50_001, cols=64, shared=32),
+    "tiny3": lambda: datagen.tiny_random_schema(3, r_T=9, c_T=7, n=3),
+    "tiny_mixed": lambda: datagen.tiny_random_schema(21, r_T=333, c_T=19, n=5),
+    "odd_cols": lambda: datagen.star_schema(datagen.rng_for(77), 5_001, 7, [(97, 13, "uniform"), (31, 2, "uniform")]),
+}
+
+_cache = {}
+
+
+def get(il, name, max_cx=17):
+    key = (name, max_cx)
+    if key not in _cache:
+        sch = SCHEMAS[name]()
+        tg = oracle.Target(sch)
+        plan = il.ilargi_plan_create(il.schema_to_device(sch), sch.r_T, sch.c_T, max_cx=max_cx)
+        _cache[key] = (sch, tg, plan)
+    return _cache[key]
+
+
+ALL = list(SCHEMAS)
+
+
+# ------------------------------------------------------------------ plan: inverse index (integer, exact)
+@pytest.mark.parametrize("name", ["config0", "config2_small", "config3_small", "tiny_mixed"])
+def test_inverse_index_exact(il, name):
+    sch, tg, plan = get(il, name)
+    for k, s in enumerate(sch.sources):
+        rowptr, perm = il.ilargi_plan_inverse_index(plan, k)
+        if s.row_idx is None:
+            assert rowptr is None
+            continue
+        ident = np.array_equal(s.row_idx[:s.rows], np.arange(s.rows)) and np.all(s.row_idx[s.rows:] == -1)
+        if ident:
+            assert rowptr is None
+            continue
+        valid = np.flatnonzero(s.row_idx >= 0)
+        want_perm = valid[np.argsort(s.row_idx[valid], kind="stable")].astype(np.int32)
+        want_ptr = np.zeros(s.rows + 1, dtype=np.int32)
+        want_ptr[1:] = np.cumsum(np.bincount(s.row_idx[valid], minlength=s.rows))
+        assert np.array_equal(rowptr, want_ptr)
+        assert np.array_equal(perm, want_perm)
+
+
+def test_inverse_index_matches_oracle_definition(il):
+    sch, tg, plan = get(il, "tiny_mixed")
+    for k, s in enumerate(sch.sources):
+        rowptr, perm = il.ilargi_plan_inverse_index(plan, k)
+        if rowptr is None:
+            continue
+        o_ptr, o_perm, _ = oracle.inverse_index(s.row_idx, s.rows)
+        assert np.array_equal(rowptr, o_ptr) and np.array_equal(perm, o_perm)
+
+
+def test_inverse_index_skewed_and_empty_segments(il):
+    rng = datagen.rng_for(5)
+    r_T, r_k = 100_000, 5_000
+    idx = datagen.bounded_zipf_keys(rng, r_T, r_k, 1.3)
+    idx[rng.random(r_T) < 0.1] = -1
+    D = rng.standard_normal((r_k, 4)).astype(np.float32)
+    sch = datagen.Schema([datagen.Source(D, idx, np.arange(4, dtype=np.int32))], r_T, 4)
+    plan = il.ilargi_plan_create(il.schema_to_device(sch), r_T, 4, max_cx=3)
+    rowptr, perm = il.ilargi_plan_inverse_index(plan, 0)
+    valid = np.flatnonzero(idx >= 0)
+    cnt = np.bincount(idx[valid], minlength=r_k)
+    assert cnt.max() > 2048 * 3 and (cnt == 0).sum() > 0      # long segments and empty ones both occur
+    assert np.array_equal(np.diff(rowptr), cnt)
+    assert np.array_equal(perm, valid[np.argsort(idx[valid], kind="stable")])
+    Y = rng.standard_normal((r_T, 3)).astype(np.float32)
+    Z = il.ilargi_segment_sum(plan, 0, dev(Y)).cpu().numpy()
+    assert rel(Z, oracle.segment_sum(idx, r_k, Y)) < OP_TOL
+    assert np.all(Z[cnt == 0] == 0.0)
+
+
+# ------------------------------------------------------------------ materialize (bit-exact)
+@pytest.mark.parametrize("name", ALL)
+def test_materialize_bit_exact(il, name):
+    sch, tg, plan = get(il, name)
+    T = il.ilargi_materialize(plan).cpu().numpy()
+    assert T.shape == tg.T32.shape
+    assert np.array_equal(T.view(np.uint32), tg.T32.view(np.uint32))
+
+
+# ------------------------------------------------------------------ LMM
+@pytest.mark.parametrize("name", ALL)
+@pytest.mark.parametrize("cx", [1, 2, 3, 4, 5, 16, 17])
+def test_lmm(il, name, cx):
+    sch, tg, plan = get(il, name)
+    X = datagen.rng_for(1000 + cx).standard_normal((sch.c_T, cx)).astype(np.float32)
+    got = il.ilargi_lmm(plan, dev(X)).cpu().numpy()
+    assert rel(got, oracle.lmm(tg, X)) < OP_TOL
+
+
+@pytest.mark.parametrize("name", ["config0", "tiny_mixed", "odd_cols"])
+def test_lmm_identity_operand_reproduces_table(il, name):
+    sch, tg, plan = get(il, name, max_cx=32)
+    if sch.c_T > 32:
+        pytest.skip("operand wider than the plan")
+    got = il.ilargi_lmm(plan, dev(np.eye(sch.c_T, dtype=np.float32))).cpu().numpy()
+    # every output is 1.0 * cell plus zeros: exact unless two sources share the cell
+    np.testing.assert_allclose(got, tg.T32, rtol=1e-6, atol=1e-6)
+    if name != "tiny_mixed":
+        assert np.array_equal(got, tg.T32)
+
+
+# ------------------------------------------------------------------ TMM
+@pytest.mark.parametrize("name", ALL)
+@pytest.mark.parametrize("cx", [1, 2, 3, 4, 5, 16, 17])
+def test_tmm(il, name, cx):
+    sch, tg, plan = get(il, name)
+    Y = datagen.rng_for(2000 + cx).standard_normal((sch.r_T, cx)).astype(np.float32)
+    got = il.ilargi_tmm(plan, dev(Y)).cpu().numpy()
+    assert rel(got, oracle.tmm(tg, Y)) < OP_TOL
+
+
+@pytest.mark.parametrize("name", ["config2_small", "config3_small"])
+def test_adjoint_identity_on_device(il, name):
+    sch, tg, plan = get(il, name)
+    rng = datagen.rng_for(31)
+    X = rng.standard_normal((sch.c_T, 4)).astype(np.float32)
+    Y = rng.standard_normal((sch.r_T, 4)).astype(np.float32)
+    TX = il.ilargi_lmm(plan, dev(X)).cpu().numpy().astype(np.float64)
+    TtY = il.ilargi_tmm(plan, dev(Y)).cpu().numpy().astype(np.float64)
+    lhs, rhs = np.sum(TX * Y), np.sum(X * TtY)
+    assert abs(lhs - rhs) < 1e-5 * np.sqrt(np.sum(TX ** 2) * np.sum(Y.astype(np.float64) ** 2))
+
+
+@pytest.mark.parametrize("name", ["config2_small", "config3_small", "tiny_mixed"])
+@pytest.mark.parametrize("cx", [1, 4, 16])
+def test_segment_sum(il, name, cx):
+    sch, tg, plan = get(il, name)
+    Y = datagen.rng_for(3000 + cx).standard_normal((sch.r_T, cx)).astype(np.float32)
+    for k, s in enumerate(sch.sources):
+        if s.row_idx is None:
+            continue
+        Z = il.ilargi_segment_sum(plan, k, dev(Y)).cpu().numpy()
+        want = np.zeros((s.rows, cx))
+        ok = s.row_idx >= 0
+        np.add.at(want, s.row_idx[ok], Y[ok].astype(np.float64))
+        assert rel(Z, want) < OP_TOL
+
+
+# ------------------------------------------------------------------ crossprod
+@pytest.mark.parametrize("name", ALL)
+def test_crossprod(il, name):
+    sch, tg, plan = get(il, name)
+    G = il.ilargi_crossprod(plan).cpu().numpy()
+    assert rel(G, oracle.crossprod(tg)) < OP_TOL
+    assert np.array_equal(G, G.T)
+
+
+# ------------------------------------------------------------------ gradient descent (Alg. 1)
+def _labels(sch, tg, kind):
+    return datagen.finish_labels(kind, oracle.lmm(tg, sch.extras["w_star"].reshape(-1, 1)), sch.extras["noise"])
+
+
+def _run_gd(il, plan, model, y, lrs, iters, c_T):
+    m = len(lrs)
+    W = torch.zeros((c_T, m), device="cuda")
+    lr = dev(np.asarray(lrs, dtype=np.float32))
+    loss = torch.zeros(m, device="cuda")
+    yd = dev(y)
+    losses = []
+    for _ in range(iters):
+        il.ilargi_gd_step(plan, model, W, yd, lr, loss)
+        losses.append(loss.cpu().numpy().copy())
+    return W.cpu().numpy(), np.array(losses)
+
+
+def test_gd_linear_config0(il):
+    sch, tg, plan = get(il, "config0")
+    y = _labels(sch, tg, "linear")
+    W, L = _run_gd(il, plan, il.LINEAR, y, [0.1], 20, sch.c_T)
+    W_ref, L_ref = oracle.gd(tg, "linear", y, np.zeros((sch.c_T, 1)), [0.1], 20)
+    assert rel(W, W_ref) < GD_TOL
+    np.testing.assert_allclose(L, L_ref, rtol=1e-4)
+
+
+def test_gd_logistic_config2(il):
+    sch, tg, plan = get(il, "config2_small")
+    y = _labels(sch, tg, "logistic")
+    W, L = _run_gd(il, plan, il.LOGISTIC, y, [0.5], 50, sch.c_T)
+    W_ref, L_ref = oracle.gd(tg, "logistic", y, np.zeros((sch.c_T, 1)), [0.5], 50)
+    assert rel(W, W_ref) < GD_TOL
+    np.testing.assert_allclose(L, L_ref, rtol=1e-4)
+    assert abs(L[0, 0] - np.log(2.0)) < 1e-6
+
+
+def test_gd_linear_config3(il):
+    sch, tg, plan = get(il, "config3_small")
+    y = _labels(sch, tg, "linear")
+    W, L = _run_gd(il, plan, il.LINEAR, y, [0.1], 10, sch.c_T)
+    W_ref, L_ref = oracle.gd(tg, "linear", y, np.zeros((sch.c_T, 1)), [0.1], 10)
+    assert rel(W, W_ref) < GD_TOL
+    np.testing.assert_allclose(L, L_ref, rtol=1e-4)
+
+
+@pytest.mark.parametrize("m", [3, 8, 17])
+def test_gd_many_models_one_learning_rate_each(il, m):
+    sch, tg, plan = get(il, "config1_small")
+    rng = datagen.rng_for(4)
+    w_star = rng.standard_normal(sch.c_T)
+    y = datagen.finish_labels("linear", oracle.lmm(tg, w_star.reshape(-1, 1)), 0.01 * rng.standard_normal(sch.r_T))
+    lrs = np.logspace(-3, 0, m)
+    W, L = _run_gd(il, plan, il.LINEAR, y, lrs, 20, sch.c_T)
+    W_ref, L_ref = oracle.gd(tg, "linear", y, np.zeros((sch.c_T, m)), lrs, 20)
+    errs = [rel(W[:, j], W_ref[:, j]) for j in range(m)]
+    assert max(errs) < GD_TOL, errs
+    np.testing.assert_allclose(L, L_ref, rtol=2e-4)
+
+
+def test_gd_without_loss_output(il):
+    sch, tg, plan = get(il, "config0")
+    y = _labels(sch, tg, "linear")
+    W = torch.zeros((sch.c_T, 1), device="cuda")
+    il.ilargi_gd_step(plan, il.LINEAR, W, dev(y), dev(np.array([0.1], dtype=np.float32)), None)
+    W_ref, _ = oracle.gd(tg, "linear", y, np.zeros((sch.c_T, 1)), [0.1], 1)
+    assert rel(W.cpu().numpy(), W_ref) < GD_TOL
+
+
+# ------------------------------------------------------------------ determinism and edge cases
+def test_results_are_bitwise_reproducible(il):
+    sch, tg, plan = get(il, "config2_small")
+    rng = datagen.rng_for(8)
+    Y = dev(rng.standard_normal((sch.r_T, 4)).astype(np.float32))
+    X = dev(rng.standard_normal((sch.c_T, 4)).astype(np.float32))
+    a1, b1, c1 = il.ilargi_tmm(plan, Y).cpu(), il.ilargi_lmm(plan, X).cpu(), il.ilargi_crossprod(plan).cpu()
+    a2, b2, c2 = il.ilargi_tmm(plan, Y).cpu(), il.ilargi_lmm(plan, X).cpu(), il.ilargi_crossprod(plan).cpu()
+    assert torch.equal(a1, a2) and torch.equal(b1, b2) and torch.equal(c1, c2)
+
+
+def test_rows_without_any_source_and_unmapped_columns(il):
+    rng = datagen.rng_for(13)
+    r_T, c_T = 1_000, 9
+    D = rng.standard_normal((50, 3)).astype(np.float32)
+    idx = np.full(r_T, -1, dtype=np.int32)
+    idx[100:200] = rng.integers(0, 50, 100)
+    sch = datagen.Schema([datagen.Source(D, idx, np.array([7, -1, 2], dtype=np.int32))], r_T, c_T)
+    tg = oracle.Target(sch)
+    plan = il.ilargi_plan_create(il.schema_to_device(sch), r_T, c_T, max_cx=2)
+    T = il.ilargi_materialize(plan).cpu().numpy()
+    assert np.array_equal(T, tg.T32) and np.all(T[:100] == 0) and np.all(T[:, [0, 1, 3, 4, 5, 6, 8]] == 0)
+    X = rng.standard_normal((c_T, 2)).astype(np.float32)
+    Y = rng.standard_normal((r_T, 2)).astype(np.float32)
+    assert rel(il.ilargi_lmm(plan, dev(X)).cpu().numpy(), oracle.lmm(tg, X)) < OP_TOL
+    got = il.ilargi_tmm(plan, dev(Y)).cpu().numpy()
+    assert rel(got, oracle.tmm(tg, Y)) < OP_TOL and np.all(got[[0, 1, 3, 4, 5, 6, 8]] == 0)
+    assert rel(il.ilargi_crossprod(plan).cpu().numpy(), oracle.crossprod(tg)) < OP_TOL
+
+
+def test_all_rows_unmatched_and_empty_sources(il):
+    rng = datagen.rng_for(14)
+    r_T, c_T = 300, 5
+    S = rng.standard_normal((r_T, 2)).astype(np.float32)
+    R = rng.standard_normal((10, 3)).astype(np.float32)
+    none = np.full(r_T, -1, dtype=np.int32)
+    empty_rows = np.zeros((0, 3), dtype=np.float32)
+    sch = datagen.Schema([
+        datagen.Source(S, None, np.array([0, 1], dtype=np.int32)),
+        datagen.Source(R, none, np.array([2, 3, 4], dtype=np.int32)),
+        datagen.Source(empty_rows, none.copy(), np.array([2, 3, 4], dtype=np.int32)),
+    ], r_T, c_T)
+    tg = oracle.Target(sch)
+    plan = il.ilargi_plan_create(il.schema_to_device(sch), r_T, c_T, max_cx=1)
+    assert np.array_equal(il.ilargi_materialize(plan).cpu().numpy(), tg.T32)
+    X = rng.standard_normal((c_T, 1)).astype(np.float32)
+    Y = rng.standard_normal((r_T, 1)).astype(np.float32)
+    assert rel(il.ilargi_lmm(plan, dev(X)).cpu().numpy(), oracle.lmm(tg, X)) < OP_TOL
+    assert rel(il.ilargi_tmm(plan, dev(Y)).cpu().numpy(), oracle.tmm(tg, Y)) < OP_TOL
+    assert rel(il.ilargi_crossprod(plan).cpu().numpy(), oracle.crossprod(tg)) < OP_TOL
+
+
+def test_index_out_of_range_is_reported(il):
+    D = torch.zeros((10, 2), device="cuda")
+    for bad in (10, -2):
+        idx = np.zeros(100, dtype=np.int32)
+        idx[57] = bad
+        with pytest.raises(il.IlargiError) as ei:
+            il.ilargi_plan_create([(D, dev(idx), np.array([0, 1], dtype=np.int32))], 100, 2, max_cx=1)
+        assert ei.value.status == il.ERR_INDEX_RANGE
+
+
+def test_operand_wider_than_plan_is_rejected(il):
+    sch, tg, plan = get(il, "config0")
+    X = torch.zeros((sch.c_T, 18), device="cuda")
+    with pytest.raises(il.IlargiError) as ei:
+        il.ilargi_lmm(plan, X)
+    assert ei.value.status == il.ERR_WORKSPACE
+
+
+def test_unaligned_table_pointer_falls_back_to_scalar_loads(il):
+    # a table whose first element is only 4-byte aligned (a view one float into a buffer)
+    rng = datagen.rng_for(15)
+    r_T, r_k, c = 4_000, 300, 8
+    S = rng.standard_normal((r_T, c)).astype(np.float32)
+    R = rng.standard_normal((r_k, c)).astype(np.float32)
+    fk = rng.integers(0, r_k, r_T).astype(np.int32)
+    sch = datagen.Schema([datagen.Source(S, None, np.arange(c, dtype=np.int32)),
+                          datagen.Source(R, fk, np.arange(c, 2 * c, dtype=np.int32))], r_T, 2 * c)
+    tg = oracle.Target(sch)
+    bufS = torch.empty(r_T * c + 1, device="cuda")
+    bufR = torch.empty(r_k * c + 1, device="cuda")
+    Sd = bufS[1:].view(r_T, c); Sd.copy_(dev(S))
+    Rd = bufR[1:].view(r_k, c); Rd.copy_(dev(R))
+    assert Sd.data_ptr() % 16 == 4
+    plan = il.ilargi_plan_create([(Sd, None, sch.sources[0].col_map), (Rd, dev(fk), sch.sources[1].col_map)],
+                                 r_T, 2 * c, max_cx=2)
+    X = rng.standard_normal((2 * c, 2)).astype(np.float32)
+    Y = rng.standard_normal((r_T, 2)).astype(np.float32)
+    assert rel(il.ilargi_lmm(plan, dev(X)).cpu().numpy(), oracle.lmm(tg, X)) < OP_TOL
+    assert rel(il.ilargi_tmm(plan, dev(Y)).cpu().numpy(), oracle.tmm(tg, Y)) < OP_TOL
+    assert np.array_equal(il.ilargi_materialize(plan).cpu().numpy(), tg.T32)
