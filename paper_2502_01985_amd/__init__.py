@@ -23,6 +23,10 @@ if not os.path.exists(LIB_PATH):
         f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()' "
         "or python paper_2502_01985_amd/build.py). There is no fallback path.")
 
+# PyTorch ships its own copy of the HIP runtime.  It has to be in the process before libilargi.so is
+# loaded so that the library binds to that same runtime (same soname) and shares torch's device context.
+import torch  # noqa: E402,F401
+
 lib = ctypes.CDLL(LIB_PATH)
 
 OK, ERR_NULL, ERR_SHAPE, ERR_COLMAP, ERR_INDEX_RANGE, ERR_WORKSPACE, ERR_UNSUPPORTED, ERR_DEVICE = range(8)
