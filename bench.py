@@ -1,0 +1,331 @@
+#!/usr/bin/env python3
+"""Benchmark of the factorized hot path on one MI355X.
+
+One *step* is one pass of the whole hot path over the operator micro-benchmark schema
+(star join, S 1,000,000 x 20, R 100,000 x 200, uniform keys, float32, seed 1):
+
+    T X (cx = 1 and 16), T^T Y (cx = 1 and 16), one gradient-descent iteration of linear
+    regression (Alg. 1, m = 1), T^T T, and the join-gather materialization,
+
+all through the C ABI, with every input already resident in HBM.  The plan (inverse index) is
+built once, outside the timed region.  `value` is the step's algorithmic bytes (the byte model
+of the design doc) divided by the step's wall time.  The JSON line also carries the per-operator
+breakdown, gradient-descent iterations/s factorized vs materialized, the roofline entry of the
+dominant kernel (timed with HIP events inside the timed region) and the CPU oracle timed on a
+bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+# ----------------------------------------------------------------------------- byte model
+def shapes_of(schema):
+    return [(s.rows, s.cols, s.row_idx is not None) for s in schema.sources]
+
+
+def bytes_tables(shapes):
+    return 4 * sum(r * c for r, c, _ in shapes)
+
+
+def bytes_lmm(shapes, r_T, c_T, c):
+    ni = [(r, k) for r, k, has in shapes if has]
+    return bytes_tables(shapes) + 4 * r_T * len(ni) + 8 * c * sum(r for r, _ in ni) + 4 * r_T * c + 4 * c_T * c
+
+
+def bytes_tmm(shapes, r_T, c_T, c):
+    ni = [(r, k) for r, k, has in shapes if has]
+    return (bytes_tables(shapes) + 4 * r_T * c + sum(4 * r_T + 4 * (r + 1) + 8 * c * r for r, _ in ni)
+            + 4 * c_T * c)
+
+
+def bytes_gd(shapes, r_T, c_T):
+    ident = sum(r * c for r, c, has in shapes if not has)
+    ni = [(r, c) for r, c, has in shapes if has]
+    return (4 * ident + 8 * sum(r * c for r, c in ni) + 4 * r_T * (2 * len(ni) + 3)
+            + 16 * sum(r for r, _ in ni) + 8 * c_T)
+
+
+def bytes_materialize(shapes, r_T, c_T):
+    ni = sum(1 for _, _, has in shapes if has)
+    return bytes_tables(shapes) + 4 * r_T * ni + 4 * r_T * c_T
+
+
+def bytes_crossprod(shapes, r_T, c_T):
+    ni = [(r, c) for r, c, has in shapes if has]
+    return bytes_tables(shapes) + sum(4 * r_T + 4 * (r + 1) for r, _ in ni) + 4 * c_T * c_T
+
+
+def complexity_ratio_lr(shapes, r_T, c_T):
+    """Eq. (1) for linear regression with dense operands (Sec. 3.1): O_materialized / O_factorized."""
+    m_T = r_T * c_T
+    o_mat = 1 * m_T + r_T * c_T + m_T + c_T * r_T
+    o_fact = sum(1 * r * c + r * c_T for r, c, _ in shapes) + sum(r * c + c * r_T for r, c, _ in shapes)
+    return o_mat / o_fact
+
+
+# ----------------------------------------------------------------------------- helpers
+def time_loop(torch, fn, reps, warm=2):
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / reps
+
+
+def make_ops(il, torch, plan, sch, dev):
+    """Device operands and the list of (name, callable, algorithmic bytes) of one step."""
+    r_T, c_T = sch.r_T, sch.c_T
+    shp = shapes_of(sch)
+    X1, X16 = dev(sch.extras["X1"]), dev(sch.extras["X16"])
+    Y1, Y16 = dev(sch.extras["Y1"]), dev(sch.extras["Y16"])
+    out_l1 = torch.empty((r_T, 1), device="cuda"); out_l16 = torch.empty((r_T, 16), device="cuda")
+    out_t1 = torch.empty((c_T, 1), device="cuda"); out_t16 = torch.empty((c_T, 16), device="cuda")
+    G = torch.empty((c_T, c_T), device="cuda")
+    Tm = torch.empty((r_T, c_T), device="cuda")
+    W = torch.zeros((c_T, 1), device="cuda")
+    lr = torch.full((1,), 0.1, device="cuda")
+    loss = torch.zeros(1, device="cuda")
+    # labels for the regression: y = T w* + noise, the product taken on the device
+    rng = np.random.Generator(np.random.PCG64(101))
+    w_star = dev(rng.standard_normal((c_T, 1)).astype(np.float32))
+    y = il.ilargi_lmm(plan, w_star).reshape(-1) + 0.01 * torch.randn(r_T, device="cuda")
+    y = y.contiguous()
+    ops = [
+        ("lmm_c1", lambda: il.ilargi_lmm(plan, X1, out_l1), bytes_lmm(shp, r_T, c_T, 1)),
+        ("tmm_c1", lambda: il.ilargi_tmm(plan, Y1, out_t1), bytes_tmm(shp, r_T, c_T, 1)),
+        ("lmm_c16", lambda: il.ilargi_lmm(plan, X16, out_l16), bytes_lmm(shp, r_T, c_T, 16)),
+        ("tmm_c16", lambda: il.ilargi_tmm(plan, Y16, out_t16), bytes_tmm(shp, r_T, c_T, 16)),
+        ("gd_step", lambda: il.ilargi_gd_step(plan, il.LINEAR, W, y, lr, loss), bytes_gd(shp, r_T, c_T)),
+        ("crossprod", lambda: il.ilargi_crossprod(plan, G), bytes_crossprod(shp, r_T, c_T)),
+        ("materialize", lambda: il.ilargi_materialize(plan, Tm), bytes_materialize(shp, r_T, c_T)),
+    ]
+    keep = dict(X1=X1, X16=X16, Y1=Y1, Y16=Y16, W=W, y=y, lr=lr, loss=loss, Tm=Tm,
+                outs=(out_l1, out_l16, out_t1, out_t16, G))
+    return ops, keep
+
+
+def cpu_baseline(sch, sample_rows, budget_s=20.0):
+    """The oracle, as it stands, on the first `sample_rows` target rows of the same workload."""
+    import datagen
+    import oracle
+    srcs = []
+    for s in sch.sources:
+        if s.row_idx is None:
+            srcs.append(datagen.Source(s.D[:sample_rows], None, s.col_map))
+        else:
+            srcs.append(datagen.Source(s.D, s.row_idx[:sample_rows], s.col_map))
+    sub = datagen.Schema(srcs, sample_rows, sch.c_T)
+    shp = shapes_of(sub)
+    nbytes = (bytes_lmm(shp, sub.r_T, sub.c_T, 1) + bytes_tmm(shp, sub.r_T, sub.c_T, 1)
+              + bytes_lmm(shp, sub.r_T, sub.c_T, 16) + bytes_tmm(shp, sub.r_T, sub.c_T, 16)
+              + bytes_gd(shp, sub.r_T, sub.c_T) + bytes_crossprod(shp, sub.r_T, sub.c_T)
+              + bytes_materialize(shp, sub.r_T, sub.c_T))
+    y = np.zeros(sample_rows, dtype=np.float32)
+    reps, t_total = 0, 0.0
+    while t_total < budget_s and reps < 50:
+        t0 = time.perf_counter()
+        tg = oracle.Target(sub)                                        # materialize (join-gather)
+        oracle.lmm(tg, sch.extras["X1"]); oracle.tmm(tg, sch.extras["Y1"][:sample_rows])
+        oracle.lmm(tg, sch.extras["X16"]); oracle.tmm(tg, sch.extras["Y16"][:sample_rows])
+        oracle.gd(tg, "linear", y, np.zeros((sub.c_T, 1)), [0.1], 1)
+        oracle.crossprod(tg)
+        t_total += time.perf_counter() - t0
+        reps += 1
+    try:
+        from threadpoolctl import threadpool_info
+        blas_threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        blas_threads = 1
+    cores = min(len(os.sched_getaffinity(0)), blas_threads) if blas_threads else len(os.sched_getaffinity(0))
+    return {
+        "value": round(nbytes * reps / t_total / 1e9, 3), "unit": "GB/s", "cores": int(cores),
+        "kind": "oracle",
+        "sample": f"first {sample_rows} of {sch.r_T} target rows, same step, {reps} repetition(s), "
+                  f"{t_total:.1f} s; host has {len(os.sched_getaffinity(0))} usable cores, BLAS threads {blas_threads}",
+        "ms_per_step_scaled_to_full": round(t_total / reps * 1e3 * sch.r_T / sample_rows, 1),
+    }
+
+
+def run_sweep(il, torch, datagen, dev, path):
+    """Factorized vs materialized over the tuple-ratio / feature-ratio grid of the micro-benchmark."""
+    rows = []
+    for r_R, c_R in datagen.CONFIG1_GRID:
+        sch = datagen.config1(r_R=r_R, c_R=c_R)
+        shp = shapes_of(sch)
+        plan = il.ilargi_plan_create(il.schema_to_device(sch), sch.r_T, sch.c_T, max_cx=16)
+        Tm = il.ilargi_materialize(plan)
+        mplan = il.ilargi_plan_create([(Tm, None, np.arange(sch.c_T, dtype=np.int32))], sch.r_T, sch.c_T, max_cx=16)
+        rec = {"r_R": r_R, "c_R": c_R, "TR": sch.r_T / r_R, "FR": c_R / 20,
+               "complexity_ratio": round(complexity_ratio_lr(shp, sch.r_T, sch.c_T), 3)}
+        rec["materialize_us"] = round(time_loop(torch, lambda: il.ilargi_materialize(plan, Tm), 5) * 1e6, 1)
+        for c in (1, 16):
+            X, Y = dev(sch.extras[f"X{c}"]), dev(sch.extras[f"Y{c}"])
+            o1 = torch.empty((sch.r_T, c), device="cuda"); o2 = torch.empty((sch.c_T, c), device="cuda")
+            for name, fn_f, fn_m, b in (
+                ("lmm", lambda: il.ilargi_lmm(plan, X, o1), lambda: il.ilargi_lmm(mplan, X, o1), bytes_lmm(shp, sch.r_T, sch.c_T, c)),
+                ("tmm", lambda: il.ilargi_tmm(plan, Y, o2), lambda: il.ilargi_tmm(mplan, Y, o2), bytes_tmm(shp, sch.r_T, sch.c_T, c)),
+            ):
+                tf, tm = time_loop(torch, fn_f, 20), time_loop(torch, fn_m, 20)
+                rec[f"{name}_c{c}"] = {"fact_us": round(tf * 1e6, 1), "mat_us": round(tm * 1e6, 1),
+                                       "speedup": round(tm / tf, 3), "fact_GBps": round(b / tf / 1e9, 1)}
+        rows.append(rec)
+        print(json.dumps(rec), file=sys.stderr, flush=True)
+        del plan, mplan, Tm
+        torch.cuda.empty_cache()
+    with open(path, "w") as f:
+        json.dump(rows, f, indent=1)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--trace", default="lmm_rows:1", help="kernel family timed for the roofline entry")
+    ap.add_argument("--cpu-sample-rows", type=int, default=100_000)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
+    ap.add_argument("--sweep", default="", help="also run the TR/FR sweep and write it to this JSON file")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives are part of it); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import torch
+    import datagen
+    import paper_2502_01985_amd as il
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+
+    def dev(a):
+        return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+    sch = datagen.config1()                      # centre of the grid: R 100,000 x 200
+    shp = shapes_of(sch)
+    t0 = time.perf_counter()
+    plan = il.ilargi_plan_create(il.schema_to_device(sch), sch.r_T, sch.c_T, max_cx=16)
+    torch.cuda.synchronize()
+    plan_ms = (time.perf_counter() - t0) * 1e3
+    ops, keep = make_ops(il, torch, plan, sch, dev)
+    step_bytes = sum(b for _, _, b in ops)
+
+    def step():
+        for _, fn, _ in ops:
+            fn()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    il.ilargi_plan_trace_begin(plan, args.trace, 4096)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    kernel_ms = il.ilargi_plan_trace_end(plan, 4096)
+    ms_per_step = elapsed / args.steps * 1e3
+
+    # per-operator breakdown (outside the timed region)
+    breakdown = {}
+    for name, fn, b in ops:
+        t = time_loop(torch, fn, 20)
+        breakdown[name] = {"us": round(t * 1e6, 1), "GBps": round(b / t / 1e9, 1),
+                           "hbm_frac": round(b / t / 1e9 / HBM_PEAK_GBPS, 4), "MB": round(b / 1e6, 1)}
+    lt_bytes = sum(b for n, _, b in ops if n.startswith(("lmm", "tmm")))
+    lt_time = sum(breakdown[n]["us"] for n in breakdown if n.startswith(("lmm", "tmm"))) * 1e-6
+
+    # gradient descent: factorized vs materialized iterations/s
+    Tm = keep["Tm"]
+    mplan = il.ilargi_plan_create([(Tm, None, np.arange(sch.c_T, dtype=np.int32))], sch.r_T, sch.c_T, max_cx=16)
+    Wm = torch.zeros((sch.c_T, 1), device="cuda")
+    t_fact = time_loop(torch, ops[4][1], 30)
+    t_mat = time_loop(torch, lambda: il.ilargi_gd_step(mplan, il.LINEAR, Wm, keep["y"], keep["lr"], keep["loss"]), 30)
+    mat_ops = {}
+    for c in (1, 16):
+        X, Y = keep[f"X{c}"], keep[f"Y{c}"]
+        o1 = torch.empty((sch.r_T, c), device="cuda"); o2 = torch.empty((sch.c_T, c), device="cuda")
+        mat_ops[f"lmm_c{c}_us"] = round(time_loop(torch, lambda: il.ilargi_lmm(mplan, X, o1), 10) * 1e6, 1)
+        mat_ops[f"tmm_c{c}_us"] = round(time_loop(torch, lambda: il.ilargi_tmm(mplan, Y, o2), 10) * 1e6, 1)
+
+    # roofline of the traced kernel family
+    r_R, c_R = shp[1][0], shp[1][1]
+    kernel_bytes = {
+        "lmm_rows:1": 4 * r_R * c_R + 4 * r_R + 4 * c_R,                       # R once, P_R written, X_R
+        "colred:1": 4 * r_R * c_R + 4 * r_R + 4 * 1024 * c_R * 4,              # R once, Z_R read, partials
+        "lmm_assemble": 4 * shp[0][0] * shp[0][1] + 12 * sch.r_T,               # S once, fk, gathered P, out
+        "colred:0": 4 * shp[0][0] * shp[0][1] + 4 * sch.r_T,
+        "materialize": bytes_materialize(shp, sch.r_T, sch.c_T),
+    }
+    roofline = None
+    if kernel_ms.size:
+        # the family is launched by several operators of the step (cx = 1, cx = 16, gradient descent);
+        # the cx = 1 launches are the ones the byte figure above describes: they are the shortest third
+        per_launch = np.sort(kernel_ms)
+        sel = per_launch[: max(1, per_launch.size // 3)] if args.trace in ("lmm_rows:1", "colred:1", "lmm_assemble", "colred:0") else per_launch
+        avg_ms = float(np.mean(sel))
+        kb = kernel_bytes.get(args.trace)
+        if kb:
+            ach = kb / (avg_ms * 1e-3) / 1e9
+            roofline = {"bound": "hbm", "kernel": args.trace, "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS,
+                        "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": None,
+                        "avg_launch_us": round(avg_ms * 1e3, 2), "launches_timed": int(sel.size),
+                        "algorithmic_bytes_per_launch": int(kb)}
+
+    if args.sweep:
+        run_sweep(il, torch, datagen, dev, args.sweep)
+
+    cpu = None if args.no_cpu else cpu_baseline(sch, args.cpu_sample_rows)
+
+    out = {
+        "metric": "factorized LMM+T^T.Y+GD hot path, algorithmic GB/s (and % HBM peak)",
+        "value": round(step_bytes / (elapsed / args.steps) / 1e9, 2),
+        "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "config1 centre: star join S 1000000x20 + R 100000x200, uniform fk, T 1000000x220; "
+                               "step = lmm(cx=1,16) + tmm(cx=1,16) + gd_step(linear, m=1) + crossprod + materialize",
+                   "seed": 1, "tuple_ratio": 10, "feature_ratio": 10,
+                   "complexity_ratio_eq1": round(complexity_ratio_lr(shp, sch.r_T, sch.c_T), 3)},
+        "hbm_frac_of_step": round(step_bytes / (elapsed / args.steps) / 1e9 / HBM_PEAK_GBPS, 4),
+        "step_algorithmic_MB": round(step_bytes / 1e6, 1),
+        "lmm_tmm_GBps": round(lt_bytes / lt_time / 1e9, 1),
+        "lmm_tmm_hbm_frac": round(lt_bytes / lt_time / 1e9 / HBM_PEAK_GBPS, 4),
+        "ops": breakdown,
+        "gd": {"factorized_it_per_s": round(1.0 / t_fact, 1), "materialized_it_per_s": round(1.0 / t_mat, 1),
+               "speedup": round(t_mat / t_fact, 3),
+               "materialize_once_us": breakdown["materialize"]["us"],
+               "break_even_iterations": (round(breakdown["materialize"]["us"] * 1e-6 / (t_fact - t_mat), 1)
+                                         if t_fact > t_mat else 0)},
+        "materialized_ops": mat_ops,
+        "plan_build_ms": round(plan_ms, 2),
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -127,6 +127,16 @@ ilargi_status_t ilargi_segment_sum(ilargi_plan_t* plan, int k, const float* Y, i
 ilargi_status_t ilargi_plan_inverse_index(const ilargi_plan_t* plan, int k, const int32_t** rowptr,
                                           const int32_t** perm, int64_t* nnz);
 
+/* Per-kernel timing for benchmarks.  After trace_begin, every launch of the kernel family named by
+ * `tag` is bracketed by a pair of HIP events on the call's stream (at most max_launches pairs; later
+ * launches run untimed).  Tags: "lmm_rows:<k>" (product of source k), "lmm_assemble", "segsum:<k>",
+ * "colred:<k>", "finalize", "materialize", "gram".  trace_end waits for the recorded events, writes
+ * the elapsed milliseconds of up to `capacity` launches to the host array `ms` (may be NULL), stores
+ * the number of recorded launches in *count and switches tracing off.  Events are host objects; no
+ * device memory is allocated. */
+ilargi_status_t ilargi_plan_trace_begin(ilargi_plan_t* plan, const char* tag, int max_launches);
+ilargi_status_t ilargi_plan_trace_end(ilargi_plan_t* plan, float* ms, int capacity, int* count);
+
 /* Message for the most recent failure on this thread ("" if none).  Static storage. */
 const char* ilargi_last_error(void);
 

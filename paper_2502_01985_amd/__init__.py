@@ -38,7 +38,8 @@ STATUS_NAMES = ["OK", "ERR_NULL", "ERR_SHAPE", "ERR_COLMAP", "ERR_INDEX_RANGE", 
 EXPORTED = [
     "ilargi_plan_workspace_bytes", "ilargi_plan_create", "ilargi_plan_destroy", "ilargi_lmm", "ilargi_tmm",
     "ilargi_crossprod", "ilargi_materialize", "ilargi_gd_step", "ilargi_segment_sum",
-    "ilargi_plan_inverse_index", "ilargi_last_error", "ilargi_version",
+    "ilargi_plan_inverse_index", "ilargi_plan_trace_begin", "ilargi_plan_trace_end", "ilargi_last_error",
+    "ilargi_version",
 ]
 
 
@@ -60,6 +61,8 @@ lib.ilargi_materialize.argtypes = [_vp, _vp, _vp]
 lib.ilargi_gd_step.argtypes = [_vp, _int, _vp, _i64, _vp, _vp, _vp, _int, _vp]
 lib.ilargi_segment_sum.argtypes = [_vp, _int, _vp, _i64, _vp, _vp]
 lib.ilargi_plan_inverse_index.argtypes = [_vp, _int, ctypes.POINTER(_vp), ctypes.POINTER(_vp), ctypes.POINTER(_i64)]
+lib.ilargi_plan_trace_begin.argtypes = [_vp, ctypes.c_char_p, _int]
+lib.ilargi_plan_trace_end.argtypes = [_vp, ctypes.POINTER(ctypes.c_float), _int, ctypes.POINTER(_int)]
 for _name in EXPORTED[:-2]:
     getattr(lib, _name).restype = _int
 lib.ilargi_last_error.restype = ctypes.c_char_p
@@ -274,6 +277,18 @@ def ilargi_plan_inverse_index(plan: Plan, k: int):
         return ws[off:off + 4 * count].view(torch.int32).cpu().numpy().copy()
 
     return view(rp.value, r_k + 1), view(pm.value, int(nnz.value))
+
+
+def ilargi_plan_trace_begin(plan: Plan, tag: str, max_launches: int) -> None:
+    _check(lib.ilargi_plan_trace_begin(plan.handle, tag.encode(), max_launches), "ilargi_plan_trace_begin")
+
+
+def ilargi_plan_trace_end(plan: Plan, capacity: int):
+    """Elapsed milliseconds of the traced launches (numpy float32 array)."""
+    buf = (ctypes.c_float * max(capacity, 1))()
+    cnt = _int(0)
+    _check(lib.ilargi_plan_trace_end(plan.handle, buf, capacity, ctypes.byref(cnt)), "ilargi_plan_trace_end")
+    return np.array(buf[:min(cnt.value, capacity)], dtype=np.float32)
 
 
 def schema_to_device(schema, device="cuda:0"):

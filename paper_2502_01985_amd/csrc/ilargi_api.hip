@@ -6,6 +6,7 @@
 
 #include <algorithm>
 #include <new>
+#include <string>
 #include <vector>
 
 #include "ilargi_internal.h"
@@ -70,10 +71,33 @@ struct ilargi_plan {
   int fused = -1;   // identity source whose product is fused into the assembly pass
   int npairs = 0;
   std::vector<size_t> block_off;  // offset (floats) of Gram block (k,l), k <= l, index k * n + l
+  // optional timing of one kernel family: event pairs recorded around every launch whose tag matches
+  std::string trace_tag;
+  std::vector<hipEvent_t> trace_events;
+  int trace_n = 0;
   template <class T> T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
+  ~ilargi_plan() { for (hipEvent_t e : trace_events) (void)hipEventDestroy(e); }
 };
 
 namespace {
+
+// Records an event pair around the launches in its scope when the plan traces this tag.
+struct TraceScope {
+  ilargi_plan* pl;
+  hipStream_t st;
+  bool on;
+  TraceScope(ilargi_plan* p, const char* tag, int k, hipStream_t s) : pl(p), st(s), on(false) {
+    if (p->trace_events.empty() || p->trace_n + 2 > (int)p->trace_events.size()) return;
+    char full[64];
+    if (k >= 0) snprintf(full, sizeof(full), "%s:%d", tag, k);
+    else snprintf(full, sizeof(full), "%s", tag);
+    if (p->trace_tag != full) return;
+    on = hipEventRecord(p->trace_events[p->trace_n], st) == hipSuccess;
+  }
+  ~TraceScope() {
+    if (on && hipEventRecord(pl->trace_events[pl->trace_n + 1], st) == hipSuccess) pl->trace_n += 2;
+  }
+};
 
 int64_t colred_rows_per_block(int64_t rows) {
   int64_t rpb = (rows + kColredBlocks - 1) / kColredBlocks;
@@ -233,7 +257,10 @@ ilargi_status_t lmm_pass(ilargi_plan* pl, const float* X, int ldx, int col0, int
     a.X = X; a.ldx = ldx; a.col0 = col0; a.ncols = ncols;
     a.out = pl->at<float>(p.o_pz); a.ldo = ldx; a.r_out = p.rows;
     a.logL = pick_logL(p.cols, p.vec);
-    HIP_TRY(launch_lmm_rows(a, p.vec, 0, st, nullptr));
+    {
+      TraceScope ts(pl, "lmm_rows", k, st);
+      HIP_TRY(launch_lmm_rows(a, p.vec, 0, st, nullptr));
+    }
     g.idx[g.n] = p.ident ? nullptr : p.idx;
     g.P[g.n] = pl->at<float>(p.o_pz);
     g.rows[g.n] = p.rows;
@@ -253,7 +280,10 @@ ilargi_status_t lmm_pass(ilargi_plan* pl, const float* X, int ldx, int col0, int
   a.g = g;
   a.y = y;
   a.loss_partial = pl->at<float>(pl->lay.o_loss);
-  HIP_TRY(launch_lmm_rows(a, vec, mode, st, loss_grid));
+  {
+    TraceScope ts(pl, "lmm_assemble", -1, st);
+    HIP_TRY(launch_lmm_rows(a, vec, mode, st, loss_grid));
+  }
   return ILARGI_OK;
 }
 
@@ -275,14 +305,20 @@ ilargi_status_t tmm_pass(ilargi_plan* pl, const float* Y, int ldy, int col0, int
       SegArgs s = seg_args(pl, k);
       s.Y = Y; s.ldy = ldy; s.col0 = col0; s.ncols = ncols;
       s.Z = pl->at<float>(p.o_pz); s.ldz = ldy; s.zcol0 = col0;
-      HIP_TRY(launch_segsum(s, st));
+      {
+        TraceScope ts(pl, "segsum", k, st);
+        HIP_TRY(launch_segsum(s, st));
+      }
       c.Z = pl->at<float>(p.o_pz); c.ldz = ldy; c.col0 = col0;
     }
     c.ncols = ncols;
     c.partial = pl->at<float>(p.o_partial);
     c.rows_per_block = colred_rows_per_block(p.rows);
     int nb = colred_nblocks(p.rows);
-    HIP_TRY(launch_colred(c, nb, st));
+    {
+      TraceScope ts(pl, "colred", k, st);
+      HIP_TRY(launch_colred(c, nb, st));
+    }
     f.s[f.n].tcol2src = pl->at<int32_t>(p.o_tcol);
     f.s[f.n].partial = c.partial;
     f.s[f.n].nblocks = nb;
@@ -296,7 +332,10 @@ ilargi_status_t tmm_pass(ilargi_plan* pl, const float* Y, int ldy, int col0, int
   f.n_loss_partial = n_loss_partial;
   f.loss = loss;
   f.loss_scale = loss_scale;
-  HIP_TRY(launch_finalize(f, (int)pl->c_T, mode, st));
+  {
+    TraceScope ts(pl, "finalize", -1, st);
+    HIP_TRY(launch_finalize(f, (int)pl->c_T, mode, st));
+  }
   return ILARGI_OK;
 }
 
@@ -451,6 +490,36 @@ ilargi_status_t ilargi_plan_destroy(ilargi_plan_t* plan) {
   return ILARGI_OK;
 }
 
+ilargi_status_t ilargi_plan_trace_begin(ilargi_plan_t* plan, const char* tag, int max_launches) {
+  if (plan == nullptr || tag == nullptr) return fail(ILARGI_ERR_NULL, "trace_begin: NULL argument");
+  if (max_launches < 1 || max_launches > (1 << 20)) return fail(ILARGI_ERR_SHAPE, "trace_begin: max_launches = %d", max_launches);
+  for (hipEvent_t e : plan->trace_events) (void)hipEventDestroy(e);
+  plan->trace_events.clear();
+  plan->trace_n = 0;
+  plan->trace_tag = tag;
+  for (int i = 0; i < 2 * max_launches; ++i) {
+    hipEvent_t e;
+    HIP_TRY(hipEventCreate(&e));
+    plan->trace_events.push_back(e);
+  }
+  return ILARGI_OK;
+}
+
+ilargi_status_t ilargi_plan_trace_end(ilargi_plan_t* plan, float* ms, int capacity, int* count) {
+  if (plan == nullptr || count == nullptr) return fail(ILARGI_ERR_NULL, "trace_end: NULL argument");
+  int n = plan->trace_n / 2;
+  *count = n;
+  for (int i = 0; i < n && i < capacity && ms != nullptr; ++i) {
+    HIP_TRY(hipEventSynchronize(plan->trace_events[2 * i + 1]));
+    HIP_TRY(hipEventElapsedTime(&ms[i], plan->trace_events[2 * i], plan->trace_events[2 * i + 1]));
+  }
+  for (hipEvent_t e : plan->trace_events) (void)hipEventDestroy(e);
+  plan->trace_events.clear();
+  plan->trace_n = 0;
+  plan->trace_tag.clear();
+  return ILARGI_OK;
+}
+
 ilargi_status_t ilargi_plan_inverse_index(const ilargi_plan_t* plan, int k, const int32_t** rowptr,
                                           const int32_t** perm, int64_t* nnz) {
   if (plan == nullptr || rowptr == nullptr || perm == nullptr || nnz == nullptr) return fail(ILARGI_ERR_NULL, "inverse_index: NULL argument");
@@ -549,7 +618,10 @@ ilargi_status_t ilargi_materialize(ilargi_plan_t* plan, float* T, void* stream) 
     ++a.n;
   }
   a.T = T; a.r_T = plan->r_T; a.c_T = (int)plan->c_T;
-  HIP_TRY(launch_materialize(a, static_cast<hipStream_t>(stream)));
+  {
+    TraceScope ts(plan, "materialize", -1, static_cast<hipStream_t>(stream));
+    HIP_TRY(launch_materialize(a, static_cast<hipStream_t>(stream)));
+  }
   return ILARGI_OK;
 }
 
@@ -570,7 +642,10 @@ ilargi_status_t ilargi_crossprod(ilargi_plan_t* plan, float* out, void* stream) 
     g.rows_per_chunk = std::max<int64_t>(16, (g.rows_per_chunk + 15) / 16 * 16);
     nch = std::max<int64_t>(1, (g.n_rows + g.rows_per_chunk - 1) / g.rows_per_chunk);
     g.partial = gpart;
-    HIP_TRY(launch_gram(g, (int)nch, st));
+    {
+      TraceScope ts(plan, "gram", -1, st);
+      HIP_TRY(launch_gram(g, (int)nch, st));
+    }
     HIP_TRY(launch_gram_reduce(gpart, (int)nch, elems, block, st));
     return ILARGI_OK;
   };
