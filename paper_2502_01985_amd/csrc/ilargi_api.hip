@@ -45,7 +45,7 @@ struct SourcePlan {
   std::vector<int32_t> colmap_h;
   // offsets into the workspace
   size_t o_colmap = 0, o_tcol = 0, o_rowptr = 0, o_perm = 0, o_chunk_seg = 0, o_chunk_beg = 0, o_chunk_end = 0,
-         o_long_seg = 0, o_long_first = 0, o_chunk_partial = 0, o_pz = 0, o_partial = 0;
+         o_long_seg = 0, o_long_first = 0, o_chunk_partial = 0, o_pz = 0, o_partial = 0, o_g = 0;
   int64_t nch_max = 0, nl_max = 0;
   int n_chunks = 0, n_long = 0;
   int64_t nnz = 0;
@@ -53,6 +53,7 @@ struct SourcePlan {
 };
 
 struct Layout {
+  size_t o_gslot = 0, o_gj0 = 0;
   size_t o_flags = 0, o_tcol_table = 0, o_pairs = 0, o_E = 0, o_loss = 0, o_sort = 0, o_hist = 0, o_zc = 0,
          o_gpartial = 0, o_blocks = 0;
   int64_t zc_floats = 0, gpartial_floats = 0, blocks_floats = 0;
@@ -69,6 +70,7 @@ struct ilargi_plan {
   std::vector<SourcePlan> src;
   Layout lay;
   int fused = -1;   // identity source whose product is fused into the assembly pass
+  bool mat_vec4 = false;  // the grouped column tables of the vectorized join-gather are valid
   int npairs = 0;
   std::vector<size_t> block_off;  // offset (floats) of Gram block (k,l), k <= l, index k * n + l
   // optional timing of one kernel family: event pairs recorded around every launch whose tag matches
@@ -137,6 +139,8 @@ ilargi_status_t make_layout(int n, const ilargi_source_t* s, int64_t r_T, int64_
   lay.o_flags = take(sizeof(int32_t) * 2 * n);
   lay.o_tcol_table = take(sizeof(void*) * n);
   lay.o_pairs = take(sizeof(GramAsmPair) * n * (n + 1) / 2);
+  lay.o_gslot = take(sizeof(int32_t) * c_T);
+  lay.o_gj0 = take(sizeof(int32_t) * c_T);
   const int64_t wmax = std::max<int64_t>(max_cx, cmax);
   for (int k = 0; k < n; ++k) {
     SourcePlan& p = src[k];
@@ -156,6 +160,7 @@ ilargi_status_t make_layout(int n, const ilargi_source_t* s, int64_t r_T, int64_
     }
     p.o_pz = take(sizeof(float) * std::max<int64_t>(p.rows, 1) * max_cx);
     p.o_partial = take(sizeof(float) * kColredBlocks * std::max<int64_t>(p.cols, 1) * kNarrowCT);
+    p.o_g = take(sizeof(float) * std::max<int64_t>(p.cols, 1) * max_cx);
   }
   lay.o_E = take(sizeof(float) * std::max<int64_t>(r_T, 1) * max_cx);
   lay.o_loss = take(sizeof(float) * 2048 * kNarrowCT);
@@ -170,6 +175,7 @@ ilargi_status_t make_layout(int n, const ilargi_source_t* s, int64_t r_T, int64_
       int64_t cc = src[k].cols * src[l].cols;
       lay.blocks_floats += cc;
       lay.gpartial_floats = std::max(lay.gpartial_floats, cc);
+      lay.gpartial_floats = std::max(lay.gpartial_floats, src[k].cols * max_cx);
       if (l > k) {
         if (src[l].has_idx && src[l].rows * 2 <= r_T) lay.zc_floats = std::max(lay.zc_floats, src[l].rows * src[k].cols);
         if (src[k].has_idx && src[k].rows * 2 <= r_T) lay.zc_floats = std::max(lay.zc_floats, src[k].rows * src[l].cols);
@@ -339,6 +345,69 @@ ilargi_status_t tmm_pass(ilargi_plan* pl, const float* Y, int ldy, int col0, int
   return ILARGI_OK;
 }
 
+// Runs the matrix-core transposed reduction in row chunks and adds the chunk results in order.
+ilargi_status_t run_tred(ilargi_plan* pl, TredArgs& g, float* block, const char* tag, int tag_k, hipStream_t st) {
+  int64_t elems = (int64_t)g.ca * g.cb;
+  if (elems <= 0) return ILARGI_OK;
+  int64_t nch = (g.n_rows + 255) / 256;
+  nch = std::min<int64_t>(nch, std::max<int64_t>(1, pl->lay.gpartial_floats / elems));
+  nch = std::min<int64_t>(std::max<int64_t>(nch, 1), 512);
+  g.rows_per_block = (g.n_rows + nch - 1) / nch;
+  g.rows_per_block = std::max<int64_t>(16, (g.rows_per_block + 15) / 16 * 16);
+  nch = std::max<int64_t>(1, (g.n_rows + g.rows_per_block - 1) / g.rows_per_block);
+  g.partial = pl->at<float>(pl->lay.o_gpartial);
+  {
+    TraceScope ts(pl, tag, tag_k, st);
+    HIP_TRY(launch_tred(g, (int)nch, st));
+  }
+  HIP_TRY(launch_tred_reduce(g.partial, (int)nch, elems, block, st));
+  return ILARGI_OK;
+}
+
+// T^T Y for an operand with many columns: segment sums, matrix-core column reduce, column assembly.
+ilargi_status_t tmm_wide(ilargi_plan* pl, const float* Y, int cx, float* out, int mode, const float* lr,
+                         float* loss, int n_loss_partial, float loss_scale, hipStream_t st) {
+  ColAsmArgs c;
+  memset(&c, 0, sizeof(c));
+  for (int k = 0; k < pl->n; ++k) {
+    SourcePlan& p = pl->src[k];
+    if (p.empty) continue;
+    TredArgs g;
+    memset(&g, 0, sizeof(g));
+    g.A = p.D; g.lda = (int)p.cols; g.ca = (int)p.cols; g.a_rows = p.rows;
+    g.ldb = cx; g.cb = cx; g.bcol0 = 0; g.b_rows = p.rows;
+    g.n_rows = p.rows;
+    if (p.ident) {
+      g.B = Y;
+    } else {
+      SegArgs s = seg_args(pl, k);
+      s.Y = Y; s.ldy = cx; s.col0 = 0; s.ncols = cx;
+      s.Z = pl->at<float>(p.o_pz); s.ldz = cx; s.zcol0 = 0;
+      {
+        TraceScope ts(pl, "segsum", k, st);
+        HIP_TRY(launch_segsum(s, st));
+      }
+      g.B = pl->at<float>(p.o_pz);
+    }
+    ilargi_status_t rc = run_tred(pl, g, pl->at<float>(p.o_g), "colred", k, st);
+    if (rc != ILARGI_OK) return rc;
+    c.tcol2src[c.n] = pl->at<int32_t>(p.o_tcol);
+    c.G[c.n] = pl->at<float>(p.o_g);
+    ++c.n;
+  }
+  c.c_T = (int)pl->c_T; c.cx = cx; c.out = out;
+  c.lr = lr; c.inv_rT = pl->r_T > 0 ? 1.0f / (float)pl->r_T : 0.0f;
+  c.loss_partial = pl->at<float>(pl->lay.o_loss); c.n_loss_partial = n_loss_partial;
+  c.loss = loss; c.loss_scale = loss_scale;
+  {
+    TraceScope ts(pl, "finalize", -1, st);
+    HIP_TRY(launch_colasm(c, mode, st));
+  }
+  return ILARGI_OK;
+}
+
+constexpr int kWideMin = 8;   // operands with at least this many columns take the matrix-core kernels
+
 ilargi_status_t check_call(const ilargi_plan* pl, const void* a, const void* b, int64_t cx, const char* what) {
   if (pl == nullptr) return fail(ILARGI_ERR_NULL, "%s: plan is NULL", what);
   if (a == nullptr || b == nullptr) return fail(ILARGI_ERR_NULL, "%s: operand pointer is NULL", what);
@@ -460,6 +529,33 @@ ilargi_status_t ilargi_plan_create(int n, const ilargi_source_t* sources, int64_
     const SourcePlan& p = pl->src[k];
     if (p.ident && !p.empty && p.rows * p.cols > best) { best = p.rows * p.cols; pl->fused = k; }
   }
+  // join-gather tables: groups of four target columns fed by four consecutive columns of one source
+  if (c_T % 4 == 0) {
+    std::vector<int32_t> gslot((size_t)c_T / 4, -1), gj0((size_t)c_T / 4, 0);
+    bool regular = true;
+    for (int64_t g = 0; g < c_T / 4 && regular; ++g) {
+      int slot = 0;
+      for (int k = 0; k < n && regular; ++k) {
+        if (pl->src[k].empty) continue;
+        int hits = 0;
+        for (int e = 0; e < 4; ++e) hits += tcol[k][4 * g + e] >= 0;
+        if (hits == 4 && gslot[g] < 0 && tcol[k][4 * g + 1] == tcol[k][4 * g] + 1 &&
+            tcol[k][4 * g + 2] == tcol[k][4 * g] + 2 && tcol[k][4 * g + 3] == tcol[k][4 * g] + 3) {
+          gslot[g] = slot;
+          gj0[g] = tcol[k][4 * g];
+        } else if (hits != 0) {
+          regular = false;
+        }
+        ++slot;
+      }
+    }
+    pl->mat_vec4 = regular;
+    if (regular) {
+      HIP_TRY(hipMemcpyAsync(pl->at<int32_t>(lay.o_gslot), gslot.data(), sizeof(int32_t) * gslot.size(), hipMemcpyHostToDevice, st));
+      HIP_TRY(hipMemcpyAsync(pl->at<int32_t>(lay.o_gj0), gj0.data(), sizeof(int32_t) * gj0.size(), hipMemcpyHostToDevice, st));
+      HIP_TRY(hipStreamSynchronize(st));
+    }
+  }
   // Gram blocks (k <= l) and the table the assembly kernel walks
   pl->block_off.assign((size_t)n * n, 0);
   std::vector<GramAsmPair> pairs;
@@ -553,6 +649,7 @@ ilargi_status_t ilargi_tmm(ilargi_plan_t* plan, const float* Y, int64_t cx, floa
   if (rc != ILARGI_OK) return rc;
   if (precision != ILARGI_F32) return fail(ILARGI_ERR_UNSUPPORTED, "tmm: bf16 inputs need a wide operand");
   hipStream_t st = static_cast<hipStream_t>(stream);
+  if (cx >= kWideMin) return tmm_wide(plan, Y, (int)cx, out, 0, nullptr, nullptr, 0, 0.0f, st);
   for (int64_t col0 = 0; col0 < cx; col0 += kNarrowCT) {
     int ncols = (int)std::min<int64_t>(kNarrowCT, cx - col0);
     rc = tmm_pass(plan, Y, (int)cx, (int)col0, ncols, out, (int)cx, 0, nullptr, nullptr, 0, 0.0f, st);
@@ -618,6 +715,8 @@ ilargi_status_t ilargi_materialize(ilargi_plan_t* plan, float* T, void* stream) 
     ++a.n;
   }
   a.T = T; a.r_T = plan->r_T; a.c_T = (int)plan->c_T;
+  a.gslot = plan->mat_vec4 ? plan->at<int32_t>(plan->lay.o_gslot) : nullptr;
+  a.gj0 = plan->mat_vec4 ? plan->at<int32_t>(plan->lay.o_gj0) : nullptr;
   {
     TraceScope ts(plan, "materialize", -1, static_cast<hipStream_t>(stream));
     HIP_TRY(launch_materialize(a, static_cast<hipStream_t>(stream)));
@@ -631,23 +730,9 @@ ilargi_status_t ilargi_crossprod(ilargi_plan_t* plan, float* out, void* stream) 
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int n = plan->n;
   float* blocks = plan->at<float>(plan->lay.o_blocks);
-  float* gpart = plan->at<float>(plan->lay.o_gpartial);
   float* zc = plan->at<float>(plan->lay.o_zc);
-  auto run_gram = [&](GramArgs& g, float* block) -> ilargi_status_t {
-    int64_t elems = (int64_t)g.ca * g.cb;
-    int64_t nch = (g.n_rows + 4095) / 4096;
-    nch = std::min<int64_t>(nch, std::max<int64_t>(1, plan->lay.gpartial_floats / elems));
-    nch = std::min<int64_t>(std::max<int64_t>(nch, 1), 1024);
-    g.rows_per_chunk = (g.n_rows + nch - 1) / nch;
-    g.rows_per_chunk = std::max<int64_t>(16, (g.rows_per_chunk + 15) / 16 * 16);
-    nch = std::max<int64_t>(1, (g.n_rows + g.rows_per_chunk - 1) / g.rows_per_chunk);
-    g.partial = gpart;
-    {
-      TraceScope ts(plan, "gram", -1, st);
-      HIP_TRY(launch_gram(g, (int)nch, st));
-    }
-    HIP_TRY(launch_gram_reduce(gpart, (int)nch, elems, block, st));
-    return ILARGI_OK;
+  auto run_gram = [&](TredArgs& g, float* block) -> ilargi_status_t {
+    return run_tred(plan, g, block, "gram", -1, st);
   };
   for (int k = 0; k < n; ++k) {
     const SourcePlan& a = plan->src[k];
@@ -656,7 +741,7 @@ ilargi_status_t ilargi_crossprod(ilargi_plan_t* plan, float* out, void* stream) 
       const SourcePlan& b = plan->src[l];
       if (b.empty) continue;
       float* block = blocks + plan->block_off[(size_t)k * n + l];
-      GramArgs g;
+      TredArgs g;
       memset(&g, 0, sizeof(g));
       ilargi_status_t rc;
       if (l == k) {

@@ -104,6 +104,10 @@ struct MatArgs {
   float* T;
   int64_t r_T;
   int c_T;
+  // optional tables for the vectorized form: per group of four target columns the feeding source slot
+  // (-1: nobody) and its first source column; NULL when some group is fed irregularly
+  const int32_t* gslot;
+  const int32_t* gj0;
 };
 
 struct GramArgs {
@@ -113,6 +117,29 @@ struct GramArgs {
   int64_t n_rows;        // t in [0, n_rows)
   int64_t rows_per_chunk;
   float* partial;        // [nchunks][ca][cb]
+};
+
+// Transposed reduction  C = sum_t w_t a_t^T b_t  on the matrix cores (see kernels_tred.hip).
+struct TredArgs {
+  const float* A; int lda, ca; const int32_t* ia; int64_t a_rows;   // row t of A = A[ia ? ia[t] : t]
+  const float* B; int ldb, cb, bcol0; const int32_t* ib; int64_t b_rows;
+  const int32_t* wptr;     // optional: w_t = wptr[t+1] - wptr[t]
+  int64_t n_rows, rows_per_block;
+  float* partial;          // [gridDim.x][ca][cb]
+};
+
+struct ColAsmArgs {
+  int n;
+  const int32_t* tcol2src[kMaxSources];
+  const float* G[kMaxSources];   // c_k x cx each
+  int c_T, cx;
+  float* out;                    // c_T x cx
+  const float* lr;
+  float inv_rT;
+  const float* loss_partial;     // [n_loss_partial][cx]
+  int n_loss_partial;
+  float* loss;
+  float loss_scale;
 };
 
 struct GramAsmPair { const float* block; int k, l, cb; };
@@ -134,6 +161,9 @@ hipError_t launch_gram(const GramArgs& a, int nchunks, hipStream_t st);
 hipError_t launch_gram_reduce(const float* partial, int nchunks, int64_t elems, float* block, hipStream_t st);
 hipError_t launch_gram_assemble(const GramAsmPair* pairs_dev, int npairs, const int32_t* const* tcol2src_dev,
                                 int c_T, float* out, hipStream_t st);
+hipError_t launch_tred(const TredArgs& a, int nchunks, hipStream_t st);
+hipError_t launch_tred_reduce(const float* partial, int nchunks, int64_t elems, float* block, hipStream_t st);
+hipError_t launch_colasm(const ColAsmArgs& a, int mode, hipStream_t st);
 hipError_t launch_fill_zero(float* p, int64_t n, hipStream_t st);
 
 inline int ilog2_ceil(int64_t v) { int l = 0; while ((1ll << l) < v) ++l; return l; }

@@ -1,0 +1,221 @@
+// Transposed reduction on the matrix cores:  C = sum_t w_t a_t^T b_t  where a_t, b_t are rows of two
+// row-major float32 matrices (optionally addressed through index vectors) and t runs over a long row range.
+// This one contraction serves
+//   * the column reduce  G_k = D_k^T Z_k  of the transposed multiply when the operand has >= 8 columns
+//     (a = D_k, b = Z_k), including the batched gradient of Alg. 1 for many models, and
+//   * every block of the Gram matrix T^T T (a, b = tables or summed tables, w = fan-out counts).
+//
+// MFMA 16x16x4 (float32): the 16 "M" rows are table columns, the 16 "N" columns operand columns, the 4 "K"
+// slots are rows t.  Lane l = 16 q + s loads the float4  a[t0 + q][j0 + 4 s .. 4 s + 3]  (a wavefront load covers
+// 4 whole rows x 64 contiguous columns, fully coalesced) and feeds its four components to four MFMAs whose
+// M index s stands for table column  j0 + 4 s + e.  The B operand of lane l is  b[t0 + q][n0 + s].
+//
+// Each wavefront owns a share of the rows and the full output tile; wavefronts and workgroups are combined
+// afterwards in a fixed order, so results are reproducible.
+#include <algorithm>
+
+#include "ilargi_internal.h"
+
+namespace ilargi {
+
+namespace {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+constexpr int kU = 4;  // row quads in flight per wavefront
+
+// JT: 64-column tiles of A per workgroup tile, NT: 16-column tiles of B.  JT * NT <= 4.
+template <int JT, int NT, bool VEC4>
+__global__ __launch_bounds__(kBlock) void tred_kernel(TredArgs a) {
+  __shared__ float red[JT * 64 * NT * 16];
+  const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+  const int s = lane % 16, q = lane / 16;
+  const int nb_slabs = (a.cb + NT * 16 - 1) / (NT * 16);
+  const int a_slab = blockIdx.y / nb_slabs, b_slab = blockIdx.y - a_slab * nb_slabs;
+  const int j0 = a_slab * JT * 64, n0 = b_slab * NT * 16;
+  const int64_t t_lo = (int64_t)blockIdx.x * a.rows_per_block;
+  const int64_t t_hi = min(t_lo + a.rows_per_block, a.n_rows);
+
+  v4f acc[JT][4][NT];
+#pragma unroll
+  for (int jt = 0; jt < JT; ++jt)
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) acc[jt][e][nt] = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
+
+  // which of this lane's column groups / operand columns exist
+  bool jok[JT], nok[NT];
+#pragma unroll
+  for (int jt = 0; jt < JT; ++jt) jok[jt] = j0 + jt * 64 + 4 * s < a.ca;
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) nok[nt] = n0 + nt * 16 + s < a.cb;
+
+  for (int64_t base = t_lo + (int64_t)wave * (4 * kU); base < t_hi; base += (int64_t)(kBlock / kWave) * (4 * kU)) {
+    float av[kU][JT][4];
+    float bv[kU][NT];
+#pragma unroll
+    for (int u = 0; u < kU; ++u) {
+      int64_t t = base + u * 4 + q;
+      int64_t ra = -1, rb = -1;
+      float w = 1.0f;
+      if (t < t_hi) {
+        ra = a.ia ? (int64_t)a.ia[t] : (t < a.a_rows ? t : -1);
+        rb = a.ib ? (int64_t)a.ib[t] : (t < a.b_rows ? t : -1);
+        if (a.wptr) w = (float)(a.wptr[t + 1] - a.wptr[t]);
+      }
+      const bool live = ra >= 0 && rb >= 0;
+#pragma unroll
+      for (int jt = 0; jt < JT; ++jt) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) av[u][jt][e] = 0.0f;
+        if (live && jok[jt]) {
+          const float* p = a.A + ra * a.lda + j0 + jt * 64 + 4 * s;
+          if constexpr (VEC4) {
+            float4 v = *reinterpret_cast<const float4*>(p);
+            av[u][jt][0] = v.x; av[u][jt][1] = v.y; av[u][jt][2] = v.z; av[u][jt][3] = v.w;
+          } else {
+            const int left = a.ca - (j0 + jt * 64 + 4 * s);
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (e < left) av[u][jt][e] = p[e];
+          }
+          if (a.wptr) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) av[u][jt][e] *= w;
+          }
+        }
+      }
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+        bv[u][nt] = (live && nok[nt]) ? a.B[rb * a.ldb + a.bcol0 + n0 + nt * 16 + s] : 0.0f;
+    }
+#pragma unroll
+    for (int u = 0; u < kU; ++u)
+#pragma unroll
+      for (int jt = 0; jt < JT; ++jt)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt)
+            acc[jt][e][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u][jt][e], bv[u][nt], acc[jt][e][nt], 0, 0, 0);
+  }
+
+  // combine the four wavefronts in order; red is [JT*64][NT*16]
+  for (int w = 0; w < kBlock / kWave; ++w) {
+    if (wave == w) {
+#pragma unroll
+      for (int jt = 0; jt < JT; ++jt)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              int j = jt * 64 + 4 * (4 * q + r) + e;
+              int n = nt * 16 + s;
+              float v = acc[jt][e][nt][r];
+              if (w == 0) red[j * (NT * 16) + n] = v;
+              else red[j * (NT * 16) + n] += v;
+            }
+    }
+    __syncthreads();
+  }
+  float* out = a.partial + (int64_t)blockIdx.x * a.ca * a.cb;
+  for (int o = tid; o < JT * 64 * NT * 16; o += kBlock) {
+    int j = o / (NT * 16), n = o - j * (NT * 16);
+    if (j0 + j < a.ca && n0 + n < a.cb) out[(int64_t)(j0 + j) * a.cb + n0 + n] = red[o];
+  }
+}
+
+// block[e] = sum over chunks, in chunk order
+__global__ __launch_bounds__(kBlock) void tred_reduce_kernel(const float* __restrict__ partial, int nchunks,
+                                                             int64_t elems, float* __restrict__ block) {
+  for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < elems;
+       e += (int64_t)gridDim.x * blockDim.x) {
+    float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
+    int c = 0;
+    for (; c + 4 <= nchunks; c += 4) {
+      s0 += partial[(int64_t)c * elems + e];
+      s1 += partial[(int64_t)(c + 1) * elems + e];
+      s2 += partial[(int64_t)(c + 2) * elems + e];
+      s3 += partial[(int64_t)(c + 3) * elems + e];
+    }
+    for (; c < nchunks; ++c) s0 += partial[(int64_t)c * elems + e];
+    block[e] = (s0 + s1) + (s2 + s3);
+  }
+}
+
+// out[t, n] = sum over sources, in order, of G_k[tcol2src_k[t], n]; MODE 1 applies the update of Alg. 1.
+template <int MODE>
+__global__ __launch_bounds__(kBlock) void colasm_kernel(ColAsmArgs a) {
+  int64_t total = (int64_t)a.c_T * a.cx;
+  for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total;
+       e += (int64_t)gridDim.x * blockDim.x) {
+    int t = (int)(e / a.cx), n = (int)(e - (int64_t)t * a.cx);
+    float acc = 0.0f;
+    for (int k = 0; k < a.n; ++k) {
+      int j = a.tcol2src[k][t];
+      if (j >= 0) acc += a.G[k][(int64_t)j * a.cx + n];
+    }
+    if constexpr (MODE == 0) a.out[e] = acc;
+    else a.out[e] = a.out[e] - a.lr[n] * (acc * a.inv_rT);
+  }
+  if constexpr (MODE == 1) {
+    // loss[n] = scale * sum of the per-workgroup partials, lanes stride the partials, fixed butterfly
+    if (a.loss != nullptr && blockIdx.x == 0) {
+      const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+      for (int n = wave; n < a.cx; n += kBlock / kWave) {
+        float s = 0.0f;
+        for (int b = lane; b < a.n_loss_partial; b += kWave) s += a.loss_partial[(int64_t)b * a.cx + n];
+        for (int m = kWave / 2; m >= 1; m >>= 1) s += __shfl_xor(s, m);
+        if (lane == 0) a.loss[n] = s * a.loss_scale;
+      }
+    }
+  }
+}
+
+}  // namespace
+
+hipError_t launch_tred(const TredArgs& a, int nchunks, hipStream_t st) {
+  if (a.ca <= 0 || a.cb <= 0 || nchunks <= 0) return hipSuccess;
+  const bool vec4 = a.lda % 4 == 0 && a.ca % 4 == 0 && reinterpret_cast<uintptr_t>(a.A) % 16 == 0;
+  int nt = a.cb <= 16 ? 1 : (a.cb <= 32 ? 2 : 4);
+  int jt = std::min(4 / nt, (a.ca + 63) / 64);
+  if (jt == 3) jt = 4;
+  int a_slabs = (a.ca + jt * 64 - 1) / (jt * 64), b_slabs = (a.cb + nt * 16 - 1) / (nt * 16);
+  dim3 grid(nchunks, a_slabs * b_slabs);
+#define ILARGI_TRED(J, N)                                                      \
+  do {                                                                         \
+    if (vec4) tred_kernel<J, N, true><<<grid, kBlock, 0, st>>>(a);             \
+    else tred_kernel<J, N, false><<<grid, kBlock, 0, st>>>(a);                 \
+  } while (0)
+  if (jt == 4) ILARGI_TRED(4, 1);
+  else if (jt == 2 && nt == 2) ILARGI_TRED(2, 2);
+  else if (jt == 2) ILARGI_TRED(2, 1);
+  else if (nt == 4) ILARGI_TRED(1, 4);
+  else if (nt == 2) ILARGI_TRED(1, 2);
+  else ILARGI_TRED(1, 1);
+#undef ILARGI_TRED
+  return hipGetLastError();
+}
+
+hipError_t launch_tred_reduce(const float* partial, int nchunks, int64_t elems, float* block, hipStream_t st) {
+  if (elems <= 0) return hipSuccess;
+  int grid = (int)((elems + kBlock - 1) / kBlock);
+  if (grid > 4096) grid = 4096;
+  tred_reduce_kernel<<<grid, kBlock, 0, st>>>(partial, nchunks, elems, block);
+  return hipGetLastError();
+}
+
+hipError_t launch_colasm(const ColAsmArgs& a, int mode, hipStream_t st) {
+  int64_t total = (int64_t)a.c_T * a.cx;
+  if (total <= 0) return hipSuccess;
+  int grid = (int)((total + kBlock - 1) / kBlock);
+  if (grid > 1024) grid = 1024;
+  if (mode == 0) colasm_kernel<0><<<grid, kBlock, 0, st>>>(a);
+  else colasm_kernel<1><<<grid, kBlock, 0, st>>>(a);
+  return hipGetLastError();
+}
+
+}  // namespace ilargi
