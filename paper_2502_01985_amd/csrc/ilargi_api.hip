@@ -163,7 +163,7 @@ ilargi_status_t make_layout(int n, const ilargi_source_t* s, int64_t r_T, int64_
     p.o_g = take(sizeof(float) * std::max<int64_t>(p.cols, 1) * max_cx);
   }
   lay.o_E = take(sizeof(float) * std::max<int64_t>(r_T, 1) * max_cx);
-  lay.o_loss = take(sizeof(float) * 2048 * kNarrowCT);
+  lay.o_loss = take(sizeof(float) * std::max<int64_t>(2048 * kNarrowCT, 1024 * max_cx));
   lay.o_sort = take(sizeof(int32_t) * 4 * std::max<int64_t>(r_T, 1));
   lay.o_hist = take(sizeof(int32_t) * sort_hist_ints(r_T));
   // Gram scratch: summed rows for the "via sums" route, chunk partials, the (k,l) blocks
@@ -250,7 +250,7 @@ int pass_width(const ilargi_plan* pl) {
 
 // out (or the residual E) for operand columns [col0, col0 + ncols):  per-source products, then the assembly.
 ilargi_status_t lmm_pass(ilargi_plan* pl, const float* X, int ldx, int col0, int ncols, float* out, int ldo,
-                         int mode, const float* y, int* loss_grid, hipStream_t st) {
+                         int mode, const float* y, int* loss_grid, bool wide, hipStream_t st) {
   GatherArgs g;
   memset(&g, 0, sizeof(g));
   g.ldp = ldx;
@@ -265,7 +265,8 @@ ilargi_status_t lmm_pass(ilargi_plan* pl, const float* X, int ldx, int col0, int
     a.logL = pick_logL(p.cols, p.vec);
     {
       TraceScope ts(pl, "lmm_rows", k, st);
-      HIP_TRY(launch_lmm_rows(a, p.vec, 0, st, nullptr));
+      if (wide) HIP_TRY(launch_lmm_mfma(a, p.vec, 0, st, nullptr));
+      else HIP_TRY(launch_lmm_rows(a, p.vec, 0, st, nullptr));
     }
     g.idx[g.n] = p.ident ? nullptr : p.idx;
     g.P[g.n] = pl->at<float>(p.o_pz);
@@ -286,9 +287,11 @@ ilargi_status_t lmm_pass(ilargi_plan* pl, const float* X, int ldx, int col0, int
   a.g = g;
   a.y = y;
   a.loss_partial = pl->at<float>(pl->lay.o_loss);
+  a.ld_loss = ldx;
   {
     TraceScope ts(pl, "lmm_assemble", -1, st);
-    HIP_TRY(launch_lmm_rows(a, vec, mode, st, loss_grid));
+    if (wide) HIP_TRY(launch_lmm_mfma(a, vec, mode, st, loss_grid));
+    else HIP_TRY(launch_lmm_rows(a, vec, mode, st, loss_grid));
   }
   return ILARGI_OK;
 }
@@ -634,10 +637,11 @@ ilargi_status_t ilargi_lmm(ilargi_plan_t* plan, const float* X, int64_t cx, floa
   if (rc != ILARGI_OK) return rc;
   if (precision != ILARGI_F32) return fail(ILARGI_ERR_UNSUPPORTED, "lmm: bf16 inputs need a wide operand");
   hipStream_t st = static_cast<hipStream_t>(stream);
+  if (cx >= kWideMin) return lmm_pass(plan, X, (int)cx, 0, (int)cx, out, (int)cx, 0, nullptr, nullptr, true, st);
   const int w = pass_width(plan);
   for (int64_t col0 = 0; col0 < cx; col0 += w) {
     int ncols = (int)std::min<int64_t>(w, cx - col0);
-    rc = lmm_pass(plan, X, (int)cx, (int)col0, ncols, out, (int)cx, 0, nullptr, nullptr, st);
+    rc = lmm_pass(plan, X, (int)cx, (int)col0, ncols, out, (int)cx, 0, nullptr, nullptr, false, st);
     if (rc != ILARGI_OK) return rc;
   }
   return ILARGI_OK;
@@ -670,10 +674,16 @@ ilargi_status_t ilargi_gd_step(ilargi_plan_t* plan, ilargi_model_t model, float*
   float* E = plan->at<float>(plan->lay.o_E);
   const int w = pass_width(plan);
   const float loss_scale = (model == ILARGI_LINEAR ? 0.5f : 1.0f) / (float)plan->r_T;
+  if (m >= kWideMin) {
+    int loss_grid = 0;
+    rc = lmm_pass(plan, W, (int)m, 0, (int)m, E, (int)m, model == ILARGI_LINEAR ? 1 : 2, y, &loss_grid, true, st);
+    if (rc != ILARGI_OK) return rc;
+    return tmm_wide(plan, E, (int)m, W, 1, lr, loss, loss_grid, loss_scale, st);
+  }
   for (int64_t col0 = 0; col0 < m; col0 += w) {
     int ncols = (int)std::min<int64_t>(w, m - col0);
     int loss_grid = 0;
-    rc = lmm_pass(plan, W, (int)m, (int)col0, ncols, E, (int)m, model == ILARGI_LINEAR ? 1 : 2, y, &loss_grid, st);
+    rc = lmm_pass(plan, W, (int)m, (int)col0, ncols, E, (int)m, model == ILARGI_LINEAR ? 1 : 2, y, &loss_grid, false, st);
     if (rc != ILARGI_OK) return rc;
     rc = tmm_pass(plan, E, (int)m, (int)col0, ncols, W, (int)m, 1, lr, loss, loss_grid, loss_scale, st);
     if (rc != ILARGI_OK) return rc;

@@ -43,7 +43,17 @@ struct LmmArgs {
   GatherArgs g;
   // gradient-descent modes
   const float* y;         // labels, r_out
-  float* loss_partial;    // [gridDim.x][kNarrowCT]
+  float* loss_partial;    // narrow kernel: [gridDim.x][kNarrowCT]; matrix-core kernel: [gridDim.x][ld_loss]
+  int ld_loss;
+};
+
+// Tile shape of the matrix-core left multiply for a table with ck columns.
+struct MfmaShape {
+  int kp;            // ck rounded up to a multiple of 16
+  int kc;            // table columns staged per step
+  int lda;           // LDS row stride of the staged rows (floats)
+  int rb;            // table rows per workgroup step
+  size_t lds_bytes;
 };
 
 struct SegArgs {
@@ -153,6 +163,8 @@ size_t sort_hist_ints(int64_t r_T);
 
 hipError_t launch_lmm_rows(const LmmArgs& a, int vec, int mode, hipStream_t st, int* grid_out);
 int lmm_grid(int64_t r_out, int logL);
+MfmaShape lmm_mfma_shape(int ck, int nt);
+hipError_t launch_lmm_mfma(const LmmArgs& a, int vec, int mode, hipStream_t st, int* grid_out);
 hipError_t launch_segsum(const SegArgs& a, hipStream_t st);
 hipError_t launch_colred(const ColredArgs& a, int nblocks, hipStream_t st);
 hipError_t launch_finalize(const FinArgs& a, int c_T, int mode, hipStream_t st);

@@ -1,0 +1,243 @@
+// Left multiply on the matrix cores for operands with >= 8 columns:  P_k = D_k (M_k^T X)  and the assembly
+// out[i,:] = D_S[i,:] X_S + sum_k P_k[row_idx_k[i], :]  (paper, Sec. 2.2), with the residual of Alg. 1 as an
+// optional epilogue.
+//
+// A workgroup stages a block of whole table rows in LDS with fully coalesced float4 loads (the rows of a
+// row-major table are one contiguous span) together with the selected operand rows X_k, then every wavefront
+// multiplies 16-row tiles with MFMA 16x16x4 (float32).  Lane l = 16 q + i reads the four table values
+// D[row i][16 step + 4 q + e], e = 0..3, as one 128-bit LDS read and uses them in four MFMAs whose K slot q
+// stands for column 16 step + 4 q + e; the B operand comes from an LDS copy of X_k stored as [k / 4][n][k % 4]
+// so that the matching four values are again one 128-bit read.
+#include <algorithm>
+
+#include "ilargi_internal.h"
+
+namespace ilargi {
+
+namespace {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float sigmoidf_stable(float z) {
+  if (z >= 0.0f) return 1.0f / (1.0f + __expf(-z));
+  float e = __expf(z);
+  return e / (1.0f + e);
+}
+
+__device__ __forceinline__ float softplusf_stable(float z) {
+  return fmaxf(z, 0.0f) + log1pf(__expf(-fabsf(z)));
+}
+
+// NT: 16-column tiles of the operand slab handled by one workgroup.  MODE as in the narrow kernel.
+template <int NT, int MODE, bool VEC4>
+__global__ __launch_bounds__(kBlock) void lmm_mfma_kernel(LmmArgs a, MfmaShape sh) {
+  extern __shared__ float lds[];
+  float* As = lds;                                   // [rb][lda]
+  float* Xs = lds + (size_t)sh.rb * sh.lda;          // [kc / 4][NT * 16][4]
+  constexpr int N = NT * 16;
+  const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+  const int li = lane % 16, q = lane / 16;
+  const int n0 = a.col0 + blockIdx.y * N;
+  const int nw = min(N, a.col0 + a.ncols - n0);       // live operand columns of this slab
+  const int nchunks = (sh.kp + sh.kc - 1) / sh.kc;
+  const int64_t nblocks = (a.r_out + sh.rb - 1) / sh.rb;
+  float loss_local[NT];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) loss_local[nt] = 0.0f;
+
+  auto load_x = [&](int k0, int kw) {
+    // Xs[(k/4) * N + n][k % 4] = X[colmap[k0 + k], n0 + n]   (zero beyond the table's columns / the slab)
+    for (int e = tid; e < kw * N; e += kBlock) {
+      int k = e / N, n = e - k * N;
+      float v = 0.0f;
+      if (k0 + k < a.ck && n < nw) {
+        int t = a.colmap[k0 + k];
+        if (t >= 0) v = a.X[(int64_t)t * a.ldx + n0 + n];
+      }
+      Xs[((k >> 2) * N + n) * 4 + (k & 3)] = v;
+    }
+  };
+
+  if (nchunks == 1) load_x(0, sh.kp);
+
+  for (int64_t blk = blockIdx.x; blk < nblocks; blk += gridDim.x) {
+    const int64_t row0 = blk * sh.rb;
+    v4f acc[NT];
+    for (int c = 0; c < nchunks; ++c) {
+      const int k0 = c * sh.kc;
+      const int kw = min(sh.kc, sh.kp - k0);            // multiple of 16
+      __syncthreads();                                   // previous tile fully consumed
+      if (nchunks > 1) load_x(k0, kw);
+      if (a.D != nullptr) {
+        // rows [row0, row0 + rb) x columns [k0, k0 + kw) of D -> As, zero outside the table
+        const int cols_here = max(0, min(kw, a.ck - k0));
+        if constexpr (VEC4) {
+          const int tpr = kw / 4;                        // float4 slots per row
+          const int live4 = cols_here / 4;               // ck % 4 == 0 in this variant
+          int r = tid / tpr, g = tid - r * tpr;
+          const int dr = kBlock / tpr, dg = kBlock - dr * tpr;
+          while (r < sh.rb) {
+            float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            int64_t row = row0 + r;
+            if (g < live4 && row < a.d_rows) v = *reinterpret_cast<const float4*>(a.D + row * a.ck + k0 + 4 * g);
+            *reinterpret_cast<float4*>(As + (size_t)r * sh.lda + 4 * g) = v;
+            r += dr; g += dg;
+            if (g >= tpr) { g -= tpr; ++r; }
+          }
+        } else {
+          int r = tid / kw, g = tid - r * kw;
+          const int dr = kBlock / kw, dg = kBlock - dr * kw;
+          while (r < sh.rb) {
+            float v = 0.0f;
+            int64_t row = row0 + r;
+            if (g < cols_here && row < a.d_rows) v = a.D[row * a.ck + k0 + g];
+            As[(size_t)r * sh.lda + g] = v;
+            r += dr; g += dg;
+            if (g >= kw) { g -= kw; ++r; }
+          }
+        }
+      }
+      __syncthreads();
+      // each wavefront walks its 16-row tiles of the block
+      const int tiles = sh.rb / 16;
+      for (int mt = wave; mt < tiles; mt += kBlock / kWave) {
+        if (c == 0) {
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt) acc[nt] = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
+        }
+        if (a.D != nullptr) {
+          const float* arow = As + (size_t)(mt * 16 + li) * sh.lda + 4 * q;
+          for (int step = 0; step < kw / 16; ++step) {
+            float4 av = *reinterpret_cast<const float4*>(arow + 16 * step);
+            const float* xb = Xs + ((size_t)(4 * step + q) * N + li) * 4;
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+              float4 bv = *reinterpret_cast<const float4*>(xb + nt * 64);
+              acc[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av.x, bv.x, acc[nt], 0, 0, 0);
+              acc[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av.y, bv.y, acc[nt], 0, 0, 0);
+              acc[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av.z, bv.z, acc[nt], 0, 0, 0);
+              acc[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av.w, bv.w, acc[nt], 0, 0, 0);
+            }
+          }
+        }
+        if (c + 1 < nchunks) continue;                   // (multi-chunk blocks have one tile per wavefront)
+        // epilogue: rows 4 q + r of the tile, operand column li of each 16-column tile
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int64_t row = row0 + mt * 16 + 4 * q + r;
+          if (row >= a.r_out) continue;
+          float g[NT];
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt) g[nt] = 0.0f;
+          for (int s = 0; s < a.g.n; ++s) {
+            int64_t j;
+            if (a.g.idx[s] != nullptr) j = a.g.idx[s][row];
+            else j = (row < a.g.rows[s]) ? row : -1;
+            if (j >= 0) {
+              const float* p = a.g.P[s] + j * a.g.ldp + n0 + li;
+#pragma unroll
+              for (int nt = 0; nt < NT; ++nt)
+                if (nt * 16 + li < nw) g[nt] += p[nt * 16];
+            }
+          }
+          float yi = 0.0f;
+          if constexpr (MODE != 0) yi = a.y[row];
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt) {
+            if (nt * 16 + li < nw) {
+              float z = acc[nt][r] + g[nt];
+              float o = z;
+              if constexpr (MODE == 1) {
+                o = z - yi;
+                loss_local[nt] = fmaf(o, o, loss_local[nt]);
+              } else if constexpr (MODE == 2) {
+                o = sigmoidf_stable(z) - yi;
+                loss_local[nt] += softplusf_stable(z) - yi * z;
+              }
+              a.out[row * a.ldo + n0 + nt * 16 + li] = o;
+            }
+          }
+        }
+      }
+    }
+  }
+
+  if constexpr (MODE != 0) {
+    // per-column loss of this workgroup: the four row groups of a wavefront, then the wavefronts in order
+    __shared__ float lsum[kBlock / kWave][N];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      float s = loss_local[nt];
+      s += __shfl_xor(s, 16);
+      s += __shfl_xor(s, 32);
+      if (q == 0) lsum[wave][nt * 16 + li] = s;
+    }
+    __syncthreads();
+    if (tid < nw) {
+      float s = 0.0f;
+      for (int w = 0; w < kBlock / kWave; ++w) s += lsum[w][tid];
+      a.loss_partial[(int64_t)blockIdx.x * a.ld_loss + n0 + tid] = s;
+    }
+  }
+}
+
+}  // namespace
+
+// Shape decisions shared with the caller: K padding, K chunking, rows per block, LDS bytes.
+MfmaShape lmm_mfma_shape(int ck, int nt) {
+  MfmaShape sh;
+  sh.kp = ck > 0 ? (ck + 15) / 16 * 16 : 16;
+  sh.kc = sh.kp <= 256 ? sh.kp : 256;
+  sh.lda = sh.kc + 4;
+  const int n = nt * 16;
+  const size_t x_floats = (size_t)sh.kc * n;
+  int rm = 1;
+  if (sh.kp == sh.kc) {
+    // several 16-row tiles per wavefront when rows are short, so that a block moves tens of KiB per barrier
+    while (rm < 8 && (size_t)(2 * rm) * 64 * sh.lda * 4 + x_floats * 4 <= 48 * 1024) rm *= 2;
+  }
+  sh.rb = 64 * rm;
+  sh.lds_bytes = ((size_t)sh.rb * sh.lda + x_floats) * sizeof(float);
+  return sh;
+}
+
+hipError_t launch_lmm_mfma(const LmmArgs& a, int vec, int mode, hipStream_t st, int* grid_out) {
+  if (grid_out) *grid_out = 0;
+  if (a.r_out <= 0 || a.ncols <= 0) return hipSuccess;
+  const int nt = a.ncols <= 16 ? 1 : (a.ncols <= 32 ? 2 : 4);
+  const MfmaShape sh = lmm_mfma_shape(a.ck, nt);
+  int64_t nblocks = (a.r_out + sh.rb - 1) / sh.rb;
+  int gx = (int)std::min<int64_t>(nblocks, 1024);
+  int gy = (a.ncols + nt * 16 - 1) / (nt * 16);
+  if (grid_out) *grid_out = gx;
+  dim3 grid(gx, gy);
+  const bool vec4 = vec == 4;
+#define ILARGI_LAUNCH(NT_, MODE_)                                                                   \
+  do {                                                                                              \
+    if (vec4) {                                                                                     \
+      auto kfn = lmm_mfma_kernel<NT_, MODE_, true>;                                                 \
+      if (sh.lds_bytes > 64 * 1024)                                                                 \
+        (void)hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh.lds_bytes); \
+      kfn<<<grid, kBlock, sh.lds_bytes, st>>>(a, sh);                                               \
+    } else {                                                                                        \
+      auto kfn = lmm_mfma_kernel<NT_, MODE_, false>;                                                \
+      if (sh.lds_bytes > 64 * 1024)                                                                 \
+        (void)hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh.lds_bytes); \
+      kfn<<<grid, kBlock, sh.lds_bytes, st>>>(a, sh);                                               \
+    }                                                                                               \
+  } while (0)
+#define ILARGI_MODES(NT_)                                    \
+  do {                                                       \
+    if (mode == 0) ILARGI_LAUNCH(NT_, 0);                    \
+    else if (mode == 1) ILARGI_LAUNCH(NT_, 1);               \
+    else ILARGI_LAUNCH(NT_, 2);                              \
+  } while (0)
+  if (nt == 1) ILARGI_MODES(1);
+  else if (nt == 2) ILARGI_MODES(2);
+  else ILARGI_MODES(4);
+#undef ILARGI_MODES
+#undef ILARGI_LAUNCH
+  return hipGetLastError();
+}
+
+}  // namespace ilargi

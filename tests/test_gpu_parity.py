@@ -68,6 +68,10 @@ def get(il, name, max_cx=17):
 ALL = list(SCHEMAS)
 
 
+def _labels(sch, tg, kind):
+    return datagen.finish_labels(kind, oracle.lmm(tg, sch.extras["w_star"].reshape(-1, 1)), sch.extras["noise"])
+
+
 # ------------------------------------------------------------------ plan: inverse index (integer, exact)
 @pytest.mark.parametrize("name", ["config0", "config2_small", "config3_small", "tiny_mixed"])
 def test_inverse_index_exact(il, name):
@@ -187,6 +191,42 @@ def test_segment_sum(il, name, cx):
         assert rel(Z, want) < OP_TOL
 
 
+# ------------------------------------------------------------------ wide operands (matrix-core kernels)
+@pytest.mark.parametrize("name", ["config1_small", "config1_wide_dim", "config3_small", "odd_cols", "tiny_mixed"])
+@pytest.mark.parametrize("cx", [8, 40, 64, 256])
+def test_wide_operands(il, name, cx):
+    sch, tg, plan = get(il, name, max_cx=256)
+    rng = datagen.rng_for(5000 + cx)
+    X = rng.standard_normal((sch.c_T, cx)).astype(np.float32)
+    Y = rng.standard_normal((sch.r_T, cx)).astype(np.float32)
+    assert rel(il.ilargi_lmm(plan, dev(X)).cpu().numpy(), oracle.lmm(tg, X)) < OP_TOL
+    assert rel(il.ilargi_tmm(plan, dev(Y)).cpu().numpy(), oracle.tmm(tg, Y)) < OP_TOL
+
+
+def test_gd_wide_batch_of_models(il):
+    # the batched hyper-parameter sweep at reduced size: 64 models, log-spaced learning rates
+    sch = datagen.config4(r_S=40_007, r_R=4_001, c_R=200, models=64)
+    tg = oracle.Target(sch)
+    y = _labels(sch, tg, "linear")
+    plan = il.ilargi_plan_create(il.schema_to_device(sch), sch.r_T, sch.c_T, max_cx=64)
+    lrs = sch.extras["lr"]
+    W, L = _run_gd(il, plan, il.LINEAR, y, lrs, 20, sch.c_T)
+    W_ref, L_ref = oracle.gd(tg, "linear", y, np.zeros((sch.c_T, 64)), lrs, 20)
+    errs = [rel(W[:, j], W_ref[:, j]) for j in range(64)]
+    assert max(errs) < GD_TOL, max(errs)
+    np.testing.assert_allclose(L, L_ref, rtol=2e-4)
+
+
+def test_gd_logistic_wide(il):
+    sch, tg, plan = get(il, "config2_small", max_cx=256)
+    y = _labels(sch, tg, "logistic")
+    lrs = np.linspace(0.05, 0.5, 16)
+    W, L = _run_gd(il, plan, il.LOGISTIC, y, lrs, 10, sch.c_T)
+    W_ref, L_ref = oracle.gd(tg, "logistic", y, np.zeros((sch.c_T, 16)), lrs, 10)
+    assert max(rel(W[:, j], W_ref[:, j]) for j in range(16)) < GD_TOL
+    np.testing.assert_allclose(L, L_ref, rtol=2e-4)
+
+
 # ------------------------------------------------------------------ crossprod
 @pytest.mark.parametrize("name", ALL)
 def test_crossprod(il, name):
@@ -197,10 +237,6 @@ def test_crossprod(il, name):
 
 
 # ------------------------------------------------------------------ gradient descent (Alg. 1)
-def _labels(sch, tg, kind):
-    return datagen.finish_labels(kind, oracle.lmm(tg, sch.extras["w_star"].reshape(-1, 1)), sch.extras["noise"])
-
-
 def _run_gd(il, plan, model, y, lrs, iters, c_T):
     m = len(lrs)
     W = torch.zeros((c_T, m), device="cuda")
