@@ -137,6 +137,13 @@ ilargi_status_t ilargi_plan_inverse_index(const ilargi_plan_t* plan, int k, cons
 ilargi_status_t ilargi_plan_trace_begin(ilargi_plan_t* plan, const char* tag, int max_launches);
 ilargi_status_t ilargi_plan_trace_end(ilargi_plan_t* plan, float* ms, int capacity, int* count);
 
+/* Plain streaming kernels for calibration (what the memory system delivers, and the scale of the
+ * profiler's byte counters): kind 0 copies n_floats floats src -> dst, kind 1 only reads src (dst
+ * receives one float per workgroup, so it needs `blocks` floats), kind 2 only writes dst.  Device
+ * pointers, 16-byte aligned, n_floats a multiple of 4, `blocks` workgroups of 256 threads. */
+ilargi_status_t ilargi_stream_probe(int kind, float* dst, const float* src, int64_t n_floats, int blocks,
+                                    void* stream);
+
 /* Message for the most recent failure on this thread ("" if none).  Static storage. */
 const char* ilargi_last_error(void);
 

@@ -38,7 +38,8 @@ STATUS_NAMES = ["OK", "ERR_NULL", "ERR_SHAPE", "ERR_COLMAP", "ERR_INDEX_RANGE", 
 EXPORTED = [
     "ilargi_plan_workspace_bytes", "ilargi_plan_create", "ilargi_plan_destroy", "ilargi_lmm", "ilargi_tmm",
     "ilargi_crossprod", "ilargi_materialize", "ilargi_gd_step", "ilargi_segment_sum",
-    "ilargi_plan_inverse_index", "ilargi_plan_trace_begin", "ilargi_plan_trace_end", "ilargi_last_error",
+    "ilargi_plan_inverse_index", "ilargi_plan_trace_begin", "ilargi_plan_trace_end", "ilargi_stream_probe",
+    "ilargi_last_error",
     "ilargi_version",
 ]
 
@@ -63,6 +64,7 @@ lib.ilargi_segment_sum.argtypes = [_vp, _int, _vp, _i64, _vp, _vp]
 lib.ilargi_plan_inverse_index.argtypes = [_vp, _int, ctypes.POINTER(_vp), ctypes.POINTER(_vp), ctypes.POINTER(_i64)]
 lib.ilargi_plan_trace_begin.argtypes = [_vp, ctypes.c_char_p, _int]
 lib.ilargi_plan_trace_end.argtypes = [_vp, ctypes.POINTER(ctypes.c_float), _int, ctypes.POINTER(_int)]
+lib.ilargi_stream_probe.argtypes = [_int, _vp, _vp, _i64, _int, _vp]
 for _name in EXPORTED[:-2]:
     getattr(lib, _name).restype = _int
 lib.ilargi_last_error.restype = ctypes.c_char_p
@@ -289,6 +291,11 @@ def ilargi_plan_trace_end(plan: Plan, capacity: int):
     cnt = _int(0)
     _check(lib.ilargi_plan_trace_end(plan.handle, buf, capacity, ctypes.byref(cnt)), "ilargi_plan_trace_end")
     return np.array(buf[:min(cnt.value, capacity)], dtype=np.float32)
+
+
+def ilargi_stream_probe(kind: int, dst, src, n_floats: int, blocks: int = 4096, stream=None) -> None:
+    _check(lib.ilargi_stream_probe(kind, dst.data_ptr(), src.data_ptr() if src is not None else None, n_floats,
+                                   blocks, _stream_ptr(stream)), "ilargi_stream_probe")
 
 
 def schema_to_device(schema, device="cuda:0"):

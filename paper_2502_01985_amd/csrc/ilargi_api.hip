@@ -250,7 +250,9 @@ int pass_width(const ilargi_plan* pl) {
 
 // out (or the residual E) for operand columns [col0, col0 + ncols):  per-source products, then the assembly.
 ilargi_status_t lmm_pass(ilargi_plan* pl, const float* X, int ldx, int col0, int ncols, float* out, int ldo,
-                         int mode, const float* y, int* loss_grid, bool wide, hipStream_t st) {
+                         int mode, const float* y, int* loss_grid, bool wide, hipStream_t st,
+                         bool* fused_gradient = nullptr) {
+  if (fused_gradient) *fused_gradient = false;
   GatherArgs g;
   memset(&g, 0, sizeof(g));
   g.ldp = ldx;
@@ -288,6 +290,12 @@ ilargi_status_t lmm_pass(ilargi_plan* pl, const float* X, int ldx, int col0, int
   a.y = y;
   a.loss_partial = pl->at<float>(pl->lay.o_loss);
   a.ld_loss = ldx;
+  if (!wide && mode != 0 && fused_gradient != nullptr && pl->fused >= 0 &&
+      lmm_can_fuse_gradient(a.ck, vec, a.logL)) {
+    // the fused source's share of the gradient comes out of the same pass over its rows
+    a.grad_partial = pl->at<float>(pl->src[pl->fused].o_partial);
+    *fused_gradient = true;
+  }
   {
     TraceScope ts(pl, "lmm_assemble", -1, st);
     if (wide) HIP_TRY(launch_lmm_mfma(a, vec, mode, st, loss_grid));
@@ -299,12 +307,21 @@ ilargi_status_t lmm_pass(ilargi_plan* pl, const float* X, int ldx, int col0, int
 // T^T Y for operand columns [col0, col0 + ncols); mode 1 turns the finalize step into the update of Alg. 1.
 ilargi_status_t tmm_pass(ilargi_plan* pl, const float* Y, int ldy, int col0, int ncols, float* out, int ldo,
                          int mode, const float* lr, float* loss, int n_loss_partial, float loss_scale,
-                         hipStream_t st) {
+                         hipStream_t st, int done_k = -1, int done_blocks = 0) {
   FinArgs f;
   memset(&f, 0, sizeof(f));
   for (int k = 0; k < pl->n; ++k) {
     SourcePlan& p = pl->src[k];
     if (p.empty) continue;
+    if (k == done_k) {
+      // partials of this source were produced by the residual pass
+      f.s[f.n].tcol2src = pl->at<int32_t>(p.o_tcol);
+      f.s[f.n].partial = pl->at<float>(p.o_partial);
+      f.s[f.n].nblocks = done_blocks;
+      f.s[f.n].ck = (int)p.cols;
+      ++f.n;
+      continue;
+    }
     ColredArgs c;
     memset(&c, 0, sizeof(c));
     c.D = p.D; c.rows = p.rows; c.ck = (int)p.cols; c.vec = p.vec;
@@ -589,6 +606,14 @@ ilargi_status_t ilargi_plan_destroy(ilargi_plan_t* plan) {
   return ILARGI_OK;
 }
 
+ilargi_status_t ilargi_stream_probe(int kind, float* dst, const float* src, int64_t n_floats, int blocks, void* stream) {
+  if (kind < 0 || kind > 2) return fail(ILARGI_ERR_UNSUPPORTED, "stream_probe: kind %d", kind);
+  if (dst == nullptr || (kind != 2 && src == nullptr)) return fail(ILARGI_ERR_NULL, "stream_probe: NULL buffer");
+  if (n_floats < 0 || n_floats % 4 != 0 || blocks < 1 || blocks > 65536) return fail(ILARGI_ERR_SHAPE, "stream_probe: bad size");
+  HIP_TRY(launch_probe(kind, dst, src, n_floats, blocks, static_cast<hipStream_t>(stream)));
+  return ILARGI_OK;
+}
+
 ilargi_status_t ilargi_plan_trace_begin(ilargi_plan_t* plan, const char* tag, int max_launches) {
   if (plan == nullptr || tag == nullptr) return fail(ILARGI_ERR_NULL, "trace_begin: NULL argument");
   if (max_launches < 1 || max_launches > (1 << 20)) return fail(ILARGI_ERR_SHAPE, "trace_begin: max_launches = %d", max_launches);
@@ -683,9 +708,12 @@ ilargi_status_t ilargi_gd_step(ilargi_plan_t* plan, ilargi_model_t model, float*
   for (int64_t col0 = 0; col0 < m; col0 += w) {
     int ncols = (int)std::min<int64_t>(w, m - col0);
     int loss_grid = 0;
-    rc = lmm_pass(plan, W, (int)m, (int)col0, ncols, E, (int)m, model == ILARGI_LINEAR ? 1 : 2, y, &loss_grid, false, st);
+    bool fusedg = false;
+    rc = lmm_pass(plan, W, (int)m, (int)col0, ncols, E, (int)m, model == ILARGI_LINEAR ? 1 : 2, y, &loss_grid, false, st,
+                  &fusedg);
     if (rc != ILARGI_OK) return rc;
-    rc = tmm_pass(plan, E, (int)m, (int)col0, ncols, W, (int)m, 1, lr, loss, loss_grid, loss_scale, st);
+    rc = tmm_pass(plan, E, (int)m, (int)col0, ncols, W, (int)m, 1, lr, loss, loss_grid, loss_scale, st,
+                  fusedg ? plan->fused : -1, loss_grid);
     if (rc != ILARGI_OK) return rc;
   }
   return ILARGI_OK;

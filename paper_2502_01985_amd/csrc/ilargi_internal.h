@@ -45,6 +45,7 @@ struct LmmArgs {
   const float* y;         // labels, r_out
   float* loss_partial;    // narrow kernel: [gridDim.x][kNarrowCT]; matrix-core kernel: [gridDim.x][ld_loss]
   int ld_loss;
+  float* grad_partial;    // narrow kernel, optional: [gridDim.x][ck][kNarrowCT] partials of D^T e
 };
 
 // Tile shape of the matrix-core left multiply for a table with ck columns.
@@ -162,7 +163,8 @@ hipError_t launch_sort_by_source_row(const int32_t* idx, int64_t r_T, int64_t r_
 size_t sort_hist_ints(int64_t r_T);
 
 hipError_t launch_lmm_rows(const LmmArgs& a, int vec, int mode, hipStream_t st, int* grid_out);
-int lmm_grid(int64_t r_out, int logL);
+int lmm_grid(int64_t r_out, int logL, bool fuseg);
+bool lmm_can_fuse_gradient(int ck, int vec, int logL);
 MfmaShape lmm_mfma_shape(int ck, int nt);
 hipError_t launch_lmm_mfma(const LmmArgs& a, int vec, int mode, hipStream_t st, int* grid_out);
 hipError_t launch_segsum(const SegArgs& a, hipStream_t st);
@@ -176,6 +178,7 @@ hipError_t launch_gram_assemble(const GramAsmPair* pairs_dev, int npairs, const 
 hipError_t launch_tred(const TredArgs& a, int nchunks, hipStream_t st);
 hipError_t launch_tred_reduce(const float* partial, int nchunks, int64_t elems, float* block, hipStream_t st);
 hipError_t launch_colasm(const ColAsmArgs& a, int mode, hipStream_t st);
+hipError_t launch_probe(int kind, float* dst, const float* src, int64_t n_floats, int blocks, hipStream_t st);
 hipError_t launch_fill_zero(float* p, int64_t n, hipStream_t st);
 
 inline int ilog2_ceil(int64_t v) { int l = 0; while ((1ll << l) < v) ++l; return l; }

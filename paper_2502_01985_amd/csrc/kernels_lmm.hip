@@ -1,23 +1,23 @@
-// Left multiply  T X = sum_k I_k (D_k (M_k^T X))  (paper, Sec. 2.2) for narrow operands.
+// Left multiply  T X = sum_k I_k (D_k (M_k^T X))  (paper, Sec. 2.2) for narrow operands (<= 4 columns per pass).
 //
 // One kernel serves both steps of the rewrite:
 //   * the per-source product  P_k = D_k X_k  with  X_k = M_k^T X  (row select through col_map, staged in LDS);
 //   * the assembly  out[i,:] = D_S[i,:] X_S + sum_k P_k[row_idx_k[i], :]  where the product of the source that
 //     is the identity on the target rows is fused into the pass that gathers the other sources' rows.
-// In the gradient-descent modes the assembled value is turned into the residual of Alg. 1 before it is stored.
+// In the gradient-descent modes the assembled value becomes the residual of Alg. 1 before it is stored, and the
+// identity source's share of the gradient,  D_S^T e, is accumulated from the table values still in registers.
 //
-// Thread mapping: a row of D is read by L = 2^logL adjacent lanes, VEC floats per lane per step, so that a
-// wavefront always loads one contiguous span of 64/L rows.  Lanes of a row combine with an xor butterfly.
+// A workgroup handles up to 256 consecutive target rows per step, in two thread mappings that meet in LDS:
+//   dot mapping     a row of D is read by L = 2^logL adjacent lanes (float4 each), so a wavefront load is one
+//                   contiguous span of 64/L rows; the lanes of a row combine with an xor butterfly;
+//   row mapping     thread t owns row t of the step: it loads row_idx (coalesced), gathers the P_k rows, adds
+//                   the dot product from LDS, applies the epilogue and stores (coalesced).
+// The row indices of the next step are prefetched while the current step computes.
 #include "ilargi_internal.h"
 
 namespace ilargi {
 
 namespace {
-
-template <int VEC> struct Vec;
-template <> struct Vec<1> { using T = float; };
-template <> struct Vec<2> { using T = float2; };
-template <> struct Vec<4> { using T = float4; };
 
 template <int VEC> __device__ __forceinline__ void load_vec(const float* p, float (&v)[VEC]) {
   if constexpr (VEC == 4) {
@@ -41,12 +41,20 @@ __device__ __forceinline__ float softplusf_stable(float z) {
   return fmaxf(z, 0.0f) + log1pf(__expf(-fabsf(z)));
 }
 
-constexpr int kUnroll = 4;
+constexpr int kUnroll = 8;     // rows per lane group and step
+constexpr int kPrefetch = 3;   // gathered sources whose row indices are prefetched one step ahead
+
+__device__ __forceinline__ int64_t gather_row(const GatherArgs& g, int s, int64_t i) {
+  if (g.idx[s] != nullptr) return g.idx[s][i];
+  return i < g.rows[s] ? i : -1;
+}
 
 // MODE 0: store the product.  MODE 1: linear residual z - y.  MODE 2: logistic residual sigmoid(z) - y.
-template <int VEC, int CT, int MODE>
+// FUSEG: also accumulate this workgroup's partial of D^T e (needs every row to fit one load per lane).
+template <int VEC, int CT, int MODE, bool FUSEG>
 __global__ __launch_bounds__(kBlock) void lmm_rows_kernel(LmmArgs a) {
-  extern __shared__ float Xs[];  // [ck][CT]
+  extern __shared__ float Xs[];                 // [ck][CT]
+  __shared__ float zbuf[2][kBlock * CT];        // dot products (then residuals) of the step's rows, ping-pong
   const int tid = threadIdx.x;
   for (int e = tid; e < a.ck * CT; e += kBlock) {
     int j = e / CT, n = e - j * CT;
@@ -58,32 +66,87 @@ __global__ __launch_bounds__(kBlock) void lmm_rows_kernel(LmmArgs a) {
   const int L = 1 << a.logL;
   const int lig = tid & (L - 1);
   const int gid = tid >> a.logL;
-  const int gpb = kBlock >> a.logL;           // row groups per workgroup
+  const int gpb = kBlock >> a.logL;                         // row groups per workgroup
+  const int U = min(kUnroll, kBlock / gpb);                 // rows per group and step
+  const int rpi = gpb * U;                                  // rows per step (<= 256)
   const int nvec = a.ck / VEC;
-  const int64_t rows_per_iter = (int64_t)gpb * kUnroll;
+  const int64_t stride = (int64_t)gridDim.x * rpi;
   float loss_local[CT];
+  float gacc[VEC][CT];
 #pragma unroll
   for (int n = 0; n < CT; ++n) loss_local[n] = 0.0f;
+#pragma unroll
+  for (int e = 0; e < VEC; ++e)
+#pragma unroll
+    for (int n = 0; n < CT; ++n) gacc[e][n] = 0.0f;
 
-  for (int64_t base = (int64_t)blockIdx.x * rows_per_iter; base < a.r_out;
-       base += (int64_t)gridDim.x * rows_per_iter) {
+  int64_t jn[kPrefetch];
+  {
+    int64_t i = (int64_t)blockIdx.x * rpi + tid;
+#pragma unroll
+    for (int s = 0; s < kPrefetch; ++s) jn[s] = (s < a.g.n && tid < rpi && i < a.r_out) ? gather_row(a.g, s, i) : -1;
+  }
+
+  int it = 0;
+  for (int64_t base = (int64_t)blockIdx.x * rpi; base < a.r_out; base += stride, ++it) {
+    float* zb = zbuf[it & 1];
+    // ---- dot mapping: issue the table loads first
+    float v[kUnroll][VEC];
     float acc[kUnroll][CT];
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u)
+    for (int u = 0; u < kUnroll; ++u) {
 #pragma unroll
       for (int n = 0; n < CT; ++n) acc[u][n] = 0.0f;
-
-    if (a.D != nullptr) {
-      if (nvec <= L) {
-        // one load per lane and row: issue all of them before the arithmetic
-        float v[kUnroll][VEC];
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-          int64_t i = base + (int64_t)u * gpb + gid;
+      for (int e = 0; e < VEC; ++e) v[u][e] = 0.0f;
+    }
+    const bool single = nvec <= L;
+    if (a.D != nullptr && single) {
 #pragma unroll
-          for (int e = 0; e < VEC; ++e) v[u][e] = 0.0f;
-          if (i < a.d_rows && lig < nvec) load_vec<VEC>(a.D + i * a.ck + lig * VEC, v[u]);
+      for (int u = 0; u < kUnroll; ++u) {
+        int64_t i = base + (int64_t)u * gpb + gid;
+        if (u < U && i < a.d_rows && lig < nvec) load_vec<VEC>(a.D + i * a.ck + lig * VEC, v[u]);
+      }
+    }
+    // ---- row mapping: gathers of this step (indices were prefetched), then the next step's indices
+    const int64_t irow = base + tid;
+    const bool rowlive = tid < rpi && irow < a.r_out;
+    float gsum[CT];
+#pragma unroll
+    for (int n = 0; n < CT; ++n) gsum[n] = 0.0f;
+    if (rowlive) {
+#pragma unroll
+      for (int s = 0; s < kPrefetch; ++s) {
+        if (s < a.g.n && jn[s] >= 0) {
+          const float* p = a.g.P[s] + jn[s] * a.g.ldp + a.col0;
+#pragma unroll
+          for (int n = 0; n < CT; ++n)
+            if (n < a.ncols) gsum[n] += p[n];
         }
+      }
+      for (int s = kPrefetch; s < a.g.n; ++s) {
+        int64_t j = gather_row(a.g, s, irow);
+        if (j >= 0) {
+          const float* p = a.g.P[s] + j * a.g.ldp + a.col0;
+#pragma unroll
+          for (int n = 0; n < CT; ++n)
+            if (n < a.ncols) gsum[n] += p[n];
+        }
+      }
+    }
+    float yi = 0.0f;
+    if constexpr (MODE != 0) {
+      if (rowlive) yi = a.y[irow];
+    }
+    {
+      int64_t inext = irow + stride;
+#pragma unroll
+      for (int s = 0; s < kPrefetch; ++s)
+        jn[s] = (s < a.g.n && tid < rpi && inext < a.r_out) ? gather_row(a.g, s, inext) : -1;
+    }
+    // ---- dot products
+    if (a.D != nullptr) {
+      if (single) {
         if (lig < nvec) {
 #pragma unroll
           for (int e = 0; e < VEC; ++e) {
@@ -98,13 +161,12 @@ __global__ __launch_bounds__(kBlock) void lmm_rows_kernel(LmmArgs a) {
         }
       } else {
         for (int t = lig; t < nvec; t += L) {
-          float v[kUnroll][VEC];
 #pragma unroll
           for (int u = 0; u < kUnroll; ++u) {
             int64_t i = base + (int64_t)u * gpb + gid;
 #pragma unroll
             for (int e = 0; e < VEC; ++e) v[u][e] = 0.0f;
-            if (i < a.d_rows) load_vec<VEC>(a.D + i * a.ck + t * VEC, v[u]);
+            if (u < U && i < a.d_rows) load_vec<VEC>(a.D + i * a.ck + t * VEC, v[u]);
           }
 #pragma unroll
           for (int e = 0; e < VEC; ++e) {
@@ -118,59 +180,62 @@ __global__ __launch_bounds__(kBlock) void lmm_rows_kernel(LmmArgs a) {
           }
         }
       }
-    }
-
-    // gathered rows of the other sources' products: lane s of the row group fetches source s
-    if (a.g.n > 0) {
+      for (int m = L >> 1; m >= 1; m >>= 1) {
 #pragma unroll
-      for (int u = 0; u < kUnroll; ++u) {
-        int64_t i = base + (int64_t)u * gpb + gid;
-        if (i < a.r_out) {
-          for (int s = lig; s < a.g.n; s += L) {
-            int64_t j;
-            if (a.g.idx[s] != nullptr) j = a.g.idx[s][i];
-            else j = (i < a.g.rows[s]) ? i : -1;
-            if (j >= 0) {
-              const float* p = a.g.P[s] + j * a.g.ldp + a.col0;
+        for (int u = 0; u < kUnroll; ++u)
 #pragma unroll
-              for (int n = 0; n < CT; ++n)
-                if (n < a.ncols) acc[u][n] += p[n];
-            }
-          }
-        }
+          for (int n = 0; n < CT; ++n) acc[u][n] += __shfl_xor(acc[u][n], m);
       }
     }
-
-    for (int m = L >> 1; m >= 1; m >>= 1) {
-#pragma unroll
-      for (int u = 0; u < kUnroll; ++u)
-#pragma unroll
-        for (int n = 0; n < CT; ++n) acc[u][n] += __shfl_xor(acc[u][n], m);
-    }
-
     if (lig == 0) {
 #pragma unroll
-      for (int u = 0; u < kUnroll; ++u) {
-        int64_t i = base + (int64_t)u * gpb + gid;
-        if (i < a.r_out) {
-          float yi = 0.0f;
-          if constexpr (MODE != 0) yi = a.y[i];
+      for (int u = 0; u < kUnroll; ++u)
+        if (u < U) {
 #pragma unroll
-          for (int n = 0; n < CT; ++n) {
-            if (n < a.ncols) {
-              float z = acc[u][n];
-              float r = z;
-              if constexpr (MODE == 1) {
-                r = z - yi;
-                loss_local[n] = fmaf(r, r, loss_local[n]);
-              } else if constexpr (MODE == 2) {
-                r = sigmoidf_stable(z) - yi;
-                loss_local[n] += softplusf_stable(z) - yi * z;
-              }
-              a.out[i * a.ldo + a.col0 + n] = r;
+          for (int n = 0; n < CT; ++n) zb[(u * gpb + gid) * CT + n] = acc[u][n];
+        }
+    }
+    __syncthreads();
+    // ---- row mapping: epilogue and store
+    if (rowlive) {
+#pragma unroll
+      for (int n = 0; n < CT; ++n) {
+        if (n < a.ncols) {
+          float z = zb[tid * CT + n] + gsum[n];
+          float r = z;
+          if constexpr (MODE == 1) {
+            r = z - yi;
+            loss_local[n] = fmaf(r, r, loss_local[n]);
+          } else if constexpr (MODE == 2) {
+            r = sigmoidf_stable(z) - yi;
+            loss_local[n] += softplusf_stable(z) - yi * z;
+          }
+          a.out[irow * a.ldo + a.col0 + n] = r;
+          if constexpr (FUSEG) zb[tid * CT + n] = r;
+        } else if constexpr (FUSEG) {
+          zb[tid * CT + n] = 0.0f;
+        }
+      }
+    } else if constexpr (FUSEG) {
+      if (tid < rpi) {
+#pragma unroll
+        for (int n = 0; n < CT; ++n) zb[tid * CT + n] = 0.0f;
+      }
+    }
+    if constexpr (FUSEG) {
+      __syncthreads();
+      // gradient share of the fused source: table values are still in registers (single-load rows only)
+      if (lig < nvec) {
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u)
+          if (u < U) {
+#pragma unroll
+            for (int n = 0; n < CT; ++n) {
+              float r = zb[(u * gpb + gid) * CT + n];
+#pragma unroll
+              for (int e = 0; e < VEC; ++e) gacc[e][n] = fmaf(v[u][e], r, gacc[e][n]);
             }
           }
-        }
       }
     }
   }
@@ -191,47 +256,80 @@ __global__ __launch_bounds__(kBlock) void lmm_rows_kernel(LmmArgs a) {
       a.loss_partial[(int64_t)blockIdx.x * kNarrowCT + tid] = s;
     }
   }
+  if constexpr (FUSEG) {
+    // column j of the table, operand column n: add the lane groups of the workgroup in a fixed order
+    __shared__ float red[VEC * CT][kBlock];
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < VEC; ++e)
+#pragma unroll
+      for (int n = 0; n < CT; ++n) red[e * CT + n][tid] = gacc[e][n];
+    __syncthreads();
+    for (int o = tid; o < a.ck * CT; o += kBlock) {
+      int j = o / CT, n = o - j * CT;
+      int jl = j / VEC, e = j - jl * VEC;
+      float s = 0.0f;
+      for (int g = 0; g < gpb; ++g) s += red[e * CT + n][g * L + jl];
+      a.grad_partial[((int64_t)blockIdx.x * a.ck + j) * kNarrowCT + n] = s;
+    }
+  }
 }
 
 template <int VEC, int CT>
-hipError_t launch_mode(const LmmArgs& a, int mode, int grid, size_t lds, hipStream_t st) {
-  switch (mode) {
-    case 0: lmm_rows_kernel<VEC, CT, 0><<<grid, kBlock, lds, st>>>(a); break;
-    case 1: lmm_rows_kernel<VEC, CT, 1><<<grid, kBlock, lds, st>>>(a); break;
-    default: lmm_rows_kernel<VEC, CT, 2><<<grid, kBlock, lds, st>>>(a); break;
+hipError_t launch_mode(const LmmArgs& a, int mode, bool fuseg, int grid, size_t lds, hipStream_t st) {
+  if (fuseg) {
+    if (mode == 1) lmm_rows_kernel<VEC, CT, 1, true><<<grid, kBlock, lds, st>>>(a);
+    else lmm_rows_kernel<VEC, CT, 2, true><<<grid, kBlock, lds, st>>>(a);
+  } else {
+    switch (mode) {
+      case 0: lmm_rows_kernel<VEC, CT, 0, false><<<grid, kBlock, lds, st>>>(a); break;
+      case 1: lmm_rows_kernel<VEC, CT, 1, false><<<grid, kBlock, lds, st>>>(a); break;
+      default: lmm_rows_kernel<VEC, CT, 2, false><<<grid, kBlock, lds, st>>>(a); break;
+    }
   }
   return hipGetLastError();
 }
 
 template <int VEC>
-hipError_t launch_ct(const LmmArgs& a, int mode, int grid, hipStream_t st) {
+hipError_t launch_ct(const LmmArgs& a, int mode, bool fuseg, int grid, hipStream_t st) {
   int ct = a.ncols <= 1 ? 1 : (a.ncols <= 2 ? 2 : 4);
   size_t lds = (size_t)a.ck * ct * sizeof(float);
   switch (ct) {
-    case 1: return launch_mode<VEC, 1>(a, mode, grid, lds, st);
-    case 2: return launch_mode<VEC, 2>(a, mode, grid, lds, st);
-    default: return launch_mode<VEC, 4>(a, mode, grid, lds, st);
+    case 1: return launch_mode<VEC, 1>(a, mode, fuseg, grid, lds, st);
+    case 2: return launch_mode<VEC, 2>(a, mode, fuseg, grid, lds, st);
+    default: return launch_mode<VEC, 4>(a, mode, fuseg, grid, lds, st);
   }
 }
 
 }  // namespace
 
-int lmm_grid(int64_t r_out, int logL) {
-  int64_t rows_per_iter = (int64_t)(kBlock >> logL) * kUnroll;
-  int64_t g = (r_out + rows_per_iter - 1) / rows_per_iter;
+int lmm_rows_per_step(int logL) {
+  int gpb = kBlock >> logL;
+  int u = kBlock / gpb < kUnroll ? kBlock / gpb : kUnroll;
+  return gpb * u;
+}
+
+int lmm_grid(int64_t r_out, int logL, bool fuseg) {
+  int64_t rpi = lmm_rows_per_step(logL);
+  int64_t g = (r_out + rpi - 1) / rpi;
+  int64_t cap = fuseg ? kColredBlocks : 2048;
   if (g < 1) g = 1;
-  if (g > 2048) g = 2048;
+  if (g > cap) g = cap;
   return (int)g;
 }
 
+// True when the fused gradient variant can serve a table with these columns.
+bool lmm_can_fuse_gradient(int ck, int vec, int logL) { return ck > 0 && ck / vec <= (1 << logL); }
+
 hipError_t launch_lmm_rows(const LmmArgs& a, int vec, int mode, hipStream_t st, int* grid_out) {
-  int grid = lmm_grid(a.r_out, a.logL);
+  const bool fuseg = a.grad_partial != nullptr && mode != 0;
+  int grid = lmm_grid(a.r_out, a.logL, fuseg);
   if (grid_out) *grid_out = grid;
   if (a.r_out <= 0) return hipSuccess;
   switch (vec) {
-    case 4: return launch_ct<4>(a, mode, grid, st);
-    case 2: return launch_ct<2>(a, mode, grid, st);
-    default: return launch_ct<1>(a, mode, grid, st);
+    case 4: return launch_ct<4>(a, mode, fuseg, grid, st);
+    case 2: return launch_ct<2>(a, mode, fuseg, grid, st);
+    default: return launch_ct<1>(a, mode, fuseg, grid, st);
   }
 }
 

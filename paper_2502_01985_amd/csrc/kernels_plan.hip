@@ -203,3 +203,40 @@ hipError_t launch_fill_zero(float* p, int64_t n, hipStream_t st) {
 }
 
 }  // namespace ilargi
+
+// Plain streaming kernels used to calibrate what the memory system delivers (benchmarks and counter
+// scaling): copy, read-only (sum into one value per workgroup) and write-only.
+namespace ilargi {
+
+__global__ __launch_bounds__(kBlock) void probe_copy_kernel(float4* __restrict__ dst, const float4* __restrict__ src,
+                                                            int64_t n4) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += (int64_t)gridDim.x * blockDim.x)
+    dst[i] = src[i];
+}
+
+__global__ __launch_bounds__(kBlock) void probe_read_kernel(const float4* __restrict__ src, int64_t n4,
+                                                            float* __restrict__ sink) {
+  float acc = 0.0f;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += (int64_t)gridDim.x * blockDim.x) {
+    float4 v = src[i];
+    acc += (v.x + v.y) + (v.z + v.w);
+  }
+  for (int m = kWave / 2; m >= 1; m >>= 1) acc += __shfl_xor(acc, m);
+  if (threadIdx.x == 0) sink[blockIdx.x] = acc;
+}
+
+__global__ __launch_bounds__(kBlock) void probe_write_kernel(float4* __restrict__ dst, int64_t n4) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += (int64_t)gridDim.x * blockDim.x)
+    dst[i] = make_float4(1.0f, 2.0f, 3.0f, 4.0f);
+}
+
+hipError_t launch_probe(int kind, float* dst, const float* src, int64_t n_floats, int blocks, hipStream_t st) {
+  int64_t n4 = n_floats / 4;
+  if (n4 <= 0) return hipSuccess;
+  if (kind == 0) probe_copy_kernel<<<blocks, kBlock, 0, st>>>((float4*)dst, (const float4*)src, n4);
+  else if (kind == 1) probe_read_kernel<<<blocks, kBlock, 0, st>>>((const float4*)src, n4, dst);
+  else probe_write_kernel<<<blocks, kBlock, 0, st>>>((float4*)dst, n4);
+  return hipGetLastError();
+}
+
+}  // namespace ilargi

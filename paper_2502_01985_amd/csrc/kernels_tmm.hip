@@ -203,37 +203,72 @@ __global__ __launch_bounds__(kBlock) void colred_kernel(ColredArgs a) {
   }
 }
 
-// One workgroup per target column: sum each contributing source's partials (lanes stride over the row
-// chunks, xor butterfly), add the sources in order.  MODE 0 stores, MODE 1 applies  W -= lr * G / r_T  and
-// reduces the loss partials (Alg. 1).
+// Sum of float4 records rec[b * stride4] over b < count by a whole workgroup: threads stride the records
+// (four independent loads in flight each), xor butterfly inside the wavefronts, wavefronts added in order.
+__device__ __forceinline__ float4 block_sum4(const float4* __restrict__ rec, int64_t stride4, int count,
+                                             float (*scratch)[4]) {
+  const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+  float4 s0 = make_float4(0.f, 0.f, 0.f, 0.f), s1 = s0, s2 = s0, s3 = s0;
+  int b = tid;
+  for (; b + 3 * kBlock < count; b += 4 * kBlock) {
+    float4 v0 = rec[(int64_t)b * stride4], v1 = rec[(int64_t)(b + kBlock) * stride4];
+    float4 v2 = rec[(int64_t)(b + 2 * kBlock) * stride4], v3 = rec[(int64_t)(b + 3 * kBlock) * stride4];
+    s0.x += v0.x; s0.y += v0.y; s0.z += v0.z; s0.w += v0.w;
+    s1.x += v1.x; s1.y += v1.y; s1.z += v1.z; s1.w += v1.w;
+    s2.x += v2.x; s2.y += v2.y; s2.z += v2.z; s2.w += v2.w;
+    s3.x += v3.x; s3.y += v3.y; s3.z += v3.z; s3.w += v3.w;
+  }
+  for (; b < count; b += kBlock) {
+    float4 v0 = rec[(int64_t)b * stride4];
+    s0.x += v0.x; s0.y += v0.y; s0.z += v0.z; s0.w += v0.w;
+  }
+  float r[4] = {(s0.x + s1.x) + (s2.x + s3.x), (s0.y + s1.y) + (s2.y + s3.y), (s0.z + s1.z) + (s2.z + s3.z),
+                (s0.w + s1.w) + (s2.w + s3.w)};
+#pragma unroll
+  for (int n = 0; n < 4; ++n)
+    for (int m = kWave / 2; m >= 1; m >>= 1) r[n] += __shfl_xor(r[n], m);
+  __syncthreads();   // scratch may still be read from a previous call
+  if (lane == 0) {
+#pragma unroll
+    for (int n = 0; n < 4; ++n) scratch[wave][n] = r[n];
+  }
+  __syncthreads();
+  float4 out;
+  out.x = ((scratch[0][0] + scratch[1][0]) + scratch[2][0]) + scratch[3][0];
+  out.y = ((scratch[0][1] + scratch[1][1]) + scratch[2][1]) + scratch[3][1];
+  out.z = ((scratch[0][2] + scratch[1][2]) + scratch[2][2]) + scratch[3][2];
+  out.w = ((scratch[0][3] + scratch[1][3]) + scratch[2][3]) + scratch[3][3];
+  return out;
+}
+
+// One workgroup per target column: sum each contributing source's per-workgroup partials (records of
+// kNarrowCT floats), add the sources in order.  MODE 0 stores, MODE 1 applies  W -= lr * G / r_T  and, in
+// one extra workgroup, reduces the loss partials (Alg. 1).
 template <int MODE>
-__global__ __launch_bounds__(kBlock) void finalize_kernel(FinArgs a) {
+__global__ __launch_bounds__(kBlock) void finalize_kernel(FinArgs a, int c_T) {
+  static_assert(kNarrowCT == 4, "records are float4");
+  __shared__ float scratch[kBlock / kWave][4];
   const int t = blockIdx.x;
-  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
-  for (int n = wave; n < a.ncols; n += kBlock / kWave) {
-    float acc = 0.0f;
-    for (int k = 0; k < a.n; ++k) {
-      int j = a.s[k].tcol2src[t];
-      if (j < 0) continue;
-      float s = 0.0f;
-      for (int b = lane; b < a.s[k].nblocks; b += kWave)
-        s += a.s[k].partial[((int64_t)b * a.s[k].ck + j) * kNarrowCT + n];
-      for (int m = kWave / 2; m >= 1; m >>= 1) s += __shfl_xor(s, m);
-      acc += s;
-    }
-    if (lane == 0) {
-      float* o = a.out + (int64_t)t * a.ldo + a.col0 + n;
-      if constexpr (MODE == 0) *o = acc;
-      else *o = *o - a.lr[a.col0 + n] * (acc * a.inv_rT);
-    }
+  if (t == c_T) {
     if constexpr (MODE == 1) {
-      if (t == 0 && a.loss != nullptr) {
-        float s = 0.0f;
-        for (int b = lane; b < a.n_loss_partial; b += kWave) s += a.loss_partial[(int64_t)b * kNarrowCT + n];
-        for (int m = kWave / 2; m >= 1; m >>= 1) s += __shfl_xor(s, m);
-        if (lane == 0) a.loss[a.col0 + n] = s * a.loss_scale;
-      }
+      float4 s = block_sum4(reinterpret_cast<const float4*>(a.loss_partial), 1, a.n_loss_partial, scratch);
+      float sv[4] = {s.x, s.y, s.z, s.w};
+      if (threadIdx.x < a.ncols) a.loss[a.col0 + threadIdx.x] = sv[threadIdx.x] * a.loss_scale;
     }
+    return;
+  }
+  float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+  for (int k = 0; k < a.n; ++k) {
+    int j = a.s[k].tcol2src[t];
+    if (j < 0) continue;
+    float4 s = block_sum4(reinterpret_cast<const float4*>(a.s[k].partial) + j, a.s[k].ck, a.s[k].nblocks, scratch);
+    acc[0] += s.x; acc[1] += s.y; acc[2] += s.z; acc[3] += s.w;
+  }
+  if (threadIdx.x < a.ncols) {
+    const int n = threadIdx.x;
+    float* o = a.out + (int64_t)t * a.ldo + a.col0 + n;
+    if constexpr (MODE == 0) *o = acc[n];
+    else *o = *o - a.lr[a.col0 + n] * (acc[n] * a.inv_rT);
   }
 }
 
@@ -285,8 +320,8 @@ hipError_t launch_colred(const ColredArgs& a, int nblocks, hipStream_t st) {
 
 hipError_t launch_finalize(const FinArgs& a, int c_T, int mode, hipStream_t st) {
   if (c_T <= 0 || a.ncols <= 0) return hipSuccess;
-  if (mode == 0) finalize_kernel<0><<<c_T, kBlock, 0, st>>>(a);
-  else finalize_kernel<1><<<c_T, kBlock, 0, st>>>(a);
+  if (mode == 0) finalize_kernel<0><<<c_T, kBlock, 0, st>>>(a, c_T);
+  else finalize_kernel<1><<<c_T + (a.loss != nullptr ? 1 : 0), kBlock, 0, st>>>(a, c_T);
   return hipGetLastError();
 }
 
