@@ -163,7 +163,7 @@ ilargi_status_t make_layout(int n, const ilargi_source_t* s, int64_t r_T, int64_
     p.o_g = take(sizeof(float) * std::max<int64_t>(p.cols, 1) * max_cx);
   }
   lay.o_E = take(sizeof(float) * std::max<int64_t>(r_T, 1) * max_cx);
-  lay.o_loss = take(sizeof(float) * std::max<int64_t>(2048 * kNarrowCT, 1024 * max_cx));
+  lay.o_loss = take(sizeof(float) * std::max<int64_t>(32768 * kNarrowCT, 1024 * max_cx));
   lay.o_sort = take(sizeof(int32_t) * 4 * std::max<int64_t>(r_T, 1));
   lay.o_hist = take(sizeof(int32_t) * sort_hist_ints(r_T));
   // Gram scratch: summed rows for the "via sums" route, chunk partials, the (k,l) blocks
@@ -787,6 +787,7 @@ ilargi_status_t ilargi_crossprod(ilargi_plan_t* plan, float* out, void* stream) 
         g.B = a.D; g.ldb = (int)a.cols; g.cb = (int)a.cols; g.b_rows = a.rows;
         g.wptr = a.ident ? nullptr : plan->at<int32_t>(a.o_rowptr);
         g.n_rows = a.rows;
+        g.upper_only = 1;
         rc = run_gram(g, block);
       } else {
         bool via_l = !b.ident && b.rows * 2 <= plan->r_T;

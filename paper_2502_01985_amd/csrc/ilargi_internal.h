@@ -17,7 +17,7 @@ constexpr int kColredBlocks = 1024;  // row chunks (= partial results) of the D^
 constexpr int kLongSeg = 2048;       // inverse-index segments longer than this are split ...
 constexpr int kSegChunk = 2048;      // ... into chunks of this many entries
 constexpr int kSortChunk = 2048;     // keys per workgroup in one radix pass
-constexpr int kMaxLdsFloats = 16384; // 64 KiB of LDS for the staged operand
+constexpr int kMaxLdsFloats = 4096;  // 16 KiB of LDS for the staged operand rows (also the column limit of a source)
 constexpr int64_t kGramPartialFloats = 4ll << 20;
 
 // Row gathers of per-source products:  out[i,:] += P_s[row_s(i), :]  (assembly step of Sec. 2.2).
@@ -137,6 +137,7 @@ struct TredArgs {
   const int32_t* wptr;     // optional: w_t = wptr[t+1] - wptr[t]
   int64_t n_rows, rows_per_block;
   float* partial;          // [gridDim.x][ca][cb]
+  int upper_only;          // A == B: only tiles touching the upper triangle are computed
 };
 
 struct ColAsmArgs {

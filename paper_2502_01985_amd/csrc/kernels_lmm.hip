@@ -53,7 +53,7 @@ __device__ __forceinline__ int64_t gather_row(const GatherArgs& g, int s, int64_
 // FUSEG: also accumulate this workgroup's partial of D^T e (needs every row to fit one load per lane).
 template <int VEC, int CT, int MODE, bool FUSEG>
 __global__ __launch_bounds__(kBlock) void lmm_rows_kernel(LmmArgs a) {
-  extern __shared__ float Xs[];                 // [ck][CT]
+  __shared__ float Xs[kMaxLdsFloats];           // [ck][CT]
   __shared__ float zbuf[2][kBlock * CT];        // dot products (then residuals) of the step's rows, ping-pong
   const int tid = threadIdx.x;
   for (int e = tid; e < a.ck * CT; e += kBlock) {
@@ -293,7 +293,7 @@ hipError_t launch_mode(const LmmArgs& a, int mode, bool fuseg, int grid, size_t 
 template <int VEC>
 hipError_t launch_ct(const LmmArgs& a, int mode, bool fuseg, int grid, hipStream_t st) {
   int ct = a.ncols <= 1 ? 1 : (a.ncols <= 2 ? 2 : 4);
-  size_t lds = (size_t)a.ck * ct * sizeof(float);
+  size_t lds = 0;
   switch (ct) {
     case 1: return launch_mode<VEC, 1>(a, mode, fuseg, grid, lds, st);
     case 2: return launch_mode<VEC, 2>(a, mode, fuseg, grid, lds, st);
@@ -312,9 +312,14 @@ int lmm_rows_per_step(int logL) {
 int lmm_grid(int64_t r_out, int logL, bool fuseg) {
   int64_t rpi = lmm_rows_per_step(logL);
   int64_t g = (r_out + rpi - 1) / rpi;
+  // one step per workgroup whenever possible: late workgroups then fill the slots early ones free, which
+  // balances better than a resident grid whose members do one or two steps each
   int64_t cap = fuseg ? kColredBlocks : 2048;
   if (g < 1) g = 1;
-  if (g > cap) g = cap;
+  if (g > cap) {
+    int64_t per = (g + cap - 1) / cap;
+    g = (g + per - 1) / per;
+  }
   return (int)g;
 }
 

@@ -77,23 +77,41 @@ __global__ __launch_bounds__(kBlock) void lmm_mfma_kernel(LmmArgs a, MfmaShape s
           int r = tid / tpr, g = tid - r * tpr;
           const int dr = kBlock / tpr, dg = kBlock - dr * tpr;
           while (r < sh.rb) {
-            float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-            int64_t row = row0 + r;
-            if (g < live4 && row < a.d_rows) v = *reinterpret_cast<const float4*>(a.D + row * a.ck + k0 + 4 * g);
-            *reinterpret_cast<float4*>(As + (size_t)r * sh.lda + 4 * g) = v;
-            r += dr; g += dg;
-            if (g >= tpr) { g -= tpr; ++r; }
+            // eight loads in flight per thread, then the LDS stores
+            float4 v[8];
+            int rr[8], gg[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+              rr[u] = r; gg[u] = g;
+              v[u] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+              int64_t row = row0 + r;
+              if (r < sh.rb && g < live4 && row < a.d_rows)
+                v[u] = *reinterpret_cast<const float4*>(a.D + row * a.ck + k0 + 4 * g);
+              r += dr; g += dg;
+              if (g >= tpr) { g -= tpr; ++r; }
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+              if (rr[u] < sh.rb) *reinterpret_cast<float4*>(As + (size_t)rr[u] * sh.lda + 4 * gg[u]) = v[u];
           }
         } else {
           int r = tid / kw, g = tid - r * kw;
           const int dr = kBlock / kw, dg = kBlock - dr * kw;
           while (r < sh.rb) {
-            float v = 0.0f;
-            int64_t row = row0 + r;
-            if (g < cols_here && row < a.d_rows) v = a.D[row * a.ck + k0 + g];
-            As[(size_t)r * sh.lda + g] = v;
-            r += dr; g += dg;
-            if (g >= kw) { g -= kw; ++r; }
+            float v[8];
+            int rr[8], gg[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+              rr[u] = r; gg[u] = g;
+              v[u] = 0.0f;
+              int64_t row = row0 + r;
+              if (r < sh.rb && g < cols_here && row < a.d_rows) v[u] = a.D[row * a.ck + k0 + g];
+              r += dr; g += dg;
+              if (g >= kw) { g -= kw; ++r; }
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+              if (rr[u] < sh.rb) As[(size_t)rr[u] * sh.lda + gg[u]] = v[u];
           }
         }
       }

@@ -35,6 +35,8 @@ __global__ __launch_bounds__(kBlock) void tred_kernel(TredArgs a) {
   const int j0 = a_slab * JT * 64, n0 = b_slab * NT * 16;
   const int64_t t_lo = (int64_t)blockIdx.x * a.rows_per_block;
   const int64_t t_hi = min(t_lo + a.rows_per_block, a.n_rows);
+  // symmetric result: tiles entirely below the diagonal are never read by the caller
+  if (a.upper_only && j0 >= n0 + NT * 16) return;
 
   v4f acc[JT][4][NT];
 #pragma unroll
@@ -128,21 +130,34 @@ __global__ __launch_bounds__(kBlock) void tred_kernel(TredArgs a) {
   }
 }
 
-// block[e] = sum over chunks, in chunk order
+// block[e] = sum over chunks.  A workgroup owns 16 consecutive elements; its 16 thread groups stride the chunks
+// with eight loads in flight each, then the groups are added in order.
 __global__ __launch_bounds__(kBlock) void tred_reduce_kernel(const float* __restrict__ partial, int nchunks,
                                                              int64_t elems, float* __restrict__ block) {
-  for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < elems;
-       e += (int64_t)gridDim.x * blockDim.x) {
-    float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
-    int c = 0;
-    for (; c + 4 <= nchunks; c += 4) {
-      s0 += partial[(int64_t)c * elems + e];
-      s1 += partial[(int64_t)(c + 1) * elems + e];
-      s2 += partial[(int64_t)(c + 2) * elems + e];
-      s3 += partial[(int64_t)(c + 3) * elems + e];
+  __shared__ float red[16][16];
+  const int el = threadIdx.x % 16, cg = threadIdx.x / 16;
+  const int64_t e = (int64_t)blockIdx.x * 16 + el;
+  float s[8];
+#pragma unroll
+  for (int u = 0; u < 8; ++u) s[u] = 0.0f;
+  if (e < elems) {
+    int c = cg;
+    for (; c + 7 * 16 < nchunks; c += 8 * 16) {
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = partial[(int64_t)(c + u * 16) * elems + e];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) s[u] += v[u];
     }
-    for (; c < nchunks; ++c) s0 += partial[(int64_t)c * elems + e];
-    block[e] = (s0 + s1) + (s2 + s3);
+    for (; c < nchunks; c += 16) s[0] += partial[(int64_t)c * elems + e];
+  }
+  red[cg][el] = ((s[0] + s[1]) + (s[2] + s[3])) + ((s[4] + s[5]) + (s[6] + s[7]));
+  __syncthreads();
+  if (threadIdx.x < 16 && e < elems) {
+    float t = 0.0f;
+#pragma unroll
+    for (int g = 0; g < 16; ++g) t += red[g][el];
+    block[e] = t;
   }
 }
 
@@ -202,9 +217,8 @@ hipError_t launch_tred(const TredArgs& a, int nchunks, hipStream_t st) {
 
 hipError_t launch_tred_reduce(const float* partial, int nchunks, int64_t elems, float* block, hipStream_t st) {
   if (elems <= 0) return hipSuccess;
-  int grid = (int)((elems + kBlock - 1) / kBlock);
-  if (grid > 4096) grid = 4096;
-  tred_reduce_kernel<<<grid, kBlock, 0, st>>>(partial, nchunks, elems, block);
+  int64_t grid = (elems + 15) / 16;
+  tred_reduce_kernel<<<(unsigned)grid, kBlock, 0, st>>>(partial, nchunks, elems, block);
   return hipGetLastError();
 }
 
