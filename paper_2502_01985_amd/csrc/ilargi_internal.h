@@ -166,7 +166,7 @@ size_t sort_hist_ints(int64_t r_T);
 hipError_t launch_lmm_rows(const LmmArgs& a, int vec, int mode, hipStream_t st, int* grid_out);
 int lmm_grid(int64_t r_out, int logL, bool fuseg);
 bool lmm_can_fuse_gradient(int ck, int vec, int logL);
-MfmaShape lmm_mfma_shape(int ck, int nt);
+MfmaShape lmm_mfma_shape(int ck, int nt, bool gathers);
 hipError_t launch_lmm_mfma(const LmmArgs& a, int vec, int mode, hipStream_t st, int* grid_out);
 hipError_t launch_segsum(const SegArgs& a, hipStream_t st);
 hipError_t launch_colred(const ColredArgs& a, int nblocks, hipStream_t st);

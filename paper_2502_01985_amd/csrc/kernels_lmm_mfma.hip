@@ -35,6 +35,7 @@ __global__ __launch_bounds__(kBlock) void lmm_mfma_kernel(LmmArgs a, MfmaShape s
   float* As = lds;                                   // [rb][lda]
   float* Xs = lds + (size_t)sh.rb * sh.lda;          // [kc / 4][NT * 16][4]
   constexpr int N = NT * 16;
+  float* Gs = Xs + (size_t)sh.kc * N;                // [rb][N] sums of the gathered product rows (if any)
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
   const int li = lane % 16, q = lane / 16;
   const int n0 = a.col0 + blockIdx.y * N;
@@ -46,15 +47,29 @@ __global__ __launch_bounds__(kBlock) void lmm_mfma_kernel(LmmArgs a, MfmaShape s
   for (int nt = 0; nt < NT; ++nt) loss_local[nt] = 0.0f;
 
   auto load_x = [&](int k0, int kw) {
-    // Xs[(k/4) * N + n][k % 4] = X[colmap[k0 + k], n0 + n]   (zero beyond the table's columns / the slab)
-    for (int e = tid; e < kw * N; e += kBlock) {
-      int k = e / N, n = e - k * N;
-      float v = 0.0f;
-      if (k0 + k < a.ck && n < nw) {
-        int t = a.colmap[k0 + k];
-        if (t >= 0) v = a.X[(int64_t)t * a.ldx + n0 + n];
+    // Xs[(k/4) * N + n][k % 4] = X[colmap[k0 + k], n0 + n]   (zero beyond the table's columns / the slab).
+    // Eight elements per thread at a time: all col_map loads, then all operand loads, then the LDS stores.
+    for (int e0 = tid; e0 < kw * N; e0 += 8 * kBlock) {
+      int tcol[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        int e = e0 + u * kBlock;
+        int k = e / N, n = e - k * N;
+        tcol[u] = (e < kw * N && k0 + k < a.ck && n < nw) ? a.colmap[k0 + k] : -1;
       }
-      Xs[((k >> 2) * N + n) * 4 + (k & 3)] = v;
+      float xv[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        int e = e0 + u * kBlock;
+        int n = e % N;
+        xv[u] = tcol[u] >= 0 ? a.X[(int64_t)tcol[u] * a.ldx + n0 + n] : 0.0f;
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        int e = e0 + u * kBlock;
+        int k = e / N, n = e - k * N;
+        if (e < kw * N) Xs[((k >> 2) * N + n) * 4 + (k & 3)] = xv[u];
+      }
     }
   };
 
@@ -115,6 +130,53 @@ __global__ __launch_bounds__(kBlock) void lmm_mfma_kernel(LmmArgs a, MfmaShape s
           }
         }
       }
+      if (a.g.n > 0 && c + 1 == nchunks) {
+        // gathered rows of the other sources' products, summed into Gs: N/4 threads per target row, all
+        // row-index loads of a batch first, then all product-row loads
+        constexpr int QN = N / 4;                         // float4 slots per row
+        constexpr int RPP = kBlock / QN;                  // rows per pass
+        const int qn = tid % QN, r0 = tid / QN;
+        const bool col_ok = 4 * qn < nw;
+        const bool vec_ok = (a.g.ldp % 4 == 0) && (n0 % 4 == 0) && (4 * qn + 3 < nw);
+        for (int rbase = 0; rbase < sh.rb; rbase += 4 * RPP) {
+          float4 gsum[4];
+#pragma unroll
+          for (int u = 0; u < 4; ++u) gsum[u] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+          for (int s = 0; s < a.g.n; ++s) {
+            int64_t j[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+              int r = rbase + u * RPP + r0;
+              int64_t row = row0 + r;
+              j[u] = -1;
+              if (r < sh.rb && row < a.r_out && col_ok) {
+                if (a.g.idx[s] != nullptr) j[u] = a.g.idx[s][row];
+                else j[u] = (row < a.g.rows[s]) ? row : -1;
+              }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+              if (j[u] >= 0) {
+                const float* p = a.g.P[s] + j[u] * a.g.ldp + n0 + 4 * qn;
+                if (vec_ok) {
+                  float4 t = *reinterpret_cast<const float4*>(p);
+                  gsum[u].x += t.x; gsum[u].y += t.y; gsum[u].z += t.z; gsum[u].w += t.w;
+                } else {
+                  gsum[u].x += p[0];
+                  if (4 * qn + 1 < nw) gsum[u].y += p[1];
+                  if (4 * qn + 2 < nw) gsum[u].z += p[2];
+                  if (4 * qn + 3 < nw) gsum[u].w += p[3];
+                }
+              }
+            }
+          }
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            int r = rbase + u * RPP + r0;
+            if (r < sh.rb) *reinterpret_cast<float4*>(Gs + (size_t)r * N + 4 * qn) = gsum[u];
+          }
+        }
+      }
       __syncthreads();
       // each wavefront walks its 16-row tiles of the block
       const int tiles = sh.rb / 16;
@@ -146,18 +208,8 @@ __global__ __launch_bounds__(kBlock) void lmm_mfma_kernel(LmmArgs a, MfmaShape s
           if (row >= a.r_out) continue;
           float g[NT];
 #pragma unroll
-          for (int nt = 0; nt < NT; ++nt) g[nt] = 0.0f;
-          for (int s = 0; s < a.g.n; ++s) {
-            int64_t j;
-            if (a.g.idx[s] != nullptr) j = a.g.idx[s][row];
-            else j = (row < a.g.rows[s]) ? row : -1;
-            if (j >= 0) {
-              const float* p = a.g.P[s] + j * a.g.ldp + n0 + li;
-#pragma unroll
-              for (int nt = 0; nt < NT; ++nt)
-                if (nt * 16 + li < nw) g[nt] += p[nt * 16];
-            }
-          }
+          for (int nt = 0; nt < NT; ++nt)
+            g[nt] = a.g.n > 0 ? Gs[(size_t)(mt * 16 + 4 * q + r) * N + nt * 16 + li] : 0.0f;
           float yi = 0.0f;
           if constexpr (MODE != 0) yi = a.y[row];
 #pragma unroll
@@ -202,7 +254,7 @@ __global__ __launch_bounds__(kBlock) void lmm_mfma_kernel(LmmArgs a, MfmaShape s
 }  // namespace
 
 // Shape decisions shared with the caller: K padding, K chunking, rows per block, LDS bytes.
-MfmaShape lmm_mfma_shape(int ck, int nt) {
+MfmaShape lmm_mfma_shape(int ck, int nt, bool gathers) {
   MfmaShape sh;
   sh.kp = ck > 0 ? (ck + 15) / 16 * 16 : 16;
   sh.kc = sh.kp <= 256 ? sh.kp : 256;
@@ -212,10 +264,10 @@ MfmaShape lmm_mfma_shape(int ck, int nt) {
   int rm = 1;
   if (sh.kp == sh.kc) {
     // several 16-row tiles per wavefront when rows are short, so that a block moves tens of KiB per barrier
-    while (rm < 8 && (size_t)(2 * rm) * 64 * sh.lda * 4 + x_floats * 4 <= 48 * 1024) rm *= 2;
+    while (rm < 8 && (size_t)(2 * rm) * 64 * (sh.lda + (gathers ? n : 0)) * 4 + x_floats * 4 <= 48 * 1024) rm *= 2;
   }
   sh.rb = 64 * rm;
-  sh.lds_bytes = ((size_t)sh.rb * sh.lda + x_floats) * sizeof(float);
+  sh.lds_bytes = ((size_t)sh.rb * sh.lda + x_floats + (gathers ? (size_t)sh.rb * n : 0)) * sizeof(float);
   return sh;
 }
 
@@ -223,7 +275,7 @@ hipError_t launch_lmm_mfma(const LmmArgs& a, int vec, int mode, hipStream_t st, 
   if (grid_out) *grid_out = 0;
   if (a.r_out <= 0 || a.ncols <= 0) return hipSuccess;
   const int nt = a.ncols <= 16 ? 1 : (a.ncols <= 32 ? 2 : 4);
-  const MfmaShape sh = lmm_mfma_shape(a.ck, nt);
+  const MfmaShape sh = lmm_mfma_shape(a.ck, nt, a.g.n > 0);
   int64_t nblocks = (a.r_out + sh.rb - 1) / sh.rb;
   int gx = (int)std::min<int64_t>(nblocks, 1024);
   int gy = (a.ncols + nt * 16 - 1) / (nt * 16);

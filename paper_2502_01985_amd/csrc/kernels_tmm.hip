@@ -72,7 +72,9 @@ __global__ __launch_bounds__(kBlock) void segsum_narrow_kernel(SegArgs a) {
   }
 }
 
-// Wide form: W lanes of a segment each own columns lane, lane + W, ... and walk the entries in order.
+// Wide form: W lanes of a segment each own columns lane, lane + W, ...  The lanes first load W different
+// entries of the inverse index (one coalesced load), pass the row numbers around with shuffles, and then issue
+// the loads of up to 16 rows of Y together; rows are added in entry order.
 template <int W>
 __global__ __launch_bounds__(kBlock) void segsum_wide_kernel(SegArgs a) {
   const int lig = threadIdx.x & (W - 1);
@@ -93,22 +95,27 @@ __global__ __launch_bounds__(kBlock) void segsum_wide_kernel(SegArgs a) {
       end = a.chunk_end[c];
       dst = a.chunk_partial + (int64_t)c * a.ncols;
     }
-    for (int n0 = lig; n0 < a.ncols; n0 += W) {
+    for (int nb = 0; nb < a.ncols; nb += W) {
+      const int n0 = nb + lig;
+      const bool nlive = n0 < a.ncols;
       float acc = 0.0f;
-      int64_t p = beg;
-      for (; p + 4 <= end; p += 4) {
-        int64_t r0 = seg_row(a, p), r1 = seg_row(a, p + 1), r2 = seg_row(a, p + 2), r3 = seg_row(a, p + 3);
-        float v0 = r0 >= 0 ? a.Y[r0 * a.ldy + a.col0 + n0] : 0.0f;
-        float v1 = r1 >= 0 ? a.Y[r1 * a.ldy + a.col0 + n0] : 0.0f;
-        float v2 = r2 >= 0 ? a.Y[r2 * a.ldy + a.col0 + n0] : 0.0f;
-        float v3 = r3 >= 0 ? a.Y[r3 * a.ldy + a.col0 + n0] : 0.0f;
-        acc += v0; acc += v1; acc += v2; acc += v3;
+      for (int64_t pb = beg; pb < end; pb += W) {
+        int myrow = (pb + lig < end) ? (int)seg_row(a, pb + lig) : -1;
+        const int cnt = (int)min((int64_t)W, end - pb);
+#pragma unroll
+        for (int e0 = 0; e0 < W; e0 += 16) {
+          if (e0 >= cnt) break;
+          float v[16];
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            int r = __shfl(myrow, e0 + e, W);
+            v[e] = (nlive && r >= 0) ? a.Y[(int64_t)r * a.ldy + a.col0 + n0] : 0.0f;
+          }
+#pragma unroll
+          for (int e = 0; e < 16; ++e) acc += v[e];
+        }
       }
-      for (; p < end; ++p) {
-        int64_t r = seg_row(a, p);
-        if (r >= 0) acc += a.Y[r * a.ldy + a.col0 + n0];
-      }
-      dst[n0] = acc;
+      if (nlive) dst[n0] = acc;
     }
   }
 }

@@ -130,6 +130,82 @@ __global__ __launch_bounds__(kBlock) void tred_kernel(TredArgs a) {
   }
 }
 
+// Form for tables with at most 48 columns: 16-column tiles of A read one float per lane, one MFMA per tile,
+// so that short rows do not leave three quarters of the MFMA rows empty.  JT <= 3, NT in {1, 2, 4}.
+template <int JT, int NT>
+__global__ __launch_bounds__(kBlock) void tred_dw_kernel(TredArgs a) {
+  constexpr int kUD = 8;
+  __shared__ float red[JT * 16 * NT * 16];
+  const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+  const int s = lane % 16, q = lane / 16;
+  const int n0 = blockIdx.y * NT * 16;
+  const int64_t t_lo = (int64_t)blockIdx.x * a.rows_per_block;
+  const int64_t t_hi = min(t_lo + a.rows_per_block, a.n_rows);
+  if (a.upper_only && 0 >= n0 + NT * 16) return;
+  v4f acc[JT][NT];
+#pragma unroll
+  for (int jt = 0; jt < JT; ++jt)
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) acc[jt][nt] = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
+  bool jok[JT], nok[NT];
+#pragma unroll
+  for (int jt = 0; jt < JT; ++jt) jok[jt] = jt * 16 + s < a.ca;
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) nok[nt] = n0 + nt * 16 + s < a.cb;
+
+  for (int64_t base = t_lo + (int64_t)wave * (4 * kUD); base < t_hi; base += (int64_t)(kBlock / kWave) * (4 * kUD)) {
+    float av[kUD][JT], bv[kUD][NT];
+#pragma unroll
+    for (int u = 0; u < kUD; ++u) {
+      int64_t t = base + u * 4 + q;
+      int64_t ra = -1, rb = -1;
+      float w = 1.0f;
+      if (t < t_hi) {
+        ra = a.ia ? (int64_t)a.ia[t] : (t < a.a_rows ? t : -1);
+        rb = a.ib ? (int64_t)a.ib[t] : (t < a.b_rows ? t : -1);
+        if (a.wptr) w = (float)(a.wptr[t + 1] - a.wptr[t]);
+      }
+      const bool live = ra >= 0 && rb >= 0;
+#pragma unroll
+      for (int jt = 0; jt < JT; ++jt) {
+        av[u][jt] = (live && jok[jt]) ? a.A[ra * a.lda + jt * 16 + s] : 0.0f;
+        if (a.wptr) av[u][jt] *= w;
+      }
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+        bv[u][nt] = (live && nok[nt]) ? a.B[rb * a.ldb + a.bcol0 + n0 + nt * 16 + s] : 0.0f;
+    }
+#pragma unroll
+    for (int u = 0; u < kUD; ++u)
+#pragma unroll
+      for (int jt = 0; jt < JT; ++jt)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+          acc[jt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u][jt], bv[u][nt], acc[jt][nt], 0, 0, 0);
+  }
+  for (int w = 0; w < kBlock / kWave; ++w) {
+    if (wave == w) {
+#pragma unroll
+      for (int jt = 0; jt < JT; ++jt)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            int j = jt * 16 + 4 * q + r, n = nt * 16 + s;
+            float v = acc[jt][nt][r];
+            if (w == 0) red[j * (NT * 16) + n] = v;
+            else red[j * (NT * 16) + n] += v;
+          }
+    }
+    __syncthreads();
+  }
+  float* out = a.partial + (int64_t)blockIdx.x * a.ca * a.cb;
+  for (int o = tid; o < JT * 16 * NT * 16; o += kBlock) {
+    int j = o / (NT * 16), n = o - j * (NT * 16);
+    if (j < a.ca && n0 + n < a.cb) out[(int64_t)j * a.cb + n0 + n] = red[o];
+  }
+}
+
 // block[e] = sum over chunks.  A workgroup owns 16 consecutive elements; its 16 thread groups stride the chunks
 // with eight loads in flight each, then the groups are added in order.
 __global__ __launch_bounds__(kBlock) void tred_reduce_kernel(const float* __restrict__ partial, int nchunks,
@@ -196,6 +272,16 @@ hipError_t launch_tred(const TredArgs& a, int nchunks, hipStream_t st) {
   if (a.ca <= 0 || a.cb <= 0 || nchunks <= 0) return hipSuccess;
   const bool vec4 = a.lda % 4 == 0 && a.ca % 4 == 0 && reinterpret_cast<uintptr_t>(a.A) % 16 == 0;
   int nt = a.cb <= 16 ? 1 : (a.cb <= 32 ? 2 : 4);
+  if (a.ca <= 48) {
+    const int jtd = (a.ca + 15) / 16;
+    dim3 gridd(nchunks, (a.cb + nt * 16 - 1) / (nt * 16));
+#define ILARGI_TDW(J, N) tred_dw_kernel<J, N><<<gridd, kBlock, 0, st>>>(a)
+    if (jtd == 1) { if (nt == 1) ILARGI_TDW(1, 1); else if (nt == 2) ILARGI_TDW(1, 2); else ILARGI_TDW(1, 4); }
+    else if (jtd == 2) { if (nt == 1) ILARGI_TDW(2, 1); else if (nt == 2) ILARGI_TDW(2, 2); else ILARGI_TDW(2, 4); }
+    else { if (nt == 1) ILARGI_TDW(3, 1); else if (nt == 2) ILARGI_TDW(3, 2); else ILARGI_TDW(3, 4); }
+#undef ILARGI_TDW
+    return hipGetLastError();
+  }
   int jt = std::min(4 / nt, (a.ca + 63) / 64);
   if (jt == 3) jt = 4;
   int a_slabs = (a.ca + jt * 64 - 1) / (jt * 64), b_slabs = (a.cb + nt * 16 - 1) / (nt * 16);
