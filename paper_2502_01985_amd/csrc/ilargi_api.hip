@@ -251,7 +251,7 @@ int pass_width(const ilargi_plan* pl) {
 // out (or the residual E) for operand columns [col0, col0 + ncols):  per-source products, then the assembly.
 ilargi_status_t lmm_pass(ilargi_plan* pl, const float* X, int ldx, int col0, int ncols, float* out, int ldo,
                          int mode, const float* y, int* loss_grid, bool wide, hipStream_t st,
-                         bool* fused_gradient = nullptr) {
+                         bool* fused_gradient = nullptr, bool bf16 = false) {
   if (fused_gradient) *fused_gradient = false;
   GatherArgs g;
   memset(&g, 0, sizeof(g));
@@ -267,7 +267,7 @@ ilargi_status_t lmm_pass(ilargi_plan* pl, const float* X, int ldx, int col0, int
     a.logL = pick_logL(p.cols, p.vec);
     {
       TraceScope ts(pl, "lmm_rows", k, st);
-      if (wide) HIP_TRY(launch_lmm_mfma(a, p.vec, 0, st, nullptr));
+      if (wide) HIP_TRY(launch_lmm_mfma(a, p.vec, 0, bf16, st, nullptr));
       else HIP_TRY(launch_lmm_rows(a, p.vec, 0, st, nullptr));
     }
     g.idx[g.n] = p.ident ? nullptr : p.idx;
@@ -298,7 +298,7 @@ ilargi_status_t lmm_pass(ilargi_plan* pl, const float* X, int ldx, int col0, int
   }
   {
     TraceScope ts(pl, "lmm_assemble", -1, st);
-    if (wide) HIP_TRY(launch_lmm_mfma(a, vec, mode, st, loss_grid));
+    if (wide) HIP_TRY(launch_lmm_mfma(a, vec, mode, bf16, st, loss_grid));
     else HIP_TRY(launch_lmm_rows(a, vec, mode, st, loss_grid));
   }
   return ILARGI_OK;
@@ -366,7 +366,8 @@ ilargi_status_t tmm_pass(ilargi_plan* pl, const float* Y, int ldy, int col0, int
 }
 
 // Runs the matrix-core transposed reduction in row chunks and adds the chunk results in order.
-ilargi_status_t run_tred(ilargi_plan* pl, TredArgs& g, float* block, const char* tag, int tag_k, hipStream_t st) {
+ilargi_status_t run_tred(ilargi_plan* pl, TredArgs& g, float* block, const char* tag, int tag_k, bool bf16,
+                         hipStream_t st) {
   int64_t elems = (int64_t)g.ca * g.cb;
   if (elems <= 0) return ILARGI_OK;
   int64_t nch = (g.n_rows + 255) / 256;
@@ -378,7 +379,7 @@ ilargi_status_t run_tred(ilargi_plan* pl, TredArgs& g, float* block, const char*
   g.partial = pl->at<float>(pl->lay.o_gpartial);
   {
     TraceScope ts(pl, tag, tag_k, st);
-    HIP_TRY(launch_tred(g, (int)nch, st));
+    HIP_TRY(launch_tred(g, (int)nch, bf16, st));
   }
   HIP_TRY(launch_tred_reduce(g.partial, (int)nch, elems, block, st));
   return ILARGI_OK;
@@ -386,7 +387,7 @@ ilargi_status_t run_tred(ilargi_plan* pl, TredArgs& g, float* block, const char*
 
 // T^T Y for an operand with many columns: segment sums, matrix-core column reduce, column assembly.
 ilargi_status_t tmm_wide(ilargi_plan* pl, const float* Y, int cx, float* out, int mode, const float* lr,
-                         float* loss, int n_loss_partial, float loss_scale, hipStream_t st) {
+                         float* loss, int n_loss_partial, float loss_scale, bool bf16, hipStream_t st) {
   ColAsmArgs c;
   memset(&c, 0, sizeof(c));
   for (int k = 0; k < pl->n; ++k) {
@@ -409,7 +410,7 @@ ilargi_status_t tmm_wide(ilargi_plan* pl, const float* Y, int cx, float* out, in
       }
       g.B = pl->at<float>(p.o_pz);
     }
-    ilargi_status_t rc = run_tred(pl, g, pl->at<float>(p.o_g), "colred", k, st);
+    ilargi_status_t rc = run_tred(pl, g, pl->at<float>(p.o_g), "colred", k, bf16, st);
     if (rc != ILARGI_OK) return rc;
     c.tcol2src[c.n] = pl->at<int32_t>(p.o_tcol);
     c.G[c.n] = pl->at<float>(p.o_g);
@@ -660,9 +661,11 @@ ilargi_status_t ilargi_lmm(ilargi_plan_t* plan, const float* X, int64_t cx, floa
                            ilargi_precision_t precision, void* stream) {
   ilargi_status_t rc = check_call(plan, X, out, cx, "lmm");
   if (rc != ILARGI_OK) return rc;
-  if (precision != ILARGI_F32) return fail(ILARGI_ERR_UNSUPPORTED, "lmm: bf16 inputs need a wide operand");
+  const bool bf16 = precision == ILARGI_BF16_IN_F32_ACC;
+  if (precision != ILARGI_F32 && !bf16) return fail(ILARGI_ERR_UNSUPPORTED, "lmm: unknown precision %d", (int)precision);
+  if (bf16 && cx < kWideMin) return fail(ILARGI_ERR_UNSUPPORTED, "lmm: bf16 inputs need an operand with at least %d columns", kWideMin);
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if (cx >= kWideMin) return lmm_pass(plan, X, (int)cx, 0, (int)cx, out, (int)cx, 0, nullptr, nullptr, true, st);
+  if (cx >= kWideMin) return lmm_pass(plan, X, (int)cx, 0, (int)cx, out, (int)cx, 0, nullptr, nullptr, true, st, nullptr, bf16);
   const int w = pass_width(plan);
   for (int64_t col0 = 0; col0 < cx; col0 += w) {
     int ncols = (int)std::min<int64_t>(w, cx - col0);
@@ -676,9 +679,11 @@ ilargi_status_t ilargi_tmm(ilargi_plan_t* plan, const float* Y, int64_t cx, floa
                            ilargi_precision_t precision, void* stream) {
   ilargi_status_t rc = check_call(plan, Y, out, cx, "tmm");
   if (rc != ILARGI_OK) return rc;
-  if (precision != ILARGI_F32) return fail(ILARGI_ERR_UNSUPPORTED, "tmm: bf16 inputs need a wide operand");
+  const bool bf16 = precision == ILARGI_BF16_IN_F32_ACC;
+  if (precision != ILARGI_F32 && !bf16) return fail(ILARGI_ERR_UNSUPPORTED, "tmm: unknown precision %d", (int)precision);
+  if (bf16 && cx < kWideMin) return fail(ILARGI_ERR_UNSUPPORTED, "tmm: bf16 inputs need an operand with at least %d columns", kWideMin);
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if (cx >= kWideMin) return tmm_wide(plan, Y, (int)cx, out, 0, nullptr, nullptr, 0, 0.0f, st);
+  if (cx >= kWideMin) return tmm_wide(plan, Y, (int)cx, out, 0, nullptr, nullptr, 0, 0.0f, bf16, st);
   for (int64_t col0 = 0; col0 < cx; col0 += kNarrowCT) {
     int ncols = (int)std::min<int64_t>(kNarrowCT, cx - col0);
     rc = tmm_pass(plan, Y, (int)cx, (int)col0, ncols, out, (int)cx, 0, nullptr, nullptr, 0, 0.0f, st);
@@ -694,16 +699,19 @@ ilargi_status_t ilargi_gd_step(ilargi_plan_t* plan, ilargi_model_t model, float*
   if (lr == nullptr) return fail(ILARGI_ERR_NULL, "gd_step: lr is NULL");
   if (model != ILARGI_LINEAR && model != ILARGI_LOGISTIC) return fail(ILARGI_ERR_UNSUPPORTED, "gd_step: unknown model %d", (int)model);
   if (plan->r_T < 1) return fail(ILARGI_ERR_SHAPE, "gd_step: the target table has no rows");
-  if (precision != ILARGI_F32) return fail(ILARGI_ERR_UNSUPPORTED, "gd_step: bf16 inputs need a wide operand");
+  const bool bf16 = precision == ILARGI_BF16_IN_F32_ACC;
+  if (precision != ILARGI_F32 && !bf16) return fail(ILARGI_ERR_UNSUPPORTED, "gd_step: unknown precision %d", (int)precision);
+  if (bf16 && m < kWideMin) return fail(ILARGI_ERR_UNSUPPORTED, "gd_step: bf16 inputs need at least %d models", kWideMin);
   hipStream_t st = static_cast<hipStream_t>(stream);
   float* E = plan->at<float>(plan->lay.o_E);
   const int w = pass_width(plan);
   const float loss_scale = (model == ILARGI_LINEAR ? 0.5f : 1.0f) / (float)plan->r_T;
   if (m >= kWideMin) {
     int loss_grid = 0;
-    rc = lmm_pass(plan, W, (int)m, 0, (int)m, E, (int)m, model == ILARGI_LINEAR ? 1 : 2, y, &loss_grid, true, st);
+    rc = lmm_pass(plan, W, (int)m, 0, (int)m, E, (int)m, model == ILARGI_LINEAR ? 1 : 2, y, &loss_grid, true, st,
+                  nullptr, bf16);
     if (rc != ILARGI_OK) return rc;
-    return tmm_wide(plan, E, (int)m, W, 1, lr, loss, loss_grid, loss_scale, st);
+    return tmm_wide(plan, E, (int)m, W, 1, lr, loss, loss_grid, loss_scale, bf16, st);
   }
   for (int64_t col0 = 0; col0 < m; col0 += w) {
     int ncols = (int)std::min<int64_t>(w, m - col0);
@@ -770,7 +778,7 @@ ilargi_status_t ilargi_crossprod(ilargi_plan_t* plan, float* out, void* stream) 
   float* blocks = plan->at<float>(plan->lay.o_blocks);
   float* zc = plan->at<float>(plan->lay.o_zc);
   auto run_gram = [&](TredArgs& g, float* block) -> ilargi_status_t {
-    return run_tred(plan, g, block, "gram", -1, st);
+    return run_tred(plan, g, block, "gram", -1, false, st);
   };
   for (int k = 0; k < n; ++k) {
     const SourcePlan& a = plan->src[k];

@@ -166,8 +166,8 @@ size_t sort_hist_ints(int64_t r_T);
 hipError_t launch_lmm_rows(const LmmArgs& a, int vec, int mode, hipStream_t st, int* grid_out);
 int lmm_grid(int64_t r_out, int logL, bool fuseg);
 bool lmm_can_fuse_gradient(int ck, int vec, int logL);
-MfmaShape lmm_mfma_shape(int ck, int nt, bool gathers);
-hipError_t launch_lmm_mfma(const LmmArgs& a, int vec, int mode, hipStream_t st, int* grid_out);
+MfmaShape lmm_mfma_shape(int ck, int nt, bool gathers, bool bf16);
+hipError_t launch_lmm_mfma(const LmmArgs& a, int vec, int mode, bool bf16, hipStream_t st, int* grid_out);
 hipError_t launch_segsum(const SegArgs& a, hipStream_t st);
 hipError_t launch_colred(const ColredArgs& a, int nblocks, hipStream_t st);
 hipError_t launch_finalize(const FinArgs& a, int c_T, int mode, hipStream_t st);
@@ -176,7 +176,7 @@ hipError_t launch_gram(const GramArgs& a, int nchunks, hipStream_t st);
 hipError_t launch_gram_reduce(const float* partial, int nchunks, int64_t elems, float* block, hipStream_t st);
 hipError_t launch_gram_assemble(const GramAsmPair* pairs_dev, int npairs, const int32_t* const* tcol2src_dev,
                                 int c_T, float* out, hipStream_t st);
-hipError_t launch_tred(const TredArgs& a, int nchunks, hipStream_t st);
+hipError_t launch_tred(const TredArgs& a, int nchunks, bool bf16, hipStream_t st);
 hipError_t launch_tred_reduce(const float* partial, int nchunks, int64_t elems, float* block, hipStream_t st);
 hipError_t launch_colasm(const ColAsmArgs& a, int mode, hipStream_t st);
 hipError_t launch_probe(int kind, float* dst, const float* src, int64_t n_floats, int blocks, hipStream_t st);

@@ -17,6 +17,7 @@ namespace ilargi {
 namespace {
 
 typedef float v4f __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 __device__ __forceinline__ float sigmoidf_stable(float z) {
   if (z >= 0.0f) return 1.0f / (1.0f + __expf(-z));
@@ -29,7 +30,9 @@ __device__ __forceinline__ float softplusf_stable(float z) {
 }
 
 // NT: 16-column tiles of the operand slab handled by one workgroup.  MODE as in the narrow kernel.
-template <int NT, int MODE, bool VEC4>
+// BF16: table and operand values are rounded to bfloat16 (nearest even) when they enter the MFMA
+// (16x16x32, eight K values per lane: lane 16 q + i holds columns 32 step + 8 q .. + 7), sums stay float32.
+template <int NT, int MODE, bool VEC4, bool BF16>
 __global__ __launch_bounds__(kBlock) void lmm_mfma_kernel(LmmArgs a, MfmaShape sh) {
   extern __shared__ float lds[];
   float* As = lds;                                   // [rb][lda]
@@ -68,7 +71,10 @@ __global__ __launch_bounds__(kBlock) void lmm_mfma_kernel(LmmArgs a, MfmaShape s
       for (int u = 0; u < 8; ++u) {
         int e = e0 + u * kBlock;
         int k = e / N, n = e - k * N;
-        if (e < kw * N) Xs[((k >> 2) * N + n) * 4 + (k & 3)] = xv[u];
+        if (e < kw * N) {
+          if constexpr (BF16) reinterpret_cast<__bf16*>(Xs)[((k >> 3) * N + n) * 8 + (k & 7)] = (__bf16)xv[u];
+          else Xs[((k >> 2) * N + n) * 4 + (k & 3)] = xv[u];
+        }
       }
     }
   };
@@ -185,7 +191,22 @@ __global__ __launch_bounds__(kBlock) void lmm_mfma_kernel(LmmArgs a, MfmaShape s
 #pragma unroll
           for (int nt = 0; nt < NT; ++nt) acc[nt] = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
         }
-        if (a.D != nullptr) {
+        if constexpr (BF16) {
+          if (a.D != nullptr) {
+            const float* arow = As + (size_t)(mt * 16 + li) * sh.lda + 8 * q;
+            for (int step = 0; step < kw / 32; ++step) {
+              float4 a0 = *reinterpret_cast<const float4*>(arow + 32 * step);
+              float4 a1 = *reinterpret_cast<const float4*>(arow + 32 * step + 4);
+              bf16x8 av;
+              av[0] = (__bf16)a0.x; av[1] = (__bf16)a0.y; av[2] = (__bf16)a0.z; av[3] = (__bf16)a0.w;
+              av[4] = (__bf16)a1.x; av[5] = (__bf16)a1.y; av[6] = (__bf16)a1.z; av[7] = (__bf16)a1.w;
+              const bf16x8* xb = reinterpret_cast<const bf16x8*>(Xs) + (size_t)(4 * step + q) * N + li;
+#pragma unroll
+              for (int nt = 0; nt < NT; ++nt)
+                acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, xb[nt * 16], acc[nt], 0, 0, 0);
+            }
+          }
+        } else if (a.D != nullptr) {
           const float* arow = As + (size_t)(mt * 16 + li) * sh.lda + 4 * q;
           for (int step = 0; step < kw / 16; ++step) {
             float4 av = *reinterpret_cast<const float4*>(arow + 16 * step);
@@ -254,9 +275,10 @@ __global__ __launch_bounds__(kBlock) void lmm_mfma_kernel(LmmArgs a, MfmaShape s
 }  // namespace
 
 // Shape decisions shared with the caller: K padding, K chunking, rows per block, LDS bytes.
-MfmaShape lmm_mfma_shape(int ck, int nt, bool gathers) {
+MfmaShape lmm_mfma_shape(int ck, int nt, bool gathers, bool bf16) {
   MfmaShape sh;
-  sh.kp = ck > 0 ? (ck + 15) / 16 * 16 : 16;
+  const int kq = bf16 ? 32 : 16;                      // K values one MFMA step consumes
+  sh.kp = ck > 0 ? (ck + kq - 1) / kq * kq : kq;
   sh.kc = sh.kp <= 256 ? sh.kp : 256;
   sh.lda = sh.kc + 4;
   const int n = nt * 16;
@@ -271,30 +293,30 @@ MfmaShape lmm_mfma_shape(int ck, int nt, bool gathers) {
   return sh;
 }
 
-hipError_t launch_lmm_mfma(const LmmArgs& a, int vec, int mode, hipStream_t st, int* grid_out) {
+hipError_t launch_lmm_mfma(const LmmArgs& a, int vec, int mode, bool bf16, hipStream_t st, int* grid_out) {
   if (grid_out) *grid_out = 0;
   if (a.r_out <= 0 || a.ncols <= 0) return hipSuccess;
   const int nt = a.ncols <= 16 ? 1 : (a.ncols <= 32 ? 2 : 4);
-  const MfmaShape sh = lmm_mfma_shape(a.ck, nt, a.g.n > 0);
+  const MfmaShape sh = lmm_mfma_shape(a.ck, nt, a.g.n > 0, bf16);
   int64_t nblocks = (a.r_out + sh.rb - 1) / sh.rb;
   int gx = (int)std::min<int64_t>(nblocks, 1024);
   int gy = (a.ncols + nt * 16 - 1) / (nt * 16);
   if (grid_out) *grid_out = gx;
   dim3 grid(gx, gy);
   const bool vec4 = vec == 4;
+#define ILARGI_LAUNCH1(NT_, MODE_, V_, B_)                                                          \
+  do {                                                                                              \
+    auto kfn = lmm_mfma_kernel<NT_, MODE_, V_, B_>;                                                 \
+    if (sh.lds_bytes > 64 * 1024)                                                                   \
+      (void)hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh.lds_bytes); \
+    kfn<<<grid, kBlock, sh.lds_bytes, st>>>(a, sh);                                                 \
+  } while (0)
 #define ILARGI_LAUNCH(NT_, MODE_)                                                                   \
   do {                                                                                              \
-    if (vec4) {                                                                                     \
-      auto kfn = lmm_mfma_kernel<NT_, MODE_, true>;                                                 \
-      if (sh.lds_bytes > 64 * 1024)                                                                 \
-        (void)hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh.lds_bytes); \
-      kfn<<<grid, kBlock, sh.lds_bytes, st>>>(a, sh);                                               \
-    } else {                                                                                        \
-      auto kfn = lmm_mfma_kernel<NT_, MODE_, false>;                                                \
-      if (sh.lds_bytes > 64 * 1024)                                                                 \
-        (void)hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh.lds_bytes); \
-      kfn<<<grid, kBlock, sh.lds_bytes, st>>>(a, sh);                                               \
-    }                                                                                               \
+    if (vec4 && bf16) ILARGI_LAUNCH1(NT_, MODE_, true, true);                                       \
+    else if (vec4) ILARGI_LAUNCH1(NT_, MODE_, true, false);                                         \
+    else if (bf16) ILARGI_LAUNCH1(NT_, MODE_, false, true);                                         \
+    else ILARGI_LAUNCH1(NT_, MODE_, false, false);                                                  \
   } while (0)
 #define ILARGI_MODES(NT_)                                    \
   do {                                                       \
@@ -307,6 +329,7 @@ hipError_t launch_lmm_mfma(const LmmArgs& a, int vec, int mode, hipStream_t st, 
   else ILARGI_MODES(4);
 #undef ILARGI_MODES
 #undef ILARGI_LAUNCH
+#undef ILARGI_LAUNCH1
   return hipGetLastError();
 }
 

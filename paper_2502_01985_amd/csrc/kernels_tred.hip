@@ -21,6 +21,7 @@ namespace ilargi {
 namespace {
 
 typedef float v4f __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int kU = 4;  // row quads in flight per wavefront
 
@@ -125,6 +126,102 @@ __global__ __launch_bounds__(kBlock) void tred_kernel(TredArgs a) {
   }
   float* out = a.partial + (int64_t)blockIdx.x * a.ca * a.cb;
   for (int o = tid; o < JT * 64 * NT * 16; o += kBlock) {
+    int j = o / (NT * 16), n = o - j * (NT * 16);
+    if (j0 + j < a.ca && n0 + n < a.cb) out[(int64_t)(j0 + j) * a.cb + n0 + n] = red[o];
+  }
+}
+
+// bfloat16-input form (MFMA 16x16x32, float32 sums): both factors are rounded to bfloat16, nearest even, as
+// they enter the MFMA.  Lane 16 q + s loads the float4  a[t0 + 8 q + u][j0 + 4 s ..]  for u = 0..7; component e
+// of the eight loads forms the A operand of MFMA e (K slots = rows t0 + 8 q + u).  One 64-column tile of A.
+template <int NT, bool VEC4>
+__global__ __launch_bounds__(kBlock) void tred_bf16_kernel(TredArgs a) {
+  __shared__ float red[64 * NT * 16];
+  const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+  const int s = lane % 16, q = lane / 16;
+  const int nb_slabs = (a.cb + NT * 16 - 1) / (NT * 16);
+  const int a_slab = blockIdx.y / nb_slabs, b_slab = blockIdx.y - a_slab * nb_slabs;
+  const int j0 = a_slab * 64, n0 = b_slab * NT * 16;
+  const int64_t t_lo = (int64_t)blockIdx.x * a.rows_per_block;
+  const int64_t t_hi = min(t_lo + a.rows_per_block, a.n_rows);
+  v4f acc[4][NT];
+#pragma unroll
+  for (int e = 0; e < 4; ++e)
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) acc[e][nt] = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
+  const bool jok = j0 + 4 * s < a.ca;
+  bool nok[NT];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) nok[nt] = n0 + nt * 16 + s < a.cb;
+
+  for (int64_t base = t_lo + (int64_t)wave * 32; base < t_hi; base += (int64_t)(kBlock / kWave) * 32) {
+    float av[8][4], bv[8][NT];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      int64_t t = base + 8 * q + u;
+      int64_t ra = -1, rb = -1;
+      float w = 1.0f;
+      if (t < t_hi) {
+        ra = a.ia ? (int64_t)a.ia[t] : (t < a.a_rows ? t : -1);
+        rb = a.ib ? (int64_t)a.ib[t] : (t < a.b_rows ? t : -1);
+        if (a.wptr) w = (float)(a.wptr[t + 1] - a.wptr[t]);
+      }
+      const bool live = ra >= 0 && rb >= 0;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) av[u][e] = 0.0f;
+      if (live && jok) {
+        const float* p = a.A + ra * a.lda + j0 + 4 * s;
+        if constexpr (VEC4) {
+          float4 v = *reinterpret_cast<const float4*>(p);
+          av[u][0] = v.x; av[u][1] = v.y; av[u][2] = v.z; av[u][3] = v.w;
+        } else {
+          const int left = a.ca - (j0 + 4 * s);
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (e < left) av[u][e] = p[e];
+        }
+        if (a.wptr) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) av[u][e] *= w;
+        }
+      }
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+        bv[u][nt] = (live && nok[nt]) ? a.B[rb * a.ldb + a.bcol0 + n0 + nt * 16 + s] : 0.0f;
+    }
+    bf16x8 bp[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int u = 0; u < 8; ++u) bp[nt][u] = (__bf16)bv[u][nt];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      bf16x8 ap;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) ap[u] = (__bf16)av[u][e];
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+        acc[e][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ap, bp[nt], acc[e][nt], 0, 0, 0);
+    }
+  }
+  for (int w = 0; w < kBlock / kWave; ++w) {
+    if (wave == w) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            int j = 4 * (4 * q + r) + e, n = nt * 16 + s;
+            float v = acc[e][nt][r];
+            if (w == 0) red[j * (NT * 16) + n] = v;
+            else red[j * (NT * 16) + n] += v;
+          }
+    }
+    __syncthreads();
+  }
+  float* out = a.partial + (int64_t)blockIdx.x * a.ca * a.cb;
+  for (int o = tid; o < 64 * NT * 16; o += kBlock) {
     int j = o / (NT * 16), n = o - j * (NT * 16);
     if (j0 + j < a.ca && n0 + n < a.cb) out[(int64_t)(j0 + j) * a.cb + n0 + n] = red[o];
   }
@@ -268,10 +365,21 @@ __global__ __launch_bounds__(kBlock) void colasm_kernel(ColAsmArgs a) {
 
 }  // namespace
 
-hipError_t launch_tred(const TredArgs& a, int nchunks, hipStream_t st) {
+hipError_t launch_tred(const TredArgs& a, int nchunks, bool bf16, hipStream_t st) {
   if (a.ca <= 0 || a.cb <= 0 || nchunks <= 0) return hipSuccess;
   const bool vec4 = a.lda % 4 == 0 && a.ca % 4 == 0 && reinterpret_cast<uintptr_t>(a.A) % 16 == 0;
   int nt = a.cb <= 16 ? 1 : (a.cb <= 32 ? 2 : 4);
+  if (bf16) {
+    dim3 gridb(nchunks, ((a.ca + 63) / 64) * ((a.cb + nt * 16 - 1) / (nt * 16)));
+#define ILARGI_TB(N)                                                                 \
+  do {                                                                               \
+    if (vec4) tred_bf16_kernel<N, true><<<gridb, kBlock, 0, st>>>(a);                \
+    else tred_bf16_kernel<N, false><<<gridb, kBlock, 0, st>>>(a);                    \
+  } while (0)
+    if (nt == 1) ILARGI_TB(1); else if (nt == 2) ILARGI_TB(2); else ILARGI_TB(4);
+#undef ILARGI_TB
+    return hipGetLastError();
+  }
   if (a.ca <= 48) {
     const int jtd = (a.ca + 15) / 16;
     dim3 gridd(nchunks, (a.cb + nt * 16 - 1) / (nt * 16));

@@ -227,6 +227,74 @@ def test_gd_logistic_wide(il):
     np.testing.assert_allclose(L, L_ref, rtol=2e-4)
 
 
+# ------------------------------------------------------------------ bfloat16-input variant
+BF16_TOL = 5e-3
+
+
+def _to_bf16_grid(a):
+    """Round float32 values to the nearest bfloat16 (ties to even), kept as float32."""
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).reshape(np.shape(a))
+
+
+@pytest.mark.parametrize("name", ["config1_small", "config3_small", "odd_cols"])
+@pytest.mark.parametrize("cx", [8, 16, 64, 100])
+def test_bf16_inputs_within_bound(il, name, cx):
+    sch, tg, plan = get(il, name, max_cx=256)
+    rng = datagen.rng_for(7000 + cx)
+    X = rng.standard_normal((sch.c_T, cx)).astype(np.float32)
+    Y = rng.standard_normal((sch.r_T, cx)).astype(np.float32)
+    e1 = rel(il.ilargi_lmm(plan, dev(X), precision=il.BF16_IN_F32_ACC).cpu().numpy(), oracle.lmm(tg, X))
+    e2 = rel(il.ilargi_tmm(plan, dev(Y), precision=il.BF16_IN_F32_ACC).cpu().numpy(), oracle.tmm(tg, Y))
+    assert e1 < BF16_TOL and e2 < BF16_TOL, (e1, e2)
+    # the rounding really happens: the result is not the float32 one
+    assert e1 > 1e-5 and e2 > 1e-5
+
+
+def test_bf16_exact_on_representable_inputs(il):
+    # tables and operands that already sit on the bfloat16 grid lose nothing: float32 tolerance applies
+    sch = datagen.config1(r_S=20_011, r_R=2_003, c_R=200)
+    for s in sch.sources:
+        s.D[...] = _to_bf16_grid(s.D)
+    tg = oracle.Target(sch)
+    plan = il.ilargi_plan_create(il.schema_to_device(sch), sch.r_T, sch.c_T, max_cx=64)
+    rng = datagen.rng_for(71)
+    X = _to_bf16_grid(rng.standard_normal((sch.c_T, 64)).astype(np.float32))
+    Y = _to_bf16_grid(rng.standard_normal((sch.r_T, 64)).astype(np.float32))
+    assert rel(il.ilargi_lmm(plan, dev(X), precision=il.BF16_IN_F32_ACC).cpu().numpy(), oracle.lmm(tg, X)) < OP_TOL
+    # T^T Y: the segment sums of Y are rounded again before the product, so only the identity source is exact
+    splan = il.ilargi_plan_create(il.schema_to_device(sch)[:1], sch.r_T, 20, max_cx=64)
+    tgS = oracle.Target(datagen.Schema(sch.sources[:1], sch.r_T, 20))
+    assert rel(il.ilargi_tmm(splan, dev(Y), precision=il.BF16_IN_F32_ACC).cpu().numpy(), oracle.tmm(tgS, Y)) < OP_TOL
+
+
+def test_bf16_needs_a_wide_operand(il):
+    sch, tg, plan = get(il, "config0")
+    with pytest.raises(il.IlargiError) as ei:
+        il.ilargi_lmm(plan, torch.zeros((sch.c_T, 4), device="cuda"), precision=il.BF16_IN_F32_ACC)
+    assert ei.value.status == il.ERR_UNSUPPORTED
+
+
+def test_bf16_gradient_descent_tracks_float32(il):
+    # no bound is given for weights under bfloat16 inputs ("parity unpinned"); 2e-2 is asserted and reported
+    sch = datagen.config4(r_S=40_007, r_R=4_001, c_R=200, models=32)
+    tg = oracle.Target(sch)
+    y = _labels(sch, tg, "linear")
+    plan = il.ilargi_plan_create(il.schema_to_device(sch), sch.r_T, sch.c_T, max_cx=32)
+    lrs = sch.extras["lr"]
+    m = len(lrs)
+    W = torch.zeros((sch.c_T, m), device="cuda")
+    lr = dev(lrs.astype(np.float32)); loss = torch.zeros(m, device="cuda"); yd = dev(y)
+    for _ in range(20):
+        il.ilargi_gd_step(plan, il.LINEAR, W, yd, lr, loss, precision=il.BF16_IN_F32_ACC)
+    W_ref, L_ref = oracle.gd(tg, "linear", y, np.zeros((sch.c_T, m)), lrs, 20)
+    errs = [rel(W.cpu().numpy()[:, j], W_ref[:, j]) for j in range(m)]
+    assert max(errs) < 2e-2, max(errs)
+    # models that have converged sit on the noise floor the input rounding leaves in the residual
+    np.testing.assert_allclose(loss.cpu().numpy(), L_ref[-1], rtol=5e-2, atol=2e-2)
+
+
 # ------------------------------------------------------------------ crossprod
 @pytest.mark.parametrize("name", ALL)
 def test_crossprod(il, name):
