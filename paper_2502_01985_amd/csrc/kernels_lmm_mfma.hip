@@ -49,31 +49,49 @@ __global__ __launch_bounds__(kBlock) void lmm_mfma_kernel(LmmArgs a, MfmaShape s
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) loss_local[nt] = 0.0f;
 
+  auto store_x = [&](int k, int n, float x) {
+    if constexpr (BF16) reinterpret_cast<__bf16*>(Xs)[((k >> 3) * N + n) * 8 + (k & 7)] = (__bf16)x;
+    else Xs[((k >> 2) * N + n) * 4 + (k & 3)] = x;
+  };
+  const bool x_vec = (a.ldx % 4 == 0) && (n0 % 4 == 0) && (reinterpret_cast<uintptr_t>(a.X) % 16 == 0);
   auto load_x = [&](int k0, int kw) {
-    // Xs[(k/4) * N + n][k % 4] = X[colmap[k0 + k], n0 + n]   (zero beyond the table's columns / the slab).
-    // Eight elements per thread at a time: all col_map loads, then all operand loads, then the LDS stores.
-    for (int e0 = tid; e0 < kw * N; e0 += 8 * kBlock) {
+    // Xs <- X[colmap[k0 + k], n0 + n]  (zero beyond the table's columns / the slab).  An item is four
+    // consecutive operand columns of one k; eight items per thread at a time: all col_map loads, then all
+    // operand loads, then the LDS stores.
+    constexpr int NQ = N / 4;
+    const int items = kw * NQ;
+    for (int e0 = tid; e0 < items; e0 += 8 * kBlock) {
       int tcol[8];
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
         int e = e0 + u * kBlock;
-        int k = e / N, n = e - k * N;
-        tcol[u] = (e < kw * N && k0 + k < a.ck && n < nw) ? a.colmap[k0 + k] : -1;
+        int k = e / NQ;
+        tcol[u] = (e < items && k0 + k < a.ck) ? a.colmap[k0 + k] : -1;
       }
-      float xv[8];
+      float4 xv[8];
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
         int e = e0 + u * kBlock;
-        int n = e % N;
-        xv[u] = tcol[u] >= 0 ? a.X[(int64_t)tcol[u] * a.ldx + n0 + n] : 0.0f;
+        int nq = e % NQ;
+        xv[u] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        if (tcol[u] >= 0 && 4 * nq < nw) {
+          const float* p = a.X + (int64_t)tcol[u] * a.ldx + n0 + 4 * nq;
+          if (x_vec && 4 * nq + 3 < nw) {
+            xv[u] = *reinterpret_cast<const float4*>(p);
+          } else {
+            xv[u].x = p[0];
+            if (4 * nq + 1 < nw) xv[u].y = p[1];
+            if (4 * nq + 2 < nw) xv[u].z = p[2];
+            if (4 * nq + 3 < nw) xv[u].w = p[3];
+          }
+        }
       }
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
         int e = e0 + u * kBlock;
-        int k = e / N, n = e - k * N;
-        if (e < kw * N) {
-          if constexpr (BF16) reinterpret_cast<__bf16*>(Xs)[((k >> 3) * N + n) * 8 + (k & 7)] = (__bf16)xv[u];
-          else Xs[((k >> 2) * N + n) * 4 + (k & 3)] = xv[u];
+        if (e < items) {
+          int k = e / NQ, n = 4 * (e - k * NQ);
+          store_x(k, n, xv[u].x); store_x(k, n + 1, xv[u].y); store_x(k, n + 2, xv[u].z); store_x(k, n + 3, xv[u].w);
         }
       }
     }
@@ -299,7 +317,8 @@ hipError_t launch_lmm_mfma(const LmmArgs& a, int vec, int mode, bool bf16, hipSt
   const int nt = a.ncols <= 16 ? 1 : (a.ncols <= 32 ? 2 : 4);
   const MfmaShape sh = lmm_mfma_shape(a.ck, nt, a.g.n > 0, bf16);
   int64_t nblocks = (a.r_out + sh.rb - 1) / sh.rb;
-  int gx = (int)std::min<int64_t>(nblocks, 1024);
+  // wide slabs stage tens of KiB of operand per workgroup: give each workgroup several row blocks
+  int gx = (int)std::min<int64_t>(nblocks, nt == 4 ? 256 : 1024);
   int gy = (a.ncols + nt * 16 - 1) / (nt * 16);
   if (grid_out) *grid_out = gx;
   dim3 grid(gx, gy);

@@ -350,10 +350,12 @@ __global__ __launch_bounds__(kBlock) void colasm_kernel(ColAsmArgs a) {
     else a.out[e] = a.out[e] - a.lr[n] * (acc * a.inv_rT);
   }
   if constexpr (MODE == 1) {
-    // loss[n] = scale * sum of the per-workgroup partials, lanes stride the partials, fixed butterfly
-    if (a.loss != nullptr && blockIdx.x == 0) {
-      const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
-      for (int n = wave; n < a.cx; n += kBlock / kWave) {
+    // loss[n] = scale * sum of the per-workgroup partials: wavefront w of the grid owns columns w, w + W, ...;
+    // its lanes stride the partials, fixed butterfly
+    if (a.loss != nullptr) {
+      const int lane = threadIdx.x % kWave;
+      const int gw = blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave, nw = gridDim.x * (kBlock / kWave);
+      for (int n = gw; n < a.cx; n += nw) {
         float s = 0.0f;
         for (int b = lane; b < a.n_loss_partial; b += kWave) s += a.loss_partial[(int64_t)b * a.cx + n];
         for (int m = kWave / 2; m >= 1; m >>= 1) s += __shfl_xor(s, m);
