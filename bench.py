@@ -192,15 +192,90 @@ def run_sweep(il, torch, datagen, dev, path):
         json.dump(rows, f, indent=1)
 
 
+def kernel_model(shp, r_T, c_T):
+    """Algorithmic bytes (or flops) of one launch of each traced kernel of the step, keyed by trace name."""
+    (r_S, c_S, _), (r_R, c_R, _) = shp[0], shp[1]
+    m = {}
+    for c in (1, 16):
+        w = 4 * c
+        m[f"lmm_c{c}/lmm_rows:1"] = ("hbm", 4 * r_R * c_R + w * r_R + w * c_R)               # R once, P_R written, X_R
+        m[f"lmm_c{c}/lmm_assemble"] = ("hbm", 4 * r_S * c_S + 4 * r_T + 2 * w * r_T + w * c_S)  # S once, fk, P rows, out
+        m[f"tmm_c{c}/segsum:1"] = ("hbm", 4 * r_T + w * r_T + 4 * (r_R + 1) + w * r_R)         # perm, Y rows, rowptr, Z_R
+        m[f"tmm_c{c}/colred:0"] = ("hbm", 4 * r_S * c_S + w * r_T)                             # S once, Y
+        m[f"tmm_c{c}/colred:1"] = ("hbm", 4 * r_R * c_R + w * r_R)                             # R once, Z_R
+    m["gd_step/lmm_rows:1"] = m["lmm_c1/lmm_rows:1"]
+    m["gd_step/lmm_assemble"] = ("hbm", 4 * r_S * c_S + 4 * r_T * 4 + 4 * c_S)                 # S once, fk, P, y, E written
+    m["gd_step/segsum:1"] = m["tmm_c1/segsum:1"]
+    m["gd_step/colred:1"] = m["tmm_c1/colred:1"]
+    m["materialize/materialize"] = ("hbm", bytes_materialize(shp, r_T, c_T))
+    return m
+
+
+def wide_batch(il, torch, datagen, dev):
+    """The batched hyper-parameter workload (256 linear regressions at once on the same schema, seed 4):
+    gradient-descent iterations/s and matrix-core utilisation, float32 and bfloat16 inputs, factorized vs
+    materialized.  Flops are the algorithmic ones of Alg. 1: 2 products x 2 m (sum_k r_k c_k)."""
+    sch = datagen.config4()
+    m = 256
+    plan = il.ilargi_plan_create(il.schema_to_device(sch), sch.r_T, sch.c_T, max_cx=m)
+    T = il.ilargi_materialize(plan)
+    mplan = il.ilargi_plan_create([(T, None, np.arange(sch.c_T, dtype=np.int32))], sch.r_T, sch.c_T, max_cx=m)
+    W = torch.zeros((sch.c_T, m), device="cuda")
+    y = torch.randn(sch.r_T, device="cuda")
+    lr = dev(sch.extras["lr"].astype(np.float32))
+    loss = torch.zeros(m, device="cuda")
+    fl_fact = 4 * m * sum(s.rows * s.cols for s in sch.sources)
+    fl_mat = 4 * m * sch.r_T * sch.c_T
+    peaks = {"f32": 157.3e12, "bf16": 2.5e15}
+    out = {}
+    for prec, pn in ((il.F32, "f32"), (il.BF16_IN_F32_ACC, "bf16")):
+        for nm, pl, fl in (("factorized", plan, fl_fact), ("materialized", mplan, fl_mat)):
+            W.zero_()
+            t = time_loop(torch, lambda: il.ilargi_gd_step(pl, il.LINEAR, W, y, lr, loss, precision=prec), 10)
+            out[f"{pn}_{nm}"] = {"gd_it_per_s": round(1.0 / t, 1), "ms_per_iteration": round(t * 1e3, 3),
+                                 "TFLOPs": round(fl / t / 1e12, 2), "mfma_frac": round(fl / t / peaks[pn], 4)}
+    out["flops_per_iteration"] = {"factorized": fl_fact, "materialized": fl_mat}
+    out["note"] = ("m = 256 models; the r_T x m residual (1 GB) is written once and read twice per iteration, "
+                   "so the factorized step is bound by HBM traffic rather than by the matrix cores")
+    return out
+
+
+def stream_probe(il, torch):
+    """What plain streaming kernels reach on this device (1 GiB buffers)."""
+    n = 1 << 28
+    src = torch.empty(n, device="cuda").normal_()
+    dst = torch.empty(n, device="cuda")
+    sink = torch.empty(65536, device="cuda")
+    res = {}
+    for kind, name, factor in ((1, "read", 1), (2, "write", 1), (0, "copy", 2)):
+        d = sink if kind == 1 else dst
+        t = time_loop(torch, lambda: il.ilargi_stream_probe(kind, d, src, n, 8192), 10)
+        res[f"{name}_GBps"] = round(factor * n * 4 / t / 1e9, 1)
+    return res
+
+
+def read_traffic_file(path, kernel):
+    """Measured HBM traffic per launch from a committed profiler summary: a line
+    '<kernel name> traffic_bytes_per_launch: <N>'."""
+    try:
+        for line in open(path):
+            if line.startswith(kernel + " ") and "traffic_bytes_per_launch:" in line:
+                return int(float(line.split("traffic_bytes_per_launch:")[1].split()[0]))
+    except OSError:
+        pass
+    return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--trace", default="lmm_rows:1", help="kernel family timed for the roofline entry")
     ap.add_argument("--cpu-sample-rows", type=int, default=100_000)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
+    ap.add_argument("--no-wide", action="store_true", help="skip the 256-model batched workload")
     ap.add_argument("--sweep", default="", help="also run the TR/FR sweep and write it to this JSON file")
+    ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "dominant_kernel_traffic.txt"))
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives are part of it); use --gpus 1",
@@ -228,22 +303,53 @@ def main() -> int:
     ops, keep = make_ops(il, torch, plan, sch, dev)
     step_bytes = sum(b for _, _, b in ops)
 
-    def step():
-        for _, fn, _ in ops:
+    def step(label=False):
+        for name, fn, _ in ops:
+            if label:
+                il.ilargi_plan_trace_label(plan, name)
             fn()
 
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    il.ilargi_plan_trace_begin(plan, args.trace, 4096)
-    torch.cuda.synchronize()
+    # an untraced run of the same length, for the cost of the event pairs
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
+    untraced = (time.perf_counter() - t0) / args.steps
+    # the timed region: every kernel launch bracketed by HIP events on the launch stream
+    il.ilargi_plan_trace_begin(plan, "*", 64 * args.steps + 64)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(label=True)
+    torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    kernel_ms = il.ilargi_plan_trace_end(plan, 4096)
+    kernel_ms, kernel_names = il.ilargi_plan_trace_end(plan, 64 * args.steps + 64, names=True)
     ms_per_step = elapsed / args.steps * 1e3
+
+    per_kernel = {}
+    for nm, ms in zip(kernel_names, kernel_ms):
+        per_kernel.setdefault(nm, []).append(float(ms))
+    model = kernel_model(shp, sch.r_T, sch.c_T)
+    kernels = {}
+    for nm, v in per_kernel.items():
+        avg = float(np.mean(v))
+        rec = {"launches": len(v), "avg_us": round(avg * 1e3, 2), "us_per_step": round(sum(v) / args.steps * 1e3, 2)}
+        if nm in model:
+            rec["algorithmic_MB"] = round(model[nm][1] / 1e6, 2)
+            rec["GBps"] = round(model[nm][1] / (avg * 1e-3) / 1e9, 1)
+            rec["hbm_frac"] = round(rec["GBps"] / HBM_PEAK_GBPS, 4)
+        kernels[nm] = rec
+    # the dominant kernel: largest share of the step among the kernels with a byte model
+    dom = max((k for k in kernels if k in model), key=lambda k: kernels[k]["us_per_step"])
+    dk = kernels[dom]
+    roofline = {"bound": "hbm", "kernel": dom, "achieved": dk["GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": dk["hbm_frac"], "traffic": read_traffic_file(args.traffic_file, dom),
+                "avg_launch_us": dk["avg_us"], "launches_timed": dk["launches"],
+                "algorithmic_bytes_per_launch": int(model[dom][1]),
+                "share_of_step": round(dk["us_per_step"] / (ms_per_step * 1e3), 4)}
 
     # per-operator times inside a running step (every operator starts on data the previous ones evicted)
     n_ev = 10
@@ -281,33 +387,16 @@ def main() -> int:
         o1 = torch.empty((sch.r_T, c), device="cuda"); o2 = torch.empty((sch.c_T, c), device="cuda")
         mat_ops[f"lmm_c{c}_us"] = round(time_loop(torch, lambda: il.ilargi_lmm(mplan, X, o1), 10) * 1e6, 1)
         mat_ops[f"tmm_c{c}_us"] = round(time_loop(torch, lambda: il.ilargi_tmm(mplan, Y, o2), 10) * 1e6, 1)
+    del mplan
 
-    # roofline of the traced kernel family
-    r_R, c_R = shp[1][0], shp[1][1]
-    kernel_bytes = {
-        "lmm_rows:1": 4 * r_R * c_R + 4 * r_R + 4 * c_R,                       # R once, P_R written, X_R
-        "colred:1": 4 * r_R * c_R + 4 * r_R + 4 * 1024 * c_R * 4,              # R once, Z_R read, partials
-        "lmm_assemble": 4 * shp[0][0] * shp[0][1] + 12 * sch.r_T,               # S once, fk, gathered P, out
-        "colred:0": 4 * shp[0][0] * shp[0][1] + 4 * sch.r_T,
-        "materialize": bytes_materialize(shp, sch.r_T, sch.c_T),
-    }
-    roofline = None
-    if kernel_ms.size:
-        # the family is launched by several operators of the step (cx = 1, cx = 16, gradient descent);
-        # the cx = 1 launches are the ones the byte figure above describes: they are the shortest third
-        per_launch = np.sort(kernel_ms)
-        sel = per_launch[: max(1, per_launch.size // 3)] if args.trace in ("lmm_rows:1", "colred:1", "lmm_assemble", "colred:0") else per_launch
-        avg_ms = float(np.mean(sel))
-        kb = kernel_bytes.get(args.trace)
-        if kb:
-            ach = kb / (avg_ms * 1e-3) / 1e9
-            roofline = {"bound": "hbm", "kernel": args.trace, "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS,
-                        "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": None,
-                        "avg_launch_us": round(avg_ms * 1e3, 2), "launches_timed": int(sel.size),
-                        "algorithmic_bytes_per_launch": int(kb)}
-
+    probe = stream_probe(il, torch)
     if args.sweep:
         run_sweep(il, torch, datagen, dev, args.sweep)
+    wide = None
+    if not args.no_wide:
+        del plan, ops, keep, Tm
+        torch.cuda.empty_cache()
+        wide = wide_batch(il, torch, datagen, dev)
 
     cpu = None if args.no_cpu else cpu_baseline(sch, args.cpu_sample_rows)
 
@@ -324,6 +413,7 @@ def main() -> int:
                    "seed": 1, "tuple_ratio": 10, "feature_ratio": 10,
                    "complexity_ratio_eq1": round(complexity_ratio_lr(shp, sch.r_T, sch.c_T), 3)},
         "hbm_frac_of_step": round(step_bytes / (elapsed / args.steps) / 1e9 / HBM_PEAK_GBPS, 4),
+        "ms_per_step_untraced": round(untraced * 1e3, 4),
         "step_algorithmic_MB": round(step_bytes / 1e6, 1),
         "lmm_tmm_GBps": round(lt_bytes / lt_time_cold / 1e9, 1),
         "lmm_tmm_hbm_frac": round(lt_bytes / lt_time_cold / 1e9 / HBM_PEAK_GBPS, 4),
@@ -337,6 +427,9 @@ def main() -> int:
                                          if t_fact > t_mat else 0)},
         "materialized_ops": mat_ops,
         "plan_build_ms": round(plan_ms, 2),
+        "kernels": dict(sorted(kernels.items(), key=lambda kv: -kv[1]["us_per_step"])[:16]),
+        "stream_probe": probe,
+        "wide_batch": wide,
         "roofline": roofline,
         "cpu_baseline": cpu,
     }

@@ -128,14 +128,18 @@ ilargi_status_t ilargi_plan_inverse_index(const ilargi_plan_t* plan, int k, cons
                                           const int32_t** perm, int64_t* nnz);
 
 /* Per-kernel timing for benchmarks.  After trace_begin, every launch of the kernel family named by
- * `tag` is bracketed by a pair of HIP events on the call's stream (at most max_launches pairs; later
- * launches run untimed).  Tags: "lmm_rows:<k>" (product of source k), "lmm_assemble", "segsum:<k>",
- * "colred:<k>", "finalize", "materialize", "gram".  trace_end waits for the recorded events, writes
- * the elapsed milliseconds of up to `capacity` launches to the host array `ms` (may be NULL), stores
- * the number of recorded launches in *count and switches tracing off.  Events are host objects; no
- * device memory is allocated. */
+ * `tag` ("*" = every family) is bracketed by a pair of HIP events on the call's stream (at most
+ * max_launches pairs; later launches run untimed).  Families: "lmm_rows:<k>" (product of source k),
+ * "lmm_assemble", "segsum:<k>", "colred:<k>", "finalize", "materialize", "gram".  trace_label sets a
+ * prefix ("<label>/<family>") for the launches that follow, so a caller can tell its operators apart.
+ * trace_end waits for the recorded events, writes the elapsed milliseconds of up to `capacity`
+ * launches to the host array `ms` (may be NULL), stores the number of recorded launches in *count
+ * and switches tracing off; trace_name copies the name of recorded launch i (valid until the next
+ * trace_begin).  Events are host objects; no device memory is allocated. */
 ilargi_status_t ilargi_plan_trace_begin(ilargi_plan_t* plan, const char* tag, int max_launches);
+ilargi_status_t ilargi_plan_trace_label(ilargi_plan_t* plan, const char* label);
 ilargi_status_t ilargi_plan_trace_end(ilargi_plan_t* plan, float* ms, int capacity, int* count);
+ilargi_status_t ilargi_plan_trace_name(const ilargi_plan_t* plan, int i, char* buf, int buf_len);
 
 /* Plain streaming kernels for calibration (what the memory system delivers, and the scale of the
  * profiler's byte counters): kind 0 copies n_floats floats src -> dst, kind 1 only reads src (dst

@@ -38,7 +38,8 @@ STATUS_NAMES = ["OK", "ERR_NULL", "ERR_SHAPE", "ERR_COLMAP", "ERR_INDEX_RANGE", 
 EXPORTED = [
     "ilargi_plan_workspace_bytes", "ilargi_plan_create", "ilargi_plan_destroy", "ilargi_lmm", "ilargi_tmm",
     "ilargi_crossprod", "ilargi_materialize", "ilargi_gd_step", "ilargi_segment_sum",
-    "ilargi_plan_inverse_index", "ilargi_plan_trace_begin", "ilargi_plan_trace_end", "ilargi_stream_probe",
+    "ilargi_plan_inverse_index", "ilargi_plan_trace_begin", "ilargi_plan_trace_label", "ilargi_plan_trace_end",
+    "ilargi_plan_trace_name", "ilargi_stream_probe",
     "ilargi_last_error",
     "ilargi_version",
 ]
@@ -64,6 +65,8 @@ lib.ilargi_segment_sum.argtypes = [_vp, _int, _vp, _i64, _vp, _vp]
 lib.ilargi_plan_inverse_index.argtypes = [_vp, _int, ctypes.POINTER(_vp), ctypes.POINTER(_vp), ctypes.POINTER(_i64)]
 lib.ilargi_plan_trace_begin.argtypes = [_vp, ctypes.c_char_p, _int]
 lib.ilargi_plan_trace_end.argtypes = [_vp, ctypes.POINTER(ctypes.c_float), _int, ctypes.POINTER(_int)]
+lib.ilargi_plan_trace_label.argtypes = [_vp, ctypes.c_char_p]
+lib.ilargi_plan_trace_name.argtypes = [_vp, _int, ctypes.c_char_p, _int]
 lib.ilargi_stream_probe.argtypes = [_int, _vp, _vp, _i64, _int, _vp]
 for _name in EXPORTED[:-2]:
     getattr(lib, _name).restype = _int
@@ -285,12 +288,25 @@ def ilargi_plan_trace_begin(plan: Plan, tag: str, max_launches: int) -> None:
     _check(lib.ilargi_plan_trace_begin(plan.handle, tag.encode(), max_launches), "ilargi_plan_trace_begin")
 
 
-def ilargi_plan_trace_end(plan: Plan, capacity: int):
-    """Elapsed milliseconds of the traced launches (numpy float32 array)."""
+def ilargi_plan_trace_label(plan: Plan, label: str) -> None:
+    _check(lib.ilargi_plan_trace_label(plan.handle, label.encode()), "ilargi_plan_trace_label")
+
+
+def ilargi_plan_trace_end(plan: Plan, capacity: int, names: bool = False):
+    """Elapsed milliseconds of the traced launches (numpy float32 array); with ``names`` also their names."""
     buf = (ctypes.c_float * max(capacity, 1))()
     cnt = _int(0)
+    got = []
+    if names:
+        # names have to be read before trace_end releases the events' bookkeeping of this run
+        i = 0
+        nb = ctypes.create_string_buffer(128)
+        while lib.ilargi_plan_trace_name(plan.handle, i, nb, 128) == OK:
+            got.append(nb.value.decode())
+            i += 1
     _check(lib.ilargi_plan_trace_end(plan.handle, buf, capacity, ctypes.byref(cnt)), "ilargi_plan_trace_end")
-    return np.array(buf[:min(cnt.value, capacity)], dtype=np.float32)
+    ms = np.array(buf[:min(cnt.value, capacity)], dtype=np.float32)
+    return (ms, got[:len(ms)]) if names else ms
 
 
 def ilargi_stream_probe(kind: int, dst, src, n_floats: int, blocks: int = 4096, stream=None) -> None:

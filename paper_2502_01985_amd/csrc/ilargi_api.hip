@@ -74,8 +74,10 @@ struct ilargi_plan {
   int npairs = 0;
   std::vector<size_t> block_off;  // offset (floats) of Gram block (k,l), k <= l, index k * n + l
   // optional timing of one kernel family: event pairs recorded around every launch whose tag matches
-  std::string trace_tag;
+  std::string trace_tag;            // "*" traces every kernel family
+  std::string trace_label;          // caller's label for the operator in flight
   std::vector<hipEvent_t> trace_events;
+  std::vector<std::string> trace_names;
   int trace_n = 0;
   template <class T> T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
   ~ilargi_plan() { for (hipEvent_t e : trace_events) (void)hipEventDestroy(e); }
@@ -93,11 +95,14 @@ struct TraceScope {
     char full[64];
     if (k >= 0) snprintf(full, sizeof(full), "%s:%d", tag, k);
     else snprintf(full, sizeof(full), "%s", tag);
-    if (p->trace_tag != full) return;
+    if (p->trace_tag != "*" && p->trace_tag != full) return;
     on = hipEventRecord(p->trace_events[p->trace_n], st) == hipSuccess;
+    if (on) p->trace_names.push_back(p->trace_label.empty() ? std::string(full) : p->trace_label + "/" + full);
   }
   ~TraceScope() {
-    if (on && hipEventRecord(pl->trace_events[pl->trace_n + 1], st) == hipSuccess) pl->trace_n += 2;
+    if (!on) return;
+    if (hipEventRecord(pl->trace_events[pl->trace_n + 1], st) == hipSuccess) pl->trace_n += 2;
+    else pl->trace_names.pop_back();
   }
 };
 
@@ -620,6 +625,7 @@ ilargi_status_t ilargi_plan_trace_begin(ilargi_plan_t* plan, const char* tag, in
   if (max_launches < 1 || max_launches > (1 << 20)) return fail(ILARGI_ERR_SHAPE, "trace_begin: max_launches = %d", max_launches);
   for (hipEvent_t e : plan->trace_events) (void)hipEventDestroy(e);
   plan->trace_events.clear();
+  plan->trace_names.clear();
   plan->trace_n = 0;
   plan->trace_tag = tag;
   for (int i = 0; i < 2 * max_launches; ++i) {
@@ -627,6 +633,19 @@ ilargi_status_t ilargi_plan_trace_begin(ilargi_plan_t* plan, const char* tag, in
     HIP_TRY(hipEventCreate(&e));
     plan->trace_events.push_back(e);
   }
+  return ILARGI_OK;
+}
+
+ilargi_status_t ilargi_plan_trace_label(ilargi_plan_t* plan, const char* label) {
+  if (plan == nullptr) return fail(ILARGI_ERR_NULL, "trace_label: plan is NULL");
+  plan->trace_label = label ? label : "";
+  return ILARGI_OK;
+}
+
+ilargi_status_t ilargi_plan_trace_name(const ilargi_plan_t* plan, int i, char* buf, int buf_len) {
+  if (plan == nullptr || buf == nullptr) return fail(ILARGI_ERR_NULL, "trace_name: NULL argument");
+  if (i < 0 || i >= (int)plan->trace_names.size() || buf_len < 1) return fail(ILARGI_ERR_SHAPE, "trace_name: index %d", i);
+  snprintf(buf, (size_t)buf_len, "%s", plan->trace_names[(size_t)i].c_str());
   return ILARGI_OK;
 }
 
@@ -642,6 +661,7 @@ ilargi_status_t ilargi_plan_trace_end(ilargi_plan_t* plan, float* ms, int capaci
   plan->trace_events.clear();
   plan->trace_n = 0;
   plan->trace_tag.clear();
+  plan->trace_label.clear();
   return ILARGI_OK;
 }
 
