@@ -128,7 +128,7 @@ ilargi_status_t ilargi_plan_inverse_index(const ilargi_plan_t* plan, int k, cons
                                           const int32_t** perm, int64_t* nnz);
 
 /* Per-kernel timing for benchmarks.  After trace_begin, every launch of the kernel family named by
- * `tag` ("*" = every family) is bracketed by a pair of HIP events on the call's stream (at most
+ * `tag` ("*" = every family; "<label>/<family>" = that family under one label) is bracketed by a pair of HIP events on the call's stream (at most
  * max_launches pairs; later launches run untimed).  Families: "lmm_rows:<k>" (product of source k),
  * "lmm_assemble", "segsum:<k>", "colred:<k>", "finalize", "materialize", "gram".  trace_label sets a
  * prefix ("<label>/<family>") for the launches that follow, so a caller can tell its operators apart.

@@ -95,9 +95,10 @@ struct TraceScope {
     char full[64];
     if (k >= 0) snprintf(full, sizeof(full), "%s:%d", tag, k);
     else snprintf(full, sizeof(full), "%s", tag);
-    if (p->trace_tag != "*" && p->trace_tag != full) return;
+    std::string name = p->trace_label.empty() ? std::string(full) : p->trace_label + "/" + full;
+    if (p->trace_tag != "*" && p->trace_tag != full && p->trace_tag != name) return;
     on = hipEventRecord(p->trace_events[p->trace_n], st) == hipSuccess;
-    if (on) p->trace_names.push_back(p->trace_label.empty() ? std::string(full) : p->trace_label + "/" + full);
+    if (on) p->trace_names.push_back(name);
   }
   ~TraceScope() {
     if (!on) return;
