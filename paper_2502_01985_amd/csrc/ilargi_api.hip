@@ -376,9 +376,16 @@ ilargi_status_t run_tred(ilargi_plan* pl, TredArgs& g, float* block, const char*
                          hipStream_t st) {
   int64_t elems = (int64_t)g.ca * g.cb;
   if (elems <= 0) return ILARGI_OK;
-  int64_t nch = (g.n_rows + 255) / 256;
-  nch = std::min<int64_t>(nch, std::max<int64_t>(1, pl->lay.gpartial_floats / elems));
-  nch = std::min<int64_t>(std::max<int64_t>(nch, 1), 512);
+  // row chunks: whole rounds of the device's workgroup slots (every workgroup does the same work, so a
+  // partly filled last round would idle most compute units), within the partial buffer, >= 64 rows each
+  int slots = 512, tiles = 1;
+  tred_occupancy(g, bf16, &slots, &tiles);
+  int64_t cap = std::max<int64_t>(1, pl->lay.gpartial_floats / elems);
+  cap = std::min<int64_t>(cap, std::max<int64_t>(1, g.n_rows / 64));
+  cap = std::min<int64_t>(cap, 4096);
+  int64_t nch = std::max<int64_t>(1, slots / tiles);
+  while (nch * 2 <= cap && g.n_rows / (nch * 2) >= 512) nch *= 2;   // more rounds only while chunks stay long
+  nch = std::min(nch, cap);
   g.rows_per_block = (g.n_rows + nch - 1) / nch;
   g.rows_per_block = std::max<int64_t>(16, (g.rows_per_block + 15) / 16 * 16);
   nch = std::max<int64_t>(1, (g.n_rows + g.rows_per_block - 1) / g.rows_per_block);
@@ -614,8 +621,8 @@ ilargi_status_t ilargi_plan_destroy(ilargi_plan_t* plan) {
 }
 
 ilargi_status_t ilargi_stream_probe(int kind, float* dst, const float* src, int64_t n_floats, int blocks, void* stream) {
-  if (kind < 0 || kind > 2) return fail(ILARGI_ERR_UNSUPPORTED, "stream_probe: kind %d", kind);
-  if (dst == nullptr || (kind != 2 && src == nullptr)) return fail(ILARGI_ERR_NULL, "stream_probe: NULL buffer");
+  if (kind < 0 || kind > 4) return fail(ILARGI_ERR_UNSUPPORTED, "stream_probe: kind %d", kind);
+  if (dst == nullptr || (kind != 2 && kind != 4 && src == nullptr)) return fail(ILARGI_ERR_NULL, "stream_probe: NULL buffer");
   if (n_floats < 0 || n_floats % 4 != 0 || blocks < 1 || blocks > 65536) return fail(ILARGI_ERR_SHAPE, "stream_probe: bad size");
   HIP_TRY(launch_probe(kind, dst, src, n_floats, blocks, static_cast<hipStream_t>(stream)));
   return ILARGI_OK;

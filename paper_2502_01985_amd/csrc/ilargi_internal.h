@@ -18,7 +18,7 @@ constexpr int kLongSeg = 2048;       // inverse-index segments longer than this 
 constexpr int kSegChunk = 2048;      // ... into chunks of this many entries
 constexpr int kSortChunk = 2048;     // keys per workgroup in one radix pass
 constexpr int kMaxLdsFloats = 4096;  // 16 KiB of LDS for the staged operand rows (also the column limit of a source)
-constexpr int64_t kGramPartialFloats = 4ll << 20;
+constexpr int64_t kGramPartialFloats = 16ll << 20;
 
 // Row gathers of per-source products:  out[i,:] += P_s[row_s(i), :]  (assembly step of Sec. 2.2).
 struct GatherArgs {
@@ -177,6 +177,7 @@ hipError_t launch_gram_reduce(const float* partial, int nchunks, int64_t elems, 
 hipError_t launch_gram_assemble(const GramAsmPair* pairs_dev, int npairs, const int32_t* const* tcol2src_dev,
                                 int c_T, float* out, hipStream_t st);
 hipError_t launch_tred(const TredArgs& a, int nchunks, bool bf16, hipStream_t st);
+void tred_occupancy(const TredArgs& a, bool bf16, int* slots, int* tiles);
 hipError_t launch_tred_reduce(const float* partial, int nchunks, int64_t elems, float* block, hipStream_t st);
 hipError_t launch_colasm(const ColAsmArgs& a, int mode, hipStream_t st);
 hipError_t launch_probe(int kind, float* dst, const float* src, int64_t n_floats, int blocks, hipStream_t st);

@@ -106,8 +106,10 @@ __global__ __launch_bounds__(kBlock) void materialize_vec4_kernel(MatArgs a) {
         int g = lane + q * kWave;
         if (g < ngroups) {
           // 0.0f + x: a source cell holding -0.0 becomes +0.0, as in the sum that defines the cell
-          float4 o = make_float4(0.0f + v[u][q].x, 0.0f + v[u][q].y, 0.0f + v[u][q].z, 0.0f + v[u][q].w);
-          *reinterpret_cast<float4*>(a.T + i * a.c_T + 4 * g) = o;
+          typedef float f4 __attribute__((ext_vector_type(4)));
+          f4 o = {0.0f + v[u][q].x, 0.0f + v[u][q].y, 0.0f + v[u][q].z, 0.0f + v[u][q].w};
+          // the table is written once and not read back here: keep it out of the caches' way
+          __builtin_nontemporal_store(o, reinterpret_cast<f4*>(a.T + i * a.c_T + 4 * g));
         }
       }
     }
@@ -123,7 +125,7 @@ hipError_t launch_materialize(const MatArgs& a, hipStream_t st) {
   if (fast) {
     int64_t waves = (a.r_T + kMatRows - 1) / kMatRows;
     int64_t grid = (waves + (kBlock / kWave) - 1) / (kBlock / kWave);
-    if (grid > 4096) grid = 4096;
+    if (grid > 65536) grid = 65536;
     materialize_vec4_kernel<<<(int)grid, kBlock, 0, st>>>(a);
   } else {
     int64_t grid = (a.r_T + (kBlock / kWave) - 1) / (kBlock / kWave);

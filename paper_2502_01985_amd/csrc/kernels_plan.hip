@@ -230,9 +230,23 @@ __global__ __launch_bounds__(kBlock) void probe_write_kernel(float4* __restrict_
     dst[i] = make_float4(1.0f, 2.0f, 3.0f, 4.0f);
 }
 
+typedef float nt4 __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(kBlock) void probe_copy_nt_kernel(nt4* __restrict__ dst, const nt4* __restrict__ src,
+                                                               int64_t n4) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += (int64_t)gridDim.x * blockDim.x)
+    __builtin_nontemporal_store(__builtin_nontemporal_load(&src[i]), &dst[i]);
+}
+__global__ __launch_bounds__(kBlock) void probe_write_nt_kernel(nt4* __restrict__ dst, int64_t n4) {
+  nt4 v = {1.0f, 2.0f, 3.0f, 4.0f};
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += (int64_t)gridDim.x * blockDim.x)
+    __builtin_nontemporal_store(v, &dst[i]);
+}
+
 hipError_t launch_probe(int kind, float* dst, const float* src, int64_t n_floats, int blocks, hipStream_t st) {
   int64_t n4 = n_floats / 4;
   if (n4 <= 0) return hipSuccess;
+  if (kind == 3) { probe_copy_nt_kernel<<<blocks, kBlock, 0, st>>>((nt4*)dst, (const nt4*)src, n4); return hipGetLastError(); }
+  if (kind == 4) { probe_write_nt_kernel<<<blocks, kBlock, 0, st>>>((nt4*)dst, n4); return hipGetLastError(); }
   if (kind == 0) probe_copy_kernel<<<blocks, kBlock, 0, st>>>((float4*)dst, (const float4*)src, n4);
   else if (kind == 1) probe_read_kernel<<<blocks, kBlock, 0, st>>>((const float4*)src, n4, dst);
   else probe_write_kernel<<<blocks, kBlock, 0, st>>>((float4*)dst, n4);

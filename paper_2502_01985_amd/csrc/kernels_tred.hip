@@ -367,47 +367,95 @@ __global__ __launch_bounds__(kBlock) void colasm_kernel(ColAsmArgs a) {
 
 }  // namespace
 
-hipError_t launch_tred(const TredArgs& a, int nchunks, bool bf16, hipStream_t st) {
-  if (a.ca <= 0 || a.cb <= 0 || nchunks <= 0) return hipSuccess;
+namespace {
+
+using TredFn = void (*)(TredArgs);
+
+struct TredChoice {
+  TredFn fn;
+  int tiles;        // workgroups per row chunk (tiles that are actually computed)
+};
+
+// Kernel variant and tile count for these shapes.
+TredChoice tred_select(const TredArgs& a, bool bf16) {
   const bool vec4 = a.lda % 4 == 0 && a.ca % 4 == 0 && reinterpret_cast<uintptr_t>(a.A) % 16 == 0;
-  int nt = a.cb <= 16 ? 1 : (a.cb <= 32 ? 2 : 4);
+  const int nt = a.cb <= 16 ? 1 : (a.cb <= 32 ? 2 : 4);
+  const int b_slabs = (a.cb + nt * 16 - 1) / (nt * 16);
+  TredChoice c{nullptr, 1};
   if (bf16) {
-    dim3 gridb(nchunks, ((a.ca + 63) / 64) * ((a.cb + nt * 16 - 1) / (nt * 16)));
-#define ILARGI_TB(N)                                                                 \
-  do {                                                                               \
-    if (vec4) tred_bf16_kernel<N, true><<<gridb, kBlock, 0, st>>>(a);                \
-    else tred_bf16_kernel<N, false><<<gridb, kBlock, 0, st>>>(a);                    \
-  } while (0)
-    if (nt == 1) ILARGI_TB(1); else if (nt == 2) ILARGI_TB(2); else ILARGI_TB(4);
-#undef ILARGI_TB
-    return hipGetLastError();
+    c.tiles = ((a.ca + 63) / 64) * b_slabs;
+    if (nt == 1) c.fn = vec4 ? tred_bf16_kernel<1, true> : tred_bf16_kernel<1, false>;
+    else if (nt == 2) c.fn = vec4 ? tred_bf16_kernel<2, true> : tred_bf16_kernel<2, false>;
+    else c.fn = vec4 ? tred_bf16_kernel<4, true> : tred_bf16_kernel<4, false>;
+    return c;
   }
   if (a.ca <= 48) {
     const int jtd = (a.ca + 15) / 16;
-    dim3 gridd(nchunks, (a.cb + nt * 16 - 1) / (nt * 16));
-#define ILARGI_TDW(J, N) tred_dw_kernel<J, N><<<gridd, kBlock, 0, st>>>(a)
-    if (jtd == 1) { if (nt == 1) ILARGI_TDW(1, 1); else if (nt == 2) ILARGI_TDW(1, 2); else ILARGI_TDW(1, 4); }
-    else if (jtd == 2) { if (nt == 1) ILARGI_TDW(2, 1); else if (nt == 2) ILARGI_TDW(2, 2); else ILARGI_TDW(2, 4); }
-    else { if (nt == 1) ILARGI_TDW(3, 1); else if (nt == 2) ILARGI_TDW(3, 2); else ILARGI_TDW(3, 4); }
-#undef ILARGI_TDW
-    return hipGetLastError();
+    c.tiles = b_slabs;
+    static const TredFn table[3][3] = {
+        {tred_dw_kernel<1, 1>, tred_dw_kernel<1, 2>, tred_dw_kernel<1, 4>},
+        {tred_dw_kernel<2, 1>, tred_dw_kernel<2, 2>, tred_dw_kernel<2, 4>},
+        {tred_dw_kernel<3, 1>, tred_dw_kernel<3, 2>, tred_dw_kernel<3, 4>}};
+    c.fn = table[jtd - 1][nt == 1 ? 0 : (nt == 2 ? 1 : 2)];
+    return c;
   }
   int jt = std::min(4 / nt, (a.ca + 63) / 64);
   if (jt == 3) jt = 4;
-  int a_slabs = (a.ca + jt * 64 - 1) / (jt * 64), b_slabs = (a.cb + nt * 16 - 1) / (nt * 16);
-  dim3 grid(nchunks, a_slabs * b_slabs);
-#define ILARGI_TRED(J, N)                                                      \
-  do {                                                                         \
-    if (vec4) tred_kernel<J, N, true><<<grid, kBlock, 0, st>>>(a);             \
-    else tred_kernel<J, N, false><<<grid, kBlock, 0, st>>>(a);                 \
-  } while (0)
-  if (jt == 4) ILARGI_TRED(4, 1);
-  else if (jt == 2 && nt == 2) ILARGI_TRED(2, 2);
-  else if (jt == 2) ILARGI_TRED(2, 1);
-  else if (nt == 4) ILARGI_TRED(1, 4);
-  else if (nt == 2) ILARGI_TRED(1, 2);
-  else ILARGI_TRED(1, 1);
-#undef ILARGI_TRED
+  const int a_slabs = (a.ca + jt * 64 - 1) / (jt * 64);
+  c.tiles = a_slabs * b_slabs;
+#define ILARGI_PICK(J, N) (vec4 ? tred_kernel<J, N, true> : tred_kernel<J, N, false>)
+  if (jt == 4) c.fn = ILARGI_PICK(4, 1);
+  else if (jt == 2 && nt == 2) c.fn = ILARGI_PICK(2, 2);
+  else if (jt == 2) c.fn = ILARGI_PICK(2, 1);
+  else if (nt == 4) c.fn = ILARGI_PICK(1, 4);
+  else if (nt == 2) c.fn = ILARGI_PICK(1, 2);
+  else c.fn = ILARGI_PICK(1, 1);
+#undef ILARGI_PICK
+  return c;
+}
+
+}  // namespace
+
+// Workgroup slots of the device for the variant these shapes select, and how many tiles each row chunk has
+// (tiles the kernel skips for a symmetric result are not counted).  The caller sizes the row chunks so that
+// the launch fills the slots in whole rounds.
+void tred_occupancy(const TredArgs& a, bool bf16, int* slots, int* tiles) {
+  TredChoice c = tred_select(a, bf16);
+  // both queries are cached: they cost far more than a launch
+  static int cus = 0;
+  static TredFn seen_fn[64];
+  static int seen_occ[64];
+  static int n_seen = 0;
+  if (cus == 0) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess && prop.multiProcessorCount > 0)
+      cus = prop.multiProcessorCount;
+  }
+  int per_cu = 0;
+  for (int i = 0; i < n_seen; ++i)
+    if (seen_fn[i] == c.fn) per_cu = seen_occ[i];
+  if (per_cu == 0) {
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(c.fn), kBlock, 0) != hipSuccess || per_cu < 1)
+      per_cu = 2;
+    if (n_seen < 64) { seen_fn[n_seen] = c.fn; seen_occ[n_seen] = per_cu; ++n_seen; }
+  }
+  *slots = per_cu * cus;
+  int t = c.tiles;
+  if (a.upper_only && !bf16 && a.ca > 48) {
+    // 64 x 64 tiles on and above the diagonal
+    int n = (a.ca + 63) / 64;
+    t = n * (n + 1) / 2;
+  }
+  *tiles = t;
+}
+
+hipError_t launch_tred(const TredArgs& a, int nchunks, bool bf16, hipStream_t st) {
+  if (a.ca <= 0 || a.cb <= 0 || nchunks <= 0) return hipSuccess;
+  TredChoice c = tred_select(a, bf16);
+  dim3 grid(nchunks, c.tiles);
+  hipLaunchKernelGGL(c.fn, grid, dim3(kBlock), 0, st, a);
   return hipGetLastError();
 }
 
