@@ -292,6 +292,8 @@ ilargi_status_t lmm_pass(ilargi_plan* pl, const float* X, int ldx, int col0, int
   }
   a.X = X; a.ldx = ldx; a.col0 = col0; a.ncols = ncols;
   a.out = out; a.ldo = ldo; a.r_out = pl->r_T;
+  // results (and residuals) larger than the caches are streamed out past them
+  a.nt_out = (int64_t)pl->r_T * ldo * (int64_t)sizeof(float) >= (64ll << 20);
   a.g = g;
   a.y = y;
   a.loss_partial = pl->at<float>(pl->lay.o_loss);

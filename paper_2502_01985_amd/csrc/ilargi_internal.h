@@ -45,6 +45,7 @@ struct LmmArgs {
   const float* y;         // labels, r_out
   float* loss_partial;    // narrow kernel: [gridDim.x][kNarrowCT]; matrix-core kernel: [gridDim.x][ld_loss]
   int ld_loss;
+  int nt_out;             // store the output with non-temporal stores (large results nobody re-reads soon)
   float* grad_partial;    // narrow kernel, optional: [gridDim.x][ck][kNarrowCT] partials of D^T e
 };
 

@@ -210,7 +210,9 @@ __global__ __launch_bounds__(kBlock) void lmm_rows_kernel(LmmArgs a) {
             r = sigmoidf_stable(z) - yi;
             loss_local[n] += softplusf_stable(z) - yi * z;
           }
-          a.out[irow * a.ldo + a.col0 + n] = r;
+          float* op = a.out + irow * a.ldo + a.col0 + n;
+          if (a.nt_out) __builtin_nontemporal_store(r, op);
+          else *op = r;
           if constexpr (FUSEG) zb[tid * CT + n] = r;
         } else if constexpr (FUSEG) {
           zb[tid * CT + n] = 0.0f;

@@ -263,7 +263,9 @@ __global__ __launch_bounds__(kBlock) void lmm_mfma_kernel(LmmArgs a, MfmaShape s
                 o = sigmoidf_stable(z) - yi;
                 loss_local[nt] += softplusf_stable(z) - yi * z;
               }
-              a.out[row * a.ldo + n0 + nt * 16 + li] = o;
+              float* op = a.out + row * a.ldo + n0 + nt * 16 + li;
+              if (a.nt_out) __builtin_nontemporal_store(o, op);
+              else *op = o;
             }
           }
         }
