@@ -32,7 +32,8 @@ __device__ __forceinline__ float softplusf_stable(float z) {
 // NT: 16-column tiles of the operand slab handled by one workgroup.  MODE as in the narrow kernel.
 // BF16: table and operand values are rounded to bfloat16 (nearest even) when they enter the MFMA
 // (16x16x32, eight K values per lane: lane 16 q + i holds columns 32 step + 8 q .. + 7), sums stay float32.
-template <int NT, int MODE, bool VEC4, bool BF16>
+// SB: global loads a thread keeps in flight while it stages a tile (8, or 16 for tiles of more than 8 float4 per thread).
+template <int NT, int MODE, bool VEC4, bool BF16, int SB>
 __global__ __launch_bounds__(kBlock) void lmm_mfma_kernel(LmmArgs a, MfmaShape sh) {
   extern __shared__ float lds[];
   float* As = lds;                                   // [rb][lda]
@@ -116,11 +117,11 @@ __global__ __launch_bounds__(kBlock) void lmm_mfma_kernel(LmmArgs a, MfmaShape s
           int r = tid / tpr, g = tid - r * tpr;
           const int dr = kBlock / tpr, dg = kBlock - dr * tpr;
           while (r < sh.rb) {
-            // eight loads in flight per thread, then the LDS stores
-            float4 v[8];
-            int rr[8], gg[8];
+            // SB loads in flight per thread, then the LDS stores
+            float4 v[SB];
+            int rr[SB], gg[SB];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
+            for (int u = 0; u < SB; ++u) {
               rr[u] = r; gg[u] = g;
               v[u] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
               int64_t row = row0 + r;
@@ -130,7 +131,7 @@ __global__ __launch_bounds__(kBlock) void lmm_mfma_kernel(LmmArgs a, MfmaShape s
               if (g >= tpr) { g -= tpr; ++r; }
             }
 #pragma unroll
-            for (int u = 0; u < 8; ++u)
+            for (int u = 0; u < SB; ++u)
               if (rr[u] < sh.rb) *reinterpret_cast<float4*>(As + (size_t)rr[u] * sh.lda + 4 * gg[u]) = v[u];
           }
         } else {
@@ -325,9 +326,10 @@ hipError_t launch_lmm_mfma(const LmmArgs& a, int vec, int mode, bool bf16, hipSt
   if (grid_out) *grid_out = gx;
   dim3 grid(gx, gy);
   const bool vec4 = vec == 4;
+  const bool sb16 = vec4 && (int64_t)sh.rb * (sh.kc / 4) > 8 * kBlock;
 #define ILARGI_LAUNCH1(NT_, MODE_, V_, B_)                                                          \
   do {                                                                                              \
-    auto kfn = lmm_mfma_kernel<NT_, MODE_, V_, B_>;                                                 \
+    auto kfn = sb16 ? lmm_mfma_kernel<NT_, MODE_, V_, B_, 16> : lmm_mfma_kernel<NT_, MODE_, V_, B_, 8>; \
     if (sh.lds_bytes > 64 * 1024)                                                                   \
       (void)hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh.lds_bytes); \
     kfn<<<grid, kBlock, sh.lds_bytes, st>>>(a, sh);                                                 \
