@@ -53,7 +53,7 @@ struct SourcePlan {
 };
 
 struct Layout {
-  size_t o_gslot = 0, o_gj0 = 0;
+  size_t o_gslot = 0, o_gj0 = 0, o_ct_slot = 0, o_ct_j = 0;
   size_t o_flags = 0, o_tcol_table = 0, o_pairs = 0, o_E = 0, o_loss = 0, o_sort = 0, o_hist = 0, o_zc = 0,
          o_gpartial = 0, o_blocks = 0;
   int64_t zc_floats = 0, gpartial_floats = 0, blocks_floats = 0;
@@ -71,6 +71,7 @@ struct ilargi_plan {
   Layout lay;
   int fused = -1;   // identity source whose product is fused into the assembly pass
   bool mat_vec4 = false;  // the grouped column tables of the vectorized join-gather are valid
+  bool mat_cols = false;  // the per-column feeder tables (at most two feeders per column) are valid
   int npairs = 0;
   std::vector<size_t> block_off;  // offset (floats) of Gram block (k,l), k <= l, index k * n + l
   // optional timing of one kernel family: event pairs recorded around every launch whose tag matches
@@ -147,6 +148,8 @@ ilargi_status_t make_layout(int n, const ilargi_source_t* s, int64_t r_T, int64_
   lay.o_pairs = take(sizeof(GramAsmPair) * n * (n + 1) / 2);
   lay.o_gslot = take(sizeof(int32_t) * c_T);
   lay.o_gj0 = take(sizeof(int32_t) * c_T);
+  lay.o_ct_slot = take(sizeof(int32_t) * 2 * c_T);
+  lay.o_ct_j = take(sizeof(int32_t) * 2 * c_T);
   const int64_t wmax = std::max<int64_t>(max_cx, cmax);
   for (int k = 0; k < n; ++k) {
     SourcePlan& p = src[k];
@@ -592,6 +595,30 @@ ilargi_status_t ilargi_plan_create(int n, const ilargi_source_t* sources, int64_
       HIP_TRY(hipStreamSynchronize(st));
     }
   }
+  // join-gather tables, general form: the first two feeders of every target column, in source order
+  {
+    std::vector<int32_t> cs((size_t)2 * c_T, -1), cj((size_t)2 * c_T, 0);
+    bool ok = true;
+    for (int64_t t = 0; t < c_T && ok; ++t) {
+      int found = 0, slot = 0;
+      for (int k = 0; k < n; ++k) {
+        if (pl->src[k].empty) continue;
+        if (tcol[k][t] >= 0) {
+          if (found == 2) { ok = false; break; }
+          cs[2 * t + found] = slot;
+          cj[2 * t + found] = tcol[k][t];
+          ++found;
+        }
+        ++slot;
+      }
+    }
+    pl->mat_cols = ok;
+    if (ok) {
+      HIP_TRY(hipMemcpyAsync(pl->at<int32_t>(lay.o_ct_slot), cs.data(), sizeof(int32_t) * cs.size(), hipMemcpyHostToDevice, st));
+      HIP_TRY(hipMemcpyAsync(pl->at<int32_t>(lay.o_ct_j), cj.data(), sizeof(int32_t) * cj.size(), hipMemcpyHostToDevice, st));
+      HIP_TRY(hipStreamSynchronize(st));
+    }
+  }
   // Gram blocks (k <= l) and the table the assembly kernel walks
   pl->block_off.assign((size_t)n * n, 0);
   std::vector<GramAsmPair> pairs;
@@ -793,6 +820,8 @@ ilargi_status_t ilargi_materialize(ilargi_plan_t* plan, float* T, void* stream) 
   a.T = T; a.r_T = plan->r_T; a.c_T = (int)plan->c_T;
   a.gslot = plan->mat_vec4 ? plan->at<int32_t>(plan->lay.o_gslot) : nullptr;
   a.gj0 = plan->mat_vec4 ? plan->at<int32_t>(plan->lay.o_gj0) : nullptr;
+  a.ct_slot = plan->mat_cols ? plan->at<int32_t>(plan->lay.o_ct_slot) : nullptr;
+  a.ct_j = plan->mat_cols ? plan->at<int32_t>(plan->lay.o_ct_j) : nullptr;
   {
     TraceScope ts(plan, "materialize", -1, static_cast<hipStream_t>(stream));
     HIP_TRY(launch_materialize(a, static_cast<hipStream_t>(stream)));

@@ -120,6 +120,11 @@ struct MatArgs {
   // (-1: nobody) and its first source column; NULL when some group is fed irregularly
   const int32_t* gslot;
   const int32_t* gj0;
+  // optional tables for the column form: for target column t the (up to two) feeding source slots
+  // ct_slot[2t], ct_slot[2t+1] (-1: none) in source order and their source columns ct_j[2t], ct_j[2t+1];
+  // NULL when some column has more than two feeders
+  const int32_t* ct_slot;
+  const int32_t* ct_j;
 };
 
 struct GramArgs {

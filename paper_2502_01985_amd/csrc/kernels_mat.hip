@@ -35,6 +35,84 @@ __global__ __launch_bounds__(kBlock) void materialize_kernel(MatArgs a) {
   }
 }
 
+// General form for tables whose columns have at most two feeding sources each (ct_slot / ct_j tables, built
+// with the plan, list them in source order).  A wavefront writes four rows per step; its 64 lanes first fetch
+// the 4 x 16 row indices (row u, source slot s) in one coalesced-by-source load and park them in LDS, then
+// every lane copies its columns t = lane, lane + 64, ... of the four rows.
+constexpr int kColBlock = 4;   // columns per lane held in registers (target tables up to 256 columns per pass)
+
+__global__ __launch_bounds__(kBlock) void materialize_cols_kernel(MatArgs a) {
+  __shared__ const float* sD[kMaxSources];
+  __shared__ const int32_t* sIdx[kMaxSources];
+  __shared__ int64_t sRows[kMaxSources];
+  __shared__ int sCk[kMaxSources];
+  __shared__ int sJ[kBlock / kWave][4][kMaxSources];
+  if (threadIdx.x < kMaxSources) {
+    int k = threadIdx.x;
+    sD[k] = k < a.n ? a.D[k] : nullptr;
+    sIdx[k] = k < a.n ? a.idx[k] : nullptr;
+    sRows[k] = k < a.n ? a.rows[k] : 0;
+    sCk[k] = k < a.n ? a.ck[k] : 0;
+  }
+  __syncthreads();
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const int64_t wave0 = ((int64_t)blockIdx.x * (kBlock / kWave) + wave) * 4;
+  const int64_t stride = (int64_t)gridDim.x * (kBlock / kWave) * 4;
+  const int ru = lane / kMaxSources, rs = lane % kMaxSources;   // (row of the step, source slot) this lane fetches
+  for (int cb = 0; cb < a.c_T; cb += kWave * kColBlock) {
+    // this lane's columns of the pass and their feeders
+    const float* dp[kColBlock][2];
+    int ck[kColBlock][2], slot[kColBlock][2];
+#pragma unroll
+    for (int q = 0; q < kColBlock; ++q) {
+      const int t = cb + lane + q * kWave;
+#pragma unroll
+      for (int f = 0; f < 2; ++f) {
+        slot[q][f] = t < a.c_T ? a.ct_slot[2 * t + f] : -1;
+        dp[q][f] = nullptr; ck[q][f] = 0;
+        if (slot[q][f] >= 0) { dp[q][f] = sD[slot[q][f]] + a.ct_j[2 * t + f]; ck[q][f] = sCk[slot[q][f]]; }
+      }
+    }
+    for (int64_t i0 = wave0; i0 < a.r_T; i0 += stride) {
+      {
+        const int64_t i = i0 + ru;
+        int r = -1;
+        if (rs < a.n && i < a.r_T) r = sIdx[rs] != nullptr ? sIdx[rs][i] : (i < sRows[rs] ? (int)i : -1);
+        __builtin_amdgcn_wave_barrier();
+        sJ[wave][ru][rs] = r;
+        __builtin_amdgcn_wave_barrier();
+      }
+      float v[4][kColBlock][2];
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int q = 0; q < kColBlock; ++q)
+#pragma unroll
+          for (int f = 0; f < 2; ++f) {
+            v[u][q][f] = 0.0f;
+            if (slot[q][f] >= 0) {
+              const int r = sJ[wave][u][slot[q][f]];
+              if (r >= 0) v[u][q][f] = dp[q][f][(int64_t)r * ck[q][f]];
+            }
+          }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int64_t i = i0 + u;
+        if (i >= a.r_T) break;
+#pragma unroll
+        for (int q = 0; q < kColBlock; ++q) {
+          const int t = cb + lane + q * kWave;
+          if (t < a.c_T) {
+            float acc = 0.0f + v[u][q][0];
+            if (slot[q][1] >= 0 && sJ[wave][u][slot[q][1]] >= 0) acc += v[u][q][1];
+            __builtin_nontemporal_store(acc, a.T + i * a.c_T + t);
+          }
+        }
+      }
+    }
+  }
+}
+
 // Fast form for the usual schema: every aligned group of four target columns is either fed by four
 // consecutive columns of one source or by nobody (gslot / gj0 tables, built with the plan).  A lane owns
 // column groups lane, lane + 64, ... of its wavefront's row and stores them as float4.
@@ -127,6 +205,11 @@ hipError_t launch_materialize(const MatArgs& a, hipStream_t st) {
     int64_t grid = (waves + (kBlock / kWave) - 1) / (kBlock / kWave);
     if (grid > 65536) grid = 65536;
     materialize_vec4_kernel<<<(int)grid, kBlock, 0, st>>>(a);
+  } else if (a.ct_slot != nullptr) {
+    int64_t waves = (a.r_T + 3) / 4;
+    int64_t grid = (waves + (kBlock / kWave) - 1) / (kBlock / kWave);
+    if (grid > 65536) grid = 65536;
+    materialize_cols_kernel<<<(int)grid, kBlock, 0, st>>>(a);
   } else {
     int64_t grid = (a.r_T + (kBlock / kWave) - 1) / (kBlock / kWave);
     if (grid > 8192) grid = 8192;
