@@ -32,8 +32,18 @@ HBM_PEAK_GBPS = 8000.0
 
 
 # ----------------------------------------------------------------------------- byte model
+def _is_identity(s):
+    """NULL row_idx, or the identity on the first r_k target rows and -1 beyond (what the plan detects)."""
+    if s.row_idx is None:
+        return True
+    idx = s.row_idx
+    return (s.rows <= idx.size and np.array_equal(idx[:s.rows], np.arange(s.rows, dtype=idx.dtype))
+            and bool(np.all(idx[s.rows:] == -1)))
+
+
 def shapes_of(schema):
-    return [(s.rows, s.cols, s.row_idx is not None) for s in schema.sources]
+    """(rows, cols, needs an inverse index) per source."""
+    return [(s.rows, s.cols, not _is_identity(s)) for s in schema.sources]
 
 
 def bytes_tables(shapes):
@@ -240,6 +250,39 @@ def wide_batch(il, torch, datagen, dev):
     return out
 
 
+def other_configs(il, torch, datagen):
+    """Gradient-descent iterations/s, factorized vs materialized, on the remaining single-model
+    configurations (full size): 0 (tiny star join, linear), 2 (three dimensions with a Zipf key, logistic),
+    3 (union with overlap, linear)."""
+    out = {}
+    for name, model, mname in (("config0", il.LINEAR, "linear"), ("config2", il.LOGISTIC, "logistic"),
+                               ("config3", il.LINEAR, "linear")):
+        sch = getattr(datagen, name)()
+        shp = shapes_of(sch)
+        t0 = time.perf_counter()
+        plan = il.ilargi_plan_create(il.schema_to_device(sch), sch.r_T, sch.c_T, max_cx=1)
+        torch.cuda.synchronize()
+        plan_ms = (time.perf_counter() - t0) * 1e3
+        T = il.ilargi_materialize(plan)
+        t_mat_once = time_loop(torch, lambda: il.ilargi_materialize(plan, T), 3, warm=1)
+        mplan = il.ilargi_plan_create([(T, None, np.arange(sch.c_T, dtype=np.int32))], sch.r_T, sch.c_T, max_cx=1)
+        W = torch.zeros((sch.c_T, 1), device="cuda")
+        y = (torch.rand(sch.r_T, device="cuda") > 0.5).float()
+        lr = torch.full((1,), 0.1, device="cuda")
+        loss = torch.zeros(1, device="cuda")
+        t_f = time_loop(torch, lambda: il.ilargi_gd_step(plan, model, W, y, lr, loss), 20)
+        t_m = time_loop(torch, lambda: il.ilargi_gd_step(mplan, model, W, y, lr, loss), 20)
+        b = bytes_gd(shp, sch.r_T, sch.c_T)
+        out[name] = {"model": mname, "r_T": sch.r_T, "c_T": sch.c_T, "sources": len(sch.sources),
+                     "gd_factorized_it_per_s": round(1.0 / t_f, 1), "gd_materialized_it_per_s": round(1.0 / t_m, 1),
+                     "speedup": round(t_m / t_f, 3), "gd_factorized_GBps": round(b / t_f / 1e9, 1),
+                     "materialize_once_us": round(t_mat_once * 1e6, 1), "plan_build_ms": round(plan_ms, 1),
+                     "complexity_ratio_eq1": round(complexity_ratio_lr(shp, sch.r_T, sch.c_T), 3)}
+        del plan, mplan, T, W, y
+        torch.cuda.empty_cache()
+    return out
+
+
 def stream_probe(il, torch):
     """What plain streaming kernels reach on this device (1 GiB buffers)."""
     n = 1 << 28
@@ -274,6 +317,7 @@ def main() -> int:
     ap.add_argument("--cpu-sample-rows", type=int, default=100_000)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--no-wide", action="store_true", help="skip the 256-model batched workload")
+    ap.add_argument("--no-configs", action="store_true", help="skip the other single-model configurations")
     ap.add_argument("--sweep", default="", help="also run the TR/FR sweep and write it to this JSON file")
     ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "dominant_kernel_traffic.txt"))
     args = ap.parse_args()
@@ -396,10 +440,12 @@ def main() -> int:
     if args.sweep:
         run_sweep(il, torch, datagen, dev, args.sweep)
     wide = None
+    del plan, ops, keep, Tm
+    torch.cuda.empty_cache()
     if not args.no_wide:
-        del plan, ops, keep, Tm
-        torch.cuda.empty_cache()
         wide = wide_batch(il, torch, datagen, dev)
+        torch.cuda.empty_cache()
+    configs = None if args.no_configs else other_configs(il, torch, datagen)
 
     cpu = None if args.no_cpu else cpu_baseline(sch, args.cpu_sample_rows)
 
@@ -432,6 +478,7 @@ def main() -> int:
         "kernels": dict(sorted(kernels.items(), key=lambda kv: -kv[1]["us_per_step"])[:16]),
         "stream_probe": probe,
         "wide_batch": wide,
+        "other_configs": configs,
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
