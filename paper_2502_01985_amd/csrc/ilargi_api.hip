@@ -307,11 +307,23 @@ ilargi_status_t lmm_pass(ilargi_plan* pl, const float* X, int ldx, int col0, int
     a.grad_partial = pl->at<float>(pl->src[pl->fused].o_partial);
     *fused_gradient = true;
   }
+  const bool wide_fuse = wide && mode != 0 && fused_gradient != nullptr && pl->fused >= 0 && col0 == 0 &&
+                         lmm_mfma_can_fuse_gradient(a.ck, ncols, bf16) &&
+                         (int64_t)256 * a.ck * ldx <= pl->lay.gpartial_floats;   // at most 256 workgroups per slab
+  if (wide_fuse) {
+    a.grad_partial = pl->at<float>(pl->lay.o_gpartial);
+    a.ld_grad = ldx;
+    *fused_gradient = true;
+  }
+  int grid = 0;
   {
     TraceScope ts(pl, "lmm_assemble", -1, st);
-    if (wide) HIP_TRY(launch_lmm_mfma(a, vec, mode, bf16, st, loss_grid));
-    else HIP_TRY(launch_lmm_rows(a, vec, mode, st, loss_grid));
+    if (wide) HIP_TRY(launch_lmm_mfma(a, vec, mode, bf16, st, &grid));
+    else HIP_TRY(launch_lmm_rows(a, vec, mode, st, &grid));
   }
+  if (loss_grid) *loss_grid = grid;
+  if (wide_fuse)   // the workgroups' shares of D^T E, added in workgroup order
+    HIP_TRY(launch_tred_reduce(a.grad_partial, grid, (int64_t)a.ck * ldx, pl->at<float>(pl->src[pl->fused].o_g), st));
   return ILARGI_OK;
 }
 
@@ -404,13 +416,21 @@ ilargi_status_t run_tred(ilargi_plan* pl, TredArgs& g, float* block, const char*
 }
 
 // T^T Y for an operand with many columns: segment sums, matrix-core column reduce, column assembly.
+// done_k: a source whose block of the result is already in its o_g buffer (formed by the assembly pass).
 ilargi_status_t tmm_wide(ilargi_plan* pl, const float* Y, int cx, float* out, int mode, const float* lr,
-                         float* loss, int n_loss_partial, float loss_scale, bool bf16, hipStream_t st) {
+                         float* loss, int n_loss_partial, float loss_scale, bool bf16, hipStream_t st,
+                         int done_k = -1) {
   ColAsmArgs c;
   memset(&c, 0, sizeof(c));
   for (int k = 0; k < pl->n; ++k) {
     SourcePlan& p = pl->src[k];
     if (p.empty) continue;
+    if (k == done_k) {
+      c.tcol2src[c.n] = pl->at<int32_t>(p.o_tcol);
+      c.G[c.n] = pl->at<float>(p.o_g);
+      ++c.n;
+      continue;
+    }
     TredArgs g;
     memset(&g, 0, sizeof(g));
     g.A = p.D; g.lda = (int)p.cols; g.ca = (int)p.cols; g.a_rows = p.rows;
@@ -765,10 +785,11 @@ ilargi_status_t ilargi_gd_step(ilargi_plan_t* plan, ilargi_model_t model, float*
   const float loss_scale = (model == ILARGI_LINEAR ? 0.5f : 1.0f) / (float)plan->r_T;
   if (m >= kWideMin) {
     int loss_grid = 0;
+    bool fusedg = false;
     rc = lmm_pass(plan, W, (int)m, 0, (int)m, E, (int)m, model == ILARGI_LINEAR ? 1 : 2, y, &loss_grid, true, st,
-                  nullptr, bf16);
+                  &fusedg, bf16);
     if (rc != ILARGI_OK) return rc;
-    return tmm_wide(plan, E, (int)m, W, 1, lr, loss, loss_grid, loss_scale, bf16, st);
+    return tmm_wide(plan, E, (int)m, W, 1, lr, loss, loss_grid, loss_scale, bf16, st, fusedg ? plan->fused : -1);
   }
   for (int64_t col0 = 0; col0 < m; col0 += w) {
     int ncols = (int)std::min<int64_t>(w, m - col0);

@@ -46,7 +46,9 @@ struct LmmArgs {
   float* loss_partial;    // narrow kernel: [gridDim.x][kNarrowCT]; matrix-core kernel: [gridDim.x][ld_loss]
   int ld_loss;
   int nt_out;             // store the output with non-temporal stores (large results nobody re-reads soon)
-  float* grad_partial;    // narrow kernel, optional: [gridDim.x][ck][kNarrowCT] partials of D^T e
+  float* grad_partial;    // optional partials of D^T e: narrow kernel [gridDim.x][ck][kNarrowCT],
+                          // matrix-core kernel [gridDim.x][ck][ld_grad]
+  int ld_grad;
 };
 
 // Tile shape of the matrix-core left multiply for a table with ck columns.
@@ -173,6 +175,7 @@ hipError_t launch_lmm_rows(const LmmArgs& a, int vec, int mode, hipStream_t st, 
 int lmm_grid(int64_t r_out, int logL, bool fuseg);
 bool lmm_can_fuse_gradient(int ck, int vec, int logL);
 MfmaShape lmm_mfma_shape(int ck, int nt, bool gathers, bool bf16);
+bool lmm_mfma_can_fuse_gradient(int ck, int ncols, bool bf16);
 hipError_t launch_lmm_mfma(const LmmArgs& a, int vec, int mode, bool bf16, hipStream_t st, int* grid_out);
 hipError_t launch_segsum(const SegArgs& a, hipStream_t st);
 hipError_t launch_colred(const ColredArgs& a, int nblocks, hipStream_t st);

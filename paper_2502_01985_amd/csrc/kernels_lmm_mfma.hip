@@ -33,7 +33,14 @@ __device__ __forceinline__ float softplusf_stable(float z) {
 // BF16: table and operand values are rounded to bfloat16 (nearest even) when they enter the MFMA
 // (16x16x32, eight K values per lane: lane 16 q + i holds columns 32 step + 8 q .. + 7), sums stay float32.
 // SB: global loads a thread keeps in flight while it stages a tile (8, or 16 for tiles of more than 8 float4 per thread).
-template <int NT, int MODE, bool VEC4, bool BF16, int SB>
+// JG > 0 (gradient-descent modes, one K chunk of at most 16 JG columns): the staged rows of D are used
+// a second time while they sit in LDS, for this workgroup's share of  D^T E  (the fused source's block of
+// T^T E, Alg. 1), written to grad_partial[blockIdx.x][ck][ld_grad].  The residual tile a lane has just formed
+// (rows 4 q + r, operand column li) is exactly the B operand of an MFMA whose K slot q stands for row 4 q + r,
+// so the four r values take four MFMAs per 16 table columns and the residuals never leave the registers.
+// With BF16 both factors of this product are rounded to bfloat16 first, which the float32 MFMA then multiplies
+// exactly, as the bfloat16 MFMA would.
+template <int NT, int MODE, bool VEC4, bool BF16, int SB, int JG>
 __global__ __launch_bounds__(kBlock) void lmm_mfma_kernel(LmmArgs a, MfmaShape sh) {
   extern __shared__ float lds[];
   float* As = lds;                                   // [rb][lda]
@@ -49,6 +56,13 @@ __global__ __launch_bounds__(kBlock) void lmm_mfma_kernel(LmmArgs a, MfmaShape s
   float loss_local[NT];
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) loss_local[nt] = 0.0f;
+  v4f gacc[JG > 0 ? JG : 1][NT];
+  if constexpr (JG > 0) {
+#pragma unroll
+    for (int jt = 0; jt < JG; ++jt)
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) gacc[jt][nt] = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
+  }
 
   auto store_x = [&](int k, int n, float x) {
     if constexpr (BF16) reinterpret_cast<__bf16*>(Xs)[((k >> 3) * N + n) * 8 + (k & 7)] = (__bf16)x;
@@ -242,9 +256,12 @@ __global__ __launch_bounds__(kBlock) void lmm_mfma_kernel(LmmArgs a, MfmaShape s
         }
         if (c + 1 < nchunks) continue;                   // (multi-chunk blocks have one tile per wavefront)
         // epilogue: rows 4 q + r of the tile, operand column li of each 16-column tile
+        float ov[NT][4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           const int64_t row = row0 + mt * 16 + 4 * q + r;
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt) ov[nt][r] = 0.0f;
           if (row >= a.r_out) continue;
           float g[NT];
 #pragma unroll
@@ -264,14 +281,60 @@ __global__ __launch_bounds__(kBlock) void lmm_mfma_kernel(LmmArgs a, MfmaShape s
                 o = sigmoidf_stable(z) - yi;
                 loss_local[nt] += softplusf_stable(z) - yi * z;
               }
+              if constexpr (BF16 && JG > 0) ov[nt][r] = (float)(__bf16)o;
+              else ov[nt][r] = o;
               float* op = a.out + row * a.ldo + n0 + nt * 16 + li;
               if (a.nt_out) __builtin_nontemporal_store(o, op);
               else *op = o;
             }
           }
         }
+        if constexpr (JG > 0) {
+          // D^T E of the tile: A operand = table column 16 jt + li of row 4 q + r (zero beyond the table: the
+          // staging zero-fills), B operand = the residual just formed (zero for rows and columns outside)
+          const float* acol = As + (size_t)(mt * 16 + 4 * q) * sh.lda + li;
+#pragma unroll
+          for (int jt = 0; jt < JG; ++jt) {
+            if (jt * 16 < sh.kp) {
+#pragma unroll
+              for (int r = 0; r < 4; ++r) {
+                float av = acol[(size_t)r * sh.lda + jt * 16];
+                if constexpr (BF16) av = (float)(__bf16)av;   // products of two bfloat16 values are exact in float32
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+                  gacc[jt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, ov[nt][r], gacc[jt][nt], 0, 0, 0);
+              }
+            }
+          }
+        }
       }
     }
+  }
+
+  if constexpr (JG > 0) {
+    // the four wavefronts' shares, added in wavefront order in LDS (over the staging area, now idle)
+    float* red = lds;
+    for (int w = 0; w < kBlock / kWave; ++w) {
+      __syncthreads();
+      if (wave == w) {
+#pragma unroll
+        for (int jt = 0; jt < JG; ++jt)
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              float* p = red + (size_t)(jt * 16 + 4 * q + r) * N + nt * 16 + li;
+              if (w == 0) *p = gacc[jt][nt][r];
+              else *p += gacc[jt][nt][r];
+            }
+      }
+    }
+    __syncthreads();
+    for (int e = tid; e < a.ck * N; e += kBlock) {
+      const int j = e / N, n = e - j * N;
+      if (n < nw) a.grad_partial[((int64_t)blockIdx.x * a.ck + j) * a.ld_grad + n0 + n] = red[e];
+    }
+    __syncthreads();
   }
 
   if constexpr (MODE != 0) {
@@ -314,45 +377,95 @@ MfmaShape lmm_mfma_shape(int ck, int nt, bool gathers, bool bf16) {
   return sh;
 }
 
+namespace {
+
+typedef void (*MfmaFn)(LmmArgs, MfmaShape);
+
+template <int NT, int MODE>
+MfmaFn pick_plain(bool vec4, bool bf16, bool sb16) {
+  if (vec4 && bf16) return sb16 ? lmm_mfma_kernel<NT, MODE, true, true, 16, 0> : lmm_mfma_kernel<NT, MODE, true, true, 8, 0>;
+  if (vec4) return sb16 ? lmm_mfma_kernel<NT, MODE, true, false, 16, 0> : lmm_mfma_kernel<NT, MODE, true, false, 8, 0>;
+  if (bf16) return sb16 ? lmm_mfma_kernel<NT, MODE, false, true, 16, 0> : lmm_mfma_kernel<NT, MODE, false, true, 8, 0>;
+  return sb16 ? lmm_mfma_kernel<NT, MODE, false, false, 16, 0> : lmm_mfma_kernel<NT, MODE, false, false, 8, 0>;
+}
+
+template <int NT>
+MfmaFn pick_mode(int mode, bool vec4, bool bf16, bool sb16) {
+  if (mode == 0) return pick_plain<NT, 0>(vec4, bf16, sb16);
+  if (mode == 1) return pick_plain<NT, 1>(vec4, bf16, sb16);
+  return pick_plain<NT, 2>(vec4, bf16, sb16);
+}
+
+// fused gradient: 64-column slabs, tables of at most 64 columns (a tile of at most 8 float4 per thread)
+template <int MODE, bool B>
+MfmaFn pick_fused(bool vec4, int jg) {
+  if (vec4) return jg == 2 ? lmm_mfma_kernel<4, MODE, true, B, 8, 2> : lmm_mfma_kernel<4, MODE, true, B, 8, 4>;
+  return jg == 2 ? lmm_mfma_kernel<4, MODE, false, B, 8, 2> : lmm_mfma_kernel<4, MODE, false, B, 8, 4>;
+}
+
+// Workgroups of this kernel and LDS size the device holds at once (cached: the query costs more than a launch).
+int resident_workgroups(MfmaFn fn, size_t lds_bytes) {
+  static int cus = 0;
+  static MfmaFn seen_fn[128];
+  static size_t seen_lds[128];
+  static int seen_occ[128];
+  static int n_seen = 0;
+  if (cus == 0) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess && prop.multiProcessorCount > 0)
+      cus = prop.multiProcessorCount;
+  }
+  for (int i = 0; i < n_seen; ++i)
+    if (seen_fn[i] == fn && seen_lds[i] == lds_bytes) return seen_occ[i] * cus;
+  int per_cu = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(fn), kBlock, lds_bytes) != hipSuccess || per_cu < 1)
+    per_cu = 1;
+  if (n_seen < 128) { seen_fn[n_seen] = fn; seen_lds[n_seen] = lds_bytes; seen_occ[n_seen] = per_cu; ++n_seen; }
+  return per_cu * cus;
+}
+
+}  // namespace
+
+// The fused D^T E needs a 64-column slab shape and a table of at most 64 columns (one K chunk).
+bool lmm_mfma_can_fuse_gradient(int ck, int ncols, bool bf16) {
+  (void)bf16;
+  return ncols > 32 && ck > 0 && ck <= 64;
+}
+
 hipError_t launch_lmm_mfma(const LmmArgs& a, int vec, int mode, bool bf16, hipStream_t st, int* grid_out) {
   if (grid_out) *grid_out = 0;
   if (a.r_out <= 0 || a.ncols <= 0) return hipSuccess;
   const int nt = a.ncols <= 16 ? 1 : (a.ncols <= 32 ? 2 : 4);
-  const MfmaShape sh = lmm_mfma_shape(a.ck, nt, a.g.n > 0, bf16);
-  int64_t nblocks = (a.r_out + sh.rb - 1) / sh.rb;
-  // wide slabs stage tens of KiB of operand per workgroup: give each workgroup several row blocks
-  int gx = (int)std::min<int64_t>(nblocks, nt == 4 ? 256 : 1024);
-  int gy = (a.ncols + nt * 16 - 1) / (nt * 16);
-  if (grid_out) *grid_out = gx;
-  dim3 grid(gx, gy);
+  MfmaShape sh = lmm_mfma_shape(a.ck, nt, a.g.n > 0, bf16);
   const bool vec4 = vec == 4;
   const bool sb16 = vec4 && (int64_t)sh.rb * (sh.kc / 4) > 8 * kBlock;
-#define ILARGI_LAUNCH1(NT_, MODE_, V_, B_)                                                          \
-  do {                                                                                              \
-    auto kfn = sb16 ? lmm_mfma_kernel<NT_, MODE_, V_, B_, 16> : lmm_mfma_kernel<NT_, MODE_, V_, B_, 8>; \
-    if (sh.lds_bytes > 64 * 1024)                                                                   \
-      (void)hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh.lds_bytes); \
-    kfn<<<grid, kBlock, sh.lds_bytes, st>>>(a, sh);                                                 \
-  } while (0)
-#define ILARGI_LAUNCH(NT_, MODE_)                                                                   \
-  do {                                                                                              \
-    if (vec4 && bf16) ILARGI_LAUNCH1(NT_, MODE_, true, true);                                       \
-    else if (vec4) ILARGI_LAUNCH1(NT_, MODE_, true, false);                                         \
-    else if (bf16) ILARGI_LAUNCH1(NT_, MODE_, false, true);                                         \
-    else ILARGI_LAUNCH1(NT_, MODE_, false, false);                                                  \
-  } while (0)
-#define ILARGI_MODES(NT_)                                    \
-  do {                                                       \
-    if (mode == 0) ILARGI_LAUNCH(NT_, 0);                    \
-    else if (mode == 1) ILARGI_LAUNCH(NT_, 1);               \
-    else ILARGI_LAUNCH(NT_, 2);                              \
-  } while (0)
-  if (nt == 1) ILARGI_MODES(1);
-  else if (nt == 2) ILARGI_MODES(2);
-  else ILARGI_MODES(4);
-#undef ILARGI_MODES
-#undef ILARGI_LAUNCH
-#undef ILARGI_LAUNCH1
+  MfmaFn fn;
+  if (a.grad_partial != nullptr) {
+    if (mode == 0 || a.D == nullptr || !lmm_mfma_can_fuse_gradient(a.ck, a.ncols, bf16)) return hipErrorInvalidValue;
+    const int jg = sh.kp <= 32 ? 2 : 4;
+    sh.lds_bytes = std::max(sh.lds_bytes, (size_t)jg * 16 * 64 * sizeof(float));   // the wavefronts' sum
+    if (bf16) fn = mode == 1 ? pick_fused<1, true>(vec4, jg) : pick_fused<2, true>(vec4, jg);
+    else fn = mode == 1 ? pick_fused<1, false>(vec4, jg) : pick_fused<2, false>(vec4, jg);
+  } else if (nt == 1) {
+    fn = pick_mode<1>(mode, vec4, bf16, sb16);
+  } else if (nt == 2) {
+    fn = pick_mode<2>(mode, vec4, bf16, sb16);
+  } else {
+    fn = pick_mode<4>(mode, vec4, bf16, sb16);
+  }
+  if (sh.lds_bytes > 64 * 1024)
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh.lds_bytes);
+  const int64_t nblocks = (a.r_out + sh.rb - 1) / sh.rb;
+  const int gy = (a.ncols + nt * 16 - 1) / (nt * 16);
+  // wide slabs stage tens of KiB of operand per workgroup: give each workgroup several row blocks; every
+  // workgroup does the same work, so the launch is kept within one round of the device's workgroup slots
+  int64_t gx = std::min<int64_t>(nblocks, nt == 4 ? 256 : 1024);
+  const int64_t slots = resident_workgroups(fn, sh.lds_bytes);
+  if (gx * gy > slots) gx = std::max<int64_t>(1, slots / gy);
+  if (grid_out) *grid_out = (int)gx;
+  hipLaunchKernelGGL(fn, dim3((unsigned)gx, (unsigned)gy), dim3(kBlock), sh.lds_bytes, st, a, sh);
   return hipGetLastError();
 }
 

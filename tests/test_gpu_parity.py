@@ -227,6 +227,25 @@ def test_gd_logistic_wide(il):
     np.testing.assert_allclose(L, L_ref, rtol=2e-4)
 
 
+@pytest.mark.parametrize("model", ["linear", "logistic"])
+@pytest.mark.parametrize("c_S,m", [(7, 33), (20, 100), (48, 64), (64, 40), (65, 40)])
+def test_gd_wide_entity_gradient_in_the_assembly_pass(il, model, c_S, m):
+    # batches above 32 models form the entity table's block of T^T E while its rows are staged for T W
+    # (tables up to 64 columns; 65 takes the separate reduction); ragged slabs, unaligned rows, both models
+    rng = datagen.rng_for(900 + c_S)
+    sch = datagen.star_schema(rng, 5_003, c_S, [(301, 24, "uniform"), (57, 9, ("zipf", 1.1))])
+    tg = oracle.Target(sch)
+    w_star = rng.standard_normal(sch.c_T) / np.sqrt(sch.c_T)
+    y = datagen.finish_labels(model, oracle.lmm(tg, w_star.reshape(-1, 1)), 0.01 * rng.standard_normal(sch.r_T))
+    plan = il.ilargi_plan_create(il.schema_to_device(sch), sch.r_T, sch.c_T, max_cx=m)
+    lrs = np.geomspace(1e-3, 5e-2, m)
+    code = il.LINEAR if model == "linear" else il.LOGISTIC
+    W, L = _run_gd(il, plan, code, y, lrs, 8, sch.c_T)
+    W_ref, L_ref = oracle.gd(tg, model, y, np.zeros((sch.c_T, m)), lrs, 8)
+    assert max(rel(W[:, j], W_ref[:, j]) for j in range(m)) < GD_TOL
+    np.testing.assert_allclose(L, L_ref, rtol=2e-4)
+
+
 # ------------------------------------------------------------------ bfloat16-input variant
 BF16_TOL = 5e-3
 
@@ -293,6 +312,30 @@ def test_bf16_gradient_descent_tracks_float32(il):
     assert max(errs) < 2e-2, max(errs)
     # models that have converged sit on the noise floor the input rounding leaves in the residual
     np.testing.assert_allclose(loss.cpu().numpy(), L_ref[-1], rtol=5e-2, atol=2e-2)
+
+
+@pytest.mark.parametrize("c_S,m", [(20, 64), (48, 40)])
+def test_bf16_first_gradient_step_exact_on_representable_inputs(il, c_S, m):
+    # from W = 0 the residual is -y; with tables and labels on the bfloat16 grid the entity table's block of the
+    # first step (formed in the assembly pass for more than 32 models) rounds nothing and meets the float32
+    # bound; the dimension table's block multiplies segment sums of -y, which do get rounded
+    rng = datagen.rng_for(950 + c_S)
+    sch = datagen.star_schema(rng, 5_003, c_S, [(301, 24, "uniform")])
+    for s in sch.sources:
+        s.D[...] = _to_bf16_grid(s.D)
+    tg = oracle.Target(sch)
+    y = _to_bf16_grid(rng.standard_normal(sch.r_T).astype(np.float32)).astype(np.float64)
+    plan = il.ilargi_plan_create(il.schema_to_device(sch), sch.r_T, sch.c_T, max_cx=m)
+    lrs = np.geomspace(1e-3, 5e-2, m)
+    W = torch.zeros((sch.c_T, m), device="cuda")
+    loss = torch.zeros(m, device="cuda")
+    il.ilargi_gd_step(plan, il.LINEAR, W, dev(y.astype(np.float32)), dev(lrs.astype(np.float32)), loss,
+                      precision=il.BF16_IN_F32_ACC)
+    W_ref, L_ref = oracle.gd(tg, "linear", y, np.zeros((sch.c_T, m)), lrs, 1)
+    W = W.cpu().numpy()
+    assert max(rel(W[:c_S, j], W_ref[:c_S, j]) for j in range(m)) < OP_TOL
+    assert max(rel(W[c_S:, j], W_ref[c_S:, j]) for j in range(m)) < BF16_TOL
+    np.testing.assert_allclose(loss.cpu().numpy(), L_ref[-1], rtol=2e-4)
 
 
 # ------------------------------------------------------------------ crossprod
