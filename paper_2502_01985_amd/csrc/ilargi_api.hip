@@ -70,6 +70,7 @@ struct ilargi_plan {
   std::vector<SourcePlan> src;
   Layout lay;
   int fused = -1;   // identity source whose product is fused into the assembly pass
+  int star_k = -1;  // two-table star join: the dimension table every target row joins (else -1)
   bool mat_vec4 = false;  // the grouped column tables of the vectorized join-gather are valid
   bool mat_cols = false;  // the per-column feeder tables (at most two feeders per column) are valid
   int npairs = 0;
@@ -465,6 +466,63 @@ ilargi_status_t tmm_wide(ilargi_plan* pl, const float* Y, int cx, float* out, in
   return ILARGI_OK;
 }
 
+// Alg. 1 for a wide batch on a two-table star join: P = R W_R, the join-order pass (residual, S^T E, segment
+// sums), R^T Z, update.  The r_T x m residual is never stored.
+ilargi_status_t gd_star_step(ilargi_plan* pl, int mode, float* W, int m, const float* y, const float* lr,
+                             float* loss, float loss_scale, bool bf16, hipStream_t st) {
+  SourcePlan& f = pl->src[pl->fused];
+  SourcePlan& d = pl->src[pl->star_k];
+  {
+    LmmArgs a;
+    memset(&a, 0, sizeof(a));
+    a.D = d.D; a.d_rows = d.rows; a.ck = (int)d.cols; a.colmap = pl->at<int32_t>(d.o_colmap);
+    a.X = W; a.ldx = m; a.col0 = 0; a.ncols = m;
+    a.out = pl->at<float>(d.o_pz); a.ldo = m; a.r_out = d.rows;
+    a.logL = pick_logL(d.cols, d.vec);
+    TraceScope ts(pl, "lmm_rows", pl->star_k, st);
+    HIP_TRY(launch_lmm_mfma(a, d.vec, 0, bf16, st, nullptr));
+  }
+  StarArgs s;
+  memset(&s, 0, sizeof(s));
+  s.S = f.D; s.cs = (int)f.cols; s.s_colmap = pl->at<int32_t>(f.o_colmap);
+  s.W = W; s.ldw = m; s.m = m;
+  s.PZ = pl->at<float>(d.o_pz); s.ldp = m; s.r_R = d.rows;
+  s.rowptr = pl->at<int32_t>(d.o_rowptr); s.perm = pl->at<int32_t>(d.o_perm); s.idx = d.idx;
+  s.y = y;
+  s.loss_partial = pl->at<float>(pl->lay.o_loss); s.ld_loss = m;
+  s.grad_partial = pl->at<float>(pl->lay.o_gpartial); s.ld_grad = m;
+  const int64_t max_grid = std::min<int64_t>(1024, pl->lay.gpartial_floats / ((int64_t)s.cs * m));
+  int grid = 0;
+  {
+    TraceScope ts(pl, "star_pass", -1, st);
+    HIP_TRY(launch_gd_star(s, f.vec, mode, bf16, (int)max_grid, st, &grid));
+  }
+  HIP_TRY(launch_tred_reduce(s.grad_partial, grid, (int64_t)s.cs * m, pl->at<float>(f.o_g), st));
+  TredArgs g;
+  memset(&g, 0, sizeof(g));
+  g.A = d.D; g.lda = (int)d.cols; g.ca = (int)d.cols; g.a_rows = d.rows;
+  g.B = pl->at<float>(d.o_pz); g.ldb = m; g.cb = m; g.bcol0 = 0; g.b_rows = d.rows;
+  g.n_rows = d.rows;
+  ilargi_status_t rc = run_tred(pl, g, pl->at<float>(d.o_g), "colred", pl->star_k, bf16, st);
+  if (rc != ILARGI_OK) return rc;
+  ColAsmArgs c;
+  memset(&c, 0, sizeof(c));
+  for (int k : {std::min(pl->fused, pl->star_k), std::max(pl->fused, pl->star_k)}) {   // source order, as in the general path
+    c.tcol2src[c.n] = pl->at<int32_t>(pl->src[k].o_tcol);
+    c.G[c.n] = pl->at<float>(pl->src[k].o_g);
+    ++c.n;
+  }
+  c.c_T = (int)pl->c_T; c.cx = m; c.out = W;
+  c.lr = lr; c.inv_rT = 1.0f / (float)pl->r_T;
+  c.loss_partial = pl->at<float>(pl->lay.o_loss); c.n_loss_partial = grid;
+  c.loss = loss; c.loss_scale = loss_scale;
+  {
+    TraceScope ts(pl, "finalize", -1, st);
+    HIP_TRY(launch_colasm(c, 1, st));
+  }
+  return ILARGI_OK;
+}
+
 constexpr int kWideMin = 8;   // operands with at least this many columns take the matrix-core kernels
 
 ilargi_status_t check_call(const ilargi_plan* pl, const void* a, const void* b, int64_t cx, const char* what) {
@@ -587,6 +645,22 @@ ilargi_status_t ilargi_plan_create(int n, const ilargi_source_t* sources, int64_
   for (int k = 0; k < n; ++k) {
     const SourcePlan& p = pl->src[k];
     if (p.ident && !p.empty && p.rows * p.cols > best) { best = p.rows * p.cols; pl->fused = k; }
+  }
+  // two-table star join: a full-height identity source plus one table that every target row joins, without
+  // very long segments; wide batches of models then run their gradient pass in join order
+  {
+    int live = 0, dim = -1;
+    for (int k = 0; k < n; ++k) {
+      const SourcePlan& p = pl->src[k];
+      if (p.empty) continue;
+      ++live;
+      if (k != pl->fused) dim = k;
+    }
+    if (live == 2 && pl->fused >= 0 && dim >= 0) {
+      const SourcePlan& f = pl->src[pl->fused];
+      const SourcePlan& d = pl->src[dim];
+      if (f.rows == r_T && d.has_idx && !d.ident && d.nnz == r_T && d.n_long == 0) pl->star_k = dim;
+    }
   }
   // join-gather tables: groups of four target columns fed by four consecutive columns of one source
   if (c_T % 4 == 0) {
@@ -783,6 +857,9 @@ ilargi_status_t ilargi_gd_step(ilargi_plan_t* plan, ilargi_model_t model, float*
   float* E = plan->at<float>(plan->lay.o_E);
   const int w = pass_width(plan);
   const float loss_scale = (model == ILARGI_LINEAR ? 0.5f : 1.0f) / (float)plan->r_T;
+  if (plan->star_k >= 0 && gd_star_supported((int)plan->src[plan->fused].cols, (int)m) &&
+      (int64_t)plan->src[plan->fused].cols * m <= plan->lay.gpartial_floats)
+    return gd_star_step(plan, model == ILARGI_LINEAR ? 1 : 2, W, (int)m, y, lr, loss, loss_scale, bf16, st);
   if (m >= kWideMin) {
     int loss_grid = 0;
     bool fusedg = false;

@@ -60,6 +60,26 @@ struct MfmaShape {
   size_t lds_bytes;
 };
 
+// Gradient-descent pass over a two-table star join for a wide batch of models (kernels_star.hip).
+struct StarArgs {
+  const float* S;            // r_T x cs, row i of S is target row i
+  int cs;
+  const int32_t* s_colmap;   // device int32[cs]
+  const float* W;            // c_T x ldw
+  int ldw, m;
+  float* PZ;                 // r_R x ldp: in  P = R W_R,  out  Z = segment sums of the residual
+  int ldp;
+  int64_t r_R;
+  const int32_t* rowptr;     // r_R + 1: inverse index of the dimension table (every target row joins one row)
+  const int32_t* perm;       // r_T
+  const int32_t* idx;        // r_T: row of R each target row joins
+  const float* y;            // r_T
+  float* loss_partial;       // [gridDim.x][ld_loss]
+  int ld_loss;
+  float* grad_partial;       // [gridDim.x][cs][ld_grad] partials of S^T E
+  int ld_grad;
+};
+
 struct SegArgs {
   const int32_t* rowptr;   // r_k + 1
   const int32_t* perm;     // nnz
@@ -177,6 +197,8 @@ bool lmm_can_fuse_gradient(int ck, int vec, int logL);
 MfmaShape lmm_mfma_shape(int ck, int nt, bool gathers, bool bf16);
 bool lmm_mfma_can_fuse_gradient(int ck, int ncols, bool bf16);
 hipError_t launch_lmm_mfma(const LmmArgs& a, int vec, int mode, bool bf16, hipStream_t st, int* grid_out);
+bool gd_star_supported(int cs, int m);
+hipError_t launch_gd_star(const StarArgs& a, int vec, int mode, bool bf16, int max_grid, hipStream_t st, int* grid_out);
 hipError_t launch_segsum(const SegArgs& a, hipStream_t st);
 hipError_t launch_colred(const ColredArgs& a, int nblocks, hipStream_t st);
 hipError_t launch_finalize(const FinArgs& a, int c_T, int mode, hipStream_t st);

@@ -1,0 +1,417 @@
+// One gradient-descent pass (Alg. 1) over a two-table star join  T = [S | I_R R]  for a batch of more than 32
+// models, without ever writing the r_T x m residual:
+//
+//   for every target row i:   e_i = f(S[i,:] W_S + P[fk(i),:]) - y_i          (P = R W_R, formed beforehand)
+//   G_S  = S^T E              (per-workgroup partials)
+//   Z[j] = sum of e_i over the rows i that join row j of R                    (the segment sums  I_R^T E)
+//
+// The pass walks the target rows in the order of the inverse index (grouped by the row of R they join), so a
+// wavefront owns 16 consecutive rows of R at a time together with all target rows that join them: their rows
+// of P are one contiguous 16-row tile (read once, kept in LDS), and the segment sums stay in registers until
+// the tile is finished.  All three products run on the matrix cores (MFMA 16x16x4 float32, or 16x16x32
+// bfloat16 for S W_S); the residual tile a lane has just formed is, as it stands, the B operand of
+//   S^T E :  A = the staged table values of rows 4 q + r,
+//   Z     :  A = 1 where row 4 q + r joins row li of the tile of R, else 0  (so each sum is exact in float32).
+// Z overwrites P in place: a wavefront reads its P tile before it writes the same rows and columns of Z.
+#include <algorithm>
+
+#include "ilargi_internal.h"
+
+namespace ilargi {
+
+namespace {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+__device__ __forceinline__ float star_sigmoid(float z) {
+  if (z >= 0.0f) return 1.0f / (1.0f + __expf(-z));
+  float e = __expf(z);
+  return e / (1.0f + e);
+}
+
+__device__ __forceinline__ float star_softplus(float z) {
+  return fmaxf(z, 0.0f) + log1pf(__expf(-fabsf(z)));
+}
+
+// LDS writes of some lanes of a wavefront become visible to the others (one wavefront executes its LDS
+// instructions in order; the fences only keep the compiler from moving accesses across this point).
+__device__ __forceinline__ void wave_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+constexpr int kN = 64;        // model columns per workgroup (four 16-column tiles)
+constexpr int kNT = 4;
+constexpr int kWaves = kBlock / kWave;
+
+// MODE 1: linear, 2: logistic.  VEC4: rows of S are read as float4.  BF16: values of S, W and E are rounded
+// to bfloat16 (nearest even) where they enter a product.  JG: 16-column tiles of S (kp / 16 rounded to 2 or 4).
+// ST: target rows a wavefront stages at a time (32 or 64).
+template <int MODE, bool VEC4, bool BF16, int JG, int ST>
+__global__ __launch_bounds__(kBlock) void gd_star_kernel(StarArgs a, int kp, int lda, int rtiles) {
+  extern __shared__ float lds[];
+  float* Xs = lds;                                            // [kp / 4][64][4]  (bf16: [kp / 8][64][8])
+  const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+  const int li = lane % 16, q = lane / 16;
+  float* wbase = lds + (size_t)kp * kN + (size_t)wave * ((size_t)ST * lda + 16 * kN + 3 * ST);
+  float* As = wbase;                                          // [ST][lda] staged rows of S
+  float* Ps = As + (size_t)ST * lda;                          // [16][64] tile of P, later of Z
+  int* iS = reinterpret_cast<int*>(Ps + 16 * kN);             // [ST] target row of each staged row
+  int* jS = iS + ST;                                          // [ST] row of the R tile it joins (-1: none)
+  float* yS = reinterpret_cast<float*>(jS + ST);              // [ST] label
+  const int n0 = blockIdx.y * kN;
+  const int nw = min(kN, a.m - n0);
+
+  // W rows of S's columns -> Xs (shared by the workgroup)
+  {
+    const bool x_vec = (a.ldw % 4 == 0) && (reinterpret_cast<uintptr_t>(a.W) % 16 == 0);
+    constexpr int NQ = kN / 4;
+    for (int e = tid; e < kp * NQ; e += kBlock) {
+      const int k = e / NQ, nq = e - k * NQ;
+      float4 xv = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+      if (k < a.cs && 4 * nq < nw) {
+        const float* p = a.W + (int64_t)a.s_colmap[k] * a.ldw + n0 + 4 * nq;
+        if (x_vec && 4 * nq + 3 < nw) {
+          xv = *reinterpret_cast<const float4*>(p);
+        } else {
+          xv.x = p[0];
+          if (4 * nq + 1 < nw) xv.y = p[1];
+          if (4 * nq + 2 < nw) xv.z = p[2];
+          if (4 * nq + 3 < nw) xv.w = p[3];
+        }
+      }
+      const float x4[4] = {xv.x, xv.y, xv.z, xv.w};
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const int n = 4 * nq + c;
+        if constexpr (BF16) reinterpret_cast<__bf16*>(Xs)[((k >> 3) * kN + n) * 8 + (k & 7)] = (__bf16)x4[c];
+        else Xs[((k >> 2) * kN + n) * 4 + (k & 3)] = x4[c];
+      }
+    }
+  }
+  __syncthreads();
+
+  float loss_local[kNT];
+  v4f gacc[JG][kNT];
+#pragma unroll
+  for (int nt = 0; nt < kNT; ++nt) loss_local[nt] = 0.0f;
+#pragma unroll
+  for (int jt = 0; jt < JG; ++jt)
+#pragma unroll
+    for (int nt = 0; nt < kNT; ++nt) gacc[jt][nt] = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
+
+  const bool p_vec = (a.ldp % 4 == 0) && (reinterpret_cast<uintptr_t>(a.PZ) % 16 == 0);
+  const int pr = lane / 16, pq = lane % 16;                   // (row mod 4, float4 slot) of the P / Z tile this lane moves
+
+  for (int rt = blockIdx.x * kWaves + wave; rt < rtiles; rt += gridDim.x * kWaves) {
+    const int64_t jb = (int64_t)rt * 16;
+    const int p_begin = a.rowptr[jb];
+    const int p_end = a.rowptr[min(jb + 16, a.r_R)];
+    wave_sync();                                              // the previous tile's Z has left Ps
+    // P tile -> Ps (zero beyond the table and the slab)
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int r = pr + 4 * u;
+      float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+      if (jb + r < a.r_R && 4 * pq < nw) {
+        const float* p = a.PZ + (jb + r) * a.ldp + n0 + 4 * pq;
+        if (p_vec && 4 * pq + 3 < nw) {
+          v = *reinterpret_cast<const float4*>(p);
+        } else {
+          v.x = p[0];
+          if (4 * pq + 1 < nw) v.y = p[1];
+          if (4 * pq + 2 < nw) v.z = p[2];
+          if (4 * pq + 3 < nw) v.w = p[3];
+        }
+      }
+      *reinterpret_cast<float4*>(Ps + r * kN + 4 * pq) = v;
+    }
+    v4f zacc[kNT];
+#pragma unroll
+    for (int nt = 0; nt < kNT; ++nt) zacc[nt] = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
+
+    int pi_next = (lane < ST && p_begin + lane < p_end) ? a.perm[p_begin + lane] : -1;
+    for (int p0 = p_begin; p0 < p_end; p0 += ST) {
+      const int cnt = min(ST, p_end - p0);
+      // per staged row: target row, joined row of the tile, label
+      const int pi = pi_next;
+      pi_next = (lane < ST && p0 + ST + lane < p_end) ? a.perm[p0 + ST + lane] : -1;
+      int jl = -1;
+      float yv = 0.0f;
+      if (pi >= 0) {
+        jl = a.idx[pi] - (int)jb;
+        yv = a.y[pi];
+      }
+      wave_sync();                                            // the previous batch is consumed
+      if (lane < ST) { iS[lane] = pi; jS[lane] = jl; yS[lane] = yv; }
+      wave_sync();
+      // rows of S -> As, zero beyond the table's columns and beyond the batch
+      if constexpr (VEC4) {
+        const int tpr = kp / 4;
+        const int live4 = a.cs / 4;
+        constexpr int SB = 8;
+        int r = lane / tpr, g = lane - r * tpr;
+        const int dr = kWave / tpr, dg = kWave - dr * tpr;
+        while (r < ST) {
+          float4 v[SB];
+          int rr[SB], gg[SB];
+#pragma unroll
+          for (int u = 0; u < SB; ++u) {
+            rr[u] = r; gg[u] = g;
+            v[u] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            if (r < cnt && g < live4) {
+              const int64_t row = iS[r];
+              v[u] = *reinterpret_cast<const float4*>(a.S + row * a.cs + 4 * g);
+            }
+            r += dr; g += dg;
+            if (g >= tpr) { g -= tpr; ++r; }
+          }
+#pragma unroll
+          for (int u = 0; u < SB; ++u)
+            if (rr[u] < ST) *reinterpret_cast<float4*>(As + (size_t)rr[u] * lda + 4 * gg[u]) = v[u];
+        }
+      } else {
+        constexpr int SB = 16;
+        int r = lane / kp, g = lane - r * kp;
+        const int dr = kWave / kp, dg = kWave - dr * kp;
+        while (r < ST) {
+          float v[SB];
+          int rr[SB], gg[SB];
+#pragma unroll
+          for (int u = 0; u < SB; ++u) {
+            rr[u] = r; gg[u] = g;
+            v[u] = 0.0f;
+            if (r < cnt && g < a.cs) {
+              const int64_t row = iS[r];
+              v[u] = a.S[row * a.cs + g];
+            }
+            r += dr; g += dg;
+            if (g >= kp) { g -= kp; ++r; }
+          }
+#pragma unroll
+          for (int u = 0; u < SB; ++u)
+            if (rr[u] < ST) As[(size_t)rr[u] * lda + gg[u]] = v[u];
+        }
+      }
+      wave_sync();
+
+      for (int t = 0; 16 * t < cnt; ++t) {
+        // z tile = S rows x W_S
+        v4f acc[kNT];
+#pragma unroll
+        for (int nt = 0; nt < kNT; ++nt) acc[nt] = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
+        if constexpr (BF16) {
+          const float* arow = As + (size_t)(t * 16 + li) * lda + 8 * q;
+          for (int step = 0; step < kp / 32; ++step) {
+            float4 a0 = *reinterpret_cast<const float4*>(arow + 32 * step);
+            float4 a1 = *reinterpret_cast<const float4*>(arow + 32 * step + 4);
+            bf16x8 av;
+            av[0] = (__bf16)a0.x; av[1] = (__bf16)a0.y; av[2] = (__bf16)a0.z; av[3] = (__bf16)a0.w;
+            av[4] = (__bf16)a1.x; av[5] = (__bf16)a1.y; av[6] = (__bf16)a1.z; av[7] = (__bf16)a1.w;
+            const bf16x8* xb = reinterpret_cast<const bf16x8*>(Xs) + (size_t)(4 * step + q) * kN + li;
+#pragma unroll
+            for (int nt = 0; nt < kNT; ++nt)
+              acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, xb[nt * 16], acc[nt], 0, 0, 0);
+          }
+        } else {
+          const float* arow = As + (size_t)(t * 16 + li) * lda + 4 * q;
+          for (int step = 0; step < kp / 16; ++step) {
+            float4 av = *reinterpret_cast<const float4*>(arow + 16 * step);
+            const float* xb = Xs + ((size_t)(4 * step + q) * kN + li) * 4;
+#pragma unroll
+            for (int nt = 0; nt < kNT; ++nt) {
+              float4 bv = *reinterpret_cast<const float4*>(xb + nt * 64);
+              acc[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av.x, bv.x, acc[nt], 0, 0, 0);
+              acc[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av.y, bv.y, acc[nt], 0, 0, 0);
+              acc[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av.z, bv.z, acc[nt], 0, 0, 0);
+              acc[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av.w, bv.w, acc[nt], 0, 0, 0);
+            }
+          }
+        }
+        // residual of rows 4 q + r, model column li of each 16-column tile
+        float ov[kNT][4];
+        float ind[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int row = t * 16 + 4 * q + r;
+          const int j = jS[row];                              // -1 beyond the batch
+          const float yi = yS[row];
+          ind[r] = j == li ? 1.0f : 0.0f;
+#pragma unroll
+          for (int nt = 0; nt < kNT; ++nt) {
+            float o = 0.0f;
+            if (j >= 0 && nt * 16 + li < nw) {
+              const float z = acc[nt][r] + Ps[j * kN + nt * 16 + li];
+              if constexpr (MODE == 1) {
+                o = z - yi;
+                loss_local[nt] = fmaf(o, o, loss_local[nt]);
+              } else {
+                o = star_sigmoid(z) - yi;
+                loss_local[nt] += star_softplus(z) - yi * z;
+              }
+            }
+            ov[nt][r] = o;
+          }
+        }
+        // segment sums (unrounded residual), then S^T E
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+          for (int nt = 0; nt < kNT; ++nt)
+            zacc[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(ind[r], ov[nt][r], zacc[nt], 0, 0, 0);
+        if constexpr (BF16) {
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int nt = 0; nt < kNT; ++nt) ov[nt][r] = (float)(__bf16)ov[nt][r];
+        }
+        const float* acol = As + (size_t)(t * 16 + 4 * q) * lda + li;
+#pragma unroll
+        for (int jt = 0; jt < JG; ++jt) {
+          if (jt * 16 < kp) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              float av = acol[(size_t)r * lda + jt * 16];
+              if constexpr (BF16) av = (float)(__bf16)av;     // products of two bfloat16 values are exact in float32
+#pragma unroll
+              for (int nt = 0; nt < kNT; ++nt)
+                gacc[jt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, ov[nt][r], gacc[jt][nt], 0, 0, 0);
+            }
+          }
+        }
+      }
+    }
+    // Z tile: through Ps so that rows leave as float4
+    wave_sync();
+#pragma unroll
+    for (int nt = 0; nt < kNT; ++nt)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) Ps[(4 * q + r) * kN + nt * 16 + li] = zacc[nt][r];
+    wave_sync();
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int r = pr + 4 * u;
+      if (jb + r < a.r_R && 4 * pq < nw) {
+        const float4 v = *reinterpret_cast<const float4*>(Ps + r * kN + 4 * pq);
+        float* p = a.PZ + (jb + r) * a.ldp + n0 + 4 * pq;
+        if (p_vec && 4 * pq + 3 < nw) {
+          *reinterpret_cast<float4*>(p) = v;
+        } else {
+          p[0] = v.x;
+          if (4 * pq + 1 < nw) p[1] = v.y;
+          if (4 * pq + 2 < nw) p[2] = v.z;
+          if (4 * pq + 3 < nw) p[3] = v.w;
+        }
+      }
+    }
+  }
+
+  // the four wavefronts' shares of S^T E, added in wavefront order in LDS (over the staging area, now idle)
+  float* red = lds;
+  for (int w = 0; w < kWaves; ++w) {
+    __syncthreads();
+    if (wave == w) {
+#pragma unroll
+      for (int jt = 0; jt < JG; ++jt)
+#pragma unroll
+        for (int nt = 0; nt < kNT; ++nt)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            float* p = red + (size_t)(jt * 16 + 4 * q + r) * kN + nt * 16 + li;
+            if (w == 0) *p = gacc[jt][nt][r];
+            else *p += gacc[jt][nt][r];
+          }
+    }
+  }
+  __syncthreads();
+  for (int e = tid; e < a.cs * kN; e += kBlock) {
+    const int j = e / kN, n = e - j * kN;
+    if (n < nw) a.grad_partial[((int64_t)blockIdx.x * a.cs + j) * a.ld_grad + n0 + n] = red[e];
+  }
+
+  // per-column loss of this workgroup: the four row groups of a wavefront, then the wavefronts in order
+  __shared__ float lsum[kWaves][kN];
+#pragma unroll
+  for (int nt = 0; nt < kNT; ++nt) {
+    float s = loss_local[nt];
+    s += __shfl_xor(s, 16);
+    s += __shfl_xor(s, 32);
+    if (q == 0) lsum[wave][nt * 16 + li] = s;
+  }
+  __syncthreads();
+  if (tid < nw) {
+    float s = 0.0f;
+    for (int w = 0; w < kWaves; ++w) s += lsum[w][tid];
+    a.loss_partial[(int64_t)blockIdx.x * a.ld_loss + n0 + tid] = s;
+  }
+}
+
+typedef void (*StarFn)(StarArgs, int, int, int);
+
+template <int MODE, bool B>
+StarFn pick_star(bool vec4, int jg) {
+  if (vec4) return jg == 2 ? gd_star_kernel<MODE, true, B, 2, 32> : gd_star_kernel<MODE, true, B, 4, 32>;
+  return jg == 2 ? gd_star_kernel<MODE, false, B, 2, 32> : gd_star_kernel<MODE, false, B, 4, 32>;
+}
+
+constexpr int kStarST = 32;
+
+int star_slots(StarFn fn, size_t lds_bytes) {
+  static int cus = 0;
+  static StarFn seen_fn[32];
+  static size_t seen_lds[32];
+  static int seen_occ[32];
+  static int n_seen = 0;
+  if (cus == 0) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess && prop.multiProcessorCount > 0)
+      cus = prop.multiProcessorCount;
+  }
+  for (int i = 0; i < n_seen; ++i)
+    if (seen_fn[i] == fn && seen_lds[i] == lds_bytes) return seen_occ[i] * cus;
+  int per_cu = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(fn), kBlock, lds_bytes) != hipSuccess || per_cu < 1)
+    per_cu = 1;
+  if (n_seen < 32) { seen_fn[n_seen] = fn; seen_lds[n_seen] = lds_bytes; seen_occ[n_seen] = per_cu; ++n_seen; }
+  return per_cu * cus;
+}
+
+}  // namespace
+
+// Tables of at most 64 columns and batches of more than 32 models.
+bool gd_star_supported(int cs, int m) { return cs > 0 && cs <= 64 && m > 32; }
+
+// max_grid: the caller's bound on workgroups per model slab (sizes of the partial buffers).
+hipError_t launch_gd_star(const StarArgs& a, int vec, int mode, bool bf16, int max_grid, hipStream_t st, int* grid_out) {
+  if (grid_out) *grid_out = 0;
+  if (!gd_star_supported(a.cs, a.m) || (mode != 1 && mode != 2) || a.r_R <= 0 || max_grid < 1) return hipErrorInvalidValue;
+  const int kq = bf16 ? 32 : 16;
+  const int kp = (a.cs + kq - 1) / kq * kq;
+  const int jg = kp <= 32 ? 2 : 4;
+  const int lda = kp + 4;
+  const int rtiles = (int)((a.r_R + 15) / 16);
+  const bool vec4 = vec == 4;
+  StarFn fn;
+  if (bf16) fn = mode == 1 ? pick_star<1, true>(vec4, jg) : pick_star<2, true>(vec4, jg);
+  else fn = mode == 1 ? pick_star<1, false>(vec4, jg) : pick_star<2, false>(vec4, jg);
+  size_t lds_floats = (size_t)kp * kN + (size_t)kWaves * ((size_t)kStarST * lda + 16 * kN + 3 * kStarST);
+  lds_floats = std::max(lds_floats, (size_t)jg * 16 * kN);     // the wavefronts' sum of S^T E
+  const size_t lds_bytes = lds_floats * sizeof(float);
+  if (lds_bytes > 64 * 1024)
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+  const int gy = (a.m + kN - 1) / kN;
+  int64_t gx = (rtiles + kWaves - 1) / kWaves;
+  const int64_t slots = star_slots(fn, lds_bytes);
+  // every wavefront walks its share of the tiles: one round of resident workgroups
+  if (gx * gy > slots) gx = std::max<int64_t>(1, slots / gy);
+  gx = std::min<int64_t>(gx, max_grid);
+  if (grid_out) *grid_out = (int)gx;
+  hipLaunchKernelGGL(fn, dim3((unsigned)gx, (unsigned)gy), dim3(kBlock), lds_bytes, st, a, kp, lda, rtiles);
+  return hipGetLastError();
+}
+
+}  // namespace ilargi
