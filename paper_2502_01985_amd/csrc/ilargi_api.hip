@@ -394,6 +394,17 @@ ilargi_status_t run_tred(ilargi_plan* pl, TredArgs& g, float* block, const char*
                          hipStream_t st) {
   int64_t elems = (int64_t)g.ca * g.cb;
   if (elems <= 0) return ILARGI_OK;
+  if (!bf16 && gram_sym_supported(g) && elems <= pl->lay.gpartial_floats) {
+    // diagonal Gram block of a table with 65..208 columns: upper-triangle tiles only
+    g.partial = pl->at<float>(pl->lay.o_gpartial);
+    int nch = 0;
+    {
+      TraceScope ts(pl, tag, tag_k, st);
+      HIP_TRY(launch_gram_sym(g, pl->lay.gpartial_floats, st, &nch));
+    }
+    HIP_TRY(launch_tred_reduce(g.partial, nch, elems, block, st));
+    return ILARGI_OK;
+  }
   // row chunks: whole rounds of the device's workgroup slots (every workgroup does the same work, so a
   // partly filled last round would idle most compute units), within the partial buffer, >= 64 rows each
   int slots = 512, tiles = 1;
@@ -934,8 +945,8 @@ ilargi_status_t ilargi_crossprod(ilargi_plan_t* plan, float* out, void* stream) 
   const int n = plan->n;
   float* blocks = plan->at<float>(plan->lay.o_blocks);
   float* zc = plan->at<float>(plan->lay.o_zc);
-  auto run_gram = [&](TredArgs& g, float* block) -> ilargi_status_t {
-    return run_tred(plan, g, block, "gram", -1, false, st);
+  auto run_gram = [&](TredArgs& g, float* block, int pair) -> ilargi_status_t {
+    return run_tred(plan, g, block, "gram", pair, false, st);   // traced as gram:<k * n + l>
   };
   for (int k = 0; k < n; ++k) {
     const SourcePlan& a = plan->src[k];
@@ -953,7 +964,7 @@ ilargi_status_t ilargi_crossprod(ilargi_plan_t* plan, float* out, void* stream) 
         g.wptr = a.ident ? nullptr : plan->at<int32_t>(a.o_rowptr);
         g.n_rows = a.rows;
         g.upper_only = 1;
-        rc = run_gram(g, block);
+        rc = run_gram(g, block, k * n + l);
       } else {
         bool via_l = !b.ident && b.rows * 2 <= plan->r_T;
         bool via_k = !a.ident && a.rows * 2 <= plan->r_T;
@@ -982,7 +993,7 @@ ilargi_status_t ilargi_crossprod(ilargi_plan_t* plan, float* out, void* stream) 
           g.B = b.D; g.ldb = (int)b.cols; g.cb = (int)b.cols; g.ib = b.ident ? nullptr : b.idx; g.b_rows = b.rows;
           g.n_rows = plan->r_T;
         }
-        rc = run_gram(g, block);
+        rc = run_gram(g, block, k * n + l);
       }
       if (rc != ILARGI_OK) return rc;
     }

@@ -207,6 +207,8 @@ hipError_t launch_gram(const GramArgs& a, int nchunks, hipStream_t st);
 hipError_t launch_gram_reduce(const float* partial, int nchunks, int64_t elems, float* block, hipStream_t st);
 hipError_t launch_gram_assemble(const GramAsmPair* pairs_dev, int npairs, const int32_t* const* tcol2src_dev,
                                 int c_T, float* out, hipStream_t st);
+bool gram_sym_supported(const TredArgs& a);
+hipError_t launch_gram_sym(TredArgs& a, int64_t partial_floats, hipStream_t st, int* nchunks_out);
 hipError_t launch_tred(const TredArgs& a, int nchunks, bool bf16, hipStream_t st);
 void tred_occupancy(const TredArgs& a, bool bf16, int* slots, int* tiles);
 hipError_t launch_tred_reduce(const float* partial, int nchunks, int64_t elems, float* block, hipStream_t st);

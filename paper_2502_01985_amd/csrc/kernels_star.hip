@@ -14,6 +14,7 @@
 //   Z     :  A = 1 where row 4 q + r joins row li of the tile of R, else 0  (so each sum is exact in float32).
 // Z overwrites P in place: a wavefront reads its P tile before it writes the same rows and columns of Z.
 #include <algorithm>
+#include <type_traits>
 
 #include "ilargi_internal.h"
 
@@ -50,7 +51,7 @@ constexpr int kWaves = kBlock / kWave;
 // to bfloat16 (nearest even) where they enter a product.  JG: 16-column tiles of S (kp / 16 rounded to 2 or 4).
 // ST: target rows a wavefront stages at a time (32 or 64).
 template <int MODE, bool VEC4, bool BF16, int JG, int ST>
-__global__ __launch_bounds__(kBlock) void gd_star_kernel(StarArgs a, int kp, int lda, int rtiles) {
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(VEC4 ? (JG == 2 ? 3 : 2) : (JG == 2 ? 2 : 1)))) void gd_star_kernel(StarArgs a, int kp, int lda, int rtiles) {
   extern __shared__ float lds[];
   float* Xs = lds;                                            // [kp / 4][64][4]  (bf16: [kp / 8][64][8])
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
@@ -102,6 +103,23 @@ __global__ __launch_bounds__(kBlock) void gd_star_kernel(StarArgs a, int kp, int
 #pragma unroll
     for (int nt = 0; nt < kNT; ++nt) gacc[jt][nt] = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
 
+  // staging slots of this lane: (row of the batch, float4 or scalar column slot), the same for every batch
+  typedef typename std::conditional<VEC4, float4, float>::type SVal;
+  constexpr int NV = VEC4 ? ST * JG / 16 : ST * JG / 4;
+  const int gslots = VEC4 ? kp / 4 : kp;                      // slots per staged row
+  const int glive = VEC4 ? a.cs / 4 : a.cs;                   // slots inside the table (cs % 4 == 0 with VEC4)
+  int rr[NV], gg[NV];
+  {
+    int r = lane / gslots, g = lane - r * gslots;
+    const int dr = kWave / gslots, dg = kWave - dr * gslots;
+#pragma unroll
+    for (int u = 0; u < NV; ++u) {
+      rr[u] = r; gg[u] = g;
+      r += dr; g += dg;
+      if (g >= gslots) { g -= gslots; ++r; }
+    }
+  }
+
   const bool p_vec = (a.ldp % 4 == 0) && (reinterpret_cast<uintptr_t>(a.PZ) % 16 == 0);
   const int pr = lane / 16, pq = lane % 16;                   // (row mod 4, float4 slot) of the P / Z tile this lane moves
 
@@ -132,70 +150,56 @@ __global__ __launch_bounds__(kBlock) void gd_star_kernel(StarArgs a, int kp, int
 #pragma unroll
     for (int nt = 0; nt < kNT; ++nt) zacc[nt] = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
 
-    int pi_next = (lane < ST && p_begin + lane < p_end) ? a.perm[p_begin + lane] : -1;
+    // Batches of ST target rows, one ahead: while the matrix cores work on a batch, the next batch's rows of
+    // S (registers), its row numbers / labels and the row list of the batch after that are already on their way.
+    int pi = (lane < ST && p_begin + lane < p_end) ? a.perm[p_begin + lane] : -1;
+    int pi_next = (lane < ST && p_begin + ST + lane < p_end) ? a.perm[p_begin + ST + lane] : -1;
+    int jl = -1;
+    float yv = 0.0f;
+    if (pi >= 0) {
+      jl = a.idx[pi] - (int)jb;
+      yv = a.y[pi];
+    }
+    wave_sync();                                              // the previous tile's batches are consumed
+    if (lane < ST) iS[lane] = pi;
+    wave_sync();
+    SVal sv[NV];
+    auto load_rows = [&](int cnt_rows) {
+#pragma unroll
+      for (int u = 0; u < NV; ++u) {
+        if constexpr (VEC4) sv[u] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        else sv[u] = 0.0f;
+        if (rr[u] < cnt_rows && gg[u] < glive) {
+          const int64_t row = iS[rr[u]];
+          if constexpr (VEC4) sv[u] = *reinterpret_cast<const float4*>(a.S + row * a.cs + 4 * gg[u]);
+          else sv[u] = a.S[row * a.cs + gg[u]];
+        }
+      }
+    };
+    load_rows(min(ST, p_end - p_begin));
     for (int p0 = p_begin; p0 < p_end; p0 += ST) {
       const int cnt = min(ST, p_end - p0);
-      // per staged row: target row, joined row of the tile, label
-      const int pi = pi_next;
-      pi_next = (lane < ST && p0 + ST + lane < p_end) ? a.perm[p0 + ST + lane] : -1;
-      int jl = -1;
-      float yv = 0.0f;
+      const int cnt_next = max(0, min(ST, p_end - p0 - ST));
+      wave_sync();                                            // the previous batch is consumed
+      if (lane < ST) { jS[lane] = jl; yS[lane] = yv; iS[lane] = pi_next; }
+#pragma unroll
+      for (int u = 0; u < NV; ++u) {
+        if (rr[u] < ST) {
+          if constexpr (VEC4) *reinterpret_cast<float4*>(As + (size_t)rr[u] * lda + 4 * gg[u]) = sv[u];
+          else As[(size_t)rr[u] * lda + gg[u]] = sv[u];
+        }
+      }
+      wave_sync();
+      // next batch: row numbers and labels, rows of S; the row list of the batch after it
+      pi = pi_next;
+      pi_next = (lane < ST && p0 + 2 * ST + lane < p_end) ? a.perm[p0 + 2 * ST + lane] : -1;
+      jl = -1;
+      yv = 0.0f;
       if (pi >= 0) {
         jl = a.idx[pi] - (int)jb;
         yv = a.y[pi];
       }
-      wave_sync();                                            // the previous batch is consumed
-      if (lane < ST) { iS[lane] = pi; jS[lane] = jl; yS[lane] = yv; }
-      wave_sync();
-      // rows of S -> As, zero beyond the table's columns and beyond the batch
-      if constexpr (VEC4) {
-        const int tpr = kp / 4;
-        const int live4 = a.cs / 4;
-        constexpr int SB = 8;
-        int r = lane / tpr, g = lane - r * tpr;
-        const int dr = kWave / tpr, dg = kWave - dr * tpr;
-        while (r < ST) {
-          float4 v[SB];
-          int rr[SB], gg[SB];
-#pragma unroll
-          for (int u = 0; u < SB; ++u) {
-            rr[u] = r; gg[u] = g;
-            v[u] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-            if (r < cnt && g < live4) {
-              const int64_t row = iS[r];
-              v[u] = *reinterpret_cast<const float4*>(a.S + row * a.cs + 4 * g);
-            }
-            r += dr; g += dg;
-            if (g >= tpr) { g -= tpr; ++r; }
-          }
-#pragma unroll
-          for (int u = 0; u < SB; ++u)
-            if (rr[u] < ST) *reinterpret_cast<float4*>(As + (size_t)rr[u] * lda + 4 * gg[u]) = v[u];
-        }
-      } else {
-        constexpr int SB = 16;
-        int r = lane / kp, g = lane - r * kp;
-        const int dr = kWave / kp, dg = kWave - dr * kp;
-        while (r < ST) {
-          float v[SB];
-          int rr[SB], gg[SB];
-#pragma unroll
-          for (int u = 0; u < SB; ++u) {
-            rr[u] = r; gg[u] = g;
-            v[u] = 0.0f;
-            if (r < cnt && g < a.cs) {
-              const int64_t row = iS[r];
-              v[u] = a.S[row * a.cs + g];
-            }
-            r += dr; g += dg;
-            if (g >= kp) { g -= kp; ++r; }
-          }
-#pragma unroll
-          for (int u = 0; u < SB; ++u)
-            if (rr[u] < ST) As[(size_t)rr[u] * lda + gg[u]] = v[u];
-        }
-      }
-      wave_sync();
+      load_rows(cnt_next);
 
       for (int t = 0; 16 * t < cnt; ++t) {
         // z tile = S rows x W_S

@@ -446,6 +446,19 @@ def test_gd_without_loss_output(il):
     assert rel(W.cpu().numpy(), W_ref) < GD_TOL
 
 
+@pytest.mark.parametrize("c_R", [65, 77, 200, 208])
+def test_crossprod_symmetric_block_of_a_wide_dimension_table(il, c_R):
+    # tables with 65..208 columns take the upper-triangle kernel for their diagonal block; ragged last tile,
+    # unaligned rows (77), skewed fan-out as row weights, rows of R that nobody joins
+    rng = datagen.rng_for(1100 + c_R)
+    sch = datagen.star_schema(rng, 3_001, 5, [(1_237, c_R, ("zipf", 1.1))])
+    tg = oracle.Target(sch)
+    plan = il.ilargi_plan_create(il.schema_to_device(sch), sch.r_T, sch.c_T, max_cx=1)
+    G = il.ilargi_crossprod(plan).cpu().numpy()
+    assert rel(G, oracle.crossprod(tg)) < OP_TOL
+    assert np.array_equal(G, G.T)
+
+
 # ------------------------------------------------------------------ determinism and edge cases
 def test_results_are_bitwise_reproducible(il):
     sch, tg, plan = get(il, "config2_small")
