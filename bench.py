@@ -245,8 +245,9 @@ def wide_batch(il, torch, datagen, dev):
             out[f"{pn}_{nm}"] = {"gd_it_per_s": round(1.0 / t, 1), "ms_per_iteration": round(t * 1e3, 3),
                                  "TFLOPs": round(fl / t / 1e12, 2), "mfma_frac": round(fl / t / peaks[pn], 4)}
     out["flops_per_iteration"] = {"factorized": fl_fact, "materialized": fl_mat}
-    out["note"] = ("m = 256 models; the r_T x m residual (1 GB) is written once and read twice per iteration, "
-                   "so the factorized step is bound by HBM traffic rather than by the matrix cores")
+    out["note"] = ("m = 256 models; the factorized step walks the target rows in join order and never stores the "
+                   "r_T x m residual (R W_R, one fused pass, R^T Z, update); the materialized step writes the "
+                   "1 GB residual and reads it back for T^T E")
     return out
 
 
