@@ -149,15 +149,6 @@ struct MatArgs {
   const int32_t* ct_j;
 };
 
-struct GramArgs {
-  const float* A; int lda, ca; const int32_t* ia; int64_t a_rows;  // row t of A = A[ia ? ia[t] : t]
-  const float* B; int ldb, cb; const int32_t* ib; int64_t b_rows;
-  const int32_t* wptr;   // optional: weight of row t = wptr[t+1] - wptr[t]
-  int64_t n_rows;        // t in [0, n_rows)
-  int64_t rows_per_chunk;
-  float* partial;        // [nchunks][ca][cb]
-};
-
 // Transposed reduction  C = sum_t w_t a_t^T b_t  on the matrix cores (see kernels_tred.hip).
 struct TredArgs {
   const float* A; int lda, ca; const int32_t* ia; int64_t a_rows;   // row t of A = A[ia ? ia[t] : t]
@@ -203,8 +194,6 @@ hipError_t launch_segsum(const SegArgs& a, hipStream_t st);
 hipError_t launch_colred(const ColredArgs& a, int nblocks, hipStream_t st);
 hipError_t launch_finalize(const FinArgs& a, int c_T, int mode, hipStream_t st);
 hipError_t launch_materialize(const MatArgs& a, hipStream_t st);
-hipError_t launch_gram(const GramArgs& a, int nchunks, hipStream_t st);
-hipError_t launch_gram_reduce(const float* partial, int nchunks, int64_t elems, float* block, hipStream_t st);
 hipError_t launch_gram_assemble(const GramAsmPair* pairs_dev, int npairs, const int32_t* const* tcol2src_dev,
                                 int c_T, float* out, hipStream_t st);
 bool gram_sym_supported(const TredArgs& a);
