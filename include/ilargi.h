@@ -16,7 +16,8 @@
  * Conventions for every call
  *   - Matrices are dense float32, row-major, with no padding between rows.
  *   - "device" pointers are HIP device addresses valid on the current device; "host" pointers are
- *     ordinary process memory.  The library never takes ownership of caller memory.
+ *     ordinary process memory.  The library never takes ownership of caller memory.  A buffer with
+ *     r_T rows may be NULL when r_T = 0 (it is empty); every other buffer must not be.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Operator calls only
  *     enqueue work on that stream and return; outputs are valid once the stream has reached that
  *     point.  ilargi_plan_create synchronizes the stream before it returns.

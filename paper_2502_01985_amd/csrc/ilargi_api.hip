@@ -536,9 +536,10 @@ ilargi_status_t gd_star_step(ilargi_plan* pl, int mode, float* W, int m, const f
 
 constexpr int kWideMin = 8;   // operands with at least this many columns take the matrix-core kernels
 
+// a: the c_T-row operand (never empty); b: the r_T-row one, which may be NULL when the target table has no rows.
 ilargi_status_t check_call(const ilargi_plan* pl, const void* a, const void* b, int64_t cx, const char* what) {
   if (pl == nullptr) return fail(ILARGI_ERR_NULL, "%s: plan is NULL", what);
-  if (a == nullptr || b == nullptr) return fail(ILARGI_ERR_NULL, "%s: operand pointer is NULL", what);
+  if (a == nullptr || (b == nullptr && pl->r_T > 0)) return fail(ILARGI_ERR_NULL, "%s: operand pointer is NULL", what);
   if (cx < 1) return fail(ILARGI_ERR_SHAPE, "%s: %lld operand columns", what, (long long)cx);
   if (cx > pl->max_cx)
     return fail(ILARGI_ERR_WORKSPACE, "%s: %lld operand columns but the plan was sized for %lld", what,
@@ -839,7 +840,7 @@ ilargi_status_t ilargi_lmm(ilargi_plan_t* plan, const float* X, int64_t cx, floa
 
 ilargi_status_t ilargi_tmm(ilargi_plan_t* plan, const float* Y, int64_t cx, float* out,
                            ilargi_precision_t precision, void* stream) {
-  ilargi_status_t rc = check_call(plan, Y, out, cx, "tmm");
+  ilargi_status_t rc = check_call(plan, out, Y, cx, "tmm");
   if (rc != ILARGI_OK) return rc;
   const bool bf16 = precision == ILARGI_BF16_IN_F32_ACC;
   if (precision != ILARGI_F32 && !bf16) return fail(ILARGI_ERR_UNSUPPORTED, "tmm: unknown precision %d", (int)precision);
@@ -894,7 +895,7 @@ ilargi_status_t ilargi_gd_step(ilargi_plan_t* plan, ilargi_model_t model, float*
 }
 
 ilargi_status_t ilargi_segment_sum(ilargi_plan_t* plan, int k, const float* Y, int64_t cx, float* Z, void* stream) {
-  ilargi_status_t rc = check_call(plan, Y, Z, cx, "segment_sum");
+  ilargi_status_t rc = check_call(plan, Z, Y, cx, "segment_sum");
   if (rc != ILARGI_OK) return rc;
   if (k < 0 || k >= plan->n) return fail(ILARGI_ERR_SHAPE, "segment_sum: source %d of %d", k, plan->n);
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -913,6 +914,7 @@ ilargi_status_t ilargi_segment_sum(ilargi_plan_t* plan, int k, const float* Y, i
 
 ilargi_status_t ilargi_materialize(ilargi_plan_t* plan, float* T, void* stream) {
   if (plan == nullptr) return fail(ILARGI_ERR_NULL, "materialize: plan is NULL");
+  if (plan->r_T == 0) return ILARGI_OK;
   if (T == nullptr) return fail(ILARGI_ERR_NULL, "materialize: T is NULL");
   MatArgs a;
   memset(&a, 0, sizeof(a));

@@ -551,3 +551,64 @@ def test_unaligned_table_pointer_falls_back_to_scalar_loads(il):
     assert rel(il.ilargi_lmm(plan, dev(X)).cpu().numpy(), oracle.lmm(tg, X)) < OP_TOL
     assert rel(il.ilargi_tmm(plan, dev(Y)).cpu().numpy(), oracle.tmm(tg, Y)) < OP_TOL
     assert np.array_equal(il.ilargi_materialize(plan).cpu().numpy(), tg.T32)
+
+
+def test_sixteen_sources_with_shared_columns(il):
+    # the largest source count the boundary accepts; columns shared by up to all of them, missing rows
+    sch = datagen.tiny_random_schema(seed=77, r_T=2_503, c_T=23, n=16)
+    tg = oracle.Target(sch)
+    plan = il.ilargi_plan_create(il.schema_to_device(sch), sch.r_T, sch.c_T, max_cx=16)
+    assert np.array_equal(il.ilargi_materialize(plan).cpu().numpy(), tg.T32)
+    rng = datagen.rng_for(78)
+    for cx in (1, 16):
+        X = rng.standard_normal((sch.c_T, cx)).astype(np.float32)
+        Y = rng.standard_normal((sch.r_T, cx)).astype(np.float32)
+        assert rel(il.ilargi_lmm(plan, dev(X)).cpu().numpy(), oracle.lmm(tg, X)) < OP_TOL
+        assert rel(il.ilargi_tmm(plan, dev(Y)).cpu().numpy(), oracle.tmm(tg, Y)) < OP_TOL
+    G = il.ilargi_crossprod(plan).cpu().numpy()
+    assert rel(G, oracle.crossprod(tg)) < OP_TOL and np.array_equal(G, G.T)
+    with pytest.raises(il.IlargiError) as ei:
+        il.ilargi_plan_create(il.schema_to_device(sch) + il.schema_to_device(sch)[:1], sch.r_T, sch.c_T, max_cx=1)
+    assert ei.value.status == il.ERR_SHAPE
+
+
+def test_source_with_the_maximum_column_count(il):
+    # 4096 columns per source is the limit (one row of the operand slice must fit the LDS staging buffer)
+    rng = datagen.rng_for(79)
+    r_T, r_k, c = 257, 37, 4096
+    R = rng.standard_normal((r_k, c)).astype(np.float32)
+    S = rng.standard_normal((r_T, 3)).astype(np.float32)
+    fk = rng.integers(0, r_k, r_T).astype(np.int32)
+    sch = datagen.Schema([datagen.Source(S, None, np.arange(3, dtype=np.int32)),
+                          datagen.Source(R, fk, np.arange(3, 3 + c, dtype=np.int32))], r_T, 3 + c)
+    tg = oracle.Target(sch)
+    plan = il.ilargi_plan_create(il.schema_to_device(sch), sch.r_T, sch.c_T, max_cx=16)
+    assert np.array_equal(il.ilargi_materialize(plan).cpu().numpy(), tg.T32)
+    for cx in (1, 3, 16):
+        X = rng.standard_normal((sch.c_T, cx)).astype(np.float32)
+        Y = rng.standard_normal((sch.r_T, cx)).astype(np.float32)
+        assert rel(il.ilargi_lmm(plan, dev(X)).cpu().numpy(), oracle.lmm(tg, X)) < OP_TOL
+        assert rel(il.ilargi_tmm(plan, dev(Y)).cpu().numpy(), oracle.tmm(tg, Y)) < OP_TOL
+    G = il.ilargi_crossprod(plan).cpu().numpy()
+    assert rel(G, oracle.crossprod(tg)) < OP_TOL and np.array_equal(G, G.T)
+    too_wide = torch.zeros((r_k, c + 1), device="cuda")
+    with pytest.raises(il.IlargiError) as ei:
+        il.ilargi_plan_create([(too_wide, dev(fk), np.arange(c + 1, dtype=np.int32))], r_T, c + 1, max_cx=1)
+    assert ei.value.status == il.ERR_UNSUPPORTED
+
+
+def test_target_table_without_rows(il):
+    # r_T = 0 (its buffers are empty, their pointers NULL): operators succeed and return empty or all-zero
+    # results, the gradient step is refused
+    D = torch.zeros((0, 2), device="cuda")
+    plan = il.ilargi_plan_create([(D, None, np.array([0, 1], dtype=np.int32))], 0, 2, max_cx=2)
+    assert il.ilargi_materialize(plan).shape == (0, 2)
+    assert il.ilargi_lmm(plan, torch.ones((2, 2), device="cuda")).shape == (0, 2)
+    out = torch.full((2, 2), 7.0, device="cuda")
+    il.ilargi_tmm(plan, torch.zeros((0, 2), device="cuda"), out)
+    assert torch.count_nonzero(out).item() == 0
+    assert torch.count_nonzero(il.ilargi_crossprod(plan)).item() == 0
+    with pytest.raises(il.IlargiError) as ei:
+        il.ilargi_gd_step(plan, il.LINEAR, torch.zeros((2, 1), device="cuda"), torch.zeros(0, device="cuda"),
+                          torch.zeros(1, device="cuda"), torch.zeros(1, device="cuda"))
+    assert ei.value.status == il.ERR_SHAPE
