@@ -220,8 +220,18 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(VEC4 ? (
               acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, xb[nt * 16], acc[nt], 0, 0, 0);
           }
         } else {
+          // whole groups of 16 table columns: one 128-bit read feeds four MFMAs; the remaining columns in
+          // groups of four (K slot q = column kb + q), so that 20 columns cost 20 MFMAs per tile, not 32
           const float* arow = As + (size_t)(t * 16 + li) * lda + 4 * q;
-          for (int step = 0; step < kp / 16; ++step) {
+          const int full = a.cs / 16;
+          for (int kb = 16 * full; kb < a.cs; kb += 4) {
+            const float av = As[(size_t)(t * 16 + li) * lda + kb + q];
+            const float* xb = Xs + ((size_t)(kb >> 2) * kN + li) * 4 + q;
+#pragma unroll
+            for (int nt = 0; nt < kNT; ++nt)
+              acc[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, xb[nt * 64], acc[nt], 0, 0, 0);
+          }
+          for (int step = 0; step < full; ++step) {
             float4 av = *reinterpret_cast<const float4*>(arow + 16 * step);
             const float* xb = Xs + ((size_t)(4 * step + q) * kN + li) * 4;
 #pragma unroll
