@@ -51,7 +51,7 @@ constexpr int kWaves = kBlock / kWave;
 // to bfloat16 (nearest even) where they enter a product.  JG: 16-column tiles of S (kp / 16 rounded to 2 or 4).
 // ST: target rows a wavefront stages at a time (32 or 64).
 template <int MODE, bool VEC4, bool BF16, int JG, int ST>
-__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(VEC4 ? (JG == 2 ? 3 : 2) : (JG == 2 ? 2 : 1)))) void gd_star_kernel(StarArgs a, int kp, int lda, int rtiles) {
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(VEC4 ? (JG == 2 ? 3 : 2) : (JG == 2 ? 2 : 1)))) void gd_star_kernel(StarArgs a, int kp, int lda, int rtiles, int fold) {
   extern __shared__ float lds[];
   float* Xs = lds;                                            // [kp / 4][64][4]  (bf16: [kp / 8][64][8])
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
@@ -64,6 +64,12 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(VEC4 ? (
   float* yS = reinterpret_cast<float*>(jS + ST);              // [ST] label
   const int n0 = blockIdx.y * kN;
   const int nw = min(kN, a.m - n0);
+  // fold: the table has 1..4 columns beyond whole groups of 16.  A tile of R then has 12 rows, and rows 12..15
+  // of the segment-sum MFMA (whose A operand is the 0/1 indicator) carry those columns of S instead, so the
+  // same MFMA forms their share of S^T E; they are collected in the last gacc slot by the lanes q == 3.
+  const int tr = fold ? 12 : 16;                              // rows of R per tile
+  const int full = a.cs / 16;
+  const int njt = fold ? full : kp / 16;                      // 16-column groups of S that take their own MFMAs
 
   // W rows of S's columns -> Xs (shared by the workgroup)
   {
@@ -124,16 +130,16 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(VEC4 ? (
   const int pr = lane / 16, pq = lane % 16;                   // (row mod 4, float4 slot) of the P / Z tile this lane moves
 
   for (int rt = blockIdx.x * kWaves + wave; rt < rtiles; rt += gridDim.x * kWaves) {
-    const int64_t jb = (int64_t)rt * 16;
+    const int64_t jb = (int64_t)rt * tr;
     const int p_begin = a.rowptr[jb];
-    const int p_end = a.rowptr[min(jb + 16, a.r_R)];
+    const int p_end = a.rowptr[min(jb + tr, a.r_R)];
     wave_sync();                                              // the previous tile's Z has left Ps
     // P tile -> Ps (zero beyond the table and the slab)
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int r = pr + 4 * u;
       float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-      if (jb + r < a.r_R && 4 * pq < nw) {
+      if (r < tr && jb + r < a.r_R && 4 * pq < nw) {
         const float* p = a.PZ + (jb + r) * a.ldp + n0 + 4 * pq;
         if (p_vec && 4 * pq + 3 < nw) {
           v = *reinterpret_cast<const float4*>(p);
@@ -223,7 +229,6 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(VEC4 ? (
           // whole groups of 16 table columns: one 128-bit read feeds four MFMAs; the remaining columns in
           // groups of four (K slot q = column kb + q), so that 20 columns cost 20 MFMAs per tile, not 32
           const float* arow = As + (size_t)(t * 16 + li) * lda + 4 * q;
-          const int full = a.cs / 16;
           for (int kb = 16 * full; kb < a.cs; kb += 4) {
             const float av = As[(size_t)(t * 16 + li) * lda + kb + q];
             const float* xb = Xs + ((size_t)(kb >> 2) * kN + li) * 4 + q;
@@ -253,6 +258,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(VEC4 ? (
           const int j = jS[row];                              // -1 beyond the batch
           const float yi = yS[row];
           ind[r] = j == li ? 1.0f : 0.0f;
+          if (fold && li >= 12) ind[r] = As[(size_t)row * lda + 16 * full + (li - 12)];
 #pragma unroll
           for (int nt = 0; nt < kNT; ++nt) {
             float o = 0.0f;
@@ -284,7 +290,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(VEC4 ? (
         const float* acol = As + (size_t)(t * 16 + 4 * q) * lda + li;
 #pragma unroll
         for (int jt = 0; jt < JG; ++jt) {
-          if (jt * 16 < kp) {
+          if (jt < njt) {
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
               float av = acol[(size_t)r * lda + jt * 16];
@@ -297,6 +303,10 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(VEC4 ? (
         }
       }
     }
+    if (fold && q == 3) {
+#pragma unroll
+      for (int nt = 0; nt < kNT; ++nt) gacc[JG - 1][nt] += zacc[nt];
+    }
     // Z tile: through Ps so that rows leave as float4
     wave_sync();
 #pragma unroll
@@ -307,7 +317,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(VEC4 ? (
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int r = pr + 4 * u;
-      if (jb + r < a.r_R && 4 * pq < nw) {
+      if (r < tr && jb + r < a.r_R && 4 * pq < nw) {
         const float4 v = *reinterpret_cast<const float4*>(Ps + r * kN + 4 * pq);
         float* p = a.PZ + (jb + r) * a.ldp + n0 + 4 * pq;
         if (p_vec && 4 * pq + 3 < nw) {
@@ -328,15 +338,19 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(VEC4 ? (
     __syncthreads();
     if (wave == w) {
 #pragma unroll
-      for (int jt = 0; jt < JG; ++jt)
+      for (int jt = 0; jt < JG; ++jt) {
+        const bool tail_slot = fold && jt == JG - 1;          // rows 16 full + r, held by the lanes q == 3
+        if ((jt >= njt && !tail_slot) || (tail_slot && q != 3)) continue;
 #pragma unroll
         for (int nt = 0; nt < kNT; ++nt)
 #pragma unroll
           for (int r = 0; r < 4; ++r) {
-            float* p = red + (size_t)(jt * 16 + 4 * q + r) * kN + nt * 16 + li;
+            const int row = tail_slot ? 16 * full + r : jt * 16 + 4 * q + r;
+            float* p = red + (size_t)row * kN + nt * 16 + li;
             if (w == 0) *p = gacc[jt][nt][r];
             else *p += gacc[jt][nt][r];
           }
+      }
     }
   }
   __syncthreads();
@@ -362,7 +376,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(VEC4 ? (
   }
 }
 
-typedef void (*StarFn)(StarArgs, int, int, int);
+typedef void (*StarFn)(StarArgs, int, int, int, int);
 
 template <int MODE, bool B>
 StarFn pick_star(bool vec4, int jg) {
@@ -407,7 +421,10 @@ hipError_t launch_gd_star(const StarArgs& a, int vec, int mode, bool bf16, int m
   const int kp = (a.cs + kq - 1) / kq * kq;
   const int jg = kp <= 32 ? 2 : 4;
   const int lda = kp + 4;
-  const int rtiles = (int)((a.r_R + 15) / 16);
+  const int tail = a.cs % 16;
+  const int fold = (!bf16 && tail >= 1 && tail <= 4) ? 1 : 0;   // see the kernel: 12-row tiles of R
+  const int tr = fold ? 12 : 16;
+  const int rtiles = (int)((a.r_R + tr - 1) / tr);
   const bool vec4 = vec == 4;
   StarFn fn;
   if (bf16) fn = mode == 1 ? pick_star<1, true>(vec4, jg) : pick_star<2, true>(vec4, jg);
@@ -424,7 +441,7 @@ hipError_t launch_gd_star(const StarArgs& a, int vec, int mode, bool bf16, int m
   if (gx * gy > slots) gx = std::max<int64_t>(1, slots / gy);
   gx = std::min<int64_t>(gx, max_grid);
   if (grid_out) *grid_out = (int)gx;
-  hipLaunchKernelGGL(fn, dim3((unsigned)gx, (unsigned)gy), dim3(kBlock), lds_bytes, st, a, kp, lda, rtiles);
+  hipLaunchKernelGGL(fn, dim3((unsigned)gx, (unsigned)gy), dim3(kBlock), lds_bytes, st, a, kp, lda, rtiles, fold);
   return hipGetLastError();
 }
 

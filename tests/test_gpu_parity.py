@@ -249,11 +249,14 @@ def test_gd_wide_entity_gradient_in_the_assembly_pass(il, model, c_S, m):
 @pytest.mark.parametrize("prec", ["f32", "bf16"])
 @pytest.mark.parametrize("model", ["linear", "logistic"])
 @pytest.mark.parametrize("c_S,r_R,keys,m", [(20, 501, "uniform", 64), (7, 333, ("zipf", 1.05), 33),
-                                            (48, 8_000, "uniform", 100), (64, 16, "uniform", 40)])
+                                            (48, 8_000, "uniform", 100), (64, 16, "uniform", 40),
+                                            (36, 501, "uniform", 64), (50, 333, ("zipf", 1.05), 40),
+                                            (3, 200, "uniform", 33)])
 def test_gd_wide_star_join_pass(il, prec, model, c_S, r_R, keys, m):
     # entity table plus one dimension table that every row joins, more than 32 models: the pass in join order
     # (residual never stored); ragged tiles of R, rows of R nobody joins (r_R = 8000 > r_T / 2), skewed keys,
-    # unaligned and 64-column entity tables, ragged model slabs
+    # unaligned and 64-column entity tables, ragged model slabs; 20, 36, 50 and 3 columns leave 1..4 columns
+    # beyond whole groups of 16, which ride in the segment-sum MFMA (12-row tiles of R)
     rng = datagen.rng_for(1000 + c_S)
     sch = datagen.star_schema(rng, 5_003, c_S, [(r_R, 24, keys)])
     tg = oracle.Target(sch)
