@@ -31,6 +31,14 @@ Readings of the paper taken here (each is also listed in the design document):
 * Logistic regression is only named by the paper (Sec. 3.1, Tab. 7-9).  Read: labels in {0,1},
   ``z = T w``, loss ``mean(softplus(z) - y z)``, gradient ``T^T (sigmoid(z) - y) / r_T``.
 
+* Tab. 2 lists ``T (/) x``, ``f(T)``, ``rowSum(T)`` and ``colSum(T)`` with cost ``m_T`` materialized and
+  ``sum_k m_k`` factorized and defines them no further.  Read: ``(/)`` is element-wise arithmetic
+  with a scalar ``x`` (times, divide, plus, minus, power), ``f`` an element-wise function (exp, log,
+  sqrt, abs, square); both are defined on the cells of the target table, ``rowSum``/``colSum`` are its
+  row and column sums.  That the factorized form may apply the operation to every source table
+  instead is a property this file does not use; the pins check when it holds (every target cell
+  fed by exactly one source cell; for times and divide always).
+
 Pins (tests/test_oracle_pins.py): brute force from Def. 1 / Def. 2 with dense 0/1 matrices on tiny
 schemas; the star-join special case ``T = [S | R[fk]]``; ``T I = T``; ``rowSum``/``colSum`` (Tab. 2);
 the adjoint identity; the weighted-Gram closed form of ``T^T T`` for a star join; the closed-form
@@ -260,3 +268,73 @@ def complexity_lmm(schema, c_X: int) -> Tuple[int, int]:
     mat = c_X * m_T + schema.r_T * m_X
     fact = sum(c_X * s.rows * s.cols + s.rows * m_X for s in schema.sources)
     return mat, fact
+
+
+# ----------------------------------------------------------------------------- scalar operators (Tab. 2)
+ELEMENTWISE_OPS = ("mul", "div", "add", "sub", "pow", "exp", "log", "sqrt", "abs", "square")
+
+
+def apply_elementwise(A: np.ndarray, op: str, x: float = 0.0) -> np.ndarray:
+    """``A (/) x`` or ``f(A)`` cell by cell in float64 (Tab. 2, first two rows)."""
+    A = np.asarray(A, dtype=np.float64)
+    if op == "mul":
+        return A * x
+    if op == "div":
+        return A / x
+    if op == "add":
+        return A + x
+    if op == "sub":
+        return A - x
+    if op == "pow":
+        return np.power(A, x)
+    if op == "exp":
+        return np.exp(A)
+    if op == "log":
+        return np.log(A)
+    if op == "sqrt":
+        return np.sqrt(A)
+    if op == "abs":
+        return np.abs(A)
+    if op == "square":
+        return A * A
+    raise ValueError(op)
+
+
+def elementwise(target, op: str, x: float = 0.0) -> np.ndarray:
+    """The element-wise operators of Tab. 2 on the materialized table, float64, ``r_T x c_T``."""
+    tg = _as_target(target)
+    out = np.empty((tg.r_T, tg.c_T), dtype=np.float64)
+    for lo, hi in _chunks(tg.r_T):
+        out[lo:hi] = apply_elementwise(tg.rows64(lo, hi), op, x)
+    return out
+
+
+def row_sum(target) -> np.ndarray:
+    """``rowSum(T)`` (Tab. 2): float64 vector of length ``r_T``."""
+    tg = _as_target(target)
+    out = np.empty(tg.r_T, dtype=np.float64)
+    for lo, hi in _chunks(tg.r_T):
+        out[lo:hi] = tg.rows64(lo, hi).sum(axis=1)
+    return out
+
+
+def col_sum(target) -> np.ndarray:
+    """``colSum(T)`` (Tab. 2): float64 vector of length ``c_T``."""
+    tg = _as_target(target)
+    out = np.zeros(tg.c_T, dtype=np.float64)
+    for lo, hi in _chunks(tg.r_T):
+        out += tg.rows64(lo, hi).sum(axis=0)
+    return out
+
+
+def cover_counts(schema) -> np.ndarray:
+    """How many source cells feed each target cell: ``sum_k I_k 1 1^T M_k^T`` (Def. 1, Def. 2), int64
+    ``r_T x c_T``.  The factorized element-wise operators need every count to be exactly one."""
+    C = np.zeros((schema.r_T, schema.c_T), dtype=np.int64)
+    for s in schema.sources:
+        if s.D.shape[0] == 0 or s.D.shape[1] == 0:
+            continue
+        rows = np.arange(schema.r_T) if s.row_idx is None else np.flatnonzero(np.asarray(s.row_idx) >= 0)
+        cols = np.asarray(s.col_map)[np.asarray(s.col_map) >= 0]
+        C[np.ix_(rows, cols)] += 1
+    return C

@@ -333,3 +333,95 @@ def test_complexity_formula_tab2():
     mat, fact = oracle.complexity_lmm(sch, 1)
     assert mat == 1 * 1000 * 220 + 1000 * 220
     assert fact == (1000 * 20 + 1000 * 220) + (100 * 200 + 100 * 220)
+
+
+# ----------------------------------------------------------------------------- scalar operators (Tab. 2)
+def _assemble_dense(schema, tables):
+    """sum_k I_k A_k M_k^T with the dense 0/1 matrices of Def. 1 / Def. 2 and the given per-source tables."""
+    out = np.zeros((schema.r_T, schema.c_T))
+    for s, A in zip(schema.sources, tables):
+        I = oracle.dense_indicator(s.row_idx, schema.r_T, s.D.shape[0])
+        M = oracle.dense_mapping(s.col_map, schema.c_T)
+        out += I @ np.asarray(A, dtype=np.float64) @ M.T
+    return out
+
+
+def _star(seed, r_T=23, positive=False):
+    rng = datagen.rng_for(seed)
+    sch = datagen.star_schema(rng, r_T, 3, [(5, 4, "uniform"), (7, 2, "uniform")])
+    if positive:
+        for s in sch.sources:
+            s.D[...] = np.abs(s.D) + 0.5
+    return sch
+
+
+def test_row_and_column_sums_equal_sums_of_the_dense_definition():
+    for seed in (41, 42):
+        sch = datagen.tiny_random_schema(seed, r_T=11, c_T=6, n=3)
+        T = oracle.brute_force_target(sch)
+        np.testing.assert_allclose(oracle.row_sum(sch), T.sum(axis=1), rtol=0, atol=1e-6)
+        np.testing.assert_allclose(oracle.col_sum(sch), T.sum(axis=0), rtol=0, atol=1e-6)
+    sch = _star(43)
+    # a star join: colSum = [colSum(S) | fan-out-weighted colSum(R_k)]; every key of R_1 used k_j times
+    fk = sch.sources[1].row_idx
+    want = np.bincount(fk, minlength=5) @ sch.sources[1].D.astype(np.float64)
+    np.testing.assert_allclose(oracle.col_sum(sch)[3:7], want, rtol=1e-6)
+    np.testing.assert_allclose(oracle.row_sum(sch).sum(), oracle.col_sum(sch).sum(), rtol=1e-12)
+
+
+@pytest.mark.parametrize("op,x", [("mul", -1.75), ("div", 3.0), ("add", 0.5), ("sub", 2.0), ("pow", 3.0),
+                                  ("exp", 0.0), ("abs", 0.0), ("square", 0.0)])
+def test_elementwise_on_the_table_equals_elementwise_on_the_sources_when_every_cell_has_one_feeder(op, x):
+    # the claim behind Tab. 2's cost sum_k m_k: with exactly one source cell per target cell the operator can
+    # be applied to the source tables and the result assembled afterwards (dense Def. 1 / Def. 2 matrices)
+    sch = _star(44)
+    assert np.all(oracle.cover_counts(sch) == 1)
+    want = oracle.apply_elementwise(oracle.brute_force_target(sch), op, x)
+    got = _assemble_dense(sch, [oracle.apply_elementwise(s.D, op, x) for s in sch.sources])
+    np.testing.assert_allclose(oracle.elementwise(sch, op, x), want, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-12)
+
+
+@pytest.mark.parametrize("op", ["log", "sqrt"])
+def test_elementwise_functions_with_a_restricted_domain(op):
+    sch = _star(45, positive=True)
+    want = oracle.apply_elementwise(oracle.brute_force_target(sch), op)
+    got = _assemble_dense(sch, [oracle.apply_elementwise(s.D, op) for s in sch.sources])
+    np.testing.assert_allclose(oracle.elementwise(sch, op), want, rtol=1e-12)
+    np.testing.assert_allclose(got, want, rtol=1e-12)
+
+
+def test_elementwise_closed_forms():
+    sch = _star(46, positive=True)
+    T = oracle.brute_force_target(sch)
+    np.testing.assert_allclose(oracle.apply_elementwise(oracle.elementwise(sch, "log"), "exp"), T, rtol=1e-12)
+    np.testing.assert_allclose(oracle.apply_elementwise(oracle.elementwise(sch, "square"), "sqrt"), T, rtol=1e-12)
+    np.testing.assert_allclose(oracle.elementwise(sch, "pow", 2.0), oracle.elementwise(sch, "square"), rtol=1e-12)
+    np.testing.assert_allclose(oracle.elementwise(sch, "div", 4.0), oracle.elementwise(sch, "mul", 0.25), rtol=1e-12)
+    np.testing.assert_allclose(oracle.elementwise(sch, "sub", 1.5), oracle.elementwise(sch, "add", -1.5), rtol=1e-12)
+    assert oracle.elementwise(sch, "exp")[0, 0] == pytest.approx(np.exp(float(T[0, 0])), rel=1e-12)
+
+
+def test_times_and_divide_distribute_over_shared_cells_but_plus_does_not():
+    # shared columns and unmatched rows: the product with a scalar is linear, so it may still be applied to the
+    # sources; plus is not (a cell with two feeders would receive x twice, an empty cell none)
+    sch = datagen.tiny_random_schema(47, r_T=13, c_T=5, n=3)
+    C = oracle.cover_counts(sch)
+    assert C.max() > 1 and C.min() == 0
+    T = oracle.brute_force_target(sch)
+    for op, x in (("mul", 2.5), ("div", -4.0)):
+        got = _assemble_dense(sch, [oracle.apply_elementwise(s.D, op, x) for s in sch.sources])
+        np.testing.assert_allclose(got, oracle.apply_elementwise(T, op, x), rtol=1e-12, atol=1e-12)
+    got = _assemble_dense(sch, [oracle.apply_elementwise(s.D, "add", 1.0) for s in sch.sources])
+    np.testing.assert_allclose(got, T + C, rtol=1e-12, atol=1e-12)      # x arrives once per feeder
+    assert not np.allclose(got, T + 1.0)
+
+
+def test_cover_counts_from_the_dense_definition():
+    sch = datagen.tiny_random_schema(48, r_T=9, c_T=7, n=4)
+    want = np.zeros((sch.r_T, sch.c_T))
+    for s in sch.sources:
+        I = oracle.dense_indicator(s.row_idx, sch.r_T, s.D.shape[0])
+        M = oracle.dense_mapping(s.col_map, sch.c_T)
+        want += I @ np.ones(s.D.shape) @ M.T
+    assert np.array_equal(oracle.cover_counts(sch), want.astype(np.int64))
