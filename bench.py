@@ -221,6 +221,35 @@ def kernel_model(shp, r_T, c_T):
     return m
 
 
+def scalar_ops(il, torch, plan, mplan, sch):
+    """Tab. 2, first four rows, on the same schema: element-wise operators, rowSum and colSum, factorized
+    (on the source tables) vs the same entry points on the materialized table.  Bytes: an element-wise
+    operator reads and writes every cell it touches once; rowSum is the left multiply by ones; colSum
+    reads the tables once (the fan-out vectors are part of the plan)."""
+    shp = shapes_of(sch)
+    cells_f = sum(r * c for r, c, _ in shp)
+    cells_m = sch.r_T * sch.c_T
+    outs_f = [torch.empty_like(D) for D, _ in plan._borrowed]
+    outs_m = [torch.empty_like(D) for D, _ in mplan._borrowed]
+    rs = torch.empty(sch.r_T, device="cuda")
+    cs = torch.empty(sch.c_T, device="cuda")
+    out = {}
+    cases = (("mul", lambda pl, o: il.ilargi_elementwise(pl, "mul", 1.5, outs=o), 8 * cells_f, 8 * cells_m),
+             ("exp", lambda pl, o: il.ilargi_elementwise(pl, "exp", 0.0, outs=o), 8 * cells_f, 8 * cells_m),
+             ("row_sum", lambda pl, o: il.ilargi_row_sum(pl, rs), bytes_lmm(shp, sch.r_T, sch.c_T, 1),
+              4 * cells_m + 4 * sch.r_T + 4 * sch.c_T),
+             ("col_sum", lambda pl, o: il.ilargi_col_sum(pl, cs), 4 * cells_f + 4 * sum(r for r, _, _ in shp) + 4 * sch.c_T,
+              4 * cells_m + 4 * sch.r_T + 4 * sch.c_T))
+    for name, fn, b_f, b_m in cases:
+        t_f = time_loop(torch, lambda: fn(plan, outs_f), 20)
+        t_m = time_loop(torch, lambda: fn(mplan, outs_m), 10)
+        out[name] = {"factorized_us": round(t_f * 1e6, 1), "materialized_us": round(t_m * 1e6, 1),
+                     "speedup": round(t_m / t_f, 2), "factorized_GBps": round(b_f / t_f / 1e9, 1),
+                     "materialized_GBps": round(b_m / t_m / 1e9, 1)}
+    out["cells"] = {"factorized": int(cells_f), "materialized": int(cells_m), "ratio_tab2": round(cells_m / cells_f, 2)}
+    return out
+
+
 def wide_batch(il, torch, datagen, dev):
     """The batched hyper-parameter workload (256 linear regressions at once on the same schema, seed 4):
     gradient-descent iterations/s and matrix-core utilisation, float32 and bfloat16 inputs, factorized vs
@@ -435,6 +464,7 @@ def main() -> int:
         o1 = torch.empty((sch.r_T, c), device="cuda"); o2 = torch.empty((sch.c_T, c), device="cuda")
         mat_ops[f"lmm_c{c}_us"] = round(time_loop(torch, lambda: il.ilargi_lmm(mplan, X, o1), 10) * 1e6, 1)
         mat_ops[f"tmm_c{c}_us"] = round(time_loop(torch, lambda: il.ilargi_tmm(mplan, Y, o2), 10) * 1e6, 1)
+    scalar = scalar_ops(il, torch, plan, mplan, sch)
     del mplan
 
     probe = stream_probe(il, torch)
@@ -478,6 +508,7 @@ def main() -> int:
         "plan_build_ms": round(plan_ms, 2),
         "kernels": dict(sorted(kernels.items(), key=lambda kv: -kv[1]["us_per_step"])[:16]),
         "stream_probe": probe,
+        "scalar_ops": scalar,
         "wide_batch": wide,
         "other_configs": configs,
         "roofline": roofline,

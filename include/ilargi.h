@@ -117,6 +117,41 @@ ilargi_status_t ilargi_gd_step(ilargi_plan_t* plan, ilargi_model_t model, float*
                                const float* y, const float* lr, float* loss,
                                ilargi_precision_t precision, void* stream);
 
+/* Element-wise operators of Tab. 2 (first two rows): arithmetic with a scalar, T (/) x, and functions f(T). */
+typedef enum {
+  ILARGI_OP_MUL = 0,    /* t * x */
+  ILARGI_OP_DIV = 1,    /* t / x */
+  ILARGI_OP_ADD = 2,    /* t + x */
+  ILARGI_OP_SUB = 3,    /* t - x */
+  ILARGI_OP_POW = 4,    /* t ^ x */
+  ILARGI_OP_EXP = 5,    /* exp(t);  x is ignored from here on */
+  ILARGI_OP_LOG = 6,
+  ILARGI_OP_SQRT = 7,
+  ILARGI_OP_ABS = 8,
+  ILARGI_OP_SQUARE = 9
+} ilargi_elementwise_t;
+
+/* T (/) x or f(T) in factorized form (Tab. 2: sum_k m_k operations instead of m_T): the result is the
+ * table described by the same row_idx / col_map with source tables D_out[k] = op(D_k, x).
+ * D_out: host array of n device pointers, D_out[k] r_k x c_k float32 (entries of empty sources are not
+ * read); D_out[k] may be the source table itself, and if every table is updated in place the plan keeps
+ * describing the result.  The factorized form equals the operator on the cells of T
+ *   - always for MUL and DIV (they distribute over the sums of shared cells and keep empty cells 0);
+ *   - for SQRT, ABS, SQUARE and POW with x > 0 (zero stays zero) when no target column is fed by two
+ *     sources;
+ *   - for ADD, SUB, EXP, LOG and POW with x <= 0 when, in addition, every target column is fed and
+ *     every source reaches every target row (each cell of T has exactly one source cell).
+ * Otherwise the call returns UNSUPPORTED and writes nothing.  Errors: NULL, UNSUPPORTED. */
+ilargi_status_t ilargi_elementwise(ilargi_plan_t* plan, ilargi_elementwise_t op, float x,
+                                   float* const* D_out, void* stream);
+
+/* rowSum(T) (Tab. 2) = T 1: out device float[r_T]. */
+ilargi_status_t ilargi_row_sum(ilargi_plan_t* plan, float* out, void* stream);
+
+/* colSum(T) (Tab. 2) = sum_k M_k (D_k^T cnt_k), cnt_k[j] = number of target rows taking row j of source k
+ * (kept with the plan): no pass over the r_T target rows.  out device float[c_T]. */
+ilargi_status_t ilargi_col_sum(ilargi_plan_t* plan, float* out, void* stream);
+
 /* I_k^T Y for one source (the segmented sum inside ilargi_tmm), exposed for inspection:
  * Z[j, :] = sum of Y[i, :] over the target rows i with row_idx_k[i] == j.
  * Y device r_T x cx, Z device r_k x cx. */
@@ -131,7 +166,8 @@ ilargi_status_t ilargi_plan_inverse_index(const ilargi_plan_t* plan, int k, cons
 /* Per-kernel timing for benchmarks.  After trace_begin, every launch of the kernel family named by
  * `tag` ("*" = every family; "<label>/<family>" = that family under one label) is bracketed by a pair of HIP events on the call's stream (at most
  * max_launches pairs; later launches run untimed).  Families: "lmm_rows:<k>" (product of source k),
- * "lmm_assemble", "segsum:<k>", "colred:<k>", "finalize", "materialize", "gram".  trace_label sets a
+ * "lmm_assemble", "segsum:<k>", "colred:<k>", "finalize", "materialize", "gram:<k n + l>", "star_pass",
+ * "elementwise:<k>".  trace_label sets a
  * prefix ("<label>/<family>") for the launches that follow, so a caller can tell its operators apart.
  * trace_end waits for the recorded events, writes the elapsed milliseconds of up to `capacity`
  * launches to the host array `ms` (may be NULL), stores the number of recorded launches in *count

@@ -37,7 +37,8 @@ STATUS_NAMES = ["OK", "ERR_NULL", "ERR_SHAPE", "ERR_COLMAP", "ERR_INDEX_RANGE", 
 
 EXPORTED = [
     "ilargi_plan_workspace_bytes", "ilargi_plan_create", "ilargi_plan_destroy", "ilargi_lmm", "ilargi_tmm",
-    "ilargi_crossprod", "ilargi_materialize", "ilargi_gd_step", "ilargi_segment_sum",
+    "ilargi_crossprod", "ilargi_materialize", "ilargi_gd_step", "ilargi_elementwise", "ilargi_row_sum",
+    "ilargi_col_sum", "ilargi_segment_sum",
     "ilargi_plan_inverse_index", "ilargi_plan_trace_begin", "ilargi_plan_trace_label", "ilargi_plan_trace_end",
     "ilargi_plan_trace_name", "ilargi_stream_probe",
     "ilargi_last_error",
@@ -62,6 +63,9 @@ lib.ilargi_crossprod.argtypes = [_vp, _vp, _vp]
 lib.ilargi_materialize.argtypes = [_vp, _vp, _vp]
 lib.ilargi_gd_step.argtypes = [_vp, _int, _vp, _i64, _vp, _vp, _vp, _int, _vp]
 lib.ilargi_segment_sum.argtypes = [_vp, _int, _vp, _i64, _vp, _vp]
+lib.ilargi_elementwise.argtypes = [_vp, _int, ctypes.c_float, _vp, _vp]
+lib.ilargi_row_sum.argtypes = [_vp, _vp, _vp]
+lib.ilargi_col_sum.argtypes = [_vp, _vp, _vp]
 lib.ilargi_plan_inverse_index.argtypes = [_vp, _int, ctypes.POINTER(_vp), ctypes.POINTER(_vp), ctypes.POINTER(_i64)]
 lib.ilargi_plan_trace_begin.argtypes = [_vp, ctypes.c_char_p, _int]
 lib.ilargi_plan_trace_end.argtypes = [_vp, ctypes.POINTER(ctypes.c_float), _int, ctypes.POINTER(_int)]
@@ -249,6 +253,46 @@ def ilargi_gd_step(plan: Plan, model: int, W, y, lr, loss=None, precision: int =
     _check(lib.ilargi_gd_step(plan.handle, model, W.data_ptr(), m, y.data_ptr(), lr.data_ptr(), lptr or None,
                               precision, _stream_ptr(stream)), "ilargi_gd_step")
     return W
+
+
+OPS = {"mul": 0, "div": 1, "add": 2, "sub": 3, "pow": 4, "exp": 5, "log": 6, "sqrt": 7, "abs": 8, "square": 9}
+
+
+def ilargi_elementwise(plan: Plan, op, x: float = 0.0, outs=None, stream=None):
+    """``op``: a name from ``OPS`` or its code.  ``outs``: one float32 CUDA tensor per source, shaped like
+    the source tables (``None``: new tensors; the source tensors themselves: in place).  Returns ``outs``."""
+    torch = _torch()
+    code = OPS[op] if isinstance(op, str) else int(op)
+    if outs is None:
+        outs = [torch.empty_like(D) for D, _ in plan._borrowed]
+    if len(outs) != len(plan._borrowed):
+        raise TypeError("one output tensor per source")
+    ptrs = (ctypes.c_void_p * len(outs))()
+    for k, (o, (D, _)) in enumerate(zip(outs, plan._borrowed)):
+        _dev_f32(o, "outs[k]")
+        if tuple(o.shape) != tuple(D.shape):
+            raise TypeError("outs[k] must have the shape of source k")
+        ptrs[k] = o.data_ptr() if o.numel() > 0 else None
+    _check(lib.ilargi_elementwise(plan.handle, code, float(x), ptrs, _stream_ptr(stream)), "ilargi_elementwise")
+    return outs
+
+
+def ilargi_row_sum(plan: Plan, out=None, stream=None):
+    torch = _torch()
+    if out is None:
+        out = torch.empty(plan.r_T, dtype=torch.float32, device=plan.workspace.device)
+    _dev_f32(out, "out")
+    _check(lib.ilargi_row_sum(plan.handle, out.data_ptr() if out.numel() else None, _stream_ptr(stream)), "ilargi_row_sum")
+    return out
+
+
+def ilargi_col_sum(plan: Plan, out=None, stream=None):
+    torch = _torch()
+    if out is None:
+        out = torch.empty(plan.c_T, dtype=torch.float32, device=plan.workspace.device)
+    _dev_f32(out, "out")
+    _check(lib.ilargi_col_sum(plan.handle, out.data_ptr(), _stream_ptr(stream)), "ilargi_col_sum")
+    return out
 
 
 def ilargi_segment_sum(plan: Plan, k: int, Y, out=None, stream=None):

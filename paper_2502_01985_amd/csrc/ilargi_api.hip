@@ -45,7 +45,7 @@ struct SourcePlan {
   std::vector<int32_t> colmap_h;
   // offsets into the workspace
   size_t o_colmap = 0, o_tcol = 0, o_rowptr = 0, o_perm = 0, o_chunk_seg = 0, o_chunk_beg = 0, o_chunk_end = 0,
-         o_long_seg = 0, o_long_first = 0, o_chunk_partial = 0, o_pz = 0, o_partial = 0, o_g = 0;
+         o_long_seg = 0, o_long_first = 0, o_chunk_partial = 0, o_pz = 0, o_partial = 0, o_g = 0, o_cnt = 0;
   int64_t nch_max = 0, nl_max = 0;
   int n_chunks = 0, n_long = 0;
   int64_t nnz = 0;
@@ -53,7 +53,7 @@ struct SourcePlan {
 };
 
 struct Layout {
-  size_t o_gslot = 0, o_gj0 = 0, o_ct_slot = 0, o_ct_j = 0;
+  size_t o_gslot = 0, o_gj0 = 0, o_ct_slot = 0, o_ct_j = 0, o_ones = 0;
   size_t o_flags = 0, o_tcol_table = 0, o_pairs = 0, o_E = 0, o_loss = 0, o_sort = 0, o_hist = 0, o_zc = 0,
          o_gpartial = 0, o_blocks = 0;
   int64_t zc_floats = 0, gpartial_floats = 0, blocks_floats = 0;
@@ -71,6 +71,8 @@ struct ilargi_plan {
   Layout lay;
   int fused = -1;   // identity source whose product is fused into the assembly pass
   int star_k = -1;  // two-table star join: the dimension table every target row joins (else -1)
+  bool cover_disjoint = false;  // no target column is fed by two sources
+  bool cover_full = false;      // every target column is fed and every source reaches every target row
   bool mat_vec4 = false;  // the grouped column tables of the vectorized join-gather are valid
   bool mat_cols = false;  // the per-column feeder tables (at most two feeders per column) are valid
   int npairs = 0;
@@ -151,6 +153,7 @@ ilargi_status_t make_layout(int n, const ilargi_source_t* s, int64_t r_T, int64_
   lay.o_gj0 = take(sizeof(int32_t) * c_T);
   lay.o_ct_slot = take(sizeof(int32_t) * 2 * c_T);
   lay.o_ct_j = take(sizeof(int32_t) * 2 * c_T);
+  lay.o_ones = take(sizeof(float) * c_T);
   const int64_t wmax = std::max<int64_t>(max_cx, cmax);
   for (int k = 0; k < n; ++k) {
     SourcePlan& p = src[k];
@@ -171,6 +174,7 @@ ilargi_status_t make_layout(int n, const ilargi_source_t* s, int64_t r_T, int64_
     p.o_pz = take(sizeof(float) * std::max<int64_t>(p.rows, 1) * max_cx);
     p.o_partial = take(sizeof(float) * kColredBlocks * std::max<int64_t>(p.cols, 1) * kNarrowCT);
     p.o_g = take(sizeof(float) * std::max<int64_t>(p.cols, 1) * max_cx);
+    p.o_cnt = take(sizeof(float) * std::max<int64_t>(p.rows, 1));
   }
   lay.o_E = take(sizeof(float) * std::max<int64_t>(r_T, 1) * max_cx);
   lay.o_loss = take(sizeof(float) * std::max<int64_t>(32768 * kNarrowCT, 1024 * max_cx));
@@ -349,7 +353,10 @@ ilargi_status_t tmm_pass(ilargi_plan* pl, const float* Y, int ldy, int col0, int
     ColredArgs c;
     memset(&c, 0, sizeof(c));
     c.D = p.D; c.rows = p.rows; c.ck = (int)p.cols; c.vec = p.vec;
-    if (p.ident) {
+    if (Y == nullptr) {
+      // colSum: I_k^T 1 is the fan-out vector kept with the plan
+      c.Z = pl->at<float>(p.o_cnt); c.ldz = 1; c.col0 = 0;
+    } else if (p.ident) {
       c.Z = Y; c.ldz = ldy; c.col0 = col0;
     } else {
       SegArgs s = seg_args(pl, k);
@@ -658,6 +665,27 @@ ilargi_status_t ilargi_plan_create(int n, const ilargi_source_t* sources, int64_
     const SourcePlan& p = pl->src[k];
     if (p.ident && !p.empty && p.rows * p.cols > best) { best = p.rows * p.cols; pl->fused = k; }
   }
+  // scalar operators: which element-wise operators may act on the sources alone, the vector of ones of
+  // rowSum and the fan-out vectors of colSum
+  {
+    pl->cover_disjoint = true;
+    pl->cover_full = true;
+    for (int64_t t = 0; t < c_T; ++t) {
+      int feeders = 0;
+      for (int k = 0; k < n; ++k) feeders += (!pl->src[k].empty && tcol[k][(size_t)t] >= 0) ? 1 : 0;
+      if (feeders > 1) pl->cover_disjoint = false;
+      if (feeders == 0) pl->cover_full = false;
+    }
+    for (int k = 0; k < n; ++k)
+      if (!pl->src[k].empty && pl->src[k].nnz != r_T) pl->cover_full = false;
+    HIP_TRY(launch_fill(pl->at<float>(lay.o_ones), c_T, 1.0f, st));
+    for (int k = 0; k < n; ++k) {
+      const SourcePlan& p = pl->src[k];
+      if (p.empty) continue;
+      if (p.ident) HIP_TRY(launch_fill(pl->at<float>(p.o_cnt), p.rows, 1.0f, st));
+      else HIP_TRY(launch_fanout(pl->at<int32_t>(p.o_rowptr), p.rows, pl->at<float>(p.o_cnt), st));
+    }
+  }
   // two-table star join: a full-height identity source plus one table that every target row joins, without
   // very long segments; wide batches of models then run their gradient pass in join order
   {
@@ -892,6 +920,46 @@ ilargi_status_t ilargi_gd_step(ilargi_plan_t* plan, ilargi_model_t model, float*
     if (rc != ILARGI_OK) return rc;
   }
   return ILARGI_OK;
+}
+
+ilargi_status_t ilargi_elementwise(ilargi_plan_t* plan, ilargi_elementwise_t op, float x, float* const* D_out,
+                                   void* stream) {
+  if (plan == nullptr) return fail(ILARGI_ERR_NULL, "elementwise: plan is NULL");
+  if (D_out == nullptr) return fail(ILARGI_ERR_NULL, "elementwise: D_out is NULL");
+  const int o = (int)op;
+  if (o < 0 || o > (int)ILARGI_OP_SQUARE) return fail(ILARGI_ERR_UNSUPPORTED, "elementwise: unknown operator %d", o);
+  // which cover of the target cells the factorized form needs (Tab. 2 states the cost, not the condition)
+  const bool linear = op == ILARGI_OP_MUL || op == ILARGI_OP_DIV;
+  const bool keeps_zero = op == ILARGI_OP_SQRT || op == ILARGI_OP_ABS || op == ILARGI_OP_SQUARE ||
+                          (op == ILARGI_OP_POW && x > 0.0f);
+  if (!linear && !plan->cover_disjoint)
+    return fail(ILARGI_ERR_UNSUPPORTED, "elementwise: operator %d needs target columns fed by one source each", o);
+  if (!linear && !keeps_zero && !plan->cover_full)
+    return fail(ILARGI_ERR_UNSUPPORTED, "elementwise: operator %d needs every target cell fed by a source cell", o);
+  for (int k = 0; k < plan->n; ++k)
+    if (!plan->src[k].empty && D_out[k] == nullptr) return fail(ILARGI_ERR_NULL, "elementwise: D_out[%d] is NULL", k);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  for (int k = 0; k < plan->n; ++k) {
+    const SourcePlan& p = plan->src[k];
+    if (p.empty) continue;
+    TraceScope ts(plan, "elementwise", k, st);
+    HIP_TRY(launch_elementwise(o, p.D, D_out[k], p.rows * p.cols, x, st));
+  }
+  return ILARGI_OK;
+}
+
+ilargi_status_t ilargi_row_sum(ilargi_plan_t* plan, float* out, void* stream) {
+  if (plan == nullptr) return fail(ILARGI_ERR_NULL, "row_sum: plan is NULL");
+  if (plan->r_T == 0) return ILARGI_OK;
+  if (out == nullptr) return fail(ILARGI_ERR_NULL, "row_sum: out is NULL");
+  return lmm_pass(plan, plan->at<float>(plan->lay.o_ones), 1, 0, 1, out, 1, 0, nullptr, nullptr, false,
+                  static_cast<hipStream_t>(stream));
+}
+
+ilargi_status_t ilargi_col_sum(ilargi_plan_t* plan, float* out, void* stream) {
+  if (plan == nullptr) return fail(ILARGI_ERR_NULL, "col_sum: plan is NULL");
+  if (out == nullptr) return fail(ILARGI_ERR_NULL, "col_sum: out is NULL");
+  return tmm_pass(plan, nullptr, 1, 0, 1, out, 1, 0, nullptr, nullptr, 0, 0.0f, static_cast<hipStream_t>(stream));
 }
 
 ilargi_status_t ilargi_segment_sum(ilargi_plan_t* plan, int k, const float* Y, int64_t cx, float* Z, void* stream) {

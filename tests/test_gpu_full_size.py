@@ -114,6 +114,22 @@ def test_config1_materialized_plan_agrees(il):
 
 
 # ------------------------------------------------------------------ configuration 2 (logistic regression, Zipf keys)
+def test_config1_scalar_operators(il):
+    # Tab. 2, first four rows, at full size: sums against the oracle; an element-wise operator applied to the
+    # sources, checked on the table it describes (a sample of rows through the oracle, cell by cell)
+    sch, tg, plan, _ = Problem.get(il, "config1", 16)
+    assert rel(il.ilargi_row_sum(plan).cpu().numpy(), oracle.row_sum(tg)) < OP_TOL
+    assert rel(il.ilargi_col_sum(plan).cpu().numpy(), oracle.col_sum(tg)) < OP_TOL
+    srcs = il.schema_to_device(sch)
+    plan2 = il.ilargi_plan_create(srcs, sch.r_T, sch.c_T, max_cx=1)
+    outs = il.ilargi_elementwise(plan2, "exp", 0.0)
+    plan3 = il.ilargi_plan_create([(o, idx, cm) for o, (_, idx, cm) in zip(outs, srcs)], sch.r_T, sch.c_T, max_cx=1)
+    T2 = il.ilargi_materialize(plan3)
+    rows = datagen.rng_for(5).integers(0, sch.r_T, 4_000)
+    want = oracle.apply_elementwise(tg.T32[rows], "exp")
+    np.testing.assert_allclose(T2[torch.from_numpy(rows).cuda()].cpu().numpy(), want, rtol=2e-6)
+
+
 def test_config2_logistic_regression(il):
     sch, tg, plan, y = Problem.get(il, "config2", 4, "logistic")
     gold = np.load(os.path.join(GOLDEN, "config2_gd.npz"))

@@ -615,3 +615,82 @@ def test_target_table_without_rows(il):
         il.ilargi_gd_step(plan, il.LINEAR, torch.zeros((2, 1), device="cuda"), torch.zeros(0, device="cuda"),
                           torch.zeros(1, device="cuda"), torch.zeros(1, device="cuda"))
     assert ei.value.status == il.ERR_SHAPE
+
+
+# ------------------------------------------------------------------ scalar operators (Tab. 2)
+@pytest.mark.parametrize("name", ALL)
+def test_row_sum_and_col_sum(il, name):
+    sch, tg, plan = get(il, name)
+    assert rel(il.ilargi_row_sum(plan).cpu().numpy(), oracle.row_sum(tg)) < OP_TOL
+    assert rel(il.ilargi_col_sum(plan).cpu().numpy(), oracle.col_sum(tg)) < OP_TOL
+
+
+def _dense_after(il, sch, srcs, outs):
+    """The table the result of an element-wise operator describes: same index arrays, new source tables."""
+    plan2 = il.ilargi_plan_create([(o, idx, cm) for o, (_, idx, cm) in zip(outs, srcs)], sch.r_T, sch.c_T, max_cx=1)
+    return il.ilargi_materialize(plan2).cpu().numpy()
+
+
+ELEMENTWISE_CASES = [("mul", -1.75), ("div", 3.0), ("add", 0.5), ("sub", 2.0), ("pow", 3.0), ("pow", 0.5),
+                     ("exp", 0.0), ("log", 0.0), ("sqrt", 0.0), ("abs", 0.0), ("square", 0.0)]
+
+
+@pytest.mark.parametrize("op,x", ELEMENTWISE_CASES)
+@pytest.mark.parametrize("maker", ["star", "star_unaligned"])
+def test_elementwise_on_a_star_join(il, maker, op, x):
+    # every target cell has exactly one source cell: all operators may act on the source tables
+    rng = datagen.rng_for(1200)
+    if maker == "star":
+        sch = datagen.star_schema(rng, 20_011, 20, [(1_003, 200, "uniform"), (57, 8, ("zipf", 1.1))])
+    else:
+        sch = datagen.star_schema(rng, 3_001, 3, [(101, 7, "uniform")])
+    if op in ("log", "sqrt") or (op == "pow" and x != int(x)):
+        for s_ in sch.sources:
+            s_.D[...] = np.abs(s_.D) + 0.25
+    tg = oracle.Target(sch)
+    srcs = il.schema_to_device(sch)
+    plan = il.ilargi_plan_create(srcs, sch.r_T, sch.c_T, max_cx=1)
+    outs = il.ilargi_elementwise(plan, op, x)
+    for o, (D, _, _) in zip(outs, srcs):
+        assert o.data_ptr() != D.data_ptr()
+    want = oracle.elementwise(tg, op, x)
+    scale = float(np.abs(tg.T32).max()) + abs(x)
+    np.testing.assert_allclose(_dense_after(il, sch, srcs, outs), want, rtol=2e-6, atol=2e-6 * scale)
+    # in place: the same plan now describes the result
+    il.ilargi_elementwise(plan, op, x, outs=[D for D, _, _ in srcs])
+    np.testing.assert_allclose(il.ilargi_materialize(plan).cpu().numpy(), want, rtol=2e-6, atol=2e-6 * scale)
+    assert rel(il.ilargi_row_sum(plan).cpu().numpy(), want.sum(axis=1)) < OP_TOL
+
+
+def test_elementwise_conditions_on_shared_and_empty_cells(il):
+    # shared columns and unmatched rows: only times and divide act on the sources alone
+    sch, tg, plan = get(il, "tiny_mixed")
+    srcs = il.schema_to_device(sch)
+    plan = il.ilargi_plan_create(srcs, sch.r_T, sch.c_T, max_cx=1)
+    C = oracle.cover_counts(sch)
+    assert C.max() > 1 and C.min() == 0
+    for op, x in (("mul", 2.5), ("div", -4.0)):
+        got = _dense_after(il, sch, srcs, il.ilargi_elementwise(plan, op, x))
+        assert rel(got, oracle.elementwise(tg, op, x)) < 1e-6
+    for op in ("add", "exp", "square", "abs"):
+        with pytest.raises(il.IlargiError) as ei:
+            il.ilargi_elementwise(plan, op, 1.0)
+        assert ei.value.status == il.ERR_UNSUPPORTED
+    # disjoint columns but rows without a match: operators that keep zero at zero are fine, the others not
+    rng = datagen.rng_for(1201)
+    sch2 = datagen.star_schema(rng, 2_003, 4, [(50, 6, "uniform")])
+    sch2.sources[1].row_idx[::7] = -1
+    tg2 = oracle.Target(sch2)
+    srcs2 = il.schema_to_device(sch2)
+    plan2 = il.ilargi_plan_create(srcs2, sch2.r_T, sch2.c_T, max_cx=1)
+    assert oracle.cover_counts(sch2).max() == 1 and oracle.cover_counts(sch2).min() == 0
+    for op, x in (("square", 0.0), ("abs", 0.0), ("pow", 2.0), ("mul", 3.0)):
+        got = _dense_after(il, sch2, srcs2, il.ilargi_elementwise(plan2, op, x))
+        np.testing.assert_allclose(got, oracle.elementwise(tg2, op, x), rtol=2e-6, atol=1e-6)
+    for op, x in (("add", 1.0), ("exp", 0.0), ("log", 0.0), ("pow", -1.0), ("pow", 0.0)):
+        with pytest.raises(il.IlargiError) as ei:
+            il.ilargi_elementwise(plan2, op, x)
+        assert ei.value.status == il.ERR_UNSUPPORTED
+    with pytest.raises(il.IlargiError) as ei:
+        il.ilargi_elementwise(plan2, 10, 0.0)
+    assert ei.value.status == il.ERR_UNSUPPORTED
