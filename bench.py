@@ -172,7 +172,7 @@ def cpu_baseline(sch, sample_rows, budget_s=20.0):
     }
 
 
-def run_sweep(il, torch, datagen, dev, path):
+def run_sweep(il, torch, datagen, dev, path, records=None):
     """Factorized vs materialized over the tuple-ratio / feature-ratio grid of the micro-benchmark."""
     rows = []
     for r_R, c_R in datagen.CONFIG1_GRID:
@@ -194,6 +194,17 @@ def run_sweep(il, torch, datagen, dev, path):
                 tf, tm = time_loop(torch, fn_f, 20), time_loop(torch, fn_m, 20)
                 rec[f"{name}_c{c}"] = {"fact_us": round(tf * 1e6, 1), "mat_us": round(tm * 1e6, 1),
                                        "speedup": round(tm / tf, 3), "fact_GBps": round(b / tf / 1e9, 1)}
+        W = torch.zeros((sch.c_T, 1), device="cuda")
+        y = torch.randn(sch.r_T, device="cuda")
+        lr = torch.full((1,), 0.1, device="cuda")
+        loss = torch.zeros(1, device="cuda")
+        tf = time_loop(torch, lambda: il.ilargi_gd_step(plan, il.LINEAR, W, y, lr, loss), 20)
+        tm = time_loop(torch, lambda: il.ilargi_gd_step(mplan, il.LINEAR, W, y, lr, loss), 20)
+        rec["gd"] = {"fact_us": round(tf * 1e6, 1), "mat_us": round(tm * 1e6, 1), "speedup": round(tm / tf, 3)}
+        rec["chooser"] = chooser_record(il, f"config1 r_R={r_R} c_R={c_R}", shp, sch.r_T, sch.c_T, tf, tm,
+                                        rec["materialize_us"] * 1e-6)
+        if records is not None:
+            records.append(rec["chooser"])
         rows.append(rec)
         print(json.dumps(rec), file=sys.stderr, flush=True)
         del plan, mplan, Tm
@@ -280,7 +291,32 @@ def wide_batch(il, torch, datagen, dev):
     return out
 
 
-def other_configs(il, torch, datagen):
+CHOOSER_ITERATIONS = 200   # the paper's training length (Sec. 5.1)
+
+
+def chooser_record(il, name, shp, r_T, c_T, t_fact, t_mat, t_join):
+    """One validation point of ilargi_choose: measured winner of a 200-iteration training (join included for
+    the materialized strategy) against the byte-model decision, Eq. (1) > 1 and the tuple/feature-ratio rule."""
+    c = il.ilargi_choose([(r, k, has) for r, k, has in shp], r_T, c_T, iterations=CHOOSER_ITERATIONS)
+    total_f = CHOOSER_ITERATIONS * t_fact
+    total_m = t_join + CHOOSER_ITERATIONS * t_mat
+    return {"schema": name, "measured_factorize": int(total_f <= total_m), "measured_speedup": round(total_m / total_f, 3),
+            "byte_model": int(c["factorize"]), "predicted_speedup": round(c["seconds_materialized"] / c["seconds_factorized"], 3),
+            "eq1_ratio": round(c["complexity_ratio"], 3), "eq1_rule": int(c["complexity_ratio"] > 1.0),
+            "tuple_ratio": round(c["tuple_ratio"], 2), "feature_ratio": round(c["feature_ratio"], 2),
+            "tr_fr_rule": int(c["morpheus_rule"])}
+
+
+def chooser_summary(records):
+    n = len(records)
+    if n == 0:
+        return None
+    acc = {rule: round(sum(int(r[rule] == r["measured_factorize"]) for r in records) / n, 3)
+           for rule in ("byte_model", "eq1_rule", "tr_fr_rule")}
+    return {"iterations": CHOOSER_ITERATIONS, "points": n, "accuracy": acc, "records": records}
+
+
+def other_configs(il, torch, datagen, records=None):
     """Gradient-descent iterations/s, factorized vs materialized, on the remaining single-model
     configurations (full size): 0 (tiny star join, linear), 2 (three dimensions with a Zipf key, logistic),
     3 (union with overlap, linear)."""
@@ -308,6 +344,8 @@ def other_configs(il, torch, datagen):
                      "speedup": round(t_m / t_f, 3), "gd_factorized_GBps": round(b / t_f / 1e9, 1),
                      "materialize_once_us": round(t_mat_once * 1e6, 1), "plan_build_ms": round(plan_ms, 1),
                      "complexity_ratio_eq1": round(complexity_ratio_lr(shp, sch.r_T, sch.c_T), 3)}
+        if records is not None:
+            records.append(chooser_record(il, name, shp, sch.r_T, sch.c_T, t_f, t_m, t_mat_once))
         del plan, mplan, T, W, y
         torch.cuda.empty_cache()
     return out
@@ -468,15 +506,19 @@ def main() -> int:
     del mplan
 
     probe = stream_probe(il, torch)
+    records = []
     if args.sweep:
-        run_sweep(il, torch, datagen, dev, args.sweep)
+        run_sweep(il, torch, datagen, dev, args.sweep, records)
+    else:
+        records.append(chooser_record(il, "config1", shapes_of(sch), sch.r_T, sch.c_T, t_fact, t_mat,
+                                      breakdown["materialize"]["us"] * 1e-6))
     wide = None
     del plan, ops, keep, Tm
     torch.cuda.empty_cache()
     if not args.no_wide:
         wide = wide_batch(il, torch, datagen, dev)
         torch.cuda.empty_cache()
-    configs = None if args.no_configs else other_configs(il, torch, datagen)
+    configs = None if args.no_configs else other_configs(il, torch, datagen, records)
 
     cpu = None if args.no_cpu else cpu_baseline(sch, args.cpu_sample_rows)
 
@@ -509,6 +551,7 @@ def main() -> int:
         "kernels": dict(sorted(kernels.items(), key=lambda kv: -kv[1]["us_per_step"])[:16]),
         "stream_probe": probe,
         "scalar_ops": scalar,
+        "chooser": chooser_summary(records),
         "wide_batch": wide,
         "other_configs": configs,
         "roofline": roofline,

@@ -152,6 +152,32 @@ ilargi_status_t ilargi_row_sum(ilargi_plan_t* plan, float* out, void* stream);
  * (kept with the plan): no pass over the r_T target rows.  out device float[c_T]. */
 ilargi_status_t ilargi_col_sum(ilargi_plan_t* plan, float* out, void* stream);
 
+/* Factorize or materialize (Sec. 3)?  Host-only: reads the shapes in `sources` and whether row_idx is NULL
+ * (D, row_idx contents and col_map are not touched), like ilargi_plan_workspace_bytes. */
+typedef struct {
+  int64_t iterations;        /* gradient-descent iterations the table will serve (>= 1); the paper trains 200 */
+  int64_t models;            /* models trained at once (>= 1) */
+  double bytes_per_second;   /* sustained memory bandwidth to price bytes with; 0 = 5.0e12 (a plain copy on MI355X) */
+  double launch_seconds;     /* cost of one dependent kernel launch; 0 = 2.5e-6 */
+} ilargi_workload_t;
+
+typedef struct {
+  int factorize;             /* 1 = the factorized path is predicted to finish the workload sooner */
+  double complexity_ratio;   /* Eq. (1) for linear regression, dense operands: O_materialized / O_factorized */
+  double tuple_ratio;        /* r_T / (rows of the sources that have a row_idx) */
+  double feature_ratio;      /* (columns of those sources) / (columns of the identity sources) */
+  int morpheus_rule;         /* 1 = tuple_ratio >= 5 and feature_ratio >= 1 (the thresholds Sec. 5.3 quotes) */
+  double bytes_factorized;   /* bytes one iteration moves, factorized */
+  double bytes_materialized; /* the same on the materialized table */
+  double bytes_join;         /* bytes the join itself moves (once) */
+  double seconds_factorized; /* predicted time of the whole workload */
+  double seconds_materialized; /* join + iterations on the table */
+} ilargi_choice_t;
+
+/* workload may be NULL (200 iterations, one model, default rates).  Errors: NULL, SHAPE. */
+ilargi_status_t ilargi_choose(int n, const ilargi_source_t* sources, int64_t r_T, int64_t c_T,
+                              const ilargi_workload_t* workload, ilargi_choice_t* out);
+
 /* I_k^T Y for one source (the segmented sum inside ilargi_tmm), exposed for inspection:
  * Z[j, :] = sum of Y[i, :] over the target rows i with row_idx_k[i] == j.
  * Y device r_T x cx, Z device r_k x cx. */

@@ -338,3 +338,33 @@ def cover_counts(schema) -> np.ndarray:
         cols = np.asarray(s.col_map)[np.asarray(s.col_map) >= 0]
         C[np.ix_(rows, cols)] += 1
     return C
+
+
+# ----------------------------------------------------------------------------- cost analysis (Sec. 3)
+def complexity_lr(schema) -> Tuple[int, int]:
+    """Sec. 3.1, linear regression with dense operands: ``(O_materialized, O_factorized)``.
+    ``w`` is ``c_T x 1`` (``c_w = 1``, ``m_w = c_T``) and ``X = T w`` is ``r_T x 1`` (``m_X = r_T``):
+    ``O_mat = (c_w m_T + r_T m_w) + (m_T + c_T m_X)`` and
+    ``O_fact = sum_k (c_w m_k + r_k m_w) + sum_k (m_k + c_k m_X)``."""
+    r_T, c_T = schema.r_T, schema.c_T
+    m_T, m_w, m_X, c_w = r_T * c_T, c_T, r_T, 1
+    o_mat = (c_w * m_T + r_T * m_w) + (m_T + c_T * m_X)
+    o_fact = 0
+    for s in schema.sources:
+        r_k, c_k = s.D.shape
+        m_k = r_k * c_k
+        o_fact += (c_w * m_k + r_k * m_w) + (m_k + c_k * m_X)
+    return o_mat, o_fact
+
+
+def tuple_and_feature_ratio(schema) -> Tuple[float, float]:
+    """The redundancy measures Sec. 5.3 compares with (thresholds 5 and 1): target rows per row of the joined
+    tables and joined columns per column of the base table.  Read for several tables: sums over the sources
+    that are joined through a row index, against the sources that are not."""
+    joined = [s for s in schema.sources if s.row_idx is not None]
+    base = [s for s in schema.sources if s.row_idx is None]
+    rows = sum(s.D.shape[0] for s in joined)
+    tr = schema.r_T / rows if rows else 0.0
+    bc = sum(s.D.shape[1] for s in base)
+    fr = sum(s.D.shape[1] for s in joined) / bc if bc else 0.0
+    return tr, fr

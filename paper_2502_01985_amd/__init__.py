@@ -38,7 +38,7 @@ STATUS_NAMES = ["OK", "ERR_NULL", "ERR_SHAPE", "ERR_COLMAP", "ERR_INDEX_RANGE", 
 EXPORTED = [
     "ilargi_plan_workspace_bytes", "ilargi_plan_create", "ilargi_plan_destroy", "ilargi_lmm", "ilargi_tmm",
     "ilargi_crossprod", "ilargi_materialize", "ilargi_gd_step", "ilargi_elementwise", "ilargi_row_sum",
-    "ilargi_col_sum", "ilargi_segment_sum",
+    "ilargi_col_sum", "ilargi_choose", "ilargi_segment_sum",
     "ilargi_plan_inverse_index", "ilargi_plan_trace_begin", "ilargi_plan_trace_label", "ilargi_plan_trace_end",
     "ilargi_plan_trace_name", "ilargi_stream_probe",
     "ilargi_last_error",
@@ -253,6 +253,38 @@ def ilargi_gd_step(plan: Plan, model: int, W, y, lr, loss=None, precision: int =
     _check(lib.ilargi_gd_step(plan.handle, model, W.data_ptr(), m, y.data_ptr(), lr.data_ptr(), lptr or None,
                               precision, _stream_ptr(stream)), "ilargi_gd_step")
     return W
+
+
+class WorkloadStruct(ctypes.Structure):
+    _fields_ = [("iterations", ctypes.c_int64), ("models", ctypes.c_int64), ("bytes_per_second", ctypes.c_double),
+                ("launch_seconds", ctypes.c_double)]
+
+
+class ChoiceStruct(ctypes.Structure):
+    _fields_ = [("factorize", ctypes.c_int), ("complexity_ratio", ctypes.c_double), ("tuple_ratio", ctypes.c_double),
+                ("feature_ratio", ctypes.c_double), ("morpheus_rule", ctypes.c_int), ("bytes_factorized", ctypes.c_double),
+                ("bytes_materialized", ctypes.c_double), ("bytes_join", ctypes.c_double),
+                ("seconds_factorized", ctypes.c_double), ("seconds_materialized", ctypes.c_double)]
+
+
+lib.ilargi_choose.argtypes = [_int, ctypes.POINTER(SourceStruct), _i64, _i64, ctypes.POINTER(WorkloadStruct),
+                              ctypes.POINTER(ChoiceStruct)]
+
+
+def ilargi_choose(shapes, r_T: int, c_T: int, iterations: int = 200, models: int = 1,
+                  bytes_per_second: float = 0.0, launch_seconds: float = 0.0) -> dict:
+    """``shapes``: one ``(rows, cols, has_row_idx)`` per source.  Host-only; returns the fields of
+    ``ilargi_choice_t`` as a dict."""
+    arr = (SourceStruct * len(shapes))()
+    for k, (rows, cols, has) in enumerate(shapes):
+        arr[k].D = None
+        arr[k].rows, arr[k].cols = int(rows), int(cols)
+        arr[k].row_idx = 1 if has else None      # only tested against NULL
+        arr[k].col_map = None
+    w = WorkloadStruct(int(iterations), int(models), float(bytes_per_second), float(launch_seconds))
+    c = ChoiceStruct()
+    _check(lib.ilargi_choose(len(shapes), arr, r_T, c_T, ctypes.byref(w), ctypes.byref(c)), "ilargi_choose")
+    return {name: getattr(c, name) for name, _ in ChoiceStruct._fields_}
 
 
 OPS = {"mul": 0, "div": 1, "add": 2, "sub": 3, "pow": 4, "exp": 5, "log": 6, "sqrt": 7, "abs": 8, "square": 9}

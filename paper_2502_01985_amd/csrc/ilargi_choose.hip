@@ -1,0 +1,109 @@
+// Factorize or materialize?  (Sec. 3: complexity ratio of Eq. (1), the tuple-ratio / feature-ratio rule the
+// paper compares with, and the "theoretical memory I/O normalised by memory bandwidth" feature of Sec. 3.3
+// turned into a prediction.)  Host code only: reads shapes, touches no device.
+//
+// The byte model prices one gradient-descent iteration of this library, operator by operator:
+//   factorized   tables: the largest identity source once (its product, residual and gradient share a pass),
+//                every other source twice (product, column reduce); per gathered source the row index and the
+//                inverse index (4 r_T each) and its product / segment-sum vectors; residual and labels;
+//   materialized the same formulas for the single identity source T;
+//   join         written table + one source row fetched per target row and gathered source (rows of a table
+//                larger than the caches are fetched again for every target row that uses them) + indices.
+// Two properties of the kernels enter: the shared pass over an identity source exists for tables of at most
+// 256 columns (wider ones are read twice), and a gathered row narrower than 32 bytes still costs a 32-byte
+// fetch (the 4-byte gathers of a one-model pass are priced at 32 bytes each).
+// Launches are priced separately: a dependent launch costs a few microseconds whatever it moves, which decides
+// small schemas.
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+
+#include "ilargi.h"
+
+namespace {
+constexpr double kFusedMaxCols = 256.0;   // widest table whose product, residual and gradient share one pass
+constexpr double kMinFetch = 32.0;        // bytes a gathered row costs at least
+}  // namespace
+
+extern "C" ilargi_status_t ilargi_choose(int n, const ilargi_source_t* sources, int64_t r_T, int64_t c_T,
+                                         const ilargi_workload_t* workload, ilargi_choice_t* out) {
+  if (sources == nullptr || out == nullptr) return ILARGI_ERR_NULL;
+  if (n < 1 || n > 16 || r_T < 0 || c_T < 1) return ILARGI_ERR_SHAPE;
+  for (int k = 0; k < n; ++k)
+    if (sources[k].rows < 0 || sources[k].cols < 0) return ILARGI_ERR_SHAPE;
+  ilargi_workload_t w = {200, 1, 0.0, 0.0};
+  if (workload != nullptr) w = *workload;
+  if (w.iterations < 1 || w.models < 1) return ILARGI_ERR_SHAPE;
+  const double bw = w.bytes_per_second > 0.0 ? w.bytes_per_second : 5.0e12;
+  const double launch = w.launch_seconds > 0.0 ? w.launch_seconds : 2.5e-6;
+
+  const double rT = (double)r_T, cT = (double)c_T, mT = rT * cT;
+  // Eq. (1) for linear regression with dense operands: w is c_T x 1 (m_w = c_T), X = T w is r_T x 1 (m_X = r_T)
+  double o_fact = 0.0;
+  for (int k = 0; k < n; ++k) {
+    const double rk = (double)sources[k].rows, ck = (double)sources[k].cols, mk = rk * ck;
+    o_fact += (mk + rk * cT) + (mk + ck * rT);
+  }
+  const double o_mat = (mT + rT * cT) + (mT + cT * rT);
+  out->complexity_ratio = o_fact > 0.0 ? o_mat / o_fact : 1.0;
+
+  // tuple ratio and feature ratio: target rows per row of the joined tables, joined columns per base column
+  double base_cols = 0.0, joined_rows = 0.0, joined_cols = 0.0;
+  int fused = -1;
+  double fused_cells = -1.0;
+  for (int k = 0; k < n; ++k) {
+    const double rk = (double)sources[k].rows, ck = (double)sources[k].cols;
+    if (sources[k].row_idx == nullptr) {
+      base_cols += ck;
+      if (rk * ck > fused_cells) { fused_cells = rk * ck; fused = k; }
+    } else {
+      joined_rows += rk;
+      joined_cols += ck;
+    }
+  }
+  out->tuple_ratio = joined_rows > 0.0 ? rT / joined_rows : 0.0;
+  out->feature_ratio = base_cols > 0.0 ? joined_cols / base_cols : 0.0;
+  out->morpheus_rule = (joined_rows > 0.0 && out->tuple_ratio >= 5.0 && out->feature_ratio >= 1.0) ? 1 : 0;
+
+  // bytes and launches of one iteration, for one pass of up to four models
+  const double pass_models = (double)std::min<int64_t>(w.models, 4);
+  const double passes = std::ceil((double)w.models / 4.0);
+  const double vec = 4.0 * pass_models;                    // bytes of one row of an operand slice
+  double b_fact = 0.0, join_fetch = 0.0;
+  int launches_fact = 2;                                   // assembly pass, update
+  for (int k = 0; k < n; ++k) {
+    const double rk = (double)sources[k].rows, ck = (double)sources[k].cols, cells = 4.0 * rk * ck;
+    if (rk == 0.0 || ck == 0.0) continue;
+    if (k == fused) {
+      const bool one_pass = ck <= kFusedMaxCols;
+      b_fact += one_pass ? cells : 2.0 * cells;
+      launches_fact += one_pass ? 0 : 1;
+      join_fetch += cells;
+      continue;
+    }
+    b_fact += 2.0 * cells;                                 // product, column reduce
+    launches_fact += 2;
+    if (sources[k].row_idx != nullptr) {
+      b_fact += 8.0 * rT + 4.0 * vec * rk;                 // row index, inverse index; P_k written and gathered, Z_k written and read
+      b_fact += 2.0 * std::max(vec, kMinFetch) * rT;       // gathered product rows, residual rows read by the segment sum
+      launches_fact += 1;
+      join_fetch += 4.0 * rT * ck + 4.0 * rT;              // one source row per target row, row index
+    } else {
+      b_fact += 2.0 * vec * rk + vec * rT;
+      join_fetch += cells;
+    }
+  }
+  b_fact += (vec + 4.0) * rT + 2.0 * vec * cT;             // residual written, labels, weights in and out
+  const bool mat_one_pass = cT <= kFusedMaxCols;
+  const double b_mat = (mat_one_pass ? 4.0 : 8.0) * mT + (vec + 4.0) * rT + 2.0 * vec * cT;
+  const double launches_mat = mat_one_pass ? 2.0 : 3.0;
+  const double b_join = 4.0 * mT + join_fetch;
+  out->bytes_factorized = b_fact * passes;
+  out->bytes_materialized = b_mat * passes;
+  out->bytes_join = b_join;
+  const double it = (double)w.iterations;
+  out->seconds_factorized = it * passes * (b_fact / bw + launches_fact * launch);
+  out->seconds_materialized = b_join / bw + launch + it * passes * (b_mat / bw + launches_mat * launch);
+  out->factorize = out->seconds_factorized <= out->seconds_materialized ? 1 : 0;
+  return ILARGI_OK;
+}

@@ -114,3 +114,58 @@ def test_calls_reject_null_plan():
     assert il.lib.ilargi_materialize(None, 4096, None) == il.ERR_NULL
     assert il.lib.ilargi_gd_step(None, 0, 4096, 1, 4096, 4096, None, 0, None) == il.ERR_NULL
     assert il.lib.ilargi_plan_destroy(None) == il.ERR_NULL
+
+
+# ----------------------------------------------------------------------------- ilargi_choose (host only)
+def _shapes(sch):
+    return [(s.D.shape[0], s.D.shape[1], s.row_idx is not None) for s in sch.sources]
+
+
+def test_choose_reports_the_paper_formulas():
+    import datagen
+    import oracle
+    for sch in (datagen.config0(), datagen.star_schema(datagen.rng_for(3), 5_000, 7, [(40, 30, "uniform"), (900, 3, "uniform")])):
+        c = il.ilargi_choose(_shapes(sch), sch.r_T, sch.c_T)
+        o_mat, o_fact = oracle.complexity_lr(sch)
+        assert c["complexity_ratio"] == pytest.approx(o_mat / o_fact, rel=1e-12)
+        tr, fr = oracle.tuple_and_feature_ratio(sch)
+        assert c["tuple_ratio"] == pytest.approx(tr, rel=1e-12) and c["feature_ratio"] == pytest.approx(fr, rel=1e-12)
+        assert c["morpheus_rule"] == int(tr >= 5.0 and fr >= 1.0)
+
+
+def test_choose_decision_follows_its_byte_model():
+    # wide dimension table, many target rows per dimension row: factorize; feature ratio 1/4: materialize
+    star = [(1_000_000, 20, False), (10_000, 800, True)]
+    cs = il.ilargi_choose(star, 1_000_000, 820)
+    assert cs["factorize"] == 1 and cs["bytes_factorized"] < cs["bytes_materialized"] / 5
+    thin = [(1_000_000, 40, False), (500_000, 10, True)]
+    c = il.ilargi_choose(thin, 1_000_000, 50)
+    assert c["factorize"] == 0 and c["seconds_materialized"] < c["seconds_factorized"]
+    # the join is paid once: a single iteration never repays it when the per-iteration times are close
+    few = il.ilargi_choose(thin, 1_000_000, 50, iterations=1)
+    assert few["factorize"] == 1 and few["bytes_join"] > few["bytes_materialized"] * 0.9
+    # tiny tables are decided by launches: five dependent launches against two
+    tiny = il.ilargi_choose([(10_000, 4, False), (1_000, 8, True)], 10_000, 12)
+    assert tiny["factorize"] == 0
+    # a small schema with a wide dimension table moves fewer bytes factorized but needs more launches: the
+    # launch price decides
+    small = [(10_000, 4, False), (100, 64, True)]
+    assert il.ilargi_choose(small, 10_000, 68)["factorize"] == 0
+    free = il.ilargi_choose(small, 10_000, 68, launch_seconds=1e-9)
+    assert free["factorize"] == 1 and free["bytes_factorized"] < free["bytes_materialized"]
+    # tables wider than 256 columns are read twice per iteration (no shared pass)
+    wide = il.ilargi_choose([(1_000, 300, False)], 1_000, 300)
+    narrow = il.ilargi_choose([(1_000, 200, False)], 1_000, 200)
+    assert wide["bytes_materialized"] / narrow["bytes_materialized"] > 2.9
+    # more models in a pass move more operand bytes but the same tables
+    m4 = il.ilargi_choose(star, 1_000_000, 820, models=4)
+    assert m4["bytes_factorized"] > cs["bytes_factorized"] and m4["factorize"] == 1
+
+
+def test_choose_rejects_bad_arguments():
+    with pytest.raises(il.IlargiError) as ei:
+        il.ilargi_choose([(10, 2, False)], 10, 2, iterations=0)
+    assert ei.value.status == il.ERR_SHAPE
+    with pytest.raises(il.IlargiError) as ei:
+        il.ilargi_choose([(10, 2, False)], 10, 0)
+    assert ei.value.status == il.ERR_SHAPE

@@ -425,3 +425,32 @@ def test_cover_counts_from_the_dense_definition():
         M = oracle.dense_mapping(s.col_map, sch.c_T)
         want += I @ np.ones(s.D.shape) @ M.T
     assert np.array_equal(oracle.cover_counts(sch), want.astype(np.int64))
+
+
+# ----------------------------------------------------------------------------- cost analysis (Sec. 3)
+def test_complexity_of_linear_regression_by_hand_and_by_parts():
+    # S 6 x 2 and R 3 x 4 joined into T 6 x 6, written out term by term from Sec. 3.1:
+    #   O_mat  = (1*36 + 6*6) + (36 + 6*6)                                  = 144
+    #   O_fact = (1*12 + 6*6) + (1*12 + 3*6) + (12 + 2*6) + (12 + 4*6)      = 138
+    rng = datagen.rng_for(51)
+    sch = datagen.star_schema(rng, 6, 2, [(3, 4, "uniform")])
+    assert oracle.complexity_lr(sch) == (144, 138)
+    # the T w half is Tab. 2's row for T X with a one-column operand
+    mat_lmm, fact_lmm = oracle.complexity_lmm(sch, 1)
+    o_mat, o_fact = oracle.complexity_lr(sch)
+    assert o_mat - mat_lmm == 6 * 6 + 6 * 6
+    assert o_fact - fact_lmm == (12 + 2 * 6) + (12 + 4 * 6)
+    # a table that is its own only source has nothing to gain: ratio exactly one
+    one = datagen.Schema([datagen.Source(sch.sources[0].D, None, np.arange(2, dtype=np.int32))], 6, 2)
+    assert oracle.complexity_lr(one)[0] == oracle.complexity_lr(one)[1]
+    assert oracle.tuple_and_feature_ratio(sch) == (2.0, 2.0)
+
+
+def test_complexity_ratio_grows_with_redundancy():
+    # more target rows per dimension row, or wider dimension tables, favour the factorized form (Sec. 3.1)
+    def ratio(r_R, c_R):
+        sch = datagen.star_schema(datagen.rng_for(52), 1_000, 4, [(r_R, c_R, "uniform")])
+        o_mat, o_fact = oracle.complexity_lr(sch)
+        return o_mat / o_fact
+    assert ratio(10, 8) > ratio(100, 8) > ratio(500, 8)
+    assert ratio(100, 40) > ratio(100, 8) > ratio(100, 2)
