@@ -261,6 +261,36 @@ def scalar_ops(il, torch, plan, mplan, sch):
     return out
 
 
+def sparse_tables(il, torch, datagen, dev):
+    """Source tables kept in compressed sparse rows (Sec. 3.1; sparsity sweep of Tab. 4) on the config-1 centre
+    schema with a fraction p of the cells set to zero: one gradient-descent iteration and the one-column
+    multiplies, tables sparse vs the same tables dense (zeros stored)."""
+    out = {}
+    base = datagen.config1()
+    for p in (0.5, 0.9, 0.99):
+        sch = datagen.sparsify(base, p, seed=11)
+        rec = {}
+        for kind in ("dense", "sparse"):
+            srcs = il.schema_to_device(sch, sparse=(kind == "sparse"))
+            plan = il.ilargi_plan_create(srcs, sch.r_T, sch.c_T, max_cx=1)
+            W = torch.zeros((sch.c_T, 1), device="cuda")
+            y = torch.randn(sch.r_T, device="cuda")
+            lr = torch.full((1,), 0.1, device="cuda")
+            loss = torch.zeros(1, device="cuda")
+            X = torch.randn(sch.c_T, 1, device="cuda"); Y = torch.randn(sch.r_T, 1, device="cuda")
+            o1 = torch.empty(sch.r_T, 1, device="cuda"); o2 = torch.empty(sch.c_T, 1, device="cuda")
+            rec[kind] = {"gd_us": round(time_loop(torch, lambda: il.ilargi_gd_step(plan, il.LINEAR, W, y, lr, loss), 20) * 1e6, 1),
+                         "lmm_c1_us": round(time_loop(torch, lambda: il.ilargi_lmm(plan, X, o1), 20) * 1e6, 1),
+                         "tmm_c1_us": round(time_loop(torch, lambda: il.ilargi_tmm(plan, Y, o2), 20) * 1e6, 1)}
+            if kind == "sparse":
+                rec["stored_entries"] = int(sum(D.nnz for D, _, _ in srcs))
+            del plan, srcs
+            torch.cuda.empty_cache()
+        rec["gd_speedup_sparse_over_dense"] = round(rec["dense"]["gd_us"] / rec["sparse"]["gd_us"], 2)
+        out[f"p={p}"] = rec
+    return out
+
+
 def wide_batch(il, torch, datagen, dev):
     """The batched hyper-parameter workload (256 linear regressions at once on the same schema, seed 4):
     gradient-descent iterations/s and matrix-core utilisation, float32 and bfloat16 inputs, factorized vs
@@ -515,8 +545,11 @@ def main() -> int:
     wide = None
     del plan, ops, keep, Tm
     torch.cuda.empty_cache()
+    sparse = None
     if not args.no_wide:
         wide = wide_batch(il, torch, datagen, dev)
+        torch.cuda.empty_cache()
+        sparse = sparse_tables(il, torch, datagen, dev)
         torch.cuda.empty_cache()
     configs = None if args.no_configs else other_configs(il, torch, datagen, records)
 
@@ -551,6 +584,7 @@ def main() -> int:
         "kernels": dict(sorted(kernels.items(), key=lambda kv: -kv[1]["us_per_step"])[:16]),
         "stream_probe": probe,
         "scalar_ops": scalar,
+        "sparse_tables": sparse,
         "chooser": chooser_summary(records),
         "wide_batch": wide,
         "other_configs": configs,

@@ -226,6 +226,21 @@ def tiny_random_schema(seed: int, r_T: int = 9, c_T: int = 7, n: int = 3,
     return Schema(sources, r_T, c_T, name=f"tiny{seed}")
 
 
+def sparsify(schema: Schema, p: float, seed: int) -> Schema:
+    """A copy of ``schema`` whose table cells are set to zero independently with probability ``p`` (the sparsity
+    parameter of the paper's synthetic data, Tab. 4); index arrays and column maps are shared with the original.
+    Draw order: one uniform matrix per source, in source order."""
+    rng = rng_for(seed)
+    sources = []
+    for s in schema.sources:
+        D = s.D.copy()
+        D[rng.random(D.shape) < p] = 0.0
+        sources.append(Source(D, s.row_idx, s.col_map))
+    out = Schema(sources, schema.r_T, schema.c_T, name=f"{schema.name}_p{p}")
+    out.extras.update(schema.extras)
+    return out
+
+
 def finish_labels(kind: str, Tw: np.ndarray, noise: np.ndarray) -> np.ndarray:
     """Labels from a product ``T @ w*`` that the caller computed: ``linear`` adds the noise,
     ``logistic`` thresholds at zero (``sign(0) = +1``) and returns the {0,1} encoding."""

@@ -66,6 +66,15 @@ typedef struct {
   int64_t rows, cols;     /* r_k, c_k (both may be 0) */
   const int32_t* row_idx; /* device int32[r_T], borrowed; NULL = identity (requires rows == r_T) */
   const int32_t* col_map; /* HOST int32[cols]; copied when the plan is created */
+  /* Optional: the table in compressed sparse rows instead of D (the paper keeps its matrices sparse,
+   * Sec. 3.1).  With csr_rowptr != NULL, D must be NULL.  Borrowed like D.  A plan with a sparse source
+   * serves lmm, tmm, gd_step, materialize, row_sum, col_sum and the element-wise operators that keep zero
+   * at zero (which then act on csr_val, nnz values), in float32; crossprod and the bf16 variants return
+   * UNSUPPORTED.  Invalid sparse rows are reported by ilargi_plan_create as INDEX_RANGE. */
+  const int32_t* csr_rowptr; /* device int32[rows + 1], rising from 0 to nnz */
+  const int32_t* csr_col;    /* device int32[nnz], in [0, cols), strictly ascending within a row */
+  const float* csr_val;      /* device float32[nnz] */
+  int64_t nnz;               /* stored entries, < 2^31 */
 } ilargi_source_t;
 
 /* Bytes of device workspace a plan over these shapes needs when operands have at most max_cx

@@ -48,7 +48,9 @@ EXPORTED = [
 
 class SourceStruct(ctypes.Structure):
     _fields_ = [("D", ctypes.c_void_p), ("rows", ctypes.c_int64), ("cols", ctypes.c_int64),
-                ("row_idx", ctypes.c_void_p), ("col_map", ctypes.c_void_p)]
+                ("row_idx", ctypes.c_void_p), ("col_map", ctypes.c_void_p),
+                ("csr_rowptr", ctypes.c_void_p), ("csr_col", ctypes.c_void_p), ("csr_val", ctypes.c_void_p),
+                ("nnz", ctypes.c_int64)]
 
 
 _vp, _i64, _int = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
@@ -116,12 +118,42 @@ def _dev_f32(t, name: str):
     return t
 
 
-def make_source_array(sources: Sequence[Tuple[int, int, int, int, np.ndarray]]):
-    """ctypes array from ``(D_ptr, rows, cols, row_idx_ptr_or_0, col_map int32 ndarray)`` tuples.
+class CSR:
+    """A source table in compressed sparse rows: int32 CUDA tensors ``rowptr`` (rows + 1) and ``col`` (nnz), a
+    float32 CUDA tensor ``val`` (nnz), and the dense shape."""
+
+    def __init__(self, rowptr, col, val, shape):
+        self.rowptr, self.col, self.val = rowptr, col, val
+        self.shape = (int(shape[0]), int(shape[1]))
+
+    @property
+    def nnz(self) -> int:
+        return int(self.val.numel())
+
+    @property
+    def device(self):
+        return self.rowptr.device
+
+    @classmethod
+    def from_dense(cls, D: np.ndarray, device="cuda:0"):
+        """Keeps the non-zero cells of a host array (row-major order, so columns ascend within a row)."""
+        torch = _torch()
+        D = np.asarray(D, dtype=np.float32)
+        r, c = np.nonzero(D)
+        rowptr = np.zeros(D.shape[0] + 1, dtype=np.int32)
+        np.cumsum(np.bincount(r, minlength=D.shape[0]), out=rowptr[1:])
+        t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(device)
+        return cls(t(rowptr), t(c.astype(np.int32)), t(D[r, c]), D.shape)
+
+
+def make_source_array(sources: Sequence[tuple]):
+    """ctypes array from ``(D_ptr, rows, cols, row_idx_ptr_or_0, col_map int32 ndarray)`` tuples, optionally
+    extended by ``(csr_rowptr_ptr, csr_col_ptr, csr_val_ptr, nnz)``.
     Returns the array and the objects that must stay alive while it is used."""
     arr = (SourceStruct * len(sources))()
     keep = []
-    for k, (dptr, rows, cols, iptr, cmap) in enumerate(sources):
+    for k, src in enumerate(sources):
+        dptr, rows, cols, iptr, cmap = src[:5]
         cm = np.ascontiguousarray(cmap, dtype=np.int32)
         keep.append(cm)
         arr[k].D = dptr or None
@@ -129,6 +161,9 @@ def make_source_array(sources: Sequence[Tuple[int, int, int, int, np.ndarray]]):
         arr[k].cols = cols
         arr[k].row_idx = iptr or None
         arr[k].col_map = cm.ctypes.data if cm.size else None
+        if len(src) > 5:
+            arr[k].csr_rowptr, arr[k].csr_col, arr[k].csr_val = src[5] or None, src[6] or None, src[7] or None
+            arr[k].nnz = src[8]
     return arr, keep
 
 
@@ -169,17 +204,28 @@ def ilargi_plan_create(sources, r_T: int, c_T: int, max_cx: int = 1, stream=None
     torch = _torch()
     tuples, borrowed, shapes = [], [], []
     for D, row_idx, col_map in sources:
-        _dev_f32(D, "D")
-        if D.dim() != 2:
-            raise TypeError("D must be 2-D")
         if row_idx is not None:
             if not (row_idx.is_cuda and row_idx.dtype == torch.int32 and row_idx.is_contiguous()
                     and row_idx.numel() == r_T):
                 raise TypeError("row_idx must be a contiguous int32 CUDA tensor of length r_T")
+        iptr = row_idx.data_ptr() if row_idx is not None else 0
+        if isinstance(D, CSR):
+            for t_, dt in ((D.rowptr, torch.int32), (D.col, torch.int32), (D.val, torch.float32)):
+                if not (t_.is_cuda and t_.dtype == dt and t_.is_contiguous()):
+                    raise TypeError("CSR parts must be contiguous CUDA tensors: int32 rowptr, int32 col, float32 val")
+            if D.rowptr.numel() != D.shape[0] + 1 or D.col.numel() != D.val.numel():
+                raise TypeError("CSR parts have inconsistent lengths")
+            borrowed.append((D, row_idx))
+            shapes.append(D.shape)
+            tuples.append((0, D.shape[0], D.shape[1], iptr, np.asarray(col_map, dtype=np.int32),
+                           D.rowptr.data_ptr(), D.col.data_ptr() if D.nnz else 0, D.val.data_ptr() if D.nnz else 0, D.nnz))
+            continue
+        _dev_f32(D, "D")
+        if D.dim() != 2:
+            raise TypeError("D must be 2-D")
         borrowed.append((D, row_idx))
         shapes.append((int(D.shape[0]), int(D.shape[1])))
-        tuples.append((D.data_ptr(), int(D.shape[0]), int(D.shape[1]),
-                       row_idx.data_ptr() if row_idx is not None else 0, np.asarray(col_map, dtype=np.int32)))
+        tuples.append((D.data_ptr(), int(D.shape[0]), int(D.shape[1]), iptr, np.asarray(col_map, dtype=np.int32)))
     arr, keep = make_source_array(tuples)
     nbytes = ctypes.c_size_t(0)
     _check(lib.ilargi_plan_workspace_bytes(len(tuples), arr, r_T, c_T, max_cx, ctypes.byref(nbytes)),
@@ -273,14 +319,18 @@ lib.ilargi_choose.argtypes = [_int, ctypes.POINTER(SourceStruct), _i64, _i64, ct
 
 def ilargi_choose(shapes, r_T: int, c_T: int, iterations: int = 200, models: int = 1,
                   bytes_per_second: float = 0.0, launch_seconds: float = 0.0) -> dict:
-    """``shapes``: one ``(rows, cols, has_row_idx)`` per source.  Host-only; returns the fields of
-    ``ilargi_choice_t`` as a dict."""
+    """``shapes``: one ``(rows, cols, has_row_idx)`` or ``(rows, cols, has_row_idx, nnz)`` (a sparse table)
+    per source.  Host-only; returns the fields of ``ilargi_choice_t`` as a dict."""
     arr = (SourceStruct * len(shapes))()
-    for k, (rows, cols, has) in enumerate(shapes):
+    for k, shp in enumerate(shapes):
+        rows, cols, has = shp[:3]
         arr[k].D = None
         arr[k].rows, arr[k].cols = int(rows), int(cols)
         arr[k].row_idx = 1 if has else None      # only tested against NULL
         arr[k].col_map = None
+        if len(shp) > 3:
+            arr[k].csr_rowptr = 1                # only tested against NULL
+            arr[k].nnz = int(shp[3])
     w = WorkloadStruct(int(iterations), int(models), float(bytes_per_second), float(launch_seconds))
     c = ChoiceStruct()
     _check(lib.ilargi_choose(len(shapes), arr, r_T, c_T, ctypes.byref(w), ctypes.byref(c)), "ilargi_choose")
@@ -296,14 +346,15 @@ def ilargi_elementwise(plan: Plan, op, x: float = 0.0, outs=None, stream=None):
     torch = _torch()
     code = OPS[op] if isinstance(op, str) else int(op)
     if outs is None:
-        outs = [torch.empty_like(D) for D, _ in plan._borrowed]
+        outs = [torch.empty_like(D.val if isinstance(D, CSR) else D) for D, _ in plan._borrowed]
     if len(outs) != len(plan._borrowed):
         raise TypeError("one output tensor per source")
     ptrs = (ctypes.c_void_p * len(outs))()
     for k, (o, (D, _)) in enumerate(zip(outs, plan._borrowed)):
         _dev_f32(o, "outs[k]")
-        if tuple(o.shape) != tuple(D.shape):
-            raise TypeError("outs[k] must have the shape of source k")
+        like = D.val if isinstance(D, CSR) else D
+        if tuple(o.shape) != tuple(like.shape):
+            raise TypeError("outs[k] must have the shape of source k (of its values for a sparse source)")
         ptrs[k] = o.data_ptr() if o.numel() > 0 else None
     _check(lib.ilargi_elementwise(plan.handle, code, float(x), ptrs, _stream_ptr(stream)), "ilargi_elementwise")
     return outs
@@ -390,12 +441,14 @@ def ilargi_stream_probe(kind: int, dst, src, n_floats: int, blocks: int = 4096, 
                                    blocks, _stream_ptr(stream)), "ilargi_stream_probe")
 
 
-def schema_to_device(schema, device="cuda:0"):
-    """Uploads a ``datagen.Schema`` and returns the ``(D, row_idx, col_map)`` list for ilargi_plan_create."""
+def schema_to_device(schema, device="cuda:0", sparse=False):
+    """Uploads a ``datagen.Schema`` and returns the ``(D, row_idx, col_map)`` list for ilargi_plan_create.
+    ``sparse``: ``True`` (every table) or a collection of source numbers to upload in compressed sparse rows."""
     torch = _torch()
     out = []
-    for s in schema.sources:
-        D = torch.from_numpy(np.ascontiguousarray(s.D)).to(device)
+    for k, s in enumerate(schema.sources):
+        as_csr = sparse is True or (sparse not in (False, None) and k in sparse)
+        D = CSR.from_dense(s.D, device) if as_csr else torch.from_numpy(np.ascontiguousarray(s.D)).to(device)
         idx = None if s.row_idx is None else torch.from_numpy(np.ascontiguousarray(s.row_idx)).to(device)
         out.append((D, idx, s.col_map))
     return out

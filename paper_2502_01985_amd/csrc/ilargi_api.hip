@@ -41,6 +41,14 @@ struct SourcePlan {
   bool has_idx = false;           // row_idx was given
   bool ident = false;             // identity on the first `rows` target rows, nothing beyond
   bool empty = false;             // contributes nothing (no rows or no columns)
+  bool sparse = false;            // given in compressed sparse rows (D is NULL)
+  const int32_t* csr_rowptr = nullptr;
+  const int32_t* csr_col = nullptr;
+  const float* csr_val = nullptr;
+  int64_t entries = 0;            // stored entries of a sparse source
+  size_t o_csc_row = 0, o_csc_val = 0, o_colptr = 0, o_tchunk_beg = 0, o_tchunk_end = 0, o_col_first = 0, o_tpartial = 0;
+  int64_t tchunk_max = 0;
+  int n_tchunks = 0;
   int vec = 1;
   std::vector<int32_t> colmap_h;
   // offsets into the workspace
@@ -53,7 +61,8 @@ struct SourcePlan {
 };
 
 struct Layout {
-  size_t o_gslot = 0, o_gj0 = 0, o_ct_slot = 0, o_ct_j = 0, o_ones = 0;
+  size_t o_gslot = 0, o_gj0 = 0, o_ct_slot = 0, o_ct_j = 0, o_ones = 0, o_tmp_a = 0, o_tmp_b = 0;
+  int64_t max_entries = 0;       // most stored entries of a sparse source (0: every source is dense)
   size_t o_flags = 0, o_tcol_table = 0, o_pairs = 0, o_E = 0, o_loss = 0, o_sort = 0, o_hist = 0, o_zc = 0,
          o_gpartial = 0, o_blocks = 0;
   int64_t zc_floats = 0, gpartial_floats = 0, blocks_floats = 0;
@@ -70,6 +79,7 @@ struct ilargi_plan {
   std::vector<SourcePlan> src;
   Layout lay;
   int fused = -1;   // identity source whose product is fused into the assembly pass
+  bool any_sparse = false;  // some source is given in compressed sparse rows: narrow kernels only
   int star_k = -1;  // two-table star join: the dimension table every target row joins (else -1)
   bool cover_disjoint = false;  // no target column is fed by two sources
   bool cover_full = false;      // every target column is fed and every source reaches every target row
@@ -142,11 +152,18 @@ ilargi_status_t make_layout(int n, const ilargi_source_t* s, int64_t r_T, int64_
     src[k].cols = s[k].cols;
     src[k].has_idx = s[k].row_idx != nullptr;
     src[k].empty = s[k].rows == 0 || s[k].cols == 0;
+    src[k].sparse = s[k].csr_rowptr != nullptr && !src[k].empty;
+    if (src[k].sparse) {
+      if (s[k].nnz < 0 || s[k].nnz > 2147483646ll || s[k].nnz > s[k].rows * s[k].cols)
+        return fail(ILARGI_ERR_SHAPE, "source %d: nnz = %lld", k, (long long)s[k].nnz);
+      src[k].entries = s[k].nnz;
+      lay.max_entries = std::max(lay.max_entries, std::max<int64_t>(s[k].nnz, 1));
+    }
     cmax = std::max<int64_t>(cmax, s[k].cols);
   }
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
-  lay.o_flags = take(sizeof(int32_t) * 2 * n);
+  lay.o_flags = take(sizeof(int32_t) * 3 * n);
   lay.o_tcol_table = take(sizeof(void*) * n);
   lay.o_pairs = take(sizeof(GramAsmPair) * n * (n + 1) / 2);
   lay.o_gslot = take(sizeof(int32_t) * c_T);
@@ -175,11 +192,27 @@ ilargi_status_t make_layout(int n, const ilargi_source_t* s, int64_t r_T, int64_
     p.o_partial = take(sizeof(float) * kColredBlocks * std::max<int64_t>(p.cols, 1) * kNarrowCT);
     p.o_g = take(sizeof(float) * std::max<int64_t>(p.cols, 1) * max_cx);
     p.o_cnt = take(sizeof(float) * std::max<int64_t>(p.rows, 1));
+    if (p.sparse) {
+      const int64_t e = std::max<int64_t>(p.entries, 1);
+      p.o_csc_row = take(sizeof(int32_t) * e);
+      p.o_csc_val = take(sizeof(float) * e);
+      p.o_colptr = take(sizeof(int32_t) * (p.cols + 1));
+      p.tchunk_max = p.entries / kSparseChunk + p.cols + 1;
+      p.o_tchunk_beg = take(sizeof(int32_t) * p.tchunk_max);
+      p.o_tchunk_end = take(sizeof(int32_t) * p.tchunk_max);
+      p.o_col_first = take(sizeof(int32_t) * (p.cols + 1));
+      p.o_tpartial = take(sizeof(float) * p.tchunk_max * kNarrowCT);
+    }
+  }
+  if (lay.max_entries > 0) {
+    lay.o_tmp_a = take(sizeof(int32_t) * lay.max_entries);
+    lay.o_tmp_b = take(sizeof(int32_t) * lay.max_entries);
   }
   lay.o_E = take(sizeof(float) * std::max<int64_t>(r_T, 1) * max_cx);
   lay.o_loss = take(sizeof(float) * std::max<int64_t>(32768 * kNarrowCT, 1024 * max_cx));
-  lay.o_sort = take(sizeof(int32_t) * 4 * std::max<int64_t>(r_T, 1));
-  lay.o_hist = take(sizeof(int32_t) * sort_hist_ints(r_T));
+  const int64_t sort_n = std::max<int64_t>(std::max<int64_t>(r_T, 1), lay.max_entries);
+  lay.o_sort = take(sizeof(int32_t) * 4 * sort_n);
+  lay.o_hist = take(sizeof(int32_t) * sort_hist_ints(sort_n));
   // Gram scratch: summed rows for the "via sums" route, chunk partials, the (k,l) blocks
   lay.zc_floats = 1;
   lay.gpartial_floats = kGramPartialFloats;
@@ -254,6 +287,22 @@ SegArgs seg_args(const ilargi_plan* pl, int k) {
   return a;
 }
 
+SparseArgs sparse_args(const ilargi_plan* pl, int k) {
+  const SourcePlan& p = pl->src[k];
+  SparseArgs a;
+  memset(&a, 0, sizeof(a));
+  a.rowptr = p.csr_rowptr; a.col = p.csr_col; a.val = p.csr_val;
+  a.rows = p.rows; a.nnz = p.entries; a.cols = (int)p.cols;
+  a.colmap = pl->at<int32_t>(p.o_colmap);
+  a.csc_row = pl->at<int32_t>(p.o_csc_row);
+  a.csc_val = pl->at<float>(p.o_csc_val);
+  a.chunk_beg = pl->at<int32_t>(p.o_tchunk_beg);
+  a.chunk_end = pl->at<int32_t>(p.o_tchunk_end);
+  a.col_first_chunk = pl->at<int32_t>(p.o_col_first);
+  a.n_chunks = p.n_tchunks;
+  return a;
+}
+
 // Widest operand slice one narrow pass can stage in LDS for every source of the plan.
 int pass_width(const ilargi_plan* pl) {
   int64_t cmax = 1;
@@ -281,7 +330,8 @@ ilargi_status_t lmm_pass(ilargi_plan* pl, const float* X, int ldx, int col0, int
     a.logL = pick_logL(p.cols, p.vec);
     {
       TraceScope ts(pl, "lmm_rows", k, st);
-      if (wide) HIP_TRY(launch_lmm_mfma(a, p.vec, 0, bf16, st, nullptr));
+      if (p.sparse) HIP_TRY(launch_spmm_rows(sparse_args(pl, k), X, ldx, col0, ncols, pl->at<float>(p.o_pz), ldx, st));
+      else if (wide) HIP_TRY(launch_lmm_mfma(a, p.vec, 0, bf16, st, nullptr));
       else HIP_TRY(launch_lmm_rows(a, p.vec, 0, st, nullptr));
     }
     g.idx[g.n] = p.ident ? nullptr : p.idx;
@@ -372,7 +422,12 @@ ilargi_status_t tmm_pass(ilargi_plan* pl, const float* Y, int ldy, int col0, int
     c.partial = pl->at<float>(p.o_partial);
     c.rows_per_block = colred_rows_per_block(p.rows);
     int nb = colred_nblocks(p.rows);
-    {
+    if (p.sparse) {
+      // D_k^T Z_k over the column-sorted view; the result takes the place of a single block of partials
+      TraceScope ts(pl, "colred", k, st);
+      HIP_TRY(launch_spmm_t(sparse_args(pl, k), c.Z, c.ldz, c.col0, ncols, pl->at<float>(p.o_tpartial), c.partial, st));
+      nb = 1;
+    } else {
       TraceScope ts(pl, "colred", k, st);
       HIP_TRY(launch_colred(c, nb, st));
     }
@@ -584,8 +639,16 @@ ilargi_status_t ilargi_plan_create(int n, const ilargi_source_t* sources, int64_
   std::vector<std::vector<int32_t>> tcol(n, std::vector<int32_t>((size_t)c_T, -1));
   for (int k = 0; k < n; ++k) {
     if (sources[k].cols > 0 && sources[k].col_map == nullptr) return fail(ILARGI_ERR_NULL, "source %d: col_map is NULL", k);
-    if (sources[k].rows > 0 && sources[k].cols > 0 && sources[k].D == nullptr)
+    if (src[k].sparse) {
+      if (sources[k].D != nullptr) return fail(ILARGI_ERR_SHAPE, "source %d: both a dense table and sparse rows are given", k);
+      if (sources[k].nnz > 0 && (sources[k].csr_col == nullptr || sources[k].csr_val == nullptr))
+        return fail(ILARGI_ERR_NULL, "source %d: csr_col or csr_val is NULL", k);
+      src[k].csr_rowptr = sources[k].csr_rowptr;
+      src[k].csr_col = sources[k].csr_col;
+      src[k].csr_val = sources[k].csr_val;
+    } else if (sources[k].rows > 0 && sources[k].cols > 0 && sources[k].D == nullptr) {
       return fail(ILARGI_ERR_NULL, "source %d: D is NULL", k);
+    }
     src[k].colmap_h.assign(sources[k].col_map, sources[k].col_map + sources[k].cols);
     for (int64_t j = 0; j < sources[k].cols; ++j) {
       int32_t t = sources[k].col_map[j];
@@ -610,7 +673,7 @@ ilargi_status_t ilargi_plan_create(int n, const ilargi_source_t* sources, int64_
   pl->src = std::move(src); pl->lay = lay;
   hipStream_t st = static_cast<hipStream_t>(stream);
 
-  HIP_TRY(hipMemsetAsync(pl->at<int32_t>(lay.o_flags), 0, sizeof(int32_t) * 2 * n, st));
+  HIP_TRY(hipMemsetAsync(pl->at<int32_t>(lay.o_flags), 0, sizeof(int32_t) * 3 * n, st));
   std::vector<const int32_t*> tcol_ptrs(n);
   for (int k = 0; k < n; ++k) {
     SourcePlan& p = pl->src[k];
@@ -618,11 +681,22 @@ ilargi_status_t ilargi_plan_create(int n, const ilargi_source_t* sources, int64_
     HIP_TRY(hipMemcpyAsync(pl->at<int32_t>(p.o_tcol), tcol[k].data(), sizeof(int32_t) * c_T, hipMemcpyHostToDevice, st));
     tcol_ptrs[k] = pl->at<int32_t>(p.o_tcol);
     if (p.has_idx) HIP_TRY(launch_check_idx(p.idx, r_T, p.rows, pl->at<int32_t>(lay.o_flags) + 2 * k, st));
+    if (p.sparse) {
+      pl->any_sparse = true;
+      SparseArgs sa;
+      memset(&sa, 0, sizeof(sa));
+      sa.rowptr = p.csr_rowptr; sa.col = p.csr_col; sa.rows = p.rows; sa.cols = (int)p.cols; sa.nnz = p.entries;
+      HIP_TRY(launch_csr_check(sa, pl->at<int32_t>(lay.o_flags) + 2 * n + k, st));
+    }
   }
   HIP_TRY(hipMemcpyAsync(pl->at<void*>(lay.o_tcol_table), tcol_ptrs.data(), sizeof(void*) * n, hipMemcpyHostToDevice, st));
-  std::vector<int32_t> flags(2 * n, 0);
-  HIP_TRY(hipMemcpyAsync(flags.data(), pl->at<int32_t>(lay.o_flags), sizeof(int32_t) * 2 * n, hipMemcpyDeviceToHost, st));
+  std::vector<int32_t> flags(3 * n, 0);
+  HIP_TRY(hipMemcpyAsync(flags.data(), pl->at<int32_t>(lay.o_flags), sizeof(int32_t) * 3 * n, hipMemcpyDeviceToHost, st));
   HIP_TRY(hipStreamSynchronize(st));
+  for (int k = 0; k < n; ++k)
+    if (flags[2 * n + k] != 0)
+      return fail(ILARGI_ERR_INDEX_RANGE, "source %d: sparse rows are not valid (row pointers must rise from 0 to nnz, "
+                  "column indices must lie in [0, cols) and ascend strictly within a row)", k);
   for (int k = 0; k < n; ++k) {
     SourcePlan& p = pl->src[k];
     if (!p.has_idx) { p.ident = true; p.nnz = p.rows; continue; }
@@ -659,11 +733,49 @@ ilargi_status_t ilargi_plan_create(int n, const ilargi_source_t* sources, int64_
     int64_t avg = p.rows > 0 ? (p.nnz + p.rows - 1) / p.rows : 1;
     p.logG = std::min(6, ilog2_ceil(std::max<int64_t>(avg, 1)));
   }
-  // the identity source with the most cells has its product fused into the assembly pass
+  // column-sorted view of every sparse source: the same stable sort, keyed by column index
+  for (int k = 0; k < n; ++k) {
+    SourcePlan& p = pl->src[k];
+    if (!p.sparse) continue;
+    int32_t* sortbuf = pl->at<int32_t>(lay.o_sort);
+    const int64_t nn = std::max<int64_t>(std::max<int64_t>(r_T, 1), lay.max_entries);
+    int32_t* entry_row = pl->at<int32_t>(lay.o_tmp_a);
+    int32_t* cperm = pl->at<int32_t>(lay.o_tmp_b);
+    SparseArgs sa;
+    memset(&sa, 0, sizeof(sa));
+    sa.rowptr = p.csr_rowptr; sa.col = p.csr_col; sa.val = p.csr_val; sa.rows = p.rows; sa.cols = (int)p.cols; sa.nnz = p.entries;
+    HIP_TRY(launch_csr_entry_rows(sa, entry_row, st));
+    HIP_TRY(launch_sort_by_source_row(p.csr_col, p.entries, p.cols, sortbuf, sortbuf + nn, sortbuf + 2 * nn, sortbuf + 3 * nn,
+                                      pl->at<int32_t>(lay.o_hist), pl->at<int32_t>(p.o_colptr), cperm, st));
+    HIP_TRY(launch_csr_gather_rows(entry_row, p.csr_val, cperm, p.entries, pl->at<int32_t>(p.o_csc_row),
+                                   pl->at<float>(p.o_csc_val), st));
+    std::vector<int32_t> colptr((size_t)p.cols + 1);
+    HIP_TRY(hipMemcpyAsync(colptr.data(), pl->at<int32_t>(p.o_colptr), sizeof(int32_t) * (p.cols + 1), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    if (colptr[(size_t)p.cols] != p.entries) return fail(ILARGI_ERR_DEVICE, "internal: column view of source %d lost entries", k);
+    std::vector<int32_t> cb, ce, first((size_t)p.cols + 1, 0);
+    for (int64_t j = 0; j < p.cols; ++j) {
+      first[(size_t)j] = (int32_t)cb.size();
+      for (int32_t b = colptr[(size_t)j]; b < colptr[(size_t)j + 1]; b += kSparseChunk) {
+        cb.push_back(b);
+        ce.push_back(std::min(colptr[(size_t)j + 1], b + kSparseChunk));
+      }
+    }
+    first[(size_t)p.cols] = (int32_t)cb.size();
+    p.n_tchunks = (int)cb.size();
+    if (p.n_tchunks > p.tchunk_max) return fail(ILARGI_ERR_WORKSPACE, "internal: column chunk table overflow");
+    if (p.n_tchunks > 0) {
+      HIP_TRY(hipMemcpyAsync(pl->at<int32_t>(p.o_tchunk_beg), cb.data(), sizeof(int32_t) * cb.size(), hipMemcpyHostToDevice, st));
+      HIP_TRY(hipMemcpyAsync(pl->at<int32_t>(p.o_tchunk_end), ce.data(), sizeof(int32_t) * ce.size(), hipMemcpyHostToDevice, st));
+    }
+    HIP_TRY(hipMemcpyAsync(pl->at<int32_t>(p.o_col_first), first.data(), sizeof(int32_t) * first.size(), hipMemcpyHostToDevice, st));
+    HIP_TRY(hipStreamSynchronize(st));
+  }
+  // the dense identity source with the most cells has its product fused into the assembly pass
   int64_t best = -1;
   for (int k = 0; k < n; ++k) {
     const SourcePlan& p = pl->src[k];
-    if (p.ident && !p.empty && p.rows * p.cols > best) { best = p.rows * p.cols; pl->fused = k; }
+    if (p.ident && !p.empty && !p.sparse && p.rows * p.cols > best) { best = p.rows * p.cols; pl->fused = k; }
   }
   // scalar operators: which element-wise operators may act on the sources alone, the vector of ones of
   // rowSum and the fan-out vectors of colSum
@@ -696,7 +808,7 @@ ilargi_status_t ilargi_plan_create(int n, const ilargi_source_t* sources, int64_
       ++live;
       if (k != pl->fused) dim = k;
     }
-    if (live == 2 && pl->fused >= 0 && dim >= 0) {
+    if (live == 2 && pl->fused >= 0 && dim >= 0 && !pl->any_sparse) {
       const SourcePlan& f = pl->src[pl->fused];
       const SourcePlan& d = pl->src[dim];
       if (f.rows == r_T && d.has_idx && !d.ident && d.nnz == r_T && d.n_long == 0) pl->star_k = dim;
@@ -855,8 +967,9 @@ ilargi_status_t ilargi_lmm(ilargi_plan_t* plan, const float* X, int64_t cx, floa
   const bool bf16 = precision == ILARGI_BF16_IN_F32_ACC;
   if (precision != ILARGI_F32 && !bf16) return fail(ILARGI_ERR_UNSUPPORTED, "lmm: unknown precision %d", (int)precision);
   if (bf16 && cx < kWideMin) return fail(ILARGI_ERR_UNSUPPORTED, "lmm: bf16 inputs need an operand with at least %d columns", kWideMin);
+  if (bf16 && plan->any_sparse) return fail(ILARGI_ERR_UNSUPPORTED, "lmm: bf16 inputs need dense source tables");
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if (cx >= kWideMin) return lmm_pass(plan, X, (int)cx, 0, (int)cx, out, (int)cx, 0, nullptr, nullptr, true, st, nullptr, bf16);
+  if (cx >= kWideMin && !plan->any_sparse) return lmm_pass(plan, X, (int)cx, 0, (int)cx, out, (int)cx, 0, nullptr, nullptr, true, st, nullptr, bf16);
   const int w = pass_width(plan);
   for (int64_t col0 = 0; col0 < cx; col0 += w) {
     int ncols = (int)std::min<int64_t>(w, cx - col0);
@@ -873,8 +986,9 @@ ilargi_status_t ilargi_tmm(ilargi_plan_t* plan, const float* Y, int64_t cx, floa
   const bool bf16 = precision == ILARGI_BF16_IN_F32_ACC;
   if (precision != ILARGI_F32 && !bf16) return fail(ILARGI_ERR_UNSUPPORTED, "tmm: unknown precision %d", (int)precision);
   if (bf16 && cx < kWideMin) return fail(ILARGI_ERR_UNSUPPORTED, "tmm: bf16 inputs need an operand with at least %d columns", kWideMin);
+  if (bf16 && plan->any_sparse) return fail(ILARGI_ERR_UNSUPPORTED, "tmm: bf16 inputs need dense source tables");
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if (cx >= kWideMin) return tmm_wide(plan, Y, (int)cx, out, 0, nullptr, nullptr, 0, 0.0f, bf16, st);
+  if (cx >= kWideMin && !plan->any_sparse) return tmm_wide(plan, Y, (int)cx, out, 0, nullptr, nullptr, 0, 0.0f, bf16, st);
   for (int64_t col0 = 0; col0 < cx; col0 += kNarrowCT) {
     int ncols = (int)std::min<int64_t>(kNarrowCT, cx - col0);
     rc = tmm_pass(plan, Y, (int)cx, (int)col0, ncols, out, (int)cx, 0, nullptr, nullptr, 0, 0.0f, st);
@@ -893,6 +1007,7 @@ ilargi_status_t ilargi_gd_step(ilargi_plan_t* plan, ilargi_model_t model, float*
   const bool bf16 = precision == ILARGI_BF16_IN_F32_ACC;
   if (precision != ILARGI_F32 && !bf16) return fail(ILARGI_ERR_UNSUPPORTED, "gd_step: unknown precision %d", (int)precision);
   if (bf16 && m < kWideMin) return fail(ILARGI_ERR_UNSUPPORTED, "gd_step: bf16 inputs need at least %d models", kWideMin);
+  if (bf16 && plan->any_sparse) return fail(ILARGI_ERR_UNSUPPORTED, "gd_step: bf16 inputs need dense source tables");
   hipStream_t st = static_cast<hipStream_t>(stream);
   float* E = plan->at<float>(plan->lay.o_E);
   const int w = pass_width(plan);
@@ -900,7 +1015,7 @@ ilargi_status_t ilargi_gd_step(ilargi_plan_t* plan, ilargi_model_t model, float*
   if (plan->star_k >= 0 && gd_star_supported((int)plan->src[plan->fused].cols, (int)m) &&
       (int64_t)plan->src[plan->fused].cols * m <= plan->lay.gpartial_floats)
     return gd_star_step(plan, model == ILARGI_LINEAR ? 1 : 2, W, (int)m, y, lr, loss, loss_scale, bf16, st);
-  if (m >= kWideMin) {
+  if (m >= kWideMin && !plan->any_sparse) {
     int loss_grid = 0;
     bool fusedg = false;
     rc = lmm_pass(plan, W, (int)m, 0, (int)m, E, (int)m, model == ILARGI_LINEAR ? 1 : 2, y, &loss_grid, true, st,
@@ -936,14 +1051,26 @@ ilargi_status_t ilargi_elementwise(ilargi_plan_t* plan, ilargi_elementwise_t op,
     return fail(ILARGI_ERR_UNSUPPORTED, "elementwise: operator %d needs target columns fed by one source each", o);
   if (!linear && !keeps_zero && !plan->cover_full)
     return fail(ILARGI_ERR_UNSUPPORTED, "elementwise: operator %d needs every target cell fed by a source cell", o);
-  for (int k = 0; k < plan->n; ++k)
-    if (!plan->src[k].empty && D_out[k] == nullptr) return fail(ILARGI_ERR_NULL, "elementwise: D_out[%d] is NULL", k);
+  if (plan->any_sparse && !linear && !keeps_zero)
+    return fail(ILARGI_ERR_UNSUPPORTED, "elementwise: operator %d does not keep the zeros a sparse table leaves out", o);
+  for (int k = 0; k < plan->n; ++k) {
+    const SourcePlan& p = plan->src[k];
+    if (!p.empty && !(p.sparse && p.entries == 0) && D_out[k] == nullptr)
+      return fail(ILARGI_ERR_NULL, "elementwise: D_out[%d] is NULL", k);
+  }
   hipStream_t st = static_cast<hipStream_t>(stream);
   for (int k = 0; k < plan->n; ++k) {
     const SourcePlan& p = plan->src[k];
     if (p.empty) continue;
     TraceScope ts(plan, "elementwise", k, st);
-    HIP_TRY(launch_elementwise(o, p.D, D_out[k], p.rows * p.cols, x, st));
+    if (p.sparse) {
+      // the stored entries; updated in place, the plan's column-sorted copy of the values follows
+      HIP_TRY(launch_elementwise(o, p.csr_val, D_out[k], p.entries, x, st));
+      if (D_out[k] == p.csr_val)
+        HIP_TRY(launch_elementwise(o, plan->at<float>(p.o_csc_val), plan->at<float>(p.o_csc_val), p.entries, x, st));
+    } else {
+      HIP_TRY(launch_elementwise(o, p.D, D_out[k], p.rows * p.cols, x, st));
+    }
   }
   return ILARGI_OK;
 }
@@ -984,6 +1111,25 @@ ilargi_status_t ilargi_materialize(ilargi_plan_t* plan, float* T, void* stream) 
   if (plan == nullptr) return fail(ILARGI_ERR_NULL, "materialize: plan is NULL");
   if (plan->r_T == 0) return ILARGI_OK;
   if (T == nullptr) return fail(ILARGI_ERR_NULL, "materialize: T is NULL");
+  if (plan->any_sparse) {
+    // zero, then one pass per source in source order: every cell receives its terms in the order of the sum
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    TraceScope ts(plan, "materialize", -1, st);
+    HIP_TRY(launch_fill_zero(T, plan->r_T * plan->c_T, st));
+    for (int k = 0; k < plan->n; ++k) {
+      const SourcePlan& p = plan->src[k];
+      if (p.empty) continue;
+      const int32_t* idx = p.ident ? nullptr : p.idx;
+      if (p.sparse) {
+        SparseArgs sa = sparse_args(plan, k);
+        HIP_TRY(launch_mat_scatter(&sa, nullptr, p.rows, (int)p.cols, sa.colmap, idx, p.rows, T, plan->r_T, (int)plan->c_T, st));
+      } else {
+        HIP_TRY(launch_mat_scatter(nullptr, p.D, p.rows, (int)p.cols, plan->at<int32_t>(p.o_colmap), idx, p.rows, T,
+                                   plan->r_T, (int)plan->c_T, st));
+      }
+    }
+    return ILARGI_OK;
+  }
   MatArgs a;
   memset(&a, 0, sizeof(a));
   for (int k = 0; k < plan->n; ++k) {
@@ -1011,6 +1157,7 @@ ilargi_status_t ilargi_materialize(ilargi_plan_t* plan, float* T, void* stream) 
 ilargi_status_t ilargi_crossprod(ilargi_plan_t* plan, float* out, void* stream) {
   if (plan == nullptr) return fail(ILARGI_ERR_NULL, "crossprod: plan is NULL");
   if (out == nullptr) return fail(ILARGI_ERR_NULL, "crossprod: out is NULL");
+  if (plan->any_sparse) return fail(ILARGI_ERR_UNSUPPORTED, "crossprod: source tables in sparse rows are not supported");
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int n = plan->n;
   float* blocks = plan->at<float>(plan->lay.o_blocks);

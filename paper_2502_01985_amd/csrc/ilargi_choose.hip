@@ -41,7 +41,8 @@ extern "C" ilargi_status_t ilargi_choose(int n, const ilargi_source_t* sources, 
   // Eq. (1) for linear regression with dense operands: w is c_T x 1 (m_w = c_T), X = T w is r_T x 1 (m_X = r_T)
   double o_fact = 0.0;
   for (int k = 0; k < n; ++k) {
-    const double rk = (double)sources[k].rows, ck = (double)sources[k].cols, mk = rk * ck;
+    const double rk = (double)sources[k].rows, ck = (double)sources[k].cols;
+    const double mk = sources[k].csr_rowptr != nullptr ? (double)sources[k].nnz : rk * ck;   // non-zero elements
     o_fact += (mk + rk * cT) + (mk + ck * rT);
   }
   const double o_mat = (mT + rT * cT) + (mT + cT * rT);
@@ -55,7 +56,7 @@ extern "C" ilargi_status_t ilargi_choose(int n, const ilargi_source_t* sources, 
     const double rk = (double)sources[k].rows, ck = (double)sources[k].cols;
     if (sources[k].row_idx == nullptr) {
       base_cols += ck;
-      if (rk * ck > fused_cells) { fused_cells = rk * ck; fused = k; }
+      if (sources[k].csr_rowptr == nullptr && rk * ck > fused_cells) { fused_cells = rk * ck; fused = k; }
     } else {
       joined_rows += rk;
       joined_cols += ck;
@@ -72,9 +73,12 @@ extern "C" ilargi_status_t ilargi_choose(int n, const ilargi_source_t* sources, 
   double b_fact = 0.0, join_fetch = 0.0;
   int launches_fact = 2;                                   // assembly pass, update
   for (int k = 0; k < n; ++k) {
-    const double rk = (double)sources[k].rows, ck = (double)sources[k].cols, cells = 4.0 * rk * ck;
+    const double rk = (double)sources[k].rows, ck = (double)sources[k].cols;
+    const bool sparse = sources[k].csr_rowptr != nullptr;
+    // a stored entry of a sparse table is a value and a column index (a row index in the column-sorted view)
+    const double cells = sparse ? 8.0 * (double)sources[k].nnz + 4.0 * rk : 4.0 * rk * ck;
     if (rk == 0.0 || ck == 0.0) continue;
-    if (k == fused) {
+    if (k == fused && !sparse) {
       const bool one_pass = ck <= kFusedMaxCols;
       b_fact += one_pass ? cells : 2.0 * cells;
       launches_fact += one_pass ? 0 : 1;
@@ -87,7 +91,7 @@ extern "C" ilargi_status_t ilargi_choose(int n, const ilargi_source_t* sources, 
       b_fact += 8.0 * rT + 4.0 * vec * rk;                 // row index, inverse index; P_k written and gathered, Z_k written and read
       b_fact += 2.0 * std::max(vec, kMinFetch) * rT;       // gathered product rows, residual rows read by the segment sum
       launches_fact += 1;
-      join_fetch += 4.0 * rT * ck + 4.0 * rT;              // one source row per target row, row index
+      join_fetch += (sparse && rk > 0.0 ? cells / rk : 4.0 * ck) * rT + 4.0 * rT;   // one source row per target row, row index
     } else {
       b_fact += 2.0 * vec * rk + vec * rT;
       join_fetch += cells;

@@ -14,6 +14,7 @@ constexpr int kWave = 64;            // gfx950 wavefront
 constexpr int kBlock = 256;          // threads per workgroup in the streaming kernels
 constexpr int kNarrowCT = 4;         // operand columns one narrow (VALU) pass handles
 constexpr int kColredBlocks = 1024;  // row chunks (= partial results) of the D^T Z reduction
+constexpr int kSparseChunk = 4096;   // entries of a column one workgroup sums
 constexpr int kLongSeg = 2048;       // inverse-index segments longer than this are split ...
 constexpr int kSegChunk = 2048;      // ... into chunks of this many entries
 constexpr int kSortChunk = 2048;     // keys per workgroup in one radix pass
@@ -58,6 +59,22 @@ struct MfmaShape {
   int lda;           // LDS row stride of the staged rows (floats)
   int rb;            // table rows per workgroup step
   size_t lds_bytes;
+};
+
+// A source table in compressed sparse rows with its column-sorted view (kernels_sparse.hip).
+struct SparseArgs {
+  const int32_t* rowptr;   // rows + 1
+  const int32_t* col;      // nnz, strictly ascending within a row
+  const float* val;        // nnz
+  int64_t rows, nnz;
+  int cols;
+  const int32_t* colmap;   // device int32[cols]
+  // column-sorted view, built with the plan
+  const int32_t* csc_row;  // nnz: row of the p-th entry in column order
+  const float* csc_val;    // nnz: its value
+  const int32_t* chunk_beg, *chunk_end;   // n_chunks ranges of that order, each inside one column
+  const int32_t* col_first_chunk;         // cols + 1
+  int n_chunks;
 };
 
 // Gradient-descent pass over a two-table star join for a wide batch of models (kernels_star.hip).
@@ -190,6 +207,16 @@ bool lmm_mfma_can_fuse_gradient(int ck, int ncols, bool bf16);
 hipError_t launch_lmm_mfma(const LmmArgs& a, int vec, int mode, bool bf16, hipStream_t st, int* grid_out);
 bool gd_star_supported(int cs, int m);
 hipError_t launch_gd_star(const StarArgs& a, int vec, int mode, bool bf16, int max_grid, hipStream_t st, int* grid_out);
+hipError_t launch_csr_check(const SparseArgs& a, int32_t* flags, hipStream_t st);
+hipError_t launch_csr_entry_rows(const SparseArgs& a, int32_t* entry_row, hipStream_t st);
+hipError_t launch_csr_gather_rows(const int32_t* entry_row, const float* val, const int32_t* perm, int64_t nnz,
+                                  int32_t* csc_row, float* csc_val, hipStream_t st);
+hipError_t launch_spmm_rows(const SparseArgs& a, const float* X, int ldx, int col0, int ncols, float* P, int ldp,
+                            hipStream_t st);
+hipError_t launch_spmm_t(const SparseArgs& a, const float* Z, int ldz, int col0, int ncols, float* partial, float* G,
+                         hipStream_t st);
+hipError_t launch_mat_scatter(const SparseArgs* sparse, const float* D, int64_t rows, int ck, const int32_t* colmap,
+                              const int32_t* idx, int64_t ident_rows, float* T, int64_t r_T, int c_T, hipStream_t st);
 hipError_t launch_segsum(const SegArgs& a, hipStream_t st);
 hipError_t launch_colred(const ColredArgs& a, int nblocks, hipStream_t st);
 hipError_t launch_finalize(const FinArgs& a, int c_T, int mode, hipStream_t st);

@@ -169,3 +169,24 @@ def test_choose_rejects_bad_arguments():
     with pytest.raises(il.IlargiError) as ei:
         il.ilargi_choose([(10, 2, False)], 10, 0)
     assert ei.value.status == il.ERR_SHAPE
+
+
+# ----------------------------------------------------------------------------- sparse sources (host side)
+def test_workspace_grows_with_the_stored_entries_of_a_sparse_source():
+    cm = np.arange(8, dtype=np.int32)
+    dense = il.ilargi_plan_workspace_bytes([(1, 1000, 8, 0, cm)], 1000, 8, 1)
+    sparse = il.ilargi_plan_workspace_bytes([(0, 1000, 8, 0, cm, 1, 1, 1, 4000)], 1000, 8, 1)
+    more = il.ilargi_plan_workspace_bytes([(0, 1000, 8, 0, cm, 1, 1, 1, 8000)], 1000, 8, 1)
+    # column-sorted rows and values and two temporaries: at least 16 bytes per stored entry, sort buffers on top
+    assert sparse - dense >= 16 * 4000 and more - sparse >= 16 * 4000
+    with pytest.raises(il.IlargiError) as ei:
+        il.ilargi_plan_workspace_bytes([(0, 1000, 8, 0, cm, 1, 1, 1, 8001)], 1000, 8, 1)    # more entries than cells
+    assert ei.value.status == il.ERR_SHAPE
+
+
+def test_choose_counts_stored_entries_for_sparse_tables():
+    dense = il.ilargi_choose([(100_000, 20, False), (10_000, 200, True)], 100_000, 220)
+    sparse = il.ilargi_choose([(100_000, 20, False, 200_000), (10_000, 200, True, 200_000)], 100_000, 220)
+    # Tab. 2: the factorized cost is counted in non-zero elements
+    assert sparse["complexity_ratio"] > dense["complexity_ratio"]
+    assert sparse["bytes_factorized"] < dense["bytes_factorized"]

@@ -694,3 +694,104 @@ def test_elementwise_conditions_on_shared_and_empty_cells(il):
     with pytest.raises(il.IlargiError) as ei:
         il.ilargi_elementwise(plan2, 10, 0.0)
     assert ei.value.status == il.ERR_UNSUPPORTED
+
+
+# ------------------------------------------------------------------ source tables in compressed sparse rows
+def _sparse_case(il, name, p, which=True, max_cx=17):
+    sch = datagen.sparsify(SCHEMAS[name](), p, seed=1300)
+    tg = oracle.Target(sch)
+    srcs = il.schema_to_device(sch, sparse=which)
+    plan = il.ilargi_plan_create(srcs, sch.r_T, sch.c_T, max_cx=max_cx)
+    return sch, tg, srcs, plan
+
+
+@pytest.mark.parametrize("p", [0.0, 0.5, 0.9])
+@pytest.mark.parametrize("name", ["config0", "config1_small", "config2_small", "config3_small", "tiny_mixed", "odd_cols"])
+def test_sparse_sources_operators_and_join(il, name, p):
+    # every table in compressed sparse rows (p = 0: all cells stored): join bit-exact, operators within the
+    # float32 bound, row and column sums
+    sch, tg, srcs, plan = _sparse_case(il, name, p)
+    assert np.array_equal(il.ilargi_materialize(plan).cpu().numpy().view(np.uint32), tg.T32.view(np.uint32))
+    rng = datagen.rng_for(1301)
+    for cx in (1, 3, 4, 5, 17):
+        X = rng.standard_normal((sch.c_T, cx)).astype(np.float32)
+        Y = rng.standard_normal((sch.r_T, cx)).astype(np.float32)
+        assert rel(il.ilargi_lmm(plan, dev(X)).cpu().numpy(), oracle.lmm(tg, X)) < OP_TOL
+        assert rel(il.ilargi_tmm(plan, dev(Y)).cpu().numpy(), oracle.tmm(tg, Y)) < OP_TOL
+    assert rel(il.ilargi_row_sum(plan).cpu().numpy(), oracle.row_sum(tg)) < OP_TOL
+    assert rel(il.ilargi_col_sum(plan).cpu().numpy(), oracle.col_sum(tg)) < OP_TOL
+
+
+@pytest.mark.parametrize("which", [(0,), (1,), True])
+@pytest.mark.parametrize("model", ["linear", "logistic"])
+def test_sparse_sources_gradient_descent(il, model, which):
+    # dense and sparse tables mixed: the entity table sparse (no shared pass), the dimension table sparse, both
+    sch, tg, srcs, plan = _sparse_case(il, "config1_small", 0.7, which)
+    rng = datagen.rng_for(1303)
+    w_star = rng.standard_normal(sch.c_T) / np.sqrt(sch.c_T)
+    y = datagen.finish_labels(model, oracle.lmm(tg, w_star.reshape(-1, 1)), 0.01 * rng.standard_normal(sch.r_T))
+    code = il.LINEAR if model == "linear" else il.LOGISTIC
+    lrs = [0.05, 0.1, 0.2, 0.3, 0.4]
+    W, L = _run_gd(il, plan, code, y, lrs, 10, sch.c_T)
+    W_ref, L_ref = oracle.gd(tg, model, y, np.zeros((sch.c_T, len(lrs))), lrs, 10)
+    assert max(rel(W[:, j], W_ref[:, j]) for j in range(len(lrs))) < GD_TOL
+    np.testing.assert_allclose(L, L_ref, rtol=2e-4)
+
+
+def test_sparse_sources_edge_cases(il):
+    # empty rows and columns, a table without any stored entry, a long column split into chunks, unmatched rows
+    rng = datagen.rng_for(1302)
+    r_T = 9_001
+    S = rng.standard_normal((r_T, 6)).astype(np.float32)
+    S[:, 2] = 0.0                                    # an empty column
+    S[100:300] = 0.0                                 # empty rows
+    S[rng.random(S.shape) < 0.3] = 0.0
+    R = np.zeros((40, 5), dtype=np.float32)          # no stored entry at all
+    Q = rng.standard_normal((7, 3)).astype(np.float32)
+    fk = rng.integers(0, 40, r_T).astype(np.int32)
+    fq = rng.integers(0, 7, r_T).astype(np.int32)
+    fq[::11] = -1
+    sch = datagen.Schema([datagen.Source(S, None, np.arange(6, dtype=np.int32)),
+                          datagen.Source(R, fk, np.arange(6, 11, dtype=np.int32)),
+                          datagen.Source(Q, fq, np.array([11, -1, 12], dtype=np.int32))], r_T, 13)
+    tg = oracle.Target(sch)
+    srcs = il.schema_to_device(sch, sparse=True)
+    assert srcs[1][0].nnz == 0 and srcs[0][0].nnz > 2 * 4096     # column chunks of 4096 entries
+    plan = il.ilargi_plan_create(srcs, r_T, 13, max_cx=4)
+    assert np.array_equal(il.ilargi_materialize(plan).cpu().numpy().view(np.uint32), tg.T32.view(np.uint32))
+    X = rng.standard_normal((13, 4)).astype(np.float32)
+    Y = rng.standard_normal((r_T, 4)).astype(np.float32)
+    assert rel(il.ilargi_lmm(plan, dev(X)).cpu().numpy(), oracle.lmm(tg, X)) < OP_TOL
+    assert rel(il.ilargi_tmm(plan, dev(Y)).cpu().numpy(), oracle.tmm(tg, Y)) < OP_TOL
+    assert rel(il.ilargi_col_sum(plan).cpu().numpy(), oracle.col_sum(tg)) < OP_TOL
+    # element-wise operators act on the stored values; only those that keep zero at zero are accepted
+    outs = il.ilargi_elementwise(plan, "square")
+    for o, (D, _, _) in zip(outs, srcs):
+        assert torch.equal(o, D.val * D.val)
+    il.ilargi_elementwise(plan, "mul", -2.0, outs=[D.val for D, _, _ in srcs])      # in place
+    assert rel(il.ilargi_tmm(plan, dev(Y)).cpu().numpy(), -2.0 * oracle.tmm(tg, Y)) < OP_TOL
+    assert rel(il.ilargi_lmm(plan, dev(X)).cpu().numpy(), -2.0 * oracle.lmm(tg, X)) < OP_TOL
+    for op in ("exp", "add", "log"):
+        with pytest.raises(il.IlargiError) as ei:
+            il.ilargi_elementwise(plan, op, 1.0)
+        assert ei.value.status == il.ERR_UNSUPPORTED
+    with pytest.raises(il.IlargiError) as ei:
+        il.ilargi_crossprod(plan)
+    assert ei.value.status == il.ERR_UNSUPPORTED
+    with pytest.raises(il.IlargiError) as ei:
+        il.ilargi_lmm(plan, torch.zeros((13, 4), device="cuda"), precision=il.BF16_IN_F32_ACC)
+    assert ei.value.status == il.ERR_UNSUPPORTED
+
+
+def test_invalid_sparse_rows_are_reported(il):
+    good = il.CSR.from_dense(np.array([[1.0, 0.0, 2.0], [0.0, 3.0, 0.0]], dtype=np.float32))
+    cm = np.arange(3, dtype=np.int32)
+    il.ilargi_plan_create([(good, None, cm)], 2, 3, max_cx=1)
+    def broken(rowptr=None, col=None):
+        return il.CSR(good.rowptr if rowptr is None else dev(np.array(rowptr, dtype=np.int32)),
+                      good.col if col is None else dev(np.array(col, dtype=np.int32)), good.val, (2, 3))
+    for bad in (broken(rowptr=[0, 3, 2]), broken(rowptr=[1, 2, 3]), broken(rowptr=[0, 2, 4]), broken(col=[0, 3, 1]),
+                broken(col=[2, 0, 1]), broken(col=[0, 0, 1]), broken(col=[-1, 2, 1])):
+        with pytest.raises(il.IlargiError) as ei:
+            il.ilargi_plan_create([(bad, None, cm)], 2, 3, max_cx=1)
+        assert ei.value.status == il.ERR_INDEX_RANGE
