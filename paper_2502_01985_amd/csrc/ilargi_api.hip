@@ -46,7 +46,10 @@ struct SourcePlan {
   const int32_t* csr_col = nullptr;
   const float* csr_val = nullptr;
   int64_t entries = 0;            // stored entries of a sparse source
-  size_t o_csc_row = 0, o_csc_val = 0, o_colptr = 0, o_tchunk_beg = 0, o_tchunk_end = 0, o_col_first = 0, o_tpartial = 0;
+  size_t o_csc_row = 0, o_csc_val = 0, o_colptr = 0, o_tchunk_beg = 0, o_tchunk_end = 0, o_col_first = 0, o_tpartial = 0,
+         o_row_block = 0;
+  int64_t row_block_max = 0;
+  int n_row_blocks = 0;
   int64_t tchunk_max = 0;
   int n_tchunks = 0;
   int vec = 1;
@@ -202,6 +205,10 @@ ilargi_status_t make_layout(int n, const ilargi_source_t* s, int64_t r_T, int64_
       p.o_tchunk_end = take(sizeof(int32_t) * p.tchunk_max);
       p.o_col_first = take(sizeof(int32_t) * (p.cols + 1));
       p.o_tpartial = take(sizeof(float) * p.tchunk_max * kNarrowCT);
+      // runs of whole rows with at most cap entries: a run ends when the next row would overflow it, so two
+      // neighbouring runs together hold more than cap entries (or one of them is a single row)
+      p.row_block_max = 2 * (p.entries / sparse_row_block_cap((int)p.cols) + 1) + p.rows / kSparseBlockRows + 2;
+      p.o_row_block = take(sizeof(int32_t) * (p.row_block_max + 1));
     }
   }
   if (lay.max_entries > 0) {
@@ -294,6 +301,8 @@ SparseArgs sparse_args(const ilargi_plan* pl, int k) {
   a.rowptr = p.csr_rowptr; a.col = p.csr_col; a.val = p.csr_val;
   a.rows = p.rows; a.nnz = p.entries; a.cols = (int)p.cols;
   a.colmap = pl->at<int32_t>(p.o_colmap);
+  a.row_block = pl->at<int32_t>(p.o_row_block);
+  a.n_row_blocks = p.n_row_blocks;
   a.csc_row = pl->at<int32_t>(p.o_csc_row);
   a.csc_val = pl->at<float>(p.o_csc_val);
   a.chunk_beg = pl->at<int32_t>(p.o_tchunk_beg);
@@ -744,6 +753,26 @@ ilargi_status_t ilargi_plan_create(int n, const ilargi_source_t* sources, int64_
     SparseArgs sa;
     memset(&sa, 0, sizeof(sa));
     sa.rowptr = p.csr_rowptr; sa.col = p.csr_col; sa.val = p.csr_val; sa.rows = p.rows; sa.cols = (int)p.cols; sa.nnz = p.entries;
+    {
+      // row blocks of the row-wise product (host side, once)
+      std::vector<int32_t> rp((size_t)p.rows + 1);
+      HIP_TRY(hipMemcpyAsync(rp.data(), p.csr_rowptr, sizeof(int32_t) * (p.rows + 1), hipMemcpyDeviceToHost, st));
+      HIP_TRY(hipStreamSynchronize(st));
+      const int cap = sparse_row_block_cap((int)p.cols);
+      std::vector<int32_t> rb;
+      rb.push_back(0);
+      int64_t r = 0;
+      while (r < p.rows) {
+        int64_t r2 = r + 1;
+        while (r2 < p.rows && r2 - r < kSparseBlockRows && rp[(size_t)r2 + 1] - rp[(size_t)r] <= cap) ++r2;
+        rb.push_back((int32_t)r2);
+        r = r2;
+      }
+      p.n_row_blocks = (int)rb.size() - 1;
+      if (p.n_row_blocks > p.row_block_max) return fail(ILARGI_ERR_WORKSPACE, "internal: row block table overflow");
+      HIP_TRY(hipMemcpyAsync(pl->at<int32_t>(p.o_row_block), rb.data(), sizeof(int32_t) * rb.size(), hipMemcpyHostToDevice, st));
+      HIP_TRY(hipStreamSynchronize(st));
+    }
     HIP_TRY(launch_csr_entry_rows(sa, entry_row, st));
     HIP_TRY(launch_sort_by_source_row(p.csr_col, p.entries, p.cols, sortbuf, sortbuf + nn, sortbuf + 2 * nn, sortbuf + 3 * nn,
                                       pl->at<int32_t>(lay.o_hist), pl->at<int32_t>(p.o_colptr), cperm, st));

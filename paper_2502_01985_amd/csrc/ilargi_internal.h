@@ -14,6 +14,7 @@ constexpr int kWave = 64;            // gfx950 wavefront
 constexpr int kBlock = 256;          // threads per workgroup in the streaming kernels
 constexpr int kNarrowCT = 4;         // operand columns one narrow (VALU) pass handles
 constexpr int kColredBlocks = 1024;  // row chunks (= partial results) of the D^T Z reduction
+constexpr int kSparseBlockRows = 1024;   // rows a row block of the sparse row-wise product holds at most
 constexpr int kSparseChunk = 4096;   // entries of a column one workgroup sums
 constexpr int kLongSeg = 2048;       // inverse-index segments longer than this are split ...
 constexpr int kSegChunk = 2048;      // ... into chunks of this many entries
@@ -69,6 +70,8 @@ struct SparseArgs {
   int64_t rows, nnz;
   int cols;
   const int32_t* colmap;   // device int32[cols]
+  const int32_t* row_block;  // n_row_blocks + 1: runs of whole rows with at most sparse_row_block_cap(cols) entries
+  int n_row_blocks;
   // column-sorted view, built with the plan
   const int32_t* csc_row;  // nnz: row of the p-th entry in column order
   const float* csc_val;    // nnz: its value
@@ -211,6 +214,7 @@ hipError_t launch_csr_check(const SparseArgs& a, int32_t* flags, hipStream_t st)
 hipError_t launch_csr_entry_rows(const SparseArgs& a, int32_t* entry_row, hipStream_t st);
 hipError_t launch_csr_gather_rows(const int32_t* entry_row, const float* val, const int32_t* perm, int64_t nnz,
                                   int32_t* csc_row, float* csc_val, hipStream_t st);
+int sparse_row_block_cap(int cols);
 hipError_t launch_spmm_rows(const SparseArgs& a, const float* X, int ldx, int col0, int ncols, float* P, int ldp,
                             hipStream_t st);
 hipError_t launch_spmm_t(const SparseArgs& a, const float* Z, int ldz, int col0, int ncols, float* partial, float* G,

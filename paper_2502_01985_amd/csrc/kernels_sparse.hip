@@ -56,67 +56,72 @@ __global__ __launch_bounds__(kBlock) void csr_gather_rows_kernel(const int32_t* 
 }
 
 // P[r, col0 + c] = sum over the entries e of row r of val[e] * X[colmap[col[e]], col0 + c], c < CT.
-// 2^logL adjacent lanes share a row; X_k (ck x CT) is staged in LDS through the column map.
+// A workgroup owns a run of whole rows with at most `cap` stored entries (row_block table, built with the
+// plan): it first copies their values and column indices to LDS with coalesced loads (all of a thread's loads
+// in flight at once - rows are short, walking them one by one would leave the memory system idle), then
+// 2^k lanes per row sum the row from LDS.  X_k (ck x CT) is staged in LDS through the column map.
 template <int CT>
 __global__ __launch_bounds__(kBlock) void spmm_rows_kernel(SparseArgs a, const float* __restrict__ X, int ldx,
                                                            int col0, int ncols, float* __restrict__ P, int ldp,
-                                                           int logL) {
-  __shared__ float Xs[kMaxLdsFloats];
+                                                           int cap) {
+  extern __shared__ float lds[];
+  float* Xs = lds;                                        // [cols][CT]
+  float* valS = lds + (size_t)a.cols * CT;                // [cap]
+  int* colS = reinterpret_cast<int*>(valS + cap);         // [cap]
+  int* rpS = colS + cap;                                  // [kSparseBlockRows + 1] row pointers of the block
   for (int e = threadIdx.x; e < a.cols * CT; e += kBlock) {
     const int j = e / CT, c = e - j * CT;
     const int t = a.colmap[j];
     Xs[e] = (t >= 0 && c < ncols) ? X[(int64_t)t * ldx + col0 + c] : 0.0f;
   }
-  __syncthreads();
-  const int L = 1 << logL;
-  const int sub = threadIdx.x & (L - 1);
-  const int64_t g0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) >> logL;
-  const int64_t ng = ((int64_t)gridDim.x * kBlock) >> logL;
-  // four rows per lane group at a time: rows are short, so the loads of several rows have to be in flight
-  // together to cover the memory latency
-  constexpr int U = 4;
-  for (int64_t r0 = g0; r0 < a.rows; r0 += U * ng) {
-    int beg[U], end[U];
-    float acc[U][CT];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int64_t r = r0 + u * ng;
-      beg[u] = r < a.rows ? a.rowptr[r] : 0;
-      end[u] = r < a.rows ? a.rowptr[r + 1] : 0;
-#pragma unroll
-      for (int c = 0; c < CT; ++c) acc[u][c] = 0.0f;
-    }
-    for (int off = sub;; off += L) {
+  for (int blk = blockIdx.x; blk < a.n_row_blocks; blk += gridDim.x) {
+    const int r_lo = a.row_block[blk], r_hi = a.row_block[blk + 1];
+    const int e_lo = a.rowptr[r_lo], e_hi = a.rowptr[r_hi];
+    const int ne = e_hi - e_lo, nr = r_hi - r_lo;
+    __syncthreads();                                      // Xs ready; the previous block's entries are consumed
+    constexpr int U = 8;
+    for (int p0 = threadIdx.x; p0 < ne; p0 += U * kBlock) {
       float v[U];
       int cc[U];
-      bool any = false;
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        const int e = beg[u] + off;
-        const bool ok = e < end[u];
-        v[u] = ok ? a.val[e] : 0.0f;
-        cc[u] = ok ? a.col[e] : 0;
-        any |= ok;
+        const int p = p0 + u * kBlock;
+        v[u] = p < ne ? a.val[e_lo + p] : 0.0f;
+        cc[u] = p < ne ? a.col[e_lo + p] : 0;
       }
-      if (!any) break;
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        const float* x = Xs + cc[u] * CT;
-#pragma unroll
-        for (int c = 0; c < CT; ++c) acc[u][c] = fmaf(v[u], x[c], acc[u][c]);
+        const int p = p0 + u * kBlock;
+        if (p < ne) { valS[p] = v[u]; colS[p] = cc[u]; }
       }
     }
+    for (int g = threadIdx.x; g <= nr; g += kBlock) rpS[g] = a.rowptr[r_lo + g] - e_lo;
+    __syncthreads();
+    // lanes per row: about eight entries per lane (a wavefront instruction then serves up to 64 rows; with a
+    // lane per entry most of the time goes into the cross-lane sums of short rows), at most a wavefront
+    int logL = 0;
+    while (logL < 6 && ((int64_t)nr << (logL + 3)) < ne) ++logL;
+    const int L = 1 << logL, sub = threadIdx.x & (L - 1);
+    for (int g = threadIdx.x >> logL; g < nr; g += kBlock >> logL) {
+      const int r = r_lo + g;
+      const int beg = rpS[g], end = rpS[g + 1];
+      float acc[CT];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
+      for (int c = 0; c < CT; ++c) acc[c] = 0.0f;
+      for (int p = beg + sub; p < end; p += L) {
+        const float v = valS[p];
+        const float* x = Xs + colS[p] * CT;
+#pragma unroll
+        for (int c = 0; c < CT; ++c) acc[c] = fmaf(v, x[c], acc[c]);
+      }
       for (int off = L >> 1; off > 0; off >>= 1) {
 #pragma unroll
-        for (int c = 0; c < CT; ++c) acc[u][c] += __shfl_xor(acc[u][c], off);
+        for (int c = 0; c < CT; ++c) acc[c] += __shfl_xor(acc[c], off);
       }
-      const int64_t r = r0 + u * ng;
-      if (sub == 0 && r < a.rows) {
+      if (sub == 0) {
 #pragma unroll
         for (int c = 0; c < CT; ++c)
-          if (c < ncols) P[r * ldp + col0 + c] = acc[u][c];
+          if (c < ncols) P[(int64_t)r * ldp + col0 + c] = acc[c];
       }
     }
   }
@@ -244,21 +249,22 @@ hipError_t launch_csr_gather_rows(const int32_t* entry_row, const float* val, co
 
 hipError_t launch_spmm_rows(const SparseArgs& a, const float* X, int ldx, int col0, int ncols, float* P, int ldp,
                             hipStream_t st) {
-  if (a.rows <= 0 || ncols <= 0) return hipSuccess;
+  if (a.rows <= 0 || ncols <= 0 || a.n_row_blocks <= 0) return hipSuccess;
   if (a.cols > kMaxLdsFloats) return hipErrorInvalidValue;
-  // lanes per row: the power of two next to the average entries per row, at most a wavefront
-  const int64_t avg = a.rows > 0 ? (a.nnz + a.rows - 1) / a.rows : 1;
-  int logL = 0;
-  while (logL < 6 && (1 << logL) < avg) ++logL;
-  const int grid = grid_of(a.rows << logL, kBlock, 4096);
   const int fit = a.cols * 4 <= kMaxLdsFloats ? 4 : (a.cols * 2 <= kMaxLdsFloats ? 2 : 1);
   if (ncols > fit) return hipErrorInvalidValue;
   const int ct = ncols <= 1 ? 1 : (ncols <= 2 ? 2 : 4);   // columns the kernel carries: the operand's, rounded up
-  if (ct == 4) spmm_rows_kernel<4><<<grid, kBlock, 0, st>>>(a, X, ldx, col0, ncols, P, ldp, logL);
-  else if (ct == 2) spmm_rows_kernel<2><<<grid, kBlock, 0, st>>>(a, X, ldx, col0, ncols, P, ldp, logL);
-  else spmm_rows_kernel<1><<<grid, kBlock, 0, st>>>(a, X, ldx, col0, ncols, P, ldp, logL);
+  const int cap = sparse_row_block_cap(a.cols);
+  const size_t lds_bytes = ((size_t)a.cols * ct + 2 * (size_t)cap + kSparseBlockRows + 1) * sizeof(float);
+  const int grid = std::min(a.n_row_blocks, 8192);
+  if (ct == 4) spmm_rows_kernel<4><<<grid, kBlock, lds_bytes, st>>>(a, X, ldx, col0, ncols, P, ldp, cap);
+  else if (ct == 2) spmm_rows_kernel<2><<<grid, kBlock, lds_bytes, st>>>(a, X, ldx, col0, ncols, P, ldp, cap);
+  else spmm_rows_kernel<1><<<grid, kBlock, lds_bytes, st>>>(a, X, ldx, col0, ncols, P, ldp, cap);
   return hipGetLastError();
 }
+
+// Entries a row block holds at most: 2048, or a whole row of the widest possible kind.
+int sparse_row_block_cap(int cols) { return std::max(2048, cols); }
 
 hipError_t launch_spmm_t(const SparseArgs& a, const float* Z, int ldz, int col0, int ncols, float* partial, float* G,
                          hipStream_t st) {
