@@ -160,6 +160,16 @@ def tmm(target, Y: np.ndarray) -> np.ndarray:
     return out
 
 
+def rmm(target, X: np.ndarray) -> np.ndarray:
+    """Right multiply ``X T`` (Tab. 2, row ``XT``), float64, ``X`` is ``r_X x r_T``."""
+    tg = _as_target(target)
+    X64 = np.asarray(X, dtype=np.float64).reshape(-1, tg.r_T)
+    out = np.zeros((X64.shape[0], tg.c_T), dtype=np.float64)
+    for lo, hi in _chunks(tg.r_T):
+        out += X64[:, lo:hi] @ tg.rows64(lo, hi)
+    return out
+
+
 def crossprod(target) -> np.ndarray:
     """Gram matrix ``T^T T``, float64, full symmetric ``c_T x c_T``."""
     tg = _as_target(target)
@@ -341,6 +351,16 @@ def cover_counts(schema) -> np.ndarray:
 
 
 # ----------------------------------------------------------------------------- cost analysis (Sec. 3)
+def complexity_rmm(schema, r_X: int) -> Tuple[int, int]:
+    """Tab. 2 row ``X T``: (materialized, factorized) operation counts for a dense ``r_X x r_T`` operand:
+    ``r_X m_T + c_T m_X`` against ``sum_k (r_X m_k + c_k m_X)``."""
+    m_T = schema.r_T * schema.c_T
+    m_X = r_X * schema.r_T
+    mat = r_X * m_T + schema.c_T * m_X
+    fact = sum(r_X * s.D.shape[0] * s.D.shape[1] + s.D.shape[1] * m_X for s in schema.sources)
+    return mat, fact
+
+
 def complexity_lr(schema) -> Tuple[int, int]:
     """Sec. 3.1, linear regression with dense operands: ``(O_materialized, O_factorized)``.
     ``w`` is ``c_T x 1`` (``c_w = 1``, ``m_w = c_T``) and ``X = T w`` is ``r_T x 1`` (``m_X = r_T``):

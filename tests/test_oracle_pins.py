@@ -454,3 +454,24 @@ def test_complexity_ratio_grows_with_redundancy():
         return o_mat / o_fact
     assert ratio(10, 8) > ratio(100, 8) > ratio(500, 8)
     assert ratio(100, 40) > ratio(100, 8) > ratio(100, 2)
+
+
+# ----------------------------------------------------------------------------- right multiply (Tab. 2, row XT)
+def test_rmm_equals_dense_definition_and_transposed_tmm():
+    for seed in (61, 62):
+        sch = datagen.tiny_random_schema(seed, r_T=12, c_T=5, n=3)
+        T = oracle.brute_force_target(sch)
+        X = datagen.rng_for(seed + 100).standard_normal((4, 12))
+        np.testing.assert_allclose(oracle.rmm(sch, X), X @ T, rtol=1e-6, atol=1e-6)
+        np.testing.assert_allclose(oracle.rmm(sch, X), oracle.tmm(sch, X.T).T, rtol=1e-12, atol=1e-12)
+    # unit vectors pick rows of the table; a row of ones gives colSum
+    sch = datagen.tiny_random_schema(63, r_T=7, c_T=4, n=2)
+    E = np.eye(7)
+    np.testing.assert_allclose(oracle.rmm(sch, E), oracle.Target(sch).T32.astype(np.float64), rtol=0, atol=0)
+    np.testing.assert_allclose(oracle.rmm(sch, np.ones((1, 7)))[0], oracle.col_sum(sch), rtol=1e-12)
+
+
+def test_rmm_complexity_by_hand():
+    # S 6 x 2, R 3 x 4, T 6 x 6, X 5 x 6: materialized 5*36 + 6*30 = 360; factorized (5*12 + 2*30) + (5*12 + 4*30) = 300
+    sch = datagen.star_schema(datagen.rng_for(64), 6, 2, [(3, 4, "uniform")])
+    assert oracle.complexity_rmm(sch, 5) == (360, 300)
