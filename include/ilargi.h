@@ -106,6 +106,12 @@ ilargi_status_t ilargi_lmm(ilargi_plan_t* plan, const float* X, int64_t cx, floa
 ilargi_status_t ilargi_tmm(ilargi_plan_t* plan, const float* Y, int64_t cx, float* out,
                            ilargi_precision_t precision, void* stream);
 
+/* Right multiply (Tab. 2, row XT):  out = X T = (T^T X^T)^T.  X device cx x r_T, out device cx x c_T,
+ * 1 <= cx <= max_cx.  Uses the plan's residual buffer as scratch (like every call on a plan it must not
+ * overlap with another). */
+ilargi_status_t ilargi_rmm(ilargi_plan_t* plan, const float* X, int64_t cx, float* out,
+                           ilargi_precision_t precision, void* stream);
+
 /* Gram matrix  out = T^T T = sum_k sum_l M_k D_k^T (I_k^T I_l) D_l M_l^T, cross terms included.
  * out device c_T x c_T, both triangles written. */
 ilargi_status_t ilargi_crossprod(ilargi_plan_t* plan, float* out, void* stream);

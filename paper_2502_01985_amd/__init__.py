@@ -37,7 +37,7 @@ STATUS_NAMES = ["OK", "ERR_NULL", "ERR_SHAPE", "ERR_COLMAP", "ERR_INDEX_RANGE", 
 
 EXPORTED = [
     "ilargi_plan_workspace_bytes", "ilargi_plan_create", "ilargi_plan_destroy", "ilargi_lmm", "ilargi_tmm",
-    "ilargi_crossprod", "ilargi_materialize", "ilargi_gd_step", "ilargi_elementwise", "ilargi_row_sum",
+    "ilargi_rmm", "ilargi_crossprod", "ilargi_materialize", "ilargi_gd_step", "ilargi_elementwise", "ilargi_row_sum",
     "ilargi_col_sum", "ilargi_choose", "ilargi_segment_sum",
     "ilargi_plan_inverse_index", "ilargi_plan_trace_begin", "ilargi_plan_trace_label", "ilargi_plan_trace_end",
     "ilargi_plan_trace_name", "ilargi_stream_probe",
@@ -61,6 +61,7 @@ lib.ilargi_plan_create.argtypes = [_int, ctypes.POINTER(SourceStruct), _i64, _i6
 lib.ilargi_plan_destroy.argtypes = [_vp]
 lib.ilargi_lmm.argtypes = [_vp, _vp, _i64, _vp, _int, _vp]
 lib.ilargi_tmm.argtypes = [_vp, _vp, _i64, _vp, _int, _vp]
+lib.ilargi_rmm.argtypes = [_vp, _vp, _i64, _vp, _int, _vp]
 lib.ilargi_crossprod.argtypes = [_vp, _vp, _vp]
 lib.ilargi_materialize.argtypes = [_vp, _vp, _vp]
 lib.ilargi_gd_step.argtypes = [_vp, _int, _vp, _i64, _vp, _vp, _vp, _int, _vp]
@@ -263,6 +264,21 @@ def ilargi_tmm(plan: Plan, Y, out=None, precision: int = F32, stream=None):
         out = torch.empty((plan.c_T, cx), dtype=torch.float32, device=Y.device)
     _dev_f32(out, "out")
     _check(lib.ilargi_tmm(plan.handle, Y.data_ptr(), cx, out.data_ptr(), precision, _stream_ptr(stream)), "ilargi_tmm")
+    return out
+
+
+def ilargi_rmm(plan: Plan, X, out=None, precision: int = F32, stream=None):
+    """``X`` is ``cx x r_T``; returns ``X T`` (``cx x c_T``)."""
+    torch = _torch()
+    _dev_f32(X, "X")
+    cx = X.shape[0] if X.dim() == 2 else 1
+    if X.numel() != plan.r_T * cx:
+        raise TypeError("X must be cx x r_T")
+    if out is None:
+        out = torch.empty((cx, plan.c_T), dtype=torch.float32, device=plan.workspace.device)
+    _dev_f32(out, "out")
+    _check(lib.ilargi_rmm(plan.handle, X.data_ptr() if X.numel() else None, cx, out.data_ptr(), precision,
+                          _stream_ptr(stream)), "ilargi_rmm")
     return out
 
 

@@ -64,7 +64,7 @@ struct SourcePlan {
 };
 
 struct Layout {
-  size_t o_gslot = 0, o_gj0 = 0, o_ct_slot = 0, o_ct_j = 0, o_ones = 0, o_tmp_a = 0, o_tmp_b = 0;
+  size_t o_gslot = 0, o_gj0 = 0, o_ct_slot = 0, o_ct_j = 0, o_ones = 0, o_tmp_a = 0, o_tmp_b = 0, o_rmm = 0;
   int64_t max_entries = 0;       // most stored entries of a sparse source (0: every source is dense)
   size_t o_flags = 0, o_tcol_table = 0, o_pairs = 0, o_E = 0, o_loss = 0, o_sort = 0, o_hist = 0, o_zc = 0,
          o_gpartial = 0, o_blocks = 0;
@@ -174,6 +174,7 @@ ilargi_status_t make_layout(int n, const ilargi_source_t* s, int64_t r_T, int64_
   lay.o_ct_slot = take(sizeof(int32_t) * 2 * c_T);
   lay.o_ct_j = take(sizeof(int32_t) * 2 * c_T);
   lay.o_ones = take(sizeof(float) * c_T);
+  lay.o_rmm = take(sizeof(float) * c_T * max_cx);
   const int64_t wmax = std::max<int64_t>(max_cx, cmax);
   for (int k = 0; k < n; ++k) {
     SourcePlan& p = src[k];
@@ -1023,6 +1024,22 @@ ilargi_status_t ilargi_tmm(ilargi_plan_t* plan, const float* Y, int64_t cx, floa
     rc = tmm_pass(plan, Y, (int)cx, (int)col0, ncols, out, (int)cx, 0, nullptr, nullptr, 0, 0.0f, st);
     if (rc != ILARGI_OK) return rc;
   }
+  return ILARGI_OK;
+}
+
+ilargi_status_t ilargi_rmm(ilargi_plan_t* plan, const float* X, int64_t cx, float* out,
+                           ilargi_precision_t precision, void* stream) {
+  // X T = (T^T X^T)^T: a one-row operand is its own transpose; otherwise transpose in, multiply, transpose out
+  if (cx == 1) return ilargi_tmm(plan, X, 1, out, precision, stream);
+  ilargi_status_t rc = check_call(plan, out, X, cx, "rmm");
+  if (rc != ILARGI_OK) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  float* Xt = plan->at<float>(plan->lay.o_E);          // r_T x cx
+  float* Gt = plan->at<float>(plan->lay.o_rmm);        // c_T x cx
+  HIP_TRY(launch_transpose(X, cx, plan->r_T, Xt, st));
+  rc = ilargi_tmm(plan, Xt, cx, Gt, precision, stream);
+  if (rc != ILARGI_OK) return rc;
+  HIP_TRY(launch_transpose(Gt, plan->c_T, cx, out, st));
   return ILARGI_OK;
 }
 

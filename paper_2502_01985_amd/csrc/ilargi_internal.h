@@ -236,6 +236,7 @@ hipError_t launch_colasm(const ColAsmArgs& a, int mode, hipStream_t st);
 hipError_t launch_probe(int kind, float* dst, const float* src, int64_t n_floats, int blocks, hipStream_t st);
 hipError_t launch_fill_zero(float* p, int64_t n, hipStream_t st);
 hipError_t launch_fill(float* p, int64_t n, float v, hipStream_t st);
+hipError_t launch_transpose(const float* in, int64_t rows, int64_t cols, float* out, hipStream_t st);
 hipError_t launch_fanout(const int32_t* rowptr, int64_t rows, float* cnt, hipStream_t st);
 hipError_t launch_elementwise(int op, const float* in, float* out, int64_t n, float x, hipStream_t st);
 

@@ -2,6 +2,8 @@
 // sum_k m_k instead of m_T), and so does colSum(T) = sum_k M_k (D_k^T cnt_k) with cnt_k the fan-out of the
 // rows of source k (the column sums of I_k); rowSum(T) = T 1 is the left multiply by a vector of ones.
 // This file holds the streaming element-wise kernel and the small fills the two sums need.
+#include <algorithm>
+
 #include "ilargi_internal.h"
 
 namespace ilargi {
@@ -54,6 +56,29 @@ __global__ __launch_bounds__(kBlock) void fanout_kernel(const int32_t* __restric
     cnt[j] = (float)(rowptr[j + 1] - rowptr[j]);
 }
 
+// out (cols x rows) = in (rows x cols)^T through 32 x 33 LDS tiles: reads and writes are both coalesced.
+__global__ __launch_bounds__(kBlock) void transpose_kernel(const float* __restrict__ in, int64_t rows, int64_t cols,
+                                                           float* __restrict__ out) {
+  __shared__ float tile[32][33];
+  const int tx = threadIdx.x % 32, ty = threadIdx.x / 32;   // 32 x 8 threads
+  const int64_t tiles_c = (cols + 31) / 32, tiles_r = (rows + 31) / 32;
+  for (int64_t t = blockIdx.x; t < tiles_r * tiles_c; t += gridDim.x) {
+    const int64_t r0 = (t / tiles_c) * 32, c0 = (t % tiles_c) * 32;
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int64_t r = r0 + ty + 8 * k, c = c0 + tx;
+      tile[ty + 8 * k][tx] = (r < rows && c < cols) ? in[r * cols + c] : 0.0f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int64_t c = c0 + ty + 8 * k, r = r0 + tx;
+      if (c < cols && r < rows) out[c * rows + r] = tile[tx][ty + 8 * k];
+    }
+  }
+}
+
 int grid_for(int64_t n) {
   int64_t g = (n + kBlock - 1) / kBlock;
   return (int)(g < 1 ? 1 : (g > 8192 ? 8192 : g));
@@ -78,6 +103,13 @@ hipError_t launch_elementwise(int op, const float* in, float* out, int64_t n, fl
     case 9: elementwise_kernel<9><<<grid, kBlock, 0, st>>>(in, out, n, x, vec4); break;
     default: return hipErrorInvalidValue;
   }
+  return hipGetLastError();
+}
+
+hipError_t launch_transpose(const float* in, int64_t rows, int64_t cols, float* out, hipStream_t st) {
+  if (rows <= 0 || cols <= 0) return hipSuccess;
+  const int64_t tiles = ((rows + 31) / 32) * ((cols + 31) / 32);
+  transpose_kernel<<<(int)std::min<int64_t>(tiles, 16384), kBlock, 0, st>>>(in, rows, cols, out);
   return hipGetLastError();
 }
 

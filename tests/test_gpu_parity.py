@@ -795,3 +795,23 @@ def test_invalid_sparse_rows_are_reported(il):
         with pytest.raises(il.IlargiError) as ei:
             il.ilargi_plan_create([(bad, None, cm)], 2, 3, max_cx=1)
         assert ei.value.status == il.ERR_INDEX_RANGE
+
+
+# ------------------------------------------------------------------ right multiply (Tab. 2, row XT)
+@pytest.mark.parametrize("name", ["config0", "config1_small", "config3_small", "tiny_mixed", "odd_cols"])
+@pytest.mark.parametrize("cx", [1, 2, 5, 16, 17])
+def test_rmm(il, name, cx):
+    sch, tg, plan = get(il, name)
+    X = datagen.rng_for(1400 + cx).standard_normal((cx, sch.r_T)).astype(np.float32)
+    assert rel(il.ilargi_rmm(plan, dev(X)).cpu().numpy(), oracle.rmm(tg, X)) < OP_TOL
+
+
+def test_rmm_sparse_sources_and_wide_operand(il):
+    sch, tg, srcs, plan = _sparse_case(il, "config1_small", 0.8)
+    X = datagen.rng_for(1401).standard_normal((9, sch.r_T)).astype(np.float32)
+    assert rel(il.ilargi_rmm(plan, dev(X)).cpu().numpy(), oracle.rmm(tg, X)) < OP_TOL
+    sch, tg, plan = get(il, "config1_small", max_cx=256)
+    X = datagen.rng_for(1402).standard_normal((100, sch.r_T)).astype(np.float32)
+    assert rel(il.ilargi_rmm(plan, dev(X)).cpu().numpy(), oracle.rmm(tg, X)) < OP_TOL
+    e = rel(il.ilargi_rmm(plan, dev(X), precision=il.BF16_IN_F32_ACC).cpu().numpy(), oracle.rmm(tg, X))
+    assert e < BF16_TOL
