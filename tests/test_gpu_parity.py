@@ -815,3 +815,33 @@ def test_rmm_sparse_sources_and_wide_operand(il):
     assert rel(il.ilargi_rmm(plan, dev(X)).cpu().numpy(), oracle.rmm(tg, X)) < OP_TOL
     e = rel(il.ilargi_rmm(plan, dev(X), precision=il.BF16_IN_F32_ACC).cpu().numpy(), oracle.rmm(tg, X))
     assert e < BF16_TOL
+
+
+# ------------------------------------------------------------------ streams
+def test_calls_on_a_side_stream(il):
+    # everything a call enqueues goes to the stream it is given: results are right when the caller only
+    # synchronizes that stream, with unrelated work on the default stream in between
+    sch = datagen.config1(r_S=50_021, r_R=5_003, c_R=200)
+    tg = oracle.Target(sch)
+    side = torch.cuda.Stream()
+    rng = datagen.rng_for(1500)
+    X = dev(rng.standard_normal((sch.c_T, 3)).astype(np.float32))
+    Y = dev(rng.standard_normal((sch.r_T, 3)).astype(np.float32))
+    X64 = dev(rng.standard_normal((sch.c_T, 64)).astype(np.float32))
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        plan = il.ilargi_plan_create(il.schema_to_device(sch), sch.r_T, sch.c_T, max_cx=64)
+        noise = torch.randn(4096, 4096, device="cuda")
+        a = il.ilargi_lmm(plan, X)
+        b = il.ilargi_tmm(plan, Y)
+        c = il.ilargi_lmm(plan, X64)
+        g = il.ilargi_crossprod(plan)
+        t = il.ilargi_materialize(plan)
+    torch.cuda.default_stream().wait_stream(side)       # the default stream only orders itself after the side stream
+    _ = (noise @ noise).sum()
+    side.synchronize()
+    assert rel(a.cpu().numpy(), oracle.lmm(tg, X.cpu().numpy())) < OP_TOL
+    assert rel(b.cpu().numpy(), oracle.tmm(tg, Y.cpu().numpy())) < OP_TOL
+    assert rel(c.cpu().numpy(), oracle.lmm(tg, X64.cpu().numpy())) < OP_TOL
+    assert rel(g.cpu().numpy(), oracle.crossprod(tg)) < OP_TOL
+    assert np.array_equal(t.cpu().numpy(), tg.T32)
