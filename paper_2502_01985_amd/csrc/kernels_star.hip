@@ -258,7 +258,10 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(VEC4 ? (
           const int j = jS[row];                              // -1 beyond the batch
           const float yi = yS[row];
           ind[r] = j == li ? 1.0f : 0.0f;
-          if (fold && li >= 12) ind[r] = As[(size_t)row * lda + 16 * full + (li - 12)];
+          if (fold && li >= 12) {
+            ind[r] = As[(size_t)row * lda + 16 * full + (li - 12)];
+            if constexpr (BF16) ind[r] = (float)(__bf16)ind[r];
+          }
 #pragma unroll
           for (int nt = 0; nt < kNT; ++nt) {
             float o = 0.0f;
@@ -275,18 +278,19 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(VEC4 ? (
             ov[nt][r] = o;
           }
         }
-        // segment sums (unrounded residual), then S^T E
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-#pragma unroll
-          for (int nt = 0; nt < kNT; ++nt)
-            zacc[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(ind[r], ov[nt][r], zacc[nt], 0, 0, 0);
+        // segment sums, then S^T E.  With BF16 the residual is rounded once as it enters these two products
+        // (the segment sum is the product with the 0/1 indicator matrix: exact sums of the rounded values)
         if constexpr (BF16) {
 #pragma unroll
           for (int r = 0; r < 4; ++r)
 #pragma unroll
             for (int nt = 0; nt < kNT; ++nt) ov[nt][r] = (float)(__bf16)ov[nt][r];
         }
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+          for (int nt = 0; nt < kNT; ++nt)
+            zacc[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(ind[r], ov[nt][r], zacc[nt], 0, 0, 0);
         const float* acol = As + (size_t)(t * 16 + 4 * q) * lda + li;
 #pragma unroll
         for (int jt = 0; jt < JG; ++jt) {
@@ -422,7 +426,7 @@ hipError_t launch_gd_star(const StarArgs& a, int vec, int mode, bool bf16, int m
   const int jg = kp <= 32 ? 2 : 4;
   const int lda = kp + 4;
   const int tail = a.cs % 16;
-  const int fold = (!bf16 && tail >= 1 && tail <= 4) ? 1 : 0;   // see the kernel: 12-row tiles of R
+  const int fold = (tail >= 1 && tail <= 4) ? 1 : 0;   // see the kernel: 12-row tiles of R
   const int tr = fold ? 12 : 16;
   const int rtiles = (int)((a.r_R + tr - 1) / tr);
   const bool vec4 = vec == 4;
