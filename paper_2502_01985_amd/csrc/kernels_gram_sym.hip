@@ -135,14 +135,13 @@ bool gram_sym_supported(const TredArgs& a) {
 hipError_t launch_gram_sym(TredArgs& a, int64_t partial_floats, hipStream_t st, int* nchunks_out) {
   if (nchunks_out) *nchunks_out = 0;
   if (!gram_sym_supported(a) || a.n_rows <= 0) return hipErrorInvalidValue;
-  static int cus = 0;
-  if (cus == 0) {
+  static const int cus = [] {
     int dev = 0;
     hipDeviceProp_t prop;
-    cus = 256;
     if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess && prop.multiProcessorCount > 0)
-      cus = prop.multiProcessorCount;
-  }
+      return (int)prop.multiProcessorCount;
+    return 256;
+  }();
   int64_t nch = std::min<int64_t>(cus, partial_floats / ((int64_t)a.ca * a.cb));
   nch = std::max<int64_t>(1, std::min<int64_t>(nch, (a.n_rows + kGsRows - 1) / kGsRows));
   a.rows_per_block = ((a.n_rows + nch - 1) / nch + kGsRows - 1) / kGsRows * kGsRows;

@@ -9,6 +9,7 @@
 // stands for column 16 step + 4 q + e; the B operand comes from an LDS copy of X_k stored as [k / 4][n][k % 4]
 // so that the matching four values are again one 128-bit read.
 #include <algorithm>
+#include <mutex>
 
 #include "ilargi_internal.h"
 
@@ -405,6 +406,8 @@ MfmaFn pick_fused(bool vec4, int jg) {
 
 // Workgroups of this kernel and LDS size the device holds at once (cached: the query costs more than a launch).
 int resident_workgroups(MfmaFn fn, size_t lds_bytes) {
+  static std::mutex cache_mutex;   // the cache below is shared by every plan of the process
+  std::lock_guard<std::mutex> lock(cache_mutex);
   static int cus = 0;
   static MfmaFn seen_fn[128];
   static size_t seen_lds[128];

@@ -14,6 +14,7 @@
 //   Z     :  A = 1 where row 4 q + r joins row li of the tile of R, else 0  (so each sum is exact in float32).
 // Z overwrites P in place: a wavefront reads its P tile before it writes the same rows and columns of Z.
 #include <algorithm>
+#include <mutex>
 #include <type_traits>
 
 #include "ilargi_internal.h"
@@ -391,6 +392,8 @@ StarFn pick_star(bool vec4, int jg) {
 constexpr int kStarST = 32;
 
 int star_slots(StarFn fn, size_t lds_bytes) {
+  static std::mutex cache_mutex;   // the cache below is shared by every plan of the process
+  std::lock_guard<std::mutex> lock(cache_mutex);
   static int cus = 0;
   static StarFn seen_fn[32];
   static size_t seen_lds[32];

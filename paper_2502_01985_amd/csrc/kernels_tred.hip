@@ -13,6 +13,7 @@
 // Each wavefront owns a share of the rows and the full output tile; wavefronts and workgroups are combined
 // afterwards in a fixed order, so results are reproducible.
 #include <algorithm>
+#include <mutex>
 
 #include "ilargi_internal.h"
 
@@ -420,6 +421,8 @@ TredChoice tred_select(const TredArgs& a, bool bf16) {
 // (tiles the kernel skips for a symmetric result are not counted).  The caller sizes the row chunks so that
 // the launch fills the slots in whole rounds.
 void tred_occupancy(const TredArgs& a, bool bf16, int* slots, int* tiles) {
+  static std::mutex cache_mutex;   // the cache below is shared by every plan of the process
+  std::lock_guard<std::mutex> lock(cache_mutex);
   TredChoice c = tred_select(a, bf16);
   // both queries are cached: they cost far more than a launch
   static int cus = 0;
