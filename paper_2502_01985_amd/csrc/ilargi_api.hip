@@ -1211,12 +1211,37 @@ ilargi_status_t ilargi_crossprod(ilargi_plan_t* plan, float* out, void* stream) 
   auto run_gram = [&](TredArgs& g, float* block, int pair) -> ilargi_status_t {
     return run_tred(plan, g, block, "gram", pair, false, st);   // traced as gram:<k * n + l>
   };
+  // two-table star join with a narrow entity table listed first: S^T S and the rows of S summed per row of R
+  // (which the off-diagonal block needs) come from one pass over S in join order
+  bool star_done = false;
+  if (plan->star_k >= 0 && plan->fused < plan->star_k) {
+    const SourcePlan& f = plan->src[plan->fused];
+    const SourcePlan& d = plan->src[plan->star_k];
+    const int64_t max_grid = std::min<int64_t>(1024, plan->lay.gpartial_floats / std::max<int64_t>(f.cols * f.cols, 1));
+    if (gram_star_supported((int)f.cols) && d.rows * 2 <= plan->r_T && d.rows * f.cols <= plan->lay.zc_floats && max_grid >= 1) {
+      GramStarArgs ga;
+      memset(&ga, 0, sizeof(ga));
+      ga.S = f.D; ga.cs = (int)f.cols; ga.r_R = d.rows;
+      ga.rowptr = plan->at<int32_t>(d.o_rowptr); ga.perm = plan->at<int32_t>(d.o_perm); ga.idx = d.idx;
+      ga.ss_partial = plan->at<float>(plan->lay.o_gpartial);
+      ga.zc = zc;
+      int grid = 0;
+      {
+        TraceScope ts(plan, "gram_star", -1, st);
+        HIP_TRY(launch_gram_star(ga, f.vec, (int)max_grid, st, &grid));
+      }
+      HIP_TRY(launch_tred_reduce(ga.ss_partial, grid, f.cols * f.cols,
+                                 blocks + plan->block_off[(size_t)plan->fused * n + plan->fused], st));
+      star_done = true;
+    }
+  }
   for (int k = 0; k < n; ++k) {
     const SourcePlan& a = plan->src[k];
     if (a.empty) continue;
     for (int l = k; l < n; ++l) {
       const SourcePlan& b = plan->src[l];
       if (b.empty) continue;
+      if (star_done && k == plan->fused && l == k) continue;   // S^T S is done
       float* block = blocks + plan->block_off[(size_t)k * n + l];
       TredArgs g;
       memset(&g, 0, sizeof(g));
@@ -1238,7 +1263,7 @@ ilargi_status_t ilargi_crossprod(ilargi_plan_t* plan, float* out, void* stream) 
           s.Y = a.D; s.ldy = (int)a.cols; s.col0 = 0; s.ncols = (int)a.cols;
           s.gidx = a.ident ? nullptr : a.idx; s.g_rows = a.ident ? a.rows : -1;
           s.Z = zc; s.ldz = (int)a.cols; s.zcol0 = 0;
-          HIP_TRY(launch_segsum(s, st));
+          if (!(star_done && k == plan->fused && l == plan->star_k)) HIP_TRY(launch_segsum(s, st));   // else zc is ready
           g.A = zc; g.lda = (int)a.cols; g.ca = (int)a.cols; g.a_rows = b.rows;
           g.B = b.D; g.ldb = (int)b.cols; g.cb = (int)b.cols; g.b_rows = b.rows;
           g.n_rows = b.rows;

@@ -100,6 +100,18 @@ struct StarArgs {
   int ld_grad;
 };
 
+// The entity table's share of the Gram matrix of a two-table star join, one pass in join order
+// (kernels_gram_star.hip).
+struct GramStarArgs {
+  const float* S; int cs;            // r_T x cs, row i of S is target row i
+  int64_t r_R;                       // rows of the dimension table
+  const int32_t* rowptr;             // r_R + 1: inverse index of R (every target row joins one row)
+  const int32_t* perm;               // r_T
+  const int32_t* idx;                // r_T: row of R each target row joins
+  float* ss_partial;                 // [gridDim.x][cs][cs] partials of S^T S (upper-triangle 16 x 16 tiles)
+  float* zc;                         // r_R x cs: rows of S summed per row of R
+};
+
 struct SegArgs {
   const int32_t* rowptr;   // r_k + 1
   const int32_t* perm;     // nnz
@@ -227,6 +239,8 @@ hipError_t launch_finalize(const FinArgs& a, int c_T, int mode, hipStream_t st);
 hipError_t launch_materialize(const MatArgs& a, hipStream_t st);
 hipError_t launch_gram_assemble(const GramAsmPair* pairs_dev, int npairs, const int32_t* const* tcol2src_dev,
                                 int c_T, float* out, hipStream_t st);
+bool gram_star_supported(int cs);
+hipError_t launch_gram_star(const GramStarArgs& a, int vec, int max_grid, hipStream_t st, int* grid_out);
 bool gram_sym_supported(const TredArgs& a);
 hipError_t launch_gram_sym(TredArgs& a, int64_t partial_floats, hipStream_t st, int* nchunks_out);
 hipError_t launch_tred(const TredArgs& a, int nchunks, bool bf16, hipStream_t st);

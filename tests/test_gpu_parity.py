@@ -462,6 +462,27 @@ def test_crossprod_symmetric_block_of_a_wide_dimension_table(il, c_R):
     assert np.array_equal(G, G.T)
 
 
+@pytest.mark.parametrize("c_S,r_R,dist", [(1, 100, "uniform"), (5, 1_237, ("zipf", 1.3)), (16, 999, "uniform"),
+                                           (17, 1_601, ("zipf", 1.1)), (20, 2_000, "uniform"), (31, 17, "uniform"),
+                                           (32, 1_000, ("zipf", 1.2)), (33, 1_000, "uniform")])
+def test_crossprod_two_table_star_in_join_order(il, c_S, r_R, dist):
+    # entity tables of up to 32 columns give S^T S and the per-row sums of S from one pass in join order:
+    # one and two column tiles, unaligned rows (5, 17, 31), a ragged last tile of R, heavy keys spanning many
+    # batches, rows of R nobody joins; 33 columns fall back to the block-by-block path
+    rng = datagen.rng_for(1300 + c_S)
+    sch = datagen.star_schema(rng, 7_003, c_S, [(r_R, 24, dist)])
+    tg = oracle.Target(sch)
+    plan = il.ilargi_plan_create(il.schema_to_device(sch), sch.r_T, sch.c_T, max_cx=1)
+    G1 = il.ilargi_crossprod(plan).cpu().numpy()
+    il.ilargi_plan_trace_begin(plan, "*", 64)
+    G2 = il.ilargi_crossprod(plan).cpu().numpy()
+    _, names = il.ilargi_plan_trace_end(plan, 64, names=True)
+    assert rel(G1, oracle.crossprod(tg)) < OP_TOL
+    assert np.array_equal(G1, G1.T) and np.array_equal(G1, G2)
+    longest = np.bincount(sch.sources[1].row_idx, minlength=r_R).max()
+    assert any(n.startswith("gram_star") for n in names) == (c_S <= 32 and longest <= 2048), (names, longest)
+
+
 # ------------------------------------------------------------------ determinism and edge cases
 def test_results_are_bitwise_reproducible(il):
     sch, tg, plan = get(il, "config2_small")
