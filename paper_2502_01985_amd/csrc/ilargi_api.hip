@@ -87,6 +87,7 @@ struct ilargi_plan {
   bool cover_disjoint = false;  // no target column is fed by two sources
   bool cover_full = false;      // every target column is fed and every source reaches every target row
   bool mat_vec4 = false;  // the grouped column tables of the vectorized join-gather are valid
+  bool mat_flat = false;  // ... and every group is an aligned float4 of its source
   bool mat_cols = false;  // the per-column feeder tables (at most two feeders per column) are valid
   int npairs = 0;
   std::vector<size_t> block_off;  // offset (floats) of Gram block (k,l), k <= l, index k * n + l
@@ -847,7 +848,7 @@ ilargi_status_t ilargi_plan_create(int n, const ilargi_source_t* sources, int64_
   // join-gather tables: groups of four target columns fed by four consecutive columns of one source
   if (c_T % 4 == 0) {
     std::vector<int32_t> gslot((size_t)c_T / 4, -1), gj0((size_t)c_T / 4, 0);
-    bool regular = true;
+    bool regular = true, flat = true;
     for (int64_t g = 0; g < c_T / 4 && regular; ++g) {
       int slot = 0;
       for (int k = 0; k < n && regular; ++k) {
@@ -858,6 +859,7 @@ ilargi_status_t ilargi_plan_create(int n, const ilargi_source_t* sources, int64_
             tcol[k][4 * g + 2] == tcol[k][4 * g] + 2 && tcol[k][4 * g + 3] == tcol[k][4 * g] + 3) {
           gslot[g] = slot;
           gj0[g] = tcol[k][4 * g];
+          if (gj0[g] % 4 != 0 || pl->src[k].cols % 4 != 0 || reinterpret_cast<uintptr_t>(pl->src[k].D) % 16 != 0) flat = false;
         } else if (hits != 0) {
           regular = false;
         }
@@ -865,6 +867,7 @@ ilargi_status_t ilargi_plan_create(int n, const ilargi_source_t* sources, int64_
       }
     }
     pl->mat_vec4 = regular;
+    pl->mat_flat = regular && flat;
     if (regular) {
       HIP_TRY(hipMemcpyAsync(pl->at<int32_t>(lay.o_gslot), gslot.data(), sizeof(int32_t) * gslot.size(), hipMemcpyHostToDevice, st));
       HIP_TRY(hipMemcpyAsync(pl->at<int32_t>(lay.o_gj0), gj0.data(), sizeof(int32_t) * gj0.size(), hipMemcpyHostToDevice, st));
@@ -1191,6 +1194,7 @@ ilargi_status_t ilargi_materialize(ilargi_plan_t* plan, float* T, void* stream) 
   a.T = T; a.r_T = plan->r_T; a.c_T = (int)plan->c_T;
   a.gslot = plan->mat_vec4 ? plan->at<int32_t>(plan->lay.o_gslot) : nullptr;
   a.gj0 = plan->mat_vec4 ? plan->at<int32_t>(plan->lay.o_gj0) : nullptr;
+  a.flat_ok = plan->mat_flat ? 1 : 0;
   a.ct_slot = plan->mat_cols ? plan->at<int32_t>(plan->lay.o_ct_slot) : nullptr;
   a.ct_j = plan->mat_cols ? plan->at<int32_t>(plan->lay.o_ct_j) : nullptr;
   {

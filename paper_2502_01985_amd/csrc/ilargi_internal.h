@@ -174,6 +174,7 @@ struct MatArgs {
   // (-1: nobody) and its first source column; NULL when some group is fed irregularly
   const int32_t* gslot;
   const int32_t* gj0;
+  int flat_ok;   // every fed group is four 16-byte-aligned values of its source (tables narrower than 4096 columns)
   // optional tables for the column form: for target column t the (up to two) feeding source slots
   // ct_slot[2t], ct_slot[2t+1] (-1: none) in source order and their source columns ct_j[2t], ct_j[2t+1];
   // NULL when some column has more than two feeders

@@ -194,13 +194,96 @@ __global__ __launch_bounds__(kBlock) void materialize_vec4_kernel(MatArgs a) {
   }
 }
 
+// The same table written as one flat stream of float4: element e is column group e % (c_T / 4) of row
+// e / (c_T / 4).  A wavefront stores kFlatU runs of 64 consecutive float4, so every store instruction fills whole
+// 128-byte lines whatever the row length (880-byte rows otherwise leave partial lines at both ends of each row).
+// Needs every fed group to be four 16-byte-aligned source values (flat_ok).  The loop body has no branches: all
+// row indices of a step are requested, then all source values, then all stores go out; elements nobody feeds
+// read a dummy location and are replaced by zero.
+constexpr int kFlatU = 4;
+constexpr int kFlatMaxGroups = 1024;
+typedef const int32_t __attribute__((address_space(1)))* GIntPtr;
+typedef float mf4 __attribute__((ext_vector_type(4)));
+typedef const mf4 __attribute__((address_space(1)))* GVecPtr;
+
+__global__ __launch_bounds__(kBlock) void materialize_flat_kernel(MatArgs a, int64_t total) {
+  __shared__ const float* sD[kMaxSources];
+  __shared__ const int32_t* sIdx[kMaxSources];
+  __shared__ int64_t sRows[kMaxSources];
+  __shared__ int sCk[kMaxSources];
+  __shared__ short gS[kFlatMaxGroups];
+  __shared__ short gJ[kFlatMaxGroups];
+  const int ngroups = a.c_T / 4;
+  if (threadIdx.x < kMaxSources) {
+    int k = threadIdx.x;
+    sD[k] = k < a.n ? a.D[k] : nullptr;
+    sIdx[k] = k < a.n ? a.idx[k] : nullptr;
+    sRows[k] = k < a.n ? a.rows[k] : 0;
+    sCk[k] = k < a.n ? a.ck[k] : 0;
+  }
+  for (int g = threadIdx.x; g < ngroups; g += kBlock) { gS[g] = (short)a.gslot[g]; gJ[g] = (short)a.gj0[g]; }
+  __syncthreads();
+  const int lane = threadIdx.x % kWave;
+  const int32_t* dummy = a.gslot;                   // 16-byte aligned, at least four values long
+  constexpr int64_t kRun = (int64_t)kWave * kFlatU;
+  const int64_t wave0 = ((int64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave) * kRun;
+  const int64_t stride = (int64_t)gridDim.x * (kBlock / kWave) * kRun;
+  for (int64_t c0 = wave0; c0 < total; c0 += stride) {
+    const int64_t row0 = c0 / ngroups;
+    const unsigned g0 = (unsigned)(c0 - row0 * ngroups);
+    int64_t irow[kFlatU];
+    int slot[kFlatU], joff[kFlatU], ridx[kFlatU];
+    bool gathered[kFlatU];
+#pragma unroll
+    for (int u = 0; u < kFlatU; ++u) {
+      const unsigned off = g0 + lane + u * kWave;
+      const unsigned dr = off / (unsigned)ngroups;
+      const int g = (int)(off - dr * (unsigned)ngroups);
+      irow[u] = row0 + dr;
+      const bool live = c0 + lane + u * kWave < total;
+      slot[u] = live ? (int)gS[g] : -1;
+      joff[u] = gJ[g];
+      const int32_t* ip = slot[u] >= 0 ? sIdx[slot[u]] : nullptr;
+      gathered[u] = ip != nullptr;
+      ridx[u] = *(GIntPtr)(gathered[u] ? ip + irow[u] : dummy);
+    }
+    mf4 v[kFlatU];
+    bool fed[kFlatU];
+#pragma unroll
+    for (int u = 0; u < kFlatU; ++u) {
+      const int sl = max(slot[u], 0);
+      const int64_t r = gathered[u] ? (int64_t)ridx[u] : (irow[u] < sRows[sl] ? irow[u] : -1);
+      fed[u] = slot[u] >= 0 && r >= 0;
+      const float* src = fed[u] ? sD[sl] + r * sCk[sl] + joff[u] : reinterpret_cast<const float*>(dummy);
+      v[u] = *(GVecPtr)src;
+    }
+#pragma unroll
+    for (int u = 0; u < kFlatU; ++u) {
+      const int64_t e = c0 + lane + u * kWave;
+      if (e < total) {
+        // 0.0f + x: a source cell holding -0.0 becomes +0.0, as in the sum that defines the cell
+        mf4 o = {0.0f + v[u].x, 0.0f + v[u].y, 0.0f + v[u].z, 0.0f + v[u].w};
+        if (!fed[u]) o = (mf4){0.0f, 0.0f, 0.0f, 0.0f};
+        // the table is written once and not read back here: keep it out of the caches' way
+        __builtin_nontemporal_store(o, reinterpret_cast<mf4*>(a.T) + e);
+      }
+    }
+  }
+}
+
 }  // namespace
 
 hipError_t launch_materialize(const MatArgs& a, hipStream_t st) {
   if (a.r_T <= 0 || a.c_T <= 0) return hipSuccess;
   bool fast = a.gslot != nullptr && a.c_T % 4 == 0 && a.c_T <= 4 * kWave * kMatGroups &&
               reinterpret_cast<uintptr_t>(a.T) % 16 == 0;
-  if (fast) {
+  const int64_t total = a.r_T * (a.c_T / 4);
+  if (fast && a.flat_ok && a.c_T / 4 <= kFlatMaxGroups && reinterpret_cast<uintptr_t>(a.gslot) % 16 == 0) {
+    int64_t waves = (total + kWave * kFlatU - 1) / (kWave * kFlatU);
+    int64_t grid = (waves + (kBlock / kWave) - 1) / (kBlock / kWave);
+    if (grid > 65536) grid = 65536;
+    materialize_flat_kernel<<<(int)grid, kBlock, 0, st>>>(a, total);
+  } else if (fast) {
     int64_t waves = (a.r_T + kMatRows - 1) / kMatRows;
     int64_t grid = (waves + (kBlock / kWave) - 1) / (kBlock / kWave);
     if (grid > 65536) grid = 65536;

@@ -513,6 +513,36 @@ def test_rows_without_any_source_and_unmapped_columns(il):
     assert rel(il.ilargi_crossprod(plan).cpu().numpy(), oracle.crossprod(tg)) < OP_TOL
 
 
+@pytest.mark.parametrize("r_T", [1, 63, 10_007])
+def test_materialize_flat_stream_form(il, r_T):
+    # aligned groups of four columns take the form that writes the table as one stream of float4: groups nobody
+    # feeds (columns 0..3 and 28..31), an identity source shorter than the table, unmatched rows, a source column
+    # offset inside the group tables (second source maps its columns 4..11 only), cells holding -0.0, ragged tail
+    rng = datagen.rng_for(15 + r_T)
+    c_T = 32
+    n_a = max(1, (2 * r_T) // 3)
+    A = rng.standard_normal((n_a, 8)).astype(np.float32)
+    B = rng.standard_normal((37, 12)).astype(np.float32)
+    A[rng.random(A.shape) < 0.1] = -0.0
+    B[rng.random(B.shape) < 0.1] = -0.0
+    idx_a = np.full(r_T, -1, dtype=np.int32)
+    idx_a[:n_a] = np.arange(n_a)
+    idx_b = rng.integers(0, 37, r_T).astype(np.int32)
+    idx_b[rng.random(r_T) < 0.2] = -1
+    map_b = np.array([-1, -1, -1, -1] + list(range(16, 24)), dtype=np.int32)
+    sch = datagen.Schema([
+        datagen.Source(A, idx_a, np.arange(4, 12, dtype=np.int32)),
+        datagen.Source(B, idx_b, map_b),
+    ], r_T, c_T)
+    tg = oracle.Target(sch)
+    plan = il.ilargi_plan_create(il.schema_to_device(sch), r_T, c_T, max_cx=1)
+    il.ilargi_plan_trace_begin(plan, "*", 8)
+    T = il.ilargi_materialize(plan).cpu().numpy()
+    il.ilargi_plan_trace_end(plan, 8)
+    assert np.array_equal(T.view(np.uint32), tg.T32.view(np.uint32))
+    assert not np.any(np.signbit(T[T == 0]))
+
+
 def test_all_rows_unmatched_and_empty_sources(il):
     rng = datagen.rng_for(14)
     r_T, c_T = 300, 5
