@@ -39,12 +39,23 @@ Readings of the paper taken here (each is also listed in the design document):
   instead is a property this file does not use; the pins check when it holds (every target cell
   fed by exactly one source cell; for times and divide always).
 
+* KMeans and Gaussian NMF are named among the evaluated models (Sec. 5, Tab. 7-9) and defined nowhere in
+  the paper.  Read, for KMeans, one iteration of Lloyd's algorithm on the rows of the target table: every
+  row goes to the centroid at the smallest squared Euclidean distance (the first one among equals), every
+  centroid becomes the mean of its rows, a centroid without rows stays where it was.  Read, for Gaussian NMF,
+  one round of the multiplicative updates of Lee and Seung for ``min ||T - W H||_F^2`` over non-negative
+  factors: ``W <- W o (T H^T) / (W H H^T)``, then, with the new ``W``, ``H <- H o (W^T T) / (W^T W H)``
+  (``o`` and ``/`` element-wise; a denominator below ``GNMF_TINY`` is raised to it).
+
 Pins (tests/test_oracle_pins.py): brute force from Def. 1 / Def. 2 with dense 0/1 matrices on tiny
 schemas; the star-join special case ``T = [S | R[fk]]``; ``T I = T``; ``rowSum``/``colSum`` (Tab. 2);
 the adjoint identity; the weighted-Gram closed form of ``T^T T`` for a star join; the closed-form
 gradient-descent iterate through an eigendecomposition and its least-squares limit; ``ln 2`` and a
 finite-difference gradient for the logistic loss; ``bincount``/stable ``argsort`` for the inverse
-index.
+index; for KMeans the nearest-centroid and one-iteration routines of ``scipy.cluster.vq``, a loop over
+points and centroids on tiny inputs, the group means of well separated blobs and the monotone objective;
+for Gaussian NMF one iteration of scikit-learn's multiplicative-update solver, the fixed point at an
+exact factorization, an element-by-element loop on tiny inputs and the monotone objective.
 """
 from __future__ import annotations
 
@@ -388,3 +399,66 @@ def tuple_and_feature_ratio(schema) -> Tuple[float, float]:
     bc = sum(s.D.shape[1] for s in base)
     fr = sum(s.D.shape[1] for s in joined) / bc if bc else 0.0
     return tr, fr
+
+
+# ----------------------------------------------------------------------------- KMeans, Gaussian NMF (named in Sec. 5; see the readings above)
+GNMF_TINY = 1e-30
+
+
+def kmeans_distances(target, C: np.ndarray) -> np.ndarray:
+    """Squared Euclidean distance of every target row to every centroid; ``C`` is ``c_T x k``, column j = centroid j."""
+    tg = _as_target(target)
+    C64 = np.asarray(C, dtype=np.float64).reshape(tg.c_T, -1)
+    d2 = np.empty((tg.r_T, C64.shape[1]), dtype=np.float64)
+    for lo, hi in _chunks(tg.r_T):
+        blk = tg.rows64(lo, hi)
+        for j in range(C64.shape[1]):
+            diff = blk - C64[:, j][None, :]
+            d2[lo:hi, j] = np.sum(diff * diff, axis=1)
+    return d2
+
+
+def kmeans_step(target, C: np.ndarray):
+    """One Lloyd iteration.  Returns the new centroids (``c_T x k``), the assignment of every row (to the old
+    centroids), the cluster sizes and the sum of squared distances to the assigned old centroids."""
+    tg = _as_target(target)
+    C64 = np.asarray(C, dtype=np.float64).reshape(tg.c_T, -1)
+    k = C64.shape[1]
+    d2 = kmeans_distances(tg, C64)
+    assign = np.argmin(d2, axis=1).astype(np.int32)          # argmin returns the first of equal minima
+    counts = np.bincount(assign, minlength=k).astype(np.int64)
+    sums = np.zeros((tg.c_T, k), dtype=np.float64)
+    for lo, hi in _chunks(tg.r_T):
+        blk = tg.rows64(lo, hi)
+        for j in range(k):
+            sums[:, j] += blk[assign[lo:hi] == j].sum(axis=0)
+    C_new = C64.copy()
+    for j in range(k):
+        if counts[j] > 0:
+            C_new[:, j] = sums[:, j] / counts[j]
+    inertia = float(np.sum(d2[np.arange(tg.r_T), assign]))
+    return C_new, assign, counts, inertia
+
+
+def gnmf_objective(target, W: np.ndarray, H: np.ndarray) -> float:
+    """``||T - W H||_F^2 / 2`` for ``W`` (``r_T x r``) and ``H`` (``r x c_T``)."""
+    tg = _as_target(target)
+    W64 = np.asarray(W, dtype=np.float64)
+    H64 = np.asarray(H, dtype=np.float64)
+    total = 0.0
+    for lo, hi in _chunks(tg.r_T):
+        res = tg.rows64(lo, hi) - W64[lo:hi] @ H64
+        total += float(np.sum(res * res))
+    return 0.5 * total
+
+
+def gnmf_step(target, W: np.ndarray, H: np.ndarray):
+    """One round of multiplicative updates: first ``W`` (with the old ``H``), then ``H`` (with the new ``W``)."""
+    tg = _as_target(target)
+    W64 = np.asarray(W, dtype=np.float64).reshape(tg.r_T, -1)
+    H64 = np.asarray(H, dtype=np.float64).reshape(-1, tg.c_T)
+    TH = lmm(tg, H64.T)                                       # T H^T, r_T x r
+    W1 = W64 * TH / np.maximum(W64 @ (H64 @ H64.T), GNMF_TINY)
+    WtT = tmm(tg, W1).T                                       # W^T T, r x c_T
+    H1 = H64 * WtT / np.maximum((W1.T @ W1) @ H64, GNMF_TINY)
+    return W1, H1

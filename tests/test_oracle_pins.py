@@ -475,3 +475,174 @@ def test_rmm_complexity_by_hand():
     # S 6 x 2, R 3 x 4, T 6 x 6, X 5 x 6: materialized 5*36 + 6*30 = 360; factorized (5*12 + 2*30) + (5*12 + 4*30) = 300
     sch = datagen.star_schema(datagen.rng_for(64), 6, 2, [(3, 4, "uniform")])
     assert oracle.complexity_rmm(sch, 5) == (360, 300)
+
+
+# ------------------------------------------------------------------ KMeans (Lloyd iteration)
+def _blob_target(rng, n_per, centres, spread):
+    """Rows drawn around given centres (in order: n_per rows per centre); returns the target and the labels."""
+    k, c = centres.shape
+    rows = np.concatenate([centres[j] + spread * rng.standard_normal((n_per, c)) for j in range(k)]).astype(np.float32)
+    labels = np.repeat(np.arange(k), n_per)
+    order = rng.permutation(rows.shape[0])
+    return oracle.Target(table=rows[order]), labels[order]
+
+
+def test_kmeans_step_equals_a_loop_over_points_and_centroids():
+    sch = datagen.tiny_random_schema(31, r_T=23, c_T=5, n=3)
+    T = oracle.materialize(sch).astype(np.float64)           # the float32 table (pinned above), widened
+    rng = datagen.rng_for(310)
+    C = rng.standard_normal((5, 4))
+    want_assign, sums, cnt, inertia = [], [[0.0] * 5 for _ in range(4)], [0] * 4, 0.0
+    for i in range(23):
+        best, best_d = -1, None
+        for j in range(4):
+            d = sum((T[i][t] - C[t][j]) ** 2 for t in range(5))
+            if best_d is None or d < best_d:
+                best, best_d = j, d
+        want_assign.append(best)
+        cnt[best] += 1
+        inertia += best_d
+        for t in range(5):
+            sums[best][t] += T[i][t]
+    C_new, assign, counts, got_inertia = oracle.kmeans_step(oracle.Target(sch), C)
+    assert list(assign) == want_assign and list(counts) == cnt
+    for j in range(4):
+        for t in range(5):
+            want = sums[j][t] / cnt[j] if cnt[j] else C[t][j]
+            assert abs(C_new[t, j] - want) < 1e-12
+    assert abs(got_inertia - inertia) < 1e-9
+
+
+def test_kmeans_step_equals_scipy_vq_and_one_kmeans2_iteration():
+    from scipy.cluster.vq import kmeans2, vq
+    sch = datagen.config0(seed=5, r_S=3_000, r_R=300)
+    tg = oracle.Target(sch)
+    rng = datagen.rng_for(311)
+    C0 = tg.T32[rng.choice(tg.r_T, 7, replace=False)].astype(np.float64).T          # c_T x 7
+    C_new, assign, counts, inertia = oracle.kmeans_step(tg, C0)
+    labels, dist = vq(tg.T32.astype(np.float64), C0.T.copy())
+    assert np.array_equal(assign, labels)
+    np.testing.assert_allclose(inertia, np.sum(dist ** 2), rtol=1e-12)
+    centres, labels2 = kmeans2(tg.T32.astype(np.float64), C0.T.copy(), iter=1, minit="matrix")
+    assert np.array_equal(assign, labels2)
+    np.testing.assert_allclose(C_new, centres.T, rtol=1e-12, atol=1e-12)
+
+
+def test_kmeans_step_on_separated_blobs_returns_the_group_means_and_keeps_empty_clusters():
+    rng = datagen.rng_for(312)
+    centres = 50.0 * np.eye(4, 6)
+    tg, labels = _blob_target(rng, 200, centres, 0.5)
+    start = np.concatenate([centres + 1.0, np.full((1, 6), 1e3)]).T                  # a fifth centroid far away
+    C_new, assign, counts, _ = oracle.kmeans_step(tg, start)
+    assert np.array_equal(assign, labels) and list(counts) == [200, 200, 200, 200, 0]
+    for j in range(4):
+        np.testing.assert_allclose(C_new[:, j], tg.T32[labels == j].astype(np.float64).mean(axis=0), rtol=1e-13)
+    assert np.array_equal(C_new[:, 4], start[:, 4])
+    # at the group means a further step changes nothing
+    C_again, assign2, _, _ = oracle.kmeans_step(tg, C_new)
+    assert np.array_equal(assign2, labels)
+    np.testing.assert_allclose(C_again, C_new, rtol=1e-13)
+
+
+def test_kmeans_objective_never_increases_and_ties_go_to_the_first_centroid():
+    sch = datagen.config0(seed=6, r_S=2_000, r_R=100)
+    tg = oracle.Target(sch)
+    C = tg.T32[:5].astype(np.float64).T
+    last = np.inf
+    for _ in range(8):
+        C, _, _, inertia = oracle.kmeans_step(tg, C)
+        assert inertia <= last * (1 + 1e-12)
+        last = inertia
+    # two identical centroids: nobody chooses the second
+    dup = np.concatenate([C[:, :1], C[:, :1], C[:, 1:]], axis=1)
+    _, assign, counts, _ = oracle.kmeans_step(tg, dup)
+    assert counts[1] == 0 and not np.any(assign == 1)
+
+
+def test_kmeans_distances_expand_into_norms_and_a_left_multiply():
+    # |t - c|^2 = |t|^2 - 2 t.c + |c|^2 : the form that turns the assignment into T C
+    sch = datagen.tiny_random_schema(33, r_T=40, c_T=6, n=3)
+    tg = oracle.Target(sch)
+    C = datagen.rng_for(313).standard_normal((6, 3))
+    T = tg.T32.astype(np.float64)
+    want = (T ** 2).sum(axis=1)[:, None] - 2.0 * oracle.lmm(tg, C) + (C ** 2).sum(axis=0)[None, :]
+    np.testing.assert_allclose(oracle.kmeans_distances(tg, C), want, rtol=1e-12, atol=1e-12)
+
+
+# ------------------------------------------------------------------ Gaussian NMF (multiplicative updates)
+def _nonneg_target(seed, r_T=300, c_T=12):
+    rng = datagen.rng_for(seed)
+    return oracle.Target(table=np.abs(rng.standard_normal((r_T, c_T))).astype(np.float32)), rng
+
+
+def test_gnmf_step_equals_one_iteration_of_sklearn_multiplicative_update():
+    import warnings
+    from sklearn.decomposition import NMF
+    tg, rng = _nonneg_target(320)
+    W0, H0 = rng.random((tg.r_T, 4)) + 0.1, rng.random((4, tg.c_T)) + 0.1
+    model = NMF(n_components=4, init="custom", solver="mu", beta_loss="frobenius", max_iter=1, tol=0.0)
+    with warnings.catch_warnings():
+        warnings.simplefilter("ignore")
+        W_lib = model.fit_transform(tg.T32.astype(np.float64), W=W0.copy(), H=H0.copy())
+    W1, H1 = oracle.gnmf_step(tg, W0, H0)
+    np.testing.assert_allclose(W1, W_lib, rtol=1e-12)
+    np.testing.assert_allclose(H1, model.components_, rtol=1e-12)
+
+
+def test_gnmf_step_element_by_element():
+    tg, rng = _nonneg_target(321, r_T=7, c_T=5)
+    T = tg.T32.astype(np.float64)
+    W, H = rng.random((7, 2)) + 0.1, rng.random((2, 5)) + 0.1
+    W1 = np.empty_like(W)
+    for i in range(7):
+        for a in range(2):
+            num = sum(T[i, t] * H[a, t] for t in range(5))
+            den = sum(W[i, b] * sum(H[b, t] * H[a, t] for t in range(5)) for b in range(2))
+            W1[i, a] = W[i, a] * num / den
+    H1 = np.empty_like(H)
+    for a in range(2):
+        for t in range(5):
+            num = sum(W1[i, a] * T[i, t] for i in range(7))
+            den = sum(sum(W1[i, a] * W1[i, b] for i in range(7)) * H[b, t] for b in range(2))
+            H1[a, t] = H[a, t] * num / den
+    got_W, got_H = oracle.gnmf_step(tg, W, H)
+    np.testing.assert_allclose(got_W, W1, rtol=1e-12)
+    np.testing.assert_allclose(got_H, H1, rtol=1e-12)
+
+
+def test_gnmf_exact_factorization_is_a_fixed_point():
+    rng = datagen.rng_for(322)
+    W = rng.integers(1, 5, (60, 3)).astype(np.float64)
+    H = rng.integers(1, 5, (3, 9)).astype(np.float64)
+    tg = oracle.Target(table=(W @ H).astype(np.float32))                             # small integers: exact
+    W1, H1 = oracle.gnmf_step(tg, W, H)
+    np.testing.assert_allclose(W1, W, rtol=1e-13)
+    np.testing.assert_allclose(H1, H, rtol=1e-13)
+    assert oracle.gnmf_objective(tg, W, H) == 0.0
+
+
+def test_gnmf_objective_never_increases_and_factors_stay_nonnegative():
+    sch = datagen.config0(seed=7, r_S=1_500, r_R=150)
+    for s in sch.sources:
+        s.D[...] = np.abs(s.D)
+    tg = oracle.Target(sch)
+    rng = datagen.rng_for(323)
+    W, H = rng.random((tg.r_T, 5)), rng.random((5, tg.c_T))
+    last = oracle.gnmf_objective(tg, W, H)
+    for _ in range(15):
+        W, H = oracle.gnmf_step(tg, W, H)
+        now = oracle.gnmf_objective(tg, W, H)
+        assert now <= last * (1 + 1e-12) and W.min() >= 0.0 and H.min() >= 0.0
+        last = now
+    T = tg.T32.astype(np.float64)
+    np.testing.assert_allclose(oracle.gnmf_objective(tg, W, H), 0.5 * np.linalg.norm(T - W @ H) ** 2, rtol=1e-12)
+
+
+def test_gnmf_zero_rows_and_columns_stay_zero_without_dividing_by_zero():
+    tg, rng = _nonneg_target(324, r_T=30, c_T=6)
+    W, H = rng.random((30, 3)), rng.random((3, 6))
+    W[4] = 0.0
+    H[:, 2] = 0.0
+    W1, H1 = oracle.gnmf_step(tg, W, H)
+    assert np.all(np.isfinite(W1)) and np.all(np.isfinite(H1))
+    assert np.all(W1[4] == 0.0) and np.all(H1[:, 2] == 0.0)
