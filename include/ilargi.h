@@ -132,6 +132,28 @@ ilargi_status_t ilargi_gd_step(ilargi_plan_t* plan, ilargi_model_t model, float*
                                const float* y, const float* lr, float* loss,
                                ilargi_precision_t precision, void* stream);
 
+/* One Lloyd iteration of KMeans over the rows of T without materializing it (KMeans is one of the models
+ * evaluated in Sec. 5, Tab. 7-9; the paper prints no algorithm for it, this is the textbook one):
+ *   a_i = argmin_j ||t_i - c_j||^2  taken as  argmin_j (||c_j||^2 - 2 (T C)_ij),  the first j among equals,
+ *   c_j <- mean of the rows with a_i = j  =  (T^T A)_j / n_j  with A the 0/1 assignment matrix;
+ *   a centroid without rows keeps its place.
+ * C device c_T x k in/out (column j is centroid j), 1 <= k <= min(max_cx, 256); assign (optional) device
+ * int32[r_T] receives a_i (with respect to the centroids the call started from); counts (optional) device
+ * int32[k] receives n_j.  Values must be finite.  Uses the plan's residual buffer as scratch.
+ * Errors: NULL, SHAPE, WORKSPACE, UNSUPPORTED (k > 256). */
+ilargi_status_t ilargi_kmeans_step(ilargi_plan_t* plan, float* C, int64_t k, int32_t* assign, int32_t* counts,
+                                   void* stream);
+
+/* One round of multiplicative updates of Gaussian NMF, T ~ W H with non-negative factors (Gaussian NMF is one
+ * of the models evaluated in Sec. 5, Tab. 7-9; the paper prints no algorithm, these are the updates of Lee and
+ * Seung for the squared Frobenius error):
+ *   W <- W o (T H^T) (/) max(W (H H^T), 1e-30)          (left multiply by H^T),
+ *   H <- H o (W^T T) (/) max((W^T W) H, 1e-30)          (transposed multiply by the new W).
+ * W device r_T x r in/out; Ht device c_T x r in/out holds H transposed (row t is column t of H);
+ * 1 <= r <= min(max_cx, 64).  Uses the plan's residual buffer as scratch.
+ * Errors: NULL, SHAPE, WORKSPACE, UNSUPPORTED (r > 64). */
+ilargi_status_t ilargi_gnmf_step(ilargi_plan_t* plan, float* W, float* Ht, int64_t r, void* stream);
+
 /* Element-wise operators of Tab. 2 (first two rows): arithmetic with a scalar, T (/) x, and functions f(T). */
 typedef enum {
   ILARGI_OP_MUL = 0,    /* t * x */

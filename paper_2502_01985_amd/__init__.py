@@ -37,7 +37,8 @@ STATUS_NAMES = ["OK", "ERR_NULL", "ERR_SHAPE", "ERR_COLMAP", "ERR_INDEX_RANGE", 
 
 EXPORTED = [
     "ilargi_plan_workspace_bytes", "ilargi_plan_create", "ilargi_plan_destroy", "ilargi_lmm", "ilargi_tmm",
-    "ilargi_rmm", "ilargi_crossprod", "ilargi_materialize", "ilargi_gd_step", "ilargi_elementwise", "ilargi_row_sum",
+    "ilargi_rmm", "ilargi_crossprod", "ilargi_materialize", "ilargi_gd_step", "ilargi_kmeans_step", "ilargi_gnmf_step",
+    "ilargi_elementwise", "ilargi_row_sum",
     "ilargi_col_sum", "ilargi_choose", "ilargi_segment_sum",
     "ilargi_plan_inverse_index", "ilargi_plan_trace_begin", "ilargi_plan_trace_label", "ilargi_plan_trace_end",
     "ilargi_plan_trace_name", "ilargi_stream_probe",
@@ -65,6 +66,8 @@ lib.ilargi_rmm.argtypes = [_vp, _vp, _i64, _vp, _int, _vp]
 lib.ilargi_crossprod.argtypes = [_vp, _vp, _vp]
 lib.ilargi_materialize.argtypes = [_vp, _vp, _vp]
 lib.ilargi_gd_step.argtypes = [_vp, _int, _vp, _i64, _vp, _vp, _vp, _int, _vp]
+lib.ilargi_kmeans_step.argtypes = [_vp, _vp, _i64, _vp, _vp, _vp]
+lib.ilargi_gnmf_step.argtypes = [_vp, _vp, _vp, _i64, _vp]
 lib.ilargi_segment_sum.argtypes = [_vp, _int, _vp, _i64, _vp, _vp]
 lib.ilargi_elementwise.argtypes = [_vp, _int, ctypes.c_float, _vp, _vp]
 lib.ilargi_row_sum.argtypes = [_vp, _vp, _vp]
@@ -280,6 +283,46 @@ def ilargi_rmm(plan: Plan, X, out=None, precision: int = F32, stream=None):
     _check(lib.ilargi_rmm(plan.handle, X.data_ptr() if X.numel() else None, cx, out.data_ptr(), precision,
                           _stream_ptr(stream)), "ilargi_rmm")
     return out
+
+
+def _dev_i32(t, name):
+    torch = _torch()
+    if t.dtype != torch.int32 or not t.is_cuda or not t.is_contiguous():
+        raise TypeError(f"{name} must be a contiguous int32 device tensor")
+
+
+def ilargi_kmeans_step(plan: Plan, C, assign=None, counts=None, stream=None):
+    """One Lloyd iteration; ``C`` (``c_T x k``, column j = centroid j) is updated in place.
+    ``assign`` (int32[r_T]) and ``counts`` (int32[k]) are optional outputs."""
+    _dev_f32(C, "C")
+    k = C.shape[1] if C.dim() == 2 else 1
+    if C.numel() != plan.c_T * k:
+        raise TypeError("C must be c_T x k")
+    if assign is not None:
+        _dev_i32(assign, "assign")
+        if assign.numel() != plan.r_T:
+            raise TypeError("assign must hold r_T values")
+    if counts is not None:
+        _dev_i32(counts, "counts")
+        if counts.numel() != k:
+            raise TypeError("counts must hold k values")
+    _check(lib.ilargi_kmeans_step(plan.handle, C.data_ptr(), k,
+                                  assign.data_ptr() if assign is not None and assign.numel() else None,
+                                  counts.data_ptr() if counts is not None else None, _stream_ptr(stream)),
+           "ilargi_kmeans_step")
+    return C
+
+
+def ilargi_gnmf_step(plan: Plan, W, Ht, stream=None):
+    """One round of multiplicative updates; ``W`` (``r_T x r``) and ``Ht`` (``c_T x r``, the transpose of H)
+    are updated in place."""
+    _dev_f32(W, "W"); _dev_f32(Ht, "Ht")
+    r = Ht.shape[1] if Ht.dim() == 2 else 1
+    if Ht.numel() != plan.c_T * r or W.numel() != plan.r_T * r:
+        raise TypeError("W must be r_T x r and Ht c_T x r")
+    _check(lib.ilargi_gnmf_step(plan.handle, W.data_ptr() if W.numel() else None, Ht.data_ptr(), r,
+                                _stream_ptr(stream)), "ilargi_gnmf_step")
+    return W, Ht
 
 
 def ilargi_crossprod(plan: Plan, out=None, stream=None):

@@ -65,6 +65,7 @@ struct SourcePlan {
 
 struct Layout {
   size_t o_gslot = 0, o_gj0 = 0, o_ct_slot = 0, o_ct_j = 0, o_ones = 0, o_tmp_a = 0, o_tmp_b = 0, o_rmm = 0;
+  size_t o_cn = 0, o_counts = 0, o_rr = 0;   // KMeans / NMF: centroid norms, cluster sizes, two small square matrices
   int64_t max_entries = 0;       // most stored entries of a sparse source (0: every source is dense)
   size_t o_flags = 0, o_tcol_table = 0, o_pairs = 0, o_E = 0, o_loss = 0, o_sort = 0, o_hist = 0, o_zc = 0,
          o_gpartial = 0, o_blocks = 0;
@@ -176,6 +177,9 @@ ilargi_status_t make_layout(int n, const ilargi_source_t* s, int64_t r_T, int64_
   lay.o_ct_j = take(sizeof(int32_t) * 2 * c_T);
   lay.o_ones = take(sizeof(float) * c_T);
   lay.o_rmm = take(sizeof(float) * c_T * max_cx);
+  lay.o_cn = take(sizeof(float) * max_cx);
+  lay.o_counts = take(sizeof(int32_t) * max_cx);
+  lay.o_rr = take(sizeof(float) * 2 * kGnmfMaxRank * kGnmfMaxRank);
   const int64_t wmax = std::max<int64_t>(max_cx, cmax);
   for (int k = 0; k < n; ++k) {
     SourcePlan& p = src[k];
@@ -1083,6 +1087,81 @@ ilargi_status_t ilargi_gd_step(ilargi_plan_t* plan, ilargi_model_t model, float*
                   fusedg ? plan->fused : -1, loss_grid);
     if (rc != ILARGI_OK) return rc;
   }
+  return ILARGI_OK;
+}
+
+ilargi_status_t ilargi_kmeans_step(ilargi_plan_t* plan, float* C, int64_t k, int32_t* assign, int32_t* counts,
+                                   void* stream) {
+  if (plan == nullptr) return fail(ILARGI_ERR_NULL, "kmeans_step: plan is NULL");
+  if (C == nullptr) return fail(ILARGI_ERR_NULL, "kmeans_step: C is NULL");
+  if (k < 1) return fail(ILARGI_ERR_SHAPE, "kmeans_step: %lld centroids", (long long)k);
+  if (k > plan->max_cx)
+    return fail(ILARGI_ERR_WORKSPACE, "kmeans_step: %lld centroids but the plan was sized for %lld operand columns",
+                (long long)k, (long long)plan->max_cx);
+  if (k > kKmeansMaxK) return fail(ILARGI_ERR_UNSUPPORTED, "kmeans_step: more than %d centroids", kKmeansMaxK);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  float* P = plan->at<float>(plan->lay.o_E);            // r_T x k: T C, then the assignment matrix
+  float* G = plan->at<float>(plan->lay.o_rmm);          // c_T x k: per-cluster sums
+  float* cn = plan->at<float>(plan->lay.o_cn);
+  int32_t* cnt = plan->at<int32_t>(plan->lay.o_counts);
+  HIP_TRY(launch_fill_zero(reinterpret_cast<float*>(cnt), k, st));   // all-zero bits are the integer 0
+  if (plan->r_T > 0) {
+    {
+      TraceScope ts(plan, "centroid_norm", -1, st);
+      HIP_TRY(launch_centroid_norm(C, plan->c_T, (int)k, cn, st));
+    }
+    ilargi_status_t rc = ilargi_lmm(plan, C, k, P, ILARGI_F32, stream);
+    if (rc != ILARGI_OK) return rc;
+    {
+      TraceScope ts(plan, "kmeans_assign", -1, st);
+      HIP_TRY(launch_kmeans_assign(P, cn, plan->r_T, (int)k, assign, cnt, st));
+    }
+    rc = ilargi_tmm(plan, P, k, G, ILARGI_F32, stream);
+    if (rc != ILARGI_OK) return rc;
+  }
+  TraceScope ts(plan, "kmeans_update", -1, st);
+  HIP_TRY(launch_kmeans_update(C, G, cnt, plan->c_T, (int)k, counts, st));
+  return ILARGI_OK;
+}
+
+ilargi_status_t ilargi_gnmf_step(ilargi_plan_t* plan, float* W, float* Ht, int64_t r, void* stream) {
+  ilargi_status_t rc = check_call(plan, Ht, W, r, "gnmf_step");
+  if (rc != ILARGI_OK) return rc;
+  if (r > kGnmfMaxRank) return fail(ILARGI_ERR_UNSUPPORTED, "gnmf_step: rank above %d", kGnmfMaxRank);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  float* P = plan->at<float>(plan->lay.o_E);            // r_T x r: T H^T
+  float* G = plan->at<float>(plan->lay.o_rmm);          // c_T x r: T^T W
+  float* HHt = plan->at<float>(plan->lay.o_rr);
+  float* WtW = HHt + kGnmfMaxRank * kGnmfMaxRank;
+  const float tiny = 1e-30f;
+  auto small_gram = [&](const float* A, int64_t rows, float* out, const char* tag) -> ilargi_status_t {
+    // out (r x r) = A^T A for a rows x r matrix, chunk sums added in order
+    if (rows <= 0) { HIP_TRY(launch_fill_zero(out, r * r, st)); return ILARGI_OK; }
+    TredArgs g;
+    memset(&g, 0, sizeof(g));
+    g.A = A; g.lda = (int)r; g.ca = (int)r; g.a_rows = rows;
+    g.B = A; g.ldb = (int)r; g.cb = (int)r; g.b_rows = rows;
+    g.n_rows = rows;
+    return run_tred(plan, g, out, tag, -1, false, st);
+  };
+  rc = small_gram(Ht, plan->c_T, HHt, "gnmf_hht");
+  if (rc != ILARGI_OK) return rc;
+  if (plan->r_T > 0) {
+    rc = ilargi_lmm(plan, Ht, r, P, ILARGI_F32, stream);
+    if (rc != ILARGI_OK) return rc;
+    TraceScope ts(plan, "gnmf_update", 0, st);
+    HIP_TRY(launch_gnmf_update(W, P, HHt, plan->r_T, (int)r, tiny, st));
+  }
+  rc = small_gram(W, plan->r_T, WtW, "gnmf_wtw");
+  if (rc != ILARGI_OK) return rc;
+  if (plan->r_T > 0) {
+    rc = ilargi_tmm(plan, W, r, G, ILARGI_F32, stream);
+    if (rc != ILARGI_OK) return rc;
+  } else {
+    HIP_TRY(launch_fill_zero(G, plan->c_T * r, st));
+  }
+  TraceScope ts(plan, "gnmf_update", 1, st);
+  HIP_TRY(launch_gnmf_update(Ht, G, WtW, plan->c_T, (int)r, tiny, st));
   return ILARGI_OK;
 }
 

@@ -254,6 +254,15 @@ hipError_t launch_fill(float* p, int64_t n, float v, hipStream_t st);
 hipError_t launch_transpose(const float* in, int64_t rows, int64_t cols, float* out, hipStream_t st);
 hipError_t launch_fanout(const int32_t* rowptr, int64_t rows, float* cnt, hipStream_t st);
 hipError_t launch_elementwise(int op, const float* in, float* out, int64_t n, float x, hipStream_t st);
+// KMeans / Gaussian NMF row-local steps (kernels_models.hip)
+constexpr int kKmeansMaxK = 256;
+constexpr int kGnmfMaxRank = 64;
+hipError_t launch_centroid_norm(const float* C, int64_t c_T, int k, float* cn, hipStream_t st);
+hipError_t launch_kmeans_assign(float* P, const float* cn, int64_t r_T, int k, int32_t* assign, int32_t* counts,
+                                hipStream_t st);
+hipError_t launch_kmeans_update(float* C, const float* G, const int32_t* counts, int64_t c_T, int k,
+                                int32_t* counts_out, hipStream_t st);
+hipError_t launch_gnmf_update(float* X, const float* P, const float* Q, int64_t rows, int k, float tiny, hipStream_t st);
 
 inline int ilog2_ceil(int64_t v) { int l = 0; while ((1ll << l) < v) ++l; return l; }
 
