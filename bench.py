@@ -261,6 +261,41 @@ def scalar_ops(il, torch, plan, mplan, sch):
     return out
 
 
+def unsupervised(il, torch, plan, mplan, sch, k=10):
+    """KMeans (one Lloyd iteration, k centroids) and Gaussian NMF (one round of multiplicative updates, rank k) on
+    the same schema, factorized vs the same entry points on the materialized table, with the factorized
+    iteration's kernels listed.  Timing only: the factors start from random positive values."""
+    g = torch.Generator(device="cuda").manual_seed(7)
+    C0 = torch.randn((sch.c_T, k), device="cuda", generator=g)
+    W0 = torch.rand((sch.r_T, k), device="cuda", generator=g) + 0.05
+    H0 = torch.rand((sch.c_T, k), device="cuda", generator=g) + 0.05
+    assign = torch.empty(sch.r_T, dtype=torch.int32, device="cuda")
+    counts = torch.empty(k, dtype=torch.int32, device="cuda")
+    out = {"k": k}
+
+    def kmeans(pl):
+        C = C0.clone()
+        return lambda: il.ilargi_kmeans_step(pl, C, assign, counts)
+
+    def gnmf(pl):
+        W, Ht = W0.clone(), H0.clone()
+        return lambda: il.ilargi_gnmf_step(pl, W, Ht)
+
+    for name, make in (("kmeans", kmeans), ("gnmf", gnmf)):
+        t_f = time_loop(torch, make(plan), 20)
+        t_m = time_loop(torch, make(mplan), 10)
+        fn = make(plan)
+        fn()
+        il.ilargi_plan_trace_begin(plan, "*", 64)
+        fn()
+        ms, names = il.ilargi_plan_trace_end(plan, 64, names=True)
+        out[name] = {"factorized_it_per_s": round(1.0 / t_f, 1), "materialized_it_per_s": round(1.0 / t_m, 1),
+                     "factorized_us": round(t_f * 1e6, 1), "materialized_us": round(t_m * 1e6, 1),
+                     "speedup": round(t_m / t_f, 2),
+                     "kernels_us": {f"{i}:{n}": round(float(v) * 1e3, 1) for i, (n, v) in enumerate(zip(names, ms))}}
+    return out
+
+
 def sparse_tables(il, torch, datagen, dev):
     """Source tables kept in compressed sparse rows (Sec. 3.1; sparsity sweep of Tab. 4) on the config-1 centre
     schema with a fraction p of the cells set to zero: one gradient-descent iteration and the one-column
@@ -533,6 +568,7 @@ def main() -> int:
         mat_ops[f"lmm_c{c}_us"] = round(time_loop(torch, lambda: il.ilargi_lmm(mplan, X, o1), 10) * 1e6, 1)
         mat_ops[f"tmm_c{c}_us"] = round(time_loop(torch, lambda: il.ilargi_tmm(mplan, Y, o2), 10) * 1e6, 1)
     scalar = scalar_ops(il, torch, plan, mplan, sch)
+    models = unsupervised(il, torch, plan, mplan, sch)
     del mplan
 
     probe = stream_probe(il, torch)
@@ -584,6 +620,7 @@ def main() -> int:
         "kernels": dict(sorted(kernels.items(), key=lambda kv: -kv[1]["us_per_step"])[:16]),
         "stream_probe": probe,
         "scalar_ops": scalar,
+        "kmeans_gnmf": models,
         "sparse_tables": sparse,
         "chooser": chooser_summary(records),
         "wide_batch": wide,

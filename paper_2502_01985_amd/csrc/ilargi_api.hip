@@ -1114,7 +1114,8 @@ ilargi_status_t ilargi_kmeans_step(ilargi_plan_t* plan, float* C, int64_t k, int
     if (rc != ILARGI_OK) return rc;
     {
       TraceScope ts(plan, "kmeans_assign", -1, st);
-      HIP_TRY(launch_kmeans_assign(P, cn, plan->r_T, (int)k, assign, cnt, st));
+      HIP_TRY(launch_kmeans_assign(P, cn, plan->r_T, (int)k, assign, plan->at<int32_t>(plan->lay.o_loss),
+                                   std::max<int64_t>(32768 * kNarrowCT, 1024 * plan->max_cx), cnt, st));
     }
     rc = ilargi_tmm(plan, P, k, G, ILARGI_F32, stream);
     if (rc != ILARGI_OK) return rc;
@@ -1149,11 +1150,17 @@ ilargi_status_t ilargi_gnmf_step(ilargi_plan_t* plan, float* W, float* Ht, int64
   if (plan->r_T > 0) {
     rc = ilargi_lmm(plan, Ht, r, P, ILARGI_F32, stream);
     if (rc != ILARGI_OK) return rc;
-    TraceScope ts(plan, "gnmf_update", 0, st);
-    HIP_TRY(launch_gnmf_update(W, P, HHt, plan->r_T, (int)r, tiny, st));
+    // the update also leaves each workgroup's share of W_new^T W_new, added here in workgroup order
+    float* part = plan->at<float>(plan->lay.o_gpartial);
+    int nparts = 0;
+    {
+      TraceScope ts(plan, "gnmf_update", 0, st);
+      HIP_TRY(launch_gnmf_update(W, P, HHt, plan->r_T, (int)r, tiny, part, plan->lay.gpartial_floats, &nparts, st));
+    }
+    HIP_TRY(launch_tred_reduce(part, nparts, r * r, WtW, st));
+  } else {
+    HIP_TRY(launch_fill_zero(WtW, r * r, st));
   }
-  rc = small_gram(W, plan->r_T, WtW, "gnmf_wtw");
-  if (rc != ILARGI_OK) return rc;
   if (plan->r_T > 0) {
     rc = ilargi_tmm(plan, W, r, G, ILARGI_F32, stream);
     if (rc != ILARGI_OK) return rc;
@@ -1161,7 +1168,7 @@ ilargi_status_t ilargi_gnmf_step(ilargi_plan_t* plan, float* W, float* Ht, int64
     HIP_TRY(launch_fill_zero(G, plan->c_T * r, st));
   }
   TraceScope ts(plan, "gnmf_update", 1, st);
-  HIP_TRY(launch_gnmf_update(Ht, G, WtW, plan->c_T, (int)r, tiny, st));
+  HIP_TRY(launch_gnmf_update(Ht, G, WtW, plan->c_T, (int)r, tiny, nullptr, 0, nullptr, st));
   return ILARGI_OK;
 }
 

@@ -258,11 +258,12 @@ hipError_t launch_elementwise(int op, const float* in, float* out, int64_t n, fl
 constexpr int kKmeansMaxK = 256;
 constexpr int kGnmfMaxRank = 64;
 hipError_t launch_centroid_norm(const float* C, int64_t c_T, int k, float* cn, hipStream_t st);
-hipError_t launch_kmeans_assign(float* P, const float* cn, int64_t r_T, int k, int32_t* assign, int32_t* counts,
-                                hipStream_t st);
+hipError_t launch_kmeans_assign(float* P, const float* cn, int64_t r_T, int k, int32_t* assign, int32_t* counts_partial,
+                                int64_t partial_ints, int32_t* counts, hipStream_t st);
 hipError_t launch_kmeans_update(float* C, const float* G, const int32_t* counts, int64_t c_T, int k,
                                 int32_t* counts_out, hipStream_t st);
-hipError_t launch_gnmf_update(float* X, const float* P, const float* Q, int64_t rows, int k, float tiny, hipStream_t st);
+hipError_t launch_gnmf_update(float* X, const float* P, const float* Q, int64_t rows, int k, float tiny,
+                              float* gram_partial, int64_t partial_floats, int* nparts_out, hipStream_t st);
 
 inline int ilog2_ceil(int64_t v) { int l = 0; while ((1ll << l) < v) ++l; return l; }
 

@@ -113,6 +113,39 @@ def test_config1_materialized_plan_agrees(il):
     assert rel(il.ilargi_tmm(mplan, dev(sch.extras["Y1"])).cpu().numpy(), oracle.tmm(tg, sch.extras["Y1"])) < OP_TOL
 
 
+def test_config1_kmeans_and_gaussian_nmf(il):
+    # the two unsupervised models at full size, ten centroids / rank ten, one step each from given values
+    sch, tg, plan, _ = Problem.get(il, "config1", 16)
+    rng = datagen.rng_for(77)
+    C0 = np.ascontiguousarray(tg.T32[rng.choice(sch.r_T, 10, replace=False)].T)
+    C = dev(C0)
+    assign = torch.empty(sch.r_T, dtype=torch.int32, device="cuda")
+    counts = torch.empty(10, dtype=torch.int32, device="cuda")
+    il.ilargi_kmeans_step(plan, C, assign, counts)
+    C_ref, a_ref, n_ref, _ = oracle.kmeans_step(tg, C0)
+    a = assign.cpu().numpy()
+    differ = np.flatnonzero(a != a_ref)
+    assert differ.size <= 20, differ.size                       # near-ties in float32 only
+    if differ.size:
+        d2 = oracle.kmeans_distances(oracle.Target(table=tg.T32[differ]), C0)
+        gap = d2[np.arange(differ.size), a[differ]] - d2[np.arange(differ.size), a_ref[differ]]
+        assert np.all(gap <= 2e-6 * d2.max(axis=1))
+    assert np.array_equal(counts.cpu().numpy(), np.bincount(a, minlength=10))
+    assert rel(C.cpu().numpy(), C_ref) < (OP_TOL if differ.size == 0 else GD_TOL)
+    # Gaussian NMF needs a non-negative table: the same schema with absolute values
+    for s in sch.sources:
+        s.D[...] = np.abs(s.D)
+    tg2 = oracle.Target(sch)
+    plan2 = il.ilargi_plan_create(il.schema_to_device(sch), sch.r_T, sch.c_T, max_cx=10)
+    W0 = (rng.random((sch.r_T, 10)) + 0.05).astype(np.float32)
+    H0 = (rng.random((10, sch.c_T)) + 0.05).astype(np.float32)
+    W, Ht = dev(W0), dev(np.ascontiguousarray(H0.T))
+    il.ilargi_gnmf_step(plan2, W, Ht)
+    W_ref, H_ref = oracle.gnmf_step(tg2, W0, H0)
+    assert rel(W.cpu().numpy(), W_ref) < OP_TOL and rel(Ht.cpu().numpy().T, H_ref) < OP_TOL
+    Problem.cache.clear()                                       # the cached schema was changed in place
+
+
 # ------------------------------------------------------------------ configuration 2 (logistic regression, Zipf keys)
 def test_config1_scalar_operators(il):
     # Tab. 2, first four rows, at full size: sums against the oracle; an element-wise operator applied to the
