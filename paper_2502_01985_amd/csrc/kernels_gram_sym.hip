@@ -2,8 +2,8 @@
 // (the cofactor block D_k^T diag(fan-out) D_k of T^T T, Sec. 2.2 / crossprod), on the matrix cores.
 //
 // C is symmetric, so only the 16 x 16 tiles (ci, cj), ci <= cj, are formed: for 200 columns that is 91 tiles
-// instead of the 169 of the full square.  A workgroup of eight wavefronts stages 32 whole rows in LDS (coalesced
-// float4 loads, every value fetched once), and each wavefront owns up to twelve tiles: for a quad of rows it
+// instead of the 169 of the full square.  A workgroup of sixteen wavefronts stages 32 whole rows in LDS (coalesced
+// float4 loads, every value fetched once), and each wavefront owns up to six tiles: for a quad of rows it
 // reads the 16 columns of tile-row ci (times the row weight) and of tile-column cj from LDS and issues one
 // MFMA 16x16x4 per tile.  In that MFMA both operands have the same layout (lane 16 q + s holds row q, column
 // s of the 16), which is why one staged copy serves both sides.  Workgroups own row chunks; their partial
@@ -19,10 +19,10 @@ namespace {
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 
-constexpr int kGsThreads = 512;
+constexpr int kGsThreads = 1024;
 constexpr int kGsWaves = kGsThreads / kWave;
 constexpr int kGsRows = 32;      // rows staged per step
-constexpr int kGsPW = 12;        // tiles per wavefront: 8 x 12 = 96 >= 91 tiles of a 208-column table
+constexpr int kGsPW = 6;         // tiles per wavefront: 16 x 6 = 96 >= 91 tiles of a 208-column table
 constexpr int kGsMaxTiles = 13;  // 16-column tiles per side
 
 template <bool VEC4>
@@ -123,7 +123,7 @@ __global__ __launch_bounds__(kGsThreads) void gram_sym_kernel(TredArgs a, int nt
 
 }  // namespace
 
-// A == B without index vectors, at most 208 columns, enough tiles to occupy eight wavefronts.
+// A == B without index vectors, at most 208 columns, enough tiles to occupy the wavefronts.
 bool gram_sym_supported(const TredArgs& a) {
   return a.upper_only && a.A == a.B && a.ia == nullptr && a.ib == nullptr && a.ca == a.cb && a.lda == a.ldb &&
          a.bcol0 == 0 && a.ca > 64 && a.ca <= 16 * kGsMaxTiles;

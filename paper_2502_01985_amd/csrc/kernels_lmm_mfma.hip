@@ -423,7 +423,6 @@ __global__ __launch_bounds__(kBlock) void lmm_prod_kernel(LmmArgs a, MfmaShape s
     for (int mt = wave; mt < sh.rb / 16; mt += kBlock / kWave) {
       v4f acc = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
       const float* arow = As + (size_t)(mt * 16 + li) * sh.lda + 4 * q;
-#pragma unroll 4
       for (int step = 0; step < sh.kp / 16; ++step) {
         const float4 av = *reinterpret_cast<const float4*>(arow + 16 * step);
         const float4 bv = *reinterpret_cast<const float4*>(Xs + ((size_t)(4 * step + q) * 16 + li) * 4);
