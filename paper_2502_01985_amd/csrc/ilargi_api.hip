@@ -403,6 +403,37 @@ ilargi_status_t tmm_pass(ilargi_plan* pl, const float* Y, int ldy, int col0, int
                          hipStream_t st, int done_k = -1, int done_blocks = 0) {
   FinArgs f;
   memset(&f, 0, sizeof(f));
+  auto colred_args = [&](int k, const float* Z, int ldz, int zcol0) {
+    const SourcePlan& p = pl->src[k];
+    ColredArgs c;
+    memset(&c, 0, sizeof(c));
+    c.D = p.D; c.rows = p.rows; c.ck = (int)p.cols; c.vec = p.vec;
+    c.Z = Z; c.ldz = ldz; c.col0 = zcol0; c.ncols = ncols;
+    c.partial = pl->at<float>(p.o_partial);
+    c.rows_per_block = colred_rows_per_block(p.rows);
+    return c;
+  };
+  auto segsum_args = [&](int k) {
+    const SourcePlan& p = pl->src[k];
+    SegArgs s = seg_args(pl, k);
+    s.Y = Y; s.ldy = ldy; s.col0 = col0; s.ncols = ncols;
+    s.Z = pl->at<float>(p.o_pz); s.ldz = ldy; s.zcol0 = col0;
+    return s;
+  };
+  // the column reduce of a dense source that takes Y directly and the segment sums of another source are
+  // independent: the first such pair shares one launch
+  int kc = -1, ks = -1;
+  if (Y != nullptr) {
+    for (int k = 0; k < pl->n; ++k) {
+      const SourcePlan& p = pl->src[k];
+      if (p.empty || k == done_k) continue;
+      if (p.ident && !p.sparse && kc < 0) kc = k;
+      if (!p.ident && ks < 0) ks = k;
+    }
+    if (kc >= 0 && ks >= 0 && !colred_segsum_supported(colred_args(kc, Y, ldy, col0), segsum_args(ks))) kc = ks = -1;
+    if (kc < 0 || ks < 0) kc = ks = -1;
+  }
+  bool pair_done = false;
   for (int k = 0; k < pl->n; ++k) {
     SourcePlan& p = pl->src[k];
     if (p.empty) continue;
@@ -415,34 +446,31 @@ ilargi_status_t tmm_pass(ilargi_plan* pl, const float* Y, int ldy, int col0, int
       ++f.n;
       continue;
     }
+    if ((k == kc || k == ks) && !pair_done) {
+      TraceScope ts(pl, "colred+segsum", kc, st);
+      HIP_TRY(launch_colred_segsum(colred_args(kc, Y, ldy, col0), colred_nblocks(pl->src[kc].rows), segsum_args(ks), st));
+      pair_done = true;
+    }
     ColredArgs c;
-    memset(&c, 0, sizeof(c));
-    c.D = p.D; c.rows = p.rows; c.ck = (int)p.cols; c.vec = p.vec;
     if (Y == nullptr) {
       // colSum: I_k^T 1 is the fan-out vector kept with the plan
-      c.Z = pl->at<float>(p.o_cnt); c.ldz = 1; c.col0 = 0;
+      c = colred_args(k, pl->at<float>(p.o_cnt), 1, 0);
     } else if (p.ident) {
-      c.Z = Y; c.ldz = ldy; c.col0 = col0;
+      c = colred_args(k, Y, ldy, col0);
     } else {
-      SegArgs s = seg_args(pl, k);
-      s.Y = Y; s.ldy = ldy; s.col0 = col0; s.ncols = ncols;
-      s.Z = pl->at<float>(p.o_pz); s.ldz = ldy; s.zcol0 = col0;
-      {
+      if (k != ks) {
         TraceScope ts(pl, "segsum", k, st);
-        HIP_TRY(launch_segsum(s, st));
+        HIP_TRY(launch_segsum(segsum_args(k), st));
       }
-      c.Z = pl->at<float>(p.o_pz); c.ldz = ldy; c.col0 = col0;
+      c = colred_args(k, pl->at<float>(p.o_pz), ldy, col0);
     }
-    c.ncols = ncols;
-    c.partial = pl->at<float>(p.o_partial);
-    c.rows_per_block = colred_rows_per_block(p.rows);
     int nb = colred_nblocks(p.rows);
     if (p.sparse) {
       // D_k^T Z_k over the column-sorted view; the result takes the place of a single block of partials
       TraceScope ts(pl, "colred", k, st);
       HIP_TRY(launch_spmm_t(sparse_args(pl, k), c.Z, c.ldz, c.col0, ncols, pl->at<float>(p.o_tpartial), c.partial, st));
       nb = 1;
-    } else {
+    } else if (k != kc) {
       TraceScope ts(pl, "colred", k, st);
       HIP_TRY(launch_colred(c, nb, st));
     }

@@ -20,14 +20,15 @@ __device__ __forceinline__ int64_t seg_row(const SegArgs& a, int64_t p) {
 // Narrow form: G = 2^logG lanes share one segment and stride over its entries; CT columns per lane.
 // Work items [0, r_k) are whole segments (skipped when longer than kLongSeg), items [r_k, r_k + n_chunks)
 // are chunks of long segments whose sums go to chunk_partial.
+// (bx of gx: this workgroup's place among the workgroups that share the work)
 template <int CT>
-__global__ __launch_bounds__(kBlock) void segsum_narrow_kernel(SegArgs a) {
+__device__ __forceinline__ void segsum_narrow_body(const SegArgs& a, int bx, int gx) {
   const int G = 1 << a.logG;
   const int lig = threadIdx.x & (G - 1);
   const int64_t n_items = a.r_k + a.n_chunks;
   const int64_t gpb = kBlock >> a.logG;
-  for (int64_t item = (int64_t)blockIdx.x * gpb + (threadIdx.x >> a.logG); item < n_items + gpb;
-       item += (int64_t)gridDim.x * gpb) {
+  for (int64_t item = (int64_t)bx * gpb + (threadIdx.x >> a.logG); item < n_items + gpb;
+       item += (int64_t)gx * gpb) {
     // keep whole wavefronts in the loop so that the butterfly below is convergent
     bool live = item < n_items;
     int64_t beg = 0, end = 0;
@@ -70,6 +71,11 @@ __global__ __launch_bounds__(kBlock) void segsum_narrow_kernel(SegArgs a) {
     }
     if (item >= n_items) break;
   }
+}
+
+template <int CT>
+__global__ __launch_bounds__(kBlock) void segsum_narrow_kernel(SegArgs a) {
+  segsum_narrow_body<CT>(a, blockIdx.x, gridDim.x);
 }
 
 // Wide form: W lanes of a segment each own columns lane, lane + W, ...  The lanes first load W different
@@ -149,16 +155,16 @@ constexpr int kUnroll = 4;
 // Partial of D^T Z over the rows of one workgroup.  blockIdx.y selects a slab of 64*VEC columns of D;
 // inside a slab lane -> (row offset, column group), so a wavefront reads whole contiguous rows.
 template <int VEC, int CT>
-__global__ __launch_bounds__(kBlock) void colred_kernel(ColredArgs a) {
+__device__ __forceinline__ void colred_body(const ColredArgs& a, int bx, int by) {
   __shared__ float red[VEC * CT][kBlock];
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
-  const int slab0 = blockIdx.y * kWave * VEC;                       // first column of the slab
+  const int slab0 = by * kWave * VEC;                               // first column of the slab
   const int wck = min(a.ck - slab0, kWave * VEC);                   // its width
   const int nvec = wck / VEC;                                       // column groups (<= 64)
   const int rp = kWave / nvec;                                      // rows per wavefront step
   const int rsub = lane / nvec, cg = lane - rsub * nvec;
   const bool active = rsub < rp;
-  const int64_t b0 = (int64_t)blockIdx.x * a.rows_per_block;
+  const int64_t b0 = (int64_t)bx * a.rows_per_block;
   const int64_t b1 = min(b0 + a.rows_per_block, a.rows);
   const int64_t step = (int64_t)rp * kUnroll;                       // rows per wavefront iteration
 
@@ -206,8 +212,23 @@ __global__ __launch_bounds__(kBlock) void colred_kernel(ColredArgs a) {
     float s = 0.0f;
     for (int w = 0; w < kBlock / kWave; ++w)
       for (int q = 0; q < rp; ++q) s += red[e * CT + n][w * kWave + q * nvec + jcg];
-    a.partial[((int64_t)blockIdx.x * a.ck + slab0 + j) * kNarrowCT + n] = s;
+    a.partial[((int64_t)bx * a.ck + slab0 + j) * kNarrowCT + n] = s;
   }
+}
+
+template <int VEC, int CT>
+__global__ __launch_bounds__(kBlock) void colred_kernel(ColredArgs a) {
+  colred_body<VEC, CT>(a, blockIdx.x, blockIdx.y);
+}
+
+// Two independent steps of a transposed multiply in one launch: the column reduce of a source that takes Y
+// directly (workgroups [0, nb_c)) and the segment sums of another source (the workgroups after them).  The
+// segment sums are bound by the latency of their gathers and use little bandwidth; next to the streaming column
+// reduce they cost almost nothing, while a launch of their own costs its full latency chain.
+template <int VEC, int CT>
+__global__ __launch_bounds__(kBlock) void colred_segsum_kernel(ColredArgs c, int nb_c, SegArgs s) {
+  if ((int)blockIdx.x < nb_c) colred_body<VEC, CT>(c, blockIdx.x, 0);
+  else segsum_narrow_body<CT>(s, blockIdx.x - nb_c, gridDim.x - nb_c);
 }
 
 // Sum of float4 records rec[b * stride4] over b < count by a whole workgroup: threads stride the records
@@ -323,6 +344,36 @@ hipError_t launch_colred(const ColredArgs& a, int nblocks, hipStream_t st) {
   else { if (ct == 1) ILARGI_COLRED(1, 1); else if (ct == 2) ILARGI_COLRED(1, 2); else ILARGI_COLRED(1, 4); }
 #undef ILARGI_COLRED
   return hipGetLastError();
+}
+
+// The fused launch needs the column reduce to be a single slab and the same operand width on both sides.
+bool colred_segsum_supported(const ColredArgs& c, const SegArgs& s) {
+  return c.ck > 0 && c.ck <= kWave * c.vec && c.ncols == s.ncols && s.ncols >= 1 && s.ncols <= kNarrowCT &&
+         s.r_k + s.n_chunks > 0;
+}
+
+hipError_t launch_colred_segsum(const ColredArgs& c, int nb_c, const SegArgs& s, hipStream_t st) {
+  if (!colred_segsum_supported(c, s) || nb_c <= 0) return hipErrorInvalidValue;
+  const int64_t gpb = kBlock >> s.logG;
+  int64_t gs = (s.r_k + s.n_chunks + gpb - 1) / gpb;
+  if (gs > 65536) gs = 65536;
+  const unsigned grid = (unsigned)(nb_c + gs);
+  const int ct = c.ncols <= 1 ? 1 : (c.ncols <= 2 ? 2 : 4);
+#define ILARGI_CS(V, C) colred_segsum_kernel<V, C><<<grid, kBlock, 0, st>>>(c, nb_c, s)
+  if (c.vec == 4) { if (ct == 1) ILARGI_CS(4, 1); else if (ct == 2) ILARGI_CS(4, 2); else ILARGI_CS(4, 4); }
+  else if (c.vec == 2) { if (ct == 1) ILARGI_CS(2, 1); else if (ct == 2) ILARGI_CS(2, 2); else ILARGI_CS(2, 4); }
+  else { if (ct == 1) ILARGI_CS(1, 1); else if (ct == 2) ILARGI_CS(1, 2); else ILARGI_CS(1, 4); }
+#undef ILARGI_CS
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  if (s.n_long > 0) {
+    int64_t total = (int64_t)s.n_long * s.ncols;
+    int g = (int)((total + kBlock - 1) / kBlock);
+    if (g > 1024) g = 1024;
+    segsum_combine_kernel<<<g, kBlock, 0, st>>>(s);
+    e = hipGetLastError();
+  }
+  return e;
 }
 
 hipError_t launch_finalize(const FinArgs& a, int c_T, int mode, hipStream_t st) {
