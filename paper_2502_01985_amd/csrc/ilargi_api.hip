@@ -553,6 +553,27 @@ ilargi_status_t tmm_wide(ilargi_plan* pl, const float* Y, int cx, float* out, in
     g.A = p.D; g.lda = (int)p.cols; g.ca = (int)p.cols; g.a_rows = p.rows;
     g.ldb = cx; g.cb = cx; g.bcol0 = 0; g.b_rows = p.rows;
     g.n_rows = p.rows;
+    if (!p.ident && !bf16 && p.n_long == 0 && cx % 4 == 0 && tmm_join_supported((int)p.cols, cx) &&
+        p.cols * cx <= pl->lay.gpartial_floats) {
+      // segment sums and D_k^T Z_k in one pass in join order: Z_k is never written (operands whose rows are
+      // whole float4s; for the others the two-step form measures the same or better)
+      TmmJoinArgs j;
+      memset(&j, 0, sizeof(j));
+      j.D = p.D; j.ck = (int)p.cols; j.r_k = p.rows;
+      j.rowptr = pl->at<int32_t>(p.o_rowptr); j.perm = pl->at<int32_t>(p.o_perm);
+      j.Y = Y; j.ldy = cx; j.col0 = 0; j.c = cx;
+      j.partial = pl->at<float>(pl->lay.o_gpartial);
+      int grid = 0;
+      {
+        TraceScope ts(pl, "tmm_join", k, st);
+        HIP_TRY(launch_tmm_join(j, pl->lay.gpartial_floats, st, &grid));
+      }
+      HIP_TRY(launch_tred_reduce(j.partial, grid, p.cols * cx, pl->at<float>(p.o_g), st));
+      c.tcol2src[c.n] = pl->at<int32_t>(p.o_tcol);
+      c.G[c.n] = pl->at<float>(p.o_g);
+      ++c.n;
+      continue;
+    }
     if (p.ident) {
       g.B = Y;
     } else {

@@ -112,6 +112,16 @@ struct GramStarArgs {
   float* zc;                         // r_R x cs: rows of S summed per row of R
 };
 
+// Join-order transposed multiply of one joined source (kernels_tmm_join.hip).
+struct TmmJoinArgs {
+  const float* D; int ck;            // r_k x ck source table
+  int64_t r_k;
+  const int32_t* rowptr;             // r_k + 1: inverse index
+  const int32_t* perm;               // target rows in source-row order
+  const float* Y; int ldy, col0, c;  // operand columns [col0, col0 + c), c <= 16
+  float* partial;                    // [gridDim.x][ck][c]
+};
+
 struct SegArgs {
   const int32_t* rowptr;   // r_k + 1
   const int32_t* perm;     // nnz
@@ -242,6 +252,8 @@ hipError_t launch_finalize(const FinArgs& a, int c_T, int mode, hipStream_t st);
 hipError_t launch_materialize(const MatArgs& a, hipStream_t st);
 hipError_t launch_gram_assemble(const GramAsmPair* pairs_dev, int npairs, const int32_t* const* tcol2src_dev,
                                 int c_T, float* out, hipStream_t st);
+bool tmm_join_supported(int ck, int c);
+hipError_t launch_tmm_join(const TmmJoinArgs& a, int64_t partial_floats, hipStream_t st, int* grid_out);
 bool gram_star_supported(int cs);
 hipError_t launch_gram_star(const GramStarArgs& a, int vec, int max_grid, hipStream_t st, int* grid_out);
 bool gram_sym_supported(const TredArgs& a);

@@ -1,0 +1,213 @@
+// Transposed multiply, share of a joined source for operands of 8..16 columns (Sec. 2.2):
+//   G_k = D_k^T (I_k^T Y)
+// in ONE pass in join order instead of a segmented sum (Z = I_k^T Y written out) followed by a reduction that
+// reads D_k and Z again.  A wavefront owns 16 rows of D_k and, through the inverse index, every target row that
+// joins them.  It gathers those rows of Y 64 at a time (next batch prefetched into registers) and adds them up
+// per row of D_k with an indicator MFMA (A = 1 where staged row 4 q + r joins row li of the tile: exact sums).
+// The summed tile then sits in the MFMA result layout, register r of lane (li, q) = Z[row 4 q + r][column li],
+// which is exactly the B operand of a 16x16x4 MFMA whose K slot q stands for row 4 q + r; with
+// A = D_k[row 4 q + r][16 ci + li] that MFMA adds the tile's share to columns 16 ci .. of G_k.  Z never leaves the
+// registers.  The wavefront's 16 rows of D_k are requested at the start of the tile and arrive while the rows
+// of Y are gathered.  Per-workgroup partial blocks are added afterwards in workgroup order.
+#include <algorithm>
+#include <cstdint>
+#include <mutex>
+#include <type_traits>
+
+#include "ilargi_internal.h"
+
+namespace ilargi {
+
+namespace {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ void tj_wave_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+constexpr int kTjST = 64;            // target rows a wavefront stages at a time
+constexpr int kTjLdy = 20;           // LDS row stride of the staged rows of Y
+constexpr int kTjWavesPerBlock = kBlock / kWave;
+constexpr int kTjWaveFloats = kTjST * kTjLdy + 2 * kTjST + 32;
+
+// NTR: 16-column tiles of D_k (compile-time bound of the accumulators); VEC4: rows of Y as float4.
+template <int NTR, bool VEC4>
+__global__ __launch_bounds__(kBlock) void tmm_join_kernel(TmmJoinArgs a, int rtiles) {
+  extern __shared__ float lds[];
+  const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+  const int li = lane % 16, q = lane / 16;
+  float* wbase = lds + (size_t)wave * kTjWaveFloats;
+  float* Ys = wbase;                                          // [ST][ldy] staged rows of Y (zero beyond c)
+  int* iS = reinterpret_cast<int*>(Ys + kTjST * kTjLdy);      // [ST] target row of each staged row
+  int* jS = iS + kTjST;                                       // [ST] row of the tile it joins (-1: none)
+  int* rpS = jS + kTjST;                                      // [17] row pointers of the tile
+
+  v4f gacc[NTR];                                              // G_k tiles: columns 16 ci .. of D_k x operand columns
+#pragma unroll
+  for (int ci = 0; ci < NTR; ++ci) gacc[ci] = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
+
+  typedef typename std::conditional<VEC4, float4, float>::type SVal;
+  constexpr int NV = VEC4 ? kTjST * 4 / kWave : kTjST * 16 / kWave;   // staging slots of a lane (16 columns per row)
+  constexpr int gslots = VEC4 ? 4 : 16;
+  const int glive = VEC4 ? a.c / 4 : a.c;
+  const int ntr = (a.ck + 15) / 16;
+
+  for (int rt = blockIdx.x * kTjWavesPerBlock + wave; rt < rtiles; rt += gridDim.x * kTjWavesPerBlock) {
+    const int64_t jb = (int64_t)rt * 16;
+    const int p_begin = a.rowptr[jb];
+    const int p_end = a.rowptr[min(jb + 16, a.r_k)];
+    // this tile of D_k in the A layout of the second product: value r of tile ci is D[jb + 4 q + r][16 ci + li]
+    float dv[NTR][4];
+#pragma unroll
+    for (int ci = 0; ci < NTR; ++ci)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int64_t row = jb + 4 * q + r;
+        const int col = 16 * ci + li;
+        dv[ci][r] = (ci < ntr && row < a.r_k && col < a.ck) ? a.D[row * a.ck + col] : 0.0f;
+      }
+    v4f zacc = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
+    tj_wave_sync();
+    if (lane <= 16) rpS[lane] = a.rowptr[min(jb + lane, a.r_k)];
+    tj_wave_sync();
+    auto joined = [&](int p) {                                // the entries of a row are consecutive
+      int j = 0;
+#pragma unroll
+      for (int k = 1; k < 16; ++k) j += p >= rpS[k] ? 1 : 0;
+      return j;
+    };
+    int pi = (lane < kTjST && p_begin + lane < p_end) ? a.perm[p_begin + lane] : -1;
+    int pi_next = (lane < kTjST && p_begin + kTjST + lane < p_end) ? a.perm[p_begin + kTjST + lane] : -1;
+    int jl = pi >= 0 ? joined(p_begin + lane) : -1;
+    tj_wave_sync();                                           // the previous tile's batches are consumed
+    if (lane < kTjST) iS[lane] = pi;
+    tj_wave_sync();
+    SVal sv[NV];
+    auto load_rows = [&](int cnt_rows) {
+#pragma unroll
+      for (int u = 0; u < NV; ++u) {
+        const int e = lane + u * kWave;
+        const int r = e / gslots, g = e - r * gslots;
+        if constexpr (VEC4) sv[u] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        else sv[u] = 0.0f;
+        if (r < cnt_rows && g < glive) {
+          const int64_t row = iS[r];
+          if constexpr (VEC4) sv[u] = *reinterpret_cast<const float4*>(a.Y + row * a.ldy + a.col0 + 4 * g);
+          else sv[u] = a.Y[row * a.ldy + a.col0 + g];
+        }
+      }
+    };
+    load_rows(min(kTjST, p_end - p_begin));
+    for (int p0 = p_begin; p0 < p_end; p0 += kTjST) {
+      const int cnt = min(kTjST, p_end - p0);
+      const int cnt_next = max(0, min(kTjST, p_end - p0 - kTjST));
+      tj_wave_sync();                                         // the previous batch is consumed
+      if (lane < kTjST) { jS[lane] = jl; iS[lane] = pi_next; }
+#pragma unroll
+      for (int u = 0; u < NV; ++u) {
+        const int e = lane + u * kWave;
+        const int r = e / gslots, g = e - r * gslots;
+        if constexpr (VEC4) *reinterpret_cast<float4*>(Ys + r * kTjLdy + 4 * g) = sv[u];
+        else Ys[r * kTjLdy + g] = sv[u];
+      }
+      tj_wave_sync();
+      pi = pi_next;
+      pi_next = (lane < kTjST && p0 + 2 * kTjST + lane < p_end) ? a.perm[p0 + 2 * kTjST + lane] : -1;
+      jl = pi >= 0 ? joined(p0 + kTjST + lane) : -1;
+      load_rows(cnt_next);
+      for (int t = 0; 16 * t < cnt; ++t) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int row = t * 16 + 4 * q + r;                 // rows beyond the batch hold zeros and join nothing
+          const float yv = Ys[row * kTjLdy + li];
+          const float ind = jS[row] == li ? 1.0f : 0.0f;
+          zacc = __builtin_amdgcn_mfma_f32_16x16x4f32(ind, yv, zacc, 0, 0, 0);
+        }
+      }
+    }
+    // G_k += D_tile^T Z_tile
+#pragma unroll
+    for (int ci = 0; ci < NTR; ++ci)
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+        gacc[ci] = __builtin_amdgcn_mfma_f32_16x16x4f32(dv[ci][r], zacc[r], gacc[ci], 0, 0, 0);
+  }
+
+  // the four wavefronts' shares added in wavefront order in LDS; tile ci, register r of lane (li, q) is
+  // G[16 ci + 4 q + r][li]
+  float* red = lds;                                           // [NTR * 16][16]
+  for (int w = 0; w < kTjWavesPerBlock; ++w) {
+    __syncthreads();
+    if (wave == w) {
+#pragma unroll
+      for (int ci = 0; ci < NTR; ++ci)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          float* p = red + (16 * ci + 4 * q + r) * 16 + li;
+          if (w == 0) *p = gacc[ci][r];
+          else *p += gacc[ci][r];
+        }
+    }
+  }
+  __syncthreads();
+  float* gp = a.partial + (int64_t)blockIdx.x * a.ck * a.c;
+  for (int e = tid; e < a.ck * a.c; e += kBlock) {
+    const int j = e / a.c, n = e - j * a.c;
+    gp[e] = red[j * 16 + n];
+  }
+}
+
+typedef void (*TjFn)(TmmJoinArgs, int);
+
+template <int NTR>
+TjFn pick_tj(bool vec4) { return vec4 ? tmm_join_kernel<NTR, true> : tmm_join_kernel<NTR, false>; }
+
+}  // namespace
+
+bool tmm_join_supported(int ck, int c) { return ck >= 1 && ck <= 208 && c >= 1 && c <= 16; }
+
+// partial: partial_floats long, one ck x c block per workgroup; *grid_out workgroups were launched.
+hipError_t launch_tmm_join(const TmmJoinArgs& a, int64_t partial_floats, hipStream_t st, int* grid_out) {
+  if (grid_out) *grid_out = 0;
+  if (!tmm_join_supported(a.ck, a.c) || a.r_k <= 0) return hipErrorInvalidValue;
+  const int rtiles = (int)((a.r_k + 15) / 16);
+  const int ntr = (a.ck + 15) / 16;
+  const bool vec4 = a.c % 4 == 0 && a.ldy % 4 == 0 && a.col0 % 4 == 0 && reinterpret_cast<uintptr_t>(a.Y) % 16 == 0;
+  TjFn fn = ntr <= 4 ? pick_tj<4>(vec4) : (ntr <= 8 ? pick_tj<8>(vec4) : pick_tj<13>(vec4));
+  const int ntr_c = ntr <= 4 ? 4 : (ntr <= 8 ? 8 : 13);
+  size_t lds_floats = std::max<size_t>((size_t)kTjWavesPerBlock * kTjWaveFloats, (size_t)ntr_c * 256);
+  const size_t lds_bytes = lds_floats * sizeof(float);
+  static std::mutex cache_mutex;
+  static TjFn seen_fn[8];
+  static int seen_slots[8];
+  static int n_seen = 0;
+  int slots = 0;
+  {
+    std::lock_guard<std::mutex> lock(cache_mutex);
+    for (int i = 0; i < n_seen; ++i)
+      if (seen_fn[i] == fn) slots = seen_slots[i];
+    if (slots == 0) {
+      int dev = 0, cus = 256, per_cu = 0;
+      hipDeviceProp_t prop;
+      if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess && prop.multiProcessorCount > 0)
+        cus = prop.multiProcessorCount;
+      if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(fn), kBlock, lds_bytes) != hipSuccess ||
+          per_cu < 1)
+        per_cu = 1;
+      slots = per_cu * cus;
+      if (n_seen < 8) { seen_fn[n_seen] = fn; seen_slots[n_seen] = slots; ++n_seen; }
+    }
+  }
+  int64_t gx = (rtiles + kTjWavesPerBlock - 1) / kTjWavesPerBlock;
+  gx = std::min<int64_t>(gx, slots);                                  // one round of resident workgroups
+  gx = std::min<int64_t>(gx, partial_floats / ((int64_t)a.ck * a.c));
+  if (gx < 1) return hipErrorInvalidValue;
+  if (grid_out) *grid_out = (int)gx;
+  hipLaunchKernelGGL(fn, dim3((unsigned)gx), dim3(kBlock), lds_bytes, st, a, rtiles);
+  return hipGetLastError();
+}
+
+}  // namespace ilargi

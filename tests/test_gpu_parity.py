@@ -156,7 +156,7 @@ def test_lmm_identity_operand_reproduces_table(il, name):
 
 # ------------------------------------------------------------------ TMM
 @pytest.mark.parametrize("name", ALL)
-@pytest.mark.parametrize("cx", [1, 2, 3, 4, 5, 16, 17])
+@pytest.mark.parametrize("cx", [1, 2, 3, 4, 5, 8, 13, 16, 17])
 def test_tmm(il, name, cx):
     sch, tg, plan = get(il, name)
     Y = datagen.rng_for(2000 + cx).standard_normal((sch.r_T, cx)).astype(np.float32)
