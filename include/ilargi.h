@@ -70,7 +70,9 @@ typedef struct {
    * Sec. 3.1).  With csr_rowptr != NULL, D must be NULL.  Borrowed like D.  A plan with a sparse source
    * serves lmm, tmm, gd_step, materialize, row_sum, col_sum and the element-wise operators that keep zero
    * at zero (which then act on csr_val, nnz values), in float32; crossprod and the bf16 variants return
-   * UNSUPPORTED.  Invalid sparse rows are reported by ilargi_plan_create as INDEX_RANGE. */
+   * UNSUPPORTED.  Invalid sparse rows are reported by ilargi_plan_create as INDEX_RANGE.  A dense table has at
+   * most 4096 columns; a sparse one up to 2^20 (one-hot encodings), provided that beyond 4096 columns no row
+   * holds more than 2048 stored entries (else UNSUPPORTED). */
   const int32_t* csr_rowptr; /* device int32[rows + 1], rising from 0 to nnz */
   const int32_t* csr_col;    /* device int32[nnz], in [0, cols), strictly ascending within a row */
   const float* csr_val;      /* device float32[nnz] */

@@ -149,8 +149,10 @@ ilargi_status_t make_layout(int n, const ilargi_source_t* s, int64_t r_T, int64_
   for (int k = 0; k < n; ++k) {
     if (s[k].rows < 0 || s[k].cols < 0 || s[k].rows > 2147483646ll)
       return fail(ILARGI_ERR_SHAPE, "source %d: rows = %lld, cols = %lld", k, (long long)s[k].rows, (long long)s[k].cols);
-    if (s[k].cols > kMaxLdsFloats)
-      return fail(ILARGI_ERR_UNSUPPORTED, "source %d: more than %d columns", k, kMaxLdsFloats);
+    if (s[k].cols > kMaxLdsFloats && s[k].csr_rowptr == nullptr)
+      return fail(ILARGI_ERR_UNSUPPORTED, "source %d: more than %d columns (wider tables must be given in sparse rows)", k,
+                  kMaxLdsFloats);
+    if (s[k].cols > (1 << 20)) return fail(ILARGI_ERR_SHAPE, "source %d: cols = %lld above 2^20", k, (long long)s[k].cols);
     if (s[k].row_idx == nullptr && s[k].rows != r_T)
       return fail(ILARGI_ERR_SHAPE, "source %d: NULL row_idx (identity) needs rows == r_T", k);
     src[k].rows = s[k].rows;
@@ -198,7 +200,8 @@ ilargi_status_t make_layout(int n, const ilargi_source_t* s, int64_t r_T, int64_
       p.o_chunk_partial = take(sizeof(float) * p.nch_max * wmax);
     }
     p.o_pz = take(sizeof(float) * std::max<int64_t>(p.rows, 1) * max_cx);
-    p.o_partial = take(sizeof(float) * kColredBlocks * std::max<int64_t>(p.cols, 1) * kNarrowCT);
+    // (a sparse source's transposed product leaves a single block of partials)
+    p.o_partial = take(sizeof(float) * (p.sparse ? 1 : kColredBlocks) * std::max<int64_t>(p.cols, 1) * kNarrowCT);
     p.o_g = take(sizeof(float) * std::max<int64_t>(p.cols, 1) * max_cx);
     p.o_cnt = take(sizeof(float) * std::max<int64_t>(p.rows, 1));
     if (p.sparse) {
@@ -230,7 +233,7 @@ ilargi_status_t make_layout(int n, const ilargi_source_t* s, int64_t r_T, int64_
   lay.zc_floats = 1;
   lay.gpartial_floats = kGramPartialFloats;
   lay.blocks_floats = 0;
-  for (int k = 0; k < n; ++k)
+  for (int k = 0; k < n && lay.max_entries == 0; ++k)    // (plans with sparse sources have no Gram matrix)
     for (int l = k; l < n; ++l) {
       int64_t cc = src[k].cols * src[l].cols;
       lay.blocks_floats += cc;
@@ -321,7 +324,8 @@ SparseArgs sparse_args(const ilargi_plan* pl, int k) {
 // Widest operand slice one narrow pass can stage in LDS for every source of the plan.
 int pass_width(const ilargi_plan* pl) {
   int64_t cmax = 1;
-  for (const SourcePlan& p : pl->src) cmax = std::max(cmax, p.cols);
+  for (const SourcePlan& p : pl->src)
+    if (p.cols <= kMaxLdsFloats) cmax = std::max(cmax, p.cols);   // wider (sparse) tables do not stage the operand
   int w = (int)std::min<int64_t>(kNarrowCT, kMaxLdsFloats / cmax);
   return w >= 4 ? 4 : (w >= 2 ? 2 : 1);
 }
@@ -814,6 +818,11 @@ ilargi_status_t ilargi_plan_create(int n, const ilargi_source_t* sources, int64_
       HIP_TRY(hipMemcpyAsync(rp.data(), p.csr_rowptr, sizeof(int32_t) * (p.rows + 1), hipMemcpyDeviceToHost, st));
       HIP_TRY(hipStreamSynchronize(st));
       const int cap = sparse_row_block_cap((int)p.cols);
+      if (p.cols > kMaxLdsFloats)
+        for (int64_t r = 0; r < p.rows; ++r)
+          if (rp[(size_t)r + 1] - rp[(size_t)r] > cap)
+            return fail(ILARGI_ERR_UNSUPPORTED, "source %d: a row of a table wider than %d columns holds more than %d entries", k,
+                        kMaxLdsFloats, cap);
       std::vector<int32_t> rb;
       rb.push_back(0);
       int64_t r = 0;

@@ -60,19 +60,24 @@ __global__ __launch_bounds__(kBlock) void csr_gather_rows_kernel(const int32_t* 
 // plan): it first copies their values and column indices to LDS with coalesced loads (all of a thread's loads
 // in flight at once - rows are short, walking them one by one would leave the memory system idle), then
 // 2^k lanes per row sum the row from LDS.  X_k (ck x CT) is staged in LDS through the column map.
-template <int CT>
+// XG (tables too wide for that, e.g. one-hot encodings with tens of thousands of columns): the operand values
+// are fetched per stored entry while the block is staged (column map, then operand, all loads of a thread in
+// flight), and LDS holds the products val * x instead of values and column indices.
+template <int CT, bool XG>
 __global__ __launch_bounds__(kBlock) void spmm_rows_kernel(SparseArgs a, const float* __restrict__ X, int ldx,
                                                            int col0, int ncols, float* __restrict__ P, int ldp,
                                                            int cap) {
   extern __shared__ float lds[];
-  float* Xs = lds;                                        // [cols][CT]
-  float* valS = lds + (size_t)a.cols * CT;                // [cap]
-  int* colS = reinterpret_cast<int*>(valS + cap);         // [cap]
-  int* rpS = colS + cap;                                  // [kSparseBlockRows + 1] row pointers of the block
-  for (int e = threadIdx.x; e < a.cols * CT; e += kBlock) {
-    const int j = e / CT, c = e - j * CT;
-    const int t = a.colmap[j];
-    Xs[e] = (t >= 0 && c < ncols) ? X[(int64_t)t * ldx + col0 + c] : 0.0f;
+  float* Xs = lds;                                        // [cols][CT]   (not XG)
+  float* valS = XG ? lds : lds + (size_t)a.cols * CT;     // [cap], XG: [cap][CT] products
+  int* colS = reinterpret_cast<int*>(valS + (size_t)cap * (XG ? CT : 1));   // [cap] (not XG)
+  int* rpS = XG ? colS : colS + cap;                      // [kSparseBlockRows + 1] row pointers of the block
+  if constexpr (!XG) {
+    for (int e = threadIdx.x; e < a.cols * CT; e += kBlock) {
+      const int j = e / CT, c = e - j * CT;
+      const int t = a.colmap[j];
+      Xs[e] = (t >= 0 && c < ncols) ? X[(int64_t)t * ldx + col0 + c] : 0.0f;
+    }
   }
   for (int blk = blockIdx.x; blk < a.n_row_blocks; blk += gridDim.x) {
     const int r_lo = a.row_block[blk], r_hi = a.row_block[blk + 1];
@@ -89,10 +94,27 @@ __global__ __launch_bounds__(kBlock) void spmm_rows_kernel(SparseArgs a, const f
         v[u] = p < ne ? a.val[e_lo + p] : 0.0f;
         cc[u] = p < ne ? a.col[e_lo + p] : 0;
       }
+      if constexpr (XG) {
+        int tc[U];
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int p = p0 + u * kBlock;
-        if (p < ne) { valS[p] = v[u]; colS[p] = cc[u]; }
+        for (int u = 0; u < U; ++u) tc[u] = p0 + u * kBlock < ne ? a.colmap[cc[u]] : -1;
+#pragma unroll
+        for (int c = 0; c < CT; ++c) {
+          float xv[U];
+#pragma unroll
+          for (int u = 0; u < U; ++u) xv[u] = (tc[u] >= 0 && c < ncols) ? X[(int64_t)tc[u] * ldx + col0 + c] : 0.0f;
+#pragma unroll
+          for (int u = 0; u < U; ++u) {
+            const int p = p0 + u * kBlock;
+            if (p < ne) valS[(size_t)p * CT + c] = v[u] * xv[u];
+          }
+        }
+      } else {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const int p = p0 + u * kBlock;
+          if (p < ne) { valS[p] = v[u]; colS[p] = cc[u]; }
+        }
       }
     }
     for (int g = threadIdx.x; g <= nr; g += kBlock) rpS[g] = a.rowptr[r_lo + g] - e_lo;
@@ -109,10 +131,15 @@ __global__ __launch_bounds__(kBlock) void spmm_rows_kernel(SparseArgs a, const f
 #pragma unroll
       for (int c = 0; c < CT; ++c) acc[c] = 0.0f;
       for (int p = beg + sub; p < end; p += L) {
-        const float v = valS[p];
-        const float* x = Xs + colS[p] * CT;
+        if constexpr (XG) {
 #pragma unroll
-        for (int c = 0; c < CT; ++c) acc[c] = fmaf(v, x[c], acc[c]);
+          for (int c = 0; c < CT; ++c) acc[c] += valS[(size_t)p * CT + c];
+        } else {
+          const float v = valS[p];
+          const float* x = Xs + colS[p] * CT;
+#pragma unroll
+          for (int c = 0; c < CT; ++c) acc[c] = fmaf(v, x[c], acc[c]);
+        }
       }
       for (int off = L >> 1; off > 0; off >>= 1) {
 #pragma unroll
@@ -250,21 +277,24 @@ hipError_t launch_csr_gather_rows(const int32_t* entry_row, const float* val, co
 hipError_t launch_spmm_rows(const SparseArgs& a, const float* X, int ldx, int col0, int ncols, float* P, int ldp,
                             hipStream_t st) {
   if (a.rows <= 0 || ncols <= 0 || a.n_row_blocks <= 0) return hipSuccess;
-  if (a.cols > kMaxLdsFloats) return hipErrorInvalidValue;
-  const int fit = a.cols * 4 <= kMaxLdsFloats ? 4 : (a.cols * 2 <= kMaxLdsFloats ? 2 : 1);
+  const bool xg = a.cols > kMaxLdsFloats;                 // operand fetched per entry instead of staged
+  const int fit = xg ? kNarrowCT : (a.cols * 4 <= kMaxLdsFloats ? 4 : (a.cols * 2 <= kMaxLdsFloats ? 2 : 1));
   if (ncols > fit) return hipErrorInvalidValue;
   const int ct = ncols <= 1 ? 1 : (ncols <= 2 ? 2 : 4);   // columns the kernel carries: the operand's, rounded up
   const int cap = sparse_row_block_cap(a.cols);
-  const size_t lds_bytes = ((size_t)a.cols * ct + 2 * (size_t)cap + kSparseBlockRows + 1) * sizeof(float);
+  const size_t lds_bytes = xg ? ((size_t)cap * ct + kSparseBlockRows + 1) * sizeof(float)
+                              : ((size_t)a.cols * ct + 2 * (size_t)cap + kSparseBlockRows + 1) * sizeof(float);
   const int grid = std::min(a.n_row_blocks, 8192);
-  if (ct == 4) spmm_rows_kernel<4><<<grid, kBlock, lds_bytes, st>>>(a, X, ldx, col0, ncols, P, ldp, cap);
-  else if (ct == 2) spmm_rows_kernel<2><<<grid, kBlock, lds_bytes, st>>>(a, X, ldx, col0, ncols, P, ldp, cap);
-  else spmm_rows_kernel<1><<<grid, kBlock, lds_bytes, st>>>(a, X, ldx, col0, ncols, P, ldp, cap);
+#define ILARGI_SPMM(C, G) spmm_rows_kernel<C, G><<<grid, kBlock, lds_bytes, st>>>(a, X, ldx, col0, ncols, P, ldp, cap)
+  if (xg) { if (ct == 4) ILARGI_SPMM(4, true); else if (ct == 2) ILARGI_SPMM(2, true); else ILARGI_SPMM(1, true); }
+  else { if (ct == 4) ILARGI_SPMM(4, false); else if (ct == 2) ILARGI_SPMM(2, false); else ILARGI_SPMM(1, false); }
+#undef ILARGI_SPMM
   return hipGetLastError();
 }
 
-// Entries a row block holds at most: 2048, or a whole row of the widest possible kind.
-int sparse_row_block_cap(int cols) { return std::max(2048, cols); }
+// Entries a row block holds at most: 2048, or a whole row of the widest table whose operand is staged in LDS.
+// Wider tables keep 2048: their rows must not hold more stored entries than that (checked with the plan).
+int sparse_row_block_cap(int cols) { return cols <= kMaxLdsFloats ? std::max(2048, cols) : 2048; }
 
 hipError_t launch_spmm_t(const SparseArgs& a, const float* Z, int ldz, int col0, int ncols, float* partial, float* G,
                          hipStream_t st) {

@@ -174,11 +174,11 @@ def test_choose_rejects_bad_arguments():
 # ----------------------------------------------------------------------------- sparse sources (host side)
 def test_workspace_grows_with_the_stored_entries_of_a_sparse_source():
     cm = np.arange(8, dtype=np.int32)
-    dense = il.ilargi_plan_workspace_bytes([(1, 1000, 8, 0, cm)], 1000, 8, 1)
+    none = il.ilargi_plan_workspace_bytes([(0, 1000, 8, 0, cm, 1, 1, 1, 0)], 1000, 8, 1)
     sparse = il.ilargi_plan_workspace_bytes([(0, 1000, 8, 0, cm, 1, 1, 1, 4000)], 1000, 8, 1)
     more = il.ilargi_plan_workspace_bytes([(0, 1000, 8, 0, cm, 1, 1, 1, 8000)], 1000, 8, 1)
     # column-sorted rows and values and two temporaries: at least 16 bytes per stored entry, sort buffers on top
-    assert sparse - dense >= 16 * 4000 and more - sparse >= 16 * 4000
+    assert sparse - none >= 16 * 4000 and more - sparse >= 16 * 4000
     with pytest.raises(il.IlargiError) as ei:
         il.ilargi_plan_workspace_bytes([(0, 1000, 8, 0, cm, 1, 1, 1, 8001)], 1000, 8, 1)    # more entries than cells
     assert ei.value.status == il.ERR_SHAPE

@@ -834,6 +834,49 @@ def test_sparse_sources_edge_cases(il):
     assert ei.value.status == il.ERR_UNSUPPORTED
 
 
+def test_sparse_table_wider_than_the_dense_limit(il):
+    # a one-hot style dimension table with 10,000 columns and a few stored entries per row (dense tables stop at
+    # 4096 columns): the operand is fetched per stored entry instead of being staged whole
+    rng = datagen.rng_for(1303)
+    r_T, r_R, c_S, c_R = 4_003, 1_501, 8, 10_000
+    S = rng.standard_normal((r_T, c_S)).astype(np.float32)
+    R = np.zeros((r_R, c_R), dtype=np.float32)
+    for j in range(r_R):
+        cols = rng.choice(c_R, size=int(rng.integers(0, 6)), replace=False)
+        R[j, cols] = rng.standard_normal(cols.size).astype(np.float32)
+    R[5, :1500] = 1.0                                   # one long row, still within the limit of such tables
+    fk = rng.integers(0, r_R, r_T).astype(np.int32)
+    fk[::13] = -1
+    c_T = c_S + c_R
+    sch = datagen.Schema([datagen.Source(S, None, np.arange(c_S, dtype=np.int32)),
+                          datagen.Source(R, fk, np.arange(c_S, c_T, dtype=np.int32))], r_T, c_T)
+    tg = oracle.Target(sch)
+    srcs = il.schema_to_device(sch, sparse=[False, True])
+    plan = il.ilargi_plan_create(srcs, r_T, c_T, max_cx=4)
+    assert np.array_equal(il.ilargi_materialize(plan).cpu().numpy().view(np.uint32), tg.T32.view(np.uint32))
+    for cx in (1, 3, 4):
+        X = rng.standard_normal((c_T, cx)).astype(np.float32)
+        Y = rng.standard_normal((r_T, cx)).astype(np.float32)
+        assert rel(il.ilargi_lmm(plan, dev(X)).cpu().numpy(), oracle.lmm(tg, X)) < OP_TOL
+        assert rel(il.ilargi_tmm(plan, dev(Y)).cpu().numpy(), oracle.tmm(tg, Y)) < OP_TOL
+    assert rel(il.ilargi_row_sum(plan).cpu().numpy(), oracle.row_sum(tg)) < OP_TOL
+    assert rel(il.ilargi_col_sum(plan).cpu().numpy(), oracle.col_sum(tg)) < OP_TOL
+    w_star = rng.standard_normal(c_T)
+    y = datagen.finish_labels("linear", oracle.lmm(tg, w_star.reshape(-1, 1)), 0.01 * rng.standard_normal(r_T))
+    W, L = _run_gd(il, plan, il.LINEAR, y, [0.05], 5, c_T)
+    W_ref, L_ref = oracle.gd(tg, "linear", y, np.zeros((c_T, 1)), [0.05], 5)
+    assert rel(W, W_ref) < GD_TOL
+    np.testing.assert_allclose(L, L_ref, rtol=2e-4)
+    # the same table stored densely is refused, and so is a row with more entries than a staged block holds
+    with pytest.raises(il.IlargiError) as ei:
+        il.ilargi_plan_create(il.schema_to_device(sch), r_T, c_T, max_cx=1)
+    assert ei.value.status == il.ERR_UNSUPPORTED
+    R[7, :2100] = 1.0
+    with pytest.raises(il.IlargiError) as ei:
+        il.ilargi_plan_create(il.schema_to_device(sch, sparse=[False, True]), r_T, c_T, max_cx=1)
+    assert ei.value.status == il.ERR_UNSUPPORTED
+
+
 def test_invalid_sparse_rows_are_reported(il):
     good = il.CSR.from_dense(np.array([[1.0, 0.0, 2.0], [0.0, 3.0, 0.0]], dtype=np.float32))
     cm = np.arange(3, dtype=np.int32)
