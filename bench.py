@@ -326,6 +326,45 @@ def sparse_tables(il, torch, datagen, dev):
     return out
 
 
+def one_hot_tables(il, torch, datagen, dev):
+    """Two joined one-hot style tables with the shape of the 'Movie' row of the paper's table of real data sets
+    (Tab. 4: 1,000,000 target rows, tables of 6,040 x 9,510 and 3,710 x 3,840; 20 stored entries per row are this
+    stand-in's choice), all tables in sparse rows.  Factorized = a plan over the two tables; materialized = the
+    same entry points on a one-source plan over the joined table, also in sparse rows (the join itself is made on
+    the host with scipy and is not timed).  Timing only."""
+    import scipy.sparse as sp
+    r_T, dims = datagen.MOVIE_SHAPE
+    tables, r_T, c_T = datagen.one_hot_star(11, r_T, dims, 20)
+    to_dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    srcs = [(il.CSR(to_dev(t.rowptr), to_dev(t.col), to_dev(t.val), (t.rows, t.cols)), to_dev(t.row_idx), t.col_map)
+            for t in tables]
+    plan = il.ilargi_plan_create(srcs, r_T, c_T, max_cx=1)
+    joined = sp.hstack([sp.csr_matrix((t.val, t.col, t.rowptr), shape=(t.rows, t.cols))[t.row_idx] for t in tables],
+                       format="csr")
+    joined.sort_indices()
+    Tm = il.CSR(to_dev(joined.indptr.astype(np.int32)), to_dev(joined.indices.astype(np.int32)),
+                to_dev(joined.data.astype(np.float32)), (r_T, c_T))
+    mplan = il.ilargi_plan_create([(Tm, None, np.arange(c_T, dtype=np.int32))], r_T, c_T, max_cx=1)
+    g = torch.Generator(device="cuda").manual_seed(3)
+    x = torch.randn((c_T, 1), device="cuda", generator=g)
+    yv = torch.randn(r_T, device="cuda", generator=g)
+    lr = torch.full((1,), 1e-3, device="cuda")
+    loss = torch.zeros(1, device="cuda")
+    o1 = torch.empty((r_T, 1), device="cuda")
+    o2 = torch.empty((c_T, 1), device="cuda")
+    out = {"r_T": r_T, "c_T": c_T, "stored_entries": {"factorized": int(sum(t.val.size for t in tables)),
+                                                        "materialized": int(joined.nnz)}}
+    for name, fn in (("lmm_c1", lambda pl, W: il.ilargi_lmm(pl, x, o1)),
+                     ("tmm_c1", lambda pl, W: il.ilargi_tmm(pl, yv, o2)),
+                     ("gd", lambda pl, W: il.ilargi_gd_step(pl, il.LINEAR, W, yv, lr, loss))):
+        Wf, Wm = torch.zeros((c_T, 1), device="cuda"), torch.zeros((c_T, 1), device="cuda")
+        t_f = time_loop(torch, lambda: fn(plan, Wf), 20)
+        t_m = time_loop(torch, lambda: fn(mplan, Wm), 10)
+        out[name] = {"factorized_us": round(t_f * 1e6, 1), "materialized_us": round(t_m * 1e6, 1),
+                     "speedup": round(t_m / t_f, 2)}
+    return out
+
+
 def wide_batch(il, torch, datagen, dev):
     """The batched hyper-parameter workload (256 linear regressions at once on the same schema, seed 4):
     gradient-descent iterations/s and matrix-core utilisation, float32 and bfloat16 inputs, factorized vs
@@ -582,10 +621,13 @@ def main() -> int:
     del plan, ops, keep, Tm
     torch.cuda.empty_cache()
     sparse = None
+    onehot = None
     if not args.no_wide:
         wide = wide_batch(il, torch, datagen, dev)
         torch.cuda.empty_cache()
         sparse = sparse_tables(il, torch, datagen, dev)
+        torch.cuda.empty_cache()
+        onehot = one_hot_tables(il, torch, datagen, dev)
         torch.cuda.empty_cache()
     configs = None if args.no_configs else other_configs(il, torch, datagen, records)
 
@@ -622,6 +664,7 @@ def main() -> int:
         "scalar_ops": scalar,
         "kmeans_gnmf": models,
         "sparse_tables": sparse,
+        "one_hot_tables": onehot,
         "chooser": chooser_summary(records),
         "wide_batch": wide,
         "other_configs": configs,

@@ -29,7 +29,8 @@ import numpy as np
 
 __all__ = [
     "Source", "Schema", "rng_for", "star_schema", "config0", "config1", "config2", "config3",
-    "config4", "tiny_random_schema", "bounded_zipf_keys", "finish_labels", "CONFIG1_GRID",
+    "config4", "tiny_random_schema", "bounded_zipf_keys", "finish_labels", "CONFIG1_GRID", "sparsify",
+    "OneHotTable", "one_hot_star", "MOVIE_SHAPE",
 ]
 
 
@@ -239,6 +240,55 @@ def sparsify(schema: Schema, p: float, seed: int) -> Schema:
     out = Schema(sources, schema.r_T, schema.c_T, name=f"{schema.name}_p{p}")
     out.extras.update(schema.extras)
     return out
+
+
+@dataclass
+class OneHotTable:
+    """A dimension table of one-hot encoded attributes in compressed sparse rows, with the rows of the target table
+    that join each of its rows (``row_idx``) and its block of target columns (``col_map``)."""
+    rowptr: np.ndarray                  # int32 [rows + 1]
+    col: np.ndarray                     # int32 [nnz], ascending within a row
+    val: np.ndarray                     # float32 [nnz]
+    rows: int
+    cols: int
+    row_idx: np.ndarray                 # int32 [r_T]
+    col_map: np.ndarray                 # int32 [cols]
+
+    def dense(self) -> np.ndarray:
+        D = np.zeros((self.rows, self.cols), dtype=np.float32)
+        r = np.repeat(np.arange(self.rows), np.diff(self.rowptr))
+        D[r, self.col] = self.val
+        return D
+
+
+# Shape of the "Movie" row of the paper's table of real data sets (Tab. 4): r_T, then (rows, columns) of the two
+# joined tables.  The data themselves are not available here; one_hot_star draws a stand-in of this shape.
+MOVIE_SHAPE = (1_000_000, ((6_040, 9_510), (3_710, 3_840)))
+
+
+def one_hot_star(seed: int, r_T: int, dims, attributes: int = 20):
+    """Joined dimension tables of one-hot style: every row of a table has ``attributes`` stored entries, one in each
+    of ``attributes`` equal column ranges (a categorical attribute each), all of value 1 except the last, which is
+    N(0,1) (a numeric attribute).  Every target row joins one uniformly drawn row of every table.  Target columns are the tables'
+    columns side by side; there is no entity table.
+    Draw order per table: the column inside each range (rows x attributes integers), the numeric values, the keys."""
+    rng = rng_for(seed)
+    tables = []
+    c0 = 0
+    for rows, cols in dims:
+        a = min(attributes, cols)
+        edges = np.linspace(0, cols, a + 1).astype(np.int64)
+        width = np.diff(edges)
+        pick = (rng.random((rows, a)) * width[None, :]).astype(np.int64)
+        col = (edges[:-1][None, :] + np.minimum(pick, width[None, :] - 1)).astype(np.int32)
+        val = np.ones((rows, a), dtype=np.float32)
+        val[:, -1] = _normal32(rng, rows)
+        rowptr = (np.arange(rows + 1, dtype=np.int64) * a).astype(np.int32)
+        fk = rng.integers(0, rows, r_T).astype(np.int32)
+        tables.append(OneHotTable(rowptr, col.reshape(-1), val.reshape(-1), rows, cols, fk,
+                                  np.arange(c0, c0 + cols, dtype=np.int32)))
+        c0 += cols
+    return tables, r_T, c0
 
 
 def finish_labels(kind: str, Tw: np.ndarray, noise: np.ndarray) -> np.ndarray:

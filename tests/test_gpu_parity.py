@@ -877,6 +877,29 @@ def test_sparse_table_wider_than_the_dense_limit(il):
     assert ei.value.status == il.ERR_UNSUPPORTED
 
 
+def test_one_hot_star_without_entity_table(il):
+    # two joined one-hot style tables side by side and nothing else (the shape of the paper's real data sets,
+    # Tab. 4, scaled down): no identity source to fuse, both tables in sparse rows
+    tables, r_T, c_T = datagen.one_hot_star(9, 20_011, ((604, 951), (371, 384)), 20)
+    sch = datagen.Schema([datagen.Source(t.dense(), t.row_idx, t.col_map) for t in tables], r_T, c_T)
+    tg = oracle.Target(sch)
+    srcs = [(il.CSR(dev(t.rowptr), dev(t.col), dev(t.val), (t.rows, t.cols)), dev(t.row_idx), t.col_map) for t in tables]
+    plan = il.ilargi_plan_create(srcs, r_T, c_T, max_cx=4)
+    assert np.array_equal(il.ilargi_materialize(plan).cpu().numpy().view(np.uint32), tg.T32.view(np.uint32))
+    rng = datagen.rng_for(1304)
+    for cx in (1, 4):
+        X = rng.standard_normal((c_T, cx)).astype(np.float32)
+        Y = rng.standard_normal((r_T, cx)).astype(np.float32)
+        assert rel(il.ilargi_lmm(plan, dev(X)).cpu().numpy(), oracle.lmm(tg, X)) < OP_TOL
+        assert rel(il.ilargi_tmm(plan, dev(Y)).cpu().numpy(), oracle.tmm(tg, Y)) < OP_TOL
+    w_star = rng.standard_normal(c_T)
+    y = datagen.finish_labels("linear", oracle.lmm(tg, w_star.reshape(-1, 1)), 0.01 * rng.standard_normal(r_T))
+    W, L = _run_gd(il, plan, il.LINEAR, y, [0.02], 6, c_T)
+    W_ref, L_ref = oracle.gd(tg, "linear", y, np.zeros((c_T, 1)), [0.02], 6)
+    assert rel(W, W_ref) < GD_TOL
+    np.testing.assert_allclose(L, L_ref, rtol=2e-4)
+
+
 def test_invalid_sparse_rows_are_reported(il):
     good = il.CSR.from_dense(np.array([[1.0, 0.0, 2.0], [0.0, 3.0, 0.0]], dtype=np.float32))
     cm = np.arange(3, dtype=np.int32)
