@@ -462,7 +462,8 @@ def stream_probe(il, torch):
     dst = torch.empty(n, device="cuda")
     sink = torch.empty(65536, device="cuda")
     res = {}
-    for kind, name, factor in ((1, "read", 1), (2, "write", 1), (0, "copy", 2)):
+    for kind, name, factor in ((1, "read", 1), (2, "write", 1), (0, "copy", 2), (4, "write_nontemporal", 1),
+                               (3, "copy_nontemporal", 2)):
         d = sink if kind == 1 else dst
         t = time_loop(torch, lambda: il.ilargi_stream_probe(kind, d, src, n, 8192), 10)
         res[f"{name}_GBps"] = round(factor * n * 4 / t / 1e9, 1)

@@ -20,7 +20,6 @@ namespace {
 typedef float v4f __attribute__((ext_vector_type(4)));
 
 constexpr int kGsThreads = 1024;
-constexpr int kGsWaves = kGsThreads / kWave;
 constexpr int kGsRows = 32;      // rows staged per step
 constexpr int kGsPW = 6;         // tiles per wavefront: 16 x 6 = 96 >= 91 tiles of a 208-column table
 constexpr int kGsMaxTiles = 13;  // 16-column tiles per side

@@ -281,7 +281,7 @@ __global__ __launch_bounds__(kBlock) void finalize_kernel(FinArgs a, int c_T) {
     if constexpr (MODE == 1) {
       float4 s = block_sum4(reinterpret_cast<const float4*>(a.loss_partial), 1, a.n_loss_partial, scratch);
       float sv[4] = {s.x, s.y, s.z, s.w};
-      if (threadIdx.x < a.ncols) a.loss[a.col0 + threadIdx.x] = sv[threadIdx.x] * a.loss_scale;
+      if ((int)threadIdx.x < a.ncols) a.loss[a.col0 + threadIdx.x] = sv[threadIdx.x] * a.loss_scale;
     }
     return;
   }
@@ -292,7 +292,7 @@ __global__ __launch_bounds__(kBlock) void finalize_kernel(FinArgs a, int c_T) {
     float4 s = block_sum4(reinterpret_cast<const float4*>(a.s[k].partial) + j, a.s[k].ck, a.s[k].nblocks, scratch);
     acc[0] += s.x; acc[1] += s.y; acc[2] += s.z; acc[3] += s.w;
   }
-  if (threadIdx.x < a.ncols) {
+  if ((int)threadIdx.x < a.ncols) {
     const int n = threadIdx.x;
     float* o = a.out + (int64_t)t * a.ldo + a.col0 + n;
     if constexpr (MODE == 0) *o = acc[n];

@@ -233,3 +233,20 @@ def test_gnmf_sparse_sources_and_limits(il):
         il.ilargi_gnmf_step(big, torch.ones((small.r_T, 65), device="cuda"), torch.ones((small.c_T, 65), device="cuda"))
     with pytest.raises(RuntimeError, match="WORKSPACE"):
         il.ilargi_gnmf_step(plan, torch.ones((tg.r_T, 65), device="cuda"), torch.ones((tg.c_T, 65), device="cuda"))
+
+
+def test_models_on_a_target_table_without_rows(il):
+    # r_T = 0: KMeans leaves the centroids where they are and reports empty clusters; the NMF round multiplies
+    # H by 0 / tiny (the numerator T^T W is zero), and W has no rows to update
+    D = torch.zeros((0, 3), device="cuda")
+    plan = il.ilargi_plan_create([(D, None, np.arange(3, dtype=np.int32))], 0, 3, max_cx=2)
+    C0 = torch.tensor([[1.0, 2.0], [3.0, 4.0], [5.0, 6.0]], device="cuda")
+    C = C0.clone()
+    counts = torch.full((2,), -1, dtype=torch.int32, device="cuda")
+    assign = torch.zeros(0, dtype=torch.int32, device="cuda")
+    il.ilargi_kmeans_step(plan, C, assign, counts)
+    assert torch.equal(C, C0) and counts.cpu().tolist() == [0, 0]
+    W = torch.zeros((0, 2), device="cuda")
+    Ht = torch.ones((3, 2), device="cuda")
+    il.ilargi_gnmf_step(plan, W, Ht)
+    assert torch.count_nonzero(Ht).item() == 0           # H o (W^T T) / max(W^T W H, tiny) with W^T T = 0

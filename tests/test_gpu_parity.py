@@ -851,7 +851,7 @@ def test_sparse_table_wider_than_the_dense_limit(il):
     sch = datagen.Schema([datagen.Source(S, None, np.arange(c_S, dtype=np.int32)),
                           datagen.Source(R, fk, np.arange(c_S, c_T, dtype=np.int32))], r_T, c_T)
     tg = oracle.Target(sch)
-    srcs = il.schema_to_device(sch, sparse=[False, True])
+    srcs = il.schema_to_device(sch, sparse=[1])
     plan = il.ilargi_plan_create(srcs, r_T, c_T, max_cx=4)
     assert np.array_equal(il.ilargi_materialize(plan).cpu().numpy().view(np.uint32), tg.T32.view(np.uint32))
     for cx in (1, 3, 4):
@@ -873,7 +873,7 @@ def test_sparse_table_wider_than_the_dense_limit(il):
     assert ei.value.status == il.ERR_UNSUPPORTED
     R[7, :2100] = 1.0
     with pytest.raises(il.IlargiError) as ei:
-        il.ilargi_plan_create(il.schema_to_device(sch, sparse=[False, True]), r_T, c_T, max_cx=1)
+        il.ilargi_plan_create(il.schema_to_device(sch, sparse=[1]), r_T, c_T, max_cx=1)
     assert ei.value.status == il.ERR_UNSUPPORTED
 
 
