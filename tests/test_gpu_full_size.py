@@ -164,7 +164,7 @@ def test_config1_scalar_operators(il):
 
 
 def test_config2_logistic_regression(il):
-    sch, tg, plan, y = Problem.get(il, "config2", 4, "logistic")
+    sch, tg, plan, y = Problem.get(il, "config2", 16, "logistic")
     gold = np.load(os.path.join(GOLDEN, "config2_gd.npz"))
     assert sha(y) == str(gold["y_sha256"])
     cnt = np.bincount(sch.sources[2].row_idx, minlength=sch.sources[2].rows)
@@ -175,8 +175,8 @@ def test_config2_logistic_regression(il):
 
 
 def test_config2_operators(il):
-    sch, tg, plan, _ = Problem.get(il, "config2", 4, "logistic")
-    check_ops(il, sch, tg, plan, [1, 3])
+    sch, tg, plan, _ = Problem.get(il, "config2", 16, "logistic")
+    check_ops(il, sch, tg, plan, [1, 3, 16])
     rowptr, perm = il.ilargi_plan_inverse_index(plan, 2)
     idx = sch.sources[2].row_idx
     assert np.array_equal(np.diff(rowptr), np.bincount(idx, minlength=sch.sources[2].rows))
@@ -185,7 +185,7 @@ def test_config2_operators(il):
 
 # ------------------------------------------------------------------ configuration 3 (union with overlap)
 def test_config3_gram_and_linear_regression(il):
-    sch, tg, plan, y = Problem.get(il, "config3", 4, "linear")
+    sch, tg, plan, y = Problem.get(il, "config3", 16, "linear")
     gold = np.load(os.path.join(GOLDEN, "config3_gd.npz"))
     assert sha(y) == str(gold["y_sha256"])
     G = il.ilargi_crossprod(plan).cpu().numpy()
@@ -196,8 +196,8 @@ def test_config3_gram_and_linear_regression(il):
 
 
 def test_config3_operators_and_join(il):
-    sch, tg, plan, _ = Problem.get(il, "config3", 4, "linear")
-    check_ops(il, sch, tg, plan, [1, 4])
+    sch, tg, plan, _ = Problem.get(il, "config3", 16, "linear")
+    check_ops(il, sch, tg, plan, [1, 4, 16])
     T = il.ilargi_materialize(plan)
     assert torch.equal(T.cpu().view(torch.int32), torch.from_numpy(tg.T32).view(torch.int32))
 
