@@ -292,6 +292,105 @@ hipError_t launch_mode(const LmmArgs& a, int mode, bool fuseg, int grid, size_t 
   return hipGetLastError();
 }
 
+// Plain product  P = D (M^T X)  for at most four operand columns, float4 rows of at most 64 float4: the role of the
+// kernel above without gathers and epilogues, as a streaming kernel without LDS or workgroup barriers.
+// L = 2^k >= ck / 4 lanes share a row (a wavefront load covers 64 / L whole rows), eight loads per lane are in
+// flight, each lane keeps its operand values in registers.  The eight partial sums of a lane are reduced across
+// the L lanes with a butterfly that halves the number of live values at each of its first three steps (a lane
+// pair exchanges one half of the values each way), ten shuffles per operand column instead of forty-eight.
+constexpr int kDotU = 8;
+
+template <int CT>
+__global__ __launch_bounds__(kBlock) void lmm_rowdot_kernel(LmmArgs a, int logL) {
+  const int tid = threadIdx.x, lane = tid % kWave;
+  const int L = 1 << logL;                                   // 8 <= L <= 64
+  const int cg = lane & (L - 1);                             // float4 column group of this lane
+  const int sub = lane >> logL;                              // row of the wavefront load
+  const int rp = kWave >> logL;                              // rows per wavefront load
+  const int nvec = a.ck / 4;
+  float4 x[CT];
+#pragma unroll
+  for (int n = 0; n < CT; ++n) x[n] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+  if (cg < nvec) {
+    int t[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) t[e] = a.colmap[4 * cg + e];
+#pragma unroll
+    for (int n = 0; n < CT; ++n) {
+      if (n < a.ncols) {
+        x[n].x = t[0] >= 0 ? a.X[(int64_t)t[0] * a.ldx + a.col0 + n] : 0.0f;
+        x[n].y = t[1] >= 0 ? a.X[(int64_t)t[1] * a.ldx + a.col0 + n] : 0.0f;
+        x[n].z = t[2] >= 0 ? a.X[(int64_t)t[2] * a.ldx + a.col0 + n] : 0.0f;
+        x[n].w = t[3] >= 0 ? a.X[(int64_t)t[3] * a.ldx + a.col0 + n] : 0.0f;
+      }
+    }
+  }
+  const int64_t rows_per_step = (int64_t)rp * kDotU;
+  const int64_t wave0 = ((int64_t)blockIdx.x * (kBlock / kWave) + tid / kWave) * rows_per_step;
+  const int64_t stride = (int64_t)gridDim.x * (kBlock / kWave) * rows_per_step;
+  // which of the eight rows of a step this lane reports after the reduction: bits of the lane number at the
+  // three halving steps (offsets L/2, L/4, L/8)
+  const int o1 = L >> 1, o2 = L >> 2, o3 = L >> 3;
+  const bool h1 = (cg & o1) != 0, h2 = (cg & o2) != 0, h3 = (cg & o3) != 0;
+  const int urow = (h1 ? 4 : 0) + (h2 ? 2 : 0) + (h3 ? 1 : 0);
+  for (int64_t base = wave0; base < a.r_out; base += stride) {
+    float4 v[kDotU];
+#pragma unroll
+    for (int u = 0; u < kDotU; ++u) {
+      const int64_t i = base + (int64_t)u * rp + sub;
+      v[u] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+      if (cg < nvec && i < a.d_rows && i < a.r_out) v[u] = *reinterpret_cast<const float4*>(a.D + i * a.ck + 4 * cg);
+    }
+#pragma unroll
+    for (int n = 0; n < CT; ++n) {
+      float s8[kDotU];
+#pragma unroll
+      for (int u = 0; u < kDotU; ++u)
+        s8[u] = fmaf(v[u].x, x[n].x, fmaf(v[u].y, x[n].y, fmaf(v[u].z, x[n].z, v[u].w * x[n].w)));
+      // offset L/2: the lower lane of a pair keeps rows 0..3, the upper one rows 4..7
+      float s4[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float keep = h1 ? s8[4 + j] : s8[j];
+        const float send = h1 ? s8[j] : s8[4 + j];
+        s4[j] = keep + __shfl_xor(send, o1);
+      }
+      float s2[2];
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const float keep = h2 ? s4[2 + j] : s4[j];
+        const float send = h2 ? s4[j] : s4[2 + j];
+        s2[j] = keep + __shfl_xor(send, o2);
+      }
+      float s1;
+      {
+        const float keep = h3 ? s2[1] : s2[0];
+        const float send = h3 ? s2[0] : s2[1];
+        s1 = keep + __shfl_xor(send, o3);
+      }
+      for (int o = o3 >> 1; o >= 1; o >>= 1) s1 += __shfl_xor(s1, o);
+      // lanes whose low bits (below L/8) are zero hold the sum of row `urow` of their wavefront-load row `sub`
+      const int64_t i = base + (int64_t)urow * rp + sub;
+      if ((cg & (o3 - 1)) == 0 && n < a.ncols && i < a.r_out) a.out[i * a.ldo + a.col0 + n] = s1;
+    }
+  }
+}
+
+hipError_t launch_rowdot(const LmmArgs& a, hipStream_t st) {
+  const int nvec = a.ck / 4;
+  int logL = 3;
+  while ((1 << logL) < nvec) ++logL;
+  const int rp = kWave >> logL;
+  const int64_t rows_per_block = (int64_t)rp * kDotU * (kBlock / kWave);
+  int64_t grid = (a.r_out + rows_per_block - 1) / rows_per_block;
+  if (grid > 4096) grid = 4096;
+  const int ct = a.ncols <= 1 ? 1 : (a.ncols <= 2 ? 2 : 4);
+  if (ct == 1) lmm_rowdot_kernel<1><<<(int)grid, kBlock, 0, st>>>(a, logL);
+  else if (ct == 2) lmm_rowdot_kernel<2><<<(int)grid, kBlock, 0, st>>>(a, logL);
+  else lmm_rowdot_kernel<4><<<(int)grid, kBlock, 0, st>>>(a, logL);
+  return hipGetLastError();
+}
+
 template <int VEC>
 hipError_t launch_ct(const LmmArgs& a, int mode, bool fuseg, int grid, hipStream_t st) {
   int ct = a.ncols <= 1 ? 1 : (a.ncols <= 2 ? 2 : 4);
@@ -333,6 +432,8 @@ hipError_t launch_lmm_rows(const LmmArgs& a, int vec, int mode, hipStream_t st, 
   int grid = lmm_grid(a.r_out, a.logL, fuseg);
   if (grid_out) *grid_out = grid;
   if (a.r_out <= 0) return hipSuccess;
+  if (mode == 0 && !fuseg && a.g.n == 0 && a.D != nullptr && vec == 4 && a.ck >= 4 && a.ck <= 256 && a.ncols <= kNarrowCT)
+    return launch_rowdot(a, st);
   switch (vec) {
     case 4: return launch_ct<4>(a, mode, fuseg, grid, st);
     case 2: return launch_ct<2>(a, mode, fuseg, grid, st);
