@@ -246,6 +246,8 @@ hipError_t launch_mat_scatter(const SparseArgs* sparse, const float* D, int64_t 
                               const int32_t* idx, int64_t ident_rows, float* T, int64_t r_T, int c_T, hipStream_t st);
 hipError_t launch_segsum(const SegArgs& a, hipStream_t st);
 hipError_t launch_colred(const ColredArgs& a, int nblocks, hipStream_t st);
+bool lmm_flat_supported(const LmmArgs& a, int vec, bool fuseg);
+hipError_t launch_lmm_flat(const LmmArgs& a, int mode, bool fuseg, hipStream_t st, int* grid_out);
 bool colred_segsum_supported(const ColredArgs& c, const SegArgs& s);
 hipError_t launch_colred_segsum(const ColredArgs& c, int nb_c, const SegArgs& s, hipStream_t st);
 hipError_t launch_finalize(const FinArgs& a, int c_T, int mode, hipStream_t st);
