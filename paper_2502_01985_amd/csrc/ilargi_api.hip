@@ -505,13 +505,8 @@ ilargi_status_t run_tred(ilargi_plan* pl, TredArgs& g, float* block, const char*
   if (elems <= 0) return ILARGI_OK;
   if (!bf16 && gram_sym_supported(g) && elems <= pl->lay.gpartial_floats) {
     // diagonal Gram block of a table with 65..208 columns: upper-triangle tiles only
-    g.partial = pl->at<float>(pl->lay.o_gpartial);
-    int nch = 0;
-    {
-      TraceScope ts(pl, tag, tag_k, st);
-      HIP_TRY(launch_gram_sym(g, pl->lay.gpartial_floats, st, &nch));
-    }
-    HIP_TRY(launch_tred_reduce(g.partial, nch, elems, block, st));
+    TraceScope ts(pl, tag, tag_k, st);
+    HIP_TRY(launch_gram_sym(g, pl->at<float>(pl->lay.o_gpartial), pl->lay.gpartial_floats, block, st));
     return ILARGI_OK;
   }
   // row chunks: whole rounds of the device's workgroup slots (every workgroup does the same work, so a

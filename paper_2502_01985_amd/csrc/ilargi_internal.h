@@ -259,7 +259,7 @@ hipError_t launch_tmm_join(const TmmJoinArgs& a, int64_t partial_floats, hipStre
 bool gram_star_supported(int cs);
 hipError_t launch_gram_star(const GramStarArgs& a, int vec, int max_grid, hipStream_t st, int* grid_out);
 bool gram_sym_supported(const TredArgs& a);
-hipError_t launch_gram_sym(TredArgs& a, int64_t partial_floats, hipStream_t st, int* nchunks_out);
+hipError_t launch_gram_sym(TredArgs& a, float* partial, int64_t partial_floats, float* block, hipStream_t st);
 hipError_t launch_tred(const TredArgs& a, int nchunks, bool bf16, hipStream_t st);
 void tred_occupancy(const TredArgs& a, bool bf16, int* slots, int* tiles);
 hipError_t launch_tred_reduce(const float* partial, int nchunks, int64_t elems, float* block, hipStream_t st);

@@ -3,11 +3,12 @@
 //
 // C is symmetric, so only the 16 x 16 tiles (ci, cj), ci <= cj, are formed: for 200 columns that is 91 tiles
 // instead of the 169 of the full square.  A workgroup of sixteen wavefronts stages 32 whole rows in LDS (coalesced
-// float4 loads, every value fetched once), and each wavefront owns up to six tiles: for a quad of rows it
-// reads the 16 columns of tile-row ci (times the row weight) and of tile-column cj from LDS and issues one
-// MFMA 16x16x4 per tile.  In that MFMA both operands have the same layout (lane 16 q + s holds row q, column
-// s of the 16), which is why one staged copy serves both sides.  Workgroups own row chunks; their partial
-// blocks are added afterwards in chunk order, so the result is reproducible.
+// float4 loads, every value fetched once), and each wavefront owns up to six tiles: for a quad of rows it reads
+// the 16 columns of tile-row ci (times the row weight) and of tile-column cj from LDS and issues one MFMA 16x16x4
+// per tile.
+// In that MFMA both operands have the same layout (lane 16 q + s holds row q, column s of the 16), which is why
+// one staged copy serves both sides.  Workgroups own row chunks; each leaves its tiles packed (a tile's register r
+// of all 64 lanes is one 256-byte run), and a second kernel adds the chunks in order and puts the sums in place.
 #include <algorithm>
 #include <type_traits>
 
@@ -21,36 +22,38 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 
 constexpr int kGsThreads = 1024;
 constexpr int kGsRows = 32;      // rows staged per step
+constexpr int kGsMaxTiles = 13;  // 16-column tiles of D
 constexpr int kGsPW = 6;         // tiles per wavefront: 16 x 6 = 96 >= 91 tiles of a 208-column table
-constexpr int kGsMaxTiles = 13;  // 16-column tiles per side
 
 template <bool VEC4>
 __global__ __launch_bounds__(kGsThreads) void gram_sym_kernel(TredArgs a, int ntile, int ldr) {
+  constexpr int PW = kGsPW;
   extern __shared__ float lds[];
   float* Rs = lds;                       // [kGsRows][ldr]
   float* Ws = lds + kGsRows * ldr;       // [kGsRows] row weights (0 beyond the chunk)
   const int tid = threadIdx.x, lane = tid % kWave;
   const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);   // uniform: the tile list lives in scalar registers
   const int s = lane % 16, q = lane / 16;
-  // this wavefront's tiles: pairs (ci, cj), ci <= cj, numbered row by row
-  // (slots beyond the last pair repeat tile (0, 0) and are not written: the inner loop stays free of branches)
-  int ci[kGsPW], cj[kGsPW];
-  bool live_tile[kGsPW];
+  const int ntot = ntile * (ntile + 1) / 2;
+  // this wavefront's tiles: the pairs (ci, cj), ci <= cj, numbered row by row; slots beyond the last tile repeat
+  // tile (0, 0) and are not written: the inner loop stays free of branches
+  int offa[PW], offb[PW];
+  bool live_tile[PW];
   {
-    int p = wave * kGsPW, i = 0;
+    int p = wave * PW, i = 0;
     while (i < ntile && p >= ntile - i) { p -= ntile - i; ++i; }
     int j = i + p;
 #pragma unroll
-    for (int u = 0; u < kGsPW; ++u) {
-      live_tile[u] = i < ntile;
-      ci[u] = live_tile[u] ? i : 0;
-      cj[u] = live_tile[u] ? j : 0;
+    for (int u = 0; u < PW; ++u) {
+      live_tile[u] = wave * PW + u < ntot;
+      offa[u] = live_tile[u] ? 16 * i : 0;
+      offb[u] = live_tile[u] ? 16 * j : 0;
       if (++j >= ntile) { ++i; j = i; }
     }
   }
-  v4f acc[kGsPW];
+  v4f acc[PW];
 #pragma unroll
-  for (int u = 0; u < kGsPW; ++u) acc[u] = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
+  for (int u = 0; u < PW; ++u) acc[u] = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
 
   const int64_t t_lo = (int64_t)blockIdx.x * a.rows_per_block;
   const int64_t t_hi = min(t_lo + a.rows_per_block, a.n_rows);
@@ -60,8 +63,8 @@ __global__ __launch_bounds__(kGsThreads) void gram_sym_kernel(TredArgs a, int nt
   typedef typename std::conditional<VEC4, float4, float>::type SVal;
   constexpr int NV = VEC4 ? (kGsRows * kGsMaxTiles * 4 + kGsThreads - 1) / kGsThreads
                           : (kGsRows * kGsMaxTiles * 16 + kGsThreads - 1) / kGsThreads;
-  const int spr = VEC4 ? width / 4 : width;   // slots per row
-  const int live = VEC4 ? a.ca / 4 : a.ca;    // slots inside the table
+  const int spr = VEC4 ? width / 4 : width;          // slots per row
+  const int live = VEC4 ? a.ca / 4 : a.ca;           // slots inside the table
   SVal sv[NV];
   float wv = 0.0f;
   auto fetch = [&](int64_t t0) {
@@ -100,23 +103,54 @@ __global__ __launch_bounds__(kGsThreads) void gram_sym_kernel(TredArgs a, int nt
       const float* row = Rs + (rq * 4 + q) * ldr + s;
       const float w = Ws[rq * 4 + q];
 #pragma unroll
-      for (int u = 0; u < kGsPW; ++u) {
-        const float av = row[16 * ci[u]] * w;
-        const float bv = row[16 * cj[u]];
+      for (int u = 0; u < PW; ++u) {
+        const float av = row[offa[u]] * w;
+        const float bv = row[offb[u]];
         acc[u] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bv, acc[u], 0, 0, 0);
       }
     }
   }
-  // tile (ci, cj): register r of lane 16 q + s is C[16 ci + 4 q + r][16 cj + s]
-  float* out = a.partial + (int64_t)blockIdx.x * a.ca * a.cb;
+  // packed: tile t of this workgroup, register r, lane
+  float* out = a.partial + (int64_t)blockIdx.x * ntot * 256;
 #pragma unroll
-  for (int u = 0; u < kGsPW; ++u) {
+  for (int u = 0; u < PW; ++u) {
     if (!live_tile[u]) continue;
+    const int t = wave * PW + u;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int j = 16 * ci[u] + 4 * q + r, n = 16 * cj[u] + s;
-      if (j < a.ca && n < a.cb) out[(int64_t)j * a.cb + n] = acc[u][r];
-    }
+    for (int r = 0; r < 4; ++r) out[(t * 4 + r) * kWave + lane] = acc[u][r];
+  }
+}
+
+// Adds the chunks of one quarter tile (register r of a tile: 64 values) in order: sixteen thread groups stride the
+// chunks, then the groups are added in order.  Tile t, register r, lane 16 q + s is element (4 q + r, s) of tile
+// (ci, cj).
+__global__ __launch_bounds__(kGsThreads) void gram_tile_reduce_kernel(const float* __restrict__ partial, int nchunks, int ntile,
+                                                                      int ca, float* __restrict__ block) {
+  __shared__ float red[16][kWave];
+  const int ntot = ntile * (ntile + 1) / 2;
+  const int t = blockIdx.x / 4, r = blockIdx.x % 4;
+  const int lane = threadIdx.x % kWave, cg = threadIdx.x / kWave;
+  const float* src = partial + ((int64_t)t * 4 + r) * kWave + lane;
+  const int64_t stride = (int64_t)ntot * 256;
+  float acc = 0.0f;
+  int c = cg;
+  for (; c + 3 * 16 < nchunks; c += 4 * 16) {
+    const float v0 = src[(int64_t)c * stride], v1 = src[(int64_t)(c + 16) * stride];
+    const float v2 = src[(int64_t)(c + 32) * stride], v3 = src[(int64_t)(c + 48) * stride];
+    acc += v0; acc += v1; acc += v2; acc += v3;
+  }
+  for (; c < nchunks; c += 16) acc += src[(int64_t)c * stride];
+  red[cg][lane] = acc;
+  __syncthreads();
+  if (threadIdx.x < kWave) {
+    float sum = 0.0f;
+#pragma unroll
+    for (int g = 0; g < 16; ++g) sum += red[g][lane];
+    const int s = lane % 16, q = lane / 16;
+    int p = t, i = 0;
+    while (p >= ntile - i) { p -= ntile - i; ++i; }
+    const int j = 16 * i + 4 * q + r, n = 16 * (i + p) + s;
+    if (j < ca && n < ca) block[(int64_t)j * ca + n] = sum;
   }
 }
 
@@ -129,10 +163,9 @@ bool gram_sym_supported(const TredArgs& a) {
 }
 
 // Splits the rows into chunks (one workgroup each, about one per compute unit, a multiple of the staging step,
-// within the caller's partial buffer of partial_floats), sets a.rows_per_block and launches; the chunk count
-// comes back for the ordered sum of the partial blocks.
-hipError_t launch_gram_sym(TredArgs& a, int64_t partial_floats, hipStream_t st, int* nchunks_out) {
-  if (nchunks_out) *nchunks_out = 0;
+// within the caller's partial buffer of partial_floats), launches the tile kernel and the ordered sum of the
+// chunks.  block receives the upper-triangle tiles of D^T diag(w) D (ca x ca).
+hipError_t launch_gram_sym(TredArgs& a, float* partial, int64_t partial_floats, float* block, hipStream_t st) {
   if (!gram_sym_supported(a) || a.n_rows <= 0) return hipErrorInvalidValue;
   static const int cus = [] {
     int dev = 0;
@@ -141,18 +174,23 @@ hipError_t launch_gram_sym(TredArgs& a, int64_t partial_floats, hipStream_t st, 
       return (int)prop.multiProcessorCount;
     return 256;
   }();
-  int64_t nch = std::min<int64_t>(cus, partial_floats / ((int64_t)a.ca * a.cb));
+  const int ntile = (a.ca + 15) / 16;
+  const int ntot = ntile * (ntile + 1) / 2;
+  int64_t nch = std::min<int64_t>(cus, partial_floats / ((int64_t)ntot * 256));
+  if (nch < 1) return hipErrorInvalidValue;
   nch = std::max<int64_t>(1, std::min<int64_t>(nch, (a.n_rows + kGsRows - 1) / kGsRows));
   a.rows_per_block = ((a.n_rows + nch - 1) / nch + kGsRows - 1) / kGsRows * kGsRows;
   nch = (a.n_rows + a.rows_per_block - 1) / a.rows_per_block;
-  const int ntile = (a.ca + 15) / 16;
+  a.partial = partial;
   int ldr = ntile * 16;
   if (ldr % 32 == 0) ldr += 16;          // rows q and q + 1 of a quad on different LDS banks
   const bool vec4 = a.ca % 4 == 0 && a.lda % 4 == 0 && reinterpret_cast<uintptr_t>(a.A) % 16 == 0;
   const size_t lds_bytes = ((size_t)kGsRows * ldr + kGsRows) * sizeof(float);
   if (vec4) hipLaunchKernelGGL(gram_sym_kernel<true>, dim3((unsigned)nch), dim3(kGsThreads), lds_bytes, st, a, ntile, ldr);
   else hipLaunchKernelGGL(gram_sym_kernel<false>, dim3((unsigned)nch), dim3(kGsThreads), lds_bytes, st, a, ntile, ldr);
-  if (nchunks_out) *nchunks_out = (int)nch;
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  gram_tile_reduce_kernel<<<4 * ntot, kGsThreads, 0, st>>>(partial, (int)nch, ntile, a.ca, block);
   return hipGetLastError();
 }
 
