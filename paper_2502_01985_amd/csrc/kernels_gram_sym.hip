@@ -24,10 +24,14 @@ constexpr int kGsThreads = 1024;
 constexpr int kGsRows = 32;      // rows staged per step
 constexpr int kGsMaxTiles = 13;  // 16-column tiles of D
 constexpr int kGsPW = 6;         // tiles per wavefront: 16 x 6 = 96 >= 91 tiles of a 208-column table
+constexpr int kGsLdr = 16 * kGsMaxTiles;   // LDS row stride, a constant (208 = 6.5 x 32 banks: the four rows of a quad
+                                           // fall on alternating halves of the banks) so that the row steps of the
+                                           // unrolled inner loop become immediate offsets of the LDS reads
 
 template <bool VEC4>
-__global__ __launch_bounds__(kGsThreads) void gram_sym_kernel(TredArgs a, int ntile, int ldr) {
+__global__ __launch_bounds__(kGsThreads) void gram_sym_kernel(TredArgs a, int ntile) {
   constexpr int PW = kGsPW;
+  constexpr int ldr = kGsLdr;
   extern __shared__ float lds[];
   float* Rs = lds;                       // [kGsRows][ldr]
   float* Ws = lds + kGsRows * ldr;       // [kGsRows] row weights (0 beyond the chunk)
@@ -83,6 +87,14 @@ __global__ __launch_bounds__(kGsThreads) void gram_sym_kernel(TredArgs a, int nt
     wv = 0.0f;
     if (tid < kGsRows && t0 + tid < t_hi) wv = a.wptr ? (float)(a.wptr[t0 + tid + 1] - a.wptr[t0 + tid]) : 1.0f;
   };
+  const float* pa[PW];
+  const float* pb[PW];
+#pragma unroll
+  for (int u = 0; u < PW; ++u) {
+    pa[u] = Rs + q * ldr + s + offa[u];
+    pb[u] = Rs + q * ldr + s + offb[u];
+  }
+  const float* wq = Ws + q;
   fetch(t_lo);
   for (int64_t t0 = t_lo; t0 < t_hi; t0 += kGsRows) {
     __syncthreads();                     // the previous rows are consumed
@@ -98,14 +110,14 @@ __global__ __launch_bounds__(kGsThreads) void gram_sym_kernel(TredArgs a, int nt
     if (tid < kGsRows) Ws[tid] = wv;
     __syncthreads();
     if (t0 + kGsRows < t_hi) fetch(t0 + kGsRows);
-#pragma unroll 2
+#pragma unroll
     for (int rq = 0; rq < kGsRows / 4; ++rq) {
-      const float* row = Rs + (rq * 4 + q) * ldr + s;
-      const float w = Ws[rq * 4 + q];
+      const float w = wq[rq * 4];
 #pragma unroll
       for (int u = 0; u < PW; ++u) {
-        const float av = row[offa[u]] * w;
-        const float bv = row[offb[u]];
+        // (pa[u], pb[u] are loop-invariant lane addresses; the row step is a compile-time offset)
+        const float av = pa[u][rq * 4 * ldr] * w;
+        const float bv = pb[u][rq * 4 * ldr];
         acc[u] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bv, acc[u], 0, 0, 0);
       }
     }
@@ -182,12 +194,11 @@ hipError_t launch_gram_sym(TredArgs& a, float* partial, int64_t partial_floats, 
   a.rows_per_block = ((a.n_rows + nch - 1) / nch + kGsRows - 1) / kGsRows * kGsRows;
   nch = (a.n_rows + a.rows_per_block - 1) / a.rows_per_block;
   a.partial = partial;
-  int ldr = ntile * 16;
-  if (ldr % 32 == 0) ldr += 16;          // rows q and q + 1 of a quad on different LDS banks
+  constexpr int ldr = kGsLdr;
   const bool vec4 = a.ca % 4 == 0 && a.lda % 4 == 0 && reinterpret_cast<uintptr_t>(a.A) % 16 == 0;
   const size_t lds_bytes = ((size_t)kGsRows * ldr + kGsRows) * sizeof(float);
-  if (vec4) hipLaunchKernelGGL(gram_sym_kernel<true>, dim3((unsigned)nch), dim3(kGsThreads), lds_bytes, st, a, ntile, ldr);
-  else hipLaunchKernelGGL(gram_sym_kernel<false>, dim3((unsigned)nch), dim3(kGsThreads), lds_bytes, st, a, ntile, ldr);
+  if (vec4) hipLaunchKernelGGL(gram_sym_kernel<true>, dim3((unsigned)nch), dim3(kGsThreads), lds_bytes, st, a, ntile);
+  else hipLaunchKernelGGL(gram_sym_kernel<false>, dim3((unsigned)nch), dim3(kGsThreads), lds_bytes, st, a, ntile);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   gram_tile_reduce_kernel<<<4 * ntot, kGsThreads, 0, st>>>(partial, (int)nch, ntile, a.ca, block);
