@@ -68,9 +68,9 @@ typedef struct {
   const int32_t* col_map; /* HOST int32[cols]; copied when the plan is created */
   /* Optional: the table in compressed sparse rows instead of D (the paper keeps its matrices sparse,
    * Sec. 3.1).  With csr_rowptr != NULL, D must be NULL.  Borrowed like D.  A plan with a sparse source
-   * serves lmm, tmm, gd_step, materialize, row_sum, col_sum and the element-wise operators that keep zero
-   * at zero (which then act on csr_val, nnz values), in float32; crossprod and the bf16 variants return
-   * UNSUPPORTED.  Invalid sparse rows are reported by ilargi_plan_create as INDEX_RANGE.  A dense table has at
+   * serves lmm, tmm, gd_step, materialize, row_sum, col_sum, crossprod (up to 16384 target columns) and the
+   * element-wise operators that keep zero at zero (which then act on csr_val, nnz values), in float32; the
+   * bf16 variants return UNSUPPORTED.  Invalid sparse rows are reported by ilargi_plan_create as INDEX_RANGE.  A dense table has at
    * most 4096 columns; a sparse one up to 2^20 (one-hot encodings), provided that beyond 4096 columns no row
    * holds more than 2048 stored entries (else UNSUPPORTED). */
   const int32_t* csr_rowptr; /* device int32[rows + 1], rising from 0 to nnz */
@@ -115,7 +115,9 @@ ilargi_status_t ilargi_rmm(ilargi_plan_t* plan, const float* X, int64_t cx, floa
                            ilargi_precision_t precision, void* stream);
 
 /* Gram matrix  out = T^T T = sum_k sum_l M_k D_k^T (I_k^T I_l) D_l M_l^T, cross terms included.
- * out device c_T x c_T, both triangles written. */
+ * out device c_T x c_T, both triangles written, symmetric to the bit.  A plan with a sparse source forms it
+ * as T^T (T I), min(max_cx, 16) identity columns at a time through lmm and tmm (so it uses the plan's
+ * residual buffer as scratch), and is limited to c_T <= 16384 (else UNSUPPORTED). */
 ilargi_status_t ilargi_crossprod(ilargi_plan_t* plan, float* out, void* stream);
 
 /* Join-gather baseline: write the materialized target table.  T device r_T x c_T.  Each cell is the

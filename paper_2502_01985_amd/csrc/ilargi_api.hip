@@ -65,6 +65,7 @@ struct SourcePlan {
 
 struct Layout {
   size_t o_gslot = 0, o_gj0 = 0, o_ct_slot = 0, o_ct_j = 0, o_ones = 0, o_tmp_a = 0, o_tmp_b = 0, o_rmm = 0;
+  size_t o_eye = 0;                          // sparse crossprod: a block of identity columns, c_T x min(max_cx, 16)
   size_t o_cn = 0, o_counts = 0, o_rr = 0;   // KMeans / NMF: centroid norms, cluster sizes, two small square matrices
   int64_t max_entries = 0;       // most stored entries of a sparse source (0: every source is dense)
   size_t o_flags = 0, o_tcol_table = 0, o_pairs = 0, o_E = 0, o_loss = 0, o_sort = 0, o_hist = 0, o_zc = 0,
@@ -225,6 +226,7 @@ ilargi_status_t make_layout(int n, const ilargi_source_t* s, int64_t r_T, int64_
     lay.o_tmp_b = take(sizeof(int32_t) * lay.max_entries);
   }
   lay.o_E = take(sizeof(float) * std::max<int64_t>(r_T, 1) * max_cx);
+  lay.o_eye = take(sizeof(float) * (lay.max_entries > 0 && c_T <= kSparseGramMaxCols ? c_T * std::min<int64_t>(max_cx, kSparseGramWidth) : 1));
   lay.o_loss = take(sizeof(float) * std::max<int64_t>(32768 * kNarrowCT, 1024 * max_cx));
   const int64_t sort_n = std::max<int64_t>(std::max<int64_t>(r_T, 1), lay.max_entries);
   lay.o_sort = take(sizeof(int32_t) * 4 * sort_n);
@@ -1346,8 +1348,31 @@ ilargi_status_t ilargi_materialize(ilargi_plan_t* plan, float* T, void* stream) 
 ilargi_status_t ilargi_crossprod(ilargi_plan_t* plan, float* out, void* stream) {
   if (plan == nullptr) return fail(ILARGI_ERR_NULL, "crossprod: plan is NULL");
   if (out == nullptr) return fail(ILARGI_ERR_NULL, "crossprod: out is NULL");
-  if (plan->any_sparse) return fail(ILARGI_ERR_UNSUPPORTED, "crossprod: source tables in sparse rows are not supported");
   hipStream_t st = static_cast<hipStream_t>(stream);
+  if (plan->any_sparse) {
+    // T^T T = T^T (T I): the identity goes through the two multiplies a block of columns at a time, which only
+    // needs the products the sparse kernels have.  Block j gives columns j0.. of the result, written as its rows
+    // j0.. (the result is symmetric); the cells below the diagonal are then copied from above it, so that the
+    // result is symmetric to the bit like the dense route's.
+    const int64_t c_T = plan->c_T;
+    if (c_T > kSparseGramMaxCols)
+      return fail(ILARGI_ERR_UNSUPPORTED, "crossprod: more than %lld target columns over sparse source tables", (long long)kSparseGramMaxCols);
+    const int w = (int)std::min<int64_t>(plan->max_cx, kSparseGramWidth);
+    float* E = plan->at<float>(plan->lay.o_eye);
+    float* P = plan->at<float>(plan->lay.o_E);
+    float* G = plan->at<float>(plan->lay.o_rmm);
+    for (int64_t j0 = 0; j0 < c_T; j0 += w) {
+      const int cw = (int)std::min<int64_t>(w, c_T - j0);
+      HIP_TRY(launch_eye_block(E, c_T, cw, j0, st));
+      ilargi_status_t rc = ilargi_lmm(plan, E, cw, P, ILARGI_F32, stream);
+      if (rc != ILARGI_OK) return rc;
+      rc = ilargi_tmm(plan, P, cw, G, ILARGI_F32, stream);
+      if (rc != ILARGI_OK) return rc;
+      HIP_TRY(launch_transpose(G, c_T, cw, out + j0 * c_T, st));
+    }
+    HIP_TRY(launch_mirror_upper(out, c_T, st));
+    return ILARGI_OK;
+  }
   const int n = plan->n;
   float* blocks = plan->at<float>(plan->lay.o_blocks);
   float* zc = plan->at<float>(plan->lay.o_zc);

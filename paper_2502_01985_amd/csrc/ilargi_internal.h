@@ -268,6 +268,10 @@ hipError_t launch_probe(int kind, float* dst, const float* src, int64_t n_floats
 hipError_t launch_fill_zero(float* p, int64_t n, hipStream_t st);
 hipError_t launch_fill(float* p, int64_t n, float v, hipStream_t st);
 hipError_t launch_transpose(const float* in, int64_t rows, int64_t cols, float* out, hipStream_t st);
+hipError_t launch_eye_block(float* E, int64_t rows, int w, int64_t j0, hipStream_t st);   // columns j0.. of the identity
+hipError_t launch_mirror_upper(float* G, int64_t n, hipStream_t st);                      // lower triangle := upper
+constexpr int64_t kSparseGramMaxCols = 16384;   // crossprod over sparse sources: the c_T x c_T result stays below 1 GiB
+constexpr int kSparseGramWidth = 16;            // identity columns multiplied through per round
 hipError_t launch_fanout(const int32_t* rowptr, int64_t rows, float* cnt, hipStream_t st);
 hipError_t launch_elementwise(int op, const float* in, float* out, int64_t n, float x, hipStream_t st);
 // KMeans / Gaussian NMF row-local steps (kernels_models.hip)

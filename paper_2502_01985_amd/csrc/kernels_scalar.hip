@@ -79,6 +79,24 @@ __global__ __launch_bounds__(kBlock) void transpose_kernel(const float* __restri
   }
 }
 
+// E (rows x w, row-major) = columns [j0, j0 + w) of the rows x rows identity.
+__global__ __launch_bounds__(kBlock) void eye_block_kernel(float* E, int64_t rows, int w, int64_t j0) {
+  const int64_t n = rows * w;
+  for (int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x; e < n; e += (int64_t)gridDim.x * kBlock) {
+    const int64_t i = e / w;
+    E[e] = (i - j0 == e - i * w) ? 1.0f : 0.0f;
+  }
+}
+
+// G (n x n): every cell below the diagonal takes the value of its mirror cell above it.
+__global__ __launch_bounds__(kBlock) void mirror_upper_kernel(float* G, int64_t n) {
+  const int64_t cells = n * n;
+  for (int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x; e < cells; e += (int64_t)gridDim.x * kBlock) {
+    const int64_t i = e / n, j = e - i * n;
+    if (j < i) G[e] = G[j * n + i];
+  }
+}
+
 int grid_for(int64_t n) {
   int64_t g = (n + kBlock - 1) / kBlock;
   return (int)(g < 1 ? 1 : (g > 8192 ? 8192 : g));
@@ -116,6 +134,18 @@ hipError_t launch_transpose(const float* in, int64_t rows, int64_t cols, float* 
 hipError_t launch_fill(float* p, int64_t n, float v, hipStream_t st) {
   if (n <= 0) return hipSuccess;
   fill_kernel<<<grid_for(n), kBlock, 0, st>>>(p, n, v);
+  return hipGetLastError();
+}
+
+hipError_t launch_eye_block(float* E, int64_t rows, int w, int64_t j0, hipStream_t st) {
+  if (rows <= 0 || w <= 0) return hipSuccess;
+  eye_block_kernel<<<grid_for(rows * w), kBlock, 0, st>>>(E, rows, w, j0);
+  return hipGetLastError();
+}
+
+hipError_t launch_mirror_upper(float* G, int64_t n, hipStream_t st) {
+  if (n <= 1) return hipSuccess;
+  mirror_upper_kernel<<<grid_for(n * n), kBlock, 0, st>>>(G, n);
   return hipGetLastError();
 }
 

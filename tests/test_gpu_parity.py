@@ -771,6 +771,19 @@ def test_sparse_sources_operators_and_join(il, name, p):
         assert rel(il.ilargi_tmm(plan, dev(Y)).cpu().numpy(), oracle.tmm(tg, Y)) < OP_TOL
     assert rel(il.ilargi_row_sum(plan).cpu().numpy(), oracle.row_sum(tg)) < OP_TOL
     assert rel(il.ilargi_col_sum(plan).cpu().numpy(), oracle.col_sum(tg)) < OP_TOL
+    G = il.ilargi_crossprod(plan).cpu().numpy()
+    assert rel(G, oracle.crossprod(tg)) < OP_TOL and np.array_equal(G, G.T)
+
+
+@pytest.mark.parametrize("max_cx", [1, 3, 16, 40])
+@pytest.mark.parametrize("which", [(0,), (1,)])
+def test_sparse_sources_crossprod_mixed_tables_and_block_widths(il, which, max_cx):
+    # one table sparse, one dense; the identity goes through in blocks of min(max_cx, 16) columns, with a ragged last block
+    sch, tg, srcs, plan = _sparse_case(il, "config1_small", 0.8, which, max_cx=max_cx)
+    G = il.ilargi_crossprod(plan).cpu().numpy()
+    assert rel(G, oracle.crossprod(tg)) < OP_TOL and np.array_equal(G, G.T)
+    G2 = il.ilargi_crossprod(plan).cpu().numpy()
+    assert np.array_equal(G, G2)
 
 
 @pytest.mark.parametrize("which", [(0,), (1,), True])
@@ -826,9 +839,9 @@ def test_sparse_sources_edge_cases(il):
         with pytest.raises(il.IlargiError) as ei:
             il.ilargi_elementwise(plan, op, 1.0)
         assert ei.value.status == il.ERR_UNSUPPORTED
-    with pytest.raises(il.IlargiError) as ei:
-        il.ilargi_crossprod(plan)
-    assert ei.value.status == il.ERR_UNSUPPORTED
+    G = il.ilargi_crossprod(plan).cpu().numpy()             # (values were scaled by -2 in place above)
+    assert rel(G, 4.0 * oracle.crossprod(tg)) < OP_TOL and np.array_equal(G, G.T)
+    assert np.count_nonzero(G[2]) == 0 and np.count_nonzero(G[6:11]) == 0      # the empty column, the empty table
     with pytest.raises(il.IlargiError) as ei:
         il.ilargi_lmm(plan, torch.zeros((13, 4), device="cuda"), precision=il.BF16_IN_F32_ACC)
     assert ei.value.status == il.ERR_UNSUPPORTED
@@ -867,6 +880,8 @@ def test_sparse_table_wider_than_the_dense_limit(il):
     W_ref, L_ref = oracle.gd(tg, "linear", y, np.zeros((c_T, 1)), [0.05], 5)
     assert rel(W, W_ref) < GD_TOL
     np.testing.assert_allclose(L, L_ref, rtol=2e-4)
+    G = il.ilargi_crossprod(plan).cpu().numpy()             # 10,008 x 10,008, 2502 blocks of four identity columns
+    assert rel(G, oracle.crossprod(tg)) < OP_TOL and np.array_equal(G, G.T)
     # the same table stored densely is refused, and so is a row with more entries than a staged block holds
     with pytest.raises(il.IlargiError) as ei:
         il.ilargi_plan_create(il.schema_to_device(sch), r_T, c_T, max_cx=1)
@@ -892,12 +907,29 @@ def test_one_hot_star_without_entity_table(il):
         Y = rng.standard_normal((r_T, cx)).astype(np.float32)
         assert rel(il.ilargi_lmm(plan, dev(X)).cpu().numpy(), oracle.lmm(tg, X)) < OP_TOL
         assert rel(il.ilargi_tmm(plan, dev(Y)).cpu().numpy(), oracle.tmm(tg, Y)) < OP_TOL
+    G = il.ilargi_crossprod(plan).cpu().numpy()
+    assert rel(G, oracle.crossprod(tg)) < OP_TOL and np.array_equal(G, G.T)
     w_star = rng.standard_normal(c_T)
     y = datagen.finish_labels("linear", oracle.lmm(tg, w_star.reshape(-1, 1)), 0.01 * rng.standard_normal(r_T))
     W, L = _run_gd(il, plan, il.LINEAR, y, [0.02], 6, c_T)
     W_ref, L_ref = oracle.gd(tg, "linear", y, np.zeros((c_T, 1)), [0.02], 6)
     assert rel(W, W_ref) < GD_TOL
     np.testing.assert_allclose(L, L_ref, rtol=2e-4)
+
+
+def test_sparse_crossprod_refuses_a_result_beyond_its_column_limit(il):
+    # 20,000 target columns would need a 1.6 GB Gram matrix through 5000 rounds of multiplies: refused, nothing written
+    r_T, c_T = 50, 20_000
+    R = np.zeros((r_T, c_T), dtype=np.float32)
+    R[np.arange(r_T), np.arange(r_T) * 7] = 1.0
+    srcs = [(il.CSR.from_dense(R), None, np.arange(c_T, dtype=np.int32))]
+    plan = il.ilargi_plan_create(srcs, r_T, c_T, max_cx=1)
+    out = torch.zeros((4,), device="cuda")              # never touched: the call fails before any launch
+    with pytest.raises(il.IlargiError) as ei:
+        # (the binding would allocate c_T x c_T first: call the entry point itself)
+        il._check(il.lib.ilargi_crossprod(plan.handle, out.data_ptr(), None), "ilargi_crossprod")
+    assert ei.value.status == il.ERR_UNSUPPORTED
+    assert torch.count_nonzero(out).item() == 0
 
 
 def test_invalid_sparse_rows_are_reported(il):
