@@ -263,20 +263,21 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(VEC4 ? (
             ind[r] = As[(size_t)row * lda + 16 * full + (li - 12)];
             if constexpr (BF16) ind[r] = (float)(__bf16)ind[r];
           }
+          // branch-free: rows beyond the batch (j < 0) read row 0 of the tile and are zeroed by a select; model
+          // columns beyond the slab carry finite values (their W and P are zero) that no store lets out
+          const bool live = j >= 0;
+          const float* prow = Ps + max(j, 0) * kN + li;
 #pragma unroll
           for (int nt = 0; nt < kNT; ++nt) {
-            float o = 0.0f;
-            if (j >= 0 && nt * 16 + li < nw) {
-              const float z = acc[nt][r] + Ps[j * kN + nt * 16 + li];
-              if constexpr (MODE == 1) {
-                o = z - yi;
-                loss_local[nt] = fmaf(o, o, loss_local[nt]);
-              } else {
-                o = star_sigmoid(z) - yi;
-                loss_local[nt] += star_softplus(z) - yi * z;
-              }
+            const float z = acc[nt][r] + prow[nt * 16];
+            if constexpr (MODE == 1) {
+              const float o = live ? z - yi : 0.0f;
+              ov[nt][r] = o;
+              loss_local[nt] = fmaf(o, o, loss_local[nt]);
+            } else {
+              ov[nt][r] = live ? star_sigmoid(z) - yi : 0.0f;
+              loss_local[nt] += live ? star_softplus(z) - yi * z : 0.0f;
             }
-            ov[nt][r] = o;
           }
         }
         // segment sums, then S^T E.  With BF16 the residual is rounded once as it enters these two products
