@@ -460,13 +460,19 @@ def stream_probe(il, torch):
     n = 1 << 28
     src = torch.empty(n, device="cuda").normal_()
     dst = torch.empty(n, device="cuda")
-    sink = torch.empty(65536, device="cuda")
+    in_order = n // 1024                 # one float4 per thread, workgroups dispatched in address order
+    sink = torch.empty(in_order, device="cuda")
     res = {}
     for kind, name, factor in ((1, "read", 1), (2, "write", 1), (0, "copy", 2), (4, "write_nontemporal", 1),
                                (3, "copy_nontemporal", 2)):
         d = sink if kind == 1 else dst
         t = time_loop(torch, lambda: il.ilargi_stream_probe(kind, d, src, n, 8192), 10)
         res[f"{name}_GBps"] = round(factor * n * 4 / t / 1e9, 1)
+        if kind in (0, 1, 2):
+            t = time_loop(torch, lambda: il.ilargi_stream_probe(kind, d, src, n, in_order), 10)
+            res[f"{name}_in_order_GBps"] = round(factor * n * 4 / t / 1e9, 1)
+    res["note"] = ("8192 workgroups with a grid stride, except *_in_order: one float4 per thread, workgroups "
+                   "dispatched in address order")
     return res
 
 

@@ -249,7 +249,9 @@ ilargi_status_t ilargi_plan_trace_name(const ilargi_plan_t* plan, int i, char* b
  * profiler's byte counters): kind 0 copies n_floats floats src -> dst, kind 1 only reads src (dst
  * receives one float per workgroup, so it needs `blocks` floats), kind 2 only writes dst; kinds 3 and 4
  * are the copy and the write with non-temporal accesses.  Device
- * pointers, 16-byte aligned, n_floats a multiple of 4, `blocks` workgroups of 256 threads. */
+ * pointers, 16-byte aligned, n_floats a multiple of 4, `blocks` workgroups of 256 threads (1 .. 2^22) that
+ * walk the buffer with a grid stride: n_floats / 1024 workgroups touch one float4 per thread, in address
+ * order, which is the pattern that writes fastest on the MI355X. */
 ilargi_status_t ilargi_stream_probe(int kind, float* dst, const float* src, int64_t n_floats, int blocks,
                                     void* stream);
 

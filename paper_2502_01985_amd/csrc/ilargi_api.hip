@@ -990,7 +990,7 @@ ilargi_status_t ilargi_plan_destroy(ilargi_plan_t* plan) {
 ilargi_status_t ilargi_stream_probe(int kind, float* dst, const float* src, int64_t n_floats, int blocks, void* stream) {
   if (kind < 0 || kind > 4) return fail(ILARGI_ERR_UNSUPPORTED, "stream_probe: kind %d", kind);
   if (dst == nullptr || (kind != 2 && kind != 4 && src == nullptr)) return fail(ILARGI_ERR_NULL, "stream_probe: NULL buffer");
-  if (n_floats < 0 || n_floats % 4 != 0 || blocks < 1 || blocks > 65536) return fail(ILARGI_ERR_SHAPE, "stream_probe: bad size");
+  if (n_floats < 0 || n_floats % 4 != 0 || blocks < 1 || blocks > (1 << 22)) return fail(ILARGI_ERR_SHAPE, "stream_probe: bad size");
   HIP_TRY(launch_probe(kind, dst, src, n_floats, blocks, static_cast<hipStream_t>(stream)));
   return ILARGI_OK;
 }

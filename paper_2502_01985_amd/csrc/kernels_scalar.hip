@@ -102,12 +102,20 @@ int grid_for(int64_t n) {
   return (int)(g < 1 ? 1 : (g > 8192 ? 8192 : g));
 }
 
+// Streaming kernels that mostly write: one element per thread, workgroups in address order.  On the MI355X a
+// grid-stride loop over a few thousand resident workgroups writes at about 4.4 TB/s, a launch of one short
+// workgroup per 4 KiB, dispatched in order, at 6 to 6.9 TB/s (reads do not care).
+int grid_for_stream(int64_t n) {
+  int64_t g = (n + kBlock - 1) / kBlock;
+  return (int)(g < 1 ? 1 : (g > (1 << 22) ? (1 << 22) : g));
+}
+
 }  // namespace
 
 hipError_t launch_elementwise(int op, const float* in, float* out, int64_t n, float x, hipStream_t st) {
   if (n <= 0) return hipSuccess;
   const int vec4 = reinterpret_cast<uintptr_t>(in) % 16 == 0 && reinterpret_cast<uintptr_t>(out) % 16 == 0;
-  const int grid = grid_for(vec4 ? n / 4 + 1 : n);
+  const int grid = grid_for_stream(vec4 ? n / 4 + 1 : n);
   switch (op) {
     case 0: elementwise_kernel<0><<<grid, kBlock, 0, st>>>(in, out, n, x, vec4); break;
     case 1: elementwise_kernel<1><<<grid, kBlock, 0, st>>>(in, out, n, x, vec4); break;
@@ -133,7 +141,7 @@ hipError_t launch_transpose(const float* in, int64_t rows, int64_t cols, float* 
 
 hipError_t launch_fill(float* p, int64_t n, float v, hipStream_t st) {
   if (n <= 0) return hipSuccess;
-  fill_kernel<<<grid_for(n), kBlock, 0, st>>>(p, n, v);
+  fill_kernel<<<grid_for_stream(n), kBlock, 0, st>>>(p, n, v);
   return hipGetLastError();
 }
 
