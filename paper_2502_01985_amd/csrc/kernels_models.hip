@@ -186,7 +186,8 @@ __global__ __launch_bounds__(kBlock) void kmeans_update_kernel(float* __restrict
 // X_new[row l / 16][16 ta + l % 16] as A and X_new[row l / 16][16 tb + l % 16] as B of tile (ta, tb), ta <= tb.
 typedef float v4f __attribute__((ext_vector_type(4)));
 
-template <int NT>
+// KQ: the rank rounded up to 16 KQ, the compile-time length of a row's denominators (kept in registers).
+template <int NT, int KQ>
 __global__ __launch_bounds__(kBlock) void gnmf_update_kernel(float* __restrict__ X, const float* __restrict__ P,
                                                              const float* __restrict__ Q, int64_t rows, int k,
                                                              int rows_pb, int vec4, float tiny,
@@ -195,10 +196,14 @@ __global__ __launch_bounds__(kBlock) void gnmf_update_kernel(float* __restrict__
   const int ld = k | 1;
   float* xt = lds;                                             // [rows_pb][ld]
   float* pt = xt + (size_t)rows_pb * ld;                       // [rows_pb][ld]
-  float* qs = pt + (size_t)rows_pb * ld;                       // [k][k]
+  constexpr int KT = 16 * KQ;
+  float* qs = pt + (size_t)rows_pb * ld;                       // [k][KT], zero beyond column k (16-byte aligned rows)
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
   const float inv_k = 1.0f / (float)k;
-  for (int e = tid; e < k * k; e += kBlock) qs[e] = Q[e];
+  for (int e = tid; e < k * KT; e += kBlock) {
+    const int b = e / KT, a = e - b * KT;
+    qs[e] = a < k ? Q[b * k + a] : 0.0f;
+  }
   constexpr int NP = NT > 0 ? NT * (NT + 1) / 2 : 1;
   v4f gacc[NP];
 #pragma unroll
@@ -217,11 +222,25 @@ __global__ __launch_bounds__(kBlock) void gnmf_update_kernel(float* __restrict__
     if (tid < nrow) {
       const float* xr = xt + tid * ld;
       float* pr = pt + tid * ld;
-      for (int a = 0; a < k; ++a) {
-        float den = 0.0f;
-        for (int b = 0; b < k; ++b) den = fmaf(xr[b], qs[b * k + a], den);
-        pr[a] = xr[a] * pr[a] / fmaxf(den, tiny);              // the new value takes the place of the consumed product
+      // den[a] = sum_b x[b] Q[b][a], b ascending: one read of x[b] and KT / 4 broadcast reads of Q's row per b
+      float den[KT];
+#pragma unroll
+      for (int a = 0; a < KT; ++a) den[a] = 0.0f;
+      for (int b = 0; b < k; ++b) {
+        const float xv = xr[b];
+        const float4* qrow = reinterpret_cast<const float4*>(qs + b * KT);
+#pragma unroll
+        for (int a4 = 0; a4 < KT / 4; ++a4) {
+          const float4 qv = qrow[a4];
+          den[4 * a4 + 0] = fmaf(xv, qv.x, den[4 * a4 + 0]);
+          den[4 * a4 + 1] = fmaf(xv, qv.y, den[4 * a4 + 1]);
+          den[4 * a4 + 2] = fmaf(xv, qv.z, den[4 * a4 + 2]);
+          den[4 * a4 + 3] = fmaf(xv, qv.w, den[4 * a4 + 3]);
+        }
       }
+#pragma unroll
+      for (int a = 0; a < KT; ++a)
+        if (a < k) pr[a] = xr[a] * pr[a] / fmaxf(den[a], tiny);   // the new value takes the place of the consumed product
     }
     __syncthreads();
     stage_out(xb, pt, total, k, ld, inv_k, vec4 != 0, tid);
@@ -327,19 +346,21 @@ hipError_t launch_gnmf_update(float* X, const float* P, const float* Q, int64_t 
   if (rows <= 0 || k <= 0) return hipSuccess;
   if (k > kGnmfMaxRank) return hipErrorInvalidValue;
   const int rows_pb = tile_rows(k, 2);
-  const size_t lds_bytes = (2 * (size_t)rows_pb * (k | 1) + (size_t)k * k) * sizeof(float);
+  const int kq = (k + 15) / 16;
+  const size_t lds_bytes = (2 * (size_t)rows_pb * (k | 1) + (size_t)k * 16 * kq) * sizeof(float);
   int grid = tile_grid(rows, rows_pb);
   if (gram_partial != nullptr) {
     grid = (int)std::min<int64_t>(std::min(grid, 2048), partial_floats / ((int64_t)k * k));
     if (grid < 1) return hipErrorInvalidValue;
   }
   const int vec4 = reinterpret_cast<uintptr_t>(X) % 16 == 0 && reinterpret_cast<uintptr_t>(P) % 16 == 0;
-  const int nt = gram_partial != nullptr ? (k + 15) / 16 : 0;
-  if (nt == 0) gnmf_update_kernel<0><<<grid, kBlock, lds_bytes, st>>>(X, P, Q, rows, k, rows_pb, vec4, tiny, gram_partial);
-  else if (nt == 1) gnmf_update_kernel<1><<<grid, kBlock, lds_bytes, st>>>(X, P, Q, rows, k, rows_pb, vec4, tiny, gram_partial);
-  else if (nt == 2) gnmf_update_kernel<2><<<grid, kBlock, lds_bytes, st>>>(X, P, Q, rows, k, rows_pb, vec4, tiny, gram_partial);
-  else if (nt == 3) gnmf_update_kernel<3><<<grid, kBlock, lds_bytes, st>>>(X, P, Q, rows, k, rows_pb, vec4, tiny, gram_partial);
-  else gnmf_update_kernel<4><<<grid, kBlock, lds_bytes, st>>>(X, P, Q, rows, k, rows_pb, vec4, tiny, gram_partial);
+  typedef void (*GnmfFn)(float*, const float*, const float*, int64_t, int, int, int, float, float*);
+  GnmfFn fn;
+  if (gram_partial != nullptr)
+    fn = kq == 1 ? gnmf_update_kernel<1, 1> : (kq == 2 ? gnmf_update_kernel<2, 2> : (kq == 3 ? gnmf_update_kernel<3, 3> : gnmf_update_kernel<4, 4>));
+  else
+    fn = kq == 1 ? gnmf_update_kernel<0, 1> : (kq == 2 ? gnmf_update_kernel<0, 2> : (kq == 3 ? gnmf_update_kernel<0, 3> : gnmf_update_kernel<0, 4>));
+  hipLaunchKernelGGL(fn, dim3((unsigned)grid), dim3(kBlock), lds_bytes, st, X, P, Q, rows, k, rows_pb, vec4, tiny, gram_partial);
   if (nparts_out) *nparts_out = grid;
   return hipGetLastError();
 }
