@@ -130,6 +130,49 @@ def make_ops(il, torch, plan, sch, dev):
     return ops, keep
 
 
+def rotated_ops(il, torch, sch, srcs, keep, ops, copies=3, reps=30):
+    """The multiplies and the GD step with the source tables rotated: `copies` independent copies of the
+    tables (and plans) take turns, so that no launch finds its tables in the 256 MB last-level cache
+    (3 x 168 MB on the config-1 centre schema)."""
+    shp = shapes_of(sch)
+    plans = []
+    held = []
+    for _ in range(copies):
+        cp = [(D.clone(), None if idx is None else idx.clone(), cm) for D, idx, cm in srcs]
+        held.append(cp)
+        plans.append(il.ilargi_plan_create(cp, sch.r_T, sch.c_T, max_cx=16))
+    o_l1, o_l16, o_t1, o_t16, _ = keep["outs"]
+    W = torch.zeros((sch.c_T, 1), device="cuda")
+    calls = {
+        "lmm_c1": lambda pl: il.ilargi_lmm(pl, keep["X1"], o_l1),
+        "tmm_c1": lambda pl: il.ilargi_tmm(pl, keep["Y1"], o_t1),
+        "lmm_c16": lambda pl: il.ilargi_lmm(pl, keep["X16"], o_l16),
+        "tmm_c16": lambda pl: il.ilargi_tmm(pl, keep["Y16"], o_t16),
+        "gd_step": lambda pl: il.ilargi_gd_step(pl, il.LINEAR, W, keep["y"], keep["lr"], keep["loss"]),
+    }
+    nbytes = {name: b for name, _, b in ops}
+    out = {}
+    for name, call in calls.items():
+        for i in range(copies):
+            call(plans[i])
+        torch.cuda.synchronize()
+        batches = []
+        for _ in range(5):
+            e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for i in range(reps):
+                call(plans[i % copies])
+            e1.record()
+            torch.cuda.synchronize()
+            batches.append(e0.elapsed_time(e1) * 1e-3 / reps)
+        t = float(np.median(batches))
+        out[name] = {"us": round(t * 1e6, 1), "GBps": round(nbytes[name] / t / 1e9, 1),
+                     "hbm_frac": round(nbytes[name] / t / 1e9 / HBM_PEAK_GBPS, 4)}
+    out["note"] = f"{copies} copies of the source tables take turns ({copies} x {round(bytes_tables(shp) / 1e6)} MB)"
+    del plans, held
+    return out
+
+
 def cpu_baseline(sch, sample_rows, budget_s=20.0):
     """The oracle, as it stands, on the first `sample_rows` target rows of the same workload."""
     import datagen
@@ -602,6 +645,8 @@ def main() -> int:
         t = time_loop(torch, fn, 20)
         breakdown[name] = {"us": round(t * 1e6, 1), "GBps": round(b / t / 1e9, 1),
                            "hbm_frac": round(b / t / 1e9 / HBM_PEAK_GBPS, 4), "MB": round(b / 1e6, 1)}
+    rotated = rotated_ops(il, torch, sch, srcs, keep, ops)
+    torch.cuda.empty_cache()
     lt_bytes = sum(b for n, _, b in ops if n.startswith(("lmm", "tmm")))
     lt_time = sum(breakdown[n]["us"] for n in breakdown if n.startswith(("lmm", "tmm"))) * 1e-6
     lt_time_cold = sum(in_step[n]["us"] for n in in_step if n.startswith(("lmm", "tmm"))) * 1e-6
@@ -664,6 +709,7 @@ def main() -> int:
         "lmm_tmm_GBps_back_to_back": round(lt_bytes / lt_time / 1e9, 1),
         "ops_in_step": in_step,
         "ops_back_to_back": breakdown,
+        "ops_tables_rotated": rotated,
         "gd": {"factorized_it_per_s": round(1.0 / t_fact, 1), "materialized_it_per_s": round(1.0 / t_mat, 1),
                "speedup": round(t_mat / t_fact, 3),
                "materialize_once_us": breakdown["materialize"]["us"],
