@@ -357,6 +357,173 @@ __global__ __launch_bounds__(kBlock) void lmm_mfma_kernel(LmmArgs a, MfmaShape s
   }
 }
 
+// Plain product  P = D (M^T X)  for wide operands (slabs of 64 columns), float32: a workgroup forms a 128 x 64 block
+// of P, a wavefront 32 x 64 of it (eight 16 x 16 accumulators).  The table and the operand pass through LDS in K
+// chunks of 32 columns, double-buffered: the next chunk is on its way from memory into registers while the matrix
+// cores work on the current one, and one workgroup barrier per chunk separates them.  Both operands are stored so
+// that one 128-bit LDS read feeds four MFMAs: lane (li, q) reads columns 4 q .. 4 q + 3 of its row (MFMA c takes
+// component c, K slot q = column 4 q + c of the 16-column group), and the operand chunk is kept as
+// [group][q][column][c].  With 26 KiB per buffer three workgroups share a compute unit, where the general kernel
+// above keeps the whole 208 x 64 operand slab in LDS and runs alone.
+constexpr int kGemmBM = 128, kGemmBN = 64, kGemmKC = 32;
+constexpr int kGemmLda = kGemmKC + 4;                          // 36: rows 16 bytes aligned, 128-bit reads conflict-free
+constexpr int kGemmStage = kGemmBM * kGemmLda + kGemmKC * kGemmBN;   // floats per buffer
+
+__global__ __launch_bounds__(kBlock) void lmm_gemm_kernel(LmmArgs a, MfmaShape sh) {
+  extern __shared__ float lds[];
+  const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+  const int li = lane % 16, q = lane / 16;
+  // Workgroup ids go round-robin over the 8 XCDs, each with an L2 of its own: the column slabs of one block of
+  // rows get ids that are 8 apart, so they run on the same XCD at about the same time and the block of rows comes
+  // from memory once.  sh.rb = number of column slabs, sh.kp = number of row blocks.
+  const int gy = sh.rb;
+  const int64_t grp = blockIdx.x / (8 * gy);
+  const int within = (int)(blockIdx.x - grp * (8 * gy));
+  const int64_t rblock = grp * 8 + within % 8;
+  if (rblock >= sh.kp) return;
+  const int64_t row0 = rblock * kGemmBM;
+  const int n0 = (within / 8) * kGemmBN;
+  const int nw = min(kGemmBN, a.ncols - n0);
+  const int nch = (a.ck + kGemmKC - 1) / kGemmKC;
+  const bool x_vec = (a.ldx % 4 == 0) && ((a.col0 + n0) % 4 == 0) && (reinterpret_cast<uintptr_t>(a.X) % 16 == 0);
+
+  // staging slots of this thread: table (row ar + 32 u, float4 ac of the chunk), operand (k row bk + 16 u, float4 bn)
+  const int ar = tid / 8, ac = tid % 8;                        // 32 rows x 8 float4 per pass, 4 passes
+  const int bk = tid / 16, bn = tid % 16;                      // 16 k rows x 16 float4 per pass, 2 passes
+  float4 va[4], vb[2];
+  // branch-free in the common case (whole slab, float4 operand rows): values nobody needs are read from the
+  // start of the buffer and replaced by zero, so that all six loads of a chunk are in flight together
+  const bool fastb = x_vec && nw == kGemmBN;
+  auto fetch = [&](int ch) {
+    const int k0 = ch * kGemmKC;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int64_t row = row0 + ar + 32 * u;
+      const int col = k0 + 4 * ac;
+      const bool ok = row < a.d_rows && col < a.ck;
+      const float4 v = *reinterpret_cast<const float4*>(ok ? a.D + row * a.ck + col : a.D);
+      va[u] = ok ? v : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    }
+    if (fastb) {
+      int t[2];
+#pragma unroll
+      for (int u = 0; u < 2; ++u) t[u] = a.colmap[min(k0 + bk + 16 * u, a.ck - 1)];
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const bool ok = k0 + bk + 16 * u < a.ck && t[u] >= 0;
+        const float4 v = *reinterpret_cast<const float4*>(ok ? a.X + (int64_t)t[u] * a.ldx + a.col0 + n0 + 4 * bn : a.X);
+        vb[u] = ok ? v : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+      }
+    } else {
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const int k = k0 + bk + 16 * u;
+        vb[u] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        const int t = k < a.ck ? a.colmap[k] : -1;
+        if (t >= 0 && 4 * bn < nw) {
+          const float* p = a.X + (int64_t)t * a.ldx + a.col0 + n0 + 4 * bn;
+          vb[u].x = p[0];
+          if (4 * bn + 1 < nw) vb[u].y = p[1];
+          if (4 * bn + 2 < nw) vb[u].z = p[2];
+          if (4 * bn + 3 < nw) vb[u].w = p[3];
+        }
+      }
+    }
+  };
+  auto stash = [&](int buf) {
+    float* As = lds + (size_t)buf * kGemmStage;
+    float* Bs = As + kGemmBM * kGemmLda;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) *reinterpret_cast<float4*>(As + (ar + 32 * u) * kGemmLda + 4 * ac) = va[u];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int kk = bk + 16 * u;                              // k within the chunk: group kk / 16, slot (kk % 16) / 4, c kk % 4
+      float* b = Bs + ((kk / 16) * 4 + (kk % 16) / 4) * (kGemmBN * 4) + (kk % 4);
+      const float x4[4] = {vb[u].x, vb[u].y, vb[u].z, vb[u].w};
+#pragma unroll
+      for (int c = 0; c < 4; ++c) b[(4 * bn + c) * 4] = x4[c];
+    }
+  };
+
+  v4f acc[2][4];
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt) acc[t][nt] = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
+
+  auto compute = [&](int ch) {
+    const int buf = ch & 1;
+    const float* As = lds + (size_t)buf * kGemmStage;
+    const float4* Bs4 = reinterpret_cast<const float4*>(As + kGemmBM * kGemmLda);
+    const int groups = min(2, (a.ck - ch * kGemmKC + 15) / 16);  // 16-column groups of this chunk that hold columns
+#pragma unroll
+    for (int g = 0; g < 2; ++g) {
+      if (g < groups) {
+        float4 av[2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+          av[t] = *reinterpret_cast<const float4*>(As + (32 * wave + 16 * t + li) * kGemmLda + 16 * g + 4 * q);
+        float4 b[4];
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) b[nt] = Bs4[(g * 4 + q) * kGemmBN + 16 * nt + li];
+        // eight independent accumulators between two MFMAs on the same one
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+#pragma unroll
+          for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+              const float ax = c == 0 ? av[t].x : (c == 1 ? av[t].y : (c == 2 ? av[t].z : av[t].w));
+              const float bx = c == 0 ? b[nt].x : (c == 1 ? b[nt].y : (c == 2 ? b[nt].z : b[nt].w));
+              acc[t][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(ax, bx, acc[t][nt], 0, 0, 0);
+            }
+      }
+    }
+  };
+  // chunk ch in LDS; chunk ch + 1 is requested before the MFMAs of chunk ch and stored after them
+  fetch(0);
+  stash(0);
+  __syncthreads();
+  for (int ch = 0; ch < nch; ++ch) {
+    if (ch + 1 < nch) fetch(ch + 1);
+    compute(ch);
+    if (ch + 1 < nch) stash((ch + 1) & 1);
+    __syncthreads();
+  }
+  // the wavefront's 32 x 64 block through LDS (its own 8 KiB of the idle buffers), so that rows leave as float4
+  float* Cs = lds + (size_t)wave * (32 * kGemmBN);
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) Cs[(16 * t + 4 * q + r) * kGemmBN + 16 * nt + li] = acc[t][nt][r];
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  const bool o_vec = (a.ldo % 4 == 0) && ((a.col0 + n0) % 4 == 0) && (reinterpret_cast<uintptr_t>(a.out) % 16 == 0);
+#pragma unroll
+  for (int it = 0; it < 8; ++it) {
+    const int r = 4 * it + q;                                  // 4 rows per pass, 16 lanes x float4 = one 256-byte row
+    const int64_t orow = row0 + 32 * wave + r;
+    if (orow < a.r_out && 4 * li < nw) {
+      const float4 v = *reinterpret_cast<const float4*>(Cs + r * kGemmBN + 4 * li);
+      float* p = a.out + orow * a.ldo + a.col0 + n0 + 4 * li;
+      if (o_vec && 4 * li + 3 < nw) {
+        typedef float f4 __attribute__((ext_vector_type(4)));
+        const f4 o = {v.x, v.y, v.z, v.w};
+        if (a.nt_out) __builtin_nontemporal_store(o, reinterpret_cast<f4*>(p));
+        else *reinterpret_cast<f4*>(p) = o;
+      } else {
+        p[0] = v.x;
+        if (4 * li + 1 < nw) p[1] = v.y;
+        if (4 * li + 2 < nw) p[2] = v.z;
+        if (4 * li + 3 < nw) p[3] = v.w;
+      }
+    }
+  }
+}
+
 // Plain product  P = D (M^T X)  for an operand of at most 16 columns and a table that fits one K chunk
 // (float4-aligned rows): the role of the kernel above without gathers, epilogue modes or gradient, with the
 // next block of rows fetched into registers while the matrix cores work on the current one.  A workgroup that
@@ -537,6 +704,20 @@ hipError_t launch_lmm_mfma(const LmmArgs& a, int vec, int mode, bool bf16, hipSt
   MfmaFn fn;
   const bool plain_product = mode == 0 && !bf16 && a.g.n == 0 && a.D != nullptr && a.grad_partial == nullptr && nt == 1 &&
                              vec4 && sh.kp == sh.kc && (int64_t)sh.rb * (sh.kp / 4) <= (int64_t)kProdSlots * kBlock;
+  // wide plain product (no gathers, no epilogue): the chunked, double-buffered kernel
+  if (mode == 0 && !bf16 && a.g.n == 0 && a.D != nullptr && a.grad_partial == nullptr && nt == 4 && vec4) {
+    const size_t lds_bytes = (size_t)2 * kGemmStage * sizeof(float);
+    const int64_t gxm = (a.r_out + kGemmBM - 1) / kGemmBM;
+    const int gyn = (a.ncols + kGemmBN - 1) / kGemmBN;
+    const int64_t total = (gxm + 7) / 8 * 8 * gyn;
+    if (gxm <= 0x7fffffff && total <= 0x7fffffff) {
+      sh.kp = (int)gxm;
+      sh.rb = gyn;
+      if (grid_out) *grid_out = (int)gxm;
+      hipLaunchKernelGGL(lmm_gemm_kernel, dim3((unsigned)total), dim3(kBlock), lds_bytes, st, a, sh);
+      return hipGetLastError();
+    }
+  }
   if (plain_product) {
     fn = lmm_prod_kernel;
   } else if (a.grad_partial != nullptr) {

@@ -192,6 +192,31 @@ def test_segment_sum(il, name, cx):
 
 
 # ------------------------------------------------------------------ wide operands (matrix-core kernels)
+@pytest.mark.parametrize("cx", [33, 64, 65, 100, 130, 192])
+@pytest.mark.parametrize("c_R", [4, 36, 72, 200])
+def test_wide_product_of_a_joined_table_chunk_and_slab_tails(il, c_R, cx):
+    # the chunked product kernel for 64-column slabs: table widths that end inside a 32-column chunk or a 16-column
+    # group, row counts off the 128-row block, operand widths that end inside a slab and are not float4 multiples,
+    # unmapped table columns
+    rng = datagen.rng_for(5100 + c_R)
+    r_T, r_R, c_S = 3_001, 1_157, 8
+    S = rng.standard_normal((r_T, c_S)).astype(np.float32)
+    R = rng.standard_normal((r_R, c_R)).astype(np.float32)
+    fk = rng.integers(0, r_R, r_T).astype(np.int32)
+    fk[::17] = -1
+    cm = np.arange(c_S, c_S + c_R, dtype=np.int32)
+    cm[1::5] = -1                                            # every fifth table column feeds nothing
+    live = cm[cm >= 0]
+    cm[cm >= 0] = c_S + np.arange(live.size, dtype=np.int32)
+    c_T = c_S + live.size
+    sch = datagen.Schema([datagen.Source(S, None, np.arange(c_S, dtype=np.int32)), datagen.Source(R, fk, cm)], r_T, c_T)
+    tg = oracle.Target(sch)
+    plan = il.ilargi_plan_create(il.schema_to_device(sch), r_T, c_T, max_cx=192)
+    X = rng.standard_normal((c_T, cx)).astype(np.float32)
+    assert rel(il.ilargi_lmm(plan, dev(X)).cpu().numpy(), oracle.lmm(tg, X)) < OP_TOL
+
+
+
 @pytest.mark.parametrize("name", ["config1_small", "config1_wide_dim", "config3_small", "odd_cols", "tiny_mixed"])
 @pytest.mark.parametrize("cx", [8, 40, 64, 256])
 def test_wide_operands(il, name, cx):
