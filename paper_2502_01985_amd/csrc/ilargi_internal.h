@@ -198,7 +198,8 @@ struct TredArgs {
   const float* B; int ldb, cb, bcol0; const int32_t* ib; int64_t b_rows;
   const int32_t* wptr;     // optional: w_t = wptr[t+1] - wptr[t]
   int64_t n_rows, rows_per_block;
-  float* partial;          // [gridDim.x][ca][cb]
+  float* partial;          // [row chunk][ca][cb]
+  int gx, gy;              // set by launch_tred: row chunks and output tiles of the launch (see tred_block_ids)
   int upper_only;          // A == B: only tiles touching the upper triangle are computed
 };
 

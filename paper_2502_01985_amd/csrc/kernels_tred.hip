@@ -26,6 +26,18 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int kU = 4;  // row quads in flight per wavefront
 
+// Row chunk bx and output tile by of this workgroup.  The launch is one-dimensional and workgroup ids go round-robin
+// over the 8 XCDs (each with an L2 of its own): the gy tiles of one row chunk get ids that are 8 apart, so they run
+// on the same XCD at about the same time and the chunk's rows of both matrices come from memory once instead of
+// once per tile.
+__device__ __forceinline__ bool tred_block_ids(const TredArgs& a, int& bx, int& by) {
+  const int64_t grp = blockIdx.x / (8 * a.gy);
+  const int within = (int)(blockIdx.x - grp * (8 * a.gy));
+  bx = (int)(grp * 8 + within % 8);
+  by = within / 8;
+  return bx < a.gx;
+}
+
 // JT: 64-column tiles of A per workgroup tile, NT: 16-column tiles of B.  JT * NT <= 4.
 template <int JT, int NT, bool VEC4>
 __global__ __launch_bounds__(kBlock) void tred_kernel(TredArgs a) {
@@ -33,9 +45,11 @@ __global__ __launch_bounds__(kBlock) void tred_kernel(TredArgs a) {
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
   const int s = lane % 16, q = lane / 16;
   const int nb_slabs = (a.cb + NT * 16 - 1) / (NT * 16);
-  const int a_slab = blockIdx.y / nb_slabs, b_slab = blockIdx.y - a_slab * nb_slabs;
+  int bx, by;
+  if (!tred_block_ids(a, bx, by)) return;
+  const int a_slab = by / nb_slabs, b_slab = by - a_slab * nb_slabs;
   const int j0 = a_slab * JT * 64, n0 = b_slab * NT * 16;
-  const int64_t t_lo = (int64_t)blockIdx.x * a.rows_per_block;
+  const int64_t t_lo = (int64_t)bx * a.rows_per_block;
   const int64_t t_hi = min(t_lo + a.rows_per_block, a.n_rows);
   // symmetric result: tiles entirely below the diagonal are never read by the caller
   if (a.upper_only && j0 >= n0 + NT * 16) return;
@@ -125,7 +139,7 @@ __global__ __launch_bounds__(kBlock) void tred_kernel(TredArgs a) {
     }
     __syncthreads();
   }
-  float* out = a.partial + (int64_t)blockIdx.x * a.ca * a.cb;
+  float* out = a.partial + (int64_t)bx * a.ca * a.cb;
   for (int o = tid; o < JT * 64 * NT * 16; o += kBlock) {
     int j = o / (NT * 16), n = o - j * (NT * 16);
     if (j0 + j < a.ca && n0 + n < a.cb) out[(int64_t)(j0 + j) * a.cb + n0 + n] = red[o];
@@ -141,9 +155,11 @@ __global__ __launch_bounds__(kBlock) void tred_bf16_kernel(TredArgs a) {
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
   const int s = lane % 16, q = lane / 16;
   const int nb_slabs = (a.cb + NT * 16 - 1) / (NT * 16);
-  const int a_slab = blockIdx.y / nb_slabs, b_slab = blockIdx.y - a_slab * nb_slabs;
+  int bx, by;
+  if (!tred_block_ids(a, bx, by)) return;
+  const int a_slab = by / nb_slabs, b_slab = by - a_slab * nb_slabs;
   const int j0 = a_slab * 64, n0 = b_slab * NT * 16;
-  const int64_t t_lo = (int64_t)blockIdx.x * a.rows_per_block;
+  const int64_t t_lo = (int64_t)bx * a.rows_per_block;
   const int64_t t_hi = min(t_lo + a.rows_per_block, a.n_rows);
   v4f acc[4][NT];
 #pragma unroll
@@ -221,7 +237,7 @@ __global__ __launch_bounds__(kBlock) void tred_bf16_kernel(TredArgs a) {
     }
     __syncthreads();
   }
-  float* out = a.partial + (int64_t)blockIdx.x * a.ca * a.cb;
+  float* out = a.partial + (int64_t)bx * a.ca * a.cb;
   for (int o = tid; o < 64 * NT * 16; o += kBlock) {
     int j = o / (NT * 16), n = o - j * (NT * 16);
     if (j0 + j < a.ca && n0 + n < a.cb) out[(int64_t)(j0 + j) * a.cb + n0 + n] = red[o];
@@ -236,8 +252,10 @@ __global__ __launch_bounds__(kBlock) void tred_dw_kernel(TredArgs a) {
   __shared__ float red[JT * 16 * NT * 16];
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
   const int s = lane % 16, q = lane / 16;
-  const int n0 = blockIdx.y * NT * 16;
-  const int64_t t_lo = (int64_t)blockIdx.x * a.rows_per_block;
+  int bx, by;
+  if (!tred_block_ids(a, bx, by)) return;
+  const int n0 = by * NT * 16;
+  const int64_t t_lo = (int64_t)bx * a.rows_per_block;
   const int64_t t_hi = min(t_lo + a.rows_per_block, a.n_rows);
   if (a.upper_only && 0 >= n0 + NT * 16) return;
   v4f acc[JT][NT];
@@ -297,7 +315,7 @@ __global__ __launch_bounds__(kBlock) void tred_dw_kernel(TredArgs a) {
     }
     __syncthreads();
   }
-  float* out = a.partial + (int64_t)blockIdx.x * a.ca * a.cb;
+  float* out = a.partial + (int64_t)bx * a.ca * a.cb;
   for (int o = tid; o < JT * 16 * NT * 16; o += kBlock) {
     int j = o / (NT * 16), n = o - j * (NT * 16);
     if (j < a.ca && n0 + n < a.cb) out[(int64_t)j * a.cb + n0 + n] = red[o];
@@ -457,8 +475,12 @@ void tred_occupancy(const TredArgs& a, bool bf16, int* slots, int* tiles) {
 hipError_t launch_tred(const TredArgs& a, int nchunks, bool bf16, hipStream_t st) {
   if (a.ca <= 0 || a.cb <= 0 || nchunks <= 0) return hipSuccess;
   TredChoice c = tred_select(a, bf16);
-  dim3 grid(nchunks, c.tiles);
-  hipLaunchKernelGGL(c.fn, grid, dim3(kBlock), 0, st, a);
+  TredArgs b = a;
+  b.gx = nchunks;
+  b.gy = c.tiles;
+  const int64_t total = ((int64_t)nchunks + 7) / 8 * 8 * c.tiles;
+  if (total > 0x7fffffff) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(c.fn, dim3((unsigned)total), dim3(kBlock), 0, st, b);
   return hipGetLastError();
 }
 
