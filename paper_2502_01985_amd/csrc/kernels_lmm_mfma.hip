@@ -391,18 +391,20 @@ __global__ __launch_bounds__(kBlock) void lmm_gemm_kernel(LmmArgs a, MfmaShape s
   const int ar = tid / 8, ac = tid % 8;                        // 32 rows x 8 float4 per pass, 4 passes
   const int bk = tid / 16, bn = tid % 16;                      // 16 k rows x 16 float4 per pass, 2 passes
   float4 va[4], vb[2];
+  unsigned dead = 0;                                           // values of the chunk in flight that must read as zero
   // branch-free in the common case (whole slab, float4 operand rows): values nobody needs are read from the
   // start of the buffer and replaced by zero, so that all six loads of a chunk are in flight together
   const bool fastb = x_vec && nw == kGemmBN;
   auto fetch = [&](int ch) {
     const int k0 = ch * kGemmKC;
+    dead = 0;
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int64_t row = row0 + ar + 32 * u;
       const int col = k0 + 4 * ac;
       const bool ok = row < a.d_rows && col < a.ck;
-      const float4 v = *reinterpret_cast<const float4*>(ok ? a.D + row * a.ck + col : a.D);
-      va[u] = ok ? v : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+      va[u] = *reinterpret_cast<const float4*>(ok ? a.D + row * a.ck + col : a.D);
+      if (!ok) dead |= 1u << u;
     }
     if (fastb) {
       int t[2];
@@ -411,8 +413,8 @@ __global__ __launch_bounds__(kBlock) void lmm_gemm_kernel(LmmArgs a, MfmaShape s
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
         const bool ok = k0 + bk + 16 * u < a.ck && t[u] >= 0;
-        const float4 v = *reinterpret_cast<const float4*>(ok ? a.X + (int64_t)t[u] * a.ldx + a.col0 + n0 + 4 * bn : a.X);
-        vb[u] = ok ? v : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        vb[u] = *reinterpret_cast<const float4*>(ok ? a.X + (int64_t)t[u] * a.ldx + a.col0 + n0 + 4 * bn : a.X);
+        if (!ok) dead |= 16u << u;
       }
     } else {
 #pragma unroll
@@ -434,12 +436,14 @@ __global__ __launch_bounds__(kBlock) void lmm_gemm_kernel(LmmArgs a, MfmaShape s
     float* As = lds + (size_t)buf * kGemmStage;
     float* Bs = As + kGemmBM * kGemmLda;
 #pragma unroll
-    for (int u = 0; u < 4; ++u) *reinterpret_cast<float4*>(As + (ar + 32 * u) * kGemmLda + 4 * ac) = va[u];
+    for (int u = 0; u < 4; ++u)
+      *reinterpret_cast<float4*>(As + (ar + 32 * u) * kGemmLda + 4 * ac) = (dead >> u & 1u) ? make_float4(0.0f, 0.0f, 0.0f, 0.0f) : va[u];
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
       const int kk = bk + 16 * u;                              // k within the chunk: group kk / 16, slot (kk % 16) / 4, c kk % 4
       float* b = Bs + ((kk / 16) * 4 + (kk % 16) / 4) * (kGemmBN * 4) + (kk % 4);
-      const float x4[4] = {vb[u].x, vb[u].y, vb[u].z, vb[u].w};
+      const float4 bz = (dead >> (4 + u) & 1u) ? make_float4(0.0f, 0.0f, 0.0f, 0.0f) : vb[u];
+      const float x4[4] = {bz.x, bz.y, bz.z, bz.w};
 #pragma unroll
       for (int c = 0; c < 4; ++c) b[(4 * bn + c) * 4] = x4[c];
     }
