@@ -501,8 +501,9 @@ ilargi_status_t tmm_pass(ilargi_plan* pl, const float* Y, int ldy, int col0, int
 }
 
 // Runs the matrix-core transposed reduction in row chunks and adds the chunk results in order.
+// transposed: block receives the cb x ca transpose of the product.
 ilargi_status_t run_tred(ilargi_plan* pl, TredArgs& g, float* block, const char* tag, int tag_k, bool bf16,
-                         hipStream_t st) {
+                         hipStream_t st, bool transposed = false) {
   int64_t elems = (int64_t)g.ca * g.cb;
   if (elems <= 0) return ILARGI_OK;
   if (!bf16 && gram_sym_supported(g) && elems <= pl->lay.gpartial_floats) {
@@ -529,7 +530,7 @@ ilargi_status_t run_tred(ilargi_plan* pl, TredArgs& g, float* block, const char*
     TraceScope ts(pl, tag, tag_k, st);
     HIP_TRY(launch_tred(g, (int)nch, bf16, st));
   }
-  HIP_TRY(launch_tred_reduce(g.partial, (int)nch, elems, block, st));
+  HIP_TRY(launch_tred_reduce(g.partial, (int)nch, elems, block, st, transposed ? g.cb : 0));
   return ILARGI_OK;
 }
 
@@ -1435,6 +1436,14 @@ ilargi_status_t ilargi_crossprod(ilargi_plan_t* plan, float* out, void* stream) 
           g.A = zc; g.lda = (int)a.cols; g.ca = (int)a.cols; g.a_rows = b.rows;
           g.B = b.D; g.ldb = (int)b.cols; g.cb = (int)b.cols; g.b_rows = b.rows;
           g.n_rows = b.rows;
+          if (a.cols <= 32 && b.cols >= 64) {
+            // few summed columns against a wide table: the wide table takes the A role (whole rows as float4,
+            // 128 columns per workgroup) and the block is written transposed, D_l^T Zc = (Zc^T D_l)^T
+            std::swap(g.A, g.B); std::swap(g.lda, g.ldb); std::swap(g.ca, g.cb); std::swap(g.a_rows, g.b_rows);
+            rc = run_tred(plan, g, block, "gram", k * n + l, false, st, true);
+            if (rc != ILARGI_OK) return rc;
+            continue;
+          }
         } else if (via_k) {
           SegArgs s = seg_args(plan, k);
           s.Y = b.D; s.ldy = (int)b.cols; s.col0 = 0; s.ncols = (int)b.cols;

@@ -263,7 +263,8 @@ bool gram_sym_supported(const TredArgs& a);
 hipError_t launch_gram_sym(TredArgs& a, float* partial, int64_t partial_floats, float* block, hipStream_t st);
 hipError_t launch_tred(const TredArgs& a, int nchunks, bool bf16, hipStream_t st);
 void tred_occupancy(const TredArgs& a, bool bf16, int* slots, int* tiles);
-hipError_t launch_tred_reduce(const float* partial, int nchunks, int64_t elems, float* block, hipStream_t st);
+// tcols > 0: the summed (elems / tcols) x tcols matrix is written transposed
+hipError_t launch_tred_reduce(const float* partial, int nchunks, int64_t elems, float* block, hipStream_t st, int tcols = 0);
 hipError_t launch_colasm(const ColAsmArgs& a, int mode, hipStream_t st);
 hipError_t launch_probe(int kind, float* dst, const float* src, int64_t n_floats, int blocks, hipStream_t st);
 hipError_t launch_fill_zero(float* p, int64_t n, hipStream_t st);

@@ -324,8 +324,9 @@ __global__ __launch_bounds__(kBlock) void tred_dw_kernel(TredArgs a) {
 
 // block[e] = sum over chunks.  A workgroup owns 16 consecutive elements; its 16 thread groups stride the chunks
 // with eight loads in flight each, then the groups are added in order.
+// tcols > 0: the partials are a (elems / tcols) x tcols matrix and block receives its transpose.
 __global__ __launch_bounds__(kBlock) void tred_reduce_kernel(const float* __restrict__ partial, int nchunks,
-                                                             int64_t elems, float* __restrict__ block) {
+                                                             int64_t elems, float* __restrict__ block, int tcols) {
   __shared__ float red[16][16];
   const int el = threadIdx.x % 16, cg = threadIdx.x / 16;
   const int64_t e = (int64_t)blockIdx.x * 16 + el;
@@ -349,7 +350,12 @@ __global__ __launch_bounds__(kBlock) void tred_reduce_kernel(const float* __rest
     float t = 0.0f;
 #pragma unroll
     for (int g = 0; g < 16; ++g) t += red[g][el];
-    block[e] = t;
+    if (tcols > 0) {
+      const int64_t i = e / tcols, j = e - i * tcols;
+      block[j * (elems / tcols) + i] = t;
+    } else {
+      block[e] = t;
+    }
   }
 }
 
@@ -484,10 +490,10 @@ hipError_t launch_tred(const TredArgs& a, int nchunks, bool bf16, hipStream_t st
   return hipGetLastError();
 }
 
-hipError_t launch_tred_reduce(const float* partial, int nchunks, int64_t elems, float* block, hipStream_t st) {
+hipError_t launch_tred_reduce(const float* partial, int nchunks, int64_t elems, float* block, hipStream_t st, int tcols) {
   if (elems <= 0) return hipSuccess;
   int64_t grid = (elems + 15) / 16;
-  tred_reduce_kernel<<<(unsigned)grid, kBlock, 0, st>>>(partial, nchunks, elems, block);
+  tred_reduce_kernel<<<(unsigned)grid, kBlock, 0, st>>>(partial, nchunks, elems, block, tcols);
   return hipGetLastError();
 }
 
