@@ -8,8 +8,8 @@ One *step* is one pass of the whole hot path over the operator micro-benchmark s
     regression (Alg. 1, m = 1), T^T T, and the join-gather materialization,
 
 all through the C ABI, with every input already resident in HBM.  The plan (inverse index) is
-built once, outside the timed region.  `value` is the step's algorithmic bytes (the byte model
-of the design doc) divided by the step's wall time.  The JSON line also carries the per-operator
+built once, outside the timed region.  `value` is the step's algorithmic bytes (what each operator
+must read or write once: the `bytes_*` functions below) divided by the step's wall time.  The JSON line also carries the per-operator
 breakdown, gradient-descent iterations/s factorized vs materialized, the roofline entry of the
 dominant kernel (timed with HIP events inside the timed region) and the CPU oracle timed on a
 bounded sample of the same workload.
