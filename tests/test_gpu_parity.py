@@ -991,6 +991,31 @@ def test_rmm_sparse_sources_and_wide_operand(il):
     assert e < BF16_TOL
 
 
+# ------------------------------------------------------------------ calibration kernels
+@pytest.mark.parametrize("blocks", [1, 8192, None])
+def test_stream_probe_copies_reads_and_writes_whole_buffers(il, blocks):
+    # the plain streaming kernels behind the bench's bandwidth figures and the counter scaling: a copy moves every
+    # float, the write fills every float, whatever the launch shape (None: one float4 per thread, in address order)
+    n = 4 * 1_000_003                                    # not a multiple of the workgroup size
+    nb = n // 1024 + 1 if blocks is None else blocks
+    src = torch.arange(n, device="cuda", dtype=torch.float32)
+    dst = torch.zeros(n, device="cuda")
+    for kind in (0, 3):
+        dst.zero_()
+        il.ilargi_stream_probe(kind, dst, src, n, nb)
+        assert torch.equal(dst, src)
+    for kind in (2, 4):
+        dst.zero_()
+        il.ilargi_stream_probe(kind, dst, None, n, nb)
+        assert torch.equal(dst.view(-1, 4), torch.tensor([1.0, 2.0, 3.0, 4.0], device="cuda").expand(n // 4, 4))
+    sink = torch.zeros(nb, device="cuda")
+    il.ilargi_stream_probe(1, sink, torch.ones(n, device="cuda"), n, nb)
+    assert sink.sum().item() > 0.0
+    with pytest.raises(il.IlargiError) as ei:
+        il.ilargi_stream_probe(0, dst, src, n, (1 << 22) + 1)
+    assert ei.value.status == il.ERR_SHAPE
+
+
 # ------------------------------------------------------------------ streams
 def test_calls_on_a_side_stream(il):
     # everything a call enqueues goes to the stream it is given: results are right when the caller only
