@@ -244,6 +244,67 @@ __global__ __launch_bounds__(kBlock) void tred_bf16_kernel(TredArgs a) {
   }
 }
 
+// Form for a wide A against at most 32 columns of B, both addressed directly: the four wavefronts of a workgroup
+// take four neighbouring 64-column slabs of A over ALL rows of the chunk (B's few columns are read by each of
+// them), so nothing has to be combined through LDS and a chunk leaves one partial result instead of four shares.
+template <int NT>
+__global__ __launch_bounds__(kBlock) void tred_cs_kernel(TredArgs a) {
+  const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+  const int s = lane % 16, q = lane / 16;
+  int bx, by;
+  if (!tred_block_ids(a, bx, by)) return;
+  const int j0 = (by * (kBlock / kWave) + wave) * 64;
+  if (j0 >= a.ca) return;                                       // (no workgroup barrier below)
+  const int64_t t_lo = (int64_t)bx * a.rows_per_block;
+  const int64_t t_hi = min(min(t_lo + a.rows_per_block, a.n_rows), min(a.a_rows, a.b_rows));
+  v4f acc[4][NT];
+#pragma unroll
+  for (int e = 0; e < 4; ++e)
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) acc[e][nt] = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
+  const bool jok = j0 + 4 * s < a.ca;
+  bool nok[NT];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) nok[nt] = nt * 16 + s < a.cb;
+  for (int64_t base = t_lo; base < t_hi; base += 4 * kU) {
+    float4 av[kU];
+    float bv[kU][NT];
+#pragma unroll
+    for (int u = 0; u < kU; ++u) {
+      const int64_t t = base + u * 4 + q;
+      const bool live = t < t_hi;
+      av[u] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+      if (live && jok) av[u] = *reinterpret_cast<const float4*>(a.A + t * a.lda + j0 + 4 * s);
+      if (a.wptr != nullptr && live) {
+        const float w = (float)(a.wptr[t + 1] - a.wptr[t]);
+        av[u].x *= w; av[u].y *= w; av[u].z *= w; av[u].w *= w;
+      }
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) bv[u][nt] = (live && nok[nt]) ? a.B[t * a.ldb + a.bcol0 + nt * 16 + s] : 0.0f;
+    }
+#pragma unroll
+    for (int u = 0; u < kU; ++u)
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        acc[0][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u].x, bv[u][nt], acc[0][nt], 0, 0, 0);
+        acc[1][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u].y, bv[u][nt], acc[1][nt], 0, 0, 0);
+        acc[2][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u].z, bv[u][nt], acc[2][nt], 0, 0, 0);
+        acc[3][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u].w, bv[u][nt], acc[3][nt], 0, 0, 0);
+      }
+  }
+  // register r of lane (s, q), component e, tile nt: column j0 + 4 (4 q + r) + e of A, column 16 nt + s of B
+  float* out = a.partial + (int64_t)bx * a.ca * a.cb;
+#pragma unroll
+  for (int e = 0; e < 4; ++e)
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int j = j0 + 4 * (4 * q + r) + e, n = nt * 16 + s;
+        if (j < a.ca && n < a.cb) out[(int64_t)j * a.cb + n] = acc[e][nt][r];
+      }
+}
+
 // Form for tables with at most 48 columns: 16-column tiles of A read one float per lane, one MFMA per tile,
 // so that short rows do not leave three quarters of the MFMA rows empty.  JT <= 3, NT in {1, 2, 4}.
 template <int JT, int NT>
@@ -412,6 +473,12 @@ TredChoice tred_select(const TredArgs& a, bool bf16) {
     if (nt == 1) c.fn = vec4 ? tred_bf16_kernel<1, true> : tred_bf16_kernel<1, false>;
     else if (nt == 2) c.fn = vec4 ? tred_bf16_kernel<2, true> : tred_bf16_kernel<2, false>;
     else c.fn = vec4 ? tred_bf16_kernel<4, true> : tred_bf16_kernel<4, false>;
+    return c;
+  }
+  // wide A against at most 32 columns of B, direct addressing: the column-split kernel
+  if (a.ca >= 64 && a.cb <= 32 && vec4 && a.ia == nullptr && a.ib == nullptr && !a.upper_only) {
+    c.tiles = (a.ca + 255) / 256;                       // four 64-column slabs per workgroup
+    c.fn = nt == 1 ? tred_cs_kernel<1> : tred_cs_kernel<2>;
     return c;
   }
   if (a.ca <= 48) {
