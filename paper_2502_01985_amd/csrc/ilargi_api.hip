@@ -576,6 +576,26 @@ ilargi_status_t tmm_wide(ilargi_plan* pl, const float* Y, int cx, float* out, in
       ++c.n;
       continue;
     }
+    if (p.ident && !bf16 && cx % 4 == 0 && reinterpret_cast<uintptr_t>(Y) % 16 == 0 && colred_flat_supported(p.D, p.cols, cx) &&
+        p.cols * cx <= pl->lay.gpartial_floats) {
+      // short rows of an identity source, operand rows of whole float4s: flat float4 stream with plain FMAs instead
+      // of padded matrix-core tiles (with element-wise operand loads the matrix-core form measures faster)
+      ColredFlatArgs f;
+      memset(&f, 0, sizeof(f));
+      f.S = p.D; f.rows = p.rows; f.nvec = (int)(p.cols / 4);
+      f.Y = Y; f.ldy = cx; f.c = cx;
+      f.partial = pl->at<float>(pl->lay.o_gpartial);
+      int grid = 0;
+      {
+        TraceScope ts(pl, "colred", k, st);
+        HIP_TRY(launch_colred_flat(f, pl->lay.gpartial_floats, st, &grid));
+      }
+      HIP_TRY(launch_tred_reduce(f.partial, grid, p.cols * cx, pl->at<float>(p.o_g), st));
+      c.tcol2src[c.n] = pl->at<int32_t>(p.o_tcol);
+      c.G[c.n] = pl->at<float>(p.o_g);
+      ++c.n;
+      continue;
+    }
     if (p.ident) {
       g.B = Y;
     } else {

@@ -263,6 +263,14 @@ bool gram_sym_supported(const TredArgs& a);
 hipError_t launch_gram_sym(TredArgs& a, float* partial, int64_t partial_floats, float* block, hipStream_t st);
 hipError_t launch_tred(const TredArgs& a, int nchunks, bool bf16, hipStream_t st);
 void tred_occupancy(const TredArgs& a, bool bf16, int* slots, int* tiles);
+// G = S^T Y for an identity source with rows of at most 16 float4 and 5..16 operand columns (kernels_colred_flat.hip).
+struct ColredFlatArgs {
+  const float* S; int64_t rows; int nvec;   // rows x (4 nvec), 16-byte aligned
+  const float* Y; int ldy; int c;           // operand rows 0 .. rows - 1, columns 0 .. c - 1
+  float* partial;                           // [workgroup][4 nvec][c]
+};
+bool colred_flat_supported(const float* S, int64_t cols, int c);
+hipError_t launch_colred_flat(const ColredFlatArgs& a, int64_t partial_floats, hipStream_t st, int* grid_out);
 // tcols > 0: the summed (elems / tcols) x tcols matrix is written transposed
 hipError_t launch_tred_reduce(const float* partial, int nchunks, int64_t elems, float* block, hipStream_t st, int tcols = 0);
 hipError_t launch_colasm(const ColAsmArgs& a, int mode, hipStream_t st);
