@@ -192,6 +192,28 @@ def test_segment_sum(il, name, cx):
 
 
 # ------------------------------------------------------------------ wide operands (matrix-core kernels)
+@pytest.mark.parametrize("cx", [8, 13, 17, 32])
+@pytest.mark.parametrize("c_R", [64, 100, 260, 516])
+def test_transposed_multiply_of_a_wide_joined_table_with_few_operand_columns(il, c_R, cx):
+    # the column-split reduction: table widths that end inside a 64-column slab, beyond the four slabs of one
+    # workgroup (260, 516 columns), operand widths around the 16-column tiles, few rows per chunk
+    rng = datagen.rng_for(5200 + c_R + cx)
+    r_T, r_R, c_S = 2_003, 333, 4
+    S = rng.standard_normal((r_T, c_S)).astype(np.float32)
+    R = rng.standard_normal((r_R, c_R)).astype(np.float32)
+    fk = rng.integers(0, r_R, r_T).astype(np.int32)
+    fk[::19] = -1
+    c_T = c_S + c_R
+    sch = datagen.Schema([datagen.Source(S, None, np.arange(c_S, dtype=np.int32)),
+                          datagen.Source(R, fk, np.arange(c_S, c_T, dtype=np.int32))], r_T, c_T)
+    tg = oracle.Target(sch)
+    plan = il.ilargi_plan_create(il.schema_to_device(sch), r_T, c_T, max_cx=32)
+    Y = rng.standard_normal((r_T, cx)).astype(np.float32)
+    G1 = il.ilargi_tmm(plan, dev(Y)).cpu().numpy()
+    assert rel(G1, oracle.tmm(tg, Y)) < OP_TOL
+    assert np.array_equal(G1, il.ilargi_tmm(plan, dev(Y)).cpu().numpy())
+
+
 @pytest.mark.parametrize("cx", [33, 64, 65, 100, 130, 192])
 @pytest.mark.parametrize("c_R", [4, 36, 72, 200])
 def test_wide_product_of_a_joined_table_chunk_and_slab_tails(il, c_R, cx):
