@@ -192,6 +192,29 @@ def test_segment_sum(il, name, cx):
 
 
 # ------------------------------------------------------------------ wide operands (matrix-core kernels)
+@pytest.mark.parametrize("cx", [8, 12, 16])
+@pytest.mark.parametrize("c_S", [4, 8, 12, 20, 28, 44, 64])
+def test_transposed_multiply_of_a_short_row_entity_table(il, c_S, cx):
+    # the flat-stream column reduce: 1..16 float4 per row (64 / nvec whole rows per wavefront step, with idle lanes
+    # when nvec does not divide 64), a row count that ends inside a step, rows beyond the entity table
+    rng = datagen.rng_for(5300 + c_S + cx)
+    r_S, extra, r_R, c_R = 3_011, 7, 97, 12
+    r_T = r_S + extra                                        # the last target rows have no entity row
+    S = rng.standard_normal((r_S, c_S)).astype(np.float32)
+    R = rng.standard_normal((r_R, c_R)).astype(np.float32)
+    fk = rng.integers(0, r_R, r_T).astype(np.int32)
+    idx_S = np.concatenate([np.arange(r_S), np.full(extra, -1)]).astype(np.int32)
+    c_T = c_S + c_R
+    sch = datagen.Schema([datagen.Source(S, idx_S, np.arange(c_S, dtype=np.int32)),
+                          datagen.Source(R, fk, np.arange(c_S, c_T, dtype=np.int32))], r_T, c_T)
+    tg = oracle.Target(sch)
+    plan = il.ilargi_plan_create(il.schema_to_device(sch), r_T, c_T, max_cx=16)
+    Y = rng.standard_normal((r_T, cx)).astype(np.float32)
+    G1 = il.ilargi_tmm(plan, dev(Y)).cpu().numpy()
+    assert rel(G1, oracle.tmm(tg, Y)) < OP_TOL
+    assert np.array_equal(G1, il.ilargi_tmm(plan, dev(Y)).cpu().numpy())
+
+
 @pytest.mark.parametrize("cx", [8, 13, 17, 32])
 @pytest.mark.parametrize("c_R", [64, 100, 260, 516])
 def test_transposed_multiply_of_a_wide_joined_table_with_few_operand_columns(il, c_R, cx):
