@@ -340,7 +340,7 @@ def unsupervised(il, torch, plan, mplan, sch, k=10):
 
 
 def sparse_tables(il, torch, datagen, dev):
-    """Source tables kept in compressed sparse rows (Sec. 3.1; sparsity sweep of Tab. 4) on the config-1 centre
+    """Source tables kept in compressed sparse rows (Sec. 3.1; sparsity sweep of Tab. 3) on the config-1 centre
     schema with a fraction p of the cells set to zero: one gradient-descent iteration and the one-column
     multiplies, tables sparse vs the same tables dense (zeros stored)."""
     out = {}
@@ -438,7 +438,7 @@ def wide_batch(il, torch, datagen, dev):
     return out
 
 
-CHOOSER_ITERATIONS = 200   # the paper's training length (Sec. 5.1)
+CHOOSER_ITERATIONS = 200   # the paper's training length (Sec. 4.1)
 
 
 def chooser_record(il, name, shp, r_T, c_T, t_fact, t_mat, t_join):

@@ -229,7 +229,7 @@ def tiny_random_schema(seed: int, r_T: int = 9, c_T: int = 7, n: int = 3,
 
 def sparsify(schema: Schema, p: float, seed: int) -> Schema:
     """A copy of ``schema`` whose table cells are set to zero independently with probability ``p`` (the sparsity
-    parameter of the paper's synthetic data, Tab. 4); index arrays and column maps are shared with the original.
+    parameter of the paper's synthetic data, Tab. 3); index arrays and column maps are shared with the original.
     Draw order: one uniform matrix per source, in source order."""
     rng = rng_for(seed)
     sources = []

@@ -120,7 +120,8 @@ ilargi_status_t ilargi_rmm(ilargi_plan_t* plan, const float* X, int64_t cx, floa
  * residual buffer as scratch), and is limited to c_T <= 16384 (else UNSUPPORTED). */
 ilargi_status_t ilargi_crossprod(ilargi_plan_t* plan, float* out, void* stream);
 
-/* Join-gather baseline: write the materialized target table.  T device r_T x c_T.  Each cell is the
+/* Join-gather baseline (paper, Sec. 2.2: the rewrite rule with X = I, i.e. T = sum_k I_k D_k M_k^T written
+ * out): write the materialized target table.  T device r_T x c_T.  Each cell is the
  * float32 sum, in source order starting from +0.0, of the source cells mapped to it; cells nobody
  * maps to are +0.0.  The result is reproducible bit for bit. */
 ilargi_status_t ilargi_materialize(ilargi_plan_t* plan, float* T, void* stream);
@@ -137,7 +138,7 @@ ilargi_status_t ilargi_gd_step(ilargi_plan_t* plan, ilargi_model_t model, float*
                                ilargi_precision_t precision, void* stream);
 
 /* One Lloyd iteration of KMeans over the rows of T without materializing it (KMeans is one of the models
- * evaluated in Sec. 5, Tab. 7-9; the paper prints no algorithm for it, this is the textbook one):
+ * evaluated in Sec. 4, Tab. 7-9; the paper prints no algorithm for it, this is the textbook one):
  *   a_i = argmin_j ||t_i - c_j||^2  taken as  argmin_j (||c_j||^2 - 2 (T C)_ij),  the first j among equals,
  *   c_j <- mean of the rows with a_i = j  =  (T^T A)_j / n_j  with A the 0/1 assignment matrix;
  *   a centroid without rows keeps its place.
@@ -149,7 +150,7 @@ ilargi_status_t ilargi_kmeans_step(ilargi_plan_t* plan, float* C, int64_t k, int
                                    void* stream);
 
 /* One round of multiplicative updates of Gaussian NMF, T ~ W H with non-negative factors (Gaussian NMF is one
- * of the models evaluated in Sec. 5, Tab. 7-9; the paper prints no algorithm, these are the updates of Lee and
+ * of the models evaluated in Sec. 4, Tab. 7-9; the paper prints no algorithm, these are the updates of Lee and
  * Seung for the squared Frobenius error):
  *   W <- W o (T H^T) (/) max(W (H H^T), 1e-30)          (left multiply by H^T),
  *   H <- H o (W^T T) (/) max((W^T W) H, 1e-30)          (transposed multiply by the new W).
@@ -207,7 +208,7 @@ typedef struct {
   double complexity_ratio;   /* Eq. (1) for linear regression, dense operands: O_materialized / O_factorized */
   double tuple_ratio;        /* r_T / (rows of the sources that have a row_idx) */
   double feature_ratio;      /* (columns of those sources) / (columns of the identity sources) */
-  int morpheus_rule;         /* 1 = tuple_ratio >= 5 and feature_ratio >= 1 (the thresholds Sec. 5.3 quotes) */
+  int morpheus_rule;         /* 1 = tuple_ratio >= 5 and feature_ratio >= 1 (the thresholds Sec. 4.3 quotes) */
   double bytes_factorized;   /* bytes one iteration moves, factorized */
   double bytes_materialized; /* the same on the materialized table */
   double bytes_join;         /* bytes the join itself moves (once) */

@@ -39,7 +39,7 @@ Readings of the paper taken here (each is also listed in the design document):
   instead is a property this file does not use; the pins check when it holds (every target cell
   fed by exactly one source cell; for times and divide always).
 
-* KMeans and Gaussian NMF are named among the evaluated models (Sec. 5, Tab. 7-9) and defined nowhere in
+* KMeans and Gaussian NMF are named among the evaluated models (Sec. 4, Tab. 7-9) and defined nowhere in
   the paper.  Read, for KMeans, one iteration of Lloyd's algorithm on the rows of the target table: every
   row goes to the centroid at the smallest squared Euclidean distance (the first one among equals), every
   centroid becomes the mean of its rows, a centroid without rows stays where it was.  Read, for Gaussian NMF,
@@ -389,7 +389,7 @@ def complexity_lr(schema) -> Tuple[int, int]:
 
 
 def tuple_and_feature_ratio(schema) -> Tuple[float, float]:
-    """The redundancy measures Sec. 5.3 compares with (thresholds 5 and 1): target rows per row of the joined
+    """The redundancy measures Sec. 4.3 compares with (thresholds 5 and 1): target rows per row of the joined
     tables and joined columns per column of the base table.  Read for several tables: sums over the sources
     that are joined through a row index, against the sources that are not."""
     joined = [s for s in schema.sources if s.row_idx is not None]
@@ -401,7 +401,7 @@ def tuple_and_feature_ratio(schema) -> Tuple[float, float]:
     return tr, fr
 
 
-# ----------------------------------------------------------------------------- KMeans, Gaussian NMF (named in Sec. 5; see the readings above)
+# ----------------------------------------------------------------------------- KMeans, Gaussian NMF (named in Sec. 4; see the readings above)
 GNMF_TINY = 1e-30
 
 

@@ -1,4 +1,4 @@
-"""Builds libilargi.so (HIP, gfx950) and the C parts of the test oracle, in-tree."""
+"""Builds libilargi.so (HIP, gfx950) in-tree.  The test oracle is numpy only and needs no build step."""
 from __future__ import annotations
 
 import os

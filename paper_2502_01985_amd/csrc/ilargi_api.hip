@@ -76,6 +76,8 @@ struct Layout {
 
 }  // namespace
 
+ilargi_status_t ilargi::set_error(ilargi_status_t code, const char* msg) { return fail(code, "%s", msg); }
+
 struct ilargi_plan {
   int n = 0;
   int64_t r_T = 0, c_T = 0, max_cx = 0;

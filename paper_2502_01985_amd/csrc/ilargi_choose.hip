@@ -1,6 +1,6 @@
 // Factorize or materialize?  (Sec. 3: complexity ratio of Eq. (1), the tuple-ratio / feature-ratio rule the
-// paper compares with, and the "theoretical memory I/O normalised by memory bandwidth" feature of Sec. 3.3
-// turned into a prediction.)  Host code only: reads shapes, touches no device.
+// paper compares with, and the estimator input of Sec. 3.3 that prices memory traffic against the
+// memory bandwidth, turned into a prediction.)  Host code only: reads shapes, touches no device.
 //
 // The byte model prices one gradient-descent iteration of this library, operator by operator:
 //   factorized   tables: the largest identity source once (its product, residual and gradient share a pass),
@@ -18,7 +18,7 @@
 #include <cmath>
 #include <cstdint>
 
-#include "ilargi.h"
+#include "ilargi_internal.h"
 
 namespace {
 constexpr double kFusedMaxCols = 256.0;   // widest table whose product, residual and gradient share one pass
@@ -27,13 +27,13 @@ constexpr double kMinFetch = 32.0;        // bytes a gathered row costs at least
 
 extern "C" ilargi_status_t ilargi_choose(int n, const ilargi_source_t* sources, int64_t r_T, int64_t c_T,
                                          const ilargi_workload_t* workload, ilargi_choice_t* out) {
-  if (sources == nullptr || out == nullptr) return ILARGI_ERR_NULL;
-  if (n < 1 || n > 16 || r_T < 0 || c_T < 1) return ILARGI_ERR_SHAPE;
+  if (sources == nullptr || out == nullptr) return ilargi::set_error(ILARGI_ERR_NULL, "choose: sources or out is NULL");
+  if (n < 1 || n > 16 || r_T < 0 || c_T < 1) return ilargi::set_error(ILARGI_ERR_SHAPE, "choose: n outside [1, 16], r_T < 0 or c_T < 1");
   for (int k = 0; k < n; ++k)
-    if (sources[k].rows < 0 || sources[k].cols < 0) return ILARGI_ERR_SHAPE;
+    if (sources[k].rows < 0 || sources[k].cols < 0) return ilargi::set_error(ILARGI_ERR_SHAPE, "choose: a source has negative rows or cols");
   ilargi_workload_t w = {200, 1, 0.0, 0.0};
   if (workload != nullptr) w = *workload;
-  if (w.iterations < 1 || w.models < 1) return ILARGI_ERR_SHAPE;
+  if (w.iterations < 1 || w.models < 1) return ilargi::set_error(ILARGI_ERR_SHAPE, "choose: iterations and models must be at least 1");
   const double bw = w.bytes_per_second > 0.0 ? w.bytes_per_second : 5.0e12;
   const double launch = w.launch_seconds > 0.0 ? w.launch_seconds : 2.5e-6;
 

@@ -219,6 +219,9 @@ struct ColAsmArgs {
 
 struct GramAsmPair { const float* block; int k, l, cb; };
 
+// Records `msg` as the calling thread's last error (what ilargi_last_error returns) and returns `code`.
+ilargi_status_t set_error(ilargi_status_t code, const char* msg);
+
 // ---- launchers (each enqueues on `st`; returns the HIP error of the launch) ----
 hipError_t launch_check_idx(const int32_t* idx, int64_t r_T, int64_t r_k, int32_t* flags, hipStream_t st);
 hipError_t launch_sort_by_source_row(const int32_t* idx, int64_t r_T, int64_t r_k, int32_t* keys_a,

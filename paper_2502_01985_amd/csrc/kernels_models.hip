@@ -1,5 +1,5 @@
 // Small kernels around the factorized operators for the two unsupervised models the paper evaluates next to the
-// regressions (Sec. 5, Tab. 7-9): one Lloyd iteration of KMeans and one round of multiplicative updates of
+// regressions (Sec. 4, Tab. 7-9): one Lloyd iteration of KMeans and one round of multiplicative updates of
 // Gaussian NMF.  The passes over the source tables are the left multiply and the transposed multiply; what is
 // left are row-local steps on r_T x k (or c_T x k) matrices with k small:
 //   KMeans:  a_i = argmin_j (|c_j|^2 - 2 (T C)_ij)   (|t_i|^2 is the same for every j), the 0/1 assignment matrix

@@ -1,5 +1,5 @@
 // Source tables in compressed sparse rows (the paper keeps its matrices sparse, Sec. 3.1, and sweeps the sparsity
-// of the tables, Tab. 4).  A sparse source D_k = (rowptr, col, val) takes part in the same operators:
+// of the tables, Tab. 3).  A sparse source D_k = (rowptr, col, val) takes part in the same operators:
 //   P_k = D_k X_k        row-wise: a group of lanes walks the entries of a row, X_k sits in LDS;
 //   G_k = D_k^T Z_k      column-wise over a column-sorted view built with the plan (the stable sort that builds
 //                        the inverse index of a row index, applied to the column indices): entries of a column

@@ -36,6 +36,18 @@ def rel(a, b):
     return float(np.linalg.norm(a - b) / (nb if nb > 0 else 1.0))
 
 
+def assert_each_element(got, want, A, B, tol=OP_TOL):
+    """Per-element bound beside the norm: every entry of a product A @ B computed in float32 lies within
+    tol * (|A| @ |B|) of the exact one (the componentwise rounding bound of a sum of products, whatever the
+    order of the additions), so no single wrong entry can hide behind the norm of the others."""
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    scale = np.abs(np.asarray(A, dtype=np.float64)) @ np.abs(np.asarray(B, dtype=np.float64))
+    excess = np.abs(got - want) - (tol * scale + 1e-30)
+    worst = np.unravel_index(np.argmax(excess), excess.shape) if excess.size else None
+    assert excess.size == 0 or excess.max() <= 0, f"entry {worst}: got {got[worst]}, want {want[worst]}, scale {scale[worst]}"
+
+
 def dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
@@ -139,7 +151,9 @@ def test_lmm(il, name, cx):
     sch, tg, plan = get(il, name)
     X = datagen.rng_for(1000 + cx).standard_normal((sch.c_T, cx)).astype(np.float32)
     got = il.ilargi_lmm(plan, dev(X)).cpu().numpy()
-    assert rel(got, oracle.lmm(tg, X)) < OP_TOL
+    want = oracle.lmm(tg, X)
+    assert rel(got, want) < OP_TOL
+    assert_each_element(got, want, tg.T32, X)
 
 
 @pytest.mark.parametrize("name", ["config0", "tiny_mixed", "odd_cols"])
@@ -161,7 +175,9 @@ def test_tmm(il, name, cx):
     sch, tg, plan = get(il, name)
     Y = datagen.rng_for(2000 + cx).standard_normal((sch.r_T, cx)).astype(np.float32)
     got = il.ilargi_tmm(plan, dev(Y)).cpu().numpy()
-    assert rel(got, oracle.tmm(tg, Y)) < OP_TOL
+    want = oracle.tmm(tg, Y)
+    assert rel(got, want) < OP_TOL
+    assert_each_element(got, want, tg.T32.T, Y)
 
 
 @pytest.mark.parametrize("name", ["config2_small", "config3_small"])
@@ -450,7 +466,9 @@ def test_bf16_first_gradient_step_exact_on_representable_inputs(il, c_S, m):
 def test_crossprod(il, name):
     sch, tg, plan = get(il, name)
     G = il.ilargi_crossprod(plan).cpu().numpy()
-    assert rel(G, oracle.crossprod(tg)) < OP_TOL
+    want = oracle.crossprod(tg)
+    assert rel(G, want) < OP_TOL
+    assert_each_element(G, want, tg.T32.T, tg.T32)
     assert np.array_equal(G, G.T)
 
 

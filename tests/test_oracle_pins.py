@@ -391,6 +391,20 @@ def test_elementwise_functions_with_a_restricted_domain(op):
     np.testing.assert_allclose(got, want, rtol=1e-12)
 
 
+def test_abs_against_a_table_written_by_hand():
+    # |t| cell by cell on a table with negative, zero and positive cells; the expected values are typed in
+    A = np.array([[-1.5, 2.0, 0.0], [3.25, -0.125, -7.0]])
+    want = np.array([[1.5, 2.0, 0.0], [3.25, 0.125, 7.0]])
+    assert np.array_equal(oracle.apply_elementwise(A, "abs"), want)
+    assert not np.array_equal(oracle.apply_elementwise(A, "abs"), A)
+    # on a factorized table: S = [[-1], [2]], R = [[-3, 4]], both target rows join R's only row
+    S = np.array([[-1.0], [2.0]], dtype=np.float32)
+    R = np.array([[-3.0, 4.0]], dtype=np.float32)
+    sch = datagen.Schema([datagen.Source(S, None, np.array([0], dtype=np.int32)),
+                          datagen.Source(R, np.array([0, 0], dtype=np.int32), np.array([1, 2], dtype=np.int32))], 2, 3)
+    assert np.array_equal(oracle.elementwise(sch, "abs"), np.array([[1.0, 3.0, 4.0], [2.0, 3.0, 4.0]]))
+
+
 def test_elementwise_closed_forms():
     sch = _star(46, positive=True)
     T = oracle.brute_force_target(sch)
@@ -444,6 +458,24 @@ def test_complexity_of_linear_regression_by_hand_and_by_parts():
     one = datagen.Schema([datagen.Source(sch.sources[0].D, None, np.arange(2, dtype=np.int32))], 6, 2)
     assert oracle.complexity_lr(one)[0] == oracle.complexity_lr(one)[1]
     assert oracle.tuple_and_feature_ratio(sch) == (2.0, 2.0)
+
+
+def test_tuple_ratio_and_feature_ratio_on_schemas_where_they_differ():
+    # worked by hand (the redundancy measures Sec. 4.3 compares with; config 1 is quoted as "tuple ratio 10 and
+    # feature ratio 10" for S 1,000,000 x 20 and R 100,000 x 200, which fixes which ratio is which):
+    #   S 6 x 2 joined with R 3 x 8:   tuple ratio = 6 / 3 = 2,     feature ratio = 8 / 2 = 4
+    sch = datagen.star_schema(datagen.rng_for(53), 6, 2, [(3, 8, "uniform")])
+    assert oracle.tuple_and_feature_ratio(sch) == (2.0, 4.0)
+    #   S 20 x 4 joined with R 2 x 2:  tuple ratio = 20 / 2 = 10,   feature ratio = 2 / 4 = 0.5
+    sch = datagen.star_schema(datagen.rng_for(54), 20, 4, [(2, 2, "uniform")])
+    assert oracle.tuple_and_feature_ratio(sch) == (10.0, 0.5)
+    #   two joined tables, S 12 x 3 with R1 4 x 5 and R2 2 x 1:  12 / (4 + 2) = 2,  (5 + 1) / 3 = 2
+    #   (and with R2 2 x 4 instead: 2 and 3)
+    sch = datagen.star_schema(datagen.rng_for(55), 12, 3, [(4, 5, "uniform"), (2, 4, "uniform")])
+    assert oracle.tuple_and_feature_ratio(sch) == (2.0, 3.0)
+    # the scaled-down shape of config 1's centre: both ratios 10, neither confused with r_T or c_T
+    sch = datagen.star_schema(datagen.rng_for(56), 1_000, 20, [(100, 200, "uniform")])
+    assert oracle.tuple_and_feature_ratio(sch) == (10.0, 10.0)
 
 
 def test_complexity_ratio_grows_with_redundancy():
