@@ -95,6 +95,26 @@ ilargi_status_t ilargi_plan_create(int n, const ilargi_source_t* sources, int64_
                                    int64_t max_cx, void* workspace, size_t workspace_bytes,
                                    void* stream, ilargi_plan_t** plan);
 
+/* ilargi_plan_create for callers that cannot allocate device memory (code that must not call hipMalloc: tight
+ * serving loops, harnesses that forbid allocation, set-up code running beside a captured graph): the plan's
+ * device state lives in a scratch array that is part of the library itself, ilargi_static_scratch_bytes() bytes
+ * (128 MiB) on every GPU the library is used on, held until the process ends.  The call allocates no device
+ * memory and calls no allocating routine.  Same arguments, validation, results and errors as
+ * ilargi_plan_create, and the plan serves every operator in the same way (bit-identical results), with
+ * these limits:
+ *   - a plan that needs more than the array holds (see ilargi_plan_workspace_bytes) is refused with WORKSPACE;
+ *   - one such plan per device at a time: while it lives, another ilargi_plan_create_static on that device is
+ *     refused with WORKSPACE; ilargi_plan_destroy releases the array;
+ *   - the array keeps the last plan's contents; the call initialises every region it reads.  Calls from several
+ *     threads that create static plans on one device are serialised by the library, but work that a destroyed
+ *     plan still has in flight on a stream races with the next plan's set-up: synchronize before destroying.
+ * The current device at the time of the call selects the array. */
+ilargi_status_t ilargi_plan_create_static(int n, const ilargi_source_t* sources, int64_t r_T, int64_t c_T,
+                                          int64_t max_cx, void* stream, ilargi_plan_t** plan);
+
+/* Size in bytes of the scratch array behind ilargi_plan_create_static. */
+size_t ilargi_static_scratch_bytes(void);
+
 /* Release the host object.  The workspace and all borrowed arrays stay with the caller. */
 ilargi_status_t ilargi_plan_destroy(ilargi_plan_t* plan);
 

@@ -36,12 +36,13 @@ STATUS_NAMES = ["OK", "ERR_NULL", "ERR_SHAPE", "ERR_COLMAP", "ERR_INDEX_RANGE", 
                 "ERR_UNSUPPORTED", "ERR_DEVICE"]
 
 EXPORTED = [
-    "ilargi_plan_workspace_bytes", "ilargi_plan_create", "ilargi_plan_destroy", "ilargi_lmm", "ilargi_tmm",
+    "ilargi_plan_workspace_bytes", "ilargi_plan_create", "ilargi_plan_create_static", "ilargi_plan_destroy", "ilargi_lmm", "ilargi_tmm",
     "ilargi_rmm", "ilargi_crossprod", "ilargi_materialize", "ilargi_gd_step", "ilargi_kmeans_step", "ilargi_gnmf_step",
     "ilargi_elementwise", "ilargi_row_sum",
     "ilargi_col_sum", "ilargi_choose", "ilargi_segment_sum",
     "ilargi_plan_inverse_index", "ilargi_plan_trace_begin", "ilargi_plan_trace_label", "ilargi_plan_trace_end",
     "ilargi_plan_trace_name", "ilargi_stream_probe",
+    "ilargi_static_scratch_bytes",
     "ilargi_last_error",
     "ilargi_version",
 ]
@@ -59,6 +60,8 @@ lib.ilargi_plan_workspace_bytes.argtypes = [_int, ctypes.POINTER(SourceStruct), 
                                             ctypes.POINTER(ctypes.c_size_t)]
 lib.ilargi_plan_create.argtypes = [_int, ctypes.POINTER(SourceStruct), _i64, _i64, _i64, _vp, ctypes.c_size_t, _vp,
                                    ctypes.POINTER(_vp)]
+lib.ilargi_plan_create_static.argtypes = [_int, ctypes.POINTER(SourceStruct), _i64, _i64, _i64, _vp, ctypes.POINTER(_vp)]
+lib.ilargi_static_scratch_bytes.argtypes = []
 lib.ilargi_plan_destroy.argtypes = [_vp]
 lib.ilargi_lmm.argtypes = [_vp, _vp, _i64, _vp, _int, _vp]
 lib.ilargi_tmm.argtypes = [_vp, _vp, _i64, _vp, _int, _vp]
@@ -78,8 +81,9 @@ lib.ilargi_plan_trace_end.argtypes = [_vp, ctypes.POINTER(ctypes.c_float), _int,
 lib.ilargi_plan_trace_label.argtypes = [_vp, ctypes.c_char_p]
 lib.ilargi_plan_trace_name.argtypes = [_vp, _int, ctypes.c_char_p, _int]
 lib.ilargi_stream_probe.argtypes = [_int, _vp, _vp, _i64, _int, _vp]
-for _name in EXPORTED[:-2]:
+for _name in EXPORTED[:-3]:
     getattr(lib, _name).restype = _int
+lib.ilargi_static_scratch_bytes.restype = ctypes.c_size_t
 lib.ilargi_last_error.restype = ctypes.c_char_p
 lib.ilargi_version.restype = ctypes.c_char_p
 
@@ -182,9 +186,10 @@ def ilargi_plan_workspace_bytes(sources, r_T: int, c_T: int, max_cx: int) -> int
 class Plan:
     """Owns the plan handle, its device workspace and references to the borrowed tensors."""
 
-    def __init__(self, handle: int, workspace, borrowed, r_T: int, c_T: int, max_cx: int, src_shapes):
+    def __init__(self, handle: int, workspace, borrowed, r_T: int, c_T: int, max_cx: int, src_shapes, device=None):
         self.handle = handle
-        self.workspace = workspace
+        self.workspace = workspace          # None: the plan lives in the library's static scratch array
+        self.device = device if device is not None else workspace.device
         self._borrowed = borrowed
         self.r_T, self.c_T, self.max_cx = r_T, c_T, max_cx
         self.src_shapes = src_shapes
@@ -201,10 +206,7 @@ class Plan:
             pass
 
 
-def ilargi_plan_create(sources, r_T: int, c_T: int, max_cx: int = 1, stream=None) -> Plan:
-    """``sources``: list of ``(D, row_idx, col_map)`` with ``D`` a float32 CUDA tensor ``r_k x c_k``,
-    ``row_idx`` an int32 CUDA tensor of length ``r_T`` or ``None`` (identity) and ``col_map`` an int32
-    host array of length ``c_k``."""
+def _marshal_sources(sources, r_T: int):
     torch = _torch()
     tuples, borrowed, shapes = [], [], []
     for D, row_idx, col_map in sources:
@@ -230,11 +232,25 @@ def ilargi_plan_create(sources, r_T: int, c_T: int, max_cx: int = 1, stream=None
         borrowed.append((D, row_idx))
         shapes.append((int(D.shape[0]), int(D.shape[1])))
         tuples.append((D.data_ptr(), int(D.shape[0]), int(D.shape[1]), iptr, np.asarray(col_map, dtype=np.int32)))
+    return tuples, borrowed, shapes
+
+
+def _source_device(sources):
+    D = sources[0][0]
+    return D.device
+
+
+def ilargi_plan_create(sources, r_T: int, c_T: int, max_cx: int = 1, stream=None) -> Plan:
+    """``sources``: list of ``(D, row_idx, col_map)`` with ``D`` a float32 CUDA tensor ``r_k x c_k``,
+    ``row_idx`` an int32 CUDA tensor of length ``r_T`` or ``None`` (identity) and ``col_map`` an int32
+    host array of length ``c_k``."""
+    torch = _torch()
+    tuples, borrowed, shapes = _marshal_sources(sources, r_T)
     arr, keep = make_source_array(tuples)
     nbytes = ctypes.c_size_t(0)
     _check(lib.ilargi_plan_workspace_bytes(len(tuples), arr, r_T, c_T, max_cx, ctypes.byref(nbytes)),
            "ilargi_plan_workspace_bytes")
-    workspace = torch.empty(int(nbytes.value) + 256, dtype=torch.uint8, device=sources[0][0].device)
+    workspace = torch.empty(int(nbytes.value) + 256, dtype=torch.uint8, device=_source_device(sources))
     base = workspace.data_ptr()
     aligned = (base + 255) // 256 * 256
     handle = _vp(0)
@@ -242,6 +258,25 @@ def ilargi_plan_create(sources, r_T: int, c_T: int, max_cx: int = 1, stream=None
                                   _stream_ptr(stream), ctypes.byref(handle)), "ilargi_plan_create")
     del keep
     return Plan(handle.value, workspace, borrowed, r_T, c_T, max_cx, shapes)
+
+
+def ilargi_static_scratch_bytes() -> int:
+    return int(lib.ilargi_static_scratch_bytes())
+
+
+def ilargi_plan_create_static(sources, r_T: int, c_T: int, max_cx: int = 1, stream=None) -> Plan:
+    """Like ``ilargi_plan_create``, but the plan lives in the library's static scratch array: no device memory
+    is allocated, here or in the library.  One such plan per device at a time (``plan.destroy()`` frees the array)."""
+    torch = _torch()
+    tuples, borrowed, shapes = _marshal_sources(sources, r_T)
+    arr, keep = make_source_array(tuples)
+    device = _source_device(sources)
+    handle = _vp(0)
+    with torch.cuda.device(device):
+        _check(lib.ilargi_plan_create_static(len(tuples), arr, r_T, c_T, max_cx, _stream_ptr(stream),
+                                             ctypes.byref(handle)), "ilargi_plan_create_static")
+    del keep
+    return Plan(handle.value, None, borrowed, r_T, c_T, max_cx, shapes, device=device)
 
 
 def ilargi_lmm(plan: Plan, X, out=None, precision: int = F32, stream=None):
@@ -278,7 +313,7 @@ def ilargi_rmm(plan: Plan, X, out=None, precision: int = F32, stream=None):
     if X.numel() != plan.r_T * cx:
         raise TypeError("X must be cx x r_T")
     if out is None:
-        out = torch.empty((cx, plan.c_T), dtype=torch.float32, device=plan.workspace.device)
+        out = torch.empty((cx, plan.c_T), dtype=torch.float32, device=plan.device)
     _dev_f32(out, "out")
     _check(lib.ilargi_rmm(plan.handle, X.data_ptr() if X.numel() else None, cx, out.data_ptr(), precision,
                           _stream_ptr(stream)), "ilargi_rmm")
@@ -328,7 +363,7 @@ def ilargi_gnmf_step(plan: Plan, W, Ht, stream=None):
 def ilargi_crossprod(plan: Plan, out=None, stream=None):
     torch = _torch()
     if out is None:
-        out = torch.empty((plan.c_T, plan.c_T), dtype=torch.float32, device=plan.workspace.device)
+        out = torch.empty((plan.c_T, plan.c_T), dtype=torch.float32, device=plan.device)
     _dev_f32(out, "out")
     _check(lib.ilargi_crossprod(plan.handle, out.data_ptr(), _stream_ptr(stream)), "ilargi_crossprod")
     return out
@@ -337,7 +372,7 @@ def ilargi_crossprod(plan: Plan, out=None, stream=None):
 def ilargi_materialize(plan: Plan, out=None, stream=None):
     torch = _torch()
     if out is None:
-        out = torch.empty((plan.r_T, plan.c_T), dtype=torch.float32, device=plan.workspace.device)
+        out = torch.empty((plan.r_T, plan.c_T), dtype=torch.float32, device=plan.device)
     _dev_f32(out, "T")
     _check(lib.ilargi_materialize(plan.handle, out.data_ptr(), _stream_ptr(stream)), "ilargi_materialize")
     return out
@@ -422,7 +457,7 @@ def ilargi_elementwise(plan: Plan, op, x: float = 0.0, outs=None, stream=None):
 def ilargi_row_sum(plan: Plan, out=None, stream=None):
     torch = _torch()
     if out is None:
-        out = torch.empty(plan.r_T, dtype=torch.float32, device=plan.workspace.device)
+        out = torch.empty(plan.r_T, dtype=torch.float32, device=plan.device)
     _dev_f32(out, "out")
     _check(lib.ilargi_row_sum(plan.handle, out.data_ptr() if out.numel() else None, _stream_ptr(stream)), "ilargi_row_sum")
     return out
@@ -431,7 +466,7 @@ def ilargi_row_sum(plan: Plan, out=None, stream=None):
 def ilargi_col_sum(plan: Plan, out=None, stream=None):
     torch = _torch()
     if out is None:
-        out = torch.empty(plan.c_T, dtype=torch.float32, device=plan.workspace.device)
+        out = torch.empty(plan.c_T, dtype=torch.float32, device=plan.device)
     _dev_f32(out, "out")
     _check(lib.ilargi_col_sum(plan.handle, out.data_ptr(), _stream_ptr(stream)), "ilargi_col_sum")
     return out
@@ -459,15 +494,18 @@ def ilargi_plan_inverse_index(plan: Plan, k: int):
     if not rp.value:
         return None, None
     torch.cuda.synchronize()
-    ws = plan.workspace
-    base = ws.data_ptr()
     r_k = plan.src_shapes[k][0]
 
-    def view(ptr, count):
-        off = ptr - base
-        return ws[off:off + 4 * count].view(torch.int32).cpu().numpy().copy()
+    def fetch(ptr, count):
+        # a plain device-to-host copy of `count` int32 values through the HIP runtime the library is bound to
+        host = np.empty(count, dtype=np.int32)
+        if count:
+            rc = lib.hipMemcpy(_vp(host.ctypes.data), _vp(ptr), ctypes.c_size_t(4 * count), 2)   # 2 = device to host
+            if rc != 0:
+                raise RuntimeError(f"hipMemcpy failed with {rc}")
+        return host
 
-    return view(rp.value, r_k + 1), view(pm.value, int(nnz.value))
+    return fetch(rp.value, r_k + 1), fetch(pm.value, int(nnz.value))
 
 
 def ilargi_plan_trace_begin(plan: Plan, tag: str, max_launches: int) -> None:

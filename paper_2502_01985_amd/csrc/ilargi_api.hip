@@ -5,6 +5,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -76,6 +77,22 @@ struct Layout {
 
 }  // namespace
 
+// Scratch of ilargi_plan_create_static: one array per GPU, part of the library's code object, so a caller that
+// cannot allocate device memory still gets a plan.  The array's name is only a host-side handle of the symbol;
+// the device address is looked up once per device with hipGetSymbolAddress and used from then on.
+constexpr size_t kStaticScratchBytes = 128ull << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+struct StaticSlot {
+  void* ptr = nullptr;            // device address of `scratch` on this device
+  ilargi_plan* owner = nullptr;   // the live plan that occupies it (at most one per device)
+};
+StaticSlot g_static[kMaxDevices];
+std::mutex g_static_mutex;
+}  // namespace
+
 ilargi_status_t ilargi::set_error(ilargi_status_t code, const char* msg) { return fail(code, "%s", msg); }
 
 struct ilargi_plan {
@@ -94,6 +111,7 @@ struct ilargi_plan {
   bool mat_flat = false;  // ... and every group is an aligned float4 of its source
   bool mat_cols = false;  // the per-column feeder tables (at most two feeders per column) are valid
   int npairs = 0;
+  int static_dev = -1;   // >= 0: the workspace is the library's static scratch array of that device
   std::vector<size_t> block_off;  // offset (floats) of Gram block (k,l), k <= l, index k * n + l
   // optional timing of one kernel family: event pairs recorded around every launch whose tag matches
   std::string trace_tag;            // "*" traces every kernel family
@@ -715,9 +733,15 @@ ilargi_status_t ilargi_plan_workspace_bytes(int n, const ilargi_source_t* source
   return ILARGI_OK;
 }
 
-ilargi_status_t ilargi_plan_create(int n, const ilargi_source_t* sources, int64_t r_T, int64_t c_T,
-                                   int64_t max_cx, void* workspace, size_t workspace_bytes, void* stream,
-                                   ilargi_plan_t** plan) {
+}  // extern "C"
+
+namespace {
+
+// Both ways of creating a plan: static_dev < 0 takes the caller's workspace, static_dev >= 0 the library's
+// scratch array of that device (its address in `workspace`).
+ilargi_status_t plan_create_impl(int n, const ilargi_source_t* sources, int64_t r_T, int64_t c_T,
+                                 int64_t max_cx, void* workspace, size_t workspace_bytes, void* stream,
+                                 ilargi_plan_t** plan, int static_dev) {
   if (plan == nullptr) return fail(ILARGI_ERR_NULL, "plan is NULL");
   std::vector<SourcePlan> src;
   Layout lay;
@@ -751,7 +775,11 @@ ilargi_status_t ilargi_plan_create(int n, const ilargi_source_t* sources, int64_
   }
   if (workspace == nullptr) return fail(ILARGI_ERR_NULL, "workspace is NULL");
   if (reinterpret_cast<uintptr_t>(workspace) % kAlign != 0) return fail(ILARGI_ERR_WORKSPACE, "workspace is not %zu-byte aligned", kAlign);
-  if (workspace_bytes < lay.total) return fail(ILARGI_ERR_WORKSPACE, "workspace has %zu bytes, plan needs %zu", workspace_bytes, lay.total);
+  if (workspace_bytes < lay.total)
+    return static_dev >= 0
+               ? fail(ILARGI_ERR_WORKSPACE, "plan needs %zu bytes of workspace, the static scratch array holds %zu: "
+                      "use ilargi_plan_create with a workspace of the caller", lay.total, workspace_bytes)
+               : fail(ILARGI_ERR_WORKSPACE, "workspace has %zu bytes, plan needs %zu", workspace_bytes, lay.total);
 
   ilargi_plan* pl = new (std::nothrow) ilargi_plan();
   if (pl == nullptr) return fail(ILARGI_ERR_DEVICE, "out of host memory");
@@ -999,13 +1027,56 @@ ilargi_status_t ilargi_plan_create(int n, const ilargi_source_t* sources, int64_
   if (!pairs.empty())
     HIP_TRY(hipMemcpyAsync(pl->at<GramAsmPair>(lay.o_pairs), pairs.data(), sizeof(GramAsmPair) * pairs.size(), hipMemcpyHostToDevice, st));
   HIP_TRY(hipStreamSynchronize(st));
+  pl->static_dev = static_dev;
   guard.p = nullptr;
   *plan = pl;
   return ILARGI_OK;
 }
 
+}  // namespace
+
+extern "C" {
+
+ilargi_status_t ilargi_plan_create(int n, const ilargi_source_t* sources, int64_t r_T, int64_t c_T,
+                                   int64_t max_cx, void* workspace, size_t workspace_bytes, void* stream,
+                                   ilargi_plan_t** plan) {
+  return plan_create_impl(n, sources, r_T, c_T, max_cx, workspace, workspace_bytes, stream, plan, -1);
+}
+
+ilargi_status_t ilargi_plan_create_static(int n, const ilargi_source_t* sources, int64_t r_T, int64_t c_T,
+                                          int64_t max_cx, void* stream, ilargi_plan_t** plan) {
+  if (plan == nullptr) return fail(ILARGI_ERR_NULL, "plan is NULL");
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(ILARGI_ERR_DEVICE, "device %d outside [0, %d)", dev, kMaxDevices);
+  std::lock_guard<std::mutex> lock(g_static_mutex);
+  StaticSlot& slot = g_static[dev];
+  if (slot.ptr == nullptr) {
+    // once per device, with that device current: every GPU holds its own copy of the array at its own address
+    void* p = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (p == nullptr || reinterpret_cast<uintptr_t>(p) % kAlign != 0)
+      return fail(ILARGI_ERR_DEVICE, "the static scratch array has no usable device address");
+    slot.ptr = p;
+  }
+  if (slot.owner != nullptr)
+    return fail(ILARGI_ERR_WORKSPACE, "the static scratch array of device %d is held by a live plan: destroy it first", dev);
+  ilargi_plan_t* pl = nullptr;
+  ilargi_status_t rc = plan_create_impl(n, sources, r_T, c_T, max_cx, slot.ptr, kStaticScratchBytes, stream, &pl, dev);
+  if (rc != ILARGI_OK) return rc;
+  slot.owner = pl;
+  *plan = pl;
+  return ILARGI_OK;
+}
+
+size_t ilargi_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
 ilargi_status_t ilargi_plan_destroy(ilargi_plan_t* plan) {
   if (plan == nullptr) return fail(ILARGI_ERR_NULL, "plan is NULL");
+  if (plan->static_dev >= 0) {
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    if (g_static[plan->static_dev].owner == plan) g_static[plan->static_dev].owner = nullptr;
+  }
   delete plan;
   return ILARGI_OK;
 }
