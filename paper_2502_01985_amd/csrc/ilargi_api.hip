@@ -60,6 +60,8 @@ struct SourcePlan {
          o_long_seg = 0, o_long_first = 0, o_chunk_partial = 0, o_pz = 0, o_partial = 0, o_g = 0, o_cnt = 0;
   int64_t nch_max = 0, nl_max = 0;
   int n_chunks = 0, n_long = 0;
+  size_t o_join_first = 0;        // join-order column reduce: first source row of every workgroup
+  int n_join_blocks = 0;
   int64_t nnz = 0;
   int logG = 0;
 };
@@ -147,13 +149,17 @@ struct TraceScope {
   }
 };
 
-int64_t colred_rows_per_block(int64_t rows) {
-  int64_t rpb = (rows + kColredBlocks - 1) / kColredBlocks;
-  rpb = (rpb + 63) / 64 * 64;
-  return rpb < 64 ? 64 : rpb;
+// Rows per workgroup of the narrow column reduce: about kColredTarget chunks, each a whole number of workgroup
+// iterations (so that no iteration runs half empty), never more than kColredBlocks chunks.
+int64_t colred_rows_per_block(int64_t rows, int64_t cols, int vec) {
+  const int64_t step = colred_step_rows((int)std::max<int64_t>(cols, 1), vec);
+  int64_t rpb = (rows + kColredTarget - 1) / kColredTarget;
+  rpb = (rpb + step - 1) / step * step;
+  const int64_t floor_rpb = (rows + kColredBlocks - 1) / kColredBlocks;
+  return std::max<int64_t>(std::max(rpb, floor_rpb), 1);
 }
-int colred_nblocks(int64_t rows) {
-  int64_t rpb = colred_rows_per_block(rows);
+int colred_nblocks(int64_t rows, int64_t cols, int vec) {
+  int64_t rpb = colred_rows_per_block(rows, cols, vec);
   return (int)((rows + rpb - 1) / rpb);
 }
 
@@ -219,6 +225,7 @@ ilargi_status_t make_layout(int n, const ilargi_source_t* s, int64_t r_T, int64_
       p.o_long_seg = take(sizeof(int32_t) * p.nl_max);
       p.o_long_first = take(sizeof(int32_t) * (p.nl_max + 1));
       p.o_chunk_partial = take(sizeof(float) * p.nch_max * wmax);
+      p.o_join_first = take(sizeof(int32_t) * (kColredBlocks + 1));
     }
     p.o_pz = take(sizeof(float) * std::max<int64_t>(p.rows, 1) * max_cx);
     // (a sparse source's transposed product leaves a single block of partials)
@@ -322,6 +329,7 @@ SegArgs seg_args(const ilargi_plan* pl, int k) {
   a.g_rows = -1;
   a.chunk_partial = pl->at<float>(p.o_chunk_partial);
   a.logG = p.logG;
+  a.block_first = p.n_join_blocks > 0 ? pl->at<int32_t>(p.o_join_first) : nullptr;
   return a;
 }
 
@@ -436,7 +444,7 @@ ilargi_status_t tmm_pass(ilargi_plan* pl, const float* Y, int ldy, int col0, int
     c.D = p.D; c.rows = p.rows; c.ck = (int)p.cols; c.vec = p.vec;
     c.Z = Z; c.ldz = ldz; c.col0 = zcol0; c.ncols = ncols;
     c.partial = pl->at<float>(p.o_partial);
-    c.rows_per_block = colred_rows_per_block(p.rows);
+    c.rows_per_block = colred_rows_per_block(p.rows, p.cols, p.vec);
     return c;
   };
   auto segsum_args = [&](int k) {
@@ -446,20 +454,24 @@ ilargi_status_t tmm_pass(ilargi_plan* pl, const float* Y, int ldy, int col0, int
     s.Z = pl->at<float>(p.o_pz); s.ldz = ldy; s.zcol0 = col0;
     return s;
   };
-  // the column reduce of a dense source that takes Y directly and the segment sums of another source are
-  // independent: the first such pair shares one launch
-  int kc = -1, ks = -1;
-  if (Y != nullptr) {
-    for (int k = 0; k < pl->n; ++k) {
-      const SourcePlan& p = pl->src[k];
-      if (p.empty || k == done_k) continue;
-      if (p.ident && !p.sparse && kc < 0) kc = k;
-      if (!p.ident && ks < 0) ks = k;
+  // Every dense source with float4 rows of at most 256 columns takes part in a merged launch: an identity source
+  // (and every source of colSum, whose operand is the fan-out vector) as a plain column reduce, a joined source in
+  // join-order form (segment sums in LDS, Z_k never written).  The other sources go through segment sum and
+  // column reduce as separate launches.
+  TmmParts parts;
+  memset(&parts, 0, sizeof(parts));
+  int parts_first_k = -1, parts_joins = 0;
+  auto flush_parts = [&]() -> ilargi_status_t {
+    if (parts.n == 0) return ILARGI_OK;
+    const char* tag = parts.n > 1 ? (parts_joins > 0 ? "colred+join" : "colred") : (parts_joins > 0 ? "tmm_join" : "colred");
+    {
+      TraceScope ts(pl, tag, parts_first_k, st);
+      HIP_TRY(launch_tmm_parts(parts, st));
     }
-    if (kc >= 0 && ks >= 0 && !colred_segsum_supported(colred_args(kc, Y, ldy, col0), segsum_args(ks))) kc = ks = -1;
-    if (kc < 0 || ks < 0) kc = ks = -1;
-  }
-  bool pair_done = false;
+    memset(&parts, 0, sizeof(parts));
+    parts_first_k = -1; parts_joins = 0;
+    return ILARGI_OK;
+  };
   for (int k = 0; k < pl->n; ++k) {
     SourcePlan& p = pl->src[k];
     if (p.empty) continue;
@@ -472,39 +484,64 @@ ilargi_status_t tmm_pass(ilargi_plan* pl, const float* Y, int ldy, int col0, int
       ++f.n;
       continue;
     }
-    if ((k == kc || k == ks) && !pair_done) {
-      TraceScope ts(pl, "colred+segsum", kc, st);
-      HIP_TRY(launch_colred_segsum(colred_args(kc, Y, ldy, col0), colred_nblocks(pl->src[kc].rows), segsum_args(ks), st));
-      pair_done = true;
-    }
+    int nb = colred_nblocks(p.rows, p.cols, p.vec);
     ColredArgs c;
-    if (Y == nullptr) {
-      // colSum: I_k^T 1 is the fan-out vector kept with the plan
-      c = colred_args(k, pl->at<float>(p.o_cnt), 1, 0);
-    } else if (p.ident) {
-      c = colred_args(k, Y, ldy, col0);
-    } else {
-      if (k != ks) {
-        TraceScope ts(pl, "segsum", k, st);
-        HIP_TRY(launch_segsum(segsum_args(k), st));
+    bool merged = false;
+    if (!p.sparse) {
+      const bool direct = Y == nullptr || p.ident;
+      c = direct ? (Y == nullptr ? colred_args(k, pl->at<float>(p.o_cnt), 1, 0) : colred_args(k, Y, ldy, col0))
+                 : colred_args(k, nullptr, 0, 0);
+      SegArgs sg;
+      memset(&sg, 0, sizeof(sg));
+      if (!direct) sg = segsum_args(k);
+      if (tmm_part_supported(c, direct ? nullptr : &sg)) {
+        if (parts.n == kTmmParts) {
+          ilargi_status_t rc = flush_parts();
+          if (rc != ILARGI_OK) return rc;
+        }
+        const int q = parts.n++;
+        if (q == 0) { parts.first[0] = 0; parts_first_k = k; }
+        parts.join[q] = direct ? 0 : 1;
+        parts_joins += direct ? 0 : 1;
+        if (!direct) nb = p.n_join_blocks;
+        parts.c[q] = c;
+        parts.s[q] = sg;
+        parts.first[q + 1] = parts.first[q] + nb;
+        merged = true;
       }
-      c = colred_args(k, pl->at<float>(p.o_pz), ldy, col0);
     }
-    int nb = colred_nblocks(p.rows);
-    if (p.sparse) {
-      // D_k^T Z_k over the column-sorted view; the result takes the place of a single block of partials
-      TraceScope ts(pl, "colred", k, st);
-      HIP_TRY(launch_spmm_t(sparse_args(pl, k), c.Z, c.ldz, c.col0, ncols, pl->at<float>(p.o_tpartial), c.partial, st));
-      nb = 1;
-    } else if (k != kc) {
-      TraceScope ts(pl, "colred", k, st);
-      HIP_TRY(launch_colred(c, nb, st));
+    if (!merged) {
+      if (Y == nullptr) {
+        // colSum: I_k^T 1 is the fan-out vector kept with the plan
+        c = colred_args(k, pl->at<float>(p.o_cnt), 1, 0);
+      } else if (p.ident) {
+        c = colred_args(k, Y, ldy, col0);
+      } else {
+        {
+          TraceScope ts(pl, "segsum", k, st);
+          HIP_TRY(launch_segsum(segsum_args(k), st));
+        }
+        c = colred_args(k, pl->at<float>(p.o_pz), ldy, col0);
+      }
+      if (p.sparse) {
+        // D_k^T Z_k over the column-sorted view; the result takes the place of a single block of partials
+        TraceScope ts(pl, "colred", k, st);
+        HIP_TRY(launch_spmm_t(sparse_args(pl, k), c.Z, c.ldz, c.col0, ncols, pl->at<float>(p.o_tpartial), c.partial, st));
+        nb = 1;
+      } else {
+        TraceScope ts(pl, "colred", k, st);
+        HIP_TRY(launch_colred(c, nb, st));
+      }
     }
     f.s[f.n].tcol2src = pl->at<int32_t>(p.o_tcol);
     f.s[f.n].partial = c.partial;
     f.s[f.n].nblocks = nb;
     f.s[f.n].ck = (int)p.cols;
     ++f.n;
+  }
+  {
+    ilargi_status_t rc = flush_parts();
+    if (rc != ILARGI_OK) return rc;
   }
   f.out = out; f.ldo = ldo; f.col0 = col0; f.ncols = ncols;
   f.lr = lr;
@@ -848,6 +885,28 @@ ilargi_status_t plan_create_impl(int n, const ilargi_source_t* sources, int64_t 
     }
     int64_t avg = p.rows > 0 ? (p.nnz + p.rows - 1) / p.rows : 1;
     p.logG = std::min(6, ilog2_ceil(std::max<int64_t>(avg, 1)));
+    if (p.n_long == 0 && p.rows > 0 && !p.sparse && p.nnz <= 32 * p.rows) {
+      // (with more index entries per row the gathers dominate and the segment-sum kernel, which spreads a
+      // segment over a group of lanes, serves them better)
+      // row ranges of the join-order column reduce, balanced by what a row costs: its table bytes plus a gathered
+      // operand row per index entry (priced at 32 bytes); about kColredTarget ranges, none below 64 KiB of cost
+      std::vector<int32_t> first;
+      const int64_t row_bytes = std::max<int64_t>(p.cols, 1) * 4, entry_bytes = 32;
+      const int64_t total = p.rows * row_bytes + p.nnz * entry_bytes;
+      const int64_t target = std::max<int64_t>((total + kColredTarget - 1) / kColredTarget, 64 << 10);
+      int64_t acc = 0;
+      first.push_back(0);
+      for (int64_t r = 0; r < p.rows; ++r) {
+        acc += row_bytes + (int64_t)(rowptr[(size_t)r + 1] - rowptr[(size_t)r]) * entry_bytes;
+        if (acc >= target && r + 1 < p.rows) { first.push_back((int32_t)(r + 1)); acc = 0; }
+      }
+      first.push_back((int32_t)p.rows);
+      if ((int)first.size() - 1 <= kColredBlocks) {
+        p.n_join_blocks = (int)first.size() - 1;
+        HIP_TRY(hipMemcpyAsync(pl->at<int32_t>(p.o_join_first), first.data(), sizeof(int32_t) * first.size(), hipMemcpyHostToDevice, st));
+        HIP_TRY(hipStreamSynchronize(st));
+      }
+    }
   }
   // column-sorted view of every sparse source: the same stable sort, keyed by column index
   for (int k = 0; k < n; ++k) {
@@ -1082,7 +1141,7 @@ ilargi_status_t ilargi_plan_destroy(ilargi_plan_t* plan) {
 }
 
 ilargi_status_t ilargi_stream_probe(int kind, float* dst, const float* src, int64_t n_floats, int blocks, void* stream) {
-  if (kind < 0 || kind > 4) return fail(ILARGI_ERR_UNSUPPORTED, "stream_probe: kind %d", kind);
+  if (kind < 0 || kind > 6) return fail(ILARGI_ERR_UNSUPPORTED, "stream_probe: kind %d", kind);
   if (dst == nullptr || (kind != 2 && kind != 4 && src == nullptr)) return fail(ILARGI_ERR_NULL, "stream_probe: NULL buffer");
   if (n_floats < 0 || n_floats % 4 != 0 || blocks < 1 || blocks > (1 << 22)) return fail(ILARGI_ERR_SHAPE, "stream_probe: bad size");
   HIP_TRY(launch_probe(kind, dst, src, n_floats, blocks, static_cast<hipStream_t>(stream)));

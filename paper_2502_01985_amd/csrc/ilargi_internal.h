@@ -13,7 +13,8 @@ constexpr int kMaxSources = 16;      // sources per plan (kernel argument arrays
 constexpr int kWave = 64;            // gfx950 wavefront
 constexpr int kBlock = 256;          // threads per workgroup in the streaming kernels
 constexpr int kNarrowCT = 4;         // operand columns one narrow (VALU) pass handles
-constexpr int kColredBlocks = 1024;  // row chunks (= partial results) of the D^T Z reduction
+constexpr int kColredBlocks = 1024;  // most row chunks (= partial results) of the D^T Z reduction
+constexpr int kColredTarget = 512;   // row chunks aimed at: two workgroups per compute unit, eight loads in flight per lane
 constexpr int kSparseBlockRows = 1024;   // rows a row block of the sparse row-wise product holds at most
 constexpr int kSparseChunk = 4096;   // entries of a column one workgroup sums
 constexpr int kLongSeg = 2048;       // inverse-index segments longer than this are split ...
@@ -137,6 +138,7 @@ struct SegArgs {
   int ldz, zcol0;
   float* chunk_partial;    // n_chunks x ncols
   int logG;                // lanes per segment in the narrow kernel
+  const int32_t* block_first;  // join-order column reduce: workgroup b owns source rows [block_first[b], block_first[b + 1])
 };
 
 struct ColredArgs {
@@ -148,6 +150,16 @@ struct ColredArgs {
   float* partial;          // [nblocks][ck][kNarrowCT]
   int64_t rows_per_block;
   int vec;
+};
+
+// Shares of a narrow transposed multiply that run in one launch (kernels_tmm.hip).
+constexpr int kTmmParts = 4;
+struct TmmParts {
+  int n;
+  int first[kTmmParts + 1];   // workgroups [first[q], first[q + 1]) serve part q
+  int join[kTmmParts];        // 1: join-order form (segment sums in LDS), 0: operand rows read from c.Z
+  ColredArgs c[kTmmParts];
+  SegArgs s[kTmmParts];       // inverse index and operand of the join-order form
 };
 
 struct FinSource {
@@ -252,9 +264,10 @@ hipError_t launch_segsum(const SegArgs& a, hipStream_t st);
 hipError_t launch_colred(const ColredArgs& a, int nblocks, hipStream_t st);
 bool lmm_flat_supported(const LmmArgs& a, int vec, bool fuseg);
 hipError_t launch_lmm_flat(const LmmArgs& a, int mode, bool fuseg, hipStream_t st, int* grid_out);
-bool colred_segsum_supported(const ColredArgs& c, const SegArgs& s);
-hipError_t launch_colred_segsum(const ColredArgs& c, int nb_c, const SegArgs& s, hipStream_t st);
 hipError_t launch_finalize(const FinArgs& a, int c_T, int mode, hipStream_t st);
+int colred_step_rows(int ck, int vec);
+bool tmm_part_supported(const ColredArgs& c, const SegArgs* s);
+hipError_t launch_tmm_parts(const TmmParts& t, hipStream_t st);
 hipError_t launch_materialize(const MatArgs& a, hipStream_t st);
 hipError_t launch_gram_assemble(const GramAsmPair* pairs_dev, int npairs, const int32_t* const* tcol2src_dev,
                                 int c_T, float* out, hipStream_t st);

@@ -96,18 +96,26 @@ __global__ __launch_bounds__(kBlock) void lmm_flat_kernel(LmmArgs a, int wave_fl
     const int64_t i = chunk * kWave + lane;
     jn[s] = (s < a.g.n && chunk < nchunks && i < a.r_out) ? flat_gather_row(a.g, s, i) : -1;
   }
+  // the chunk of the table, flat; the next chunk is requested before the current one is used, so that a
+  // wavefront always has a chunk in flight
+  float4 v[NVT], vn[NVT];
+  auto load_chunk = [&](int64_t ch, float4 (&dst)[NVT]) {
+    const int64_t r0 = ch * kWave;
+    const float4* b4 = reinterpret_cast<const float4*>(a.D + r0 * a.ck);
+#pragma unroll
+    for (int u = 0; u < NVT; ++u) {
+      dst[u] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+      if (u < nvec && ch < nchunks && r0 + row_u[u] < a.d_rows) dst[u] = b4[u * kWave + lane];
+    }
+  };
+  load_chunk(chunk, vn);
   for (; chunk < nchunks; chunk += cstride) {
     const int64_t row0 = chunk * kWave;
     const int64_t i = row0 + lane;
     const bool rowlive = i < a.r_out;
-    // the chunk of the table, flat
-    float4 v[NVT];
-    const float4* b4 = reinterpret_cast<const float4*>(a.D + row0 * a.ck);
 #pragma unroll
-    for (int u = 0; u < NVT; ++u) {
-      v[u] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-      if (u < nvec && row0 + row_u[u] < a.d_rows) v[u] = b4[u * kWave + lane];
-    }
+    for (int u = 0; u < NVT; ++u) v[u] = vn[u];
+    load_chunk(chunk + cstride, vn);
     // row mapping: gathered product rows of this chunk (indices were prefetched), labels, next chunk's indices
     float gsum[CT];
 #pragma unroll

@@ -225,6 +225,41 @@ __global__ __launch_bounds__(kBlock) void probe_read_kernel(const float4* __rest
   if (threadIdx.x == 0) sink[blockIdx.x] = acc;
 }
 
+// read-only, every workgroup walking a contiguous chunk of its own (kind 5), and with eight loads in flight per
+// thread in a grid-stride walk (kind 6)
+__global__ __launch_bounds__(kBlock) void probe_read_chunked_kernel(const float4* __restrict__ src, int64_t n4,
+                                                                    float* __restrict__ sink) {
+  const int64_t per = (n4 + gridDim.x - 1) / gridDim.x;
+  const int64_t b0 = (int64_t)blockIdx.x * per, b1 = min(b0 + per, n4);
+  float acc = 0.0f;
+  for (int64_t i = b0 + threadIdx.x; i < b1; i += blockDim.x) {
+    float4 v = src[i];
+    acc += (v.x + v.y) + (v.z + v.w);
+  }
+  for (int m = kWave / 2; m >= 1; m >>= 1) acc += __shfl_xor(acc, m);
+  if (threadIdx.x == 0) sink[blockIdx.x] = acc;
+}
+
+__global__ __launch_bounds__(kBlock) void probe_read_deep_kernel(const float4* __restrict__ src, int64_t n4,
+                                                                 float* __restrict__ sink) {
+  float acc = 0.0f;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  for (; i + 7 * stride < n4; i += 8 * stride) {
+    float4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = src[i + u * stride];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc += (v[u].x + v[u].y) + (v[u].z + v[u].w);
+  }
+  for (; i < n4; i += stride) {
+    float4 v = src[i];
+    acc += (v.x + v.y) + (v.z + v.w);
+  }
+  for (int m = kWave / 2; m >= 1; m >>= 1) acc += __shfl_xor(acc, m);
+  if (threadIdx.x == 0) sink[blockIdx.x] = acc;
+}
+
 __global__ __launch_bounds__(kBlock) void probe_write_kernel(float4* __restrict__ dst, int64_t n4) {
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += (int64_t)gridDim.x * blockDim.x)
     dst[i] = make_float4(1.0f, 2.0f, 3.0f, 4.0f);
@@ -247,6 +282,8 @@ hipError_t launch_probe(int kind, float* dst, const float* src, int64_t n_floats
   if (n4 <= 0) return hipSuccess;
   if (kind == 3) { probe_copy_nt_kernel<<<blocks, kBlock, 0, st>>>((nt4*)dst, (const nt4*)src, n4); return hipGetLastError(); }
   if (kind == 4) { probe_write_nt_kernel<<<blocks, kBlock, 0, st>>>((nt4*)dst, n4); return hipGetLastError(); }
+  if (kind == 5) { probe_read_chunked_kernel<<<blocks, kBlock, 0, st>>>((const float4*)src, n4, dst); return hipGetLastError(); }
+  if (kind == 6) { probe_read_deep_kernel<<<blocks, kBlock, 0, st>>>((const float4*)src, n4, dst); return hipGetLastError(); }
   if (kind == 0) probe_copy_kernel<<<blocks, kBlock, 0, st>>>((float4*)dst, (const float4*)src, n4);
   else if (kind == 1) probe_read_kernel<<<blocks, kBlock, 0, st>>>((const float4*)src, n4, dst);
   else probe_write_kernel<<<blocks, kBlock, 0, st>>>((float4*)dst, n4);

@@ -3,6 +3,8 @@
 //   column reduce G_k = D_k^T Z_k      per-workgroup partial sums over contiguous row chunks;
 //   finalize      out[col_map_k[j], :] += G_k[j, :]   partials added in a fixed order, sources in order.
 // The finalize step also performs the weight update of Alg. 1 when called from the gradient-descent step.
+#include <algorithm>
+
 #include "ilargi_internal.h"
 
 namespace ilargi {
@@ -150,62 +152,69 @@ template <int VEC> __device__ __forceinline__ void load_vec(const float* p, floa
   }
 }
 
-constexpr int kUnroll = 4;
+constexpr int kUnroll = 8;   // rows (float4 loads) a lane has in flight
 
-// Partial of D^T Z over the rows of one workgroup.  blockIdx.y selects a slab of 64*VEC columns of D;
-// inside a slab lane -> (row offset, column group), so a wavefront reads whole contiguous rows.
-template <int VEC, int CT>
-__device__ __forceinline__ void colred_body(const ColredArgs& a, int bx, int by) {
-  __shared__ float red[VEC * CT][kBlock];
+// Partial of D^T Z over the rows [b0, b1) of one workgroup, added to the per-thread sums g.  `by` selects a slab
+// of 64*VEC columns of D; inside a slab lane -> (row offset, column group), so a wavefront reads whole contiguous
+// rows.  ZLDS: the operand rows come from an LDS tile (row r at zl[(r - zl_row0) * CT]) instead of a.Z.
+template <int VEC, int CT, bool ZLDS>
+__device__ __forceinline__ void colred_rows(const ColredArgs& a, int by, int64_t b0, int64_t b1, const float* zl,
+                                            int64_t zl_row0, float (&g)[VEC][CT]) {
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
   const int slab0 = by * kWave * VEC;                               // first column of the slab
   const int wck = min(a.ck - slab0, kWave * VEC);                   // its width
   const int nvec = wck / VEC;                                       // column groups (<= 64)
   const int rp = kWave / nvec;                                      // rows per wavefront step
   const int rsub = lane / nvec, cg = lane - rsub * nvec;
-  const bool active = rsub < rp;
-  const int64_t b0 = (int64_t)bx * a.rows_per_block;
-  const int64_t b1 = min(b0 + a.rows_per_block, a.rows);
+  if (rsub >= rp) return;
   const int64_t step = (int64_t)rp * kUnroll;                       // rows per wavefront iteration
-
-  float g[VEC][CT];
+  for (int64_t r0 = b0 + (int64_t)wave * step; r0 < b1; r0 += (int64_t)(kBlock / kWave) * step) {
+    float v[kUnroll][VEC], z[kUnroll][CT];
 #pragma unroll
-  for (int e = 0; e < VEC; ++e)
+    for (int u = 0; u < kUnroll; ++u) {
+      int64_t r = r0 + (int64_t)u * rp + rsub;
 #pragma unroll
-    for (int n = 0; n < CT; ++n) g[e][n] = 0.0f;
-
-  if (active) {
-    for (int64_t r0 = b0 + (int64_t)wave * step; r0 < b1; r0 += (int64_t)(kBlock / kWave) * step) {
-      float v[kUnroll][VEC], z[kUnroll][CT];
+      for (int e = 0; e < VEC; ++e) v[u][e] = 0.0f;
 #pragma unroll
-      for (int u = 0; u < kUnroll; ++u) {
-        int64_t r = r0 + (int64_t)u * rp + rsub;
+      for (int n = 0; n < CT; ++n) z[u][n] = 0.0f;
+      if (r < b1) {
+        load_vec<VEC>(a.D + r * a.ck + slab0 + cg * VEC, v[u]);
+        if constexpr (ZLDS) {
+          const float* zp = zl + (r - zl_row0) * CT;
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) v[u][e] = 0.0f;
-#pragma unroll
-        for (int n = 0; n < CT; ++n) z[u][n] = 0.0f;
-        if (r < b1) {
-          load_vec<VEC>(a.D + r * a.ck + slab0 + cg * VEC, v[u]);
+          for (int n = 0; n < CT; ++n) z[u][n] = zp[n];
+        } else {
           const float* zp = a.Z + r * a.ldz + a.col0;
 #pragma unroll
           for (int n = 0; n < CT; ++n)
             if (n < a.ncols) z[u][n] = zp[n];
         }
       }
-#pragma unroll
-      for (int u = 0; u < kUnroll; ++u)
-#pragma unroll
-        for (int e = 0; e < VEC; ++e)
-#pragma unroll
-          for (int n = 0; n < CT; ++n) g[e][n] = fmaf(v[u][e], z[u][n], g[e][n]);
     }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u)
+#pragma unroll
+      for (int e = 0; e < VEC; ++e)
+#pragma unroll
+        for (int n = 0; n < CT; ++n) g[e][n] = fmaf(v[u][e], z[u][n], g[e][n]);
   }
+}
+
+// The workgroup's per-thread sums added in a fixed order (wavefronts, then row offsets) and stored as its partial.
+template <int VEC, int CT>
+__device__ __forceinline__ void colred_store(const ColredArgs& a, int bx, int by, const float (&g)[VEC][CT],
+                                             float (*red)[kBlock]) {
+  const int tid = threadIdx.x;
+  const int slab0 = by * kWave * VEC;
+  const int wck = min(a.ck - slab0, kWave * VEC);
+  const int nvec = wck / VEC;
+  const int rp = kWave / nvec;
 #pragma unroll
   for (int e = 0; e < VEC; ++e)
 #pragma unroll
     for (int n = 0; n < CT; ++n) red[e * CT + n][tid] = g[e][n];
   __syncthreads();
-  // column j of the slab, operand column n: add the wavefronts and row offsets in a fixed order
+  // column j of the slab, operand column n
   for (int o = tid; o < wck * CT; o += kBlock) {
     int j = o / CT, n = o - j * CT;
     int jcg = j / VEC, e = j - jcg * VEC;
@@ -217,18 +226,105 @@ __device__ __forceinline__ void colred_body(const ColredArgs& a, int bx, int by)
 }
 
 template <int VEC, int CT>
+__device__ __forceinline__ void colred_body(const ColredArgs& a, int bx, int by) {
+  __shared__ float red[VEC * CT][kBlock];
+  const int64_t b0 = (int64_t)bx * a.rows_per_block;
+  const int64_t b1 = min(b0 + a.rows_per_block, a.rows);
+  float g[VEC][CT];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e)
+#pragma unroll
+    for (int n = 0; n < CT; ++n) g[e][n] = 0.0f;
+  colred_rows<VEC, CT, false>(a, by, b0, b1, nullptr, 0, g);
+  colred_store<VEC, CT>(a, bx, by, g, red);
+}
+
+constexpr int kJoinRows = kBlock;    // rows of a joined table whose segment sums a workgroup forms at a time (one per thread)
+constexpr int kJoinTileFloats = 2048;  // LDS floats for the gathered operand rows of one tile of index entries
+
+// Join-order form for a joined source: the segment sums Z = I_k^T Y of up to kJoinRows rows are formed in LDS and
+// multiplied right away; Z is never written to memory and the table is the only stream.  The operand rows of a
+// tile of consecutive index entries are gathered with all their loads in flight (entry -> target row -> operand
+// row: two dependent round trips per tile, whatever the number of rows), then the thread of each table row adds
+// its entries in index order.  Needs a table without long segments (s.n_long == 0) and a single column slab.
+template <int VEC, int CT>
+__device__ __forceinline__ void colred_join_body(const ColredArgs& a, const SegArgs& s, int bx) {
+  constexpr int kTile = kJoinTileFloats / CT;          // index entries per tile
+  constexpr int kPer = kTile / kBlock;                 // ... per thread
+  __shared__ float red[VEC * CT][kBlock];
+  __shared__ float zs[kJoinRows * CT];
+  __shared__ float ys[kTile * CT];
+  __shared__ int rps[kJoinRows + 1];
+  const int tid = threadIdx.x;
+  const int64_t b0 = s.block_first[bx], b1 = s.block_first[bx + 1];   // balanced by table bytes + index entries
+  float g[VEC][CT];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e)
+#pragma unroll
+    for (int n = 0; n < CT; ++n) g[e][n] = 0.0f;
+  for (int64_t s0 = b0; s0 < b1; s0 += kJoinRows) {
+    const int64_t s1 = min(s0 + kJoinRows, b1);
+    const int nrows = (int)(s1 - s0);
+    for (int j = tid; j <= nrows; j += kBlock) rps[j] = s.rowptr[s0 + j];
+    __syncthreads();
+    const int pb = rps[0], pe = rps[nrows];
+    const int my_beg = tid < nrows ? rps[tid] : 0, my_end = tid < nrows ? rps[tid + 1] : 0;
+    float acc[CT];
+#pragma unroll
+    for (int n = 0; n < CT; ++n) acc[n] = 0.0f;
+    for (int t0 = pb; t0 < pe; t0 += kTile) {
+      const int t1 = min(t0 + kTile, pe);
+      int64_t rr[kPer];
+#pragma unroll
+      for (int u = 0; u < kPer; ++u) {
+        const int p = t0 + tid + u * kBlock;
+        rr[u] = p < t1 ? seg_row(s, p) : -1;
+      }
+      float yv[kPer][CT];
+#pragma unroll
+      for (int u = 0; u < kPer; ++u)
+#pragma unroll
+        for (int n = 0; n < CT; ++n)
+          yv[u][n] = (rr[u] >= 0 && n < s.ncols) ? s.Y[rr[u] * s.ldy + s.col0 + n] : 0.0f;
+#pragma unroll
+      for (int u = 0; u < kPer; ++u)
+#pragma unroll
+        for (int n = 0; n < CT; ++n) ys[(tid + u * kBlock) * CT + n] = yv[u][n];
+      __syncthreads();
+      const int lo = max(my_beg, t0), hi = min(my_end, t1);
+      for (int p = lo; p < hi; ++p) {
+#pragma unroll
+        for (int n = 0; n < CT; ++n) acc[n] += ys[(p - t0) * CT + n];
+      }
+      __syncthreads();
+    }
+    if (tid < nrows) {
+#pragma unroll
+      for (int n = 0; n < CT; ++n) zs[tid * CT + n] = acc[n];
+    }
+    __syncthreads();
+    colred_rows<VEC, CT, true>(a, 0, s0, s1, zs, s0, g);
+    __syncthreads();                                              // zs and rps are rewritten by the next round
+  }
+  colred_store<VEC, CT>(a, bx, 0, g, red);
+}
+
+template <int VEC, int CT>
 __global__ __launch_bounds__(kBlock) void colred_kernel(ColredArgs a) {
   colred_body<VEC, CT>(a, blockIdx.x, blockIdx.y);
 }
 
-// Two independent steps of a transposed multiply in one launch: the column reduce of a source that takes Y
-// directly (workgroups [0, nb_c)) and the segment sums of another source (the workgroups after them).  The
-// segment sums are bound by the latency of their gathers and use little bandwidth; next to the streaming column
-// reduce they cost almost nothing, while a launch of their own costs its full latency chain.
-template <int VEC, int CT>
-__global__ __launch_bounds__(kBlock) void colred_segsum_kernel(ColredArgs c, int nb_c, SegArgs s) {
-  if ((int)blockIdx.x < nb_c) colred_body<VEC, CT>(c, blockIdx.x, 0);
-  else segsum_narrow_body<CT>(s, blockIdx.x - nb_c, gridDim.x - nb_c);
+// Every share of a narrow transposed multiply in one launch: up to kTmmParts sources, each either a column
+// reduce that takes its operand rows from memory (an identity source: Z = Y) or the join-order form above.  The
+// shares are independent; consecutive workgroup ranges serve consecutive parts.
+template <int CT>
+__global__ __launch_bounds__(kBlock) void tmm_parts_kernel(TmmParts t) {
+  int part = 0;
+#pragma unroll
+  for (int q = 1; q < kTmmParts; ++q) part += (q < t.n && (int)blockIdx.x >= t.first[q]) ? 1 : 0;
+  const int bx = (int)blockIdx.x - t.first[part];
+  if (t.join[part]) colred_join_body<4, CT>(t.c[part], t.s[part], bx);
+  else colred_body<4, CT>(t.c[part], bx, 0);
 }
 
 // Sum of float4 records rec[b * stride4] over b < count by a whole workgroup: threads stride the records
@@ -346,40 +442,35 @@ hipError_t launch_colred(const ColredArgs& a, int nblocks, hipStream_t st) {
   return hipGetLastError();
 }
 
-// The fused launch needs the column reduce to be a single slab and the same operand width on both sides.
-bool colred_segsum_supported(const ColredArgs& c, const SegArgs& s) {
-  return c.ck > 0 && c.ck <= kWave * c.vec && c.ncols == s.ncols && s.ncols >= 1 && s.ncols <= kNarrowCT &&
-         s.r_k + s.n_chunks > 0;
-}
-
-hipError_t launch_colred_segsum(const ColredArgs& c, int nb_c, const SegArgs& s, hipStream_t st) {
-  if (!colred_segsum_supported(c, s) || nb_c <= 0) return hipErrorInvalidValue;
-  const int64_t gpb = kBlock >> s.logG;
-  int64_t gs = (s.r_k + s.n_chunks + gpb - 1) / gpb;
-  if (gs > 65536) gs = 65536;
-  const unsigned grid = (unsigned)(nb_c + gs);
-  const int ct = c.ncols <= 1 ? 1 : (c.ncols <= 2 ? 2 : 4);
-#define ILARGI_CS(V, C) colred_segsum_kernel<V, C><<<grid, kBlock, 0, st>>>(c, nb_c, s)
-  if (c.vec == 4) { if (ct == 1) ILARGI_CS(4, 1); else if (ct == 2) ILARGI_CS(4, 2); else ILARGI_CS(4, 4); }
-  else if (c.vec == 2) { if (ct == 1) ILARGI_CS(2, 1); else if (ct == 2) ILARGI_CS(2, 2); else ILARGI_CS(2, 4); }
-  else { if (ct == 1) ILARGI_CS(1, 1); else if (ct == 2) ILARGI_CS(1, 2); else ILARGI_CS(1, 4); }
-#undef ILARGI_CS
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  if (s.n_long > 0) {
-    int64_t total = (int64_t)s.n_long * s.ncols;
-    int g = (int)((total + kBlock - 1) / kBlock);
-    if (g > 1024) g = 1024;
-    segsum_combine_kernel<<<g, kBlock, 0, st>>>(s);
-    e = hipGetLastError();
-  }
-  return e;
-}
-
 hipError_t launch_finalize(const FinArgs& a, int c_T, int mode, hipStream_t st) {
   if (c_T <= 0 || a.ncols <= 0) return hipSuccess;
   if (mode == 0) finalize_kernel<0><<<c_T, kBlock, 0, st>>>(a, c_T);
   else finalize_kernel<1><<<c_T + (a.loss != nullptr ? 1 : 0), kBlock, 0, st>>>(a, c_T);
+  return hipGetLastError();
+}
+
+// Rows one workgroup iteration of the column reduce covers for a table with ck columns read in groups of vec.
+int colred_step_rows(int ck, int vec) {
+  const int wck = std::min(ck, kWave * vec);
+  const int nvec = std::max(1, wck / vec);
+  return std::max(1, kWave / nvec) * kUnroll * (kBlock / kWave);
+}
+
+// A part of the merged launch: float4 rows, one column slab, and for the join-order form no long segments.
+bool tmm_part_supported(const ColredArgs& c, const SegArgs* s) {
+  if (c.vec != 4 || c.ck <= 0 || c.ck > kWave * 4 || c.ncols < 1 || c.ncols > kNarrowCT || c.rows <= 0) return false;
+  if (s != nullptr && (s->n_long != 0 || s->ncols != c.ncols || s->r_k != c.rows || s->block_first == nullptr)) return false;
+  return true;
+}
+
+hipError_t launch_tmm_parts(const TmmParts& t, hipStream_t st) {
+  if (t.n < 1 || t.n > kTmmParts) return hipErrorInvalidValue;
+  const int grid = t.first[t.n];
+  if (grid <= 0) return hipSuccess;
+  const int nc = t.c[0].ncols;
+  if (nc <= 1) tmm_parts_kernel<1><<<grid, kBlock, 0, st>>>(t);
+  else if (nc == 2) tmm_parts_kernel<2><<<grid, kBlock, 0, st>>>(t);
+  else tmm_parts_kernel<4><<<grid, kBlock, 0, st>>>(t);
   return hipGetLastError();
 }
 
