@@ -113,6 +113,8 @@ struct ilargi_plan {
   bool mat_flat = false;  // ... and every group is an aligned float4 of its source
   bool mat_cols = false;  // the per-column feeder tables (at most two feeders per column) are valid
   int npairs = 0;
+  bool small_gd = false;  // the schema is small enough for the single-workgroup gradient-descent iteration
+  int small_ident = -1, small_joined = -1;   // ... its entity table and its joined table (or -1)
   int static_dev = -1;   // >= 0: the workspace is the library's static scratch array of that device
   std::vector<size_t> block_off;  // offset (floats) of Gram block (k,l), k <= l, index k * n + l
   // optional timing of one kernel family: event pairs recorded around every launch whose tag matches
@@ -1014,6 +1016,36 @@ ilargi_status_t plan_create_impl(int n, const ilargi_source_t* sources, int64_t 
       if (f.rows == r_T && d.has_idx && !d.ident && d.nnz == r_T && d.n_long == 0) pl->star_k = dim;
     }
   }
+  // a small two-table star join (or a small single table): one gradient-descent iteration then runs as a
+  // single workgroup with the tables in registers, which replaces five dependent launches by one
+  {
+    int live = 0, ki = -1, kj = -1;
+    for (int k = 0; k < n; ++k) {
+      const SourcePlan& p = pl->src[k];
+      if (p.empty) continue;
+      ++live;
+      if (p.ident && ki < 0) ki = k; else kj = k;
+    }
+    bool ok = !pl->any_sparse && ki >= 0 && live <= 2 && c_T <= 1024 && r_T >= 1;
+    if (ok) {
+      const SourcePlan& f = pl->src[ki];
+      ok = f.rows == r_T && f.vec == 4 && f.cols <= 16 && r_T <= small_star_max_rows((int)f.cols / 4);
+    }
+    if (ok && live == 2) {
+      const SourcePlan& d = pl->src[kj];
+      ok = !d.ident && d.vec == 4 && d.cols <= 16 && d.rows <= 1024 && d.n_long == 0 && d.nnz <= 16384;
+    }
+    if (ok) {
+      SmallStarArgs probe;
+      memset(&probe, 0, sizeof(probe));
+      probe.r_T = (int)r_T; probe.nnz = live == 2 ? (int)pl->src[kj].nnz : 0;
+      probe.cs = (int)pl->src[ki].cols;
+      if (live == 2) { probe.R = pl->src[kj].D; probe.cr = (int)pl->src[kj].cols; }
+      ok = small_star_lds_bytes(probe) <= kSmallGdMaxLds;
+    }
+    pl->small_gd = ok;
+    pl->small_ident = ki; pl->small_joined = live == 2 ? kj : -1;
+  }
   // join-gather tables: groups of four target columns fed by four consecutive columns of one source
   if (c_T % 4 == 0) {
     std::vector<int32_t> gslot((size_t)c_T / 4, -1), gj0((size_t)c_T / 4, 0);
@@ -1273,6 +1305,35 @@ ilargi_status_t ilargi_gd_step(ilargi_plan_t* plan, ilargi_model_t model, float*
   float* E = plan->at<float>(plan->lay.o_E);
   const int w = pass_width(plan);
   const float loss_scale = (model == ILARGI_LINEAR ? 0.5f : 1.0f) / (float)plan->r_T;
+  if (plan->small_gd && !bf16 && m <= kNarrowCT) {
+    // small schema: the whole iteration of a model in one launch of one workgroup
+    SmallStarArgs a;
+    memset(&a, 0, sizeof(a));
+    const SourcePlan& f = plan->src[plan->small_ident];
+    a.S = f.D; a.cs = (int)f.cols; a.tcol_s = plan->at<int32_t>(f.o_tcol);
+    for (int j = 0; j < 16; ++j) {
+      a.colmap[0][j] = j < f.cols ? (int16_t)f.colmap_h[(size_t)j] : (int16_t)-1;
+      a.colmap[1][j] = -1;
+    }
+    a.s_first = 1;
+    if (plan->small_joined >= 0) {
+      const SourcePlan& d = plan->src[plan->small_joined];
+      a.R = d.D; a.cr = (int)d.cols; a.r_R = (int)d.rows; a.idx = d.idx;
+      a.rowptr = plan->at<int32_t>(d.o_rowptr); a.perm = plan->at<int32_t>(d.o_perm); a.nnz = (int)d.nnz;
+      a.tcol_r = plan->at<int32_t>(d.o_tcol);
+      for (int j = 0; j < d.cols; ++j) a.colmap[1][j] = (int16_t)d.colmap_h[(size_t)j];
+      a.s_first = plan->small_ident < plan->small_joined ? 1 : 0;
+    }
+    a.W = W; a.ldw = (int)m; a.y = y; a.lr = lr; a.loss = loss;
+    a.r_T = (int)plan->r_T; a.c_T = (int)plan->c_T;
+    a.inv_rT = 1.0f / (float)plan->r_T; a.loss_scale = loss_scale;
+    for (int col = 0; col < (int)m; ++col) {
+      a.col = col;
+      TraceScope ts(plan, "small_gd", -1, st);
+      HIP_TRY(launch_small_star(a, model == ILARGI_LINEAR ? 1 : 2, st));
+    }
+    return ILARGI_OK;
+  }
   if (plan->star_k >= 0 && gd_star_supported((int)plan->src[plan->fused].cols, (int)m) &&
       (int64_t)plan->src[plan->fused].cols * m <= plan->lay.gpartial_floats)
     return gd_star_step(plan, model == ILARGI_LINEAR ? 1 : 2, W, (int)m, y, lr, loss, loss_scale, bf16, st);

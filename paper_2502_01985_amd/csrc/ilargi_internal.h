@@ -234,6 +234,28 @@ struct GramAsmPair { const float* block; int k, l, cb; };
 // Records `msg` as the calling thread's last error (what ilargi_last_error returns) and returns `code`.
 ilargi_status_t set_error(ilargi_status_t code, const char* msg);
 
+// One gradient-descent iteration on a small two-table star join in a single workgroup (kernels_small.hip).
+constexpr size_t kSmallGdMaxLds = 152 << 10;    // dynamic LDS the kernel may use (of the 160 KiB of a compute unit)
+struct SmallStarArgs {
+  const float* S; int cs;       // entity table r_T x cs: cs <= 16, a multiple of 4, 16-byte aligned
+  const float* R; int cr, r_R;  // joined table (NULL: none), r_R <= 1024 rows, cr <= 16
+  const int32_t* idx;           // r_T keys into R (-1: none)
+  const int32_t* rowptr;        // inverse index of R
+  const int32_t* perm;
+  int nnz;
+  const int32_t* tcol_s;        // device int32[c_T]: column of S feeding target column t, or -1
+  const int32_t* tcol_r;
+  int16_t colmap[2][16];        // target column of every column of S and of R, or -1
+  int s_first;                  // S comes before R in the plan (order of the sums in shared target columns)
+  float* W; int ldw, col;       // weight column `col` of the c_T x ldw matrix, updated in place
+  const float* y; const float* lr; float* loss;
+  int r_T, c_T;
+  float inv_rT, loss_scale;
+};
+int small_star_max_rows(int nvs);
+size_t small_star_lds_bytes(const SmallStarArgs& a);
+hipError_t launch_small_star(const SmallStarArgs& a, int mode, hipStream_t st);
+
 // ---- launchers (each enqueues on `st`; returns the HIP error of the launch) ----
 hipError_t launch_check_idx(const int32_t* idx, int64_t r_T, int64_t r_k, int32_t* flags, hipStream_t st);
 hipError_t launch_sort_by_source_row(const int32_t* idx, int64_t r_T, int64_t r_k, int32_t* keys_a,

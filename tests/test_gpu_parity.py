@@ -528,6 +528,50 @@ def test_gd_many_models_one_learning_rate_each(il, m):
     np.testing.assert_allclose(L, L_ref, rtol=2e-4)
 
 
+@pytest.mark.parametrize("model", ["linear", "logistic"])
+@pytest.mark.parametrize("r_T,c_S,r_R,c_R", [(999, 4, 1000, 8), (16_384, 4, 1_024, 16), (8_192, 8, 300, 4), (5_120, 12, 77, 12),
+                                             (4_096, 16, 1, 16), (16_000, 4, 0, 0), (5_000, 12, 0, 0), (3, 16, 2, 4)])
+def test_gd_small_star_join_in_one_workgroup(il, model, r_T, c_S, r_R, c_R):
+    # schemas small enough for the single-launch iteration: every row length of the two tables (1..4 float4), the
+    # largest sizes the path takes, fewer rows than threads, a table alone (no joined source), a one-row table
+    rng = datagen.rng_for(7000 + r_T + c_S + c_R)
+    dims = [(r_R, c_R, "uniform")] if r_R > 0 else []
+    sch = datagen.star_schema(rng, r_T, c_S, dims)
+    tg = oracle.Target(sch)
+    w_star = rng.standard_normal(sch.c_T) / np.sqrt(sch.c_T)
+    y = datagen.finish_labels(model, oracle.lmm(tg, w_star.reshape(-1, 1)), 0.1 * rng.standard_normal(r_T))
+    plan = il.ilargi_plan_create(il.schema_to_device(sch), sch.r_T, sch.c_T, max_cx=3)
+    lrs = [0.1, 0.02, 0.3]
+    code = il.LINEAR if model == "linear" else il.LOGISTIC
+    W, L = _run_gd(il, plan, code, y, lrs, 6, sch.c_T)
+    W_ref, L_ref = oracle.gd(tg, model, y, np.zeros((sch.c_T, 3)), lrs, 6)
+    assert max(rel(W[:, j], W_ref[:, j]) for j in range(3)) < GD_TOL
+    np.testing.assert_allclose(L, L_ref, rtol=1e-4)
+    W2, L2 = _run_gd(il, plan, code, y, lrs, 6, sch.c_T)
+    assert np.array_equal(W, W2) and np.array_equal(L, L2)          # same bits on every run
+
+
+def test_gd_small_star_join_with_missing_keys_shared_and_unfed_columns(il):
+    # the joined table listed first, a target column fed by both tables, one fed by nobody, one source column
+    # dropped, target rows without a key, rows of the joined table nobody uses
+    rng = datagen.rng_for(7100)
+    r_T, r_R = 3_000, 200
+    S = rng.standard_normal((r_T, 8)).astype(np.float32)
+    R = rng.standard_normal((r_R, 4)).astype(np.float32)
+    fk = rng.integers(0, r_R // 2, size=r_T).astype(np.int32)
+    fk[rng.random(r_T) < 0.1] = -1
+    sch = datagen.Schema([datagen.Source(R, fk, np.array([9, 2, -1, 10], dtype=np.int32)),
+                          datagen.Source(S, None, np.array([0, 1, 2, 3, 4, 5, 6, 7], dtype=np.int32))], r_T, 12)
+    tg = oracle.Target(sch)
+    y = rng.standard_normal(r_T).astype(np.float32)
+    plan = il.ilargi_plan_create(il.schema_to_device(sch), sch.r_T, sch.c_T, max_cx=1)
+    W, L = _run_gd(il, plan, il.LINEAR, y, [0.2], 8, sch.c_T)
+    W_ref, L_ref = oracle.gd(tg, "linear", y, np.zeros((sch.c_T, 1)), [0.2], 8)
+    assert rel(W, W_ref) < GD_TOL
+    np.testing.assert_allclose(L, L_ref, rtol=1e-4)
+    assert W[8, 0] == 0.0 and W[11, 0] == 0.0                       # columns nobody feeds keep their weight
+
+
 def test_gd_without_loss_output(il):
     sch, tg, plan = get(il, "config0")
     y = _labels(sch, tg, "linear")
