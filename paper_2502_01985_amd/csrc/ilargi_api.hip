@@ -424,7 +424,8 @@ ilargi_status_t lmm_pass(ilargi_plan* pl, const float* X, int ldx, int col0, int
   int grid = 0;
   {
     TraceScope ts(pl, "lmm_assemble", -1, st);
-    if (wide) HIP_TRY(launch_lmm_mfma(a, vec, mode, bf16, st, &grid));
+    if (wide && !bf16 && lmm_flat_wide_supported(a, vec, mode)) HIP_TRY(launch_lmm_flat_wide(a, st, &grid));
+    else if (wide) HIP_TRY(launch_lmm_mfma(a, vec, mode, bf16, st, &grid));
     else HIP_TRY(launch_lmm_rows(a, vec, mode, st, &grid));
   }
   if (loss_grid) *loss_grid = grid;
@@ -600,12 +601,34 @@ ilargi_status_t tmm_wide(ilargi_plan* pl, const float* Y, int cx, float* out, in
                          int done_k = -1) {
   ColAsmArgs c;
   memset(&c, 0, sizeof(c));
+  // which kernel serves a source: 1 join-order pass, 2 flat column reduce, 0 segment sums + matrix-core reduce
+  auto route = [&](const SourcePlan& p) {
+    if (!p.ident && !bf16 && p.n_long == 0 && cx % 4 == 0 && tmm_join_supported((int)p.cols, cx) &&
+        p.cols * cx <= pl->lay.gpartial_floats)
+      return 1;
+    if (p.ident && !bf16 && cx % 4 == 0 && reinterpret_cast<uintptr_t>(Y) % 16 == 0 && colred_flat_supported(p.D, p.cols, cx) &&
+        p.cols * cx <= pl->lay.gpartial_floats)
+      return 2;
+    return 0;
+  };
+  // When every source leaves per-workgroup partial blocks (routes 1 and 2), the blocks stay side by side in the
+  // partial buffer and the column assembly adds them itself: one launch instead of a reduction per source.
+  bool defer = cx <= 64;
+  int64_t worst = 0;                                     // floats of all blocks if every launch took 1024 workgroups
+  for (int k = 0; k < pl->n && defer; ++k) {
+    if (pl->src[k].empty || k == done_k) continue;
+    if (route(pl->src[k]) == 0) defer = false;
+    worst += 1024 * pl->src[k].cols * cx;
+  }
+  if (worst > pl->lay.gpartial_floats) defer = false;
+  int64_t part_off = 0;
   for (int k = 0; k < pl->n; ++k) {
     SourcePlan& p = pl->src[k];
     if (p.empty) continue;
     if (k == done_k) {
       c.tcol2src[c.n] = pl->at<int32_t>(p.o_tcol);
       c.G[c.n] = pl->at<float>(p.o_g);
+      c.ck[c.n] = (int)p.cols;
       ++c.n;
       continue;
     }
@@ -614,44 +637,43 @@ ilargi_status_t tmm_wide(ilargi_plan* pl, const float* Y, int cx, float* out, in
     g.A = p.D; g.lda = (int)p.cols; g.ca = (int)p.cols; g.a_rows = p.rows;
     g.ldb = cx; g.cb = cx; g.bcol0 = 0; g.b_rows = p.rows;
     g.n_rows = p.rows;
-    if (!p.ident && !bf16 && p.n_long == 0 && cx % 4 == 0 && tmm_join_supported((int)p.cols, cx) &&
-        p.cols * cx <= pl->lay.gpartial_floats) {
-      // segment sums and D_k^T Z_k in one pass in join order: Z_k is never written (operands whose rows are
-      // whole float4s; for the others the two-step form measures the same or better)
-      TmmJoinArgs j;
-      memset(&j, 0, sizeof(j));
-      j.D = p.D; j.ck = (int)p.cols; j.r_k = p.rows;
-      j.rowptr = pl->at<int32_t>(p.o_rowptr); j.perm = pl->at<int32_t>(p.o_perm);
-      j.Y = Y; j.ldy = cx; j.col0 = 0; j.c = cx;
-      j.partial = pl->at<float>(pl->lay.o_gpartial);
+    const int rt = route(p);
+    if (rt != 0) {
+      float* part = pl->at<float>(pl->lay.o_gpartial) + part_off;
+      const int64_t room = pl->lay.gpartial_floats - part_off;
       int grid = 0;
-      {
+      if (rt == 1) {
+        // segment sums and D_k^T Z_k in one pass in join order: Z_k is never written (operands whose rows are
+        // whole float4s; for the others the two-step form measures the same or better)
+        TmmJoinArgs j;
+        memset(&j, 0, sizeof(j));
+        j.D = p.D; j.ck = (int)p.cols; j.r_k = p.rows;
+        j.rowptr = pl->at<int32_t>(p.o_rowptr); j.perm = pl->at<int32_t>(p.o_perm);
+        j.Y = Y; j.ldy = cx; j.col0 = 0; j.c = cx;
+        j.partial = part;
         TraceScope ts(pl, "tmm_join", k, st);
-        HIP_TRY(launch_tmm_join(j, pl->lay.gpartial_floats, st, &grid));
-      }
-      HIP_TRY(launch_tred_reduce(j.partial, grid, p.cols * cx, pl->at<float>(p.o_g), st));
-      c.tcol2src[c.n] = pl->at<int32_t>(p.o_tcol);
-      c.G[c.n] = pl->at<float>(p.o_g);
-      ++c.n;
-      continue;
-    }
-    if (p.ident && !bf16 && cx % 4 == 0 && reinterpret_cast<uintptr_t>(Y) % 16 == 0 && colred_flat_supported(p.D, p.cols, cx) &&
-        p.cols * cx <= pl->lay.gpartial_floats) {
-      // short rows of an identity source, operand rows of whole float4s: flat float4 stream with plain FMAs instead
-      // of padded matrix-core tiles (with element-wise operand loads the matrix-core form measures faster)
-      ColredFlatArgs f;
-      memset(&f, 0, sizeof(f));
-      f.S = p.D; f.rows = p.rows; f.nvec = (int)(p.cols / 4);
-      f.Y = Y; f.ldy = cx; f.c = cx;
-      f.partial = pl->at<float>(pl->lay.o_gpartial);
-      int grid = 0;
-      {
+        HIP_TRY(launch_tmm_join(j, room, st, &grid));
+      } else {
+        // short rows of an identity source, operand rows of whole float4s: flat float4 stream with plain FMAs
+        // instead of padded matrix-core tiles (with element-wise operand loads the matrix-core form measures faster)
+        ColredFlatArgs f;
+        memset(&f, 0, sizeof(f));
+        f.S = p.D; f.rows = p.rows; f.nvec = (int)(p.cols / 4);
+        f.Y = Y; f.ldy = cx; f.c = cx;
+        f.partial = part;
         TraceScope ts(pl, "colred", k, st);
-        HIP_TRY(launch_colred_flat(f, pl->lay.gpartial_floats, st, &grid));
+        HIP_TRY(launch_colred_flat(f, room, st, &grid));
       }
-      HIP_TRY(launch_tred_reduce(f.partial, grid, p.cols * cx, pl->at<float>(p.o_g), st));
       c.tcol2src[c.n] = pl->at<int32_t>(p.o_tcol);
-      c.G[c.n] = pl->at<float>(p.o_g);
+      c.ck[c.n] = (int)p.cols;
+      if (defer) {
+        c.G[c.n] = part;
+        c.nparts[c.n] = grid;
+        part_off += (int64_t)grid * p.cols * cx;
+      } else {
+        HIP_TRY(launch_tred_reduce(part, grid, p.cols * cx, pl->at<float>(p.o_g), st));
+        c.G[c.n] = pl->at<float>(p.o_g);
+      }
       ++c.n;
       continue;
     }
@@ -671,6 +693,7 @@ ilargi_status_t tmm_wide(ilargi_plan* pl, const float* Y, int cx, float* out, in
     if (rc != ILARGI_OK) return rc;
     c.tcol2src[c.n] = pl->at<int32_t>(p.o_tcol);
     c.G[c.n] = pl->at<float>(p.o_g);
+    c.ck[c.n] = (int)p.cols;
     ++c.n;
   }
   c.c_T = (int)pl->c_T; c.cx = cx; c.out = out;

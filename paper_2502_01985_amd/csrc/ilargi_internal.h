@@ -218,7 +218,9 @@ struct TredArgs {
 struct ColAsmArgs {
   int n;
   const int32_t* tcol2src[kMaxSources];
-  const float* G[kMaxSources];   // c_k x cx each
+  const float* G[kMaxSources];   // c_k x cx each; with nparts[k] > 1: that many such blocks, to be added in order
+  int nparts[kMaxSources];       // (0 counts as 1)
+  int ck[kMaxSources];
   int c_T, cx;
   float* out;                    // c_T x cx
   const float* lr;
@@ -269,6 +271,8 @@ bool lmm_can_fuse_gradient(int ck, int vec, int logL);
 MfmaShape lmm_mfma_shape(int ck, int nt, bool gathers, bool bf16);
 bool lmm_mfma_can_fuse_gradient(int ck, int ncols, bool bf16);
 hipError_t launch_lmm_mfma(const LmmArgs& a, int vec, int mode, bool bf16, hipStream_t st, int* grid_out);
+bool lmm_flat_wide_supported(const LmmArgs& a, int vec, int mode);
+hipError_t launch_lmm_flat_wide(const LmmArgs& a, hipStream_t st, int* grid_out);
 bool gd_star_supported(int cs, int m);
 hipError_t launch_gd_star(const StarArgs& a, int vec, int mode, bool bf16, int max_grid, hipStream_t st, int* grid_out);
 hipError_t launch_csr_check(const SparseArgs& a, int32_t* flags, hipStream_t st);

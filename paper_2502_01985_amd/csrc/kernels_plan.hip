@@ -76,6 +76,45 @@ __global__ __launch_bounds__(1024) void exclusive_scan_kernel(int32_t* __restric
   }
 }
 
+// Two-level form for long arrays: every workgroup scans its own 1024 integers in place and leaves their sum;
+// the sums are scanned by the single-workgroup kernel above and added back.
+__global__ __launch_bounds__(1024) void scan_blocks_kernel(int32_t* __restrict__ a, int64_t n,
+                                                           int32_t* __restrict__ totals) {
+  __shared__ int32_t wsum[16];
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const int64_t i = (int64_t)blockIdx.x * 1024 + threadIdx.x;
+  const int32_t v = i < n ? a[i] : 0;
+  int32_t inc = v;
+  for (int d = 1; d < kWave; d <<= 1) {
+    int32_t t = __shfl_up(inc, d);
+    if (lane >= d) inc += t;
+  }
+  if (lane == kWave - 1) wsum[wave] = inc;
+  __syncthreads();
+  int32_t woff = 0;
+  for (int w = 0; w < wave; ++w) woff += wsum[w];
+  if (i < n) a[i] = woff + inc - v;
+  if (threadIdx.x == 1023) totals[blockIdx.x] = woff + inc;
+}
+
+__global__ __launch_bounds__(1024) void scan_add_kernel(int32_t* __restrict__ a, int64_t n,
+                                                        const int32_t* __restrict__ totals) {
+  const int64_t i = (int64_t)blockIdx.x * 1024 + threadIdx.x;
+  if (i < n) a[i] += totals[blockIdx.x];
+}
+
+// In-place exclusive prefix sum of n integers; `totals` holds ceil(n / 1024) integers of scratch.
+static void launch_exclusive_scan(int32_t* a, int64_t n, int32_t* totals, hipStream_t st) {
+  if (n <= 4096) {
+    exclusive_scan_kernel<<<1, 1024, 0, st>>>(a, n);
+    return;
+  }
+  const int nb = (int)((n + 1023) / 1024);
+  scan_blocks_kernel<<<nb, 1024, 0, st>>>(a, n, totals);
+  exclusive_scan_kernel<<<1, 1024, 0, st>>>(totals, nb);
+  scan_add_kernel<<<nb, 1024, 0, st>>>(a, n, totals);
+}
+
 // Stable scatter of one chunk: a single wavefront walks its keys 64 at a time; the rank of a key among
 // the equal digits of the same step comes from a ballot match, the running per-digit offsets sit in LDS.
 template <bool FIRST>
@@ -140,7 +179,8 @@ __global__ __launch_bounds__(kBlock) void copy_i32_kernel(const int32_t* __restr
 
 size_t sort_hist_ints(int64_t r_T) {
   int64_t nchunks = (r_T + kSortChunk - 1) / kSortChunk;
-  return (size_t)(256 * (nchunks > 0 ? nchunks : 1));
+  const int64_t h = 256 * (nchunks > 0 ? nchunks : 1);
+  return (size_t)(h + (h + 1023) / 1024 + 1);     // digit-major histogram, then the block sums of its two-level scan
 }
 
 // Sorts (key = source row or r_k for "none", value = target row) by key, stably, and derives rowptr.
@@ -169,7 +209,7 @@ hipError_t launch_sort_by_source_row(const int32_t* idx, int64_t r_T, int64_t r_
     } else {
       radix_hist_kernel<false><<<nchunks, kBlock, 0, st>>>(kin, r_T, (uint32_t)r_k, shift, nchunks, hist);
     }
-    exclusive_scan_kernel<<<1, 1024, 0, st>>>(hist, (int64_t)256 * nchunks);
+    launch_exclusive_scan(hist, (int64_t)256 * nchunks, hist + (int64_t)256 * nchunks, st);
     if (p == 0) {
       radix_scatter_kernel<true><<<nchunks, kWave, 0, st>>>(kin, vin, r_T, (uint32_t)r_k, shift, nchunks, hist,
                                                            kout, vout);

@@ -451,6 +451,62 @@ __global__ __launch_bounds__(kBlock) void colasm_kernel(ColAsmArgs a) {
   }
 }
 
+// The same with sources that still hold per-workgroup partial blocks (nparts[k] blocks of c_k x cx): one workgroup
+// per target column; thread (n, slice) adds the blocks slice, slice + S, ... of operand column n, the slices are
+// added in order through LDS, the sources in source order.  For operands of at most 64 columns.
+template <int MODE>
+__global__ __launch_bounds__(kBlock) void colasm_parts_kernel(ColAsmArgs a, int nw) {
+  __shared__ float part[kBlock];
+  const int t = blockIdx.x;
+  if (t >= a.c_T) {
+    if constexpr (MODE == 1) {
+      // one extra workgroup: loss[n] = scale * sum of the per-workgroup partials, wavefront per column
+      if (a.loss != nullptr) {
+        const int lane = threadIdx.x % kWave;
+        for (int n = threadIdx.x / kWave; n < a.cx; n += kBlock / kWave) {
+          float s = 0.0f;
+          for (int b = lane; b < a.n_loss_partial; b += kWave) s += a.loss_partial[(int64_t)b * a.cx + n];
+          for (int m = kWave / 2; m >= 1; m >>= 1) s += __shfl_xor(s, m);
+          if (lane == 0) a.loss[n] = s * a.loss_scale;
+        }
+      }
+    }
+    return;
+  }
+  const int n = threadIdx.x % nw, sl = threadIdx.x / nw, ns = kBlock / nw;
+  float acc = 0.0f;
+  for (int k = 0; k < a.n; ++k) {
+    const int j = a.tcol2src[k][t];
+    const int np = a.nparts[k] > 0 ? a.nparts[k] : 1;
+    float s = 0.0f;
+    if (j >= 0 && n < a.cx) {
+      const float* g = a.G[k] + (int64_t)j * a.cx + n;
+      const int64_t stride = (int64_t)a.ck[k] * a.cx;
+      float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
+      int b = sl;
+      for (; b + 3 * ns < np; b += 4 * ns) {
+        s0 += g[(int64_t)b * stride]; s1 += g[(int64_t)(b + ns) * stride];
+        s2 += g[(int64_t)(b + 2 * ns) * stride]; s3 += g[(int64_t)(b + 3 * ns) * stride];
+      }
+      for (; b < np; b += ns) s0 += g[(int64_t)b * stride];
+      s = (s0 + s1) + (s2 + s3);
+    }
+    __syncthreads();                                   // the previous source's sums are consumed
+    part[threadIdx.x] = s;
+    __syncthreads();
+    if (sl == 0) {
+      float v = 0.0f;
+      for (int q = 0; q < ns; ++q) v += part[q * nw + n];
+      acc += v;
+    }
+  }
+  if (sl == 0 && n < a.cx) {
+    float* o = a.out + (int64_t)t * a.cx + n;
+    if constexpr (MODE == 0) *o = acc;
+    else *o = *o - a.lr[n] * (acc * a.inv_rT);
+  }
+}
+
 }  // namespace
 
 namespace {
@@ -567,6 +623,15 @@ hipError_t launch_tred_reduce(const float* partial, int nchunks, int64_t elems, 
 hipError_t launch_colasm(const ColAsmArgs& a, int mode, hipStream_t st) {
   int64_t total = (int64_t)a.c_T * a.cx;
   if (total <= 0) return hipSuccess;
+  bool parts = false;
+  for (int k = 0; k < a.n; ++k) parts = parts || a.nparts[k] > 1;
+  if (parts && a.cx <= 64) {
+    const int nw = a.cx <= 16 ? 16 : (a.cx <= 32 ? 32 : 64);
+    const int grid = a.c_T + ((mode == 1 && a.loss != nullptr) ? 1 : 0);
+    if (mode == 0) colasm_parts_kernel<0><<<grid, kBlock, 0, st>>>(a, nw);
+    else colasm_parts_kernel<1><<<grid, kBlock, 0, st>>>(a, nw);
+    return hipGetLastError();
+  }
   int grid = (int)((total + kBlock - 1) / kBlock);
   if (grid > 1024) grid = 1024;
   if (mode == 0) colasm_kernel<0><<<grid, kBlock, 0, st>>>(a);
