@@ -62,6 +62,10 @@ struct SourcePlan {
   int n_chunks = 0, n_long = 0;
   size_t o_join_first = 0;        // join-order column reduce: first source row of every workgroup
   int n_join_blocks = 0;
+  bool sliced = false;            // the inverse index is also split by slice of target rows (large target tables)
+  size_t o_sl_rowptr = 0, o_sl_perm = 0, o_sl_chunk0 = 0, o_sl_ch_beg = 0, o_sl_ch_end = 0, o_sl_nchunk = 0,
+         o_sl_ch_partial = 0, o_zslice = 0;
+  int sl_cap = 0, sl_logG = 0;
   int64_t nnz = 0;
   int logG = 0;
 };
@@ -228,6 +232,20 @@ ilargi_status_t make_layout(int n, const ilargi_source_t* s, int64_t r_T, int64_
       p.o_long_first = take(sizeof(int32_t) * (p.nl_max + 1));
       p.o_chunk_partial = take(sizeof(float) * p.nch_max * wmax);
       p.o_join_first = take(sizeof(int32_t) * (kColredBlocks + 1));
+      // a residual of 6 MB or more does not stay in an XCD's 4 MB of L2: segments are then also split by slice
+      // of target rows (worth it when a source row still has entries in most slices)
+      p.sliced = r_T >= 1500000 && p.rows > 0 && p.rows * kSegSlices <= r_T && s[k].csr_rowptr == nullptr;
+      if (p.sliced) {
+        p.sl_cap = (int)segsum_sliced_chunk_cap(r_T);
+        p.o_sl_rowptr = take(sizeof(int32_t) * (kSegSlices * p.rows + 1));
+        p.o_sl_perm = take(sizeof(int32_t) * std::max<int64_t>(r_T, 1));
+        p.o_sl_chunk0 = take(sizeof(int32_t) * kSegSlices * p.rows);
+        p.o_sl_ch_beg = take(sizeof(int32_t) * kSegSlices * p.sl_cap);
+        p.o_sl_ch_end = take(sizeof(int32_t) * kSegSlices * p.sl_cap);
+        p.o_sl_nchunk = take(sizeof(int32_t) * kSegSlices);
+        p.o_sl_ch_partial = take(sizeof(float) * kSegSlices * p.sl_cap * kNarrowCT);
+        p.o_zslice = take(sizeof(float) * kSegSlices * p.rows * kNarrowCT);
+      }
     }
     p.o_pz = take(sizeof(float) * std::max<int64_t>(p.rows, 1) * max_cx);
     // (a sparse source's transposed product leaves a single block of partials)
@@ -332,6 +350,14 @@ SegArgs seg_args(const ilargi_plan* pl, int k) {
   a.chunk_partial = pl->at<float>(p.o_chunk_partial);
   a.logG = p.logG;
   a.block_first = p.n_join_blocks > 0 ? pl->at<int32_t>(p.o_join_first) : nullptr;
+  if (p.sliced && !p.ident) {
+    a.sl_rowptr = pl->at<int32_t>(p.o_sl_rowptr); a.sl_perm = pl->at<int32_t>(p.o_sl_perm);
+    a.sl_chunk0 = pl->at<int32_t>(p.o_sl_chunk0);
+    a.sl_ch_beg = pl->at<int32_t>(p.o_sl_ch_beg); a.sl_ch_end = pl->at<int32_t>(p.o_sl_ch_end);
+    a.sl_nchunk = pl->at<int32_t>(p.o_sl_nchunk); a.sl_ch_partial = pl->at<float>(p.o_sl_ch_partial);
+    a.sl_cap = p.sl_cap; a.sl_logG = p.sl_logG;
+    a.Zs = pl->at<float>(p.o_zslice);
+  }
   return a;
 }
 
@@ -519,6 +545,13 @@ ilargi_status_t tmm_pass(ilargi_plan* pl, const float* Y, int ldy, int col0, int
         c = colred_args(k, pl->at<float>(p.o_cnt), 1, 0);
       } else if (p.ident) {
         c = colred_args(k, Y, ldy, col0);
+      } else if (p.sliced) {
+        // large target table: per-slice sums over the sliced index, added by the column reduce
+        {
+          TraceScope ts(pl, "segsum", k, st);
+          HIP_TRY(launch_segsum_sliced(segsum_args(k), st));
+        }
+        c = colred_args(k, pl->at<float>(p.o_pz), ldy, col0);
       } else {
         {
           TraceScope ts(pl, "segsum", k, st);
@@ -910,6 +943,24 @@ ilargi_status_t plan_create_impl(int n, const ilargi_source_t* sources, int64_t 
     }
     int64_t avg = p.rows > 0 ? (p.nnz + p.rows - 1) / p.rows : 1;
     p.logG = std::min(6, ilog2_ceil(std::max<int64_t>(avg, 1)));
+    if (p.sliced) {
+      int64_t slice_rows = (r_T + kSegSlices - 1) / kSegSlices;
+      slice_rows = (slice_rows + 63) / 64 * 64;
+      HIP_TRY(hipMemsetAsync(pl->at<int32_t>(p.o_sl_nchunk), 0, sizeof(int32_t) * kSegSlices, st));
+      // (the sort's buffers are free again: scratch for the runs' positions and for the scan)
+      HIP_TRY(launch_build_sliced_index(pl->at<int32_t>(p.o_rowptr), pl->at<int32_t>(p.o_perm), p.rows, p.nnz, slice_rows,
+                                        pl->at<int32_t>(p.o_sl_rowptr), pl->at<int32_t>(p.o_sl_perm),
+                                        pl->at<int32_t>(p.o_sl_chunk0), pl->at<int32_t>(p.o_sl_ch_beg),
+                                        pl->at<int32_t>(p.o_sl_ch_end), pl->at<int32_t>(p.o_sl_nchunk), p.sl_cap,
+                                        pl->at<int32_t>(lay.o_sort), pl->at<int32_t>(lay.o_hist), st));
+      int32_t nch[kSegSlices];
+      HIP_TRY(hipMemcpyAsync(nch, pl->at<int32_t>(p.o_sl_nchunk), sizeof(nch), hipMemcpyDeviceToHost, st));
+      HIP_TRY(hipStreamSynchronize(st));
+      for (int x = 0; x < kSegSlices; ++x)
+        if (nch[x] > p.sl_cap) return fail(ILARGI_ERR_WORKSPACE, "internal: chunk table of the sliced index overflows");
+      // lanes per (slice, source row) run: about four entries per lane, which it keeps in flight together
+      p.sl_logG = std::min(6, ilog2_ceil(std::max<int64_t>((avg + 4 * kSegSlices - 1) / (4 * kSegSlices), 1)));
+    }
     if (p.n_long == 0 && p.rows > 0 && !p.sparse && p.nnz <= 32 * p.rows) {
       // (with more index entries per row the gathers dominate and the segment-sum kernel, which spreads a
       // segment over a group of lanes, serves them better)

@@ -17,6 +17,9 @@ constexpr int kColredBlocks = 1024;  // most row chunks (= partial results) of t
 constexpr int kColredTarget = 512;   // row chunks aimed at: two workgroups per compute unit, eight loads in flight per lane
 constexpr int kSparseBlockRows = 1024;   // rows a row block of the sparse row-wise product holds at most
 constexpr int kSparseChunk = 4096;   // entries of a column one workgroup sums
+constexpr int kSegSlices = 8;        // slices of target rows of the sliced segment sum (one per XCD and its L2)
+constexpr int kSlLong = 256;         // ... runs of a (slice, source row) longer than this are cut into chunks
+constexpr int kSlChunk = 1024;       // ... of this many entries, each summed by a whole workgroup
 constexpr int kLongSeg = 2048;       // inverse-index segments longer than this are split ...
 constexpr int kSegChunk = 2048;      // ... into chunks of this many entries
 constexpr int kSortChunk = 2048;     // keys per workgroup in one radix pass
@@ -139,6 +142,15 @@ struct SegArgs {
   float* chunk_partial;    // n_chunks x ncols
   int logG;                // lanes per segment in the narrow kernel
   const int32_t* block_first;  // join-order column reduce: workgroup b owns source rows [block_first[b], block_first[b + 1])
+  // sliced form (large target tables): a second copy of the index ordered by (slice of target rows, source row)
+  const int32_t* sl_rowptr;    // [kSegSlices * r_k + 1] entries of (slice x, source row j) are sl_perm[sl_rowptr[x r_k + j] ..)
+  const int32_t* sl_perm;      // NULL: no sliced index
+  const int32_t* sl_chunk0;    // [kSegSlices][r_k] first chunk record of a run longer than kSlLong, else -1
+  const int32_t* sl_ch_beg, *sl_ch_end;   // [kSegSlices][sl_cap] chunk records: ranges of sl_perm
+  const int32_t* sl_nchunk;    // [kSegSlices] their number
+  float* sl_ch_partial;        // [kSegSlices][sl_cap][CT] chunk sums
+  int sl_cap, sl_logG;
+  float* Zs;                   // [kSegSlices][r_k][CT] per-slice sums of the short runs
 };
 
 struct ColredArgs {
@@ -264,6 +276,8 @@ hipError_t launch_sort_by_source_row(const int32_t* idx, int64_t r_T, int64_t r_
                                      int32_t* vals_a, int32_t* keys_b, int32_t* vals_b, int32_t* hist,
                                      int32_t* rowptr, int32_t* perm, hipStream_t st);
 size_t sort_hist_ints(int64_t r_T);
+// In-place exclusive prefix sum of n integers on the device; `totals` is scratch of ceil(n / 1024) integers.
+void launch_exclusive_scan(int32_t* a, int64_t n, int32_t* totals, hipStream_t st);
 
 hipError_t launch_lmm_rows(const LmmArgs& a, int vec, int mode, hipStream_t st, int* grid_out);
 int lmm_grid(int64_t r_out, int logL, bool fuseg);
@@ -287,6 +301,13 @@ hipError_t launch_spmm_t(const SparseArgs& a, const float* Z, int ldz, int col0,
 hipError_t launch_mat_scatter(const SparseArgs* sparse, const float* D, int64_t rows, int ck, const int32_t* colmap,
                               const int32_t* idx, int64_t ident_rows, float* T, int64_t r_T, int c_T, hipStream_t st);
 hipError_t launch_segsum(const SegArgs& a, hipStream_t st);
+// Builds the sliced copy of an inverse index (see SegArgs): sl_rowptr, sl_perm, the chunk records of long runs.
+// src_beg: scratch of kSegSlices * r_k integers; scan_scratch: of (kSegSlices * r_k + 1) / 1024 + 1 integers.
+hipError_t launch_build_sliced_index(const int32_t* rowptr, const int32_t* perm, int64_t r_k, int64_t nnz, int64_t slice_rows,
+                                     int32_t* sl_rowptr, int32_t* sl_perm, int32_t* sl_chunk0, int32_t* ch_beg, int32_t* ch_end,
+                                     int32_t* sl_nchunk, int cap, int32_t* src_beg, int32_t* scan_scratch, hipStream_t st);
+int64_t segsum_sliced_chunk_cap(int64_t nnz);
+hipError_t launch_segsum_sliced(const SegArgs& a, hipStream_t st);
 hipError_t launch_colred(const ColredArgs& a, int nblocks, hipStream_t st);
 bool lmm_flat_supported(const LmmArgs& a, int vec, bool fuseg);
 hipError_t launch_lmm_flat(const LmmArgs& a, int mode, bool fuseg, hipStream_t st, int* grid_out);

@@ -104,7 +104,7 @@ __global__ __launch_bounds__(1024) void scan_add_kernel(int32_t* __restrict__ a,
 }
 
 // In-place exclusive prefix sum of n integers; `totals` holds ceil(n / 1024) integers of scratch.
-static void launch_exclusive_scan(int32_t* a, int64_t n, int32_t* totals, hipStream_t st) {
+void launch_exclusive_scan(int32_t* a, int64_t n, int32_t* totals, hipStream_t st) {
   if (n <= 4096) {
     exclusive_scan_kernel<<<1, 1024, 0, st>>>(a, n);
     return;

@@ -128,6 +128,209 @@ __global__ __launch_bounds__(kBlock) void segsum_wide_kernel(SegArgs a) {
   }
 }
 
+// Chunks of a run of `len` entries (more than kSlLong): about kSlChunk entries each, at most eight, so that the
+// thread that adds a run's chunk sums has a short chain.
+__host__ __device__ __forceinline__ int sliced_chunks(int len) {
+  const int n = (len + kSlChunk - 1) / kSlChunk;
+  return n > 8 ? 8 : n;
+}
+
+// Plan time, step 1: the entries of a segment are in ascending order of target row, so those that fall into slice
+// x of the target rows (rows [x * slice_rows, (x + 1) * slice_rows)) are a contiguous run of it; its bounds come
+// from a binary search per (source row, slice).  Writes the run's length to len[x r_k + j] (slice-major) and its
+// first position in perm to src_beg.
+__global__ __launch_bounds__(kBlock) void slice_runs_kernel(const int32_t* __restrict__ rowptr, const int32_t* __restrict__ perm,
+                                                            int64_t r_k, int64_t slice_rows, int32_t* __restrict__ len,
+                                                            int32_t* __restrict__ src_beg) {
+  for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < r_k; j += (int64_t)gridDim.x * blockDim.x) {
+    const int32_t e = rowptr[j + 1];
+    int32_t prev = rowptr[j];
+    for (int x = 0; x < kSegSlices; ++x) {
+      const int64_t bound = (int64_t)(x + 1) * slice_rows;       // first entry whose target row is >= bound
+      int32_t lo = prev, hi = e;
+      while (lo < hi) {
+        const int32_t mid = lo + (hi - lo) / 2;
+        if ((int64_t)perm[mid] < bound) lo = mid + 1; else hi = mid;
+      }
+      if (x == kSegSlices - 1) lo = e;
+      len[(int64_t)x * r_k + j] = lo - prev;
+      src_beg[(int64_t)x * r_k + j] = prev;
+      prev = lo;
+    }
+  }
+  if (blockIdx.x == 0 && threadIdx.x == 0) len[(int64_t)kSegSlices * r_k] = 0;
+}
+
+// Step 3 (after the exclusive scan of the lengths): entry q of the sliced copy belongs to the run `it` with
+// sl_rowptr[it] <= q < sl_rowptr[it + 1] (binary search) and is entry src_beg[it] + q - sl_rowptr[it] of perm.
+__global__ __launch_bounds__(kBlock) void slice_copy_kernel(const int32_t* __restrict__ perm, const int32_t* __restrict__ sl_rowptr,
+                                                            const int32_t* __restrict__ src_beg, int64_t nitems, int64_t nnz,
+                                                            int32_t* __restrict__ sl_perm) {
+  for (int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; q < nnz; q += (int64_t)gridDim.x * blockDim.x) {
+    int64_t lo = 0, hi = nitems;                                 // last run that starts at or before q
+    while (hi - lo > 1) {
+      const int64_t mid = (lo + hi) / 2;
+      if ((int64_t)sl_rowptr[mid] <= q) lo = mid; else hi = mid;
+    }
+    sl_perm[q] = perm[(int64_t)src_beg[lo] + q - sl_rowptr[lo]];
+  }
+}
+
+// Step 4: a run of more than kSlLong entries is cut into chunks, listed per slice (the list is filled through an
+// integer atomic counter: the order of the runs in it does not matter, the chunks of one run are consecutive and
+// every sum has a fixed order).
+__global__ __launch_bounds__(kBlock) void slice_chunks_kernel(const int32_t* __restrict__ sl_rowptr, int64_t r_k,
+                                                              int32_t* __restrict__ sl_chunk0, int32_t* __restrict__ ch_beg,
+                                                              int32_t* __restrict__ ch_end, int32_t* __restrict__ sl_nchunk, int cap) {
+  const int64_t nitems = (int64_t)kSegSlices * r_k;
+  for (int64_t it = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; it < nitems; it += (int64_t)gridDim.x * blockDim.x) {
+    const int x = (int)(it / r_k);
+    const int32_t b = sl_rowptr[it], e = sl_rowptr[it + 1];
+    int32_t c0 = -1;
+    if (e - b > kSlLong) {
+      const int n = sliced_chunks(e - b);
+      const int clen = (e - b + n - 1) / n;
+      c0 = atomicAdd(&sl_nchunk[x], n);
+      for (int c = 0; c < n && c0 + c < cap; ++c) {
+        ch_beg[(int64_t)x * cap + c0 + c] = min(e, b + c * clen);
+        ch_end[(int64_t)x * cap + c0 + c] = min(e, b + (c + 1) * clen);
+      }
+    }
+    sl_chunk0[it] = c0;
+  }
+}
+
+// Segment sums over the sliced index for narrow operands.  Workgroup b serves slice b % kSegSlices: workgroups
+// are dealt to the XCDs in turn, so the operand rows a slice gathers (r_T / 8 rows: 2.5 MB of a 5-million-row
+// residual) stay in the L2 of one XCD instead of crossing the fabric once per index entry.  Lane groups of
+// 2^sl_logG lanes take the (slice, source row) runs of at most kSlLong entries; the chunks of the longer runs are
+// summed by whole workgroups (thread t adds the entries t, t + 256, ..., then a fixed tree over the threads).
+template <int CT>
+__global__ __launch_bounds__(kBlock) void segsum_sliced_kernel(SegArgs a) {
+  __shared__ float red[CT][kBlock];
+  const int x = blockIdx.x % kSegSlices, bi = blockIdx.x / kSegSlices, nb = gridDim.x / kSegSlices;
+  const int G = 1 << a.sl_logG;
+  const int lig = threadIdx.x & (G - 1);
+  const int64_t gpb = kBlock >> a.sl_logG;
+  const int32_t* rp_x = a.sl_rowptr + (int64_t)x * a.r_k;
+  float* Zx = a.Zs + (int64_t)x * a.r_k * CT;
+  for (int64_t base = (int64_t)bi * gpb; base < a.r_k; base += (int64_t)nb * gpb) {   // same trip count for all threads
+    const int64_t j = base + (threadIdx.x >> a.sl_logG);
+    bool live = j < a.r_k;
+    int32_t beg = 0, end = 0;
+    if (live) {
+      beg = rp_x[j]; end = rp_x[j + 1];
+      if (end - beg > kSlLong) live = false;
+    }
+    float acc[CT];
+#pragma unroll
+    for (int n = 0; n < CT; ++n) acc[n] = 0.0f;
+    if (live) {
+      // four entries of the lane in flight: first their target rows, then the operand rows
+      for (int64_t p = beg + lig; p < end; p += 4 * G) {
+        int64_t r[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) r[u] = p + u * G < end ? (int64_t)a.sl_perm[p + u * G] : -1;
+        float y[4][CT];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+          for (int n = 0; n < CT; ++n) y[u][n] = (r[u] >= 0 && n < a.ncols) ? a.Y[r[u] * a.ldy + a.col0 + n] : 0.0f;
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+          for (int n = 0; n < CT; ++n) acc[n] += y[u][n];
+      }
+    }
+    for (int m = G >> 1; m >= 1; m >>= 1) {
+#pragma unroll
+      for (int n = 0; n < CT; ++n) acc[n] += __shfl_xor(acc[n], m);
+    }
+    if (live && lig == 0) {
+#pragma unroll
+      for (int n = 0; n < CT; ++n) Zx[j * CT + n] = acc[n];
+    }
+  }
+  // chunks of the long runs of this slice
+  const int nchunk = min(a.sl_nchunk[x], a.sl_cap);
+  for (int q = bi; q < nchunk; q += nb) {
+    const int32_t beg = a.sl_ch_beg[(int64_t)x * a.sl_cap + q], end = a.sl_ch_end[(int64_t)x * a.sl_cap + q];
+    float acc[CT];
+#pragma unroll
+    for (int n = 0; n < CT; ++n) acc[n] = 0.0f;
+    for (int64_t p = beg + threadIdx.x; p < end; p += 4 * kBlock) {
+      int64_t r[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) r[u] = p + u * kBlock < end ? (int64_t)a.sl_perm[p + u * kBlock] : -1;
+      float y[4][CT];
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int n = 0; n < CT; ++n) y[u][n] = (r[u] >= 0 && n < a.ncols) ? a.Y[r[u] * a.ldy + a.col0 + n] : 0.0f;
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int n = 0; n < CT; ++n) acc[n] += y[u][n];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int n = 0; n < CT; ++n) red[n][threadIdx.x] = acc[n];
+    __syncthreads();
+    for (int w = kBlock / 2; w >= 1; w >>= 1) {
+      if ((int)threadIdx.x < w) {
+#pragma unroll
+        for (int n = 0; n < CT; ++n) red[n][threadIdx.x] += red[n][threadIdx.x + w];
+      }
+      __syncthreads();
+    }
+    if ((int)threadIdx.x < CT) a.sl_ch_partial[((int64_t)x * a.sl_cap + q) * CT + threadIdx.x] = red[threadIdx.x][0];
+  }
+}
+
+// Z[j, :] = the per-slice sums of source row j added in slice order; a long run's sum is its chunks added in order.
+template <int CT>
+__global__ __launch_bounds__(kBlock) void segsum_sliced_combine_kernel(SegArgs a) {
+  for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < a.r_k; j += (int64_t)gridDim.x * blockDim.x) {
+    int c0[kSegSlices];
+    float v[kSegSlices][CT];
+#pragma unroll
+    for (int x = 0; x < kSegSlices; ++x) {                       // all slices requested together
+      const int64_t it = (int64_t)x * a.r_k + j;
+      c0[x] = a.sl_chunk0[it];
+#pragma unroll
+      for (int n = 0; n < CT; ++n) v[x][n] = a.Zs[it * CT + n];
+    }
+    float z[CT];
+#pragma unroll
+    for (int n = 0; n < CT; ++n) z[n] = 0.0f;
+#pragma unroll
+    for (int x = 0; x < kSegSlices; ++x) {
+      if (c0[x] >= 0) {
+        const int64_t it = (int64_t)x * a.r_k + j;
+        const int nch = sliced_chunks(a.sl_rowptr[it + 1] - a.sl_rowptr[it]);
+        float cp[8][CT];
+#pragma unroll
+        for (int c = 0; c < 8; ++c)
+#pragma unroll
+          for (int n = 0; n < CT; ++n)
+            cp[c][n] = c < nch ? a.sl_ch_partial[((int64_t)x * a.sl_cap + c0[x] + c) * CT + n] : 0.0f;
+#pragma unroll
+        for (int n = 0; n < CT; ++n) {
+          float s = 0.0f;
+#pragma unroll
+          for (int c = 0; c < 8; ++c) s += cp[c][n];
+          v[x][n] = s;
+        }
+      }
+#pragma unroll
+      for (int n = 0; n < CT; ++n) z[n] += v[x][n];
+    }
+#pragma unroll
+    for (int n = 0; n < CT; ++n)
+      if (n < a.ncols) a.Z[j * a.ldz + a.zcol0 + n] = z[n];
+  }
+}
+
 // Long segments: add the chunk sums in chunk order.
 __global__ __launch_bounds__(kBlock) void segsum_combine_kernel(SegArgs a) {
   int64_t total = (int64_t)a.n_long * a.ncols;
@@ -427,6 +630,47 @@ hipError_t launch_segsum(const SegArgs& a, hipStream_t st) {
     e = hipGetLastError();
   }
   return e;
+}
+
+hipError_t launch_build_sliced_index(const int32_t* rowptr, const int32_t* perm, int64_t r_k, int64_t nnz, int64_t slice_rows,
+                                     int32_t* sl_rowptr, int32_t* sl_perm, int32_t* sl_chunk0, int32_t* ch_beg, int32_t* ch_end,
+                                     int32_t* sl_nchunk, int cap, int32_t* src_beg, int32_t* scan_scratch, hipStream_t st) {
+  if (r_k <= 0) return hipSuccess;
+  const int64_t nitems = (int64_t)kSegSlices * r_k;
+  int grid = (int)std::min<int64_t>((r_k + kBlock - 1) / kBlock, 4096);
+  slice_runs_kernel<<<grid, kBlock, 0, st>>>(rowptr, perm, r_k, slice_rows, sl_rowptr, src_beg);
+  launch_exclusive_scan(sl_rowptr, nitems + 1, scan_scratch, st);
+  if (nnz > 0) {
+    grid = (int)std::min<int64_t>((nnz + kBlock - 1) / kBlock, 8192);
+    slice_copy_kernel<<<grid, kBlock, 0, st>>>(perm, sl_rowptr, src_beg, nitems, nnz, sl_perm);
+  }
+  grid = (int)std::min<int64_t>((nitems + kBlock - 1) / kBlock, 4096);
+  slice_chunks_kernel<<<grid, kBlock, 0, st>>>(sl_rowptr, r_k, sl_chunk0, ch_beg, ch_end, sl_nchunk, cap);
+  return hipGetLastError();
+}
+
+// Chunk records a slice needs at most for an index of nnz entries.
+int64_t segsum_sliced_chunk_cap(int64_t nnz) { return nnz / kSlLong + 1; }
+
+hipError_t launch_segsum_sliced(const SegArgs& a, hipStream_t st) {
+  if (a.sl_perm == nullptr || a.ncols < 1 || a.ncols > kNarrowCT || a.r_k <= 0) return hipErrorInvalidValue;
+  const int64_t gpb = kBlock >> a.sl_logG;
+  int64_t nb = (a.r_k + gpb - 1) / gpb;                 // workgroups per slice
+  nb = std::min<int64_t>(std::max<int64_t>(nb, 64), 2048);
+  const unsigned grid = (unsigned)(nb * kSegSlices);
+  int cgrid = (int)((a.r_k + kBlock - 1) / kBlock);
+  if (cgrid > 2048) cgrid = 2048;
+  if (a.ncols == 1) {
+    segsum_sliced_kernel<1><<<grid, kBlock, 0, st>>>(a);
+    segsum_sliced_combine_kernel<1><<<cgrid, kBlock, 0, st>>>(a);
+  } else if (a.ncols == 2) {
+    segsum_sliced_kernel<2><<<grid, kBlock, 0, st>>>(a);
+    segsum_sliced_combine_kernel<2><<<cgrid, kBlock, 0, st>>>(a);
+  } else {
+    segsum_sliced_kernel<4><<<grid, kBlock, 0, st>>>(a);
+    segsum_sliced_combine_kernel<4><<<cgrid, kBlock, 0, st>>>(a);
+  }
+  return hipGetLastError();
 }
 
 hipError_t launch_colred(const ColredArgs& a, int nblocks, hipStream_t st) {

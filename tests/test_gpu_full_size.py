@@ -237,3 +237,31 @@ def test_config4_bf16_inputs(il):
     errs = np.array([rel(W[:, j], gold["W"][:, j]) for j in range(256)])
     print(f"bf16-input GD, 256 models: max relative weight error {errs.max():.3e}, median {np.median(errs):.3e}")
     assert errs.max() < 2e-2, errs.max()
+
+
+def test_sliced_segment_sums_on_a_large_target_table(il):
+    # target tables from 1.5 million rows on split every segment of the inverse index by slice of target rows
+    # (narrow transposed multiply and gradient descent); a Zipf key gives runs far beyond the long-segment limit in
+    # every slice, the second table has rows with entries in only some slices, the third is a tiny one
+    rng = datagen.rng_for(8100)
+    sch = datagen.star_schema(rng, 1_600_037, 4, [(1_000, 8, ("zipf", 1.3)), (150_000, 4, "uniform"), (37, 5, "uniform")])
+    tg = oracle.Target(sch)
+    plan = il.ilargi_plan_create(il.schema_to_device(sch), sch.r_T, sch.c_T, max_cx=4)
+    for cx in (1, 3, 4):
+        Y = rng.standard_normal((sch.r_T, cx)).astype(np.float32)
+        got = il.ilargi_tmm(plan, dev(Y)).cpu().numpy()
+        assert rel(got, oracle.tmm(tg, Y)) < OP_TOL
+        assert np.array_equal(got, il.ilargi_tmm(plan, dev(Y)).cpu().numpy())          # same bits on every run
+    assert rel(il.ilargi_col_sum(plan).cpu().numpy(), oracle.col_sum(sch)) < OP_TOL
+    w_star = rng.standard_normal(sch.c_T) / np.sqrt(sch.c_T)
+    y = datagen.finish_labels("logistic", oracle.lmm(tg, w_star.reshape(-1, 1)), 0.1 * rng.standard_normal(sch.r_T))
+    W = torch.zeros((sch.c_T, 1), device="cuda")
+    lr = dev(np.array([0.5], dtype=np.float32))
+    loss = torch.zeros(1, device="cuda")
+    losses = []
+    for _ in range(5):
+        il.ilargi_gd_step(plan, il.LOGISTIC, W, dev(y), lr, loss)
+        losses.append(float(loss.item()))
+    W_ref, L_ref = oracle.gd(tg, "logistic", y, np.zeros((sch.c_T, 1)), [0.5], 5)
+    assert rel(W.cpu().numpy(), W_ref) < GD_TOL
+    np.testing.assert_allclose(np.array(losses), L_ref[:, 0], rtol=1e-4)
