@@ -435,6 +435,7 @@ hipError_t launch_lmm_rows(const LmmArgs& a, int vec, int mode, hipStream_t st, 
   if (mode == 0 && !fuseg && a.g.n == 0 && a.D != nullptr && vec == 4 && a.ck >= 4 && a.ck <= 256 && a.ncols <= kNarrowCT)
     return launch_rowdot(a, st);
   if (lmm_flat_supported(a, vec, fuseg)) return launch_lmm_flat(a, mode, fuseg, st, grid_out);
+  if (lmm_flat_pair_supported(a, vec, fuseg)) return launch_lmm_flat_pair(a, mode, fuseg, st, grid_out);
   switch (vec) {
     case 4: return launch_ct<4>(a, mode, fuseg, grid, st);
     case 2: return launch_ct<2>(a, mode, fuseg, grid, st);

@@ -23,14 +23,6 @@ namespace ilargi {
 
 namespace {
 
-__device__ __forceinline__ float flat_sigmoid(float z) {
-  if (z >= 0.0f) return 1.0f / (1.0f + __expf(-z));
-  float e = __expf(z);
-  return e / (1.0f + e);
-}
-
-__device__ __forceinline__ float flat_softplus(float z) { return fmaxf(z, 0.0f) + log1pf(__expf(-fabsf(z))); }
-
 __device__ __forceinline__ void flat_wave_sync() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();
@@ -39,11 +31,6 @@ __device__ __forceinline__ void flat_wave_sync() {
 
 constexpr int kFlatGather = 3;                 // gathered sources (their row indices are prefetched a chunk ahead)
 constexpr int kFlatWaves = kBlock / kWave;
-
-__device__ __forceinline__ int64_t flat_gather_row(const GatherArgs& g, int s, int64_t i) {
-  if (g.idx[s] != nullptr) return g.idx[s][i];
-  return i < g.rows[s] ? i : -1;
-}
 
 // NVT: compile-time bound of nvec = ck / 4.  wave_floats: LDS floats of one wavefront.
 template <int NVT, int CT, int MODE, bool FUSEG>
@@ -90,11 +77,26 @@ __global__ __launch_bounds__(kBlock) void lmm_flat_kernel(LmmArgs a, int wave_fl
   const int64_t nchunks = (a.r_out + kWave - 1) / kWave;
   const int64_t cstride = (int64_t)gridDim.x * kFlatWaves;
   int64_t chunk = (int64_t)blockIdx.x * kFlatWaves + wave;
-  int64_t jn[kFlatGather];
+  // the gathered sources' pointers, read from the kernel arguments once
+  const int32_t* gidx[kFlatGather];
+  const float* gP[kFlatGather];
+  int64_t grows[kFlatGather];
+#pragma unroll
+  for (int s = 0; s < kFlatGather; ++s) {
+    gidx[s] = s < a.g.n ? a.g.idx[s] : nullptr;
+    gP[s] = s < a.g.n ? a.g.P[s] + a.col0 : nullptr;
+    grows[s] = s < a.g.n ? a.g.rows[s] : 0;
+  }
+  const int ng = a.g.n, ldp_g = a.g.ldp;
+  const int64_t r_out = a.r_out;
+  auto gather_row = [&](int s, int64_t i) -> int {
+    return gidx[s] != nullptr ? gidx[s][i] : (i < grows[s] ? (int)i : -1);
+  };
+  int jn[kFlatGather];
 #pragma unroll
   for (int s = 0; s < kFlatGather; ++s) {
     const int64_t i = chunk * kWave + lane;
-    jn[s] = (s < a.g.n && chunk < nchunks && i < a.r_out) ? flat_gather_row(a.g, s, i) : -1;
+    jn[s] = (s < ng && chunk < nchunks && i < r_out) ? gather_row(s, i) : -1;
   }
   // the chunk of the table, flat; the next chunk is requested before the current one is used, so that a
   // wavefront always has a chunk in flight
@@ -120,26 +122,25 @@ __global__ __launch_bounds__(kBlock) void lmm_flat_kernel(LmmArgs a, int wave_fl
     float gsum[CT];
 #pragma unroll
     for (int n = 0; n < CT; ++n) gsum[n] = 0.0f;
-    if (rowlive) {
 #pragma unroll
-      for (int s = 0; s < kFlatGather; ++s) {
-        if (s < a.g.n && jn[s] >= 0) {
-          const float* p = a.g.P[s] + jn[s] * a.g.ldp + a.col0;
+    for (int s = 0; s < kFlatGather; ++s) {
+      if (s < ng) {
+        // branch-free: a missing key reads row 0 and contributes nothing
+        const float* p = gP[s] + (int64_t)max(jn[s], 0) * ldp_g;
+        float pv[CT];
 #pragma unroll
-          for (int n = 0; n < CT; ++n)
-            if (n < a.ncols) gsum[n] += p[n];
-        }
+        for (int n = 0; n < CT; ++n) pv[n] = n < a.ncols ? p[n] : 0.0f;
+#pragma unroll
+        for (int n = 0; n < CT; ++n) gsum[n] += jn[s] >= 0 ? pv[n] : 0.0f;
       }
     }
     float yi = 0.0f;
-    if constexpr (MODE != 0) {
-      if (rowlive) yi = a.y[i];
-    }
+    if constexpr (MODE != 0) yi = a.y[min(i, r_out - 1)];
     {
       const int64_t inext = i + cstride * kWave;
 #pragma unroll
       for (int s = 0; s < kFlatGather; ++s)
-        jn[s] = (s < a.g.n && chunk + cstride < nchunks && inext < a.r_out) ? flat_gather_row(a.g, s, inext) : -1;
+        jn[s] = (s < ng && chunk + cstride < nchunks && inext < r_out) ? gather_row(s, inext) : -1;
     }
     // partial dot products into the tile
     flat_wave_sync();                                          // the previous chunk's tile is consumed
@@ -168,8 +169,11 @@ __global__ __launch_bounds__(kBlock) void lmm_flat_kernel(LmmArgs a, int wave_fl
           r = z - yi;
           loss_local[n] = fmaf(r, r, loss_local[n]);
         } else if constexpr (MODE == 2) {
-          r = flat_sigmoid(z) - yi;
-          loss_local[n] += flat_softplus(z) - yi * z;
+          // one exponential serves the sigmoid and the softplus: e = exp(-|z|)
+          const float e = __expf(-fabsf(z));
+          const float inv = __frcp_rn(1.0f + e);
+          r = (z >= 0.0f ? inv : e * inv) - yi;
+          loss_local[n] += fmaxf(z, 0.0f) + log1pf(e) - yi * z;
         }
         float* op = a.out + i * a.ldo + a.col0 + n;
         if (a.nt_out) __builtin_nontemporal_store(r, op);

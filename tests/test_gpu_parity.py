@@ -572,6 +572,35 @@ def test_gd_small_star_join_with_missing_keys_shared_and_unfed_columns(il):
     assert W[8, 0] == 0.0 and W[11, 0] == 0.0                       # columns nobody feeds keep their weight
 
 
+@pytest.mark.parametrize("c_S", [2, 6, 10, 14, 18])
+def test_entity_table_with_8_byte_aligned_rows_read_as_row_pairs(il, c_S):
+    # entity tables whose number of columns is 2 modulo 4 (and whose row count is even) are streamed as pairs of
+    # rows: left multiply with 1..4 operand columns, gradient descent with the fused gradient block (linear and
+    # logistic), several chunks per wavefront, a ragged last chunk, keys missing for some rows
+    rng = datagen.rng_for(7200 + c_S)
+    r_T = 70_002
+    sch = datagen.star_schema(rng, r_T, c_S, [(977, 12, "uniform"), (61, 5, ("zipf", 1.2))])
+    sch.sources[1].row_idx[rng.random(r_T) < 0.05] = -1
+    tg = oracle.Target(sch)
+    plan = il.ilargi_plan_create(il.schema_to_device(sch), sch.r_T, sch.c_T, max_cx=4)
+    for cx in (1, 2, 3, 4):
+        X = rng.standard_normal((sch.c_T, cx)).astype(np.float32)
+        got = il.ilargi_lmm(plan, dev(X)).cpu().numpy()
+        want = oracle.lmm(tg, X)
+        assert rel(got, want) < OP_TOL
+        assert_each_element(got, want, tg.T32, X)
+    w_star = rng.standard_normal(sch.c_T) / np.sqrt(sch.c_T)
+    for model, code in (("linear", il.LINEAR), ("logistic", il.LOGISTIC)):
+        y = datagen.finish_labels(model, oracle.lmm(tg, w_star.reshape(-1, 1)), 0.1 * rng.standard_normal(r_T))
+        lrs = [0.1, 0.3]
+        W, L = _run_gd(il, plan, code, y, lrs, 5, sch.c_T)
+        W_ref, L_ref = oracle.gd(tg, model, y, np.zeros((sch.c_T, 2)), lrs, 5)
+        assert max(rel(W[:, j], W_ref[:, j]) for j in range(2)) < GD_TOL
+        np.testing.assert_allclose(L, L_ref, rtol=1e-4)
+        W2, _ = _run_gd(il, plan, code, y, lrs, 5, sch.c_T)
+        assert np.array_equal(W, W2)
+
+
 def test_gd_without_loss_output(il):
     sch, tg, plan = get(il, "config0")
     y = _labels(sch, tg, "linear")
