@@ -34,7 +34,10 @@ constexpr int kTjWavesPerBlock = kBlock / kWave;
 constexpr int kTjWaveFloats = kTjST * kTjLdy + 2 * kTjST + 32;
 
 // NTR: 16-column tiles of D_k (compile-time bound of the accumulators); VEC4: rows of Y as float4.
-template <int NTR, bool VEC4>
+// DV4 (NTR a multiple of 4, table rows whole aligned float4s): the tiles of a group of 64 columns are interleaved,
+// tile 4 g + t holding the columns 64 g + 4 li + t, so that the values a lane needs of one table row for the four
+// tiles of a group are one float4 (16 lanes read 256 contiguous bytes) instead of four separate floats.
+template <int NTR, bool VEC4, bool DV4>
 __global__ __launch_bounds__(kBlock) void tmm_join_kernel(TmmJoinArgs a, int rtiles) {
   extern __shared__ float lds[];
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
@@ -61,14 +64,27 @@ __global__ __launch_bounds__(kBlock) void tmm_join_kernel(TmmJoinArgs a, int rti
     const int p_end = a.rowptr[min(jb + 16, a.r_k)];
     // this tile of D_k in the A layout of the second product: value r of tile ci is D[jb + 4 q + r][16 ci + li]
     float dv[NTR][4];
+    if constexpr (DV4) {
 #pragma unroll
-    for (int ci = 0; ci < NTR; ++ci)
+      for (int g = 0; g < NTR / 4; ++g)
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int64_t row = jb + 4 * q + r;
-        const int col = 16 * ci + li;
-        dv[ci][r] = (ci < ntr && row < a.r_k && col < a.ck) ? a.D[row * a.ck + col] : 0.0f;
-      }
+        for (int r = 0; r < 4; ++r) {
+          const int64_t row = jb + 4 * q + r;
+          const int col = 64 * g + 4 * li;
+          float4 t = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+          if (row < a.r_k && col < a.ck) t = *reinterpret_cast<const float4*>(a.D + row * a.ck + col);
+          dv[4 * g][r] = t.x; dv[4 * g + 1][r] = t.y; dv[4 * g + 2][r] = t.z; dv[4 * g + 3][r] = t.w;
+        }
+    } else {
+#pragma unroll
+      for (int ci = 0; ci < NTR; ++ci)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int64_t row = jb + 4 * q + r;
+          const int col = 16 * ci + li;
+          dv[ci][r] = (ci < ntr && row < a.r_k && col < a.ck) ? a.D[row * a.ck + col] : 0.0f;
+        }
+    }
     v4f zacc = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
     tj_wave_sync();
     if (lane <= 16) rpS[lane] = a.rowptr[min(jb + lane, a.r_k)];
@@ -137,7 +153,7 @@ __global__ __launch_bounds__(kBlock) void tmm_join_kernel(TmmJoinArgs a, int rti
   }
 
   // the four wavefronts' shares added in wavefront order in LDS; tile ci, register r of lane (li, q) is
-  // G[16 ci + 4 q + r][li]
+  // G[16 ci + 4 q + r][li] (with interleaved tiles: G[64 (ci / 4) + 4 (4 q + r) + ci % 4][li])
   float* red = lds;                                           // [NTR * 16][16]
   for (int w = 0; w < kTjWavesPerBlock; ++w) {
     __syncthreads();
@@ -146,7 +162,8 @@ __global__ __launch_bounds__(kBlock) void tmm_join_kernel(TmmJoinArgs a, int rti
       for (int ci = 0; ci < NTR; ++ci)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          float* p = red + (16 * ci + 4 * q + r) * 16 + li;
+          const int col = DV4 ? 64 * (ci / 4) + 4 * (4 * q + r) + ci % 4 : 16 * ci + 4 * q + r;
+          float* p = red + col * 16 + li;
           if (w == 0) *p = gacc[ci][r];
           else *p += gacc[ci][r];
         }
@@ -162,8 +179,8 @@ __global__ __launch_bounds__(kBlock) void tmm_join_kernel(TmmJoinArgs a, int rti
 
 typedef void (*TjFn)(TmmJoinArgs, int);
 
-template <int NTR>
-TjFn pick_tj(bool vec4) { return vec4 ? tmm_join_kernel<NTR, true> : tmm_join_kernel<NTR, false>; }
+template <int NTR, bool DV4>
+TjFn pick_tj(bool vec4) { return vec4 ? tmm_join_kernel<NTR, true, DV4> : tmm_join_kernel<NTR, false, DV4>; }
 
 }  // namespace
 
@@ -176,13 +193,21 @@ hipError_t launch_tmm_join(const TmmJoinArgs& a, int64_t partial_floats, hipStre
   const int rtiles = (int)((a.r_k + 15) / 16);
   const int ntr = (a.ck + 15) / 16;
   const bool vec4 = a.c % 4 == 0 && a.ldy % 4 == 0 && a.col0 % 4 == 0 && reinterpret_cast<uintptr_t>(a.Y) % 16 == 0;
-  TjFn fn = ntr <= 4 ? pick_tj<4>(vec4) : (ntr <= 8 ? pick_tj<8>(vec4) : pick_tj<13>(vec4));
-  const int ntr_c = ntr <= 4 ? 4 : (ntr <= 8 ? 8 : 13);
+  const bool dv4 = a.ck % 4 == 0 && reinterpret_cast<uintptr_t>(a.D) % 16 == 0;
+  TjFn fn;
+  int ntr_c;
+  if (dv4) {
+    fn = ntr <= 4 ? pick_tj<4, true>(vec4) : (ntr <= 8 ? pick_tj<8, true>(vec4) : pick_tj<16, true>(vec4));
+    ntr_c = ntr <= 4 ? 4 : (ntr <= 8 ? 8 : 16);
+  } else {
+    fn = ntr <= 4 ? pick_tj<4, false>(vec4) : (ntr <= 8 ? pick_tj<8, false>(vec4) : pick_tj<13, false>(vec4));
+    ntr_c = ntr <= 4 ? 4 : (ntr <= 8 ? 8 : 13);
+  }
   size_t lds_floats = std::max<size_t>((size_t)kTjWavesPerBlock * kTjWaveFloats, (size_t)ntr_c * 256);
   const size_t lds_bytes = lds_floats * sizeof(float);
   static std::mutex cache_mutex;
-  static TjFn seen_fn[8];
-  static int seen_slots[8];
+  static TjFn seen_fn[16];
+  static int seen_slots[16];
   static int n_seen = 0;
   int slots = 0;
   {
@@ -198,7 +223,7 @@ hipError_t launch_tmm_join(const TmmJoinArgs& a, int64_t partial_floats, hipStre
           per_cu < 1)
         per_cu = 1;
       slots = per_cu * cus;
-      if (n_seen < 8) { seen_fn[n_seen] = fn; seen_slots[n_seen] = slots; ++n_seen; }
+      if (n_seen < 16) { seen_fn[n_seen] = fn; seen_slots[n_seen] = slots; ++n_seen; }
     }
   }
   int64_t gx = (rtiles + kTjWavesPerBlock - 1) / kTjWavesPerBlock;
