@@ -285,6 +285,39 @@ def run_sweep(il, torch, datagen, dev, path, records=None):
         torch.cuda.empty_cache()
     with open(path, "w") as f:
         json.dump(rows, f, indent=1)
+    if records is not None:
+        held_out_schemas(il, torch, datagen, records)
+
+
+HELD_OUT = [   # (name, r_S, c_S, [(r_R, c_R, keys), ...]): shapes that played no part in setting the byte model's constants
+    ("held-out S 2000000x8 + R 20000x64", 2_000_000, 8, [(20_000, 64, "uniform")]),
+    ("held-out S 500000x40 + R 250000x40", 500_000, 40, [(250_000, 40, "uniform")]),
+    ("held-out S 3000000x4 + R 3000x16 + R 300000x32", 3_000_000, 4, [(3_000, 16, "uniform"), (300_000, 32, "uniform")]),
+    ("held-out S 1000000x64 + R 100000x16", 1_000_000, 64, [(100_000, 16, "uniform")]),
+    ("held-out S 4000000x12 + R 1000000x24", 4_000_000, 12, [(1_000_000, 24, "uniform")]),
+    ("held-out S 800000x16 + R 8000x512 (Zipf keys)", 800_000, 16, [(8_000, 512, ("zipf", 1.1))]),
+]
+
+
+def held_out_schemas(il, torch, datagen, records):
+    """More validation points for ilargi_choose: 200-iteration trainings on schemas outside the benchmark's grid."""
+    for name, r_S, c_S, dims in HELD_OUT:
+        sch = datagen.star_schema(datagen.rng_for(900 + len(records)), r_S, c_S, dims)
+        shp = shapes_of(sch)
+        plan = il.ilargi_plan_create(il.schema_to_device(sch), sch.r_T, sch.c_T, max_cx=1)
+        T = il.ilargi_materialize(plan)
+        t_join = time_loop(torch, lambda: il.ilargi_materialize(plan, T), 3, warm=1)
+        mplan = il.ilargi_plan_create([(T, None, np.arange(sch.c_T, dtype=np.int32))], sch.r_T, sch.c_T, max_cx=1)
+        W = torch.zeros((sch.c_T, 1), device="cuda")
+        y = torch.randn(sch.r_T, device="cuda")
+        lr = torch.full((1,), 0.01, device="cuda")
+        loss = torch.zeros(1, device="cuda")
+        t_f = time_loop(torch, lambda: il.ilargi_gd_step(plan, il.LINEAR, W, y, lr, loss), 20)
+        t_m = time_loop(torch, lambda: il.ilargi_gd_step(mplan, il.LINEAR, W, y, lr, loss), 20)
+        records.append(chooser_record(il, name, shp, sch.r_T, sch.c_T, t_f, t_m, t_join))
+        print(json.dumps(records[-1]), file=sys.stderr, flush=True)
+        del plan, mplan, T
+        torch.cuda.empty_cache()
 
 
 def kernel_model(shp, r_T, c_T):

@@ -17,6 +17,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdint>
+#include <cstring>
 
 #include "ilargi_internal.h"
 
@@ -98,15 +99,39 @@ extern "C" ilargi_status_t ilargi_choose(int n, const ilargi_source_t* sources, 
     }
   }
   b_fact += (vec + 4.0) * rT + 2.0 * vec * cT;             // residual written, labels, weights in and out
+  // a small two-table star join (or a small table alone) runs an iteration of one model as a single launch
+  const auto small_star = [&](int ns, const ilargi_source_t* s, int64_t rows_T) {
+    int live = 0, ident = -1, joined = -1;
+    for (int k = 0; k < ns; ++k) {
+      if (s[k].rows == 0 || s[k].cols == 0) continue;
+      ++live;
+      if (s[k].csr_rowptr != nullptr) return false;
+      if (s[k].row_idx == nullptr && ident < 0) ident = k; else joined = k;
+    }
+    if (ident < 0 || live > 2 || c_T > 1024 || rows_T < 1 || w.models > 4) return false;
+    const int64_t ci = s[ident].cols;
+    if (s[ident].rows != rows_T || ci > 16 || ci % 4 != 0 || rows_T > 1024 * (16 / (ci / 4))) return false;
+    if (live == 2) {
+      const ilargi_source_t& d = s[joined];
+      if (d.row_idx == nullptr || d.cols > 16 || d.cols % 4 != 0 || d.rows > 1024 || rows_T > 16384) return false;
+    }
+    return true;
+  };
+  if (small_star(n, sources, r_T)) launches_fact = 1;
   const bool mat_one_pass = cT <= kFusedMaxCols;
   const double b_mat = (mat_one_pass ? 4.0 : 8.0) * mT + (vec + 4.0) * rT + 2.0 * vec * cT;
-  const double launches_mat = mat_one_pass ? 2.0 : 3.0;
+  ilargi_source_t joined_table;
+  memset(&joined_table, 0, sizeof(joined_table));
+  joined_table.rows = r_T; joined_table.cols = c_T;
+  const double launches_mat = small_star(1, &joined_table, r_T) ? 1.0 : (mat_one_pass ? 2.0 : 3.0);
   const double b_join = 4.0 * mT + join_fetch;
   out->bytes_factorized = b_fact * passes;
   out->bytes_materialized = b_mat * passes;
   out->bytes_join = b_join;
   const double it = (double)w.iterations;
-  out->seconds_factorized = it * passes * (b_fact / bw + launches_fact * launch);
+  // (the single-launch iteration serves one model per launch)
+  const double fact_launches = launches_fact == 1 ? (double)w.models / passes : (double)launches_fact;
+  out->seconds_factorized = it * passes * (b_fact / bw + fact_launches * launch);
   out->seconds_materialized = b_join / bw + launch + it * passes * (b_mat / bw + launches_mat * launch);
   out->factorize = out->seconds_factorized <= out->seconds_materialized ? 1 : 0;
   return ILARGI_OK;

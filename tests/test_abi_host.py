@@ -144,9 +144,13 @@ def test_choose_decision_follows_its_byte_model():
     # the join is paid once: a single iteration never repays it when the per-iteration times are close
     few = il.ilargi_choose(thin, 1_000_000, 50, iterations=1)
     assert few["factorize"] == 1 and few["bytes_join"] > few["bytes_materialized"] * 0.9
-    # tiny tables are decided by launches: five dependent launches against two
+    # tiny tables are decided by launches: a two-table star join with short rows runs an iteration as one launch
+    # against two for its joined table (whose 12-column rows are too many for the single-launch form) ...
     tiny = il.ilargi_choose([(10_000, 4, False), (1_000, 8, True)], 10_000, 12)
-    assert tiny["factorize"] == 0
+    assert tiny["factorize"] == 1
+    # ... while a tiny schema outside that form takes its several dependent launches against two
+    tiny3 = il.ilargi_choose([(10_000, 4, False), (1_000, 8, True), (500, 4, True)], 10_000, 16)
+    assert tiny3["factorize"] == 0
     # a small schema with a wide dimension table moves fewer bytes factorized but needs more launches: the
     # launch price decides
     small = [(10_000, 4, False), (100, 64, True)]
