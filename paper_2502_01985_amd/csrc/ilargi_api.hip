@@ -119,6 +119,7 @@ struct ilargi_plan {
   int npairs = 0;
   bool small_gd = false;  // the schema is small enough for the single-workgroup gradient-descent iteration
   int small_ident = -1, small_joined = -1;   // ... its entity table and its joined table (or -1)
+  bool rowjoin_gd = false;  // fetching every source's row per target row moves fewer bytes than the factorized sequence
   int static_dev = -1;   // >= 0: the workspace is the library's static scratch array of that device
   std::vector<size_t> block_off;  // offset (floats) of Gram block (k,l), k <= l, index k * n + l
   // optional timing of one kernel family: event pairs recorded around every launch whose tag matches
@@ -1122,6 +1123,24 @@ ilargi_status_t plan_create_impl(int n, const ilargi_source_t* sources, int64_t 
     pl->small_gd = ok;
     pl->small_ident = ki; pl->small_joined = live == 2 ? kj : -1;
   }
+  // sources whose rows feed fewer than two target rows on average (union-style integration): a gradient-descent
+  // iteration of one model joins the rows on the fly, reading every table once, when that moves clearly fewer
+  // bytes than the factorized sequence (fused source once, every other source for its product and its column reduce)
+  {
+    int live = 0;
+    bool ok = !pl->any_sparse;
+    double bytes_join = 0.0, bytes_fact = 0.0;
+    for (int k = 0; k < n && ok; ++k) {
+      const SourcePlan& p = pl->src[k];
+      if (p.empty) continue;
+      ++live;
+      ok = live <= kRowJoinSources && p.vec == 4 && p.cols % 4 == 0 && p.cols <= 64 &&
+           reinterpret_cast<uintptr_t>(p.D) % 16 == 0;
+      bytes_join += 4.0 * (double)p.nnz * (double)p.cols;
+      bytes_fact += (k == pl->fused ? 4.0 : 8.0) * (double)p.rows * (double)p.cols + (p.ident ? 0.0 : 24.0 * (double)r_T);
+    }
+    pl->rowjoin_gd = ok && live >= 2 && r_T >= 1 && bytes_join <= 0.85 * bytes_fact;
+  }
   // join-gather tables: groups of four target columns fed by four consecutive columns of one source
   if (c_T % 4 == 0) {
     std::vector<int32_t> gslot((size_t)c_T / 4, -1), gj0((size_t)c_T / 4, 0);
@@ -1408,6 +1427,40 @@ ilargi_status_t ilargi_gd_step(ilargi_plan_t* plan, ilargi_model_t model, float*
       TraceScope ts(plan, "small_gd", -1, st);
       HIP_TRY(launch_small_star(a, model == ILARGI_LINEAR ? 1 : 2, st));
     }
+    return ILARGI_OK;
+  }
+  if (plan->rowjoin_gd && !bf16 && m == 1) {
+    // every table read once: product, residual and every source's block of the gradient in one pass
+    RowJoinArgs a;
+    memset(&a, 0, sizeof(a));
+    FinArgs f;
+    memset(&f, 0, sizeof(f));
+    for (int k = 0; k < plan->n; ++k) {
+      const SourcePlan& p = plan->src[k];
+      if (p.empty) continue;
+      const int s = a.n++;
+      a.D[s] = p.D; a.ck[s] = (int)p.cols; a.rows[s] = p.rows;
+      a.idx[s] = p.ident ? nullptr : p.idx;
+      a.colmap[s] = plan->at<int32_t>(p.o_colmap);
+      a.grad_partial[s] = plan->at<float>(p.o_partial);
+      f.s[s].tcol2src = plan->at<int32_t>(p.o_tcol);
+      f.s[s].partial = plan->at<float>(p.o_partial);
+      f.s[s].ck = (int)p.cols;
+    }
+    a.W = W; a.ldw = (int)m; a.col = 0; a.y = y; a.r_T = plan->r_T;
+    a.loss_partial = plan->at<float>(plan->lay.o_loss);
+    int grid = 0;
+    {
+      TraceScope ts(plan, "gd_rowjoin", -1, st);
+      HIP_TRY(launch_gd_rowjoin(a, model == ILARGI_LINEAR ? 1 : 2, kColredBlocks, st, &grid));
+    }
+    f.n = a.n;
+    for (int s = 0; s < f.n; ++s) f.s[s].nblocks = grid;
+    f.out = W; f.ldo = 1; f.col0 = 0; f.ncols = 1;
+    f.lr = lr; f.inv_rT = 1.0f / (float)plan->r_T;
+    f.loss_partial = a.loss_partial; f.n_loss_partial = grid; f.loss = loss; f.loss_scale = loss_scale;
+    TraceScope ts(plan, "finalize", -1, st);
+    HIP_TRY(launch_finalize(f, (int)plan->c_T, 1, st));
     return ILARGI_OK;
   }
   if (plan->star_k >= 0 && gd_star_supported((int)plan->src[plan->fused].cols, (int)m) &&

@@ -14,6 +14,10 @@
 // fetch (the 4-byte gathers of a one-model pass are priced at 32 bytes each).
 // Launches are priced separately: a dependent launch costs a few microseconds whatever it moves, which decides
 // small schemas.
+// Stacked tables (an identity source that ends before the target table does: union-style integration) are the
+// one case where the shapes say how many target rows a gathered source reaches: at most its own row count.  If
+// fetching those rows once per target row is clearly cheaper than the factorized sequence, an iteration of one
+// model joins the rows on the fly and reads every table once; the same rule as in the plan decides.
 #include <algorithm>
 #include <cmath>
 #include <cstdint>
@@ -118,6 +122,27 @@ extern "C" ilargi_status_t ilargi_choose(int n, const ilargi_source_t* sources, 
     return true;
   };
   if (small_star(n, sources, r_T)) launches_fact = 1;
+  {
+    bool stacked = false, ok = w.models == 1;
+    for (int k = 0; k < n; ++k)
+      if (sources[k].row_idx == nullptr && sources[k].rows > 0 && sources[k].cols > 0 && sources[k].rows < r_T) stacked = true;
+    int live = 0, gathered = 0;
+    double fetch = 0.0, seq = 0.0;
+    for (int k = 0; k < n && ok; ++k) {
+      const double rk = (double)sources[k].rows, ck = (double)sources[k].cols;
+      if (rk == 0.0 || ck == 0.0) continue;
+      ++live;
+      ok = sources[k].csr_rowptr == nullptr && sources[k].cols <= 64 && sources[k].cols % 4 == 0 && live <= ilargi::kRowJoinSources;
+      const bool ident = sources[k].row_idx == nullptr;
+      gathered += ident ? 0 : 1;
+      fetch += 4.0 * (ident ? rk : std::min(rT, rk)) * ck;
+      seq += (k == fused ? 4.0 : 8.0) * rk * ck + (ident ? 0.0 : 24.0 * rT);
+    }
+    if (ok && stacked && live >= 2 && launches_fact != 1 && fetch <= 0.85 * seq) {
+      b_fact = fetch + 4.0 * rT * (double)gathered + 4.0 * rT + 2.0 * vec * cT;
+      launches_fact = 2;
+    }
+  }
   const bool mat_one_pass = cT <= kFusedMaxCols;
   const double b_mat = (mat_one_pass ? 4.0 : 8.0) * mT + (vec + 4.0) * rT + 2.0 * vec * cT;
   ilargi_source_t joined_table;

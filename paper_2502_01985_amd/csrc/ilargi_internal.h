@@ -270,6 +270,23 @@ int small_star_max_rows(int nvs);
 size_t small_star_lds_bytes(const SmallStarArgs& a);
 hipError_t launch_small_star(const SmallStarArgs& a, int mode, hipStream_t st);
 
+// Gradient-descent pass that joins the rows of its sources on the fly in target order (kernels_rowjoin.hip).
+constexpr int kRowJoinSources = 3;
+struct RowJoinArgs {
+  int n;                                    // sources, 1 .. kRowJoinSources
+  const float* D[kRowJoinSources];          // rows[s] x ck[s], 16-byte aligned, ck a multiple of 4, at most 64
+  int ck[kRowJoinSources];
+  int64_t rows[kRowJoinSources];
+  const int32_t* idx[kRowJoinSources];      // r_T row indices (-1: none); NULL: identity on the first rows[s] target rows
+  const int32_t* colmap[kRowJoinSources];   // device int32[ck]
+  const float* W; int ldw, col;             // weight column `col` of the c_T x ldw matrix
+  const float* y; int64_t r_T;
+  float* loss_partial;                      // [gridDim.x][kNarrowCT]
+  float* grad_partial[kRowJoinSources];     // [gridDim.x][ck][kNarrowCT] partials of D_s^T e
+};
+bool gd_rowjoin_supported(const RowJoinArgs& a);
+hipError_t launch_gd_rowjoin(const RowJoinArgs& a, int mode, int max_grid, hipStream_t st, int* grid_out);
+
 // ---- launchers (each enqueues on `st`; returns the HIP error of the launch) ----
 hipError_t launch_check_idx(const int32_t* idx, int64_t r_T, int64_t r_k, int32_t* flags, hipStream_t st);
 hipError_t launch_sort_by_source_row(const int32_t* idx, int64_t r_T, int64_t r_k, int32_t* keys_a,

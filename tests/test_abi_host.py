@@ -164,6 +164,18 @@ def test_choose_decision_follows_its_byte_model():
     # more models in a pass move more operand bytes but the same tables
     m4 = il.ilargi_choose(star, 1_000_000, 820, models=4)
     assert m4["bytes_factorized"] > cs["bytes_factorized"] and m4["factorize"] == 1
+    # stacked tables (the identity source ends before the target does): one model reads every table once per
+    # iteration, which is fewer bytes than the joined table with its shared columns stored once per row ...
+    union = [(2_000_000, 64, False), (2_000_000, 64, True)]
+    u1 = il.ilargi_choose(union, 3_400_000, 96)
+    assert u1["factorize"] == 1 and u1["bytes_factorized"] == pytest.approx(4.0 * 2 * 2_000_000 * 64, rel=0.05)
+    assert u1["bytes_factorized"] < 0.85 * u1["bytes_materialized"]
+    # ... while two models at once go through the factorized sequence, which reads the second table twice
+    u2 = il.ilargi_choose(union, 3_400_000, 96, models=2)
+    assert u2["bytes_factorized"] > 1.4 * u1["bytes_factorized"] and u2["factorize"] == 0
+    # rows wider than the on-the-fly join takes: the sequence again
+    u3 = il.ilargi_choose([(2_000_000, 128, False), (2_000_000, 128, True)], 3_400_000, 192)
+    assert u3["bytes_factorized"] > 1.4 * 4.0 * 2 * 2_000_000 * 128
 
 
 def test_choose_rejects_bad_arguments():

@@ -601,6 +601,76 @@ def test_entity_table_with_8_byte_aligned_rows_read_as_row_pairs(il, c_S):
         assert np.array_equal(W, W2)
 
 
+def _traced_kernels(il, plan, call):
+    il.ilargi_plan_trace_begin(plan, "*", 64)
+    call()
+    _, names = il.ilargi_plan_trace_end(plan, 64, names=True)
+    return names
+
+
+@pytest.mark.parametrize("model", ["linear", "logistic"])
+@pytest.mark.parametrize("rows,cols,shared,overlap", [(20_011, 64, 32, 0.3), (70_001, 36, 4, 0.5), (2_000, 8, 8, 1.0),
+                                                      (50_000, 4, 0, 0.0)])
+def test_gd_union_of_two_sources_joined_on_the_fly(il, model, rows, cols, shared, overlap):
+    # union-style integration (every table row lands on one target row): one model trains in a single pass that
+    # reads every table once.  Row lengths of 1 .. 16 float4, shared columns, all / some / no entities matched,
+    # several steps per wavefront and a ragged last step.
+    sch = datagen.config3(seed=7300 + cols, rows=rows, cols=cols, shared=shared, overlap=overlap)
+    tg = oracle.Target(sch)
+    rng = datagen.rng_for(7301 + cols)
+    w_star = rng.standard_normal(sch.c_T) / np.sqrt(sch.c_T)
+    y = datagen.finish_labels(model, oracle.lmm(tg, w_star.reshape(-1, 1)), 0.1 * rng.standard_normal(sch.r_T))
+    plan = il.ilargi_plan_create(il.schema_to_device(sch), sch.r_T, sch.c_T, max_cx=2)
+    code = il.LINEAR if model == "linear" else il.LOGISTIC
+    W, L = _run_gd(il, plan, code, y, [0.2], 6, sch.c_T)
+    W_ref, L_ref = oracle.gd(tg, model, y, np.zeros((sch.c_T, 1)), [0.2], 6)
+    assert rel(W, W_ref) < GD_TOL
+    np.testing.assert_allclose(L, L_ref, rtol=1e-4)
+    W2, L2 = _run_gd(il, plan, code, y, [0.2], 6, sch.c_T)
+    assert np.array_equal(W, W2) and np.array_equal(L, L2)
+    Wd = torch.zeros((sch.c_T, 1), device="cuda")
+    names = _traced_kernels(il, plan, lambda: il.ilargi_gd_step(plan, code, Wd, dev(y), dev(np.array([0.2], dtype=np.float32)),
+                                                                 torch.zeros(1, device="cuda")))
+    assert any(n.startswith("gd_rowjoin") for n in names), names
+    # two models at once take the general path and agree with it
+    W3, _ = _run_gd(il, plan, code, y, [0.2, 0.2], 6, sch.c_T)
+    assert rel(W3[:, 0], W_ref[:, 0]) < GD_TOL and rel(W3[:, 1], W_ref[:, 0]) < GD_TOL
+
+
+def test_gd_union_of_three_sources_with_missing_rows_and_dropped_columns(il):
+    # three tables side by side, none of them an identity source: permuted keys, target rows that some tables do
+    # not reach, a table column that feeds no target column, a target column fed by two tables, one fed by nobody
+    rng = datagen.rng_for(7400)
+    r_T = 40_007
+    sources = []
+    widths = (12, 64, 20)
+    col0 = (0, 10, 74)                                   # columns 10, 11 are shared by the first two tables
+    for k, ck in enumerate(widths):
+        r_k = r_T - 1000 * k
+        D = rng.standard_normal((r_k, ck)).astype(np.float32)
+        idx = np.full(r_T, -1, dtype=np.int32)
+        where = rng.permutation(r_T)[:r_k - 500]         # 500 rows of every table stay unused
+        idx[where] = rng.permutation(r_k)[:r_k - 500].astype(np.int32)
+        cm = np.arange(col0[k], col0[k] + ck, dtype=np.int32)
+        if k == 2:
+            cm[3] = -1
+        sources.append(datagen.Source(D, idx, cm))
+    c_T = 96                                             # columns 94, 95 fed by nobody
+    sch = datagen.Schema(sources, r_T, c_T)
+    tg = oracle.Target(sch)
+    y = rng.standard_normal(r_T).astype(np.float32)
+    plan = il.ilargi_plan_create(il.schema_to_device(sch), sch.r_T, sch.c_T, max_cx=1)
+    W, L = _run_gd(il, plan, il.LINEAR, y, [0.1], 5, sch.c_T)
+    W_ref, L_ref = oracle.gd(tg, "linear", y, np.zeros((sch.c_T, 1)), [0.1], 5)
+    assert rel(W, W_ref) < GD_TOL
+    np.testing.assert_allclose(L, L_ref, rtol=1e-4)
+    assert W[94, 0] == 0.0 and W[95, 0] == 0.0 and W[77, 0] == 0.0
+    Wd = torch.zeros((sch.c_T, 1), device="cuda")
+    names = _traced_kernels(il, plan, lambda: il.ilargi_gd_step(plan, il.LINEAR, Wd, dev(y), dev(np.array([0.1], dtype=np.float32)),
+                                                                 torch.zeros(1, device="cuda")))
+    assert any(n.startswith("gd_rowjoin") for n in names), names
+
+
 def test_gd_without_loss_output(il):
     sch, tg, plan = get(il, "config0")
     y = _labels(sch, tg, "linear")
