@@ -43,20 +43,6 @@ __global__ __launch_bounds__(kBlock) void lmm_flat_kernel(LmmArgs a, int wave_fl
   float* wbase = lds + 4 * NVT * CT + (size_t)wave * wave_floats;
   float* Pd = wbase;                                           // [CT][64 * ldp] partial dot products
   float* Es = Pd + CT * kWave * ldp;                           // [CT][64] residuals by row (FUSEG)
-  for (int e = tid; e < nvec * CT; e += kBlock) {
-    const int part = e / CT, n = e - part * CT;
-    float4 x = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-    if (n < a.ncols) {
-      const int t0 = a.colmap[4 * part], t1 = a.colmap[4 * part + 1], t2 = a.colmap[4 * part + 2], t3 = a.colmap[4 * part + 3];
-      if (t0 >= 0) x.x = a.X[(int64_t)t0 * a.ldx + a.col0 + n];
-      if (t1 >= 0) x.y = a.X[(int64_t)t1 * a.ldx + a.col0 + n];
-      if (t2 >= 0) x.z = a.X[(int64_t)t2 * a.ldx + a.col0 + n];
-      if (t3 >= 0) x.w = a.X[(int64_t)t3 * a.ldx + a.col0 + n];
-    }
-    Xs4[e] = x;
-  }
-  __syncthreads();
-
   // float4 number 64 u + lane of a chunk: its row, its part of the row, its place in the partial-dot tile
   int row_u[NVT], part_u[NVT];
 #pragma unroll
@@ -111,6 +97,20 @@ __global__ __launch_bounds__(kBlock) void lmm_flat_kernel(LmmArgs a, int wave_fl
     }
   };
   load_chunk(chunk, vn);
+  // the operand is staged while the first chunk and its row indices travel
+  for (int e = tid; e < nvec * CT; e += kBlock) {
+    const int part = e / CT, n = e - part * CT;
+    float4 x = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    if (n < a.ncols) {
+      const int t0 = a.colmap[4 * part], t1 = a.colmap[4 * part + 1], t2 = a.colmap[4 * part + 2], t3 = a.colmap[4 * part + 3];
+      if (t0 >= 0) x.x = a.X[(int64_t)t0 * a.ldx + a.col0 + n];
+      if (t1 >= 0) x.y = a.X[(int64_t)t1 * a.ldx + a.col0 + n];
+      if (t2 >= 0) x.z = a.X[(int64_t)t2 * a.ldx + a.col0 + n];
+      if (t3 >= 0) x.w = a.X[(int64_t)t3 * a.ldx + a.col0 + n];
+    }
+    Xs4[e] = x;
+  }
+  __syncthreads();
   for (; chunk < nchunks; chunk += cstride) {
     const int64_t row0 = chunk * kWave;
     const int64_t i = row0 + lane;

@@ -46,13 +46,6 @@ __global__ __launch_bounds__(kBlock) void lmm_flat_wide_kernel(LmmArgs a, int st
   float* Xs = lds;                                             // [ck][16]
   float* Ss = lds + (size_t)4 * NVT * kFwN + (size_t)wave * wave_floats;   // [64][stride] this wavefront's rows
   int* Is = reinterpret_cast<int*>(Ss + kWave * stride);       // [kFwGather][64] row indices of the step
-  for (int e = tid; e < a.ck * kFwN; e += kBlock) {
-    const int j = e / kFwN, n = e - j * kFwN;
-    const int t = a.colmap[j];
-    Xs[e] = (t >= 0 && n < a.ncols) ? a.X[(int64_t)t * a.ldx + a.col0 + n] : 0.0f;
-  }
-  __syncthreads();
-
   const int g4 = lane % 4, rl = lane / 4;                      // output columns 4 g4 .., rows rl + 16 q
   const bool col_live = 4 * g4 < a.ncols;
   const int64_t nchunks = (a.r_out + kWave - 1) / kWave;
@@ -77,8 +70,30 @@ __global__ __launch_bounds__(kBlock) void lmm_flat_wide_kernel(LmmArgs a, int st
     for (int s = 0; s < kFwGather; ++s)
       jn[s] = (s < a.g.n && ch < nchunks && i < a.r_out) ? (int)fw_gather_row(a.g, s, i) : -1;
   };
+  // the first step's rows and indices are requested before anything else, so that they travel while the operand
+  // is staged: column-map entries first, then the operand values they name (two round trips for all of a thread's
+  // elements together)
   load_chunk(chunk, vn);
   load_idx(chunk);
+  {
+    constexpr int U = (4 * NVT * kFwN + kBlock - 1) / kBlock;
+    int tc[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int j = (tid + u * kBlock) / kFwN;
+      tc[u] = j < a.ck ? a.colmap[j] : -1;
+    }
+    float xv[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int n = (tid + u * kBlock) % kFwN;
+      xv[u] = (tc[u] >= 0 && n < a.ncols) ? a.X[(int64_t)tc[u] * a.ldx + a.col0 + n] : 0.0f;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (tid + u * kBlock < a.ck * kFwN) Xs[tid + u * kBlock] = xv[u];
+  }
+  __syncthreads();
   for (; chunk < nchunks; chunk += cstride) {
     const int64_t row0 = chunk * kWave;
 #pragma unroll

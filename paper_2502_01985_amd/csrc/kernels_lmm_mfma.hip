@@ -528,96 +528,6 @@ __global__ __launch_bounds__(kBlock) void lmm_gemm_kernel(LmmArgs a, MfmaShape s
   }
 }
 
-// Plain product  P = D (M^T X)  for an operand of at most 16 columns and a table that fits one K chunk
-// (float4-aligned rows): the role of the kernel above without gathers, epilogue modes or gradient, with the
-// next block of rows fetched into registers while the matrix cores work on the current one.  A workgroup that
-// walks several row blocks then pays the memory latency once instead of once per block.
-constexpr int kProdSlots = 16;   // float4 staging slots per thread: rb * (kp / 4) <= 16 * 256
-
-__global__ __launch_bounds__(kBlock) void lmm_prod_kernel(LmmArgs a, MfmaShape sh) {
-  extern __shared__ float lds[];
-  float* As = lds;                                   // [rb][lda]
-  float* Xs = lds + (size_t)sh.rb * sh.lda;          // [kp / 4][16][4]
-  const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
-  const int li = lane % 16, q = lane / 16;
-  const int n0 = a.col0;
-  const int nw = a.ncols;                            // <= 16
-  const int tpr = sh.kp / 4;                         // float4 slots per staged row
-  const int live4 = a.ck / 4;
-  const int nslots = sh.rb * tpr;
-  const int64_t nblocks = (a.r_out + sh.rb - 1) / sh.rb;
-  float4 v[kProdSlots];
-  auto fetch = [&](int64_t row0) {
-#pragma unroll
-    for (int u = 0; u < kProdSlots; ++u) {
-      const int e = tid + u * kBlock;
-      const int r = e / tpr, g = e - r * tpr;
-      v[u] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-      if (e < nslots && g < live4 && row0 + r < a.d_rows)
-        v[u] = *reinterpret_cast<const float4*>(a.D + (row0 + r) * a.ck + 4 * g);
-    }
-  };
-  if ((int64_t)blockIdx.x < nblocks) fetch((int64_t)blockIdx.x * sh.rb);
-  {
-    // operand rows selected by the column map, as [k / 4][n][k % 4]: element e = 16 k + n; all column-map
-    // loads of a thread first, then all operand loads (two memory round trips, under the first fetch)
-    int tc[kProdSlots];
-#pragma unroll
-    for (int u = 0; u < kProdSlots; ++u) {
-      const int k = (tid + u * kBlock) / 16;
-      tc[u] = k < a.ck ? a.colmap[k] : -1;
-    }
-    float xv[kProdSlots];
-#pragma unroll
-    for (int u = 0; u < kProdSlots; ++u) {
-      const int n = (tid + u * kBlock) % 16;
-      xv[u] = (tc[u] >= 0 && n < nw) ? a.X[(int64_t)tc[u] * a.ldx + n0 + n] : 0.0f;
-    }
-#pragma unroll
-    for (int u = 0; u < kProdSlots; ++u) {
-      const int e = tid + u * kBlock;
-      const int k = e / 16, n = e % 16;
-      if (k < sh.kp) Xs[((k >> 2) * 16 + n) * 4 + (k & 3)] = xv[u];
-    }
-  }
-  for (int64_t blk = blockIdx.x; blk < nblocks; blk += gridDim.x) {
-    const int64_t row0 = blk * sh.rb;
-    __syncthreads();                                 // the previous rows are consumed (and Xs is written)
-#pragma unroll
-    for (int u = 0; u < kProdSlots; ++u) {
-      const int e = tid + u * kBlock;
-      const int r = e / tpr, g = e - r * tpr;
-      if (e < nslots) *reinterpret_cast<float4*>(As + (size_t)r * sh.lda + 4 * g) = v[u];
-    }
-    __syncthreads();
-    if (blk + gridDim.x < nblocks) fetch((blk + gridDim.x) * sh.rb);
-    for (int mt = wave; mt < sh.rb / 16; mt += kBlock / kWave) {
-      v4f acc = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
-      const float* arow = As + (size_t)(mt * 16 + li) * sh.lda + 4 * q;
-      for (int step = 0; step < sh.kp / 16; ++step) {
-        const float4 av = *reinterpret_cast<const float4*>(arow + 16 * step);
-        const float4 bv = *reinterpret_cast<const float4*>(Xs + ((size_t)(4 * step + q) * 16 + li) * 4);
-        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av.x, bv.x, acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av.y, bv.y, acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av.z, bv.z, acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av.w, bv.w, acc, 0, 0, 0);
-      }
-      // rows 4 q + r of the tile, operand column li
-      if (li < nw) {
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const int64_t row = row0 + mt * 16 + 4 * q + r;
-          if (row < a.r_out) {
-            float* op = a.out + row * a.ldo + n0 + li;
-            if (a.nt_out) __builtin_nontemporal_store(acc[r], op);
-            else *op = acc[r];
-          }
-        }
-      }
-    }
-  }
-}
-
 }  // namespace
 
 // Shape decisions shared with the caller: K padding, K chunking, rows per block, LDS bytes.
@@ -706,8 +616,8 @@ hipError_t launch_lmm_mfma(const LmmArgs& a, int vec, int mode, bool bf16, hipSt
   const bool vec4 = vec == 4;
   const bool sb16 = vec4 && (int64_t)sh.rb * (sh.kc / 4) > 8 * kBlock;
   MfmaFn fn;
-  const bool plain_product = mode == 0 && !bf16 && a.g.n == 0 && a.D != nullptr && a.grad_partial == nullptr && nt == 1 &&
-                             vec4 && sh.kp == sh.kc && (int64_t)sh.rb * (sh.kp / 4) <= (int64_t)kProdSlots * kBlock;
+  // plain product with at most 16 result columns (no gathers, no epilogue): the streaming kernel
+  if (!bf16 && nt == 1 && lmm_prod_stream_supported(a, vec, mode)) return launch_lmm_prod_stream(a, st);
   // wide plain product (no gathers, no epilogue): the chunked, double-buffered kernel
   if (mode == 0 && !bf16 && a.g.n == 0 && a.D != nullptr && a.grad_partial == nullptr && nt == 4 && vec4) {
     const size_t lds_bytes = (size_t)2 * kGemmStage * sizeof(float);
@@ -722,9 +632,7 @@ hipError_t launch_lmm_mfma(const LmmArgs& a, int vec, int mode, bool bf16, hipSt
       return hipGetLastError();
     }
   }
-  if (plain_product) {
-    fn = lmm_prod_kernel;
-  } else if (a.grad_partial != nullptr) {
+  if (a.grad_partial != nullptr) {
     if (mode == 0 || a.D == nullptr || !lmm_mfma_can_fuse_gradient(a.ck, a.ncols, bf16)) return hipErrorInvalidValue;
     const int jg = sh.kp <= 32 ? 2 : 4;
     sh.lds_bytes = std::max(sh.lds_bytes, (size_t)jg * 16 * 64 * sizeof(float));   // the wavefronts' sum
