@@ -71,6 +71,16 @@ def bytes_gd(shapes, r_T, c_T):
             + 16 * sum(r for r, _ in ni) + 8 * c_T)
 
 
+def bytes_gd_rows_joined(schema):
+    """One model's iteration that fetches every source's row per target row and uses it twice (stacked tables):
+    every reached table row once, row indices, labels, weights in and out."""
+    b = 0
+    for s in schema.sources:
+        reached = s.rows if _is_identity(s) else int(np.count_nonzero(s.row_idx >= 0))
+        b += 4 * reached * s.cols + (0 if _is_identity(s) else 4 * schema.r_T)
+    return b + 4 * schema.r_T + 8 * schema.c_T
+
+
 def bytes_materialize(shapes, r_T, c_T):
     ni = sum(1 for _, _, has in shapes if has)
     return bytes_tables(shapes) + 4 * r_T * ni + 4 * r_T * c_T
@@ -569,8 +579,12 @@ def other_configs(il, torch, datagen, records=None):
             eager = {"gd_factorized_it_per_s": round(1.0 / t_f, 1), "gd_materialized_it_per_s": round(1.0 / t_m, 1)}
             t_f = graph_time(torch, lambda: il.ilargi_gd_step(plan, model, W, y, lr, loss), 50)
             t_m = graph_time(torch, lambda: il.ilargi_gd_step(mplan, model, W, y, lr, loss), 50)
-        b = bytes_gd(shp, sch.r_T, sch.c_T)
-        out[name] = {"model": mname, "r_T": sch.r_T, "c_T": sch.c_T, "sources": len(sch.sources),
+        il.ilargi_plan_trace_begin(plan, "*", 64)
+        il.ilargi_gd_step(plan, model, W, y, lr, loss)
+        _, launched = il.ilargi_plan_trace_end(plan, 64, names=True)
+        joined = any(k.startswith("gd_rowjoin") for k in launched)
+        b = bytes_gd_rows_joined(sch) if joined else bytes_gd(shp, sch.r_T, sch.c_T)
+        out[name] = {"model": mname, "launches": launched, "gd_factorized_MB": round(b / 1e6, 1), "r_T": sch.r_T, "c_T": sch.c_T, "sources": len(sch.sources),
                      "gd_factorized_it_per_s": round(1.0 / t_f, 1), "gd_materialized_it_per_s": round(1.0 / t_m, 1),
                      "speedup": round(t_m / t_f, 3), "gd_factorized_GBps": round(b / t_f / 1e9, 1),
                      "materialize_once_us": round(t_mat_once * 1e6, 1), "plan_build_ms": round(plan_ms, 1),

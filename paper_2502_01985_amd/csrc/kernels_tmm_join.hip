@@ -31,7 +31,7 @@ __device__ __forceinline__ void tj_wave_sync() {
 constexpr int kTjST = 64;            // target rows a wavefront stages at a time
 constexpr int kTjLdy = 20;           // LDS row stride of the staged rows of Y
 constexpr int kTjWavesPerBlock = kBlock / kWave;
-constexpr int kTjWaveFloats = kTjST * kTjLdy + 2 * kTjST + 32;
+constexpr int kTjWaveFloats = kTjST * kTjLdy + 2 * kTjST + 64;
 
 // NTR: 16-column tiles of D_k (compile-time bound of the accumulators); VEC4: rows of Y as float4.
 // DV4 (NTR a multiple of 4, table rows whole aligned float4s): the tiles of a group of 64 columns are interleaved,
@@ -47,6 +47,7 @@ __global__ __launch_bounds__(kBlock) void tmm_join_kernel(TmmJoinArgs a, int rti
   int* iS = reinterpret_cast<int*>(Ys + kTjST * kTjLdy);      // [ST] target row of each staged row
   int* jS = iS + kTjST;                                       // [ST] row of the tile it joins (-1: none)
   int* rpS = jS + kTjST;                                      // [17] row pointers of the tile
+  int* rpN = rpS + 32;                                        // [17] ... of the wavefront's next tile
 
   v4f gacc[NTR];                                              // G_k tiles: columns 16 ci .. of D_k x operand columns
 #pragma unroll
@@ -58,10 +59,51 @@ __global__ __launch_bounds__(kBlock) void tmm_join_kernel(TmmJoinArgs a, int rti
   const int glive = VEC4 ? a.c / 4 : a.c;
   const int ntr = (a.ck + 15) / 16;
 
-  for (int rt = blockIdx.x * kTjWavesPerBlock + wave; rt < rtiles; rt += gridDim.x * kTjWavesPerBlock) {
+  // A wavefront walks its tiles with the memory chain of the next tile already under way: the row pointers of a
+  // tile are requested two tiles ahead, the target rows of its first two batches one tile ahead, and the rows of Y
+  // of its first batch while the last batch of the tile before it is on the matrix cores.
+  const int tstride = gridDim.x * kTjWavesPerBlock;
+  int rt = blockIdx.x * kTjWavesPerBlock + wave;
+  // lane l <= 16 holds row pointer l of a tile (0 for a tile beyond the table: an empty range)
+  auto load_rp = [&](int t) -> int {
+    return (t < rtiles && lane <= 16) ? a.rowptr[min((int64_t)t * 16 + lane, a.r_k)] : 0;
+  };
+  int rp_cur = load_rp(rt), rp_n1 = load_rp(rt + tstride);
+  int pb = __builtin_amdgcn_readlane(rp_cur, 0), pe = __builtin_amdgcn_readlane(rp_cur, 16);
+  int pi = (lane < kTjST && pb + lane < pe) ? a.perm[pb + lane] : -1;
+  int pi_next = (lane < kTjST && pb + kTjST + lane < pe) ? a.perm[pb + kTjST + lane] : -1;
+  int jl = -1;
+  bool have_sv = false;                                       // the first batch of the tile is already in sv / jl
+  SVal sv[NV];
+  auto load_rows = [&](int cnt_rows) {
+#pragma unroll
+    for (int u = 0; u < NV; ++u) {
+      const int e = lane + u * kWave;
+      const int r = e / gslots, g = e - r * gslots;
+      if constexpr (VEC4) sv[u] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+      else sv[u] = 0.0f;
+      if (r < cnt_rows && g < glive) {
+        const int64_t row = iS[r];
+        if constexpr (VEC4) sv[u] = *reinterpret_cast<const float4*>(a.Y + row * a.ldy + a.col0 + 4 * g);
+        else sv[u] = a.Y[row * a.ldy + a.col0 + g];
+      }
+    }
+  };
+  // row of the tile an entry joins, from the tile's 17 row pointers in LDS (the entries of a row are consecutive)
+  auto joined = [&](const int* rp, int p) {
+    int j = 0;
+#pragma unroll
+    for (int k = 1; k < 16; ++k) j += p >= rp[k] ? 1 : 0;
+    return j;
+  };
+  for (; rt < rtiles; rt += tstride) {
     const int64_t jb = (int64_t)rt * 16;
-    const int p_begin = a.rowptr[jb];
-    const int p_end = a.rowptr[min(jb + 16, a.r_k)];
+    const int p_begin = pb, p_end = pe;
+    // the tile after this one: its range and the target rows of its first two batches; row pointers of the one after
+    const int rp_n2 = load_rp(rt + 2 * tstride);
+    const int nb = __builtin_amdgcn_readlane(rp_n1, 0), ne = __builtin_amdgcn_readlane(rp_n1, 16);
+    const int npi = (lane < kTjST && nb + lane < ne) ? a.perm[nb + lane] : -1;
+    const int npi_next = (lane < kTjST && nb + kTjST + lane < ne) ? a.perm[nb + kTjST + lane] : -1;
     // this tile of D_k in the A layout of the second product: value r of tile ci is D[jb + 4 q + r][16 ci + li]
     float dv[NTR][4];
     if constexpr (DV4) {
@@ -86,42 +128,20 @@ __global__ __launch_bounds__(kBlock) void tmm_join_kernel(TmmJoinArgs a, int rti
         }
     }
     v4f zacc = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
-    tj_wave_sync();
-    if (lane <= 16) rpS[lane] = a.rowptr[min(jb + lane, a.r_k)];
-    tj_wave_sync();
-    auto joined = [&](int p) {                                // the entries of a row are consecutive
-      int j = 0;
-#pragma unroll
-      for (int k = 1; k < 16; ++k) j += p >= rpS[k] ? 1 : 0;
-      return j;
-    };
-    int pi = (lane < kTjST && p_begin + lane < p_end) ? a.perm[p_begin + lane] : -1;
-    int pi_next = (lane < kTjST && p_begin + kTjST + lane < p_end) ? a.perm[p_begin + kTjST + lane] : -1;
-    int jl = pi >= 0 ? joined(p_begin + lane) : -1;
     tj_wave_sync();                                           // the previous tile's batches are consumed
-    if (lane < kTjST) iS[lane] = pi;
+    if (lane <= 16) { rpS[lane] = rp_cur; rpN[lane] = rp_n1; }
+    if (!have_sv && lane < kTjST) iS[lane] = pi;
     tj_wave_sync();
-    SVal sv[NV];
-    auto load_rows = [&](int cnt_rows) {
-#pragma unroll
-      for (int u = 0; u < NV; ++u) {
-        const int e = lane + u * kWave;
-        const int r = e / gslots, g = e - r * gslots;
-        if constexpr (VEC4) sv[u] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-        else sv[u] = 0.0f;
-        if (r < cnt_rows && g < glive) {
-          const int64_t row = iS[r];
-          if constexpr (VEC4) sv[u] = *reinterpret_cast<const float4*>(a.Y + row * a.ldy + a.col0 + 4 * g);
-          else sv[u] = a.Y[row * a.ldy + a.col0 + g];
-        }
-      }
-    };
-    load_rows(min(kTjST, p_end - p_begin));
+    if (!have_sv) {
+      jl = pi >= 0 ? joined(rpS, p_begin + lane) : -1;
+      load_rows(min(kTjST, p_end - p_begin));
+    }
     for (int p0 = p_begin; p0 < p_end; p0 += kTjST) {
       const int cnt = min(kTjST, p_end - p0);
-      const int cnt_next = max(0, min(kTjST, p_end - p0 - kTjST));
+      const bool last = p0 + kTjST >= p_end;                  // then the next tile's first batch follows
+      const int cnt_next = last ? min(kTjST, ne - nb) : min(kTjST, p_end - p0 - kTjST);
       tj_wave_sync();                                         // the previous batch is consumed
-      if (lane < kTjST) { jS[lane] = jl; iS[lane] = pi_next; }
+      if (lane < kTjST) { jS[lane] = jl; iS[lane] = last ? npi : pi_next; }
 #pragma unroll
       for (int u = 0; u < NV; ++u) {
         const int e = lane + u * kWave;
@@ -130,9 +150,15 @@ __global__ __launch_bounds__(kBlock) void tmm_join_kernel(TmmJoinArgs a, int rti
         else Ys[r * kTjLdy + g] = sv[u];
       }
       tj_wave_sync();
-      pi = pi_next;
-      pi_next = (lane < kTjST && p0 + 2 * kTjST + lane < p_end) ? a.perm[p0 + 2 * kTjST + lane] : -1;
-      jl = pi >= 0 ? joined(p0 + kTjST + lane) : -1;
+      if (!last) {
+        pi = pi_next;
+        pi_next = (lane < kTjST && p0 + 2 * kTjST + lane < p_end) ? a.perm[p0 + 2 * kTjST + lane] : -1;
+        jl = pi >= 0 ? joined(rpS, p0 + kTjST + lane) : -1;
+      } else {
+        pi = npi;
+        pi_next = npi_next;
+        jl = pi >= 0 ? joined(rpN, nb + lane) : -1;
+      }
       load_rows(cnt_next);
       for (int t = 0; 16 * t < cnt; ++t) {
 #pragma unroll
@@ -144,6 +170,14 @@ __global__ __launch_bounds__(kBlock) void tmm_join_kernel(TmmJoinArgs a, int rti
         }
       }
     }
+    if (p_end > p_begin) {
+      have_sv = true;                                         // the last batch fetched the next tile's first one
+    } else {
+      have_sv = false;
+      pi = npi;
+      pi_next = npi_next;
+    }
+    rp_cur = rp_n1; rp_n1 = rp_n2; pb = nb; pe = ne;
     // G_k += D_tile^T Z_tile
 #pragma unroll
     for (int ci = 0; ci < NTR; ++ci)
