@@ -128,8 +128,16 @@ struct ilargi_plan {
   std::vector<hipEvent_t> trace_events;
   std::vector<std::string> trace_names;
   int trace_n = 0;
+  // a second stream for independent blocks of one call (crossprod); NULL: everything runs on the caller's stream
+  hipStream_t side = nullptr;
+  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
   template <class T> T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
-  ~ilargi_plan() { for (hipEvent_t e : trace_events) (void)hipEventDestroy(e); }
+  ~ilargi_plan() {
+    for (hipEvent_t e : trace_events) (void)hipEventDestroy(e);
+    if (ev_fork) (void)hipEventDestroy(ev_fork);
+    if (ev_join) (void)hipEventDestroy(ev_join);
+    if (side) (void)hipStreamDestroy(side);
+  }
 };
 
 namespace {
@@ -596,21 +604,23 @@ ilargi_status_t tmm_pass(ilargi_plan* pl, const float* Y, int ldy, int col0, int
 
 // Runs the matrix-core transposed reduction in row chunks and adds the chunk results in order.
 // transposed: block receives the cb x ca transpose of the product.
+// part / part_floats: the partial-block space of this call (default: all of the plan's).
 ilargi_status_t run_tred(ilargi_plan* pl, TredArgs& g, float* block, const char* tag, int tag_k, bool bf16,
-                         hipStream_t st, bool transposed = false) {
+                         hipStream_t st, bool transposed = false, float* part = nullptr, int64_t part_floats = 0) {
   int64_t elems = (int64_t)g.ca * g.cb;
   if (elems <= 0) return ILARGI_OK;
-  if (!bf16 && gram_sym_supported(g) && elems <= pl->lay.gpartial_floats) {
+  if (part == nullptr) { part = pl->at<float>(pl->lay.o_gpartial); part_floats = pl->lay.gpartial_floats; }
+  if (!bf16 && gram_sym_supported(g) && elems <= part_floats) {
     // diagonal Gram block of a table with 65..208 columns: upper-triangle tiles only
     TraceScope ts(pl, tag, tag_k, st);
-    HIP_TRY(launch_gram_sym(g, pl->at<float>(pl->lay.o_gpartial), pl->lay.gpartial_floats, block, st));
+    HIP_TRY(launch_gram_sym(g, part, part_floats, block, st));
     return ILARGI_OK;
   }
   // row chunks: whole rounds of the device's workgroup slots (every workgroup does the same work, so a
   // partly filled last round would idle most compute units), within the partial buffer, >= 64 rows each
   int slots = 512, tiles = 1;
   tred_occupancy(g, bf16, &slots, &tiles);
-  int64_t cap = std::max<int64_t>(1, pl->lay.gpartial_floats / elems);
+  int64_t cap = std::max<int64_t>(1, part_floats / elems);
   cap = std::min<int64_t>(cap, std::max<int64_t>(1, g.n_rows / 64));
   cap = std::min<int64_t>(cap, 4096);
   int64_t nch = std::max<int64_t>(1, slots / tiles);
@@ -619,7 +629,7 @@ ilargi_status_t run_tred(ilargi_plan* pl, TredArgs& g, float* block, const char*
   g.rows_per_block = (g.n_rows + nch - 1) / nch;
   g.rows_per_block = std::max<int64_t>(16, (g.rows_per_block + 15) / 16 * 16);
   nch = std::max<int64_t>(1, (g.n_rows + g.rows_per_block - 1) / g.rows_per_block);
-  g.partial = pl->at<float>(pl->lay.o_gpartial);
+  g.partial = part;
   {
     TraceScope ts(pl, tag, tag_k, st);
     HIP_TRY(launch_tred(g, (int)nch, bf16, st));
@@ -1214,6 +1224,19 @@ ilargi_status_t plan_create_impl(int n, const ilargi_source_t* sources, int64_t 
     HIP_TRY(hipMemcpyAsync(pl->at<GramAsmPair>(lay.o_pairs), pairs.data(), sizeof(GramAsmPair) * pairs.size(), hipMemcpyHostToDevice, st));
   HIP_TRY(hipStreamSynchronize(st));
   pl->static_dev = static_dev;
+  if (static_dev < 0) {
+    // (a plan on the static scratch array is for callers that must not allocate: it creates no stream either)
+    if (hipStreamCreateWithFlags(&pl->side, hipStreamNonBlocking) != hipSuccess) pl->side = nullptr;
+    if (pl->side != nullptr &&
+        (hipEventCreateWithFlags(&pl->ev_fork, hipEventDisableTiming) != hipSuccess ||
+         hipEventCreateWithFlags(&pl->ev_join, hipEventDisableTiming) != hipSuccess)) {
+      if (pl->ev_fork) (void)hipEventDestroy(pl->ev_fork);
+      pl->ev_fork = nullptr;
+      (void)hipStreamDestroy(pl->side);
+      pl->side = nullptr;
+    }
+    (void)hipGetLastError();
+  }
   guard.p = nullptr;
   *plan = pl;
   return ILARGI_OK;
@@ -1719,8 +1742,15 @@ ilargi_status_t ilargi_crossprod(ilargi_plan_t* plan, float* out, void* stream) 
   const int n = plan->n;
   float* blocks = plan->at<float>(plan->lay.o_blocks);
   float* zc = plan->at<float>(plan->lay.o_zc);
+  // The diagonal block of the dimension table of a two-table star join does not depend on the pass over the
+  // entity table: with a second stream it runs beside it, each with its own half of the partial-block space.
+  float* gpart = plan->at<float>(plan->lay.o_gpartial);
+  const int64_t gfloats = plan->lay.gpartial_floats;
+  bool forked = false;
+  float* part_main = gpart;
+  int64_t part_main_floats = gfloats;
   auto run_gram = [&](TredArgs& g, float* block, int pair) -> ilargi_status_t {
-    return run_tred(plan, g, block, "gram", pair, false, st);   // traced as gram:<k * n + l>
+    return run_tred(plan, g, block, "gram", pair, false, st, false, part_main, part_main_floats);   // traced as gram:<k * n + l>
   };
   // two-table star join with a narrow entity table listed first: S^T S and the rows of S summed per row of R
   // (which the off-diagonal block needs) come from one pass over S in join order
@@ -1728,18 +1758,40 @@ ilargi_status_t ilargi_crossprod(ilargi_plan_t* plan, float* out, void* stream) 
   if (plan->star_k >= 0 && plan->fused < plan->star_k) {
     const SourcePlan& f = plan->src[plan->fused];
     const SourcePlan& d = plan->src[plan->star_k];
-    const int64_t max_grid = std::min<int64_t>(1024, plan->lay.gpartial_floats / std::max<int64_t>(f.cols * f.cols, 1));
+    const int64_t max_grid = std::min<int64_t>(1024, gfloats / 2 / std::max<int64_t>(f.cols * f.cols, 1));
     if (gram_star_supported((int)f.cols) && d.rows * 2 <= plan->r_T && d.rows * f.cols <= plan->lay.zc_floats && max_grid >= 1) {
+      const bool fork = plan->side != nullptr && d.cols * d.cols <= gfloats / 2;
+      if (fork) {
+        HIP_TRY(hipEventRecord(plan->ev_fork, st));
+        part_main_floats = gfloats / 2;
+      }
       GramStarArgs ga;
       memset(&ga, 0, sizeof(ga));
       ga.S = f.D; ga.cs = (int)f.cols; ga.r_R = d.rows;
       ga.rowptr = plan->at<int32_t>(d.o_rowptr); ga.perm = plan->at<int32_t>(d.o_perm); ga.idx = d.idx;
-      ga.ss_partial = plan->at<float>(plan->lay.o_gpartial);
+      ga.ss_partial = gpart;
       ga.zc = zc;
       int grid = 0;
       {
         TraceScope ts(plan, "gram_star", -1, st);
         HIP_TRY(launch_gram_star(ga, f.vec, (int)max_grid, st, &grid));
+      }
+      if (fork) {
+        // R^T diag(cnt) R on the second stream, upper half of the partial space (enqueued after the pass over S, which
+        // is bound by memory latency and leaves the matrix cores to it)
+        HIP_TRY(hipStreamWaitEvent(plan->side, plan->ev_fork, 0));
+        TredArgs g;
+        memset(&g, 0, sizeof(g));
+        g.A = d.D; g.lda = (int)d.cols; g.ca = (int)d.cols; g.a_rows = d.rows;
+        g.B = d.D; g.ldb = (int)d.cols; g.cb = (int)d.cols; g.b_rows = d.rows;
+        g.wptr = plan->at<int32_t>(d.o_rowptr);
+        g.n_rows = d.rows;
+        g.upper_only = 1;
+        ilargi_status_t rc = run_tred(plan, g, blocks + plan->block_off[(size_t)plan->star_k * n + plan->star_k], "gram",
+                                      plan->star_k * n + plan->star_k, false, plan->side, false, gpart + gfloats / 2, gfloats / 2);
+        if (rc != ILARGI_OK) return rc;
+        HIP_TRY(hipEventRecord(plan->ev_join, plan->side));
+        forked = true;
       }
       HIP_TRY(launch_tred_reduce(ga.ss_partial, grid, f.cols * f.cols,
                                  blocks + plan->block_off[(size_t)plan->fused * n + plan->fused], st));
@@ -1753,6 +1805,7 @@ ilargi_status_t ilargi_crossprod(ilargi_plan_t* plan, float* out, void* stream) 
       const SourcePlan& b = plan->src[l];
       if (b.empty) continue;
       if (star_done && k == plan->fused && l == k) continue;   // S^T S is done
+      if (forked && k == plan->star_k && l == k) continue;     // this block is on the second stream
       float* block = blocks + plan->block_off[(size_t)k * n + l];
       TredArgs g;
       memset(&g, 0, sizeof(g));
@@ -1782,7 +1835,7 @@ ilargi_status_t ilargi_crossprod(ilargi_plan_t* plan, float* out, void* stream) 
             // few summed columns against a wide table: the wide table takes the A role (whole rows as float4,
             // 128 columns per workgroup) and the block is written transposed, D_l^T Zc = (Zc^T D_l)^T
             std::swap(g.A, g.B); std::swap(g.lda, g.ldb); std::swap(g.ca, g.cb); std::swap(g.a_rows, g.b_rows);
-            rc = run_tred(plan, g, block, "gram", k * n + l, false, st, true);
+            rc = run_tred(plan, g, block, "gram", k * n + l, false, st, true, part_main, part_main_floats);
             if (rc != ILARGI_OK) return rc;
             continue;
           }
@@ -1805,6 +1858,7 @@ ilargi_status_t ilargi_crossprod(ilargi_plan_t* plan, float* out, void* stream) 
       if (rc != ILARGI_OK) return rc;
     }
   }
+  if (forked) HIP_TRY(hipStreamWaitEvent(st, plan->ev_join, 0));   // join
   HIP_TRY(launch_gram_assemble(plan->at<GramAsmPair>(plan->lay.o_pairs), plan->npairs,
                                plan->at<const int32_t*>(plan->lay.o_tcol_table), (int)plan->c_T, out, st));
   return ILARGI_OK;
