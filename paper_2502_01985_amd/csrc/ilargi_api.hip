@@ -1224,7 +1224,11 @@ ilargi_status_t plan_create_impl(int n, const ilargi_source_t* sources, int64_t 
     HIP_TRY(hipMemcpyAsync(pl->at<GramAsmPair>(lay.o_pairs), pairs.data(), sizeof(GramAsmPair) * pairs.size(), hipMemcpyHostToDevice, st));
   HIP_TRY(hipStreamSynchronize(st));
   pl->static_dev = static_dev;
-  if (static_dev < 0) {
+  // crossprod of a two-table star join runs the dimension table's Gram block beside the pass over the entity table;
+  // only such plans pay for a second stream (creating one takes milliseconds)
+  const bool wants_side = pl->star_k >= 0 && pl->fused >= 0 && pl->fused < pl->star_k &&
+                          gram_star_supported((int)pl->src[pl->fused].cols);
+  if (static_dev < 0 && wants_side) {
     // (a plan on the static scratch array is for callers that must not allocate: it creates no stream either)
     if (hipStreamCreateWithFlags(&pl->side, hipStreamNonBlocking) != hipSuccess) pl->side = nullptr;
     if (pl->side != nullptr &&
