@@ -414,6 +414,7 @@ ilargi_status_t lmm_pass(ilargi_plan* pl, const float* X, int ldx, int col0, int
     a.X = X; a.ldx = ldx; a.col0 = col0; a.ncols = ncols;
     a.out = pl->at<float>(p.o_pz); a.ldo = ldx; a.r_out = p.rows;
     a.logL = pick_logL(p.cols, p.vec);
+    a.scratch = pl->at<float>(pl->lay.o_gpartial); a.scratch_floats = pl->lay.gpartial_floats;   // free until the assembly
     {
       TraceScope ts(pl, "lmm_rows", k, st);
       if (p.sparse) HIP_TRY(launch_spmm_rows(sparse_args(pl, k), X, ldx, col0, ncols, pl->at<float>(p.o_pz), ldx, st));
@@ -616,6 +617,19 @@ ilargi_status_t run_tred(ilargi_plan* pl, TredArgs& g, float* block, const char*
     HIP_TRY(launch_gram_sym(g, part, part_floats, block, st));
     return ILARGI_OK;
   }
+  if (bf16 && !transposed && tred_stream_bf16_supported(g)) {
+    // bfloat16 inputs over plain rows: one workgroup per compute unit keeps its whole ca x cb block in registers
+    const int grid = tred_stream_bf16_grid(g, part_floats);
+    if (grid >= 1) {
+      g.partial = part;
+      {
+        TraceScope ts(pl, tag, tag_k, st);
+        HIP_TRY(launch_tred_stream_bf16(g, grid, st));
+      }
+      HIP_TRY(launch_tred_reduce(g.partial, g.gx, elems, block, st, 0));
+      return ILARGI_OK;
+    }
+  }
   // row chunks: whole rounds of the device's workgroup slots (every workgroup does the same work, so a
   // partly filled last round would idle most compute units), within the partial buffer, >= 64 rows each
   int slots = 512, tiles = 1;
@@ -764,6 +778,7 @@ ilargi_status_t gd_star_step(ilargi_plan* pl, int mode, float* W, int m, const f
     a.X = W; a.ldx = m; a.col0 = 0; a.ncols = m;
     a.out = pl->at<float>(d.o_pz); a.ldo = m; a.r_out = d.rows;
     a.logL = pick_logL(d.cols, d.vec);
+    a.scratch = pl->at<float>(pl->lay.o_gpartial); a.scratch_floats = pl->lay.gpartial_floats;   // free until the star pass
     TraceScope ts(pl, "lmm_rows", pl->star_k, st);
     HIP_TRY(launch_lmm_mfma(a, d.vec, 0, bf16, st, nullptr));
   }

@@ -52,6 +52,8 @@ struct LmmArgs {
   float* loss_partial;    // narrow kernel: [gridDim.x][kNarrowCT]; matrix-core kernel: [gridDim.x][ld_loss]
   int ld_loss;
   int nt_out;             // store the output with non-temporal stores (large results nobody re-reads soon)
+  float* scratch;         // optional device scratch of scratch_floats floats (the caller's, free for the launch)
+  int64_t scratch_floats;
   float* grad_partial;    // optional partials of D^T e: narrow kernel [gridDim.x][ck][kNarrowCT],
                           // matrix-core kernel [gridDim.x][ck][ld_grad]
   int ld_grad;
@@ -304,6 +306,8 @@ bool lmm_mfma_can_fuse_gradient(int ck, int ncols, bool bf16);
 hipError_t launch_lmm_mfma(const LmmArgs& a, int vec, int mode, bool bf16, hipStream_t st, int* grid_out);
 bool lmm_flat_pair_supported(const LmmArgs& a, int vec, bool fuseg);
 hipError_t launch_lmm_flat_pair(const LmmArgs& a, int mode, bool fuseg, hipStream_t st, int* grid_out);
+bool lmm_prod_bf16_supported(const LmmArgs& a, int vec, int mode);
+hipError_t launch_lmm_prod_bf16(const LmmArgs& a, hipStream_t st);
 bool lmm_prod_stream_supported(const LmmArgs& a, int vec, int mode);
 hipError_t launch_lmm_prod_stream(const LmmArgs& a, hipStream_t st);
 bool lmm_flat_wide_supported(const LmmArgs& a, int vec, int mode);
@@ -346,6 +350,10 @@ hipError_t launch_gram_star(const GramStarArgs& a, int vec, int max_grid, hipStr
 bool gram_sym_supported(const TredArgs& a);
 hipError_t launch_gram_sym(TredArgs& a, float* partial, int64_t partial_floats, float* block, hipStream_t st);
 hipError_t launch_tred(const TredArgs& a, int nchunks, bool bf16, hipStream_t st);
+// bfloat16-input column reduce over plain rows (kernels_wide_bf16.hip): a.partial receives a.gx blocks of ca x cb
+bool tred_stream_bf16_supported(const TredArgs& a);
+int tred_stream_bf16_grid(const TredArgs& a, int64_t partial_floats);
+hipError_t launch_tred_stream_bf16(TredArgs& a, int grid, hipStream_t st);
 void tred_occupancy(const TredArgs& a, bool bf16, int* slots, int* tiles);
 // G = S^T Y for an identity source with rows of at most 16 float4 and 5..16 operand columns (kernels_colred_flat.hip).
 struct ColredFlatArgs {
