@@ -617,14 +617,14 @@ ilargi_status_t run_tred(ilargi_plan* pl, TredArgs& g, float* block, const char*
     HIP_TRY(launch_gram_sym(g, part, part_floats, block, st));
     return ILARGI_OK;
   }
-  if (bf16 && !transposed && tred_stream_bf16_supported(g)) {
-    // bfloat16 inputs over plain rows: one workgroup per compute unit keeps its whole ca x cb block in registers
-    const int grid = tred_stream_bf16_grid(g, part_floats);
+  if (!transposed && tred_stream_supported(g) && (bf16 || (elems >= 64 * 64 && g.n_rows >= 1024))) {
+    // plain rows of both operands: one workgroup per compute unit keeps its whole ca x cb block in registers
+    const int grid = tred_stream_grid(g, part_floats);
     if (grid >= 1) {
       g.partial = part;
       {
         TraceScope ts(pl, tag, tag_k, st);
-        HIP_TRY(launch_tred_stream_bf16(g, grid, st));
+        HIP_TRY(launch_tred_stream(g, grid, bf16, st));
       }
       HIP_TRY(launch_tred_reduce(g.partial, g.gx, elems, block, st, 0));
       return ILARGI_OK;

@@ -350,10 +350,10 @@ hipError_t launch_gram_star(const GramStarArgs& a, int vec, int max_grid, hipStr
 bool gram_sym_supported(const TredArgs& a);
 hipError_t launch_gram_sym(TredArgs& a, float* partial, int64_t partial_floats, float* block, hipStream_t st);
 hipError_t launch_tred(const TredArgs& a, int nchunks, bool bf16, hipStream_t st);
-// bfloat16-input column reduce over plain rows (kernels_wide_bf16.hip): a.partial receives a.gx blocks of ca x cb
-bool tred_stream_bf16_supported(const TredArgs& a);
-int tred_stream_bf16_grid(const TredArgs& a, int64_t partial_floats);
-hipError_t launch_tred_stream_bf16(TredArgs& a, int grid, hipStream_t st);
+// streaming column reduce over plain rows (kernels_wide_bf16.hip): a.partial receives a.gx blocks of ca x cb
+bool tred_stream_supported(const TredArgs& a);
+int tred_stream_grid(const TredArgs& a, int64_t partial_floats);
+hipError_t launch_tred_stream(TredArgs& a, int grid, bool bf16, hipStream_t st);
 void tred_occupancy(const TredArgs& a, bool bf16, int* slots, int* tiles);
 // G = S^T Y for an identity source with rows of at most 16 float4 and 5..16 operand columns (kernels_colred_flat.hip).
 struct ColredFlatArgs {

@@ -1,5 +1,5 @@
-// Wide-batch kernels with bfloat16 inputs and float32 accumulation (values are rounded to bfloat16, nearest even,
-// where they enter a product; products of two bfloat16 values are exact in float32):
+// Streaming kernels of the wide batch.  With bfloat16 inputs and float32 accumulation (values are rounded to
+// bfloat16, nearest even, where they enter a product; products of two bfloat16 values are exact in float32):
 //   lmm_prod_bf16_kernel     P = D (M^T X)            per-source product of the left multiply (Sec. 2.2)
 //   tred_stream_bf16_kernel  C = A^T B  over all rows  column reduce of the transposed multiply (Sec. 2.2)
 // A bfloat16 MFMA does sixteen times the work of a float32 one per cycle, so neither kernel is bound by the matrix
@@ -250,6 +250,113 @@ __global__ __launch_bounds__(kWbThreads) void tred_stream_bf16_kernel(TredArgs a
   }
 }
 
+// The same column reduce with float32 inputs (16x16x4 MFMA).  Here the matrix cores are the bound (a float32 MFMA
+// does a sixteenth of the work per cycle).  The tiles are staged transposed as well, [column][32 rows]: the
+// summation index of a product may be dealt to the K slots in any order as long as both operands agree, so K slot
+// q of the four products of group h stands for rows 16 h + 4 q .. + 3, and one 128-bit LDS read per operand feeds
+// four products on one accumulator.
+constexpr int kTfLdr = kTsStepRows + 4;      // floats per staged column (rows of a step + padding)
+
+__global__ __launch_bounds__(kWbThreads) void tred_stream_f32_kernel(TredArgs a, int mtc, int ntc) {
+  extern __shared__ __align__(16) unsigned char lds_raw[];
+  const int cap = 16 * mtc;
+  float* buf = reinterpret_cast<float*>(lds_raw);             // two buffers of [cap][kTfLdr] (A) then [kWbSlab][kTfLdr] (B)
+  const int buf_floats = (cap + kWbSlab) * kTfLdr;
+  const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+  const int li = lane % 16, q = lane / 16;
+  for (int e = tid; e < 2 * buf_floats; e += kWbThreads) buf[e] = 0.0f;   // padding columns stay zero
+  // this thread's loading task: threads 0..255 an 8 x 4 block of B, threads 256.. one of A
+  const bool is_b = tid < 256;
+  const int t = is_b ? tid : tid - 256;
+  const int quads = is_b ? kWbSlab / 4 : a.ca / 4;
+  const int rb = t / quads, cq = t - rb * quads;              // row octet of the step, column quad
+  const bool task = rb < 4 && (is_b ? 4 * cq < a.cb : true);
+  const float* base = is_b ? a.B + a.bcol0 + 4 * cq : a.A + 4 * cq;
+  const int ld = is_b ? a.ldb : a.lda;
+  const int64_t row_begin = (int64_t)blockIdx.x * a.rows_per_block;
+  const int64_t row_end = min(a.n_rows, row_begin + a.rows_per_block);
+
+  float4 x[8];
+  unsigned live = 0;
+  auto fetch = [&](int64_t r0) {                              // rows r0 + 8 rb + i, branch-free
+    live = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int64_t row = r0 + 8 * rb + i;
+      const bool ok = task && row < row_end;
+      x[i] = *reinterpret_cast<const float4*>(ok ? base + row * ld : (is_b ? a.B : a.A));
+      live |= (ok ? 1u : 0u) << i;
+    }
+  };
+  v4f acc[kTsMt][2];
+#pragma unroll
+  for (int mt = 0; mt < kTsMt; ++mt)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) acc[mt][j] = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
+
+  fetch(row_begin);
+  __syncthreads();
+  int cur = 0;
+  for (int64_t r0 = row_begin; r0 < row_end; r0 += kTsStepRows, cur ^= 1) {
+    float* As = buf + (size_t)cur * buf_floats;               // [cap][kTfLdr]
+    float* Bs = As + cap * kTfLdr;                            // [kWbSlab][kTfLdr]
+    if (task) {
+      float xs[8][4];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const bool ok = (live >> i & 1u) != 0;
+        xs[i][0] = ok ? x[i].x : 0.0f; xs[i][1] = ok ? x[i].y : 0.0f;
+        xs[i][2] = ok ? x[i].z : 0.0f; xs[i][3] = ok ? x[i].w : 0.0f;
+      }
+      float* dst = (is_b ? Bs : As) + (size_t)(4 * cq) * kTfLdr + 8 * rb;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        *reinterpret_cast<float4*>(dst + c * kTfLdr) = make_float4(xs[0][c], xs[1][c], xs[2][c], xs[3][c]);
+        *reinterpret_cast<float4*>(dst + c * kTfLdr + 4) = make_float4(xs[4][c], xs[5][c], xs[6][c], xs[7][c]);
+      }
+    }
+    fetch(r0 + kTsStepRows);
+    __syncthreads();
+#pragma unroll
+    for (int h = 0; h < kTsStepRows / 16; ++h) {
+      float4 bf[2];
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        bf[j] = *reinterpret_cast<const float4*>(Bs + (size_t)(16 * (2 * wave + j) + li) * kTfLdr + 16 * h + 4 * q);
+#pragma unroll
+      for (int mt = 0; mt < kTsMt; ++mt) {
+        if (mt < mtc) {
+          const float4 af = *reinterpret_cast<const float4*>(As + (size_t)(16 * mt + li) * kTfLdr + 16 * h + 4 * q);
+#pragma unroll
+          for (int j = 0; j < 2; ++j) {
+            if (2 * wave + j < ntc) {
+              acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.x, bf[j].x, acc[mt][j], 0, 0, 0);
+              acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.y, bf[j].y, acc[mt][j], 0, 0, 0);
+              acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.z, bf[j].z, acc[mt][j], 0, 0, 0);
+              acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.w, bf[j].w, acc[mt][j], 0, 0, 0);
+            }
+          }
+        }
+      }
+    }
+  }
+  float* out = a.partial + (int64_t)blockIdx.x * a.ca * a.cb;
+#pragma unroll
+  for (int mt = 0; mt < kTsMt; ++mt) {
+    if (mt < mtc) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int n = 16 * (2 * wave + j) + li;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int m = 16 * mt + 4 * q + r;
+          if (m < a.ca && n < a.cb) out[(int64_t)m * a.cb + n] = acc[mt][j][r];
+        }
+      }
+    }
+  }
+}
+
 typedef void (*PbFn)(LmmArgs, int, const bf16x8*);
 
 int wb_cus() {
@@ -302,7 +409,7 @@ hipError_t launch_lmm_prod_bf16(const LmmArgs& a, hipStream_t st) {
 }
 
 // Plain rows of both operands (no row gathers, no weights), whole aligned float4s, at most 256 columns each.
-bool tred_stream_bf16_supported(const TredArgs& a) {
+bool tred_stream_supported(const TredArgs& a) {
   if (a.ia != nullptr || a.ib != nullptr || a.wptr != nullptr || a.upper_only) return false;
   if (a.ca < 4 || a.ca > 256 || a.ca % 4 != 0 || a.lda % 4 != 0 || reinterpret_cast<uintptr_t>(a.A) % 16 != 0) return false;
   if (a.cb < 4 || a.cb > kWbSlab || a.cb % 4 != 0 || a.ldb % 4 != 0 || a.bcol0 % 4 != 0 || reinterpret_cast<uintptr_t>(a.B) % 16 != 0) return false;
@@ -311,19 +418,26 @@ bool tred_stream_bf16_supported(const TredArgs& a) {
 }
 
 // Workgroups (= partial blocks of ca x cb floats) the launch will use within partial_floats; 0: does not fit.
-int tred_stream_bf16_grid(const TredArgs& a, int64_t partial_floats) {
+int tred_stream_grid(const TredArgs& a, int64_t partial_floats) {
   const int64_t elems = (int64_t)a.ca * a.cb;
   int64_t grid = std::min<int64_t>(wb_cus(), (a.n_rows + kTsStepRows - 1) / kTsStepRows);
   grid = std::min<int64_t>(grid, partial_floats / elems);
   return (int)std::max<int64_t>(grid, 0);
 }
 
-hipError_t launch_tred_stream_bf16(TredArgs& a, int grid, hipStream_t st) {
-  if (!tred_stream_bf16_supported(a) || grid < 1 || a.partial == nullptr) return hipErrorInvalidValue;
+hipError_t launch_tred_stream(TredArgs& a, int grid, bool bf16, hipStream_t st) {
+  if (!tred_stream_supported(a) || grid < 1 || a.partial == nullptr) return hipErrorInvalidValue;
   a.rows_per_block = ((a.n_rows + grid - 1) / grid + kTsStepRows - 1) / kTsStepRows * kTsStepRows;
   const int used = (int)((a.n_rows + a.rows_per_block - 1) / a.rows_per_block);
   a.gx = used;
   const int mtc = (a.ca + 15) / 16, ntc = (a.cb + 15) / 16;
+  if (!bf16) {
+    const size_t lds_f32 = (size_t)2 * (16 * mtc + kWbSlab) * kTfLdr * sizeof(float);
+    if (lds_f32 > 64 * 1024)
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(tred_stream_f32_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_f32);
+    hipLaunchKernelGGL(tred_stream_f32_kernel, dim3((unsigned)used), dim3(kWbThreads), lds_f32, st, a, mtc, ntc);
+    return hipGetLastError();
+  }
   const size_t lds_bytes = (size_t)2 * (4 * 16 * mtc + 4 * kWbSlab) * 16;
   if (lds_bytes > 64 * 1024)
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(tred_stream_bf16_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
