@@ -306,6 +306,8 @@ bool lmm_mfma_can_fuse_gradient(int ck, int ncols, bool bf16);
 hipError_t launch_lmm_mfma(const LmmArgs& a, int vec, int mode, bool bf16, hipStream_t st, int* grid_out);
 bool lmm_flat_pair_supported(const LmmArgs& a, int vec, bool fuseg);
 hipError_t launch_lmm_flat_pair(const LmmArgs& a, int mode, bool fuseg, hipStream_t st, int* grid_out);
+bool lmm_prod_f32_wide_supported(const LmmArgs& a, int vec, int mode);
+hipError_t launch_lmm_prod_f32_wide(const LmmArgs& a, hipStream_t st);
 bool lmm_prod_bf16_supported(const LmmArgs& a, int vec, int mode);
 hipError_t launch_lmm_prod_bf16(const LmmArgs& a, hipStream_t st);
 bool lmm_prod_stream_supported(const LmmArgs& a, int vec, int mode);

@@ -618,6 +618,8 @@ hipError_t launch_lmm_mfma(const LmmArgs& a, int vec, int mode, bool bf16, hipSt
   MfmaFn fn;
   // plain product with bfloat16 inputs and a wide operand: the whole operand slab in LDS, table rows streamed
   if (bf16 && a.ncols >= 64 && lmm_prod_bf16_supported(a, vec, mode)) return launch_lmm_prod_bf16(a, st);
+  // the same in float32 (slabs of 128 columns)
+  if (!bf16 && a.ncols >= 64 && lmm_prod_f32_wide_supported(a, vec, mode)) return launch_lmm_prod_f32_wide(a, st);
   // plain product with at most 16 result columns (no gathers, no epilogue): the streaming kernel
   if (!bf16 && nt == 1 && lmm_prod_stream_supported(a, vec, mode)) return launch_lmm_prod_stream(a, st);
   // wide plain product (no gathers, no epilogue): the chunked, double-buffered kernel

@@ -357,6 +357,131 @@ __global__ __launch_bounds__(kWbThreads) void tred_stream_f32_kernel(TredArgs a,
   }
 }
 
+// The float32 product for a wide operand, same plan: the operand slab (here 128 columns, [K / 4][128][4 consecutive
+// K] floats, packed beforehand) in LDS, table rows streamed from memory straight into A operands.  Lane (row li, q)
+// loads the float4 at columns 16 s + 4 q of its row; its four values and one 128-bit LDS read are four 16x16x4
+// products on one accumulator (K slot q of product e stands for column 16 s + 4 q + e).  The matrix cores are the
+// bound here: 52 products per column tile and 16 table rows.
+constexpr int kFsSlab = 128;
+
+__global__ __launch_bounds__(kBlock) void lmm_pack_f32_kernel(LmmArgs a, int nst, float4* __restrict__ packed) {
+  const int items = 4 * nst * kFsSlab;
+  const int it = blockIdx.x * kBlock + threadIdx.x;
+  if (it >= items) return;
+  const int n0 = blockIdx.y * kFsSlab;
+  const int nw = min(kFsSlab, a.ncols - n0);
+  const int n = it % kFsSlab, o = it / kFsSlab;
+  const float* Xc = a.X + a.col0 + n0;
+  const int ns = min(n, nw - 1);
+  int t[4];
+#pragma unroll
+  for (int c = 0; c < 4; ++c) t[c] = 4 * o + c < a.ck ? a.colmap[4 * o + c] : -1;
+  float x[4];
+#pragma unroll
+  for (int c = 0; c < 4; ++c) x[c] = Xc[(int64_t)max(t[c], 0) * a.ldx + ns];
+#pragma unroll
+  for (int c = 0; c < 4; ++c) x[c] = (t[c] >= 0 && n < nw) ? x[c] : 0.0f;
+  packed[(size_t)blockIdx.y * items + it] = make_float4(x[0], x[1], x[2], x[3]);
+}
+
+// NST: compile-time bound of the 16-column steps of a table row.
+template <int NST>
+__global__ __launch_bounds__(kWbThreads) void lmm_prod_f32_wide_kernel(LmmArgs a, int nst, const float4* __restrict__ packed) {
+  extern __shared__ __align__(16) unsigned char lds_raw[];
+  float4* Bs = reinterpret_cast<float4*>(lds_raw);            // [4 nst][kFsSlab]
+  const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+  const int li = lane % 16, q = lane / 16;
+  const int ck = a.ck;
+  const int n0 = blockIdx.y * kFsSlab;
+  const int nw = min(kFsSlab, a.ncols - n0);
+  const int ntc = (nw + 15) / 16;
+  const int64_t ntiles = (a.r_out + 15) / 16;
+  const int64_t tstride = (int64_t)gridDim.x * kWbWaves;
+  int64_t tile = (int64_t)blockIdx.x * kWbWaves + wave;
+
+  float4 av[NST];
+  unsigned live = 0;
+  auto fetch = [&](int64_t t) {                               // branch-free, see lmm_prod_bf16_kernel
+    const int64_t row = t * 16 + li;
+    const bool in = t < ntiles && row < a.d_rows;
+    const float* rp = a.D + (in ? row * ck + 4 * q : 0);
+    live = 0;
+#pragma unroll
+    for (int s = 0; s < NST; ++s) {
+      const bool ok = s < nst && in && 16 * s + 4 * q < ck;
+      av[s] = *reinterpret_cast<const float4*>(ok ? rp + 16 * s : a.D);
+      live |= (ok ? 1u : 0u) << s;
+    }
+  };
+  fetch(tile);
+  {
+    const float4* src = packed + (size_t)blockIdx.y * 4 * nst * kFsSlab;
+    float4 t[NST];
+#pragma unroll
+    for (int u = 0; u < NST; ++u) t[u] = src[min(u, nst - 1) * kWbThreads + tid];
+#pragma unroll
+    for (int u = 0; u < NST; ++u)
+      if (u < nst) Bs[u * kWbThreads + tid] = t[u];
+  }
+  __syncthreads();
+
+  for (; tile < ntiles; tile += tstride) {
+    float4 ac[NST];
+#pragma unroll
+    for (int s = 0; s < NST; ++s) ac[s] = (live >> s & 1u) ? av[s] : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    fetch(tile + tstride);
+    const int64_t row0 = tile * 16;
+    // The operand values are read half a column tile ahead of the products that use them (a product chain that
+    // waits for its own LDS reads leaves the matrix cores idle half of the time): units of H steps, the next
+    // unit's values requested before the current unit's products are issued.
+    constexpr int H = (NST + 1) / 2;
+    float4 bn[H];
+    auto read_unit = [&](int nt, int half) {
+#pragma unroll
+      for (int e = 0; e < H; ++e) bn[e] = Bs[(size_t)(4 * min(half * H + e, nst - 1) + q) * kFsSlab + 16 * nt + li];
+    };
+    read_unit(0, 0);
+#pragma unroll
+    for (int nt = 0; nt < kFsSlab / 16; ++nt) {
+      if (nt < ntc) {
+        v4f acc = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+          float4 bv[H];
+#pragma unroll
+          for (int e = 0; e < H; ++e) bv[e] = bn[e];
+          if (half == 0) read_unit(nt, 1);
+          else read_unit(min(nt + 1, kFsSlab / 16 - 1), 0);
+#pragma unroll
+          for (int e = 0; e < H; ++e) {
+            const int sidx = half * H + e;
+            if (sidx < NST && sidx < nst) {
+              acc = __builtin_amdgcn_mfma_f32_16x16x4f32(ac[sidx].x, bv[e].x, acc, 0, 0, 0);
+              acc = __builtin_amdgcn_mfma_f32_16x16x4f32(ac[sidx].y, bv[e].y, acc, 0, 0, 0);
+              acc = __builtin_amdgcn_mfma_f32_16x16x4f32(ac[sidx].z, bv[e].z, acc, 0, 0, 0);
+              acc = __builtin_amdgcn_mfma_f32_16x16x4f32(ac[sidx].w, bv[e].w, acc, 0, 0, 0);
+            }
+          }
+        }
+        const int n = 16 * nt + li;
+        if (n < nw) {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const int64_t row = row0 + 4 * q + r;
+            if (row < a.r_out) {
+              float* op = a.out + row * a.ldo + a.col0 + n0 + n;
+              if (a.nt_out) __builtin_nontemporal_store(acc[r], op);
+              else *op = acc[r];
+            }
+          }
+        }
+      }
+    }
+  }
+}
+
+typedef void (*PfFn)(LmmArgs, int, const float4*);
+
 typedef void (*PbFn)(LmmArgs, int, const bf16x8*);
 
 int wb_cus() {
@@ -402,6 +527,41 @@ hipError_t launch_lmm_prod_bf16(const LmmArgs& a, hipStream_t st) {
   bf16x8* packed = reinterpret_cast<bf16x8*>(a.scratch);
   const int items = 4 * nst * kWbSlab;
   hipLaunchKernelGGL(lmm_pack_bf16_kernel, dim3((unsigned)((items + kBlock - 1) / kBlock), (unsigned)slabs), dim3(kBlock), 0, st, a, nst, packed);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(fn, dim3((unsigned)grid, (unsigned)slabs), dim3(kWbThreads), lds_bytes, st, a, nst, packed);
+  return hipGetLastError();
+}
+
+// The float32 counterpart (same conditions; scratch of 8 KiB per 16 table columns and slab of 128 operand columns).
+bool lmm_prod_f32_wide_supported(const LmmArgs& a, int vec, int mode) {
+  if (mode != 0 || a.D == nullptr || vec != 4 || a.ck < 4 || a.ck % 4 != 0 || a.ck > 256) return false;
+  if (a.g.n != 0 || a.grad_partial != nullptr || a.ncols < 1) return false;
+  if (reinterpret_cast<uintptr_t>(a.D) % 16 != 0 || a.d_rows < a.r_out) return false;
+  const int64_t nst = (a.ck + 15) / 16, slabs = (a.ncols + kFsSlab - 1) / kFsSlab;
+  if (a.scratch == nullptr || reinterpret_cast<uintptr_t>(a.scratch) % 16 != 0 || a.scratch_floats < slabs * 4 * nst * kFsSlab * 4) return false;
+  return true;
+}
+
+hipError_t launch_lmm_prod_f32_wide(const LmmArgs& a, hipStream_t st) {
+  if (!lmm_prod_f32_wide_supported(a, 4, 0)) return hipErrorInvalidValue;
+  if (a.r_out <= 0) return hipSuccess;
+  const int nst = (a.ck + 15) / 16;
+  PfFn fn = nst <= 2 ? lmm_prod_f32_wide_kernel<2>
+          : nst <= 4 ? lmm_prod_f32_wide_kernel<4>
+          : nst <= 8 ? lmm_prod_f32_wide_kernel<8>
+          : nst <= 13 ? lmm_prod_f32_wide_kernel<13> : lmm_prod_f32_wide_kernel<16>;
+  const size_t lds_bytes = (size_t)4 * nst * kFsSlab * 16;
+  if (lds_bytes > 64 * 1024)
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+  const int64_t ntiles = (a.r_out + 15) / 16;
+  const int slabs = (a.ncols + kFsSlab - 1) / kFsSlab;
+  const int per_cu = lds_bytes <= 48 * 1024 ? 2 : 1;
+  int64_t grid = (ntiles + kWbWaves - 1) / kWbWaves;
+  grid = std::min<int64_t>(grid, std::max(1, per_cu * wb_cus() / slabs));
+  float4* packed = reinterpret_cast<float4*>(a.scratch);
+  const int items = 4 * nst * kFsSlab;
+  hipLaunchKernelGGL(lmm_pack_f32_kernel, dim3((unsigned)((items + kBlock - 1) / kBlock), (unsigned)slabs), dim3(kBlock), 0, st, a, nst, packed);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(fn, dim3((unsigned)grid, (unsigned)slabs), dim3(kWbThreads), lds_bytes, st, a, nst, packed);
