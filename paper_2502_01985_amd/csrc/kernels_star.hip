@@ -52,7 +52,7 @@ constexpr int kWaves = kBlock / kWave;
 // to bfloat16 (nearest even) where they enter a product.  JG: 16-column tiles of S (kp / 16 rounded to 2 or 4).
 // ST: target rows a wavefront stages at a time (32 or 64).
 template <int MODE, bool VEC4, bool BF16, int JG, int ST>
-__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(VEC4 ? (JG == 2 ? 3 : 2) : (JG == 2 ? 2 : 1)))) void gd_star_kernel(StarArgs a, int kp, int lda, int rtiles, int fold) {
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(VEC4 ? (JG == 2 && !BF16 ? 3 : 2) : (JG == 2 ? 2 : 1)))) void gd_star_kernel(StarArgs a, int kp, int lda, int rtiles, int fold) {
   extern __shared__ float lds[];
   float* Xs = lds;                                            // [kp / 4][64][4]  (bf16: [kp / 8][64][8])
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
@@ -208,7 +208,9 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(VEC4 ? (
       }
       load_rows(cnt_next);
 
-      for (int t = 0; 16 * t < cnt; ++t) {
+      // residual tile t of the batch: ov[nt][r] = residual of row 4 q + r, model column li of tile nt (rounded to
+      // bfloat16 with BF16), ind[r] = the indicator (or folded table) value of that row for row li of the tile of R
+      auto residual_tile = [&](int t, float (&ov)[kNT][4], float (&ind)[4]) {
         // z tile = S rows x W_S
         v4f acc[kNT];
 #pragma unroll
@@ -251,8 +253,6 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(VEC4 ? (
           }
         }
         // residual of rows 4 q + r, model column li of each 16-column tile
-        float ov[kNT][4];
-        float ind[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           const int row = t * 16 + 4 * q + r;
@@ -280,30 +280,91 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(VEC4 ? (
             }
           }
         }
-        // segment sums, then S^T E.  With BF16 the residual is rounded once as it enters these two products
-        // (the segment sum is the product with the 0/1 indicator matrix: exact sums of the rounded values)
+        // With BF16 the residual is rounded once as it enters the two products below
         if constexpr (BF16) {
 #pragma unroll
           for (int r = 0; r < 4; ++r)
 #pragma unroll
             for (int nt = 0; nt < kNT; ++nt) ov[nt][r] = (float)(__bf16)ov[nt][r];
         }
+      };
+      if constexpr (!BF16) {
+        for (int t = 0; 16 * t < cnt; ++t) {
+          float ov[kNT][4];
+          float ind[4];
+          residual_tile(t, ov, ind);
+          // segment sums (the product with the 0/1 indicator matrix), then S^T E
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
+          for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int nt = 0; nt < kNT; ++nt)
+              zacc[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(ind[r], ov[nt][r], zacc[nt], 0, 0, 0);
+          const float* acol = As + (size_t)(t * 16 + 4 * q) * lda + li;
+#pragma unroll
+          for (int jt = 0; jt < JG; ++jt) {
+            if (jt < njt) {
+#pragma unroll
+              for (int r = 0; r < 4; ++r) {
+                const float av = acol[(size_t)r * lda + jt * 16];
+#pragma unroll
+                for (int nt = 0; nt < kNT; ++nt)
+                  gacc[jt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, ov[nt][r], gacc[jt][nt], 0, 0, 0);
+              }
+            }
+          }
+        }
+      } else {
+        // Two tiles (32 rows) at a time: their residuals, as they sit in the lanes, are the B operand of one
+        // 16x16x32 bfloat16 MFMA whose K octet q stands for the rows 4 q .. 4 q + 3 of the first tile followed by
+        // those of the second; the indicator (segment sums) and the staged table values (S^T E) are packed in the
+        // same order.  Every value is a bfloat16 value already, every product exact, the sums float32.
+        for (int t = 0; 16 * t < cnt; t += 2) {
+          bf16x8 ia, eb[kNT];
+          {
+            float ov[kNT][4];
+            float ind[4];
+            residual_tile(t, ov, ind);                        // packed at once: one tile of float residuals alive at a time
+#pragma unroll
+            for (int r = 0; r < 4; ++r) ia[r] = (__bf16)ind[r];
+#pragma unroll
+            for (int nt = 0; nt < kNT; ++nt)
+#pragma unroll
+              for (int r = 0; r < 4; ++r) eb[nt][r] = (__bf16)ov[nt][r];
+          }
+          if (16 * (t + 1) < cnt) {
+            float ov[kNT][4];
+            float ind[4];
+            residual_tile(t + 1, ov, ind);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) ia[4 + r] = (__bf16)ind[r];
+#pragma unroll
+            for (int nt = 0; nt < kNT; ++nt)
+#pragma unroll
+              for (int r = 0; r < 4; ++r) eb[nt][4 + r] = (__bf16)ov[nt][r];
+          } else {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) ia[4 + r] = (__bf16)0.0f;
+#pragma unroll
+            for (int nt = 0; nt < kNT; ++nt)
+#pragma unroll
+              for (int r = 0; r < 4; ++r) eb[nt][4 + r] = (__bf16)0.0f;
+          }
 #pragma unroll
           for (int nt = 0; nt < kNT; ++nt)
-            zacc[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(ind[r], ov[nt][r], zacc[nt], 0, 0, 0);
-        const float* acol = As + (size_t)(t * 16 + 4 * q) * lda + li;
+            zacc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ia, eb[nt], zacc[nt], 0, 0, 0);
+          const float* acol = As + (size_t)(t * 16 + 4 * q) * lda + li;
 #pragma unroll
-        for (int jt = 0; jt < JG; ++jt) {
-          if (jt < njt) {
+          for (int jt = 0; jt < JG; ++jt) {
+            if (jt < njt) {
+              bf16x8 sa;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-              float av = acol[(size_t)r * lda + jt * 16];
-              if constexpr (BF16) av = (float)(__bf16)av;     // products of two bfloat16 values are exact in float32
+              for (int r = 0; r < 4; ++r) {
+                sa[r] = (__bf16)acol[(size_t)r * lda + jt * 16];
+                sa[4 + r] = (__bf16)acol[(size_t)(16 + r) * lda + jt * 16];
+              }
 #pragma unroll
               for (int nt = 0; nt < kNT; ++nt)
-                gacc[jt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, ov[nt][r], gacc[jt][nt], 0, 0, 0);
+                gacc[jt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sa, eb[nt], gacc[jt][nt], 0, 0, 0);
             }
           }
         }
