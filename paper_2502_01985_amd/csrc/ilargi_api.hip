@@ -131,6 +131,7 @@ struct ilargi_plan {
   // a second stream for independent blocks of one call (crossprod); NULL: everything runs on the caller's stream
   hipStream_t side = nullptr;
   hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+  bool side_tried = false;   // creating a stream takes milliseconds: done at the first call that wants it
   template <class T> T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
   ~ilargi_plan() {
     for (hipEvent_t e : trace_events) (void)hipEventDestroy(e);
@@ -163,6 +164,29 @@ struct TraceScope {
     else pl->trace_names.pop_back();
   }
 };
+
+// The plan's second stream, created at the first call that can use it (never for a plan on the static scratch array,
+// whose callers must not allocate, and never while `st` is being captured into a graph).  NULL: run on one stream.
+hipStream_t side_stream(ilargi_plan* pl, hipStream_t st) {
+  if (pl->side != nullptr || pl->side_tried || pl->static_dev >= 0) return pl->side;
+  hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(st, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone) {
+    (void)hipGetLastError();
+    return nullptr;                                           // not now; a later eager call may create it
+  }
+  pl->side_tried = true;
+  if (hipStreamCreateWithFlags(&pl->side, hipStreamNonBlocking) != hipSuccess) pl->side = nullptr;
+  if (pl->side != nullptr &&
+      (hipEventCreateWithFlags(&pl->ev_fork, hipEventDisableTiming) != hipSuccess ||
+       hipEventCreateWithFlags(&pl->ev_join, hipEventDisableTiming) != hipSuccess)) {
+    if (pl->ev_fork) (void)hipEventDestroy(pl->ev_fork);
+    pl->ev_fork = nullptr;
+    (void)hipStreamDestroy(pl->side);
+    pl->side = nullptr;
+  }
+  (void)hipGetLastError();
+  return pl->side;
+}
 
 // Rows per workgroup of the narrow column reduce: about kColredTarget chunks, each a whole number of workgroup
 // iterations (so that no iteration runs half empty), never more than kColredBlocks chunks.
@@ -1239,23 +1263,6 @@ ilargi_status_t plan_create_impl(int n, const ilargi_source_t* sources, int64_t 
     HIP_TRY(hipMemcpyAsync(pl->at<GramAsmPair>(lay.o_pairs), pairs.data(), sizeof(GramAsmPair) * pairs.size(), hipMemcpyHostToDevice, st));
   HIP_TRY(hipStreamSynchronize(st));
   pl->static_dev = static_dev;
-  // crossprod of a two-table star join runs the dimension table's Gram block beside the pass over the entity table;
-  // only such plans pay for a second stream (creating one takes milliseconds)
-  const bool wants_side = pl->star_k >= 0 && pl->fused >= 0 && pl->fused < pl->star_k &&
-                          gram_star_supported((int)pl->src[pl->fused].cols);
-  if (static_dev < 0 && wants_side) {
-    // (a plan on the static scratch array is for callers that must not allocate: it creates no stream either)
-    if (hipStreamCreateWithFlags(&pl->side, hipStreamNonBlocking) != hipSuccess) pl->side = nullptr;
-    if (pl->side != nullptr &&
-        (hipEventCreateWithFlags(&pl->ev_fork, hipEventDisableTiming) != hipSuccess ||
-         hipEventCreateWithFlags(&pl->ev_join, hipEventDisableTiming) != hipSuccess)) {
-      if (pl->ev_fork) (void)hipEventDestroy(pl->ev_fork);
-      pl->ev_fork = nullptr;
-      (void)hipStreamDestroy(pl->side);
-      pl->side = nullptr;
-    }
-    (void)hipGetLastError();
-  }
   guard.p = nullptr;
   *plan = pl;
   return ILARGI_OK;
@@ -1779,7 +1786,7 @@ ilargi_status_t ilargi_crossprod(ilargi_plan_t* plan, float* out, void* stream) 
     const SourcePlan& d = plan->src[plan->star_k];
     const int64_t max_grid = std::min<int64_t>(1024, gfloats / 2 / std::max<int64_t>(f.cols * f.cols, 1));
     if (gram_star_supported((int)f.cols) && d.rows * 2 <= plan->r_T && d.rows * f.cols <= plan->lay.zc_floats && max_grid >= 1) {
-      const bool fork = plan->side != nullptr && d.cols * d.cols <= gfloats / 2;
+      const bool fork = d.cols * d.cols <= gfloats / 2 && side_stream(plan, st) != nullptr;
       if (fork) {
         HIP_TRY(hipEventRecord(plan->ev_fork, st));
         part_main_floats = gfloats / 2;
