@@ -278,6 +278,43 @@ def test_wide_product_of_a_joined_table_chunk_and_slab_tails(il, c_R, cx):
 
 
 
+@pytest.mark.parametrize("prec", ["f32", "bf16"])
+@pytest.mark.parametrize("r_R,c_R,cx", [(31, 4, 64), (1_157, 20, 100), (5_003, 100, 256), (2_050, 256, 300),
+                                        (1_024, 204, 68), (4_097, 36, 64)])
+def test_streaming_wide_product_and_column_reduce_tails(il, prec, r_R, c_R, cx):
+    # the streaming kernels of the wide batch (operand slab in LDS, table rows straight into the matrix cores; the
+    # column reduce with its whole result block in registers): table widths of 1 to 16 column groups and ones that
+    # end inside a group or inside a 32-column step, row counts below one tile / one 32-row step and off both,
+    # operand widths that end inside a slab or need a second slab, keys missing, unmapped table columns.  Inputs
+    # are small integers (exact in bfloat16, sums exact in float32), so both precisions must equal the oracle.
+    rng = datagen.rng_for(5200 + c_R + cx)
+    r_T, c_S = 6_011, 8
+    S = rng.integers(-3, 4, (r_T, c_S)).astype(np.float32)
+    R = rng.integers(-3, 4, (r_R, c_R)).astype(np.float32)
+    fk = rng.integers(0, r_R, r_T).astype(np.int32)
+    fk[::13] = -1
+    cm = np.arange(c_S, c_S + c_R, dtype=np.int32)
+    if c_R > 4:
+        cm[2::7] = -1
+        live = cm[cm >= 0]
+        cm[cm >= 0] = c_S + np.arange(live.size, dtype=np.int32)
+        c_T = c_S + live.size
+    else:
+        c_T = c_S + c_R
+    sch = datagen.Schema([datagen.Source(S, None, np.arange(c_S, dtype=np.int32)), datagen.Source(R, fk, cm)], r_T, c_T)
+    tg = oracle.Target(sch)
+    plan = il.ilargi_plan_create(il.schema_to_device(sch), r_T, c_T, max_cx=cx)
+    code = il.F32 if prec == "f32" else il.BF16_IN_F32_ACC
+    X = rng.integers(-2, 3, (c_T, cx)).astype(np.float32)
+    Y = rng.integers(-2, 3, (r_T, cx)).astype(np.float32)
+    got = il.ilargi_lmm(plan, dev(X), precision=code).cpu().numpy()
+    assert np.array_equal(got, oracle.lmm(tg, X).astype(np.float32))
+    got = il.ilargi_tmm(plan, dev(Y), precision=code).cpu().numpy()
+    assert np.array_equal(got, oracle.tmm(tg, Y).astype(np.float32))
+    names = _traced_kernels(il, plan, lambda: il.ilargi_lmm(plan, dev(X), precision=code))
+    assert any(n.startswith("lmm_rows") for n in names), names
+
+
 @pytest.mark.parametrize("name", ["config1_small", "config1_wide_dim", "config3_small", "odd_cols", "tiny_mixed"])
 @pytest.mark.parametrize("cx", [8, 40, 64, 256])
 def test_wide_operands(il, name, cx):
