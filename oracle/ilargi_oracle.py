@@ -281,6 +281,47 @@ def gd(target, model: str, y: np.ndarray, W0: np.ndarray, lr: Sequence[float], i
     return W, np.array(losses)
 
 
+# ----------------------------------------------------------------------------- bfloat16-input variant of Alg. 1
+def round_to_bf16(a: np.ndarray) -> np.ndarray:
+    """Values rounded to the nearest number with 8 significant bits (bfloat16: sign, 8 exponent bits,
+    7 stored mantissa bits), ties to the even neighbour, returned as float64.  Works on the float32 bit
+    pattern: the input is first rounded to float32, as the device holds it."""
+    f32 = np.ascontiguousarray(a, dtype=np.float32)
+    bits = f32.view(np.uint32).astype(np.uint64)
+    bits = (bits + 0x7FFF + ((bits >> 16) & 1)) & 0xFFFF0000
+    return bits.astype(np.uint32).view(np.float32).reshape(f32.shape).astype(np.float64)
+
+
+def gd_bf16_inputs(target, model: str, y: np.ndarray, W0: np.ndarray, lr: Sequence[float], iters: int):
+    """Alg. 1 with both factors of every product rounded to bfloat16 as they enter it and everything else
+    exact: ``z = rd(T) rd(W)``, residual ``e`` (``z - y`` or ``sigmoid(z) - y``) and loss from the unrounded
+    ``z``, gradient ``rd(T)^T rd(e) / r_T``, weights kept unrounded between iterations.  This is the arithmetic
+    of the reduced-precision variant with exact accumulation; it exists to check the tolerance that the tests
+    of that variant use against Alg. 1 in full precision (``gd``).  Returns weights and per-iteration losses."""
+    tg = _as_target(target)
+    W = np.array(W0, dtype=np.float64).reshape(tg.c_T, -1).copy()
+    lr64 = np.asarray(lr, dtype=np.float64).reshape(1, -1)
+    y64 = np.asarray(y, dtype=np.float64).reshape(-1, 1)
+    losses = []
+    for _ in range(iters):
+        Wr = round_to_bf16(W)
+        loss = np.zeros(W.shape[1])
+        grad = np.zeros_like(W)
+        for lo, hi in _chunks(tg.r_T):
+            blk = round_to_bf16(tg.T32[lo:hi])
+            z = blk @ Wr
+            if model == "linear":
+                e = z - y64[lo:hi]
+                loss += 0.5 * np.sum(e * e, axis=0)
+            else:
+                e = _sigmoid(z) - y64[lo:hi]
+                loss += np.sum(_softplus(z) - y64[lo:hi] * z, axis=0)
+            grad += blk.T @ round_to_bf16(e)
+        losses.append(loss / tg.r_T)
+        W -= (grad / tg.r_T) * lr64
+    return W, np.array(losses)
+
+
 # ----------------------------------------------------------------------------- complexity (Tab. 2)
 def complexity_lmm(schema, c_X: int) -> Tuple[int, int]:
     """Tab. 2 row ``T X``: (materialized, factorized) operation counts for dense operands."""

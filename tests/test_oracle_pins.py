@@ -678,3 +678,67 @@ def test_gnmf_zero_rows_and_columns_stay_zero_without_dividing_by_zero():
     W1, H1 = oracle.gnmf_step(tg, W, H)
     assert np.all(np.isfinite(W1)) and np.all(np.isfinite(H1))
     assert np.all(W1[4] == 0.0) and np.all(H1[:, 2] == 0.0)
+
+
+# ------------------------------------------------------------------ bfloat16-input variant of Alg. 1
+def test_round_to_bf16_against_torch_and_hand_values():
+    import torch
+    rng = datagen.rng_for(321)
+    a = np.concatenate([rng.standard_normal(5000) * 10.0 ** rng.integers(-20, 20, 5000),
+                        [0.0, -0.0, 1.0, -1.0, 2.0 ** -126, 3.0e38]]).astype(np.float32)
+    want = torch.from_numpy(a).to(torch.bfloat16).to(torch.float64).numpy()
+    got = oracle.round_to_bf16(a)
+    assert np.array_equal(got, want)
+    # 8 significant bits: neighbours of 1 are 1 - 2^-8 and 1 + 2^-7; ties go to the even mantissa
+    assert oracle.round_to_bf16(np.array([1.0 + 2.0 ** -8]))[0] == 1.0                    # tie, 1.0 is even
+    assert oracle.round_to_bf16(np.array([1.0 + 3 * 2.0 ** -8]))[0] == 1.0 + 2.0 ** -6    # tie, up to the even one
+    assert oracle.round_to_bf16(np.array([1.0 + 2.0 ** -8 + 2.0 ** -20]))[0] == 1.0 + 2.0 ** -7
+    assert oracle.round_to_bf16(np.array([1.0 - 2.0 ** -10]))[0] == 1.0
+    rel_err = np.abs(got - a.astype(np.float64))[a != 0] / np.abs(a.astype(np.float64))[a != 0]
+    assert rel_err.max() <= 2.0 ** -8
+
+
+def test_gd_bf16_inputs_first_step_is_exact_on_representable_inputs():
+    # from w = 0 the first iteration multiplies representable tables by zeros and by -y: no rounding takes place
+    rng = datagen.rng_for(322)
+    sch = datagen.star_schema(rng, 400, 6, [(30, 5, "uniform")])
+    for s in sch.sources:
+        s.D[...] = oracle.round_to_bf16(s.D).astype(np.float32)
+    tg = oracle.Target(sch)
+    y = oracle.round_to_bf16(rng.standard_normal(sch.r_T))
+    W1, L1 = oracle.gd(tg, "linear", y, np.zeros((sch.c_T, 2)), [0.1, 0.3], 1)
+    W2, L2 = oracle.gd_bf16_inputs(tg, "linear", y, np.zeros((sch.c_T, 2)), [0.1, 0.3], 1)
+    np.testing.assert_allclose(W2, W1, rtol=1e-13, atol=0)
+    np.testing.assert_allclose(L2, L1, rtol=1e-13)
+    # a second iteration multiplies by weights that are no bfloat16 numbers: the two differ, by no more than a few u
+    W1, _ = oracle.gd(tg, "linear", y, np.zeros((sch.c_T, 2)), [0.1, 0.3], 2)
+    W2, _ = oracle.gd_bf16_inputs(tg, "linear", y, np.zeros((sch.c_T, 2)), [0.1, 0.3], 2)
+    d = np.linalg.norm(W2 - W1) / np.linalg.norm(W1)
+    assert 1e-6 < d < 2.0 ** -6
+
+
+@pytest.mark.parametrize("model", ["linear", "logistic"])
+@pytest.mark.parametrize("shape", [(5_003, 20, 501, 24, "uniform", 8, 5e-2), (5_003, 3, 200, 24, "uniform", 8, 5e-2),
+                                   (5_003, 64, 16, 24, "uniform", 8, 5e-2), (5_003, 50, 333, 24, ("zipf", 1.05), 8, 5e-2),
+                                   (20_000, 20, 2_000, 200, "uniform", 20, 1.0), (20_000, 20, 2_000, 200, "uniform", 50, 0.7)])
+def test_bf16_gd_weight_tolerance_holds_for_the_emulated_arithmetic(model, shape):
+    # the derived bound (tests/tolerances.py) against Alg. 1 with rounded product inputs and exact accumulation,
+    # on the kinds of schema the device tests of the reduced-precision variant use; the rounding is visible
+    # (error above a hundredth of the bound) and within it
+    from tolerances import bf16_gd_weight_tol, lambda_max
+    r_S, c_S, r_R, c_R, keys, iters, lr_hi = shape
+    rng = datagen.rng_for(323 + c_S + iters)
+    sch = datagen.star_schema(rng, r_S, c_S, [(r_R, c_R, keys)])
+    tg = oracle.Target(sch)
+    w_star = rng.standard_normal(sch.c_T) / np.sqrt(sch.c_T)
+    y = datagen.finish_labels(model, oracle.lmm(tg, w_star.reshape(-1, 1)), 0.01 * rng.standard_normal(sch.r_T))
+    lam = lambda_max(oracle.crossprod(tg), sch.r_T)
+    lrs = np.geomspace(1e-3, lr_hi, 6)
+    if lrs[-1] * lam >= 1.9:
+        lrs = lrs * (1.9 / (lrs[-1] * lam))
+    W, _ = oracle.gd(tg, model, y, np.zeros((sch.c_T, len(lrs))), lrs, iters)
+    Wb, _ = oracle.gd_bf16_inputs(tg, model, y, np.zeros((sch.c_T, len(lrs))), lrs, iters)
+    for j, lr in enumerate(lrs):
+        err = np.linalg.norm(Wb[:, j] - W[:, j]) / np.linalg.norm(W[:, j])
+        tol = bf16_gd_weight_tol(iters, sch.c_T, sch.r_T, lr, lam)
+        assert tol / 100 < err < tol, (j, lr, err, tol)
