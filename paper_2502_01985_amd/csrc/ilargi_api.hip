@@ -703,10 +703,63 @@ ilargi_status_t tmm_wide(ilargi_plan* pl, const float* Y, int cx, float* out, in
     worst += 1024 * pl->src[k].cols * cx;
   }
   if (worst > pl->lay.gpartial_floats) defer = false;
+  auto join_args = [&](const SourcePlan& p, float* part) {
+    TmmJoinArgs j;
+    memset(&j, 0, sizeof(j));
+    j.D = p.D; j.ck = (int)p.cols; j.r_k = p.rows;
+    j.rowptr = pl->at<int32_t>(p.o_rowptr); j.perm = pl->at<int32_t>(p.o_perm);
+    j.Y = Y; j.ldy = cx; j.col0 = 0; j.c = cx;
+    j.partial = part;
+    return j;
+  };
+  auto flat_args = [&](const SourcePlan& p, float* part) {
+    ColredFlatArgs f;
+    memset(&f, 0, sizeof(f));
+    f.S = p.D; f.rows = p.rows; f.nvec = (int)(p.cols / 4);
+    f.Y = Y; f.ldy = cx; f.c = cx;
+    f.partial = part;
+    return f;
+  };
+  // The first identity source that takes the flat column reduce and the first joined source that takes the
+  // join-order pass share a launch (the streaming part fills the gaps the gathers of the other leave).
+  int pair_f = -1, pair_j = -1;
+  float* pair_part[2] = {nullptr, nullptr};
+  int pair_grid[2] = {0, 0};
+  if (defer) {
+    for (int k = 0; k < pl->n; ++k) {
+      if (pl->src[k].empty || k == done_k) continue;
+      const int rt = route(pl->src[k]);
+      if (rt == 2 && pair_f < 0) pair_f = k;
+      if (rt == 1 && pair_j < 0) pair_j = k;
+    }
+    if (pair_f < 0 || pair_j < 0 ||
+        !tmm_pair_supported(flat_args(pl->src[pair_f], nullptr), join_args(pl->src[pair_j], nullptr)))
+      pair_f = pair_j = -1;
+  }
   int64_t part_off = 0;
   for (int k = 0; k < pl->n; ++k) {
     SourcePlan& p = pl->src[k];
     if (p.empty) continue;
+    if (pair_f >= 0 && (k == pair_f || k == pair_j)) {
+      if (pair_part[0] == nullptr) {
+        const SourcePlan& pf = pl->src[pair_f];
+        const SourcePlan& pj = pl->src[pair_j];
+        const int64_t room_f = 1024 * pf.cols * cx, room_j = 1024 * pj.cols * cx;     // within `worst`
+        pair_part[0] = pl->at<float>(pl->lay.o_gpartial) + part_off;
+        pair_part[1] = pair_part[0] + room_f;
+        part_off += room_f + room_j;
+        TraceScope ts(pl, "colred+join", pair_f, st);
+        HIP_TRY(launch_tmm_pair(flat_args(pf, pair_part[0]), join_args(pj, pair_part[1]), pj.nnz, room_f, room_j, st,
+                                &pair_grid[0], &pair_grid[1]));
+      }
+      const int w = k == pair_f ? 0 : 1;
+      c.tcol2src[c.n] = pl->at<int32_t>(p.o_tcol);
+      c.ck[c.n] = (int)p.cols;
+      c.G[c.n] = pair_part[w];
+      c.nparts[c.n] = pair_grid[w];
+      ++c.n;
+      continue;
+    }
     if (k == done_k) {
       c.tcol2src[c.n] = pl->at<int32_t>(p.o_tcol);
       c.G[c.n] = pl->at<float>(p.o_g);
@@ -727,22 +780,13 @@ ilargi_status_t tmm_wide(ilargi_plan* pl, const float* Y, int cx, float* out, in
       if (rt == 1) {
         // segment sums and D_k^T Z_k in one pass in join order: Z_k is never written (operands whose rows are
         // whole float4s; for the others the two-step form measures the same or better)
-        TmmJoinArgs j;
-        memset(&j, 0, sizeof(j));
-        j.D = p.D; j.ck = (int)p.cols; j.r_k = p.rows;
-        j.rowptr = pl->at<int32_t>(p.o_rowptr); j.perm = pl->at<int32_t>(p.o_perm);
-        j.Y = Y; j.ldy = cx; j.col0 = 0; j.c = cx;
-        j.partial = part;
+        const TmmJoinArgs j = join_args(p, part);
         TraceScope ts(pl, "tmm_join", k, st);
         HIP_TRY(launch_tmm_join(j, room, st, &grid));
       } else {
         // short rows of an identity source, operand rows of whole float4s: flat float4 stream with plain FMAs
         // instead of padded matrix-core tiles (with element-wise operand loads the matrix-core form measures faster)
-        ColredFlatArgs f;
-        memset(&f, 0, sizeof(f));
-        f.S = p.D; f.rows = p.rows; f.nvec = (int)(p.cols / 4);
-        f.Y = Y; f.ldy = cx; f.c = cx;
-        f.partial = part;
+        const ColredFlatArgs f = flat_args(p, part);
         TraceScope ts(pl, "colred", k, st);
         HIP_TRY(launch_colred_flat(f, room, st, &grid));
       }

@@ -365,6 +365,11 @@ struct ColredFlatArgs {
 };
 bool colred_flat_supported(const float* S, int64_t cols, int c);
 hipError_t launch_colred_flat(const ColredFlatArgs& a, int64_t partial_floats, hipStream_t st, int* grid_out);
+// The flat column reduce of an identity source and the join-order pass of a joined source (nnz_j index entries) in one
+// launch; *grid_f and *grid_j workgroups leave partial blocks in f.partial and j.partial.
+bool tmm_pair_supported(const ColredFlatArgs& f, const TmmJoinArgs& j);
+hipError_t launch_tmm_pair(const ColredFlatArgs& f, const TmmJoinArgs& j, int64_t nnz_j, int64_t room_f, int64_t room_j,
+                           hipStream_t st, int* grid_f, int* grid_j);
 // tcols > 0: the summed (elems / tcols) x tcols matrix is written transposed
 hipError_t launch_tred_reduce(const float* partial, int nchunks, int64_t elems, float* block, hipStream_t st, int tcols = 0);
 hipError_t launch_colasm(const ColAsmArgs& a, int mode, hipStream_t st);

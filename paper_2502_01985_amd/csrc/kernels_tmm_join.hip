@@ -15,6 +15,7 @@
 #include <type_traits>
 
 #include "ilargi_internal.h"
+#include "colred_flat_body.h"
 
 namespace ilargi {
 
@@ -38,8 +39,7 @@ constexpr int kTjWaveFloats = kTjST * kTjLdy + 2 * kTjST + 64;
 // tile 4 g + t holding the columns 64 g + 4 li + t, so that the values a lane needs of one table row for the four
 // tiles of a group are one float4 (16 lanes read 256 contiguous bytes) instead of four separate floats.
 template <int NTR, bool VEC4, bool DV4>
-__global__ __launch_bounds__(kBlock) void tmm_join_kernel(TmmJoinArgs a, int rtiles) {
-  extern __shared__ float lds[];
+__device__ __forceinline__ void tmm_join_body(const TmmJoinArgs& a, int rtiles, float* lds, int bid, int nblocks) {
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
   const int li = lane % 16, q = lane / 16;
   float* wbase = lds + (size_t)wave * kTjWaveFloats;
@@ -62,8 +62,8 @@ __global__ __launch_bounds__(kBlock) void tmm_join_kernel(TmmJoinArgs a, int rti
   // A wavefront walks its tiles with the memory chain of the next tile already under way: the row pointers of a
   // tile are requested two tiles ahead, the target rows of its first two batches one tile ahead, and the rows of Y
   // of its first batch while the last batch of the tile before it is on the matrix cores.
-  const int tstride = gridDim.x * kTjWavesPerBlock;
-  int rt = blockIdx.x * kTjWavesPerBlock + wave;
+  const int tstride = nblocks * kTjWavesPerBlock;
+  int rt = bid * kTjWavesPerBlock + wave;
   // lane l <= 16 holds row pointer l of a tile (0 for a tile beyond the table: an empty range)
   auto load_rp = [&](int t) -> int {
     return (t < rtiles && lane <= 16) ? a.rowptr[min((int64_t)t * 16 + lane, a.r_k)] : 0;
@@ -204,14 +204,37 @@ __global__ __launch_bounds__(kBlock) void tmm_join_kernel(TmmJoinArgs a, int rti
     }
   }
   __syncthreads();
-  float* gp = a.partial + (int64_t)blockIdx.x * a.ck * a.c;
+  float* gp = a.partial + (int64_t)bid * a.ck * a.c;
   for (int e = tid; e < a.ck * a.c; e += kBlock) {
     const int j = e / a.c, n = e - j * a.c;
     gp[e] = red[j * 16 + n];
   }
 }
 
+template <int NTR, bool VEC4, bool DV4>
+__global__ __launch_bounds__(kBlock) void tmm_join_kernel(TmmJoinArgs a, int rtiles) {
+  extern __shared__ float lds[];
+  tmm_join_body<NTR, VEC4, DV4>(a, rtiles, lds, (int)blockIdx.x, (int)gridDim.x);
+}
+
+// The join-order pass of a joined source and the flat column reduce of an identity source in ONE launch: the two
+// are independent parts of the same transposed multiply, the first bound by the latency of its gathers, the second
+// a plain stream.  Workgroups are dealt to the eight XCDs in turn, so roles are given to groups of eight consecutive
+// workgroups: every XCD then runs the same mix.  Of the (n_f + n_j) / 8 groups, n_f / 8 are dealt evenly among the
+// others and run the column reduce (group g is the a(g)-th of them when a(g + 1) > a(g), a(g) = floor(g n_f / (n_f + n_j))).
+// n_f and n_j are multiples of 8.
+template <int NTR, bool DV4, int CMAX>
+__global__ __launch_bounds__(kBlock) void tmm_pair_kernel(TmmJoinArgs j, int rtiles, ColredFlatArgs f, int n_f, int n_j) {
+  extern __shared__ float lds[];
+  const int64_t g = blockIdx.x / 8, nt = (int64_t)n_f + n_j;
+  const int x = blockIdx.x % 8;
+  const int a0 = (int)(g * n_f / nt), a1 = (int)((g + 1) * n_f / nt);
+  if (a1 > a0) colred_flat_body<CMAX, true>(f, lds, 8 * a0 + x, n_f);
+  else tmm_join_body<NTR, true, DV4>(j, rtiles, lds, (int)(8 * (g - a0) + x), n_j);
+}
+
 typedef void (*TjFn)(TmmJoinArgs, int);
+typedef void (*TpFn)(TmmJoinArgs, int, ColredFlatArgs, int, int);
 
 template <int NTR, bool DV4>
 TjFn pick_tj(bool vec4) { return vec4 ? tmm_join_kernel<NTR, true, DV4> : tmm_join_kernel<NTR, false, DV4>; }
@@ -266,6 +289,72 @@ hipError_t launch_tmm_join(const TmmJoinArgs& a, int64_t partial_floats, hipStre
   if (gx < 1) return hipErrorInvalidValue;
   if (grid_out) *grid_out = (int)gx;
   hipLaunchKernelGGL(fn, dim3((unsigned)gx), dim3(kBlock), lds_bytes, st, a, rtiles);
+  return hipGetLastError();
+}
+
+// Both parts in one launch (operands of 8, 12 or 16 columns whose rows are whole aligned float4s).  The split of
+// the resident workgroups follows the bytes each part has to move (measured on a star join of 10^6 x 20 and
+// 10^5 x 200: within 4 % of the best split for 8, 12 and 16 operand columns).
+bool tmm_pair_supported(const ColredFlatArgs& f, const TmmJoinArgs& j) {
+  if (!tmm_join_supported(j.ck, j.c) || !colred_flat_supported(f.S, 4 * (int64_t)f.nvec, f.c)) return false;
+  if (f.c != j.c || f.c % 4 != 0 || j.col0 != 0 || j.ldy % 4 != 0 || f.ldy % 4 != 0) return false;
+  if (reinterpret_cast<uintptr_t>(j.Y) % 16 != 0 || reinterpret_cast<uintptr_t>(f.Y) % 16 != 0) return false;
+  if (j.ck % 4 != 0 || reinterpret_cast<uintptr_t>(j.D) % 16 != 0) return false;
+  // at least eight workgroups' worth of work on either side (roles go to groups of eight workgroups)
+  const int64_t fsteps = (f.rows + kWave / f.nvec - 1) / (kWave / f.nvec);
+  return (j.r_k + 15) / 16 >= 8 * kTjWavesPerBlock && fsteps >= 16 * kTjWavesPerBlock;
+}
+
+hipError_t launch_tmm_pair(const ColredFlatArgs& f, const TmmJoinArgs& j, int64_t nnz_j, int64_t room_f, int64_t room_j,
+                           hipStream_t st, int* grid_f, int* grid_j) {
+  *grid_f = *grid_j = 0;
+  if (!tmm_pair_supported(f, j)) return hipErrorInvalidValue;
+  const int rtiles = (int)((j.r_k + 15) / 16);
+  const int ntr = (j.ck + 15) / 16;
+  const int ntr_c = ntr <= 4 ? 4 : (ntr <= 8 ? 8 : 16);
+  const int cmax = f.c <= 8 ? 8 : 16;
+  TpFn fn;
+  if (cmax == 8) fn = ntr_c == 4 ? tmm_pair_kernel<4, true, 8> : (ntr_c == 8 ? tmm_pair_kernel<8, true, 8> : tmm_pair_kernel<16, true, 8>);
+  else fn = ntr_c == 4 ? tmm_pair_kernel<4, true, 16> : (ntr_c == 8 ? tmm_pair_kernel<8, true, 16> : tmm_pair_kernel<16, true, 16>);
+  size_t lds_floats = std::max<size_t>((size_t)kTjWavesPerBlock * kTjWaveFloats, (size_t)ntr_c * 256);
+  lds_floats = std::max<size_t>(lds_floats, (size_t)colred_flat_lds_floats(cmax));
+  const size_t lds_bytes = lds_floats * sizeof(float);
+  static std::mutex cache_mutex;
+  static TpFn seen_fn[8];
+  static int seen_slots[8];
+  static int n_seen = 0;
+  int slots = 0;
+  {
+    std::lock_guard<std::mutex> lock(cache_mutex);
+    for (int i = 0; i < n_seen; ++i)
+      if (seen_fn[i] == fn) slots = seen_slots[i];
+    if (slots == 0) {
+      int dev = 0, cus = 256, per_cu = 0;
+      hipDeviceProp_t prop;
+      if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess && prop.multiProcessorCount > 0)
+        cus = prop.multiProcessorCount;
+      if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(fn), kBlock, lds_bytes) != hipSuccess ||
+          per_cu < 1)
+        per_cu = 1;
+      slots = per_cu * cus;
+      if (n_seen < 8) { seen_fn[n_seen] = fn; seen_slots[n_seen] = slots; ++n_seen; }
+    }
+  }
+  const double bytes_f = 4.0 * (double)f.rows * (4 * f.nvec + f.c);
+  const double bytes_j = 4.0 * (double)j.r_k * j.ck + (double)nnz_j * (4.0 + 4.0 * j.c);
+  const double share = bytes_f / (bytes_f + bytes_j);
+  int n_f = (int)(slots * share + 0.5);
+  n_f = std::max(1, std::min(n_f, slots - 1));
+  int n_j = slots - n_f;
+  n_j = (int)std::min<int64_t>(n_j, (rtiles + kTjWavesPerBlock - 1) / kTjWavesPerBlock);
+  const int64_t fsteps = (f.rows + kWave / f.nvec - 1) / (kWave / f.nvec);
+  n_f = (int)std::min<int64_t>(n_f, (fsteps + 2 * kTjWavesPerBlock - 1) / (2 * kTjWavesPerBlock));
+  n_f = (int)std::min<int64_t>(n_f, room_f / ((int64_t)4 * f.nvec * f.c));
+  n_j = (int)std::min<int64_t>(n_j, room_j / ((int64_t)j.ck * j.c));
+  n_f = n_f / 8 * 8; n_j = n_j / 8 * 8;
+  if (n_f < 8 || n_j < 8) return hipErrorInvalidValue;
+  *grid_f = n_f; *grid_j = n_j;
+  hipLaunchKernelGGL(fn, dim3((unsigned)(n_f + n_j)), dim3(kBlock), lds_bytes, st, j, rtiles, f, n_f, n_j);
   return hipGetLastError();
 }
 

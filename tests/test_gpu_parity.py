@@ -232,6 +232,38 @@ def test_transposed_multiply_of_a_short_row_entity_table(il, c_S, cx):
     assert np.array_equal(G1, il.ilargi_tmm(plan, dev(Y)).cpu().numpy())
 
 
+@pytest.mark.parametrize("cx", [8, 12, 16])
+@pytest.mark.parametrize("c_S,r_R,c_R", [(20, 1_001, 36), (64, 517, 208), (4, 2_000, 100), (12, 8_000, 64)])
+def test_transposed_multiply_with_the_flat_reduce_and_the_join_order_pass_in_one_launch(il, c_S, r_R, c_R, cx):
+    # identity source with short rows + joined source, operands of whole float4 rows: both parts share a launch
+    # (roles dealt to groups of eight workgroups).  Ragged row tiles on both sides, 3 / 13 / 7 / 4 column tiles of
+    # the joined table, keys that are missing (-1), rows of the joined table nobody joins (r_R = 8000 > r_T), a
+    # third source whose join-order pass runs in a launch of its own; results repeat bit for bit
+    rng = datagen.rng_for(5300 + c_S + cx)
+    r_T, r_Q, c_Q = 7_003, 701, 24
+    S = rng.standard_normal((r_T, c_S)).astype(np.float32)
+    R = rng.standard_normal((r_R, c_R)).astype(np.float32)
+    Q = rng.standard_normal((r_Q, c_Q)).astype(np.float32)
+    fk = rng.integers(0, r_R, r_T).astype(np.int32)
+    fk[::23] = -1
+    fq = rng.integers(0, r_Q, r_T).astype(np.int32)
+    c_T = c_S + c_R + c_Q
+    sch = datagen.Schema([datagen.Source(S, None, np.arange(c_S, dtype=np.int32)),
+                          datagen.Source(R, fk, np.arange(c_S, c_S + c_R, dtype=np.int32)),
+                          datagen.Source(Q, fq, np.arange(c_S + c_R, c_T, dtype=np.int32))], r_T, c_T)
+    tg = oracle.Target(sch)
+    plan = il.ilargi_plan_create(il.schema_to_device(sch), r_T, c_T, max_cx=16)
+    Y = rng.standard_normal((r_T, cx)).astype(np.float32)
+    il.ilargi_plan_trace_begin(plan, "*", 16)
+    G1 = il.ilargi_tmm(plan, dev(Y)).cpu().numpy()
+    _, names = il.ilargi_plan_trace_end(plan, 16, names=True)
+    assert any(n.startswith("colred+join") for n in names), names
+    want = oracle.tmm(tg, Y)
+    assert rel(G1, want) < OP_TOL
+    assert_each_element(G1, want, tg.T32.T, Y)
+    assert np.array_equal(G1, il.ilargi_tmm(plan, dev(Y)).cpu().numpy())
+
+
 @pytest.mark.parametrize("cx", [8, 13, 17, 32])
 @pytest.mark.parametrize("c_R", [64, 100, 260, 516])
 def test_transposed_multiply_of_a_wide_joined_table_with_few_operand_columns(il, c_R, cx):
