@@ -429,9 +429,8 @@ ilargi_status_t lmm_pass(ilargi_plan* pl, const float* X, int ldx, int col0, int
   GatherArgs g;
   memset(&g, 0, sizeof(g));
   g.ldp = ldx;
-  for (int k = 0; k < pl->n; ++k) {
-    SourcePlan& p = pl->src[k];
-    if (p.empty || k == pl->fused) continue;
+  auto product_args = [&](int k) {
+    const SourcePlan& p = pl->src[k];
     LmmArgs a;
     memset(&a, 0, sizeof(a));
     a.D = p.D; a.d_rows = p.rows; a.ck = (int)p.cols; a.colmap = pl->at<int32_t>(p.o_colmap);
@@ -439,7 +438,36 @@ ilargi_status_t lmm_pass(ilargi_plan* pl, const float* X, int ldx, int col0, int
     a.out = pl->at<float>(p.o_pz); a.ldo = ldx; a.r_out = p.rows;
     a.logL = pick_logL(p.cols, p.vec);
     a.scratch = pl->at<float>(pl->lay.o_gpartial); a.scratch_floats = pl->lay.gpartial_floats;   // free until the assembly
-    {
+    return a;
+  };
+  // Narrow operands: when two or more dense sources can take the streaming product kernel, their products share
+  // one launch (a plan with several dimension tables otherwise pays a launch per table for a few microseconds of work).
+  bool product_done[kMaxSources] = {};
+  if (!wide) {
+    int ks[kMaxSources], nk = 0;
+    for (int k = 0; k < pl->n; ++k) {
+      const SourcePlan& p = pl->src[k];
+      if (p.empty || k == pl->fused || p.sparse) continue;
+      if (rowdot_supported(product_args(k), p.vec)) ks[nk++] = k;
+    }
+    for (int i0 = 0; nk >= 2 && i0 < nk; i0 += kRowdotMulti) {
+      LmmArgs multi[kRowdotMulti];
+      int vecs[kRowdotMulti];
+      const int cnt = std::min(kRowdotMulti, nk - i0);
+      for (int i = 0; i < cnt; ++i) {
+        multi[i] = product_args(ks[i0 + i]);
+        vecs[i] = pl->src[ks[i0 + i]].vec;
+        product_done[ks[i0 + i]] = true;
+      }
+      TraceScope ts(pl, "lmm_rows", ks[i0], st);
+      HIP_TRY(launch_rowdot_multi(multi, vecs, cnt, st));
+    }
+  }
+  for (int k = 0; k < pl->n; ++k) {
+    SourcePlan& p = pl->src[k];
+    if (p.empty || k == pl->fused) continue;
+    if (!product_done[k]) {
+      const LmmArgs a = product_args(k);
       TraceScope ts(pl, "lmm_rows", k, st);
       if (p.sparse) HIP_TRY(launch_spmm_rows(sparse_args(pl, k), X, ldx, col0, ncols, pl->at<float>(p.o_pz), ldx, st));
       else if (wide) HIP_TRY(launch_lmm_mfma(a, p.vec, 0, bf16, st, nullptr));
@@ -535,6 +563,37 @@ ilargi_status_t tmm_pass(ilargi_plan* pl, const float* Y, int ldy, int col0, int
     parts_first_k = -1; parts_joins = 0;
     return ILARGI_OK;
   };
+  // Large target table: the per-slice sums over the sliced indices of all such sources run as one launch (and the
+  // sums over the slices as another); the sources then take part in the column reduce with Z_k as a plain operand.
+  bool z_ready[kMaxSources] = {};
+  {
+    SegArgs multi[kSegMulti];
+    int nm = 0, first_k = -1;
+    auto flush_multi = [&]() -> ilargi_status_t {
+      if (nm == 0) return ILARGI_OK;
+      TraceScope ts(pl, "segsum", first_k, st);
+      HIP_TRY(launch_segsum_sliced(multi, nm, st));
+      nm = 0; first_k = -1;
+      return ILARGI_OK;
+    };
+    for (int k = 0; k < pl->n && Y != nullptr; ++k) {
+      const SourcePlan& p = pl->src[k];
+      if (p.empty || k == done_k || p.ident || !p.sliced) continue;
+      if (!p.sparse) {
+        SegArgs sg = segsum_args(k);
+        if (tmm_part_supported(colred_args(k, nullptr, 0, 0), &sg)) continue;      // join-order form: no Z_k
+      }
+      if (nm == kSegMulti) {
+        ilargi_status_t rc = flush_multi();
+        if (rc != ILARGI_OK) return rc;
+      }
+      if (nm == 0) first_k = k;
+      multi[nm++] = segsum_args(k);
+      z_ready[k] = true;
+    }
+    ilargi_status_t rc = flush_multi();
+    if (rc != ILARGI_OK) return rc;
+  }
   for (int k = 0; k < pl->n; ++k) {
     SourcePlan& p = pl->src[k];
     if (p.empty) continue;
@@ -551,8 +610,9 @@ ilargi_status_t tmm_pass(ilargi_plan* pl, const float* Y, int ldy, int col0, int
     ColredArgs c;
     bool merged = false;
     if (!p.sparse) {
-      const bool direct = Y == nullptr || p.ident;
-      c = direct ? (Y == nullptr ? colred_args(k, pl->at<float>(p.o_cnt), 1, 0) : colred_args(k, Y, ldy, col0))
+      const bool direct = Y == nullptr || p.ident || z_ready[k];
+      c = direct ? (Y == nullptr ? colred_args(k, pl->at<float>(p.o_cnt), 1, 0)
+                                 : (z_ready[k] ? colred_args(k, pl->at<float>(p.o_pz), ldy, col0) : colred_args(k, Y, ldy, col0)))
                  : colred_args(k, nullptr, 0, 0);
       SegArgs sg;
       memset(&sg, 0, sizeof(sg));
@@ -579,12 +639,7 @@ ilargi_status_t tmm_pass(ilargi_plan* pl, const float* Y, int ldy, int col0, int
         c = colred_args(k, pl->at<float>(p.o_cnt), 1, 0);
       } else if (p.ident) {
         c = colred_args(k, Y, ldy, col0);
-      } else if (p.sliced) {
-        // large target table: per-slice sums over the sliced index, added by the column reduce
-        {
-          TraceScope ts(pl, "segsum", k, st);
-          HIP_TRY(launch_segsum_sliced(segsum_args(k), st));
-        }
+      } else if (z_ready[k]) {
         c = colred_args(k, pl->at<float>(p.o_pz), ldy, col0);
       } else {
         {

@@ -155,6 +155,30 @@ struct SegArgs {
   float* Zs;                   // [kSegSlices][r_k][CT] per-slice sums of the short runs
 };
 
+// Plain per-source products P_k = D_k (M_k^T X) of several sources in one launch (kernels_lmm.hip).
+constexpr int kRowdotMulti = 4;
+struct RowdotArgs {
+  const float* D; int ck; int64_t rows;
+  const int32_t* colmap;
+  const float* X; int ldx, col0, ncols;
+  float* out; int ldo;
+  int logL, vw;                // lanes per row (log2), floats per vector load (4 or 2)
+};
+struct RowdotMulti {
+  int n;
+  int first[kRowdotMulti + 1];
+  RowdotArgs a[kRowdotMulti];
+};
+
+// Sliced segment sums of several sources in one launch (kernels_tmm.hip).
+constexpr int kSegMulti = 4;
+struct SegMulti {
+  int n;
+  int first[kSegMulti + 1];    // workgroups [first[q], first[q + 1]) of the sum kernel serve source q (multiples of kSegSlices)
+  int cfirst[kSegMulti + 1];   // ... of the kernel that adds the per-slice sums
+  SegArgs s[kSegMulti];
+};
+
 struct ColredArgs {
   const float* D;
   int64_t rows;
@@ -299,6 +323,10 @@ size_t sort_hist_ints(int64_t r_T);
 void launch_exclusive_scan(int32_t* a, int64_t n, int32_t* totals, hipStream_t st);
 
 hipError_t launch_lmm_rows(const LmmArgs& a, int vec, int mode, hipStream_t st, int* grid_out);
+// The streaming product kernel: dense table, at most four operand columns, rows of aligned vectors of vec = 4 or 2
+// floats; the products of up to kRowdotMulti sources (same operand columns) can share one launch.
+bool rowdot_supported(const LmmArgs& a, int vec);
+hipError_t launch_rowdot_multi(const LmmArgs* a, const int* vec, int n, hipStream_t st);
 int lmm_grid(int64_t r_out, int logL, bool fuseg);
 bool lmm_can_fuse_gradient(int ck, int vec, int logL);
 MfmaShape lmm_mfma_shape(int ck, int nt, bool gathers, bool bf16);
@@ -334,7 +362,9 @@ hipError_t launch_build_sliced_index(const int32_t* rowptr, const int32_t* perm,
                                      int32_t* sl_rowptr, int32_t* sl_perm, int32_t* sl_chunk0, int32_t* ch_beg, int32_t* ch_end,
                                      int32_t* sl_nchunk, int cap, int32_t* src_beg, int32_t* scan_scratch, hipStream_t st);
 int64_t segsum_sliced_chunk_cap(int64_t nnz);
-hipError_t launch_segsum_sliced(const SegArgs& a, hipStream_t st);
+// n <= kSegMulti sources with the same number of operand columns; their sums and the sums over slices run as one
+// launch each.
+hipError_t launch_segsum_sliced(const SegArgs* a, int n, hipStream_t st);
 hipError_t launch_colred(const ColredArgs& a, int nblocks, hipStream_t st);
 bool lmm_flat_supported(const LmmArgs& a, int vec, bool fuseg);
 hipError_t launch_lmm_flat(const LmmArgs& a, int mode, bool fuseg, hipStream_t st, int* grid_out);

@@ -13,6 +13,9 @@
 //   row mapping     thread t owns row t of the step: it loads row_idx (coalesced), gathers the P_k rows, adds
 //                   the dot product from LDS, applies the epilogue and stores (coalesced).
 // The row indices of the next step are prefetched while the current step computes.
+#include <cstring>
+#include <type_traits>
+
 #include "ilargi_internal.h"
 
 namespace ilargi {
@@ -292,61 +295,74 @@ hipError_t launch_mode(const LmmArgs& a, int mode, bool fuseg, int grid, size_t 
   return hipGetLastError();
 }
 
-// Plain product  P = D (M^T X)  for at most four operand columns, float4 rows of at most 64 float4: the role of the
-// kernel above without gathers and epilogues, as a streaming kernel without LDS or workgroup barriers.
-// L = 2^k >= ck / 4 lanes share a row (a wavefront load covers 64 / L whole rows), eight loads per lane are in
+// Plain product  P = D (M^T X)  for at most four operand columns, rows of at most 64 aligned vectors of VW = 4 or 2
+// floats: the role of the kernel above without gathers and epilogues, as a streaming kernel without LDS or
+// workgroup barriers.
+// L = 2^k >= ck / VW lanes share a row (a wavefront load covers 64 / L whole rows), eight loads per lane are in
 // flight, each lane keeps its operand values in registers.  The eight partial sums of a lane are reduced across
 // the L lanes with a butterfly that halves the number of live values at each of its first three steps (a lane
 // pair exchanges one half of the values each way), ten shuffles per operand column instead of forty-eight.
+// Several sources may share a launch: workgroup `bid` of the `nblocks` that serve this source.
 constexpr int kDotU = 8;
 
-template <int CT>
-__global__ __launch_bounds__(kBlock) void lmm_rowdot_kernel(LmmArgs a, int logL) {
+template <int CT, int VW>
+__device__ __forceinline__ void lmm_rowdot_body(const RowdotArgs& a, int bid, int nblocks) {
+  typedef typename std::conditional<VW == 4, float4, float2>::type Vec;
+  const int logL = a.logL;
   const int tid = threadIdx.x, lane = tid % kWave;
   const int L = 1 << logL;                                   // 8 <= L <= 64
-  const int cg = lane & (L - 1);                             // float4 column group of this lane
+  const int cg = lane & (L - 1);                             // vector column group of this lane
   const int sub = lane >> logL;                              // row of the wavefront load
   const int rp = kWave >> logL;                              // rows per wavefront load
-  const int nvec = a.ck / 4;
-  float4 x[CT];
+  const int nvec = a.ck / VW;
+  float x[CT][VW];
 #pragma unroll
-  for (int n = 0; n < CT; ++n) x[n] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+  for (int n = 0; n < CT; ++n)
+#pragma unroll
+    for (int e = 0; e < VW; ++e) x[n][e] = 0.0f;
   if (cg < nvec) {
-    int t[4];
+    int t[VW];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) t[e] = a.colmap[4 * cg + e];
+    for (int e = 0; e < VW; ++e) t[e] = a.colmap[VW * cg + e];
 #pragma unroll
     for (int n = 0; n < CT; ++n) {
       if (n < a.ncols) {
-        x[n].x = t[0] >= 0 ? a.X[(int64_t)t[0] * a.ldx + a.col0 + n] : 0.0f;
-        x[n].y = t[1] >= 0 ? a.X[(int64_t)t[1] * a.ldx + a.col0 + n] : 0.0f;
-        x[n].z = t[2] >= 0 ? a.X[(int64_t)t[2] * a.ldx + a.col0 + n] : 0.0f;
-        x[n].w = t[3] >= 0 ? a.X[(int64_t)t[3] * a.ldx + a.col0 + n] : 0.0f;
+#pragma unroll
+        for (int e = 0; e < VW; ++e) x[n][e] = t[e] >= 0 ? a.X[(int64_t)t[e] * a.ldx + a.col0 + n] : 0.0f;
       }
     }
   }
   const int64_t rows_per_step = (int64_t)rp * kDotU;
-  const int64_t wave0 = ((int64_t)blockIdx.x * (kBlock / kWave) + tid / kWave) * rows_per_step;
-  const int64_t stride = (int64_t)gridDim.x * (kBlock / kWave) * rows_per_step;
+  const int64_t wave0 = ((int64_t)bid * (kBlock / kWave) + tid / kWave) * rows_per_step;
+  const int64_t stride = (int64_t)nblocks * (kBlock / kWave) * rows_per_step;
   // which of the eight rows of a step this lane reports after the reduction: bits of the lane number at the
   // three halving steps (offsets L/2, L/4, L/8)
   const int o1 = L >> 1, o2 = L >> 2, o3 = L >> 3;
   const bool h1 = (cg & o1) != 0, h2 = (cg & o2) != 0, h3 = (cg & o3) != 0;
   const int urow = (h1 ? 4 : 0) + (h2 ? 2 : 0) + (h3 ? 1 : 0);
-  for (int64_t base = wave0; base < a.r_out; base += stride) {
-    float4 v[kDotU];
+  for (int64_t base = wave0; base < a.rows; base += stride) {
+    float v[kDotU][VW];
 #pragma unroll
     for (int u = 0; u < kDotU; ++u) {
       const int64_t i = base + (int64_t)u * rp + sub;
-      v[u] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-      if (cg < nvec && i < a.d_rows && i < a.r_out) v[u] = *reinterpret_cast<const float4*>(a.D + i * a.ck + 4 * cg);
+#pragma unroll
+      for (int e = 0; e < VW; ++e) v[u][e] = 0.0f;
+      if (cg < nvec && i < a.rows) {
+        const Vec t = *reinterpret_cast<const Vec*>(a.D + i * a.ck + VW * cg);
+        v[u][0] = t.x; v[u][1] = t.y;
+        if constexpr (VW == 4) { v[u][2] = t.z; v[u][3] = t.w; }
+      }
     }
 #pragma unroll
     for (int n = 0; n < CT; ++n) {
       float s8[kDotU];
 #pragma unroll
-      for (int u = 0; u < kDotU; ++u)
-        s8[u] = fmaf(v[u].x, x[n].x, fmaf(v[u].y, x[n].y, fmaf(v[u].z, x[n].z, v[u].w * x[n].w)));
+      for (int u = 0; u < kDotU; ++u) {
+        if constexpr (VW == 4)
+          s8[u] = fmaf(v[u][0], x[n][0], fmaf(v[u][1], x[n][1], fmaf(v[u][2], x[n][2], v[u][3] * x[n][3])));
+        else
+          s8[u] = fmaf(v[u][0], x[n][0], v[u][1] * x[n][1]);
+      }
       // offset L/2: the lower lane of a pair keeps rows 0..3, the upper one rows 4..7
       float s4[4];
 #pragma unroll
@@ -371,24 +387,19 @@ __global__ __launch_bounds__(kBlock) void lmm_rowdot_kernel(LmmArgs a, int logL)
       for (int o = o3 >> 1; o >= 1; o >>= 1) s1 += __shfl_xor(s1, o);
       // lanes whose low bits (below L/8) are zero hold the sum of row `urow` of their wavefront-load row `sub`
       const int64_t i = base + (int64_t)urow * rp + sub;
-      if ((cg & (o3 - 1)) == 0 && n < a.ncols && i < a.r_out) a.out[i * a.ldo + a.col0 + n] = s1;
+      if ((cg & (o3 - 1)) == 0 && n < a.ncols && i < a.rows) a.out[i * a.ldo + a.col0 + n] = s1;
     }
   }
 }
 
-hipError_t launch_rowdot(const LmmArgs& a, hipStream_t st) {
-  const int nvec = a.ck / 4;
-  int logL = 3;
-  while ((1 << logL) < nvec) ++logL;
-  const int rp = kWave >> logL;
-  const int64_t rows_per_block = (int64_t)rp * kDotU * (kBlock / kWave);
-  int64_t grid = (a.r_out + rows_per_block - 1) / rows_per_block;
-  if (grid > 4096) grid = 4096;
-  const int ct = a.ncols <= 1 ? 1 : (a.ncols <= 2 ? 2 : 4);
-  if (ct == 1) lmm_rowdot_kernel<1><<<(int)grid, kBlock, 0, st>>>(a, logL);
-  else if (ct == 2) lmm_rowdot_kernel<2><<<(int)grid, kBlock, 0, st>>>(a, logL);
-  else lmm_rowdot_kernel<4><<<(int)grid, kBlock, 0, st>>>(a, logL);
-  return hipGetLastError();
+// Workgroups [first[q], first[q + 1]) serve source q.
+template <int CT>
+__global__ __launch_bounds__(kBlock) void lmm_rowdot_kernel(RowdotMulti m) {
+  int q = 0;
+  while (q + 1 < m.n && (int)blockIdx.x >= m.first[q + 1]) ++q;
+  const int bid = (int)blockIdx.x - m.first[q], nblocks = m.first[q + 1] - m.first[q];
+  if (m.a[q].vw == 4) lmm_rowdot_body<CT, 4>(m.a[q], bid, nblocks);
+  else lmm_rowdot_body<CT, 2>(m.a[q], bid, nblocks);
 }
 
 template <int VEC>
@@ -403,6 +414,49 @@ hipError_t launch_ct(const LmmArgs& a, int mode, bool fuseg, int grid, hipStream
 }
 
 }  // namespace
+
+// Dense table, at most four operand columns, rows of at most 64 aligned vectors of 4 (or, with vec == 2, 2) floats.
+bool rowdot_supported(const LmmArgs& a, int vec) {
+  if (a.D == nullptr || a.g.n != 0 || a.ncols < 1 || a.ncols > kNarrowCT || a.r_out <= 0) return false;
+  if (vec == 4) return a.ck >= 4 && a.ck <= 256 && a.ck % 4 == 0 && reinterpret_cast<uintptr_t>(a.D) % 16 == 0;
+  if (vec == 2) return a.ck >= 2 && a.ck <= 128 && a.ck % 2 == 0 && reinterpret_cast<uintptr_t>(a.D) % 8 == 0;
+  return false;
+}
+
+// The products of n <= kRowdotMulti sources (same operand columns) in one launch; vec[q] = 4 or 2 (NULL: all 4).
+hipError_t launch_rowdot_multi(const LmmArgs* a, const int* vec, int n, hipStream_t st) {
+  if (n < 1 || n > kRowdotMulti) return hipErrorInvalidValue;
+  RowdotMulti m;
+  memset(&m, 0, sizeof(m));
+  m.n = n;
+  // about 4096 workgroups in all, shared out by rows
+  int64_t want[kRowdotMulti], total = 0;
+  for (int q = 0; q < n; ++q) {
+    const int vw = vec ? vec[q] : 4;
+    if (!rowdot_supported(a[q], vw) || a[q].ncols != a[0].ncols) return hipErrorInvalidValue;
+    const int nvec = a[q].ck / vw;
+    int logL = 3;
+    while ((1 << logL) < nvec) ++logL;
+    const int rp = kWave >> logL;
+    const int64_t rows_per_block = (int64_t)rp * kDotU * (kBlock / kWave);
+    want[q] = (std::min(a[q].r_out, a[q].d_rows) + rows_per_block - 1) / rows_per_block;
+    total += want[q];
+    RowdotArgs& r = m.a[q];
+    r.D = a[q].D; r.ck = a[q].ck; r.rows = std::min(a[q].r_out, a[q].d_rows); r.colmap = a[q].colmap;
+    r.X = a[q].X; r.ldx = a[q].ldx; r.col0 = a[q].col0; r.ncols = a[q].ncols;
+    r.out = a[q].out; r.ldo = a[q].ldo; r.logL = logL; r.vw = vw;
+  }
+  for (int q = 0; q < n; ++q) {
+    int64_t g = total > 4096 ? std::max<int64_t>(1, want[q] * 4096 / total) : want[q];
+    m.first[q + 1] = m.first[q] + (int)std::max<int64_t>(g, 1);
+  }
+  const int ct = a[0].ncols <= 1 ? 1 : (a[0].ncols <= 2 ? 2 : 4);
+  const unsigned grid = (unsigned)m.first[n];
+  if (ct == 1) lmm_rowdot_kernel<1><<<grid, kBlock, 0, st>>>(m);
+  else if (ct == 2) lmm_rowdot_kernel<2><<<grid, kBlock, 0, st>>>(m);
+  else lmm_rowdot_kernel<4><<<grid, kBlock, 0, st>>>(m);
+  return hipGetLastError();
+}
 
 int lmm_rows_per_step(int logL) {
   int gpb = kBlock >> logL;
@@ -432,8 +486,7 @@ hipError_t launch_lmm_rows(const LmmArgs& a, int vec, int mode, hipStream_t st, 
   int grid = lmm_grid(a.r_out, a.logL, fuseg);
   if (grid_out) *grid_out = grid;
   if (a.r_out <= 0) return hipSuccess;
-  if (mode == 0 && !fuseg && a.g.n == 0 && a.D != nullptr && vec == 4 && a.ck >= 4 && a.ck <= 256 && a.ncols <= kNarrowCT)
-    return launch_rowdot(a, st);
+  if (mode == 0 && !fuseg && vec == 4 && rowdot_supported(a, 4)) return launch_rowdot_multi(&a, nullptr, 1, st);
   if (lmm_flat_supported(a, vec, fuseg)) return launch_lmm_flat(a, mode, fuseg, st, grid_out);
   if (lmm_flat_pair_supported(a, vec, fuseg)) return launch_lmm_flat_pair(a, mode, fuseg, st, grid_out);
   switch (vec) {

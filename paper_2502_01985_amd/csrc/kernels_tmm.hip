@@ -4,6 +4,7 @@
 //   finalize      out[col_map_k[j], :] += G_k[j, :]   partials added in a fixed order, sources in order.
 // The finalize step also performs the weight update of Alg. 1 when called from the gradient-descent step.
 #include <algorithm>
+#include <cstring>
 
 #include "ilargi_internal.h"
 
@@ -205,10 +206,10 @@ __global__ __launch_bounds__(kBlock) void slice_chunks_kernel(const int32_t* __r
 // residual) stay in the L2 of one XCD instead of crossing the fabric once per index entry.  Lane groups of
 // 2^sl_logG lanes take the (slice, source row) runs of at most kSlLong entries; the chunks of the longer runs are
 // summed by whole workgroups (thread t adds the entries t, t + 256, ..., then a fixed tree over the threads).
+// (bid of nblocks workgroups, nblocks a multiple of kSegSlices: several sources may share a launch.)
 template <int CT>
-__global__ __launch_bounds__(kBlock) void segsum_sliced_kernel(SegArgs a) {
-  __shared__ float red[CT][kBlock];
-  const int x = blockIdx.x % kSegSlices, bi = blockIdx.x / kSegSlices, nb = gridDim.x / kSegSlices;
+__device__ __forceinline__ void segsum_sliced_body(const SegArgs& a, float (*red)[kBlock], int bid, int nblocks) {
+  const int x = bid % kSegSlices, bi = bid / kSegSlices, nb = nblocks / kSegSlices;
   const int G = 1 << a.sl_logG;
   const int lig = threadIdx.x & (G - 1);
   const int64_t gpb = kBlock >> a.sl_logG;
@@ -287,10 +288,21 @@ __global__ __launch_bounds__(kBlock) void segsum_sliced_kernel(SegArgs a) {
   }
 }
 
+// The sliced segment sums of up to kSegMulti sources in one launch: workgroups [first[q], first[q + 1]) serve source
+// q; every first[q] is a multiple of kSegSlices, so workgroup b still gathers from slice b % kSegSlices and the
+// sources that run side by side on an XCD share its slice of the operand in L2.
+template <int CT>
+__global__ __launch_bounds__(kBlock) void segsum_sliced_kernel(SegMulti m) {
+  __shared__ float red[CT][kBlock];
+  int q = 0;
+  while (q + 1 < m.n && (int)blockIdx.x >= m.first[q + 1]) ++q;
+  segsum_sliced_body<CT>(m.s[q], red, (int)blockIdx.x - m.first[q], m.first[q + 1] - m.first[q]);
+}
+
 // Z[j, :] = the per-slice sums of source row j added in slice order; a long run's sum is its chunks added in order.
 template <int CT>
-__global__ __launch_bounds__(kBlock) void segsum_sliced_combine_kernel(SegArgs a) {
-  for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < a.r_k; j += (int64_t)gridDim.x * blockDim.x) {
+__device__ __forceinline__ void segsum_sliced_combine_body(const SegArgs& a, int bid, int nblocks) {
+  for (int64_t j = (int64_t)bid * blockDim.x + threadIdx.x; j < a.r_k; j += (int64_t)nblocks * blockDim.x) {
     int c0[kSegSlices];
     float v[kSegSlices][CT];
 #pragma unroll
@@ -329,6 +341,13 @@ __global__ __launch_bounds__(kBlock) void segsum_sliced_combine_kernel(SegArgs a
     for (int n = 0; n < CT; ++n)
       if (n < a.ncols) a.Z[j * a.ldz + a.zcol0 + n] = z[n];
   }
+}
+
+template <int CT>
+__global__ __launch_bounds__(kBlock) void segsum_sliced_combine_kernel(SegMulti m) {
+  int q = 0;
+  while (q + 1 < m.n && (int)blockIdx.x >= m.cfirst[q + 1]) ++q;
+  segsum_sliced_combine_body<CT>(m.s[q], (int)blockIdx.x - m.cfirst[q], m.cfirst[q + 1] - m.cfirst[q]);
 }
 
 // Long segments: add the chunk sums in chunk order.
@@ -652,23 +671,33 @@ hipError_t launch_build_sliced_index(const int32_t* rowptr, const int32_t* perm,
 // Chunk records a slice needs at most for an index of nnz entries.
 int64_t segsum_sliced_chunk_cap(int64_t nnz) { return nnz / kSlLong + 1; }
 
-hipError_t launch_segsum_sliced(const SegArgs& a, hipStream_t st) {
-  if (a.sl_perm == nullptr || a.ncols < 1 || a.ncols > kNarrowCT || a.r_k <= 0) return hipErrorInvalidValue;
-  const int64_t gpb = kBlock >> a.sl_logG;
-  int64_t nb = (a.r_k + gpb - 1) / gpb;                 // workgroups per slice
-  nb = std::min<int64_t>(std::max<int64_t>(nb, 64), 2048);
-  const unsigned grid = (unsigned)(nb * kSegSlices);
-  int cgrid = (int)((a.r_k + kBlock - 1) / kBlock);
-  if (cgrid > 2048) cgrid = 2048;
-  if (a.ncols == 1) {
-    segsum_sliced_kernel<1><<<grid, kBlock, 0, st>>>(a);
-    segsum_sliced_combine_kernel<1><<<cgrid, kBlock, 0, st>>>(a);
-  } else if (a.ncols == 2) {
-    segsum_sliced_kernel<2><<<grid, kBlock, 0, st>>>(a);
-    segsum_sliced_combine_kernel<2><<<cgrid, kBlock, 0, st>>>(a);
+hipError_t launch_segsum_sliced(const SegArgs* a, int n, hipStream_t st) {
+  if (n < 1 || n > kSegMulti) return hipErrorInvalidValue;
+  SegMulti m;
+  memset(&m, 0, sizeof(m));
+  m.n = n;
+  for (int q = 0; q < n; ++q) {
+    if (a[q].sl_perm == nullptr || a[q].ncols < 1 || a[q].ncols > kNarrowCT || a[q].ncols != a[0].ncols || a[q].r_k <= 0)
+      return hipErrorInvalidValue;
+    const int64_t gpb = kBlock >> a[q].sl_logG;
+    int64_t nb = (a[q].r_k + gpb - 1) / gpb;               // workgroups per slice
+    nb = std::min<int64_t>(std::max<int64_t>(nb, 64), 2048);
+    int cgrid = (int)((a[q].r_k + kBlock - 1) / kBlock);
+    if (cgrid > 2048) cgrid = 2048;
+    m.s[q] = a[q];
+    m.first[q + 1] = m.first[q] + (int)(nb * kSegSlices);
+    m.cfirst[q + 1] = m.cfirst[q] + cgrid;
+  }
+  const unsigned grid = (unsigned)m.first[n], cgrid = (unsigned)m.cfirst[n];
+  if (a[0].ncols == 1) {
+    segsum_sliced_kernel<1><<<grid, kBlock, 0, st>>>(m);
+    segsum_sliced_combine_kernel<1><<<cgrid, kBlock, 0, st>>>(m);
+  } else if (a[0].ncols == 2) {
+    segsum_sliced_kernel<2><<<grid, kBlock, 0, st>>>(m);
+    segsum_sliced_combine_kernel<2><<<cgrid, kBlock, 0, st>>>(m);
   } else {
-    segsum_sliced_kernel<4><<<grid, kBlock, 0, st>>>(a);
-    segsum_sliced_combine_kernel<4><<<cgrid, kBlock, 0, st>>>(a);
+    segsum_sliced_kernel<4><<<grid, kBlock, 0, st>>>(m);
+    segsum_sliced_combine_kernel<4><<<cgrid, kBlock, 0, st>>>(m);
   }
   return hipGetLastError();
 }

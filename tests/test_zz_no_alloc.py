@@ -1,6 +1,8 @@
 """ilargi_plan_create_static (the plan lives in the library's static scratch array, no device allocation)
 against ilargi_plan_create (caller's workspace): same inverse indices, same operator results, on two plans in
 a row, the second over a smaller input so that the array still holds the first plan's data."""
+import gc
+
 import numpy as np
 import pytest
 
@@ -39,10 +41,12 @@ def _compare(il, sch, seed, max_cx=16):
     """Runs every hot-path operator on a plan in the caller's workspace and on one in the static array."""
     srcs = il.schema_to_device(sch)
     ref = il.ilargi_plan_create(srcs, sch.r_T, sch.c_T, max_cx=max_cx)
+    # tensors of earlier tests that are still waiting for the garbage collector must not be released in between
+    gc.collect()
     torch.cuda.synchronize()
     before = torch.cuda.memory_allocated()
     st = il.ilargi_plan_create_static(srcs, sch.r_T, sch.c_T, max_cx=max_cx)
-    assert torch.cuda.memory_allocated() == before, "creating the static plan allocated device memory"
+    assert torch.cuda.memory_allocated() <= before, "creating the static plan allocated device memory"
     assert st.workspace is None
     try:
         # integer work: the inverse indices are identical
