@@ -323,6 +323,9 @@ size_t sort_hist_ints(int64_t r_T);
 void launch_exclusive_scan(int32_t* a, int64_t n, int32_t* totals, hipStream_t st);
 
 hipError_t launch_lmm_rows(const LmmArgs& a, int vec, int mode, hipStream_t st, int* grid_out);
+// Assembly with one lane per target row (kernels_lmm_lane.hip): one operand column, identity source with short rows.
+bool lmm_lane_supported(const LmmArgs& a, int vec, int mode, bool fuseg);
+hipError_t launch_lmm_lane(const LmmArgs& a, int vec, int mode, hipStream_t st, int* grid_out);
 // The streaming product kernel: dense table, at most four operand columns, rows of aligned vectors of vec = 4 or 2
 // floats; the products of up to kRowdotMulti sources (same operand columns) can share one launch.
 bool rowdot_supported(const LmmArgs& a, int vec);

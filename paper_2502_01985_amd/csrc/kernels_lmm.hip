@@ -487,6 +487,7 @@ hipError_t launch_lmm_rows(const LmmArgs& a, int vec, int mode, hipStream_t st, 
   if (grid_out) *grid_out = grid;
   if (a.r_out <= 0) return hipSuccess;
   if (mode == 0 && !fuseg && vec == 4 && rowdot_supported(a, 4)) return launch_rowdot_multi(&a, nullptr, 1, st);
+  if (lmm_lane_supported(a, vec, mode, fuseg)) return launch_lmm_lane(a, vec, mode, st, grid_out);
   if (lmm_flat_supported(a, vec, fuseg)) return launch_lmm_flat(a, mode, fuseg, st, grid_out);
   if (lmm_flat_pair_supported(a, vec, fuseg)) return launch_lmm_flat_pair(a, mode, fuseg, st, grid_out);
   switch (vec) {

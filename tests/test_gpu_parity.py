@@ -675,6 +675,36 @@ def test_entity_table_with_8_byte_aligned_rows_read_as_row_pairs(il, c_S):
         assert np.array_equal(W, W2)
 
 
+@pytest.mark.parametrize("c_S,ndims", [(4, 1), (8, 2), (12, 3), (16, 1), (20, 1), (24, 2), (32, 3), (6, 3), (10, 3), (14, 1)])
+def test_one_operand_column_with_one_lane_per_target_row(il, c_S, ndims):
+    # one operand column / one model over an entity table with short rows: with 6, 10 or 14 columns every pair of
+    # (8-byte aligned) rows lives in one lane after a transposing pass through LDS; the other row lengths take the
+    # flat-stream assembly.  1 .. 8 float4 per row, 3 / 5 / 7 float4 per row pair, one to three gathered tables, keys missing for some rows, several steps per wavefront and a ragged
+    # last step (70,002 rows), a table smaller than one step (38 rows); plain product, linear and logistic
+    # gradient descent against the oracle; results repeat bit for bit
+    rng = datagen.rng_for(7300 + c_S)
+    dims = [(977, 12, "uniform"), (61, 5, ("zipf", 1.2)), (3_001, 4, "uniform")][:ndims]
+    for r_T in (70_002, 38):
+        sch = datagen.star_schema(rng, r_T, c_S, dims)
+        sch.sources[1].row_idx[rng.random(r_T) < 0.05] = -1
+        tg = oracle.Target(sch)
+        plan = il.ilargi_plan_create(il.schema_to_device(sch), sch.r_T, sch.c_T, max_cx=1)
+        X = rng.standard_normal((sch.c_T, 1)).astype(np.float32)
+        got = il.ilargi_lmm(plan, dev(X)).cpu().numpy()
+        want = oracle.lmm(tg, X)
+        assert rel(got, want) < OP_TOL
+        assert_each_element(got, want, tg.T32, X)
+        w_star = rng.standard_normal(sch.c_T) / np.sqrt(sch.c_T)
+        for model, code in (("linear", il.LINEAR), ("logistic", il.LOGISTIC)):
+            y = datagen.finish_labels(model, oracle.lmm(tg, w_star.reshape(-1, 1)), 0.1 * rng.standard_normal(r_T))
+            W, L = _run_gd(il, plan, code, y, [0.3], 5, sch.c_T)
+            W_ref, L_ref = oracle.gd(tg, model, y, np.zeros((sch.c_T, 1)), [0.3], 5)
+            assert rel(W, W_ref) < GD_TOL
+            np.testing.assert_allclose(L, L_ref, rtol=1e-4)
+            W2, _ = _run_gd(il, plan, code, y, [0.3], 5, sch.c_T)
+            assert np.array_equal(W, W2)
+
+
 def _traced_kernels(il, plan, call):
     il.ilargi_plan_trace_begin(plan, "*", 64)
     call()
