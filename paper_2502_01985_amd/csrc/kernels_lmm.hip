@@ -429,7 +429,7 @@ hipError_t launch_rowdot_multi(const LmmArgs* a, const int* vec, int n, hipStrea
   RowdotMulti m;
   memset(&m, 0, sizeof(m));
   m.n = n;
-  // about 4096 workgroups in all, shared out by rows
+  // at most `cap` workgroups in all, shared out by rows
   int64_t want[kRowdotMulti], total = 0;
   for (int q = 0; q < n; ++q) {
     const int vw = vec ? vec[q] : 4;
@@ -446,8 +446,9 @@ hipError_t launch_rowdot_multi(const LmmArgs* a, const int* vec, int n, hipStrea
     r.X = a[q].X; r.ldx = a[q].ldx; r.col0 = a[q].col0; r.ncols = a[q].ncols;
     r.out = a[q].out; r.ldo = a[q].ldo; r.logL = logL; r.vw = vw;
   }
+  const int64_t cap = 4096;   // (fewer, longer-lived workgroups with the next step's rows requested ahead measured the same)
   for (int q = 0; q < n; ++q) {
-    int64_t g = total > 4096 ? std::max<int64_t>(1, want[q] * 4096 / total) : want[q];
+    int64_t g = total > cap ? std::max<int64_t>(1, want[q] * cap / total) : want[q];
     m.first[q + 1] = m.first[q] + (int)std::max<int64_t>(g, 1);
   }
   const int ct = a[0].ncols <= 1 ? 1 : (a[0].ncols <= 2 ? 2 : 4);
