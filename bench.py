@@ -589,6 +589,15 @@ def other_configs(il, torch, datagen, records=None):
                      "speedup": round(t_m / t_f, 3), "gd_factorized_GBps": round(b / t_f / 1e9, 1),
                      "materialize_once_us": round(t_mat_once * 1e6, 1), "plan_build_ms": round(plan_ms, 1),
                      "complexity_ratio_eq1": round(complexity_ratio_lr(shp, sch.r_T, sch.c_T), 3)}
+        if name == "config3":
+            # the Gram matrix this configuration asks for, factorized vs on the joined table
+            G = torch.empty((sch.c_T, sch.c_T), device="cuda")
+            t_cf = time_loop(torch, lambda: il.ilargi_crossprod(plan, G), 10)
+            t_cm = time_loop(torch, lambda: il.ilargi_crossprod(mplan, G), 10)
+            out[name]["crossprod_us"] = round(t_cf * 1e6, 1)
+            out[name]["crossprod_materialized_us"] = round(t_cm * 1e6, 1)
+            out[name]["crossprod_MB"] = round(4 * sum(r * c for r, c, _ in shp) / 1e6, 1)
+            out[name]["crossprod_GFLOP"] = round(2.0 * sch.r_T * sch.c_T * sch.c_T / 1e9, 2)
         if eager is not None:
             out[name]["timed_as"] = "captured graph of 50 iterations (GPU time); enqueued one by one from Python: " + json.dumps(eager)
         if records is not None:

@@ -78,6 +78,10 @@ struct Layout {
   size_t o_flags = 0, o_tcol_table = 0, o_pairs = 0, o_E = 0, o_loss = 0, o_sort = 0, o_hist = 0, o_zc = 0,
          o_gpartial = 0, o_blocks = 0;
   int64_t zc_floats = 0, gpartial_floats = 0, blocks_floats = 0;
+  // crossprod "via pairs": lists of (row of source k, row of source l) for the target rows both feed
+  int n_pairlists = 0;
+  int pairlist_k[kMaxPairLists] = {}, pairlist_l[kMaxPairLists] = {};
+  size_t o_pairlist[kMaxPairLists] = {};     // 2 r_T integers each: rows of k, then rows of l
   size_t total = 0;
 };
 
@@ -117,6 +121,7 @@ struct ilargi_plan {
   bool mat_flat = false;  // ... and every group is an aligned float4 of its source
   bool mat_cols = false;  // the per-column feeder tables (at most two feeders per column) are valid
   int npairs = 0;
+  int64_t pairlist_n[kMaxPairLists] = {};   // entries of the pair lists of the layout
   bool small_gd = false;  // the schema is small enough for the single-workgroup gradient-descent iteration
   int small_ident = -1, small_joined = -1;   // ... its entity table and its joined table (or -1)
   bool rowjoin_gd = false;  // fetching every source's row per target row moves fewer bytes than the factorized sequence
@@ -322,10 +327,18 @@ ilargi_status_t make_layout(int n, const ilargi_source_t* s, int64_t r_T, int64_
       lay.gpartial_floats = std::max(lay.gpartial_floats, cc);
       lay.gpartial_floats = std::max(lay.gpartial_floats, src[k].cols * max_cx);
       if (l > k) {
-        if (src[l].has_idx && src[l].rows * 2 <= r_T) lay.zc_floats = std::max(lay.zc_floats, src[l].rows * src[k].cols);
-        if (src[k].has_idx && src[k].rows * 2 <= r_T) lay.zc_floats = std::max(lay.zc_floats, src[k].rows * src[l].cols);
+        const bool via_l = src[l].has_idx && src[l].rows * 2 <= r_T, via_k = src[k].has_idx && src[k].rows * 2 <= r_T;
+        if (via_l) lay.zc_floats = std::max(lay.zc_floats, src[l].rows * src[k].cols);
+        if (via_k) lay.zc_floats = std::max(lay.zc_floats, src[k].rows * src[l].cols);
+        if (!via_l && !via_k && lay.n_pairlists < kMaxPairLists && src[k].cols >= 4 && src[k].cols <= 64 && src[l].cols >= 4 &&
+            src[l].cols <= 64 && src[k].rows > 0 && src[l].rows > 0 && r_T > 0) {
+          lay.pairlist_k[lay.n_pairlists] = k;
+          lay.pairlist_l[lay.n_pairlists] = l;
+          ++lay.n_pairlists;
+        }
       }
     }
+  for (int i = 0; i < lay.n_pairlists; ++i) lay.o_pairlist[i] = take(sizeof(int32_t) * 2 * r_T);
   lay.o_zc = take(sizeof(float) * lay.zc_floats);
   lay.o_gpartial = take(sizeof(float) * lay.gpartial_floats);
   lay.o_blocks = take(sizeof(float) * std::max<int64_t>(lay.blocks_floats, 1));
@@ -690,6 +703,16 @@ ilargi_status_t run_tred(ilargi_plan* pl, TredArgs& g, float* block, const char*
   int64_t elems = (int64_t)g.ca * g.cb;
   if (elems <= 0) return ILARGI_OK;
   if (part == nullptr) { part = pl->at<float>(pl->lay.o_gpartial); part_floats = pl->lay.gpartial_floats; }
+  if (!bf16 && gram_narrow_supported(g) && elems <= part_floats) {
+    // diagonal Gram block of a table with 36..64 columns: streaming kernel over interleaved column tiles
+    int nch = 0;
+    {
+      TraceScope ts(pl, tag, tag_k, st);
+      HIP_TRY(launch_gram_narrow(g, part, part_floats, st, &nch));
+    }
+    HIP_TRY(launch_tred_reduce(part, nch, elems, block, st, 0));
+    return ILARGI_OK;
+  }
   if (!bf16 && gram_sym_supported(g) && elems <= part_floats) {
     // diagonal Gram block of a table with 65..208 columns: upper-triangle tiles only
     TraceScope ts(pl, tag, tag_k, st);
@@ -1357,6 +1380,19 @@ ilargi_status_t plan_create_impl(int n, const ilargi_source_t* sources, int64_t 
       }
       boff += (size_t)(pl->src[k].cols * pl->src[l].cols);
     }
+  // pair lists of the source pairs whose Gram block is formed over the rows both feed
+  for (int i = 0; i < lay.n_pairlists; ++i) {
+    const SourcePlan& a = pl->src[lay.pairlist_k[i]];
+    const SourcePlan& b = pl->src[lay.pairlist_l[i]];
+    int32_t* scan = pl->at<int32_t>(lay.o_sort);                 // free again: r_T + 1 integers
+    int32_t* list = pl->at<int32_t>(lay.o_pairlist[i]);
+    HIP_TRY(launch_pair_list(a.ident ? nullptr : a.idx, a.rows, b.ident ? nullptr : b.idx, b.rows, r_T, scan,
+                             pl->at<int32_t>(lay.o_hist), list, list + r_T, st));
+    int32_t cnt = 0;
+    HIP_TRY(hipMemcpyAsync(&cnt, scan + r_T, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    pl->pairlist_n[i] = cnt;
+  }
   pl->npairs = (int)pairs.size();
   if (!pairs.empty())
     HIP_TRY(hipMemcpyAsync(pl->at<GramAsmPair>(lay.o_pairs), pairs.data(), sizeof(GramAsmPair) * pairs.size(), hipMemcpyHostToDevice, st));
@@ -1974,8 +2010,31 @@ ilargi_status_t ilargi_crossprod(ilargi_plan_t* plan, float* out, void* stream) 
           g.B = zc; g.ldb = (int)b.cols; g.cb = (int)b.cols; g.b_rows = a.rows;
           g.n_rows = a.rows;
         } else {
-          g.A = a.D; g.lda = (int)a.cols; g.ca = (int)a.cols; g.ia = a.ident ? nullptr : a.idx; g.a_rows = a.rows;
-          g.B = b.D; g.ldb = (int)b.cols; g.cb = (int)b.cols; g.ib = b.ident ? nullptr : b.idx; g.b_rows = b.rows;
+          g.A = a.D; g.lda = (int)a.cols; g.ca = (int)a.cols; g.a_rows = a.rows;
+          g.B = b.D; g.ldb = (int)b.cols; g.cb = (int)b.cols; g.b_rows = b.rows;
+          int li = -1;
+          for (int i = 0; i < plan->lay.n_pairlists; ++i)
+            if (plan->lay.pairlist_k[i] == k && plan->lay.pairlist_l[i] == l) li = i;
+          if (li >= 0) {
+            // the rows both sources feed were listed with the plan: a streaming kernel over the pairs
+            const int32_t* list = plan->at<int32_t>(plan->lay.o_pairlist[li]);
+            g.ia = list; g.ib = list + plan->r_T; g.n_rows = plan->pairlist_n[li];
+            if (g.n_rows == 0) {
+              HIP_TRY(launch_fill_zero(block, (int64_t)g.ca * g.cb, st));
+              continue;
+            }
+            if (gram_pairs_supported(g) && (int64_t)g.ca * g.cb <= part_main_floats) {
+              int nch = 0;
+              {
+                TraceScope ts(plan, "gram", k * n + l, st);
+                HIP_TRY(launch_gram_narrow(g, part_main, part_main_floats, st, &nch));
+              }
+              HIP_TRY(launch_tred_reduce(part_main, nch, (int64_t)g.ca * g.cb, block, st, 0));
+              continue;
+            }
+          }
+          g.ia = a.ident ? nullptr : a.idx;
+          g.ib = b.ident ? nullptr : b.idx;
           g.n_rows = plan->r_T;
         }
         rc = run_gram(g, block, k * n + l);

@@ -9,6 +9,7 @@
 
 namespace ilargi {
 
+constexpr int kMaxPairLists = 4;     // pair lists of crossprod a plan holds (source pairs joined row by row)
 constexpr int kMaxSources = 16;      // sources per plan (kernel argument arrays are this long)
 constexpr int kWave = 64;            // gfx950 wavefront
 constexpr int kBlock = 256;          // threads per workgroup in the streaming kernels
@@ -382,6 +383,13 @@ bool tmm_join_supported(int ck, int c);
 hipError_t launch_tmm_join(const TmmJoinArgs& a, int64_t partial_floats, hipStream_t st, int* grid_out);
 bool gram_star_supported(int cs);
 hipError_t launch_gram_star(const GramStarArgs& a, int vec, int max_grid, hipStream_t st, int* grid_out);
+// Gram blocks of tables with at most 64 columns as streaming matrix-core kernels (kernels_gram_narrow.hip): the
+// diagonal block of a table with 36..64 columns, and the block of two tables over a list of row pairs.
+bool gram_narrow_supported(const TredArgs& a);
+bool gram_pairs_supported(const TredArgs& a);
+hipError_t launch_gram_narrow(TredArgs& a, float* partial, int64_t partial_floats, hipStream_t st, int* nch_out);
+hipError_t launch_pair_list(const int32_t* idx_a, int64_t rows_a, const int32_t* idx_b, int64_t rows_b, int64_t r_T,
+                            int32_t* scan, int32_t* totals, int32_t* list_a, int32_t* list_b, hipStream_t st);
 bool gram_sym_supported(const TredArgs& a);
 hipError_t launch_gram_sym(TredArgs& a, float* partial, int64_t partial_floats, float* block, hipStream_t st);
 hipError_t launch_tred(const TredArgs& a, int nchunks, bool bf16, hipStream_t st);

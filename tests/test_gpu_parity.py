@@ -797,6 +797,41 @@ def test_crossprod_symmetric_block_of_a_wide_dimension_table(il, c_R):
     assert np.array_equal(G, G.T)
 
 
+@pytest.mark.parametrize("rows,cols,shared,overlap", [(50_001, 64, 32, 0.3), (7_003, 36, 4, 0.5), (12_345, 52, 52, 1.0),
+                                                      (9_999, 40, 0, 0.0), (33, 64, 16, 0.4), (20_000, 8, 8, 0.25)])
+def test_crossprod_of_stacked_tables_with_at_most_64_columns(il, rows, cols, shared, overlap):
+    # union-style integration: the diagonal blocks of tables with 36..64 columns and the block of the row pairs both
+    # tables feed run as streaming matrix-core kernels over interleaved column tiles.  Ragged runs (rows that are no
+    # multiple of 32), column counts that leave lanes idle (36, 40, 52), every / no / some entities in both tables
+    # (no pairs at all: the block is zero), a table of 8 columns (pair block only), fewer rows than one run;
+    # symmetric to the bit and the same bits on a second call
+    sch = datagen.config3(seed=900 + cols, rows=rows, cols=cols, shared=shared, overlap=overlap)
+    tg = oracle.Target(sch)
+    plan = il.ilargi_plan_create(il.schema_to_device(sch), sch.r_T, sch.c_T, max_cx=1)
+    G = il.ilargi_crossprod(plan).cpu().numpy()
+    want = oracle.crossprod(tg)
+    assert rel(G, want) < OP_TOL
+    assert_each_element(G, want, tg.T32.T, tg.T32)
+    assert np.array_equal(G, G.T)
+    assert np.array_equal(G, il.ilargi_crossprod(plan).cpu().numpy())
+
+
+@pytest.mark.parametrize("c_R", [36, 48, 64])
+def test_crossprod_weighted_diagonal_block_of_a_joined_table_with_at_most_64_columns(il, c_R):
+    # the fan-out of a joined table's rows weighs its diagonal block: skewed keys, rows nobody joins (weight 0),
+    # a second joined table whose pair block with the first goes through the listed row pairs
+    rng = datagen.rng_for(1400 + c_R)
+    sch = datagen.star_schema(rng, 9_001, 40, [(7_000, c_R, ("zipf", 1.1)), (6_500, 12, "uniform")])
+    sch.sources[2].row_idx[rng.random(sch.r_T) < 0.3] = -1
+    tg = oracle.Target(sch)
+    plan = il.ilargi_plan_create(il.schema_to_device(sch), sch.r_T, sch.c_T, max_cx=1)
+    G = il.ilargi_crossprod(plan).cpu().numpy()
+    want = oracle.crossprod(tg)
+    assert rel(G, want) < OP_TOL
+    assert_each_element(G, want, tg.T32.T, tg.T32)
+    assert np.array_equal(G, G.T)
+
+
 @pytest.mark.parametrize("c_S,r_R,dist", [(1, 100, "uniform"), (5, 1_237, ("zipf", 1.3)), (16, 999, "uniform"),
                                            (17, 1_601, ("zipf", 1.1)), (20, 2_000, "uniform"), (31, 17, "uniform"),
                                            (32, 1_000, ("zipf", 1.2)), (33, 1_000, "uniform")])
