@@ -55,7 +55,10 @@ finite-difference gradient for the logistic loss; ``bincount``/stable ``argsort`
 index; for KMeans the nearest-centroid and one-iteration routines of ``scipy.cluster.vq``, a loop over
 points and centroids on tiny inputs, the group means of well separated blobs and the monotone objective;
 for Gaussian NMF one iteration of scikit-learn's multiplicative-update solver, the fixed point at an
-exact factorization, an element-by-element loop on tiny inputs and the monotone objective.
+exact factorization, an element-by-element loop on tiny inputs and the monotone objective; for the rounding to
+bfloat16 torch's conversion and hand-worked ties, for Alg. 1 with rounded product inputs (``gd_bf16_inputs``, the
+arithmetic of the reduced-precision variant with exact accumulation) the first iteration on representable inputs,
+which must equal Alg. 1's, and the error bound derived for it in tests/tolerances.py.
 """
 from __future__ import annotations
 
