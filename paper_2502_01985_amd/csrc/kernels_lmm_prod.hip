@@ -96,6 +96,71 @@ __global__ __launch_bounds__(kBlock) void lmm_prod_stream_kernel(LmmArgs a, int 
   }
 }
 
+// Tables wider than 256 columns (up to 1024): the same product in chunks of 256 columns.  A wavefront walks the
+// (tile, chunk) pairs of its tiles in order, one accumulator per tile; the whole operand (ck x 16) stays in LDS.
+constexpr int kPsChunk = 16;         // 16-column steps per chunk
+
+__global__ __launch_bounds__(kBlock) void lmm_prod_stream_chunked_kernel(LmmArgs a, int nst) {
+  extern __shared__ __align__(16) float lds[];       // Xs [4 nst][16][4]
+  const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+  const int li = lane % 16, q = lane / 16;
+  const int64_t ntiles = (a.r_out + 15) / 16;
+  const int64_t tstride = (int64_t)gridDim.x * kPsWaves;
+  const int nchunks = (nst + kPsChunk - 1) / kPsChunk;
+  const int ck = a.ck;
+  float4 av[kPsChunk];
+  auto fetch = [&](int64_t t, int kc) {
+    const int64_t row = min(t * 16 + li, a.d_rows - 1);       // clamped; rows beyond the table are never stored
+    const float* rp = a.D + row * ck + 4 * q;
+#pragma unroll
+    for (int s = 0; s < kPsChunk; ++s) {
+      const int col = 16 * (kc * kPsChunk + s) + 4 * q;
+      const float4 v = *reinterpret_cast<const float4*>(rp + min(col, ck - 4) - 4 * q);
+      av[s] = (col < ck && t < ntiles) ? v : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    }
+  };
+  int64_t tile = (int64_t)blockIdx.x * kPsWaves + wave;
+  fetch(min(tile, ntiles - 1), 0);
+  for (int e = tid; e < 16 * nst * 16; e += kBlock) {         // element e = 16 k + n
+    const int k = e / 16, n = e % 16;
+    const int t = k < ck ? a.colmap[k] : -1;
+    lds[((k >> 2) * 16 + n) * 4 + (k & 3)] = (t >= 0 && n < a.ncols) ? a.X[(int64_t)t * a.ldx + a.col0 + n] : 0.0f;
+  }
+  __syncthreads();
+  for (; tile < ntiles; tile += tstride) {
+    v4f acc = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
+    for (int kc = 0; kc < nchunks; ++kc) {
+      float4 ac[kPsChunk];
+#pragma unroll
+      for (int s = 0; s < kPsChunk; ++s) ac[s] = av[s];
+      // the next chunk of this tile, or the first chunk of the wavefront's next tile
+      if (kc + 1 < nchunks) fetch(tile, kc + 1);
+      else fetch(min(tile + tstride, ntiles - 1), 0);
+#pragma unroll
+      for (int s = 0; s < kPsChunk; ++s) {
+        const int step = min(kc * kPsChunk + s, nst - 1);     // (steps beyond the table multiply zeros)
+        const float4 bv = *reinterpret_cast<const float4*>(lds + ((4 * step + q) * 16 + li) * 4);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(ac[s].x, bv.x, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(ac[s].y, bv.y, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(ac[s].z, bv.z, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(ac[s].w, bv.w, acc, 0, 0, 0);
+      }
+    }
+    const int64_t row0 = tile * 16;
+    if (li < a.ncols) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int64_t row = row0 + 4 * q + r;
+        if (row < a.r_out) {
+          float* op = a.out + row * a.ldo + a.col0 + li;
+          if (a.nt_out) __builtin_nontemporal_store(acc[r], op);
+          else *op = acc[r];
+        }
+      }
+    }
+  }
+}
+
 typedef void (*PsFn)(LmmArgs, int);
 
 int ps_slots(PsFn fn, size_t lds_bytes) {
@@ -120,11 +185,11 @@ int ps_slots(PsFn fn, size_t lds_bytes) {
 
 }  // namespace
 
-// A dense table with 16-byte aligned rows of at most 256 columns, a result of at most 16 columns, no gathers and
-// no epilogue.
+// A dense table with 16-byte aligned rows of at most 1024 columns (more than 256: in chunks), a result of at most 16
+// columns, no gathers and no epilogue.
 bool lmm_prod_stream_supported(const LmmArgs& a, int vec, int mode) {
-  if (mode != 0 || a.D == nullptr || vec != 4 || a.ck < 4 || a.ck % 4 != 0 || a.ck > 256) return false;
-  if (a.g.n != 0 || a.grad_partial != nullptr || a.ncols < 1 || a.ncols > 16) return false;
+  if (mode != 0 || a.D == nullptr || vec != 4 || a.ck < 4 || a.ck % 4 != 0 || a.ck > 1024) return false;
+  if (a.g.n != 0 || a.grad_partial != nullptr || a.ncols < 1 || a.ncols > 16 || a.d_rows < 1) return false;
   if (reinterpret_cast<uintptr_t>(a.D) % 16 != 0 || a.d_rows < a.r_out) return false;
   return true;
 }
@@ -133,6 +198,14 @@ hipError_t launch_lmm_prod_stream(const LmmArgs& a, hipStream_t st) {
   if (!lmm_prod_stream_supported(a, 4, 0)) return hipErrorInvalidValue;
   if (a.r_out <= 0) return hipSuccess;
   const int nst = (a.ck + 15) / 16;
+  if (nst > 16) {
+    const size_t lds_bytes = (size_t)16 * nst * 16 * sizeof(float);
+    const int64_t ntiles = (a.r_out + 15) / 16;
+    int64_t grid = (ntiles + kPsWaves - 1) / kPsWaves;
+    grid = std::min<int64_t>(grid, ps_slots(lmm_prod_stream_chunked_kernel, lds_bytes));
+    hipLaunchKernelGGL(lmm_prod_stream_chunked_kernel, dim3((unsigned)grid), dim3(kBlock), lds_bytes, st, a, nst);
+    return hipGetLastError();
+  }
   PsFn fn = nst <= 2 ? lmm_prod_stream_kernel<2>
           : nst <= 4 ? lmm_prod_stream_kernel<4>
           : nst <= 8 ? lmm_prod_stream_kernel<8>
