@@ -71,6 +71,12 @@ def bytes_gd(shapes, r_T, c_T):
             + 16 * sum(r for r, _ in ni) + 8 * c_T)
 
 
+def bytes_gd_clustered(shapes, r_T, c_T):
+    """One model's iteration over a two-table star join whose entity table is kept in join order: both tables once,
+    the key, the target row and the label of every row, weights in and out."""
+    return bytes_tables(shapes) + 12 * r_T + 8 * c_T
+
+
 def bytes_gd_rows_joined(schema):
     """One model's iteration that fetches every source's row per target row and uses it twice (stacked tables):
     every reached table row once, row indices, labels, weights in and out."""
@@ -135,6 +141,7 @@ def graph_time(torch, fn, iters, replays=10):
 
 STEP_OPS = ("lmm_c1", "tmm_c1", "lmm_c16", "tmm_c16")     # the step: T X and T^T Y, one and sixteen operand columns
 OTHER_OPS = ("gd_step", "crossprod", "materialize")          # timed on their own, outside `value`
+CLUSTERED_OP = "gd_clustered"    # gd_step on plans that keep the entity table in join order (ilargi_plan_cluster)
 
 
 class Workload:
@@ -164,7 +171,8 @@ class Workload:
         self.y = (il.ilargi_lmm(self.plans[0], w_star).reshape(-1) + 0.01 * torch.randn(r_T, device="cuda")).contiguous()
         self.nbytes = {"lmm_c1": bytes_lmm(self.shp, r_T, c_T, 1), "tmm_c1": bytes_tmm(self.shp, r_T, c_T, 1),
                        "lmm_c16": bytes_lmm(self.shp, r_T, c_T, 16), "tmm_c16": bytes_tmm(self.shp, r_T, c_T, 16),
-                       "gd_step": bytes_gd(self.shp, r_T, c_T), "crossprod": bytes_crossprod(self.shp, r_T, c_T),
+                       "gd_step": bytes_gd(self.shp, r_T, c_T), CLUSTERED_OP: bytes_gd_clustered(self.shp, r_T, c_T),
+                       "crossprod": bytes_crossprod(self.shp, r_T, c_T),
                        "materialize": bytes_materialize(self.shp, r_T, c_T)}
 
     def call(self, name, plan):
@@ -175,7 +183,7 @@ class Workload:
         if name.startswith("tmm_c"):
             c = int(name[5:])
             return il.ilargi_tmm(plan, self.Y[c], self.out_t[c])
-        if name == "gd_step":
+        if name in ("gd_step", CLUSTERED_OP):
             return il.ilargi_gd_step(plan, il.LINEAR, self.W, self.y, self.lr, self.loss)
         if name == "crossprod":
             return il.ilargi_crossprod(plan, self.G)
@@ -184,6 +192,15 @@ class Workload:
                 self.Tm = self.torch.empty((self.sch.r_T, self.sch.c_T), device="cuda")
             return il.ilargi_materialize(plan, self.Tm)
         raise KeyError(name)
+
+    def cluster(self, on):
+        """Every copy of the tables gets (or drops) the join-ordered copy of its entity table."""
+        for plan in self.plans:
+            if on:
+                self.il.ilargi_plan_cluster(plan)
+            else:
+                self.il.ilargi_plan_cluster(plan, None)
+        self.torch.cuda.synchronize()
 
     def step(self, i, rotate=True, label=False):
         """One step: the four multiplies on copy i of the tables (copy 0 when not rotating)."""
@@ -354,6 +371,8 @@ def kernel_model(shp, r_T, c_T):
     m["gd_step/segsum:1"] = m["tmm_c1/segsum:1"]
     m["gd_step/colred:1"] = m["tmm_c1/colred:1"]
     m["gd_step/tmm_join:1"] = m["tmm_c1/tmm_join:1"]
+    # the clustered iteration: S (join-ordered copy) and R once, key / target row / label of every row
+    m["gd_clustered/gd_cluster"] = ("hbm", 4 * r_S * c_S + 4 * r_R * c_R + 12 * r_T)
     m["materialize/materialize"] = ("hbm", bytes_materialize(shp, r_T, c_T))
     # Gram matrix: S^T S and the rows of S summed per row of R in one join-order pass; the cross block
     # Zc^T R; the diagonal block R^T diag(cnt) R (upper-triangle 16 x 16 tiles on the matrix cores)
@@ -663,6 +682,8 @@ def run_only(il, torch, wl, name, reps):
     il.ilargi_stream_probe(0, dst, src, n, n // 1024)
     torch.cuda.synchronize()
     del src, dst
+    if name == CLUSTERED_OP:
+        wl.cluster(True)
     for i in range(3):
         wl.call(name, wl.plans[i % len(wl.plans)])
     torch.cuda.synchronize()
@@ -688,7 +709,7 @@ def main() -> int:
     ap.add_argument("--no-wide", action="store_true", help="skip the 256-model batched workload")
     ap.add_argument("--no-configs", action="store_true", help="skip the other single-model configurations")
     ap.add_argument("--no-extras", action="store_true", help="skip the scalar operators, KMeans / NMF and sparse tables")
-    ap.add_argument("--only", default="", help="run one operator alone (for a profiler): " + ", ".join(STEP_OPS + OTHER_OPS)
+    ap.add_argument("--only", default="", help="run one operator alone (for a profiler): " + ", ".join(STEP_OPS + OTHER_OPS + (CLUSTERED_OP,))
                     + ", wide_f32, wide_bf16")
     ap.add_argument("--sweep", default="", help="also run the TR/FR sweep and write it to this JSON file")
     ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "traffic_by_operator_and_kernel.txt"))
@@ -726,7 +747,7 @@ def main() -> int:
     del plan
     wl = Workload(il, torch, sch, srcs, dev)
     if args.only:
-        if args.only not in STEP_OPS + OTHER_OPS:
+        if args.only not in STEP_OPS + OTHER_OPS + (CLUSTERED_OP,):
             print(f"bench.py: unknown operator {args.only}", file=sys.stderr)
             return 2
         return run_only(il, torch, wl, args.only, args.steps)
@@ -807,6 +828,17 @@ def main() -> int:
             wl.call(n, wl.plans[0])
     torch.cuda.synchronize()
     other_kernels = kernel_records(trace_collect(il, wl.plans[:1], 256), 3)
+    # the same iteration on plans that keep the entity table in join order (84 MB more per copy of the tables)
+    wl.cluster(True)
+    clustered = {"tables_rotated": wl.op_record(CLUSTERED_OP, wl.time_op(CLUSTERED_OP, rotate=True)),
+                 "warm_tables": wl.op_record(CLUSTERED_OP, wl.time_op(CLUSTERED_OP, rotate=False))}
+    trace_all(il, wl.plans[:1], 64)
+    il.ilargi_plan_trace_label(wl.plans[0], CLUSTERED_OP)
+    for _ in range(3):
+        wl.call(CLUSTERED_OP, wl.plans[0])
+    torch.cuda.synchronize()
+    other_kernels.update(kernel_records(trace_collect(il, wl.plans[:1], 64), 3))
+    wl.cluster(False)
 
     # gradient descent: factorized vs materialized iterations/s (the materialized strategy = the join once, then
     # the same entry point on a one-source plan over T, 880 MB: larger than every cache)
@@ -875,7 +907,14 @@ def main() -> int:
                "factorized_it_per_s_warm_tables": round(1.0 / t_fact_warm, 1),
                "factorized_GBps": ops_rot["gd_step"]["GBps"], "factorized_hbm_frac": ops_rot["gd_step"]["hbm_frac"],
                "materialize_once_us": ops_warm["materialize"]["us"],
-               "break_even_iterations": (round(t_join / (t_fact - t_mat), 1) if t_fact > t_mat else 0)},
+               "break_even_iterations": (round(t_join / (t_fact - t_mat), 1) if t_fact > t_mat else 0),
+               "clustered_entity_table": {
+                   "it_per_s": round(1e6 / clustered["tables_rotated"]["us"], 1),
+                   "it_per_s_warm_tables": round(1e6 / clustered["warm_tables"]["us"], 1),
+                   "speedup_over_materialized": round(t_mat * 1e6 / clustered["tables_rotated"]["us"], 3),
+                   "tables_rotated": clustered["tables_rotated"], "warm_tables": clustered["warm_tables"],
+                   "note": "ilargi_plan_cluster: the plan keeps the entity table in join order (one more copy of S); "
+                           "one launch reads S and R once and stores only partial sums"}},
         "ops_tables_rotated": ops_rot,
         "ops_warm_tables": ops_warm,
         "materialized_ops": mat_ops,

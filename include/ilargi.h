@@ -118,6 +118,24 @@ size_t ilargi_static_scratch_bytes(void);
 /* Release the host object.  The workspace and all borrowed arrays stay with the caller. */
 ilargi_status_t ilargi_plan_destroy(ilargi_plan_t* plan);
 
+/* Clustered entity table (a data layout, not an operator of the paper: Alg. 1 sums over the target rows, and
+ * a sum does not depend on the order of its terms).  For a two-table star join T = [S | I_R R] -- an identity
+ * source S of r_T rows and one source R that every target row joins -- the plan can keep a copy of S with its
+ * rows in join order (grouped by the row of R they join, the order of the inverse index).  ilargi_gd_step
+ * with one model in float32 then reads S and R once per iteration as two plain streams: the product R w_R,
+ * the residual and the segment sums I_R^T e of Sec. 2.2's rules never go to memory.  Every other operator
+ * ignores the copy.
+ *   ilargi_plan_cluster_bytes: size of the buffer, 4 r_T c_S + 4 r_T bytes rounded up to 256-byte pieces.
+ *     Errors: NULL, UNSUPPORTED (not such a join; S needs 4..32 columns, R 4..256 columns, both in whole
+ *     16-byte aligned float4s).
+ *   ilargi_plan_cluster: fills `buffer` (device, 256-byte aligned, owned by the caller, used by the plan until
+ *     it is destroyed or the call is repeated) on `stream`.  The copy holds the values S has at this call;
+ *     sources must stay unchanged while the plan lives anyway, and ilargi_elementwise applied to S in place
+ *     makes the plan forget the copy.  buffer == NULL: forget the copy.  Errors: NULL, UNSUPPORTED, WORKSPACE,
+ *     DEVICE. */
+ilargi_status_t ilargi_plan_cluster_bytes(const ilargi_plan_t* plan, size_t* bytes);
+ilargi_status_t ilargi_plan_cluster(ilargi_plan_t* plan, void* buffer, size_t buffer_bytes, void* stream);
+
 /* Left multiply (paper, Sec. 2.2):  out = T X = sum_k I_k (D_k (M_k^T X)).
  * X device c_T x cx, out device r_T x cx, 1 <= cx <= max_cx.  Errors: NULL, WORKSPACE, UNSUPPORTED. */
 ilargi_status_t ilargi_lmm(ilargi_plan_t* plan, const float* X, int64_t cx, float* out,
@@ -254,7 +272,7 @@ ilargi_status_t ilargi_plan_inverse_index(const ilargi_plan_t* plan, int k, cons
 /* Per-kernel timing for benchmarks.  After trace_begin, every launch of the kernel family named by
  * `tag` ("*" = every family; "<label>/<family>" = that family under one label) is bracketed by a pair of HIP events on the call's stream (at most
  * max_launches pairs; later launches run untimed).  Families: "lmm_rows:<k>" (product of source k),
- * "lmm_assemble", "segsum:<k>", "colred:<k>", "finalize", "materialize", "gram:<k n + l>", "star_pass",
+ * "lmm_assemble", "segsum:<k>", "colred:<k>", "finalize", "materialize", "gram:<k n + l>", "star_pass", "gd_cluster",
  * "elementwise:<k>".  trace_label sets a
  * prefix ("<label>/<family>") for the launches that follow, so a caller can tell its operators apart.
  * trace_end waits for the recorded events, writes the elapsed milliseconds of up to `capacity`

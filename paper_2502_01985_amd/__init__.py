@@ -36,7 +36,8 @@ STATUS_NAMES = ["OK", "ERR_NULL", "ERR_SHAPE", "ERR_COLMAP", "ERR_INDEX_RANGE", 
                 "ERR_UNSUPPORTED", "ERR_DEVICE"]
 
 EXPORTED = [
-    "ilargi_plan_workspace_bytes", "ilargi_plan_create", "ilargi_plan_create_static", "ilargi_plan_destroy", "ilargi_lmm", "ilargi_tmm",
+    "ilargi_plan_workspace_bytes", "ilargi_plan_create", "ilargi_plan_create_static", "ilargi_plan_destroy",
+    "ilargi_plan_cluster_bytes", "ilargi_plan_cluster", "ilargi_lmm", "ilargi_tmm",
     "ilargi_rmm", "ilargi_crossprod", "ilargi_materialize", "ilargi_gd_step", "ilargi_kmeans_step", "ilargi_gnmf_step",
     "ilargi_elementwise", "ilargi_row_sum",
     "ilargi_col_sum", "ilargi_choose", "ilargi_segment_sum",
@@ -63,6 +64,8 @@ lib.ilargi_plan_create.argtypes = [_int, ctypes.POINTER(SourceStruct), _i64, _i6
 lib.ilargi_plan_create_static.argtypes = [_int, ctypes.POINTER(SourceStruct), _i64, _i64, _i64, _vp, ctypes.POINTER(_vp)]
 lib.ilargi_static_scratch_bytes.argtypes = []
 lib.ilargi_plan_destroy.argtypes = [_vp]
+lib.ilargi_plan_cluster_bytes.argtypes = [_vp, ctypes.POINTER(ctypes.c_size_t)]
+lib.ilargi_plan_cluster.argtypes = [_vp, _vp, ctypes.c_size_t, _vp]
 lib.ilargi_lmm.argtypes = [_vp, _vp, _i64, _vp, _int, _vp]
 lib.ilargi_tmm.argtypes = [_vp, _vp, _i64, _vp, _int, _vp]
 lib.ilargi_rmm.argtypes = [_vp, _vp, _i64, _vp, _int, _vp]
@@ -258,6 +261,30 @@ def ilargi_plan_create(sources, r_T: int, c_T: int, max_cx: int = 1, stream=None
                                   _stream_ptr(stream), ctypes.byref(handle)), "ilargi_plan_create")
     del keep
     return Plan(handle.value, workspace, borrowed, r_T, c_T, max_cx, shapes)
+
+
+def ilargi_plan_cluster_bytes(plan: Plan) -> int:
+    nbytes = ctypes.c_size_t(0)
+    _check(lib.ilargi_plan_cluster_bytes(plan.handle, ctypes.byref(nbytes)), "ilargi_plan_cluster_bytes")
+    return int(nbytes.value)
+
+
+def ilargi_plan_cluster(plan: Plan, buffer="new", stream=None) -> None:
+    """Keeps a join-ordered copy of the entity table of a two-table star join with the plan.  ``buffer``: a uint8
+    CUDA tensor of at least ``ilargi_plan_cluster_bytes(plan)`` bytes (256-byte aligned), ``"new"`` to allocate one
+    here, or ``None`` to make the plan forget the copy."""
+    torch = _torch()
+    if buffer is None:
+        _check(lib.ilargi_plan_cluster(plan.handle, None, 0, _stream_ptr(stream)), "ilargi_plan_cluster")
+        plan._cluster = None
+        return
+    if isinstance(buffer, str):
+        buffer = torch.empty(ilargi_plan_cluster_bytes(plan), dtype=torch.uint8, device=plan.device)
+    if not (buffer.is_cuda and buffer.dtype == torch.uint8 and buffer.is_contiguous()):
+        raise TypeError("buffer must be a contiguous uint8 CUDA tensor")
+    _check(lib.ilargi_plan_cluster(plan.handle, buffer.data_ptr(), buffer.numel(), _stream_ptr(stream)),
+           "ilargi_plan_cluster")
+    plan._cluster = buffer
 
 
 def ilargi_static_scratch_bytes() -> int:

@@ -126,6 +126,11 @@ struct ilargi_plan {
   int small_ident = -1, small_joined = -1;   // ... its entity table and its joined table (or -1)
   bool rowjoin_gd = false;  // fetching every source's row per target row moves fewer bytes than the factorized sequence
   int static_dev = -1;   // >= 0: the workspace is the library's static scratch array of that device
+  // two-table star join: the entity table with its rows in join order and the row of the dimension table each joins,
+  // in a buffer the caller gave to ilargi_plan_cluster (NULL: not clustered)
+  const float* cluster_sp = nullptr;
+  const int32_t* cluster_keys = nullptr;
+  int cluster_k = -1;   // the joined source
   std::vector<size_t> block_off;  // offset (floats) of Gram block (k,l), k <= l, index k * n + l
   // optional timing of one kernel family: event pairs recorded around every launch whose tag matches
   std::string trace_tag;            // "*" traces every kernel family
@@ -1441,6 +1446,66 @@ ilargi_status_t ilargi_plan_create_static(int n, const ilargi_source_t* sources,
 
 size_t ilargi_static_scratch_bytes(void) { return kStaticScratchBytes; }
 
+namespace {
+// A two-table star join (full-height identity source, one other source that every target row joins, segments of any
+// length) whose tables the one-pass kernel takes: the joined source, or -1.
+int cluster_dim(const ilargi_plan* pl) {
+  if (pl->fused < 0 || pl->any_sparse || pl->r_T < 1) return -1;
+  int live = 0, dim = -1;
+  for (int k = 0; k < pl->n; ++k) {
+    if (pl->src[k].empty) continue;
+    ++live;
+    if (k != pl->fused) dim = k;
+  }
+  if (live != 2 || dim < 0) return -1;
+  const SourcePlan& f = pl->src[pl->fused];
+  const SourcePlan& d = pl->src[dim];
+  const bool ok = gd_cluster_supported((int)f.cols, (int)d.cols) && f.rows == pl->r_T && d.has_idx && !d.ident &&
+                  d.nnz == pl->r_T && d.rows >= 1 && reinterpret_cast<uintptr_t>(f.D) % 16 == 0 &&
+                  reinterpret_cast<uintptr_t>(d.D) % 16 == 0;
+  return ok ? dim : -1;
+}
+}  // namespace
+
+ilargi_status_t ilargi_plan_cluster_bytes(const ilargi_plan_t* plan, size_t* bytes) {
+  if (plan == nullptr) return fail(ILARGI_ERR_NULL, "plan_cluster_bytes: plan is NULL");
+  if (bytes == nullptr) return fail(ILARGI_ERR_NULL, "plan_cluster_bytes: bytes is NULL");
+  if (cluster_dim(plan) < 0)
+    return fail(ILARGI_ERR_UNSUPPORTED, "plan_cluster: needs a two-table star join (entity table of 4..32 columns, dimension "
+                                        "table of 4..256 columns, whole aligned float4 rows, every target row joined)");
+  const SourcePlan& f = plan->src[plan->fused];
+  *bytes = align_up(sizeof(float) * (size_t)plan->r_T * (size_t)f.cols) + align_up(sizeof(int32_t) * (size_t)plan->r_T);
+  return ILARGI_OK;
+}
+
+ilargi_status_t ilargi_plan_cluster(ilargi_plan_t* plan, void* buffer, size_t buffer_bytes, void* stream) {
+  if (plan == nullptr) return fail(ILARGI_ERR_NULL, "plan_cluster: plan is NULL");
+  if (buffer == nullptr) {
+    plan->cluster_sp = nullptr;
+    plan->cluster_keys = nullptr;
+    return ILARGI_OK;
+  }
+  size_t need = 0;
+  ilargi_status_t rc = ilargi_plan_cluster_bytes(plan, &need);
+  if (rc != ILARGI_OK) return rc;
+  if (reinterpret_cast<uintptr_t>(buffer) % kAlign != 0) return fail(ILARGI_ERR_WORKSPACE, "plan_cluster: buffer is not 256-byte aligned");
+  if (buffer_bytes < need)
+    return fail(ILARGI_ERR_WORKSPACE, "plan_cluster: buffer of %zu bytes, %zu needed", buffer_bytes, need);
+  const int dim = cluster_dim(plan);
+  const SourcePlan& f = plan->src[plan->fused];
+  const SourcePlan& d = plan->src[dim];
+  float* sp = static_cast<float*>(buffer);
+  int32_t* keys = reinterpret_cast<int32_t*>(static_cast<char*>(buffer) + align_up(sizeof(float) * (size_t)plan->r_T * (size_t)f.cols));
+  plan->cluster_sp = nullptr;
+  plan->cluster_keys = nullptr;
+  HIP_TRY(launch_cluster_rows(f.D, (int)f.cols, plan->at<int32_t>(d.o_perm), d.idx, plan->r_T, sp, keys,
+                              static_cast<hipStream_t>(stream)));
+  plan->cluster_sp = sp;
+  plan->cluster_keys = keys;
+  plan->cluster_k = dim;
+  return ILARGI_OK;
+}
+
 ilargi_status_t ilargi_plan_destroy(ilargi_plan_t* plan) {
   if (plan == nullptr) return fail(ILARGI_ERR_NULL, "plan is NULL");
   if (plan->static_dev >= 0) {
@@ -1613,6 +1678,43 @@ ilargi_status_t ilargi_gd_step(ilargi_plan_t* plan, ilargi_model_t model, float*
     }
     return ILARGI_OK;
   }
+  if (plan->cluster_sp != nullptr && !bf16 && m == 1) {
+    // clustered entity table: both tables are streams, every table read once, nothing but partial sums written
+    const SourcePlan& fs = plan->src[plan->fused];
+    const SourcePlan& d = plan->src[plan->cluster_k];
+    ClusterArgs a;
+    memset(&a, 0, sizeof(a));
+    a.Sp = plan->cluster_sp; a.cs = (int)fs.cols;
+    a.keys = plan->cluster_keys; a.perm = plan->at<int32_t>(d.o_perm);
+    a.R = d.D; a.cr = (int)d.cols; a.r_R = d.rows;
+    a.s_colmap = plan->at<int32_t>(fs.o_colmap); a.r_colmap = plan->at<int32_t>(d.o_colmap);
+    a.W = W; a.ldw = (int)m; a.col = 0; a.y = y; a.r_T = plan->r_T;
+    a.loss_partial = plan->at<float>(plan->lay.o_loss);
+    a.grad_partial_s = plan->at<float>(fs.o_partial);
+    a.grad_partial_r = plan->at<float>(d.o_partial);
+    int grid = 0;
+    {
+      TraceScope ts(plan, "gd_cluster", -1, st);
+      HIP_TRY(launch_gd_cluster(a, model == ILARGI_LINEAR ? 1 : 2, kColredBlocks, st, &grid));
+    }
+    FinArgs f;
+    memset(&f, 0, sizeof(f));
+    for (int k = 0; k < plan->n; ++k) {
+      const SourcePlan& p = plan->src[k];
+      if (p.empty) continue;
+      const int s = f.n++;
+      f.s[s].tcol2src = plan->at<int32_t>(p.o_tcol);
+      f.s[s].partial = plan->at<float>(p.o_partial);
+      f.s[s].ck = (int)p.cols;
+      f.s[s].nblocks = grid;
+    }
+    f.out = W; f.ldo = 1; f.col0 = 0; f.ncols = 1;
+    f.lr = lr; f.inv_rT = 1.0f / (float)plan->r_T;
+    f.loss_partial = a.loss_partial; f.n_loss_partial = grid; f.loss = loss; f.loss_scale = loss_scale;
+    TraceScope ts(plan, "finalize", -1, st);
+    HIP_TRY(launch_finalize(f, (int)plan->c_T, 1, st));
+    return ILARGI_OK;
+  }
   if (plan->rowjoin_gd && !bf16 && m == 1) {
     // every table read once: product, residual and every source's block of the gradient in one pass
     RowJoinArgs a;
@@ -1776,6 +1878,11 @@ ilargi_status_t ilargi_elementwise(ilargi_plan_t* plan, ilargi_elementwise_t op,
       return fail(ILARGI_ERR_NULL, "elementwise: D_out[%d] is NULL", k);
   }
   hipStream_t st = static_cast<hipStream_t>(stream);
+  // an entity table rewritten in place no longer matches its join-ordered copy: the plan forgets the copy
+  if (plan->cluster_sp != nullptr && D_out[plan->fused] == plan->src[plan->fused].D) {
+    plan->cluster_sp = nullptr;
+    plan->cluster_keys = nullptr;
+  }
   for (int k = 0; k < plan->n; ++k) {
     const SourcePlan& p = plan->src[k];
     if (p.empty) continue;

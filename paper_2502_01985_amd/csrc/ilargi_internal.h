@@ -314,6 +314,27 @@ struct RowJoinArgs {
 bool gd_rowjoin_supported(const RowJoinArgs& a);
 hipError_t launch_gd_rowjoin(const RowJoinArgs& a, int mode, int max_grid, hipStream_t st, int* grid_out);
 
+// Gradient-descent pass of one model over a two-table star join whose entity table is kept in join order
+// (kernels_gd_cluster.hip): both tables are read once, no product, residual or segment sum is stored.
+struct ClusterArgs {
+  const float* Sp; int cs;                  // the entity table with its rows in join order, r_T x cs, 16-byte aligned
+  const int32_t* keys;                      // int32[r_T], ascending: the row of the dimension table each of those rows joins
+  const int32_t* perm;                      // int32[r_T]: its target row (where its label is)
+  const float* R; int cr; int64_t r_R;      // dimension table, r_R x cr, 16-byte aligned, cr a multiple of 4, at most 256
+  const int32_t* s_colmap;                  // device int32[cs], int32[cr]: target column of every table column (-1: none)
+  const int32_t* r_colmap;
+  const float* W; int ldw, col;             // weight column `col` of the c_T x ldw matrix
+  const float* y; int64_t r_T;
+  float* loss_partial;                      // [gridDim.x][kNarrowCT]
+  float* grad_partial_s;                    // [gridDim.x][cs][kNarrowCT] partials of S^T e
+  float* grad_partial_r;                    // [gridDim.x][cr][kNarrowCT] partials of R^T (I_R^T e)
+};
+bool gd_cluster_supported(int cs, int cr);
+// Sp[p, :] = S[perm[p], :], keys[p] = idx[perm[p]] for p < r_T.
+hipError_t launch_cluster_rows(const float* S, int cs, const int32_t* perm, const int32_t* idx, int64_t r_T, float* Sp,
+                               int32_t* keys, hipStream_t st);
+hipError_t launch_gd_cluster(const ClusterArgs& a, int mode, int max_grid, hipStream_t st, int* grid_out);
+
 // ---- launchers (each enqueues on `st`; returns the HIP error of the launch) ----
 hipError_t launch_check_idx(const int32_t* idx, int64_t r_T, int64_t r_k, int32_t* flags, hipStream_t st);
 hipError_t launch_sort_by_source_row(const int32_t* idx, int64_t r_T, int64_t r_k, int32_t* keys_a,

@@ -1,0 +1,146 @@
+"""Gradient descent over a two-table star join whose entity table is kept in join order (ilargi_plan_cluster):
+the one-pass iteration against the oracle's Alg. 1 and against the plan's unclustered iteration."""
+import numpy as np
+import pytest
+import torch
+
+import datagen
+import oracle
+
+pytestmark = pytest.mark.gpu
+
+GD_TOL = 1e-4
+
+
+@pytest.fixture(scope="module")
+def il():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2502_01985_amd as mod
+    return mod
+
+
+def rel(a, b):
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    nb = np.linalg.norm(b)
+    return float(np.linalg.norm(a - b) / (nb if nb > 0 else 1.0))
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def _run_gd(il, plan, model, y, lrs, iters, c_T):
+    m = len(lrs)
+    W = torch.zeros((c_T, m), device="cuda")
+    lr = dev(np.asarray(lrs, dtype=np.float32))
+    loss = torch.zeros(m, device="cuda")
+    yd = dev(y)
+    losses = []
+    for _ in range(iters):
+        il.ilargi_gd_step(plan, model, W, yd, lr, loss)
+        losses.append(loss.cpu().numpy().copy())
+    return W.cpu().numpy(), np.array(losses)
+
+
+# (r_T, c_S, r_R, c_R, keys): the benchmark's shape scaled down; the narrowest tables; a full-width dimension table
+# with a ragged last chunk; fan-out 1 with more rows of R than target rows (runs of more than eight rows of R per
+# chunk, rows nobody joins); skewed keys (segments spanning many chunks); fewer rows than a chunk; one row of R
+SHAPES = [(30_011, 20, 3_001, 200, "uniform"), (50_003, 4, 301, 24, "uniform"), (20_003, 8, 257, 256, "uniform"),
+          (9_999, 32, 12_000, 4, "uniform"), (60_001, 12, 50, 36, ("zipf", 1.1)), (37, 16, 5, 8, "uniform"),
+          (4_100, 28, 1, 12, "uniform")]
+
+
+@pytest.mark.parametrize("model", ["linear", "logistic"])
+@pytest.mark.parametrize("r_T,c_S,r_R,c_R,keys", SHAPES)
+def test_gd_clustered_entity_table(il, model, r_T, c_S, r_R, c_R, keys):
+    print(f"case {model} {r_T} {c_S} {r_R} {c_R} {keys}", flush=True)
+    rng = datagen.rng_for(9100 + r_T + c_S + c_R)
+    sch = datagen.star_schema(rng, r_T, c_S, [(r_R, c_R, keys)])
+    tg = oracle.Target(sch)
+    w_star = rng.standard_normal(sch.c_T) / np.sqrt(sch.c_T)
+    y = datagen.finish_labels(model, oracle.lmm(tg, w_star.reshape(-1, 1)), 0.1 * rng.standard_normal(r_T))
+    plan = il.ilargi_plan_create(il.schema_to_device(sch), sch.r_T, sch.c_T, max_cx=2)
+    code = il.LINEAR if model == "linear" else il.LOGISTIC
+    lr = [0.05]
+    W0, L0 = _run_gd(il, plan, code, y, lr, 5, sch.c_T)               # the plan's usual iteration
+    il.ilargi_plan_cluster(plan)
+    W, L = _run_gd(il, plan, code, y, lr, 5, sch.c_T)
+    W_ref, L_ref = oracle.gd(tg, model, y, np.zeros((sch.c_T, 1)), lr, 5)
+    assert rel(W, W_ref) < GD_TOL
+    assert np.abs(W - W_ref).max() <= GD_TOL * max(np.abs(W_ref).max(), 1e-30) * 10
+    np.testing.assert_allclose(L, L_ref, rtol=1e-4)
+    assert rel(W, W0) < GD_TOL
+    W2, L2 = _run_gd(il, plan, code, y, lr, 5, sch.c_T)
+    assert np.array_equal(W, W2) and np.array_equal(L, L2)          # same bits on every run
+    # two models: the clustered copy is not used, the result is the usual one
+    Wm, _ = _run_gd(il, plan, code, y, [0.05, 0.01], 2, sch.c_T)
+    Wm_ref, _ = oracle.gd(tg, model, y, np.zeros((sch.c_T, 2)), [0.05, 0.01], 2)
+    assert rel(Wm, Wm_ref) < GD_TOL
+    # forgetting the copy brings back the usual iteration, bit for bit
+    il.ilargi_plan_cluster(plan, None)
+    W3, L3 = _run_gd(il, plan, code, y, lr, 5, sch.c_T)
+    assert np.array_equal(W3, W0) and np.array_equal(L3, L0)
+
+
+def test_clustered_copy_is_the_table_in_join_order(il):
+    rng = datagen.rng_for(9200)
+    sch = datagen.star_schema(rng, 7_001, 12, [(300, 16, "uniform")])
+    srcs = il.schema_to_device(sch)
+    plan = il.ilargi_plan_create(srcs, sch.r_T, sch.c_T, max_cx=1)
+    nbytes = il.ilargi_plan_cluster_bytes(plan)
+    buf = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+    il.ilargi_plan_cluster(plan, buf)
+    torch.cuda.synchronize()
+    fk = sch.sources[1].row_idx
+    order = np.argsort(fk, kind="stable")
+    raw = buf.cpu().numpy()
+    sp = raw[:4 * sch.r_T * 12].view(np.float32).reshape(sch.r_T, 12)
+    off = (4 * sch.r_T * 12 + 255) // 256 * 256
+    keys = raw[off:off + 4 * sch.r_T].view(np.int32)
+    assert np.array_equal(sp.view(np.uint32), sch.sources[0].D[order].view(np.uint32))
+    assert np.array_equal(keys, fk[order])
+
+
+def test_cluster_is_refused_where_it_does_not_apply(il):
+    rng = datagen.rng_for(9300)
+    # a key is missing: not every target row joins
+    sch = datagen.star_schema(rng, 2_000, 8, [(100, 8, "uniform")])
+    sch.sources[1].row_idx[17] = -1
+    plan = il.ilargi_plan_create(il.schema_to_device(sch), sch.r_T, sch.c_T, max_cx=1)
+    with pytest.raises(il.IlargiError):
+        il.ilargi_plan_cluster(plan)
+    # three tables
+    sch = datagen.star_schema(rng, 2_000, 8, [(100, 8, "uniform"), (50, 4, "uniform")])
+    plan = il.ilargi_plan_create(il.schema_to_device(sch), sch.r_T, sch.c_T, max_cx=1)
+    with pytest.raises(il.IlargiError):
+        il.ilargi_plan_cluster_bytes(plan)
+    # an entity table whose rows are not whole float4s; a dimension table wider than 256 columns
+    for c_S, c_R in [(6, 8), (8, 260)]:
+        sch = datagen.star_schema(rng, 2_000, c_S, [(100, c_R, "uniform")])
+        plan = il.ilargi_plan_create(il.schema_to_device(sch), sch.r_T, sch.c_T, max_cx=1)
+        with pytest.raises(il.IlargiError):
+            il.ilargi_plan_cluster(plan)
+    # a buffer that is too small
+    sch = datagen.star_schema(rng, 2_000, 8, [(100, 8, "uniform")])
+    plan = il.ilargi_plan_create(il.schema_to_device(sch), sch.r_T, sch.c_T, max_cx=1)
+    small = torch.zeros(il.ilargi_plan_cluster_bytes(plan) - 256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(il.IlargiError):
+        il.ilargi_plan_cluster(plan, small)
+
+
+def test_elementwise_in_place_on_the_entity_table_drops_the_copy(il):
+    rng = datagen.rng_for(9400)
+    sch = datagen.star_schema(rng, 6_000, 8, [(200, 12, "uniform")])
+    srcs = il.schema_to_device(sch)
+    plan = il.ilargi_plan_create(srcs, sch.r_T, sch.c_T, max_cx=1)
+    il.ilargi_plan_cluster(plan)
+    il.ilargi_elementwise(plan, "mul", 0.5, outs=[D for D, _, _ in srcs])
+    for s in sch.sources:
+        s.D[...] = s.D * np.float32(0.5)
+    tg = oracle.Target(sch)
+    y = rng.standard_normal(sch.r_T).astype(np.float32)
+    W, L = _run_gd(il, plan, il.LINEAR, y, [0.05], 3, sch.c_T)
+    W_ref, L_ref = oracle.gd(tg, "linear", y, np.zeros((sch.c_T, 1)), [0.05], 3)
+    assert rel(W, W_ref) < GD_TOL
