@@ -72,9 +72,9 @@ def bytes_gd(shapes, r_T, c_T):
 
 
 def bytes_gd_clustered(shapes, r_T, c_T):
-    """One model's iteration over a two-table star join whose entity table is kept in join order: both tables once,
-    the key, the target row and the label of every row, weights in and out."""
-    return bytes_tables(shapes) + 12 * r_T + 8 * c_T
+    """One model's iteration over a two-table star join whose entity table and labels are kept in join order: both
+    tables once, the key and the label of every row, weights in and out."""
+    return bytes_tables(shapes) + 8 * r_T + 8 * c_T
 
 
 def bytes_gd_rows_joined(schema):
@@ -197,7 +197,7 @@ class Workload:
         """Every copy of the tables gets (or drops) the join-ordered copy of its entity table."""
         for plan in self.plans:
             if on:
-                self.il.ilargi_plan_cluster(plan)
+                self.il.ilargi_plan_cluster(plan, y=self.y)
             else:
                 self.il.ilargi_plan_cluster(plan, None)
         self.torch.cuda.synchronize()
@@ -371,8 +371,8 @@ def kernel_model(shp, r_T, c_T):
     m["gd_step/segsum:1"] = m["tmm_c1/segsum:1"]
     m["gd_step/colred:1"] = m["tmm_c1/colred:1"]
     m["gd_step/tmm_join:1"] = m["tmm_c1/tmm_join:1"]
-    # the clustered iteration: S (join-ordered copy) and R once, key / target row / label of every row
-    m["gd_clustered/gd_cluster"] = ("hbm", 4 * r_S * c_S + 4 * r_R * c_R + 12 * r_T)
+    # the clustered iteration: S (join-ordered copy) and R once, key and label of every row
+    m["gd_clustered/gd_cluster"] = ("hbm", 4 * r_S * c_S + 4 * r_R * c_R + 8 * r_T)
     m["materialize/materialize"] = ("hbm", bytes_materialize(shp, r_T, c_T))
     # Gram matrix: S^T S and the rows of S summed per row of R in one join-order pass; the cross block
     # Zc^T R; the diagonal block R^T diag(cnt) R (upper-triangle 16 x 16 tiles on the matrix cores)

@@ -125,16 +125,20 @@ ilargi_status_t ilargi_plan_destroy(ilargi_plan_t* plan);
  * with one model in float32 then reads S and R once per iteration as two plain streams: the product R w_R,
  * the residual and the segment sums I_R^T e of Sec. 2.2's rules never go to memory.  Every other operator
  * ignores the copy.
- *   ilargi_plan_cluster_bytes: size of the buffer, 4 r_T c_S + 4 r_T bytes rounded up to 256-byte pieces.
+ *   ilargi_plan_cluster_bytes: size of the buffer, 4 r_T c_S + 8 r_T bytes rounded up to 256-byte pieces.
  *     Errors: NULL, UNSUPPORTED (not such a join; S needs 4..32 columns, R 4..256 columns, both in whole
  *     16-byte aligned float4s).
  *   ilargi_plan_cluster: fills `buffer` (device, 256-byte aligned, owned by the caller, used by the plan until
  *     it is destroyed or the call is repeated) on `stream`.  The copy holds the values S has at this call;
  *     sources must stay unchanged while the plan lives anyway, and ilargi_elementwise applied to S in place
- *     makes the plan forget the copy.  buffer == NULL: forget the copy.  Errors: NULL, UNSUPPORTED, WORKSPACE,
- *     DEVICE. */
+ *     makes the plan forget the copy.  `y` (optional, device float[r_T]): the labels of the training set; they
+ *     are copied in join order as well, and an ilargi_gd_step whose y is this same pointer reads them from the
+ *     copy instead of gathering them (the vector must then stay unchanged like a source table; a gd_step with
+ *     any other y gathers its labels as usual).  buffer == NULL: forget the copy.
+ *     Errors: NULL, UNSUPPORTED, WORKSPACE, DEVICE. */
 ilargi_status_t ilargi_plan_cluster_bytes(const ilargi_plan_t* plan, size_t* bytes);
-ilargi_status_t ilargi_plan_cluster(ilargi_plan_t* plan, void* buffer, size_t buffer_bytes, void* stream);
+ilargi_status_t ilargi_plan_cluster(ilargi_plan_t* plan, void* buffer, size_t buffer_bytes, const float* y,
+                                    void* stream);
 
 /* Left multiply (paper, Sec. 2.2):  out = T X = sum_k I_k (D_k (M_k^T X)).
  * X device c_T x cx, out device r_T x cx, 1 <= cx <= max_cx.  Errors: NULL, WORKSPACE, UNSUPPORTED. */

@@ -65,7 +65,7 @@ lib.ilargi_plan_create_static.argtypes = [_int, ctypes.POINTER(SourceStruct), _i
 lib.ilargi_static_scratch_bytes.argtypes = []
 lib.ilargi_plan_destroy.argtypes = [_vp]
 lib.ilargi_plan_cluster_bytes.argtypes = [_vp, ctypes.POINTER(ctypes.c_size_t)]
-lib.ilargi_plan_cluster.argtypes = [_vp, _vp, ctypes.c_size_t, _vp]
+lib.ilargi_plan_cluster.argtypes = [_vp, _vp, ctypes.c_size_t, _vp, _vp]
 lib.ilargi_lmm.argtypes = [_vp, _vp, _i64, _vp, _int, _vp]
 lib.ilargi_tmm.argtypes = [_vp, _vp, _i64, _vp, _int, _vp]
 lib.ilargi_rmm.argtypes = [_vp, _vp, _i64, _vp, _int, _vp]
@@ -269,22 +269,27 @@ def ilargi_plan_cluster_bytes(plan: Plan) -> int:
     return int(nbytes.value)
 
 
-def ilargi_plan_cluster(plan: Plan, buffer="new", stream=None) -> None:
+def ilargi_plan_cluster(plan: Plan, buffer="new", y=None, stream=None) -> None:
     """Keeps a join-ordered copy of the entity table of a two-table star join with the plan.  ``buffer``: a uint8
     CUDA tensor of at least ``ilargi_plan_cluster_bytes(plan)`` bytes (256-byte aligned), ``"new"`` to allocate one
-    here, or ``None`` to make the plan forget the copy."""
+    here, or ``None`` to make the plan forget the copy.  ``y``: the labels (float32 CUDA tensor of length r_T) to keep
+    in join order as well; ``ilargi_gd_step`` called with this same tensor then reads them from the copy."""
     torch = _torch()
     if buffer is None:
-        _check(lib.ilargi_plan_cluster(plan.handle, None, 0, _stream_ptr(stream)), "ilargi_plan_cluster")
+        _check(lib.ilargi_plan_cluster(plan.handle, None, 0, None, _stream_ptr(stream)), "ilargi_plan_cluster")
         plan._cluster = None
         return
     if isinstance(buffer, str):
         buffer = torch.empty(ilargi_plan_cluster_bytes(plan), dtype=torch.uint8, device=plan.device)
     if not (buffer.is_cuda and buffer.dtype == torch.uint8 and buffer.is_contiguous()):
         raise TypeError("buffer must be a contiguous uint8 CUDA tensor")
-    _check(lib.ilargi_plan_cluster(plan.handle, buffer.data_ptr(), buffer.numel(), _stream_ptr(stream)),
-           "ilargi_plan_cluster")
-    plan._cluster = buffer
+    if y is not None:
+        _dev_f32(y, "y")
+        if y.numel() != plan.r_T:
+            raise TypeError("y must have r_T entries")
+    _check(lib.ilargi_plan_cluster(plan.handle, buffer.data_ptr(), buffer.numel(), y.data_ptr() if y is not None else None,
+                                   _stream_ptr(stream)), "ilargi_plan_cluster")
+    plan._cluster = (buffer, y)
 
 
 def ilargi_static_scratch_bytes() -> int:

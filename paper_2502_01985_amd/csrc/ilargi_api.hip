@@ -131,6 +131,8 @@ struct ilargi_plan {
   const float* cluster_sp = nullptr;
   const int32_t* cluster_keys = nullptr;
   int cluster_k = -1;   // the joined source
+  const float* cluster_y_src = nullptr;   // the label vector whose join-ordered copy cluster_yp holds (NULL: none)
+  const float* cluster_yp = nullptr;
   std::vector<size_t> block_off;  // offset (floats) of Gram block (k,l), k <= l, index k * n + l
   // optional timing of one kernel family: event pairs recorded around every launch whose tag matches
   std::string trace_tag;            // "*" traces every kernel family
@@ -1474,15 +1476,16 @@ ilargi_status_t ilargi_plan_cluster_bytes(const ilargi_plan_t* plan, size_t* byt
     return fail(ILARGI_ERR_UNSUPPORTED, "plan_cluster: needs a two-table star join (entity table of 4..32 columns, dimension "
                                         "table of 4..256 columns, whole aligned float4 rows, every target row joined)");
   const SourcePlan& f = plan->src[plan->fused];
-  *bytes = align_up(sizeof(float) * (size_t)plan->r_T * (size_t)f.cols) + align_up(sizeof(int32_t) * (size_t)plan->r_T);
+  *bytes = align_up(sizeof(float) * (size_t)plan->r_T * (size_t)f.cols) + 2 * align_up(sizeof(int32_t) * (size_t)plan->r_T);
   return ILARGI_OK;
 }
 
-ilargi_status_t ilargi_plan_cluster(ilargi_plan_t* plan, void* buffer, size_t buffer_bytes, void* stream) {
+ilargi_status_t ilargi_plan_cluster(ilargi_plan_t* plan, void* buffer, size_t buffer_bytes, const float* y, void* stream) {
   if (plan == nullptr) return fail(ILARGI_ERR_NULL, "plan_cluster: plan is NULL");
   if (buffer == nullptr) {
     plan->cluster_sp = nullptr;
     plan->cluster_keys = nullptr;
+    plan->cluster_y_src = plan->cluster_yp = nullptr;
     return ILARGI_OK;
   }
   size_t need = 0;
@@ -1496,13 +1499,16 @@ ilargi_status_t ilargi_plan_cluster(ilargi_plan_t* plan, void* buffer, size_t bu
   const SourcePlan& d = plan->src[dim];
   float* sp = static_cast<float*>(buffer);
   int32_t* keys = reinterpret_cast<int32_t*>(static_cast<char*>(buffer) + align_up(sizeof(float) * (size_t)plan->r_T * (size_t)f.cols));
+  float* yp = reinterpret_cast<float*>(reinterpret_cast<char*>(keys) + align_up(sizeof(int32_t) * (size_t)plan->r_T));
   plan->cluster_sp = nullptr;
   plan->cluster_keys = nullptr;
-  HIP_TRY(launch_cluster_rows(f.D, (int)f.cols, plan->at<int32_t>(d.o_perm), d.idx, plan->r_T, sp, keys,
+  plan->cluster_y_src = plan->cluster_yp = nullptr;
+  HIP_TRY(launch_cluster_rows(f.D, (int)f.cols, plan->at<int32_t>(d.o_perm), d.idx, plan->r_T, sp, keys, y, yp,
                               static_cast<hipStream_t>(stream)));
   plan->cluster_sp = sp;
   plan->cluster_keys = keys;
   plan->cluster_k = dim;
+  if (y != nullptr) { plan->cluster_y_src = y; plan->cluster_yp = yp; }
   return ILARGI_OK;
 }
 
@@ -1689,6 +1695,7 @@ ilargi_status_t ilargi_gd_step(ilargi_plan_t* plan, ilargi_model_t model, float*
     a.R = d.D; a.cr = (int)d.cols; a.r_R = d.rows;
     a.s_colmap = plan->at<int32_t>(fs.o_colmap); a.r_colmap = plan->at<int32_t>(d.o_colmap);
     a.W = W; a.ldw = (int)m; a.col = 0; a.y = y; a.r_T = plan->r_T;
+    a.yp = y == plan->cluster_y_src ? plan->cluster_yp : nullptr;   // the labels the copy was made with
     a.loss_partial = plan->at<float>(plan->lay.o_loss);
     a.grad_partial_s = plan->at<float>(fs.o_partial);
     a.grad_partial_r = plan->at<float>(d.o_partial);
@@ -1882,6 +1889,7 @@ ilargi_status_t ilargi_elementwise(ilargi_plan_t* plan, ilargi_elementwise_t op,
   if (plan->cluster_sp != nullptr && D_out[plan->fused] == plan->src[plan->fused].D) {
     plan->cluster_sp = nullptr;
     plan->cluster_keys = nullptr;
+    plan->cluster_y_src = plan->cluster_yp = nullptr;
   }
   for (int k = 0; k < plan->n; ++k) {
     const SourcePlan& p = plan->src[k];

@@ -325,14 +325,15 @@ struct ClusterArgs {
   const int32_t* r_colmap;
   const float* W; int ldw, col;             // weight column `col` of the c_T x ldw matrix
   const float* y; int64_t r_T;
+  const float* yp;                          // the labels in join order, float[r_T], or NULL (then y is gathered through perm)
   float* loss_partial;                      // [gridDim.x][kNarrowCT]
   float* grad_partial_s;                    // [gridDim.x][cs][kNarrowCT] partials of S^T e
   float* grad_partial_r;                    // [gridDim.x][cr][kNarrowCT] partials of R^T (I_R^T e)
 };
 bool gd_cluster_supported(int cs, int cr);
-// Sp[p, :] = S[perm[p], :], keys[p] = idx[perm[p]] for p < r_T.
+// Sp[p, :] = S[perm[p], :], keys[p] = idx[perm[p]] and, with labels y, yp[p] = y[perm[p]] for p < r_T.
 hipError_t launch_cluster_rows(const float* S, int cs, const int32_t* perm, const int32_t* idx, int64_t r_T, float* Sp,
-                               int32_t* keys, hipStream_t st);
+                               int32_t* keys, const float* y, float* yp, hipStream_t st);
 hipError_t launch_gd_cluster(const ClusterArgs& a, int mode, int max_grid, hipStream_t st, int* grid_out);
 
 // ---- launchers (each enqueues on `st`; returns the HIP error of the launch) ----

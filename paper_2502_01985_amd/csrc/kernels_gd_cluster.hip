@@ -37,6 +37,14 @@ __device__ __forceinline__ void gc_wave_sync() {
 
 constexpr int kGcWaves = kBlock / kWave;
 
+typedef float gc_v4f __attribute__((ext_vector_type(4)));
+// A float4 that is read once: loaded with the non-temporal hint so that it does not displace the labels, which every
+// wavefront gathers from, in the L2.
+__device__ __forceinline__ float4 gc_stream4(const float4* p) {
+  const gc_v4f t = __builtin_nontemporal_load(reinterpret_cast<const gc_v4f*>(p));
+  return make_float4(t.x, t.y, t.z, t.w);
+}
+
 // Value of `x` in the lane the data-parallel-primitive control word names (all lanes active).
 template <int CTRL>
 __device__ __forceinline__ float gc_dpp(float x) {
@@ -70,14 +78,14 @@ __device__ __forceinline__ void gc_wave_sum4(float (&d)[4]) {
   }
 }
 
-// NVT: compile-time bound of nvec = cs / 4.  MODE 1 linear, 2 logistic.  wave_floats: LDS floats of one wavefront.
+// NVT = cs / 4, the float4s of a row of S.  MODE 1 linear, 2 logistic.  wave_floats: LDS floats of one wavefront.
 template <int NVT, int MODE>
 __global__ __launch_bounds__(kBlock) void gd_cluster_kernel(ClusterArgs a, int wave_floats) {
   extern __shared__ float lds[];
   const int tid = threadIdx.x, lane = tid % kWave;
   const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);  // uniform: chunk numbers and key runs live in scalar registers
-  const int nvec = a.cs / 4;
-  const int ldp = nvec | 1;                                    // odd row stride of the partial-dot tile
+  constexpr int nvec = NVT;
+  constexpr int ldp = nvec | 1;                                    // odd row stride of the partial-dot tile
   float4* Xs4 = reinterpret_cast<float4*>(lds);                // [NVT] weights of the columns of S
   float* wbase = lds + 4 * NVT + (size_t)wave * wave_floats;
   float* Pd = wbase;                                           // [64 * ldp] partial dot products
@@ -89,21 +97,10 @@ __global__ __launch_bounds__(kBlock) void gd_cluster_kernel(ClusterArgs a, int w
     row_u[u] = u < nvec ? e / nvec : 0;
     part_u[u] = u < nvec ? e - row_u[u] * nvec : 0;
   }
-  // this lane's four columns of R and their weights
   const int nvr = a.cr / 4;
   const bool rlive = lane < nvr;
-  float4 wr = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-  if (rlive) {
-    float w[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      const int t = a.r_colmap[4 * lane + c];
-      if (t >= 0) w[c] = a.W[(int64_t)t * a.ldw + a.col];
-    }
-    wr = make_float4(w[0], w[1], w[2], w[3]);
-  }
-  const float4* R4 = reinterpret_cast<const float4*>(a.R) + (rlive ? lane : 0);
   const int jmax = (int)a.r_R - 1;
+  float4 wr = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
 
   float loss_local = 0.0f;
   float4 gacc[NVT];
@@ -115,39 +112,52 @@ __global__ __launch_bounds__(kBlock) void gd_cluster_kernel(ClusterArgs a, int w
   const int64_t nchunks = (r_T + kWave - 1) / kWave;
   const int64_t cstride = (int64_t)gridDim.x * kGcWaves;
   int64_t chunk = (int64_t)blockIdx.x * kGcWaves + wave;
-  // keys and target rows of the chunk, one chunk ahead
-  int kn = -1, pn = 0;
-  {
-    const int64_t i = chunk * kWave + lane;
-    if (chunk < nchunks && i < r_T) { kn = a.keys[i]; pn = a.perm[i]; }
-  }
-  float4 v[NVT], vn[NVT];
+  // The loop is free of branches around its loads (addresses are clamped into the buffers, values that must not
+  // count are zeroed by a select), and everything a chunk consumes -- its rows of S, its keys, target rows and
+  // labels, the first eight rows of its run of R -- is requested in one group a chunk earlier, right after the
+  // previous group has arrived: a wavefront then computes a whole chunk without waiting for memory.  The run of R
+  // needs the keys, so the keys are requested two chunks ahead.
+  const int64_t last4 = r_T * nvec - 1;                        // last float4 of Sp
   auto load_chunk = [&](int64_t ch, float4 (&dst)[NVT]) {
-    const int64_t r0 = ch * kWave;
-    const float4* b4 = reinterpret_cast<const float4*>(a.Sp + r0 * a.cs);
+    const int64_t f0 = ch * kWave * nvec + lane;
+    const float4* b4 = reinterpret_cast<const float4*>(a.Sp);
 #pragma unroll
     for (int u = 0; u < NVT; ++u) {
-      dst[u] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-      if (u < nvec && ch < nchunks && r0 + row_u[u] < r_T) dst[u] = b4[u * kWave + lane];
+      const int64_t f = f0 + u * kWave;
+      const float4 x = gc_stream4(b4 + min(f, last4));
+      const bool ok = u < nvec && f <= last4;
+      dst[u] = make_float4(ok ? x.x : 0.0f, ok ? x.y : 0.0f, ok ? x.z : 0.0f, ok ? x.w : 0.0f);
     }
   };
-  load_chunk(chunk, vn);
-  if (tid < nvec) {
-    float w[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      const int t = a.s_colmap[4 * tid + c];
-      if (t >= 0) w[c] = a.W[(int64_t)t * a.ldw + a.col];
-    }
-    Xs4[tid] = make_float4(w[0], w[1], w[2], w[3]);
-  }
-  __syncthreads();
-  // four rows j0 .. j0 + 3 of R (zero beyond jhi)
+  // labels: kept in join order with the copy of S (then a row's label sits at its own index and the target rows are
+  // not needed: the second index stream rereads the keys, which hit), else gathered from the target rows
+  const float* ylab = a.yp != nullptr ? a.yp : a.y;
+  const int32_t* pidx = a.yp != nullptr ? a.keys : a.perm;
+  auto load_keys = [&](int64_t ch, int& k, int& p) {
+    const int64_t i = ch * kWave + lane;
+    const int64_t ic = min(i, r_T - 1);
+    const int kk = __builtin_nontemporal_load(a.keys + ic), pp = __builtin_nontemporal_load(pidx + ic);
+    k = i < r_T ? kk : -1;
+    p = i < r_T ? (a.yp != nullptr ? (int)ic : pp) : 0;
+  };
+  // the run of rows of R a chunk joins (keys ascend; clamped to the table whatever the key buffer holds); jhi < jlo
+  // for a chunk beyond the table
+  auto run_of = [&](int64_t ch, int k, int& jlo, int& jhi) {
+    const int64_t left = r_T - ch * kWave;
+    const int nlive = (int)min((int64_t)kWave, max(left, (int64_t)1));
+    const int lo = min(max(__builtin_amdgcn_readlane(k, 0), 0), jmax);
+    const int hi = min(max(__builtin_amdgcn_readlane(k, nlive - 1), lo), jmax);
+    jlo = lo;
+    jhi = left > 0 ? hi : lo - 1;
+  };
+  // four rows j0 .. j0 + 3 of R (zero beyond jhi and beyond the table's columns)
+  const float4* R4 = reinterpret_cast<const float4*>(a.R) + min(lane, nvr - 1);
   auto load_rows = [&](int j0, int jhi, float4 (&r)[4]) {
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
-      r[b] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-      if (rlive && j0 + b <= jhi) r[b] = R4[(int64_t)(j0 + b) * nvr];
+      const float4 x = gc_stream4(R4 + (int64_t)min(j0 + b, jmax) * nvr);
+      const bool ok = rlive && j0 + b <= jhi;
+      r[b] = make_float4(ok ? x.x : 0.0f, ok ? x.y : 0.0f, ok ? x.z : 0.0f, ok ? x.w : 0.0f);
     }
   };
   // pass 1: their products with w_R, handed to the lanes whose key matches
@@ -174,27 +184,57 @@ __global__ __launch_bounds__(kBlock) void gd_cluster_kernel(ClusterArgs a, int w
     }
   };
 
+  // the first chunk's group, and the keys of the second
+  float4 v[NVT], vn[NVT], rk0[4], rk1[4], rn0[4], rn1[4];
+  int kn, pn, kn2, pn2, jlo_n, jhi_n;
+  load_keys(chunk, kn, pn);
+  load_keys(chunk + cstride, kn2, pn2);
+  load_chunk(chunk, vn);
+  run_of(chunk, kn, jlo_n, jhi_n);
+  load_rows(jlo_n, jhi_n, rn0);
+  load_rows(jlo_n + 4, jhi_n, rn1);
+  float yn = ylab[pn];
+  // the weights are looked up while the first group travels
+  // this lane's four columns of R and their weights
+  if (rlive) {
+    float w[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const int t = a.r_colmap[4 * lane + c];
+      if (t >= 0) w[c] = a.W[(int64_t)t * a.ldw + a.col];
+    }
+    wr = make_float4(w[0], w[1], w[2], w[3]);
+  }
+  if (tid < nvec) {
+    float w[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const int t = a.s_colmap[4 * tid + c];
+      if (t >= 0) w[c] = a.W[(int64_t)t * a.ldw + a.col];
+    }
+    Xs4[tid] = make_float4(w[0], w[1], w[2], w[3]);
+  }
+  __syncthreads();
+
   for (; chunk < nchunks; chunk += cstride) {
-    const int64_t row0 = chunk * kWave;
-    const int64_t i = row0 + lane;
+    const int64_t i = chunk * kWave + lane;
     const bool rowlive = i < r_T;
+    // the group requested a chunk ago
 #pragma unroll
     for (int u = 0; u < NVT; ++u) v[u] = vn[u];
+#pragma unroll
+    for (int b = 0; b < 4; ++b) { rk0[b] = rn0[b]; rk1[b] = rn1[b]; }
+    const int kj = kn;
+    const float yi = yn;
+    const int jlo = jlo_n, jhi = jhi_n;
+    // the next chunk's group; the keys of the chunk after it
+    kn = kn2; pn = pn2;
     load_chunk(chunk + cstride, vn);
-    const int kj = rowlive ? kn : -1;
-    const float yi = rowlive ? a.y[pn] : 0.0f;
-    {
-      const int64_t inext = i + cstride * kWave;
-      kn = -1; pn = 0;
-      if (chunk + cstride < nchunks && inext < r_T) { kn = a.keys[inext]; pn = a.perm[inext]; }
-    }
-    // the run of rows of R this chunk joins (keys ascend; clamped to the table whatever the key buffer holds)
-    const int nlive = (int)min((int64_t)kWave, r_T - row0);
-    const int jlo = min(max(__builtin_amdgcn_readlane(kj, 0), 0), jmax);
-    const int jhi = min(max(__builtin_amdgcn_readlane(kj, nlive - 1), jlo), jmax);
-    float4 rk0[4], rk1[4];
-    load_rows(jlo, jhi, rk0);
-    load_rows(jlo + 4, jhi, rk1);
+    run_of(chunk + cstride, kn, jlo_n, jhi_n);
+    load_rows(jlo_n, jhi_n, rn0);
+    load_rows(jlo_n + 4, jhi_n, rn1);
+    yn = ylab[pn];
+    load_keys(chunk + 2 * cstride, kn2, pn2);
     // partial dot products of the rows of S into the tile
     gc_wave_sync();                                            // the previous chunk's tile is consumed
 #pragma unroll
@@ -208,7 +248,7 @@ __global__ __launch_bounds__(kBlock) void gd_cluster_kernel(ClusterArgs a, int w
     float pl = 0.0f;
     dots(rk0, jlo, kj, pl);
     dots(rk1, jlo + 4, kj, pl);
-    for (int j0 = jlo + 8; j0 <= jhi; j0 += 4) {
+    for (int j0 = jlo + 8; j0 <= jhi; j0 += 4) {               // (runs of more than eight rows: fan-out below eight)
       float4 r[4];
       load_rows(j0, jhi, r);
       dots(r, j0, kj, pl);
@@ -217,21 +257,20 @@ __global__ __launch_bounds__(kBlock) void gd_cluster_kernel(ClusterArgs a, int w
     float z = 0.0f;
     {
       const float* pr = Pd + lane * ldp;
-      for (int p = 0; p < nvec; ++p) z += pr[p];
+#pragma unroll
+      for (int p = 0; p < NVT; ++p) z += p < nvec ? pr[p] : 0.0f;
     }
     z += pl;
     float r_e = 0.0f;
-    if (rowlive) {
-      if constexpr (MODE == 1) {
-        r_e = z - yi;
-        loss_local = fmaf(r_e, r_e, loss_local);
-      } else {
-        // one exponential serves the sigmoid and the softplus: e = exp(-|z|)
-        const float e = __expf(-fabsf(z));
-        const float inv = __frcp_rn(1.0f + e);
-        r_e = (z >= 0.0f ? inv : e * inv) - yi;
-        loss_local += fmaxf(z, 0.0f) + log1pf(e) - yi * z;
-      }
+    if constexpr (MODE == 1) {
+      r_e = rowlive ? z - yi : 0.0f;
+      loss_local = fmaf(r_e, r_e, loss_local);
+    } else {
+      // one exponential serves the sigmoid and the softplus: e = exp(-|z|)
+      const float e = __expf(-fabsf(z));
+      const float inv = __frcp_rn(1.0f + e);
+      r_e = rowlive ? (z >= 0.0f ? inv : e * inv) - yi : 0.0f;
+      loss_local += rowlive ? fmaxf(z, 0.0f) + log1pf(e) - yi * z : 0.0f;
     }
     Es[lane] = r_e;
     gc_wave_sync();
@@ -328,28 +367,38 @@ __global__ __launch_bounds__(kBlock) void gd_cluster_kernel(ClusterArgs a, int w
   }
 }
 
-// Sp[p, :] = S[perm[p], :] as float4, keys[p] = idx[perm[p]].
+// Sp[p, :] = S[perm[p], :] as float4, keys[p] = idx[perm[p]], yp[p] = y[perm[p]] (when labels are given).
 __global__ __launch_bounds__(kBlock) void cluster_rows_kernel(const float4* __restrict__ S4, int nvec, const int32_t* __restrict__ perm,
                                                              const int32_t* __restrict__ idx, int64_t r_T,
-                                                             float4* __restrict__ Sp4, int32_t* __restrict__ keys) {
+                                                             float4* __restrict__ Sp4, int32_t* __restrict__ keys,
+                                                             const float* __restrict__ y, float* __restrict__ yp) {
   const int64_t total = r_T * nvec;
   for (int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x; e < total; e += (int64_t)gridDim.x * kBlock) {
     const int64_t p = e / nvec;
     const int g = (int)(e - p * nvec);
     const int64_t t = perm[p];
     Sp4[e] = S4[t * nvec + g];
-    if (g == 0) keys[p] = idx[t];
+    if (g == 0) {
+      keys[p] = idx[t];
+      if (y != nullptr) yp[p] = y[t];
+    }
   }
 }
 
 typedef void (*GcFn)(ClusterArgs, int);
 
-int gc_nvt(int nvec) { return nvec <= 4 ? 4 : (nvec == 5 ? 5 : 8); }
-
-GcFn gc_pick(int nvt, int mode) {
-  if (nvt == 4) return mode == 1 ? gd_cluster_kernel<4, 1> : gd_cluster_kernel<4, 2>;
-  if (nvt == 5) return mode == 1 ? gd_cluster_kernel<5, 1> : gd_cluster_kernel<5, 2>;
-  return mode == 1 ? gd_cluster_kernel<8, 1> : gd_cluster_kernel<8, 2>;
+template <int MODE>
+GcFn gc_pick(int nvec) {
+  switch (nvec) {
+    case 1: return gd_cluster_kernel<1, MODE>;
+    case 2: return gd_cluster_kernel<2, MODE>;
+    case 3: return gd_cluster_kernel<3, MODE>;
+    case 4: return gd_cluster_kernel<4, MODE>;
+    case 5: return gd_cluster_kernel<5, MODE>;
+    case 6: return gd_cluster_kernel<6, MODE>;
+    case 7: return gd_cluster_kernel<7, MODE>;
+    default: return gd_cluster_kernel<8, MODE>;
+  }
 }
 
 int gc_slots(GcFn fn, size_t lds_bytes) {
@@ -380,8 +429,9 @@ bool gd_cluster_supported(int cs, int cr) {
 }
 
 hipError_t launch_cluster_rows(const float* S, int cs, const int32_t* perm, const int32_t* idx, int64_t r_T, float* Sp,
-                               int32_t* keys, hipStream_t st) {
+                               int32_t* keys, const float* y, float* yp, hipStream_t st) {
   if (S == nullptr || perm == nullptr || idx == nullptr || Sp == nullptr || keys == nullptr || cs < 4 || cs % 4 != 0 ||
+      (y != nullptr && yp == nullptr) ||
       reinterpret_cast<uintptr_t>(S) % 16 != 0 || reinterpret_cast<uintptr_t>(Sp) % 16 != 0)
     return hipErrorInvalidValue;
   if (r_T <= 0) return hipSuccess;
@@ -389,23 +439,23 @@ hipError_t launch_cluster_rows(const float* S, int cs, const int32_t* perm, cons
   const int64_t total = r_T * nvec;
   const int grid = (int)std::min<int64_t>((total + kBlock - 1) / kBlock, 8192);
   hipLaunchKernelGGL(cluster_rows_kernel, dim3((unsigned)grid), dim3(kBlock), 0, st, reinterpret_cast<const float4*>(S), nvec, perm,
-                     idx, r_T, reinterpret_cast<float4*>(Sp), keys);
+                     idx, r_T, reinterpret_cast<float4*>(Sp), keys, y, yp);
   return hipGetLastError();
 }
 
 hipError_t launch_gd_cluster(const ClusterArgs& a, int mode, int max_grid, hipStream_t st, int* grid_out) {
   if (grid_out) *grid_out = 0;
   if (!gd_cluster_supported(a.cs, a.cr) || (mode != 1 && mode != 2) || max_grid < 1 || a.r_T < 1 || a.r_R < 1) return hipErrorInvalidValue;
-  if (a.Sp == nullptr || a.keys == nullptr || a.perm == nullptr || a.R == nullptr || a.y == nullptr || a.W == nullptr)
+  if (a.Sp == nullptr || a.keys == nullptr || a.perm == nullptr || a.R == nullptr || (a.y == nullptr && a.yp == nullptr) || a.W == nullptr)
     return hipErrorInvalidValue;
   if (reinterpret_cast<uintptr_t>(a.Sp) % 16 != 0 || reinterpret_cast<uintptr_t>(a.R) % 16 != 0) return hipErrorInvalidValue;
   const int nvec = a.cs / 4;
-  const int nvt = gc_nvt(nvec);
+  const int nvt = nvec;
   const int ldp = nvec | 1;
   int wave_floats = std::max(kWave * ldp + kWave, nvt * kWave * 4);
   wave_floats = (wave_floats + 3) / 4 * 4;
   const size_t lds_bytes = ((size_t)4 * nvt + (size_t)kGcWaves * wave_floats) * sizeof(float);
-  GcFn fn = gc_pick(nvt, mode);
+  GcFn fn = mode == 1 ? gc_pick<1>(nvec) : gc_pick<2>(nvec);
   const int64_t nchunks = (a.r_T + kWave - 1) / kWave;
   int64_t grid = (nchunks + kGcWaves - 1) / kGcWaves;
   grid = std::min<int64_t>(grid, gc_slots(fn, lds_bytes));         // one round of resident workgroups

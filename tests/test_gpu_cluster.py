@@ -36,7 +36,7 @@ def _run_gd(il, plan, model, y, lrs, iters, c_T):
     W = torch.zeros((c_T, m), device="cuda")
     lr = dev(np.asarray(lrs, dtype=np.float32))
     loss = torch.zeros(m, device="cuda")
-    yd = dev(y)
+    yd = y if isinstance(y, torch.Tensor) else dev(y)
     losses = []
     for _ in range(iters):
         il.ilargi_gd_step(plan, model, W, yd, lr, loss)
@@ -74,6 +74,17 @@ def test_gd_clustered_entity_table(il, model, r_T, c_S, r_R, c_R, keys):
     assert rel(W, W0) < GD_TOL
     W2, L2 = _run_gd(il, plan, code, y, lr, 5, sch.c_T)
     assert np.array_equal(W, W2) and np.array_equal(L, L2)          # same bits on every run
+    # the labels kept in join order with the copy: the same sums in the same order, so the same bits; another label
+    # vector is gathered as before
+    yd = dev(y)
+    il.ilargi_plan_cluster(plan, y=yd)
+    W4, L4 = _run_gd(il, plan, code, yd, lr, 5, sch.c_T)
+    assert np.array_equal(W, W4) and np.array_equal(L, L4)
+    y_other = (1.0 - y if model == "logistic" else -y).astype(np.float32)
+    W5, L5 = _run_gd(il, plan, code, y_other, lr, 5, sch.c_T)
+    W5_ref, L5_ref = oracle.gd(tg, model, y_other, np.zeros((sch.c_T, 1)), lr, 5)
+    assert rel(W5, W5_ref) < GD_TOL
+    np.testing.assert_allclose(L5, L5_ref, rtol=1e-4)
     # two models: the clustered copy is not used, the result is the usual one
     Wm, _ = _run_gd(il, plan, code, y, [0.05, 0.01], 2, sch.c_T)
     Wm_ref, _ = oracle.gd(tg, model, y, np.zeros((sch.c_T, 2)), [0.05, 0.01], 2)
@@ -101,6 +112,12 @@ def test_clustered_copy_is_the_table_in_join_order(il):
     keys = raw[off:off + 4 * sch.r_T].view(np.int32)
     assert np.array_equal(sp.view(np.uint32), sch.sources[0].D[order].view(np.uint32))
     assert np.array_equal(keys, fk[order])
+    y = rng.standard_normal(sch.r_T).astype(np.float32)
+    il.ilargi_plan_cluster(plan, buf, y=dev(y))
+    torch.cuda.synchronize()
+    off2 = off + (4 * sch.r_T + 255) // 256 * 256
+    yp = buf.cpu().numpy()[off2:off2 + 4 * sch.r_T].view(np.float32)
+    assert np.array_equal(yp.view(np.uint32), y[order].view(np.uint32))
 
 
 def test_cluster_is_refused_where_it_does_not_apply(il):
