@@ -831,7 +831,8 @@ def main() -> int:
     # the same iteration on plans that keep the entity table in join order (84 MB more per copy of the tables)
     wl.cluster(True)
     clustered = {"tables_rotated": wl.op_record(CLUSTERED_OP, wl.time_op(CLUSTERED_OP, rotate=True)),
-                 "warm_tables": wl.op_record(CLUSTERED_OP, wl.time_op(CLUSTERED_OP, rotate=False))}
+                 "warm_tables": wl.op_record(CLUSTERED_OP, wl.time_op(CLUSTERED_OP, rotate=False)),
+                 "crossprod": wl.op_record("crossprod", wl.time_op("crossprod", rotate=True))}
     trace_all(il, wl.plans[:1], 64)
     il.ilargi_plan_trace_label(wl.plans[0], CLUSTERED_OP)
     for _ in range(3):
@@ -913,6 +914,7 @@ def main() -> int:
                    "it_per_s_warm_tables": round(1e6 / clustered["warm_tables"]["us"], 1),
                    "speedup_over_materialized": round(t_mat * 1e6 / clustered["tables_rotated"]["us"], 3),
                    "tables_rotated": clustered["tables_rotated"], "warm_tables": clustered["warm_tables"],
+                   "crossprod_tables_rotated": clustered["crossprod"],
                    "note": "ilargi_plan_cluster: the plan keeps the entity table in join order (one more copy of S); "
                            "one launch reads S and R once and stores only partial sums"}},
         "ops_tables_rotated": ops_rot,

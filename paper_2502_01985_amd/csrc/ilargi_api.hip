@@ -2045,6 +2045,8 @@ ilargi_status_t ilargi_crossprod(ilargi_plan_t* plan, float* out, void* stream) 
       memset(&ga, 0, sizeof(ga));
       ga.S = f.D; ga.cs = (int)f.cols; ga.r_R = d.rows;
       ga.rowptr = plan->at<int32_t>(d.o_rowptr); ga.perm = plan->at<int32_t>(d.o_perm); ga.idx = d.idx;
+      // (a join-ordered copy of S kept with the plan turns the gathered rows into a stream; same sums, same order)
+      ga.Sp = (plan->cluster_sp != nullptr && plan->cluster_k == plan->star_k) ? plan->cluster_sp : nullptr;
       ga.ss_partial = gpart;
       ga.zc = zc;
       int grid = 0;

@@ -115,6 +115,7 @@ struct GramStarArgs {
   const int32_t* rowptr;             // r_R + 1: inverse index of R (every target row joins one row)
   const int32_t* perm;               // r_T
   const int32_t* idx;                // r_T: row of R each target row joins
+  const float* Sp;                   // NULL, or S with its rows in join order (Sp[p, :] = S[perm[p], :]): then a plain stream
   float* ss_partial;                 // [gridDim.x][cs][cs] partials of S^T S (upper-triangle 16 x 16 tiles)
   float* zc;                         // r_R x cs: rows of S summed per row of R
 };

@@ -51,6 +51,7 @@ __global__ __launch_bounds__(kBlock) void gram_star_kernel(GramStarArgs a, int r
   constexpr int gslots = VEC4 ? 8 : 32;
   const int glive = VEC4 ? a.cs / 4 : a.cs;
   const bool two = a.cs > 16;                                 // a second 16-column tile of S exists
+  const float* Sb = a.Sp != nullptr ? a.Sp : a.S;
 
   for (int rt = blockIdx.x * kGsWavesPerBlock + wave; rt < rtiles; rt += gridDim.x * kGsWavesPerBlock) {
     const int64_t jb = (int64_t)rt * 16;
@@ -71,8 +72,10 @@ __global__ __launch_bounds__(kBlock) void gram_star_kernel(GramStarArgs a, int r
       return j;
     };
 
-    int pi = (lane < kGsST && p_begin + lane < p_end) ? a.perm[p_begin + lane] : -1;
-    int pi_next = (lane < kGsST && p_begin + kGsST + lane < p_end) ? a.perm[p_begin + kGsST + lane] : -1;
+    // the row of the table entry p of the inverse index stands for: its target row, or, in the join-ordered copy, p
+    auto row_at = [&](int p) { return a.Sp != nullptr ? p : a.perm[p]; };
+    int pi = (lane < kGsST && p_begin + lane < p_end) ? row_at(p_begin + lane) : -1;
+    int pi_next = (lane < kGsST && p_begin + kGsST + lane < p_end) ? row_at(p_begin + kGsST + lane) : -1;
     int jl = pi >= 0 ? joined(p_begin + lane) : -1;
     gs_wave_sync();                                           // the previous tile's batches are consumed
     if (lane < kGsST) iS[lane] = pi;
@@ -87,8 +90,8 @@ __global__ __launch_bounds__(kBlock) void gram_star_kernel(GramStarArgs a, int r
         else sv[u] = 0.0f;
         if (r < cnt_rows && g < glive) {
           const int64_t row = iS[r];
-          if constexpr (VEC4) sv[u] = *reinterpret_cast<const float4*>(a.S + row * a.cs + 4 * g);
-          else sv[u] = a.S[row * a.cs + g];
+          if constexpr (VEC4) sv[u] = *reinterpret_cast<const float4*>(Sb + row * a.cs + 4 * g);
+          else sv[u] = Sb[row * a.cs + g];
         }
       }
     };
@@ -107,7 +110,7 @@ __global__ __launch_bounds__(kBlock) void gram_star_kernel(GramStarArgs a, int r
       }
       gs_wave_sync();
       pi = pi_next;
-      pi_next = (lane < kGsST && p0 + 2 * kGsST + lane < p_end) ? a.perm[p0 + 2 * kGsST + lane] : -1;
+      pi_next = (lane < kGsST && p0 + 2 * kGsST + lane < p_end) ? row_at(p0 + 2 * kGsST + lane) : -1;
       jl = pi >= 0 ? joined(p0 + kGsST + lane) : -1;
       load_rows(cnt_next);
 

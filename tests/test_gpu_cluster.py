@@ -161,3 +161,19 @@ def test_elementwise_in_place_on_the_entity_table_drops_the_copy(il):
     W, L = _run_gd(il, plan, il.LINEAR, y, [0.05], 3, sch.c_T)
     W_ref, L_ref = oracle.gd(tg, "linear", y, np.zeros((sch.c_T, 1)), [0.05], 3)
     assert rel(W, W_ref) < GD_TOL
+
+
+@pytest.mark.parametrize("r_T,c_S,r_R,c_R", [(30_011, 20, 3_001, 200), (20_003, 8, 257, 96), (9_000, 32, 1_000, 72)])
+def test_crossprod_streams_the_clustered_copy(il, r_T, c_S, r_R, c_R):
+    # the Gram matrix's pass over the entity table reads the join-ordered copy as a stream: the same sums in the same
+    # order as with the rows gathered, so the same bits
+    rng = datagen.rng_for(9500 + r_T)
+    sch = datagen.star_schema(rng, r_T, c_S, [(r_R, c_R, "uniform")])
+    tg = oracle.Target(sch)
+    plan = il.ilargi_plan_create(il.schema_to_device(sch), sch.r_T, sch.c_T, max_cx=1)
+    G0 = il.ilargi_crossprod(plan).cpu().numpy()
+    il.ilargi_plan_cluster(plan)
+    G1 = il.ilargi_crossprod(plan).cpu().numpy()
+    assert np.array_equal(G0, G1)
+    assert rel(G1, oracle.crossprod(tg)) < 1e-5
+    assert np.array_equal(G1, G1.T)
