@@ -302,6 +302,15 @@ def run_sweep(il, torch, datagen, dev, path, records=None):
         tf = time_loop(torch, lambda: il.ilargi_gd_step(plan, il.LINEAR, W, y, lr, loss), 20)
         tm = time_loop(torch, lambda: il.ilargi_gd_step(mplan, il.LINEAR, W, y, lr, loss), 20)
         rec["gd"] = {"fact_us": round(tf * 1e6, 1), "mat_us": round(tm * 1e6, 1), "speedup": round(tm / tf, 3)}
+        # the same iteration with the entity table (and the labels) kept in join order, where the one-pass kernel
+        # takes the tables (dimension tables of at most 256 columns)
+        try:
+            il.ilargi_plan_cluster(plan, y=y)
+            tc = time_loop(torch, lambda: il.ilargi_gd_step(plan, il.LINEAR, W, y, lr, loss), 20)
+            rec["gd"].update({"clustered_us": round(tc * 1e6, 1), "clustered_speedup": round(tm / tc, 3)})
+            il.ilargi_plan_cluster(plan, None)
+        except il.IlargiError:
+            pass
         rec["chooser"] = chooser_record(il, f"config1 r_R={r_R} c_R={c_R}", shp, sch.r_T, sch.c_T, tf, tm,
                                         rec["materialize_us"] * 1e-6)
         if records is not None:

@@ -37,14 +37,6 @@ __device__ __forceinline__ void gc_wave_sync() {
 
 constexpr int kGcWaves = kBlock / kWave;
 
-typedef float gc_v4f __attribute__((ext_vector_type(4)));
-// A float4 that is read once: loaded with the non-temporal hint so that it does not displace the labels, which every
-// wavefront gathers from, in the L2.
-__device__ __forceinline__ float4 gc_stream4(const float4* p) {
-  const gc_v4f t = __builtin_nontemporal_load(reinterpret_cast<const gc_v4f*>(p));
-  return make_float4(t.x, t.y, t.z, t.w);
-}
-
 // Value of `x` in the lane the data-parallel-primitive control word names (all lanes active).
 template <int CTRL>
 __device__ __forceinline__ float gc_dpp(float x) {
@@ -124,7 +116,7 @@ __global__ __launch_bounds__(kBlock) void gd_cluster_kernel(ClusterArgs a, int w
 #pragma unroll
     for (int u = 0; u < NVT; ++u) {
       const int64_t f = f0 + u * kWave;
-      const float4 x = gc_stream4(b4 + min(f, last4));
+      const float4 x = b4[min(f, last4)];
       const bool ok = u < nvec && f <= last4;
       dst[u] = make_float4(ok ? x.x : 0.0f, ok ? x.y : 0.0f, ok ? x.z : 0.0f, ok ? x.w : 0.0f);
     }
@@ -136,7 +128,7 @@ __global__ __launch_bounds__(kBlock) void gd_cluster_kernel(ClusterArgs a, int w
   auto load_keys = [&](int64_t ch, int& k, int& p) {
     const int64_t i = ch * kWave + lane;
     const int64_t ic = min(i, r_T - 1);
-    const int kk = __builtin_nontemporal_load(a.keys + ic), pp = __builtin_nontemporal_load(pidx + ic);
+    const int kk = a.keys[ic], pp = pidx[ic];
     k = i < r_T ? kk : -1;
     p = i < r_T ? (a.yp != nullptr ? (int)ic : pp) : 0;
   };
@@ -155,7 +147,7 @@ __global__ __launch_bounds__(kBlock) void gd_cluster_kernel(ClusterArgs a, int w
   auto load_rows = [&](int j0, int jhi, float4 (&r)[4]) {
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
-      const float4 x = gc_stream4(R4 + (int64_t)min(j0 + b, jmax) * nvr);
+      const float4 x = R4[(int64_t)min(j0 + b, jmax) * nvr];
       const bool ok = rlive && j0 + b <= jhi;
       r[b] = make_float4(ok ? x.x : 0.0f, ok ? x.y : 0.0f, ok ? x.z : 0.0f, ok ? x.w : 0.0f);
     }

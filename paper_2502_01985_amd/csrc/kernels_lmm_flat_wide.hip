@@ -33,7 +33,7 @@ constexpr int kFwN = 16;                     // operand columns of the staged op
 typedef float nt4f __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ int64_t fw_gather_row(const GatherArgs& g, int s, int64_t i) {
-  if (g.idx[s] != nullptr) return __builtin_nontemporal_load(g.idx[s] + i);      // read once
+  if (g.idx[s] != nullptr) return g.idx[s][i];
   return i < g.rows[s] ? i : -1;
 }
 
@@ -60,11 +60,7 @@ __global__ __launch_bounds__(kBlock) void lmm_flat_wide_kernel(LmmArgs a, int st
     for (int u = 0; u < NVT; ++u) {
       const int e = u * kWave + lane;
       dst[u] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-      if (u < nvec && ch < nchunks && r0 + e / nvec < a.d_rows) {
-        // read once: the non-temporal hint keeps the table from displacing the gathered product rows in the L2
-        const nt4f t = __builtin_nontemporal_load(reinterpret_cast<const nt4f*>(b4 + e));
-        dst[u] = make_float4(t.x, t.y, t.z, t.w);
-      }
+      if (u < nvec && ch < nchunks && r0 + e / nvec < a.d_rows) dst[u] = b4[e];
     }
   };
   int jn[kFwGather];

@@ -14,7 +14,7 @@ namespace {
 
 // Row of Y addressed by entry p of the inverse index (or -1 to skip).
 __device__ __forceinline__ int64_t seg_row(const SegArgs& a, int64_t p) {
-  int64_t i = __builtin_nontemporal_load(a.perm + p);       // read once
+  int64_t i = a.perm[p];
   if (a.gidx != nullptr) return a.gidx[i];
   if (a.g_rows >= 0 && i >= a.g_rows) return -1;
   return i;
@@ -362,20 +362,15 @@ __global__ __launch_bounds__(kBlock) void segsum_combine_kernel(SegArgs a) {
   }
 }
 
-typedef float tmm_v4f __attribute__((ext_vector_type(4)));
-typedef float tmm_v2f __attribute__((ext_vector_type(2)));
-
-// Table values are read once: loaded with the non-temporal hint so that they do not displace the operand rows, which
-// are gathered from, in the L2.
 template <int VEC> __device__ __forceinline__ void load_vec(const float* p, float (&v)[VEC]) {
   if constexpr (VEC == 4) {
-    const tmm_v4f t = __builtin_nontemporal_load(reinterpret_cast<const tmm_v4f*>(p));
+    float4 t = *reinterpret_cast<const float4*>(p);
     v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
   } else if constexpr (VEC == 2) {
-    const tmm_v2f t = __builtin_nontemporal_load(reinterpret_cast<const tmm_v2f*>(p));
+    float2 t = *reinterpret_cast<const float2*>(p);
     v[0] = t.x; v[1] = t.y;
   } else {
-    v[0] = __builtin_nontemporal_load(p);
+    v[0] = *p;
   }
 }
 
