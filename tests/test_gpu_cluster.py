@@ -177,3 +177,32 @@ def test_crossprod_streams_the_clustered_copy(il, r_T, c_S, r_R, c_R):
     assert np.array_equal(G0, G1)
     assert rel(G1, oracle.crossprod(tg)) < 1e-5
     assert np.array_equal(G1, G1.T)
+
+
+@pytest.mark.parametrize("model", ["linear", "logistic"])
+def test_gd_clustered_with_shared_dropped_and_unfed_columns(il, model):
+    # the joined table listed first, a target column fed by both tables, one fed by nobody, one column of each
+    # table dropped, rows of the joined table nobody uses; more than one chunk per wavefront
+    rng = datagen.rng_for(9600)
+    r_T, r_R = 200_003, 9_000
+    S = rng.standard_normal((r_T, 8)).astype(np.float32)
+    R = rng.standard_normal((r_R, 12)).astype(np.float32)
+    fk = rng.integers(0, r_R // 2, size=r_T).astype(np.int32)
+    r_map = np.array([9, 2, -1, 10, 12, 13, 14, 15, 16, 17, 18, 19], dtype=np.int32)
+    s_map = np.array([0, 1, 2, 3, -1, 5, 6, 7], dtype=np.int32)
+    sch = datagen.Schema([datagen.Source(R, fk, r_map), datagen.Source(S, None, s_map)], r_T, 21)
+    tg = oracle.Target(sch)
+    w_star = rng.standard_normal(sch.c_T) / np.sqrt(sch.c_T)
+    y = datagen.finish_labels(model, oracle.lmm(tg, w_star.reshape(-1, 1)), 0.1 * rng.standard_normal(r_T))
+    code = il.LINEAR if model == "linear" else il.LOGISTIC
+    plan = il.ilargi_plan_create(il.schema_to_device(sch), sch.r_T, sch.c_T, max_cx=1)
+    yd = dev(y)
+    il.ilargi_plan_cluster(plan, y=yd)
+    W, L = _run_gd(il, plan, code, yd, [0.2], 6, sch.c_T)
+    W_ref, L_ref = oracle.gd(tg, model, y, np.zeros((sch.c_T, 1)), [0.2], 6)
+    assert rel(W, W_ref) < GD_TOL
+    np.testing.assert_allclose(L, L_ref, rtol=1e-4)
+    assert W[8, 0] == 0.0 and W[11, 0] == 0.0 and W[4, 0] == 0.0 and W[20, 0] == 0.0   # columns nobody feeds keep their weight
+    il.ilargi_plan_cluster(plan, None)
+    W0, L0 = _run_gd(il, plan, code, yd, [0.2], 6, sch.c_T)
+    assert rel(W, W0) < GD_TOL
