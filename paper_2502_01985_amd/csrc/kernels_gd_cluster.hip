@@ -147,7 +147,7 @@ __global__ __launch_bounds__(kBlock) void gd_cluster_kernel(ClusterArgs a, int w
   auto load_rows = [&](int j0, int jhi, float4 (&r)[4]) {
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
-      const float4 x = R4[(int64_t)min(j0 + b, jmax) * nvr];
+      const float4 x = R4[(int64_t)min(j0 + b, max(jhi, 0)) * nvr];        // (beyond the run: its last row again, a cache hit)
       const bool ok = rlive && j0 + b <= jhi;
       r[b] = make_float4(ok ? x.x : 0.0f, ok ? x.y : 0.0f, ok ? x.z : 0.0f, ok ? x.w : 0.0f);
     }
