@@ -536,6 +536,16 @@ def wide_batch(il, torch, datagen, dev, mfma_file):
                 ms, names = il.ilargi_plan_trace_end(pl, 64, names=True)
                 rec["kernels_us"] = {f"{i}:{n}": round(float(v) * 1e3, 1) for i, (n, v) in enumerate(zip(names, ms))}
             out[f"{pn}_{nm}"] = rec
+    # the same iterations on a plan that keeps the entity table and the labels in join order: the fused pass streams
+    # the copy instead of gathering rows of S (same sums, same order, same bits)
+    il.ilargi_plan_cluster(plan, y=y)
+    for prec, pn in ((il.F32, "f32"), (il.BF16_IN_F32_ACC, "bf16")):
+        W.zero_()
+        t = time_loop(torch, lambda: il.ilargi_gd_step(plan, il.LINEAR, W, y, lr, loss, precision=prec), 10)
+        out[f"{pn}_factorized_clustered"] = {"gd_it_per_s": round(1.0 / t, 1), "ms_per_iteration": round(t * 1e3, 3),
+                                             "TFLOPs": round(fl_fact / t / 1e12, 2),
+                                             "mfma_frac": round(fl_fact / t / peaks[pn], 4)}
+    il.ilargi_plan_cluster(plan, None)
     out["bf16_over_f32_factorized"] = round(out["f32_factorized"]["ms_per_iteration"] / out["bf16_factorized"]["ms_per_iteration"], 3)
     busy = {}
     for key in ("wide_f32/lmm_rows:1", "wide_f32/star_pass", "wide_f32/colred:1",

@@ -942,6 +942,11 @@ ilargi_status_t gd_star_step(ilargi_plan* pl, int mode, float* W, int m, const f
   s.PZ = pl->at<float>(d.o_pz); s.ldp = m; s.r_R = d.rows;
   s.rowptr = pl->at<int32_t>(d.o_rowptr); s.perm = pl->at<int32_t>(d.o_perm); s.idx = d.idx;
   s.y = y;
+  if (pl->cluster_sp != nullptr && pl->cluster_k == pl->star_k) {
+    // the join-ordered copy of S (same rows in the same order): a stream instead of gathered rows
+    s.Sp = pl->cluster_sp; s.keys = pl->cluster_keys;
+    s.yp = y == pl->cluster_y_src ? pl->cluster_yp : nullptr;
+  }
   s.loss_partial = pl->at<float>(pl->lay.o_loss); s.ld_loss = m;
   s.grad_partial = pl->at<float>(pl->lay.o_gpartial); s.ld_grad = m;
   const int64_t max_grid = std::min<int64_t>(1024, pl->lay.gpartial_floats / ((int64_t)s.cs * m));

@@ -101,6 +101,9 @@ struct StarArgs {
   const int32_t* perm;       // r_T
   const int32_t* idx;        // r_T: row of R each target row joins
   const float* y;            // r_T
+  const float* Sp;           // NULL, or S with its rows in join order (Sp[p, :] = S[perm[p], :]) ...
+  const int32_t* keys;       // ... with the row of R each of those rows joins, r_T ...
+  const float* yp;           // ... and, if not NULL, their labels, r_T
   float* loss_partial;       // [gridDim.x][ld_loss]
   int ld_loss;
   float* grad_partial;       // [gridDim.x][cs][ld_grad] partials of S^T E

@@ -127,6 +127,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(VEC4 ? (
     }
   }
 
+  const float* Sb = a.Sp != nullptr ? a.Sp : a.S;
   const bool p_vec = (a.ldp % 4 == 0) && (reinterpret_cast<uintptr_t>(a.PZ) % 16 == 0);
   const int pr = lane / 16, pq = lane % 16;                   // (row mod 4, float4 slot) of the P / Z tile this lane moves
 
@@ -159,13 +160,18 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(VEC4 ? (
 
     // Batches of ST target rows, one ahead: while the matrix cores work on a batch, the next batch's rows of
     // S (registers), its row numbers / labels and the row list of the batch after that are already on their way.
-    int pi = (lane < ST && p_begin + lane < p_end) ? a.perm[p_begin + lane] : -1;
-    int pi_next = (lane < ST && p_begin + ST + lane < p_end) ? a.perm[p_begin + ST + lane] : -1;
+    // the row of the table entry p of the inverse index stands for, its key and its label: through the target row,
+    // or straight from the join-ordered copy of the table (and of the labels) when the plan keeps one
+    auto row_at = [&](int p) { return a.Sp != nullptr ? p : a.perm[p]; };
+    auto key_at = [&](int r) { return a.Sp != nullptr ? a.keys[r] : a.idx[r]; };
+    auto label_at = [&](int r) { return a.Sp == nullptr ? a.y[r] : (a.yp != nullptr ? a.yp[r] : a.y[a.perm[r]]); };
+    int pi = (lane < ST && p_begin + lane < p_end) ? row_at(p_begin + lane) : -1;
+    int pi_next = (lane < ST && p_begin + ST + lane < p_end) ? row_at(p_begin + ST + lane) : -1;
     int jl = -1;
     float yv = 0.0f;
     if (pi >= 0) {
-      jl = a.idx[pi] - (int)jb;
-      yv = a.y[pi];
+      jl = key_at(pi) - (int)jb;
+      yv = label_at(pi);
     }
     wave_sync();                                              // the previous tile's batches are consumed
     if (lane < ST) iS[lane] = pi;
@@ -178,8 +184,8 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(VEC4 ? (
         else sv[u] = 0.0f;
         if (rr[u] < cnt_rows && gg[u] < glive) {
           const int64_t row = iS[rr[u]];
-          if constexpr (VEC4) sv[u] = *reinterpret_cast<const float4*>(a.S + row * a.cs + 4 * gg[u]);
-          else sv[u] = a.S[row * a.cs + gg[u]];
+          if constexpr (VEC4) sv[u] = *reinterpret_cast<const float4*>(Sb + row * a.cs + 4 * gg[u]);
+          else sv[u] = Sb[row * a.cs + gg[u]];
         }
       }
     };
@@ -199,12 +205,12 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(VEC4 ? (
       wave_sync();
       // next batch: row numbers and labels, rows of S; the row list of the batch after it
       pi = pi_next;
-      pi_next = (lane < ST && p0 + 2 * ST + lane < p_end) ? a.perm[p0 + 2 * ST + lane] : -1;
+      pi_next = (lane < ST && p0 + 2 * ST + lane < p_end) ? row_at(p0 + 2 * ST + lane) : -1;
       jl = -1;
       yv = 0.0f;
       if (pi >= 0) {
-        jl = a.idx[pi] - (int)jb;
-        yv = a.y[pi];
+        jl = key_at(pi) - (int)jb;
+        yv = label_at(pi);
       }
       load_rows(cnt_next);
 

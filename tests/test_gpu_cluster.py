@@ -206,3 +206,37 @@ def test_gd_clustered_with_shared_dropped_and_unfed_columns(il, model):
     il.ilargi_plan_cluster(plan, None)
     W0, L0 = _run_gd(il, plan, code, yd, [0.2], 6, sch.c_T)
     assert rel(W, W0) < GD_TOL
+
+
+@pytest.mark.parametrize("prec", ["f32", "bf16"])
+def test_wide_batch_streams_the_clustered_copy(il, prec):
+    # many models at once: the join-order pass reads the join-ordered copy (and its labels) as streams -- the same
+    # rows in the same order, so the same bits as with the rows gathered
+    rng = datagen.rng_for(9700)
+    sch = datagen.star_schema(rng, 40_003, 20, [(3_001, 72, "uniform")])
+    tg = oracle.Target(sch)
+    m = 40
+    w_star = rng.standard_normal(sch.c_T) / np.sqrt(sch.c_T)
+    y = datagen.finish_labels("linear", oracle.lmm(tg, w_star.reshape(-1, 1)), 0.1 * rng.standard_normal(sch.r_T))
+    lrs = np.geomspace(1e-3, 5e-2, m)
+    plan = il.ilargi_plan_create(il.schema_to_device(sch), sch.r_T, sch.c_T, max_cx=m)
+    precision = il.F32 if prec == "f32" else il.BF16_IN_F32_ACC
+    yd, lr = dev(y), dev(lrs.astype(np.float32))
+
+    def run():
+        W = torch.zeros((sch.c_T, m), device="cuda")
+        loss = torch.zeros(m, device="cuda")
+        for _ in range(3):
+            il.ilargi_gd_step(plan, il.LINEAR, W, yd, lr, loss, precision=precision)
+        return W.cpu().numpy(), loss.cpu().numpy()
+
+    W0, L0 = run()
+    il.ilargi_plan_cluster(plan)                   # the copy without labels: labels gathered through the index
+    W1, L1 = run()
+    il.ilargi_plan_cluster(plan, y=yd)             # ... and with them
+    W2, L2 = run()
+    assert np.array_equal(W0, W1) and np.array_equal(L0, L1)
+    assert np.array_equal(W0, W2) and np.array_equal(L0, L2)
+    if prec == "f32":
+        W_ref, _ = oracle.gd(tg, "linear", y, np.zeros((sch.c_T, m)), lrs, 3)
+        assert max(rel(W2[:, j], W_ref[:, j]) for j in range(m)) < GD_TOL
