@@ -240,3 +240,4 @@ def test_wide_batch_streams_the_clustered_copy(il, prec):
     if prec == "f32":
         W_ref, _ = oracle.gd(tg, "linear", y, np.zeros((sch.c_T, m)), lrs, 3)
         assert max(rel(W2[:, j], W_ref[:, j]) for j in range(m)) < GD_TOL
+
