@@ -241,3 +241,46 @@ def test_wide_batch_streams_the_clustered_copy(il, prec):
         W_ref, _ = oracle.gd(tg, "linear", y, np.zeros((sch.c_T, m)), lrs, 3)
         assert max(rel(W2[:, j], W_ref[:, j]) for j in range(m)) < GD_TOL
 
+
+def test_clustered_iteration_replayed_from_a_captured_graph(il):
+    # two iterations captured in a HIP graph (kernel launches only: nothing in the path clears memory with a memset
+    # node) and replayed three times, with eager work and synchronisations between the replays: every replay
+    # continues the same trajectory as eager calls, bit for bit
+    rng = datagen.rng_for(9900)
+    sch = datagen.star_schema(rng, 50_003, 12, [(2_000, 40, "uniform")])
+    tg = oracle.Target(sch)
+    w_star = rng.standard_normal(sch.c_T) / np.sqrt(sch.c_T)
+    y = datagen.finish_labels("linear", oracle.lmm(tg, w_star.reshape(-1, 1)), 0.1 * rng.standard_normal(sch.r_T))
+    plan = il.ilargi_plan_create(il.schema_to_device(sch), sch.r_T, sch.c_T, max_cx=1)
+    yd, lr = dev(y), dev(np.array([0.1], dtype=np.float32))
+    il.ilargi_plan_cluster(plan, y=yd)
+    W_e = torch.zeros((sch.c_T, 1), device="cuda")
+    loss_e = torch.zeros(1, device="cuda")
+    eager = []
+    for _ in range(6):
+        il.ilargi_gd_step(plan, il.LINEAR, W_e, yd, lr, loss_e)
+        eager.append((W_e.cpu().numpy().copy(), loss_e.cpu().numpy().copy()))
+    W = torch.zeros((sch.c_T, 1), device="cuda")
+    loss = torch.zeros(1, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        il.ilargi_gd_step(plan, il.LINEAR, W, yd, lr, loss)           # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    W.zero_()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for _ in range(2):
+            il.ilargi_gd_step(plan, il.LINEAR, W, yd, lr, loss)
+    W.zero_()
+    for k in range(3):
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(W.cpu().numpy(), eager[2 * k + 1][0])
+        assert np.array_equal(loss.cpu().numpy(), eager[2 * k + 1][1])
+        scratch = torch.randn(1 << 20, device="cuda").sum().item()      # eager work between the replays
+        assert np.isfinite(scratch)
+    W_ref, _ = oracle.gd(tg, "linear", y, np.zeros((sch.c_T, 1)), [0.1], 6)
+    assert rel(W.cpu().numpy(), W_ref) < GD_TOL
+
