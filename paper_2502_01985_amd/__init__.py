@@ -196,6 +196,7 @@ class Plan:
         self._borrowed = borrowed
         self.r_T, self.c_T, self.max_cx = r_T, c_T, max_cx
         self.src_shapes = src_shapes
+        self._cluster = None                # (buffer, labels) handed to ilargi_plan_cluster: kept alive with the plan
 
     def destroy(self) -> None:
         if self.handle:
