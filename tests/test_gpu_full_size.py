@@ -147,6 +147,32 @@ def test_config1_kmeans_and_gaussian_nmf(il):
     Problem.cache.clear()                                       # the cached schema was changed in place
 
 
+def test_config1_gradient_descent_on_the_clustered_entity_table(il):
+    # the benchmark's schema at full size: the one-pass iteration over the join-ordered copy (linear and logistic, five
+    # iterations each) against the oracle's Alg. 1, and the Gram matrix bit for bit against the plan without the copy
+    sch, tg, plan, _ = Problem.get(il, "config1", 16)
+    rng = datagen.rng_for(4711)
+    w_star = rng.standard_normal(sch.c_T) / np.sqrt(sch.c_T)
+    G0 = il.ilargi_crossprod(plan).cpu().numpy()
+    for model, code, lr in (("linear", il.LINEAR, 0.05), ("logistic", il.LOGISTIC, 0.5)):
+        y = datagen.finish_labels(model, oracle.lmm(tg, w_star.reshape(-1, 1)), 0.1 * rng.standard_normal(sch.r_T))
+        yd = dev(y)
+        il.ilargi_plan_cluster(plan, y=yd)
+        W = torch.zeros((sch.c_T, 1), device="cuda")
+        lrd = dev(np.array([lr], dtype=np.float32))
+        loss = torch.zeros(1, device="cuda")
+        losses = []
+        for _ in range(5):
+            il.ilargi_gd_step(plan, code, W, yd, lrd, loss)
+            losses.append(loss.cpu().numpy().copy())
+        W_ref, L_ref = oracle.gd(tg, model, y, np.zeros((sch.c_T, 1)), [lr], 5)
+        assert rel(W.cpu().numpy(), W_ref) < GD_TOL, model
+        np.testing.assert_allclose(np.array(losses), L_ref, rtol=1e-4)
+    G1 = il.ilargi_crossprod(plan).cpu().numpy()
+    assert np.array_equal(G0, G1)
+    il.ilargi_plan_cluster(plan, None)
+
+
 # ------------------------------------------------------------------ configuration 2 (logistic regression, Zipf keys)
 def test_config1_scalar_operators(il):
     # Tab. 2, first four rows, at full size: sums against the oracle; an element-wise operator applied to the
@@ -241,6 +267,31 @@ def test_config4_bf16_inputs(il):
     tols = np.array([bf16_gd_weight_tol(20, sch.c_T, sch.r_T, lr_j, lam) for lr_j in sch.extras["lr"]])
     print(f"  bound {tols.min():.3e} .. {tols.max():.3e} (lambda_max {lam:.4f})")
     assert np.all(errs < tols), (errs / tols).max()
+
+
+def test_config4_batched_models_on_the_clustered_entity_table(il):
+    # 256 models at full size with the fused pass streaming the join-ordered copy, its keys and labels: the same bits
+    # as the pass that gathers the rows, in both precisions, and the oracle's weights in float32
+    sch, tg, plan, y = Problem.get(il, "config4", 256, "linear")
+    gold = np.load(os.path.join(GOLDEN, "config4_gd.npz"))
+    lrs = sch.extras["lr"]
+    yd, lr = dev(y), dev(np.asarray(lrs, dtype=np.float32))
+
+    def run(precision):
+        W = torch.zeros((sch.c_T, 256), device="cuda")
+        loss = torch.zeros(256, device="cuda")
+        for _ in range(20):
+            il.ilargi_gd_step(plan, il.LINEAR, W, yd, lr, loss, precision=precision)
+        return W.cpu().numpy(), loss.cpu().numpy()
+
+    plain = {p: run(p) for p in (il.F32, il.BF16_IN_F32_ACC)}
+    il.ilargi_plan_cluster(plan, y=yd)
+    for p in (il.F32, il.BF16_IN_F32_ACC):
+        W, L = run(p)
+        assert np.array_equal(W, plain[p][0]) and np.array_equal(L, plain[p][1])
+    errs = np.array([rel(plain[il.F32][0][:, j], gold["W"][:, j]) for j in range(256)])
+    assert errs.max() < GD_TOL
+    il.ilargi_plan_cluster(plan, None)
 
 
 def test_sliced_segment_sums_on_a_large_target_table(il):
