@@ -1689,7 +1689,15 @@ ilargi_status_t ilargi_gd_step(ilargi_plan_t* plan, ilargi_model_t model, float*
     }
     return ILARGI_OK;
   }
-  if (plan->cluster_sp != nullptr && !bf16 && m == 1) {
+  // The one-pass iteration requests the first eight rows of the dimension table of every 64 target rows ahead of time
+  // and the rest on demand: it pays from a fan-out of about four on, or when the dimension table is the larger of the
+  // two (then reading it once instead of twice outweighs the waits).  Measured on the benchmark's tuple-ratio x
+  // feature-ratio grid; below that the usual sequence is faster and is kept.
+  const bool cluster_pays = plan->cluster_sp != nullptr &&
+                            (plan->r_T >= 4 * plan->src[plan->cluster_k].rows ||
+                             plan->src[plan->cluster_k].rows * plan->src[plan->cluster_k].cols >=
+                                 plan->src[plan->fused].rows * plan->src[plan->fused].cols);
+  if (cluster_pays && !bf16 && m == 1) {
     // clustered entity table: both tables are streams, every table read once, nothing but partial sums written
     const SourcePlan& fs = plan->src[plan->fused];
     const SourcePlan& d = plan->src[plan->cluster_k];

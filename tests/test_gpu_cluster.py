@@ -45,10 +45,12 @@ def _run_gd(il, plan, model, y, lrs, iters, c_T):
 
 
 # (r_T, c_S, r_R, c_R, keys): the benchmark's shape scaled down; the narrowest tables; a full-width dimension table
-# with a ragged last chunk; fan-out 1 with more rows of R than target rows (runs of more than eight rows of R per
-# chunk, rows nobody joins); skewed keys (segments spanning many chunks); fewer rows than a chunk; one row of R
+# with a ragged last chunk; fan-out 1 with more rows of R than target rows and R the larger table (runs of more than
+# eight rows of R per chunk, rows nobody joins); the same fan-out with R the smaller table (the usual sequence is
+# kept); skewed keys (segments spanning many chunks); fewer rows than a chunk; one row of R
 SHAPES = [(30_011, 20, 3_001, 200, "uniform"), (50_003, 4, 301, 24, "uniform"), (20_003, 8, 257, 256, "uniform"),
-          (9_999, 32, 12_000, 4, "uniform"), (60_001, 12, 50, 36, ("zipf", 1.1)), (37, 16, 5, 8, "uniform"),
+          (9_999, 4, 12_000, 24, "uniform"), (9_999, 32, 12_000, 4, "uniform"), (60_001, 12, 50, 36, ("zipf", 1.1)),
+          (37, 16, 5, 8, "uniform"),
           (4_100, 28, 1, 12, "uniform")]
 
 
