@@ -142,6 +142,7 @@ def graph_time(torch, fn, iters, replays=10):
 STEP_OPS = ("lmm_c1", "tmm_c1", "lmm_c16", "tmm_c16")     # the step: T X and T^T Y, one and sixteen operand columns
 OTHER_OPS = ("gd_step", "crossprod", "materialize")          # timed on their own, outside `value`
 CLUSTERED_OP = "gd_clustered"    # gd_step on plans that keep the entity table in join order (ilargi_plan_cluster)
+CLUSTERED_GATHER_OP = "gd_clustered_gathered_labels"   # ... without the labels in the copy (--only, for the profiler)
 
 
 class Workload:
@@ -172,6 +173,7 @@ class Workload:
         self.nbytes = {"lmm_c1": bytes_lmm(self.shp, r_T, c_T, 1), "tmm_c1": bytes_tmm(self.shp, r_T, c_T, 1),
                        "lmm_c16": bytes_lmm(self.shp, r_T, c_T, 16), "tmm_c16": bytes_tmm(self.shp, r_T, c_T, 16),
                        "gd_step": bytes_gd(self.shp, r_T, c_T), CLUSTERED_OP: bytes_gd_clustered(self.shp, r_T, c_T),
+                       CLUSTERED_GATHER_OP: bytes_gd_clustered(self.shp, r_T, c_T) + 4 * r_T,
                        "crossprod": bytes_crossprod(self.shp, r_T, c_T),
                        "materialize": bytes_materialize(self.shp, r_T, c_T)}
 
@@ -183,7 +185,7 @@ class Workload:
         if name.startswith("tmm_c"):
             c = int(name[5:])
             return il.ilargi_tmm(plan, self.Y[c], self.out_t[c])
-        if name in ("gd_step", CLUSTERED_OP):
+        if name in ("gd_step", CLUSTERED_OP, CLUSTERED_GATHER_OP):
             return il.ilargi_gd_step(plan, il.LINEAR, self.W, self.y, self.lr, self.loss)
         if name == "crossprod":
             return il.ilargi_crossprod(plan, self.G)
@@ -193,11 +195,11 @@ class Workload:
             return il.ilargi_materialize(plan, self.Tm)
         raise KeyError(name)
 
-    def cluster(self, on):
+    def cluster(self, on, labels=True):
         """Every copy of the tables gets (or drops) the join-ordered copy of its entity table."""
         for plan in self.plans:
             if on:
-                self.il.ilargi_plan_cluster(plan, y=self.y)
+                self.il.ilargi_plan_cluster(plan, y=self.y if labels else None)
             else:
                 self.il.ilargi_plan_cluster(plan, None)
         self.torch.cuda.synchronize()
@@ -382,6 +384,8 @@ def kernel_model(shp, r_T, c_T):
     m["gd_step/tmm_join:1"] = m["tmm_c1/tmm_join:1"]
     # the clustered iteration: S (join-ordered copy) and R once, key and label of every row
     m["gd_clustered/gd_cluster"] = ("hbm", 4 * r_S * c_S + 4 * r_R * c_R + 8 * r_T)
+    # ... with the labels gathered through the index (target row and label instead of the label alone)
+    m["gd_clustered_gathered_labels/gd_cluster"] = ("hbm", 4 * r_S * c_S + 4 * r_R * c_R + 12 * r_T)
     m["materialize/materialize"] = ("hbm", bytes_materialize(shp, r_T, c_T))
     # Gram matrix: S^T S and the rows of S summed per row of R in one join-order pass; the cross block
     # Zc^T R; the diagonal block R^T diag(cnt) R (upper-triangle 16 x 16 tiles on the matrix cores)
@@ -703,6 +707,8 @@ def run_only(il, torch, wl, name, reps):
     del src, dst
     if name == CLUSTERED_OP:
         wl.cluster(True)
+    if name == CLUSTERED_GATHER_OP:
+        wl.cluster(True, labels=False)
     for i in range(3):
         wl.call(name, wl.plans[i % len(wl.plans)])
     torch.cuda.synchronize()
@@ -728,7 +734,7 @@ def main() -> int:
     ap.add_argument("--no-wide", action="store_true", help="skip the 256-model batched workload")
     ap.add_argument("--no-configs", action="store_true", help="skip the other single-model configurations")
     ap.add_argument("--no-extras", action="store_true", help="skip the scalar operators, KMeans / NMF and sparse tables")
-    ap.add_argument("--only", default="", help="run one operator alone (for a profiler): " + ", ".join(STEP_OPS + OTHER_OPS + (CLUSTERED_OP,))
+    ap.add_argument("--only", default="", help="run one operator alone (for a profiler): " + ", ".join(STEP_OPS + OTHER_OPS + (CLUSTERED_OP, CLUSTERED_GATHER_OP))
                     + ", wide_f32, wide_bf16")
     ap.add_argument("--sweep", default="", help="also run the TR/FR sweep and write it to this JSON file")
     ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "traffic_by_operator_and_kernel.txt"))
@@ -766,7 +772,7 @@ def main() -> int:
     del plan
     wl = Workload(il, torch, sch, srcs, dev)
     if args.only:
-        if args.only not in STEP_OPS + OTHER_OPS + (CLUSTERED_OP,):
+        if args.only not in STEP_OPS + OTHER_OPS + (CLUSTERED_OP, CLUSTERED_GATHER_OP):
             print(f"bench.py: unknown operator {args.only}", file=sys.stderr)
             return 2
         return run_only(il, torch, wl, args.only, args.steps)
