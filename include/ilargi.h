@@ -126,8 +126,8 @@ ilargi_status_t ilargi_plan_destroy(ilargi_plan_t* plan);
  * the residual and the segment sums I_R^T e of Sec. 2.2's rules never go to memory.  ilargi_crossprod streams the
  * copy instead of gathering rows of S (same result, bit for bit); every other operator ignores it.  The one-pass
  * iteration pays when at least about four target rows join a row of R on average, or when R holds more cells
- * than S (a wavefront requests the first eight rows of R of every 64 target rows ahead of time, the rest on
- * demand): ilargi_gd_step takes it in those two cases and keeps its usual sequence otherwise.
+ * than S (every row of R costs the pass two reductions over a wavefront, however few target rows it serves):
+ * ilargi_gd_step takes it in those two cases and keeps its usual sequence otherwise.
  *   ilargi_plan_cluster_bytes: size of the buffer, 4 r_T c_S + 8 r_T bytes rounded up to 256-byte pieces.
  *     Errors: NULL, UNSUPPORTED (not such a join; S needs 4..32 columns, R 4..256 columns, both in whole
  *     16-byte aligned float4s).

@@ -1689,10 +1689,10 @@ ilargi_status_t ilargi_gd_step(ilargi_plan_t* plan, ilargi_model_t model, float*
     }
     return ILARGI_OK;
   }
-  // The one-pass iteration requests the first eight rows of the dimension table of every 64 target rows ahead of time
-  // and the rest on demand: it pays from a fan-out of about four on, or when the dimension table is the larger of the
-  // two (then reading it once instead of twice outweighs the waits).  Measured on the benchmark's tuple-ratio x
-  // feature-ratio grid; below that the usual sequence is faster and is kept.
+  // Every row of the dimension table costs the one-pass iteration two reductions over a wavefront, however few target
+  // rows it serves: the pass pays from a fan-out of about four on (level at four, measured), or when the dimension
+  // table is the larger of the two (then reading it once instead of twice outweighs that arithmetic).  Measured on the
+  // benchmark's tuple-ratio x feature-ratio grid; below that the usual sequence is faster and is kept.
   const bool cluster_pays = plan->cluster_sp != nullptr &&
                             (plan->r_T >= 4 * plan->src[plan->cluster_k].rows ||
                              plan->src[plan->cluster_k].rows * plan->src[plan->cluster_k].cols >=
